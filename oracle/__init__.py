@@ -1,0 +1,170 @@
+"""ctypes front end of the CPU oracle (``forward_prune.c``) -- TEST INFRASTRUCTURE.
+
+Only tests, the smoke check and the bench's ``cpu_baseline`` leg may import this package; the
+product path never does.  It imports nothing from the GPU package.
+
+Every function here is a thin marshalling layer: all arithmetic is in the C file, which follows
+Algorithm 1, the removal rule of Sec. 2.1 and the creation-order rule of Sec. 3.2 of the paper.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "forward_prune.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, no threading)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fPIC", "-shared",
+                               _SRC, "-o", tmp])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.orc_certificate.restype = ctypes.c_int64
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+i64 = ctypes.c_int64
+i32 = ctypes.c_int32
+
+
+@dataclass
+class Adjacency:
+    num_ops: int
+    num_tensors: int
+    in_rowptr: np.ndarray
+    in_idx: np.ndarray
+    out_rowptr: np.ndarray
+    out_idx: np.ndarray
+    prod_rowptr: np.ndarray
+    prod_idx: np.ndarray
+
+
+def build_csr(n_rows: int, row, col):
+    row, col = _c(row, np.int32), _c(col, np.int32)
+    rowptr = np.empty(n_rows + 1, np.int32)
+    idx = np.empty(row.shape[0], np.int32)
+    rc = _load().orc_build_csr(i64(n_rows), i64(row.shape[0]), _p(row), _p(col), _p(rowptr), _p(idx))
+    if rc:
+        raise ValueError("orc_build_csr: id out of range")
+    return rowptr, idx
+
+
+def build_adjacency(num_ops, num_tensors, in_op, in_tensor, out_op, out_tensor) -> Adjacency:
+    in_rowptr, in_idx = build_csr(num_ops, in_op, in_tensor)
+    out_rowptr, out_idx = build_csr(num_ops, out_op, out_tensor)
+    prod_rowptr = np.empty(num_tensors + 1, np.int32)
+    prod_idx = np.empty(out_idx.shape[0], np.int32)
+    rc = _load().orc_build_producers(i64(num_ops), i64(num_tensors), _p(out_rowptr), _p(out_idx),
+                                     _p(prod_rowptr), _p(prod_idx))
+    if rc:
+        raise ValueError("orc_build_producers: tensor id out of range")
+    return Adjacency(num_ops, num_tensors, in_rowptr, in_idx, out_rowptr, out_idx, prod_rowptr, prod_idx)
+
+
+def mark(adj: Adjacency, num_sets: int, tgt_rowptr, tgt_idx, M: Optional[np.ndarray] = None):
+    """Algorithm 1 for every target set; returns (M, parent_edges_per_set)."""
+    tgt_rowptr, tgt_idx = _c(tgt_rowptr, np.int32), _c(tgt_idx, np.int32)
+    total = tgt_rowptr.shape[0] - 1
+    if M is None:
+        M = np.zeros(adj.num_tensors, np.uint64)
+    edges = np.zeros(total, np.int64)
+    rc = _load().orc_forward_prune(i64(adj.num_ops), i64(adj.num_tensors), _p(adj.in_rowptr),
+                                   _p(adj.in_idx), _p(adj.prod_rowptr), _p(adj.prod_idx), i64(total),
+                                   i32(num_sets), _p(tgt_rowptr), _p(tgt_idx), _p(M), _p(edges))
+    if rc:
+        raise ValueError("orc_forward_prune: bad argument")
+    return M, edges
+
+
+def keep(adj: Adjacency, M: np.ndarray):
+    K = np.empty(adj.num_ops, np.uint64)
+    flag = np.empty(adj.num_ops, np.uint8)
+    _load().orc_keep(i64(adj.num_ops), _p(adj.out_rowptr), _p(adj.out_idx), _p(M), _p(K), _p(flag))
+    return K, flag
+
+
+def compact(K: np.ndarray, num_graphs: int = 1, graph_op_offsets=None):
+    P = K.shape[0]
+    batched = num_graphs > 1 and graph_op_offsets is not None
+    kept_ops = np.empty(P, np.int32)
+    kept_masks = np.empty(P, np.uint64)
+    kept_count = np.zeros(1 + (num_graphs + 1 if batched else 0), np.int64)
+    pq = np.zeros(64 * (num_graphs if batched else 1), np.int64)
+    off = _c(graph_op_offsets, np.int64) if batched else None
+    _load().orc_compact(i64(P), _p(K), i32(num_graphs), _p(off), _p(kept_ops), _p(kept_masks),
+                        _p(kept_count), _p(pq))
+    n = int(kept_count[0])
+    return kept_ops[:n].copy(), kept_masks[:n].copy(), kept_count, pq
+
+
+def seed_masks(num_tensors: int, num_sets: int, tgt_rowptr, tgt_idx) -> np.ndarray:
+    tgt_rowptr, tgt_idx = _c(tgt_rowptr, np.int32), _c(tgt_idx, np.int32)
+    S = np.zeros(num_tensors, np.uint64)
+    rc = _load().orc_seed_masks(i64(num_tensors), i64(tgt_rowptr.shape[0] - 1), i32(num_sets),
+                                _p(tgt_rowptr), _p(tgt_idx), _p(S))
+    if rc:
+        raise ValueError("orc_seed_masks: target id out of range")
+    return S
+
+
+def reverse_sweep(adj: Adjacency, S: np.ndarray):
+    M = S.copy()
+    K = np.empty(adj.num_ops, np.uint64)
+    _load().orc_reverse_sweep(i64(adj.num_ops), _p(adj.in_rowptr), _p(adj.in_idx), _p(adj.out_rowptr),
+                              _p(adj.out_idx), _p(M), _p(K))
+    return M, K
+
+
+def certificate(adj: Adjacency, S: np.ndarray, M: np.ndarray, K: np.ndarray) -> int:
+    """Number of violated fixed-point equations (0 proves M, K correct on a DAG)."""
+    R = S.copy()
+    return int(_load().orc_certificate(i64(adj.num_ops), i64(adj.num_tensors), _p(adj.in_rowptr),
+                                       _p(adj.in_idx), _p(adj.out_rowptr), _p(adj.out_idx),
+                                       _p(_c(M, np.uint64)), _p(_c(K, np.uint64)), _p(R)))
+
+
+@dataclass
+class PruneResult:
+    tensor_mask: np.ndarray      # M  [T] uint64
+    op_mask: np.ndarray          # K  [P] uint64
+    op_flag: np.ndarray          # [P] uint8
+    kept_ops: np.ndarray         # ascending operator ids
+    kept_masks: np.ndarray
+    kept_count: np.ndarray       # [1] or [1 + G + 1]
+    per_query_count: np.ndarray  # [64] or [G*64]
+    parent_edges: np.ndarray
+
+
+def forward_prune(adj: Adjacency, num_sets: int, tgt_rowptr, tgt_idx, num_graphs: int = 1,
+                  graph_op_offsets=None) -> PruneResult:
+    """Whole path: Algorithm 1 per set, removal rule, ordered compaction."""
+    M, edges = mark(adj, num_sets, tgt_rowptr, tgt_idx)
+    K, flag = keep(adj, M)
+    kept_ops, kept_masks, kept_count, pq = compact(K, num_graphs, graph_op_offsets)
+    return PruneResult(M, K, flag, kept_ops, kept_masks, kept_count, pq, edges)
