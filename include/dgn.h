@@ -1,0 +1,193 @@
+/*
+ * libdgn -- batched Forward Prune of tensor/operator DAGs on AMD CDNA4 (gfx950).
+ *
+ * What is computed (Dragon paper, arXiv 1707.08265):
+ *   - graph model, Sec. 2.2: nodes are tensors; x_i -> x_j is an edge iff some operator takes x_i
+ *     as an input and x_j as an output;
+ *   - Algorithm 1 ("Backward Traversing for Forward-Pass"): starting from the solving targets,
+ *     mark every tensor the targets depend on;
+ *   - removal rule, Sec. 2.1: an operator whose outputs are all un-coloured is removed;
+ *   - Sec. 3.2: surviving operators keep their creation (= topological) order.
+ *
+ * Here up to 64 target sets are solved at once: bit q of a 64-bit mask is the flag m_x of an
+ * independent run of Algorithm 1 with target set q.  With
+ *      K[o] = OR_{u in out(o)} M[u]                       (operator keep mask)
+ *      M[t] = S[t] | OR_{o : t in in(o)} K[o]             (least fixed point; S = seed masks)
+ * the library returns M, K, the flags K != 0 and the kept operators compacted in ascending id.
+ *
+ * General conventions
+ *   - Plain C ABI.  Unless a parameter says HOST, every pointer is a DEVICE pointer owned by the
+ *     caller; the library never allocates or frees device memory (sizes of the caller-provided
+ *     graph storage and scratch come from the *_workspace queries).  Device buffers must be
+ *     8-byte aligned (256-byte alignment is recommended for graph_mem and scratch).
+ *   - dgn_stream is a hipStream_t (NULL = the default stream).  All kernels are enqueued on it.
+ *   - Every function returns DGN_OK (0) or a negative DGN_ERR_* code; nothing throws or aborts.
+ *   - All counts must be below 2^31 - 1 (ids and offsets are int32 on the device).
+ *   - Operator ids must be a topological (creation) order: every producer of an operator's input
+ *     has a smaller id than the operator.  M, K and the flags are correct for any DAG; the
+ *     "ascending id = topological order" meaning of the kept list needs this precondition.
+ *     Duplicate edges, tensors with several producers, and operators with no inputs or no
+ *     outputs are legal.
+ */
+#ifndef DGN_H
+#define DGN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DGN_VERSION 100 /* 0.1.0 */
+#define DGN_MAX_SETS 64
+
+typedef void *dgn_stream;             /* hipStream_t */
+typedef struct dgn_graph dgn_graph;   /* opaque host handle; immutable after build */
+
+enum {
+    DGN_OK = 0,
+    DGN_ERR_INVALID_ARG = -1,         /* negative size, inconsistent descriptor, bad option      */
+    DGN_ERR_NULL_PTR = -2,            /* a required pointer is NULL                               */
+    DGN_ERR_TOO_LARGE = -3,           /* a count is >= 2^31 - 1                                   */
+    DGN_ERR_ID_OUT_OF_RANGE = -4,     /* an operator / tensor / target id is outside its range    */
+    DGN_ERR_TOO_MANY_SETS = -5,       /* num_sets outside 1..64                                   */
+    DGN_ERR_WORKSPACE_TOO_SMALL = -6, /* graph_bytes or scratch_bytes below the queried size      */
+    DGN_ERR_NOT_TOPOLOGICAL = -7,     /* validation found a producer id >= its consumer id        */
+    DGN_ERR_HIP = -8,                 /* a HIP call failed; see dgn_last_hip_error()              */
+    DGN_ERR_BAD_CSR = -9              /* row pointers not monotone or not ending at nnz           */
+};
+
+/* Operators as two COO edge lists, in any order (Sec. 2.2: an operator with its inputs and its
+ * outputs).  Edge e of the first list says "operator in_op[e] reads tensor in_tensor[e]", edge e
+ * of the second "operator out_op[e] writes tensor out_tensor[e]".
+ * A packed batch of independent graphs (num_graphs > 1) uses global ids; graph g owns operators
+ * [graph_op_offsets[g], graph_op_offsets[g+1]) and tensors likewise; no edge may cross graphs. */
+typedef struct dgn_coo_desc {
+    int64_t num_ops, num_tensors;
+    int64_t nnz_in, nnz_out;
+    const int32_t *in_op, *in_tensor;       /* device [nnz_in]  */
+    const int32_t *out_op, *out_tensor;     /* device [nnz_out] */
+    int32_t num_graphs;                     /* 1, or G for a packed batch */
+    const int64_t *graph_op_offsets;        /* HOST [G+1], or NULL when num_graphs == 1 */
+    const int64_t *graph_tensor_offsets;    /* HOST [G+1], or NULL when num_graphs == 1 */
+} dgn_coo_desc;
+
+/* The same graph already in CSR form (operator -> inputs, operator -> outputs).  The four arrays
+ * are BORROWED: they must stay valid and unchanged for the life of the handle. */
+typedef struct dgn_csr_desc {
+    int64_t num_ops, num_tensors;
+    int64_t nnz_in, nnz_out;
+    const int32_t *in_rowptr, *in_idx;      /* device [num_ops+1], [nnz_in]  */
+    const int32_t *out_rowptr, *out_idx;    /* device [num_ops+1], [nnz_out] */
+    int32_t num_graphs;
+    const int64_t *graph_op_offsets;        /* HOST [G+1] or NULL */
+    const int64_t *graph_tensor_offsets;    /* HOST [G+1] or NULL */
+} dgn_csr_desc;
+
+typedef struct dgn_options {
+    int32_t validate;        /* build: also check the topological precondition (one extra pass)   */
+    int32_t recompute_keep;  /* prune: recompute K from M with the stand-alone removal-rule pass
+                                instead of using the K the traversal accumulated (same values)   */
+    int32_t traversal;       /* 0 = automatic; 1 = force the generic one-launch-per-level path   */
+    int32_t reserved[5];     /* must be zero */
+} dgn_options;
+
+/* Schedule-dependent counters (not part of the result; excluded from parity). HOST struct. */
+typedef struct dgn_stats {
+    int64_t levels;          /* frontier levels processed                                        */
+    int64_t tensor_visits;   /* frontier entries processed, summed over levels                   */
+    int64_t max_frontier;    /* largest frontier                                                 */
+    int64_t launches;        /* kernels enqueued by the call                                     */
+    int64_t reserved[4];
+} dgn_stats;
+
+/* ---- graph construction -------------------------------------------------------------------- */
+
+/* Bytes of caller-provided device storage for the graph (lives as long as the handle) and of
+ * scratch (needed only during dgn_graph_build).  Validates the descriptor's sizes on the host. */
+int dgn_graph_build_workspace(const dgn_coo_desc *desc, size_t *graph_bytes, size_t *scratch_bytes);
+
+/* Build, on the device, the adjacency the traversal needs (Sec. 2.2 edge definition):
+ *   operator -> input tensors   CSR, rows keep the COO order of their edges (stable);
+ *   operator -> output tensors  CSR, likewise;
+ *   tensor   -> producing operators CSR, rows ascending in operator id.
+ * Stable LSD radix sort on the significant key bits plus prefix sums, all inside graph_mem /
+ * scratch.  Every id is range-checked on the device (-> DGN_ERR_ID_OUT_OF_RANGE); with
+ * options->validate the topological precondition is checked too (-> DGN_ERR_NOT_TOPOLOGICAL).
+ * The call synchronises the stream once before returning to report those errors.  options may be
+ * NULL.  On success *out receives a handle; scratch may be reused afterwards, graph_mem may not. */
+int dgn_graph_build(const dgn_coo_desc *desc, void *graph_mem, size_t graph_bytes, void *scratch,
+                    size_t scratch_bytes, const dgn_options *options, dgn_stream stream,
+                    dgn_graph **out);
+
+int dgn_graph_from_csr_workspace(const dgn_csr_desc *desc, size_t *graph_bytes, size_t *scratch_bytes);
+
+/* As dgn_graph_build, for a caller that already holds the two operator CSRs: only the
+ * tensor -> producer CSR is built (into graph_mem).  Row pointers are checked to be monotone and
+ * to end at nnz (-> DGN_ERR_BAD_CSR), ids are range-checked. */
+int dgn_graph_from_csr(const dgn_csr_desc *desc, void *graph_mem, size_t graph_bytes, void *scratch,
+                       size_t scratch_bytes, const dgn_options *options, dgn_stream stream,
+                       dgn_graph **out);
+
+/* Device pointers of the built adjacency (any output pointer may be NULL).  For parity checks of
+ * the builder; the arrays belong to the handle's graph_mem (or to the caller for borrowed CSRs). */
+int dgn_graph_get_csr(const dgn_graph *g, const int32_t **in_rowptr, const int32_t **in_idx,
+                      const int32_t **out_rowptr, const int32_t **out_idx,
+                      const int32_t **prod_rowptr, const int32_t **prod_idx);
+
+/* Sizes of a built graph (any output pointer may be NULL). */
+int dgn_graph_get_sizes(const dgn_graph *g, int64_t *num_ops, int64_t *num_tensors, int64_t *nnz_in,
+                        int64_t *nnz_out, int32_t *num_graphs);
+
+/* Frees the host handle only (device storage belongs to the caller). NULL is accepted. */
+void dgn_graph_destroy(dgn_graph *g);
+
+/* ---- Forward Prune ----------------------------------------------------------------------- */
+
+/* Scratch bytes dgn_prune / dgn_keep_compact need for this graph. */
+int dgn_prune_workspace(const dgn_graph *g, int32_t num_sets, size_t *scratch_bytes);
+
+/* Algorithm 1 for num_sets (= Q, 1..64) target sets per graph at once, then the removal rule of
+ * Sec. 2.1 and the creation-order compaction of Sec. 3.2.
+ *
+ *   tgt_rowptr [G*Q+1], tgt_idx [num_targets]: CSR of the target sets; set s = g*Q + q belongs to
+ *       graph g and owns bit q.  Ids are global tensor ids.  Empty sets, duplicate targets and a
+ *       tensor in several sets are legal.  An id outside [0, num_tensors) is skipped and reported
+ *       as DGN_ERR_ID_OUT_OF_RANGE.
+ *   tensor_mask [num_tensors]  out: M.   op_mask [num_ops]  out: K.  Bits >= Q are zero.
+ *   op_flag     [num_ops]      out: K != 0 as 0/1 bytes; may be NULL.
+ *   kept_ops    [num_ops]      out: ascending ids of the operators with K != 0 (first kept_count).
+ *   kept_masks  [num_ops]      out: K of each kept operator, parallel to kept_ops; may be NULL.
+ *   kept_count  out int64: [0] = number kept; for a packed batch additionally [1+g], g = 0..G, =
+ *       number of kept operators with id < graph_op_offsets[g]  (so [1 + G + 1] entries).
+ *   per_query_count out int64 [64], or [G*64] for a packed batch: operators whose K has bit q;
+ *       may be NULL.
+ *   options, stats: HOST, may be NULL.
+ *
+ * All outputs are cleared and rewritten in full by the call.  Kernels run on `stream`; the call
+ * reads a few status words back and synchronises the stream before returning, because the number
+ * of frontier levels depends on the data.  Calls on the same graph may run concurrently only with
+ * distinct scratch and output buffers. */
+int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const int32_t *tgt_rowptr,
+              const int32_t *tgt_idx, uint64_t *tensor_mask, uint64_t *op_mask, uint8_t *op_flag,
+              int32_t *kept_ops, uint64_t *kept_masks, int64_t *kept_count, int64_t *per_query_count,
+              void *scratch, size_t scratch_bytes, const dgn_options *options, dgn_stats *stats,
+              dgn_stream stream);
+
+/* Removal rule + compaction only (Sec. 2.1, Sec. 3.2), for a caller that supplies the coloured
+ * masks: K[o] = OR of tensor_mask_in over the outputs of o, then the same outputs as dgn_prune.
+ * Asynchronous on `stream`: nothing is read back. */
+int dgn_keep_compact(const dgn_graph *g, const uint64_t *tensor_mask_in, uint64_t *op_mask,
+                     uint8_t *op_flag, int32_t *kept_ops, uint64_t *kept_masks, int64_t *kept_count,
+                     int64_t *per_query_count, void *scratch, size_t scratch_bytes, dgn_stream stream);
+
+/* ---- misc ---------------------------------------------------------------------------------- */
+const char *dgn_strerror(int code);
+int dgn_version(void);
+int dgn_last_hip_error(void);   /* hipError_t of the last failed HIP call on this thread */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DGN_H */

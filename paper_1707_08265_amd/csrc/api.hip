@@ -1,0 +1,506 @@
+// C ABI of libdgn: argument checking, workspace layout and kernel sequencing (declared in dgn.h).
+// Host code only decides *which* kernels run and where their buffers live; every step of the path
+// itself (adjacency build, seeding, traversal, removal rule, compaction) is a device kernel.
+#include <new>
+#include <string.h>
+
+#include "common.h"
+
+using namespace dgn;
+
+namespace {
+
+thread_local int t_last_hip = 0;
+
+inline int hip_fail(hipError_t e)
+{
+    t_last_hip = (int)e;
+    return DGN_ERR_HIP;
+}
+#define DGN_HIP(expr)                                   \
+    do {                                                \
+        hipError_t e__ = (expr);                        \
+        if (e__ != hipSuccess) return hip_fail(e__);    \
+    } while (0)
+
+constexpr int64_t kMaxCount = 2147483646;   // counts must stay below 2^31 - 1
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// carve consecutive 256-byte aligned regions out of one buffer
+struct Carver {
+    char *base;
+    size_t off = 0;
+    explicit Carver(void *p) : base(static_cast<char *>(p)) {}
+    template <typename T> T *take(size_t count)
+    {
+        T *r = base ? reinterpret_cast<T *>(base + off) : nullptr;
+        off += align256(count * sizeof(T));
+        return r;
+    }
+};
+
+inline int key_bits_for(int64_t n)
+{
+    int b = 1;
+    while (b < 31 && ((int64_t)1 << b) < n) ++b;
+    return b;
+}
+
+int check_sizes(int64_t P, int64_t T, int64_t Ein, int64_t Eout, int32_t G, const int64_t *op_off,
+                const int64_t *t_off)
+{
+    if (P < 0 || T < 0 || Ein < 0 || Eout < 0 || G < 1) return DGN_ERR_INVALID_ARG;
+    if (P > kMaxCount || T > kMaxCount || Ein > kMaxCount || Eout > kMaxCount) return DGN_ERR_TOO_LARGE;
+    if (G > 1) {
+        if (!op_off || !t_off) return DGN_ERR_NULL_PTR;
+        if (op_off[0] != 0 || t_off[0] != 0 || op_off[G] != P || t_off[G] != T) return DGN_ERR_INVALID_ARG;
+        for (int32_t g = 0; g < G; ++g)
+            if (op_off[g + 1] < op_off[g] || t_off[g + 1] < t_off[g]) return DGN_ERR_INVALID_ARG;
+    }
+    return DGN_OK;
+}
+
+struct GraphLayout {
+    int32_t *in_rowptr, *in_idx, *out_rowptr, *out_idx, *prod_rowptr, *prod_idx;
+    int64_t *op_off, *t_off;
+    size_t bytes;
+};
+
+GraphLayout graph_layout(void *mem, int64_t P, int64_t T, int64_t Ein, int64_t Eout, int32_t G, bool own_op_csr)
+{
+    Carver c(mem);
+    GraphLayout L{};
+    if (own_op_csr) {
+        L.in_rowptr = c.take<int32_t>(P + 1);
+        L.in_idx = c.take<int32_t>(Ein);
+        L.out_rowptr = c.take<int32_t>(P + 1);
+        L.out_idx = c.take<int32_t>(Eout);
+    }
+    L.prod_rowptr = c.take<int32_t>(T + 1);
+    L.prod_idx = c.take<int32_t>(Eout);
+    if (G > 1) {
+        L.op_off = c.take<int64_t>(G + 1);
+        L.t_off = c.take<int64_t>(G + 1);
+    }
+    L.bytes = c.off > 0 ? c.off : 256;
+    return L;
+}
+
+struct BuildScratch {
+    int32_t *status;        // [64] ints; status[0] = error bits
+    int32_t *sorted_ops;    // [Eout] operator id of every entry of out_idx
+    void *sort_tmp;
+    void *scan_tmp;
+    size_t bytes;
+};
+
+BuildScratch build_scratch(void *mem, int64_t P, int64_t T, int64_t Ein, int64_t Eout)
+{
+    Carver c(mem);
+    BuildScratch S{};
+    S.status = c.take<int32_t>(64);
+    S.sorted_ops = c.take<int32_t>(Eout);
+    const int64_t emax = Ein > Eout ? Ein : Eout;
+    S.sort_tmp = c.take<char>(sort_tmp_bytes(emax));
+    S.scan_tmp = c.take<char>(scan_tmp_bytes((P > T ? P : T) + 1));
+    S.bytes = c.off;
+    return S;
+}
+
+struct PruneScratch {
+    TravState *state;
+    int32_t *q0, *q1;
+    u64 *bm0, *bm1;
+    u64 *opbits;
+    int32_t *block_counts;
+    size_t bm_bytes, opbits_bytes;
+    size_t bytes;
+};
+
+PruneScratch prune_scratch(void *mem, int64_t P, int64_t T)
+{
+    Carver c(mem);
+    PruneScratch S{};
+    S.state = c.take<TravState>(4);
+    S.q0 = c.take<int32_t>(T);
+    S.q1 = c.take<int32_t>(T);
+    const size_t bmw = (size_t)((T + 63) / 64);
+    S.bm0 = c.take<u64>(bmw);
+    S.bm1 = c.take<u64>(bmw);
+    S.bm_bytes = bmw * 8;
+    const size_t obw = (size_t)((P + 63) / 64);
+    S.opbits = c.take<u64>(obw);
+    S.opbits_bytes = obw * 8;
+    S.block_counts = c.take<int32_t>((P + kCompactTile - 1) / kCompactTile + 1);
+    S.bytes = c.off;
+    return S;
+}
+
+// One small pinned buffer per host thread for status read-backs (never freed: a few hundred bytes).
+int pinned_buffer(void **out)
+{
+    thread_local void *buf = nullptr;
+    if (!buf) DGN_HIP(hipHostMalloc(&buf, 256, hipHostMallocDefault));
+    *out = buf;
+    return DGN_OK;
+}
+
+int error_bits_to_code(int32_t bits)
+{
+    if (bits & kErrCsr) return DGN_ERR_BAD_CSR;
+    if (bits & (kErrIdRange | kErrCrossGraph)) return DGN_ERR_ID_OUT_OF_RANGE;
+    if (bits & kErrTopo) return DGN_ERR_NOT_TOPOLOGICAL;
+    return DGN_OK;
+}
+
+int check_options(const dgn_options *o)
+{
+    if (!o) return DGN_OK;
+    for (int i = 0; i < 5; ++i)
+        if (o->reserved[i] != 0) return DGN_ERR_INVALID_ARG;
+    if (o->traversal < 0 || o->traversal > 1) return DGN_ERR_INVALID_ARG;
+    return DGN_OK;
+}
+
+}  // namespace
+
+struct dgn_graph {
+    GraphView v;
+    int64_t P, T, Ein, Eout;
+    int32_t G;
+    int num_cus;
+};
+
+namespace {
+
+int finish_build(dgn_graph *h, const GraphLayout &L, const int64_t *op_off_host, const int64_t *t_off_host,
+                 int32_t *status, const dgn_options *options, hipStream_t s, dgn_graph **out)
+{
+    if (h->G > 1) {
+        DGN_HIP(hipMemcpyAsync(L.op_off, op_off_host, sizeof(int64_t) * (h->G + 1), hipMemcpyHostToDevice, s));
+        DGN_HIP(hipMemcpyAsync(L.t_off, t_off_host, sizeof(int64_t) * (h->G + 1), hipMemcpyHostToDevice, s));
+        h->v.op_off = L.op_off;
+        h->v.t_off = L.t_off;
+        DGN_HIP(launch_check_graph_ranges(h->v, status, s));
+    }
+    if (options && options->validate) DGN_HIP(launch_check_topological(h->v, status, s));
+    void *pin = nullptr;
+    int rc = pinned_buffer(&pin);
+    if (rc) return rc;
+    DGN_HIP(hipMemcpyAsync(pin, status, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    DGN_HIP(hipStreamSynchronize(s));
+    rc = error_bits_to_code(*static_cast<int32_t *>(pin));
+    if (rc) return rc;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    DGN_HIP(hipGetDevice(&dev));
+    DGN_HIP(hipGetDeviceProperties(&prop, dev));
+    h->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    *out = h;
+    return DGN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int dgn_version(void) { return DGN_VERSION; }
+int dgn_last_hip_error(void) { return t_last_hip; }
+
+const char *dgn_strerror(int code)
+{
+    switch (code) {
+        case DGN_OK: return "ok";
+        case DGN_ERR_INVALID_ARG: return "invalid argument";
+        case DGN_ERR_NULL_PTR: return "required pointer is NULL";
+        case DGN_ERR_TOO_LARGE: return "count too large for 32-bit ids";
+        case DGN_ERR_ID_OUT_OF_RANGE: return "operator, tensor or target id out of range";
+        case DGN_ERR_TOO_MANY_SETS: return "number of target sets must be 1..64";
+        case DGN_ERR_WORKSPACE_TOO_SMALL: return "graph storage or scratch smaller than the queried size";
+        case DGN_ERR_NOT_TOPOLOGICAL: return "operator ids are not a topological order";
+        case DGN_ERR_HIP: return "HIP runtime error";
+        case DGN_ERR_BAD_CSR: return "malformed CSR row pointers";
+        default: return "unknown error";
+    }
+}
+
+int dgn_graph_build_workspace(const dgn_coo_desc *d, size_t *graph_bytes, size_t *scratch_bytes)
+{
+    if (!d || !graph_bytes || !scratch_bytes) return DGN_ERR_NULL_PTR;
+    int rc = check_sizes(d->num_ops, d->num_tensors, d->nnz_in, d->nnz_out, d->num_graphs, d->graph_op_offsets,
+                         d->graph_tensor_offsets);
+    if (rc) return rc;
+    *graph_bytes = graph_layout(nullptr, d->num_ops, d->num_tensors, d->nnz_in, d->nnz_out, d->num_graphs, true).bytes;
+    *scratch_bytes = build_scratch(nullptr, d->num_ops, d->num_tensors, d->nnz_in, d->nnz_out).bytes;
+    return DGN_OK;
+}
+
+int dgn_graph_build(const dgn_coo_desc *d, void *graph_mem, size_t graph_bytes, void *scratch, size_t scratch_bytes,
+                    const dgn_options *options, dgn_stream stream, dgn_graph **out)
+{
+    if (!d || !out) return DGN_ERR_NULL_PTR;
+    *out = nullptr;
+    size_t need_g = 0, need_s = 0;
+    int rc = dgn_graph_build_workspace(d, &need_g, &need_s);
+    if (rc) return rc;
+    rc = check_options(options);
+    if (rc) return rc;
+    if (!graph_mem || !scratch) return DGN_ERR_NULL_PTR;
+    if ((d->nnz_in > 0 && (!d->in_op || !d->in_tensor)) || (d->nnz_out > 0 && (!d->out_op || !d->out_tensor)))
+        return DGN_ERR_NULL_PTR;
+    if (graph_bytes < need_g || scratch_bytes < need_s) return DGN_ERR_WORKSPACE_TOO_SMALL;
+    if (((uintptr_t)graph_mem | (uintptr_t)scratch) & 7) return DGN_ERR_INVALID_ARG;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t P = d->num_ops, T = d->num_tensors, Ein = d->nnz_in, Eout = d->nnz_out;
+    const GraphLayout L = graph_layout(graph_mem, P, T, Ein, Eout, d->num_graphs, true);
+    const BuildScratch S = build_scratch(scratch, P, T, Ein, Eout);
+
+    // row degrees (with id range checks), then row pointers by prefix sum
+    FillRegion clr[4] = {{L.in_rowptr, align256((P + 1) * 4)},
+                         {L.out_rowptr, align256((P + 1) * 4)},
+                         {L.prod_rowptr, align256((T + 1) * 4)},
+                         {S.status, 256}};
+    DGN_HIP(launch_clear(clr, 4, s));
+    DGN_HIP(launch_degree_hist(d->in_op, d->in_tensor, Ein, (int32_t)P, (int32_t)T, L.in_rowptr, S.status, s));
+    DGN_HIP(launch_degree_hist(d->out_op, d->out_tensor, Eout, (int32_t)P, (int32_t)T, L.out_rowptr, S.status, s));
+    DGN_HIP(launch_degree_hist(d->out_tensor, d->out_op, Eout, (int32_t)T, (int32_t)P, L.prod_rowptr, S.status, s));
+    DGN_HIP(launch_exclusive_scan(L.in_rowptr, L.in_rowptr, P, S.scan_tmp, s));
+    DGN_HIP(launch_exclusive_scan(L.out_rowptr, L.out_rowptr, P, S.scan_tmp, s));
+    DGN_HIP(launch_exclusive_scan(L.prod_rowptr, L.prod_rowptr, T, S.scan_tmp, s));
+    // stable sorts: edges by operator (rows keep COO order), then outputs by tensor, which leaves each
+    // tensor's producers ascending in operator id
+    DGN_HIP(launch_sort_pairs(d->in_op, d->in_tensor, nullptr, L.in_idx, Ein, key_bits_for(P), S.sort_tmp, s));
+    DGN_HIP(launch_sort_pairs(d->out_op, d->out_tensor, S.sorted_ops, L.out_idx, Eout, key_bits_for(P), S.sort_tmp, s));
+    DGN_HIP(launch_sort_pairs(L.out_idx, S.sorted_ops, nullptr, L.prod_idx, Eout, key_bits_for(T), S.sort_tmp, s));
+
+    dgn_graph *h = new (std::nothrow) dgn_graph();
+    if (!h) return DGN_ERR_INVALID_ARG;
+    h->P = P; h->T = T; h->Ein = Ein; h->Eout = Eout; h->G = d->num_graphs;
+    h->v = GraphView{(int32_t)P, (int32_t)T, (int32_t)Ein, (int32_t)Eout, d->num_graphs, L.in_rowptr, L.in_idx,
+                     L.out_rowptr, L.out_idx, L.prod_rowptr, L.prod_idx, nullptr, nullptr};
+    rc = finish_build(h, L, d->graph_op_offsets, d->graph_tensor_offsets, S.status, options, s, out);
+    if (rc) delete h;
+    return rc;
+}
+
+int dgn_graph_from_csr_workspace(const dgn_csr_desc *d, size_t *graph_bytes, size_t *scratch_bytes)
+{
+    if (!d || !graph_bytes || !scratch_bytes) return DGN_ERR_NULL_PTR;
+    int rc = check_sizes(d->num_ops, d->num_tensors, d->nnz_in, d->nnz_out, d->num_graphs, d->graph_op_offsets,
+                         d->graph_tensor_offsets);
+    if (rc) return rc;
+    *graph_bytes = graph_layout(nullptr, d->num_ops, d->num_tensors, d->nnz_in, d->nnz_out, d->num_graphs, false).bytes;
+    *scratch_bytes = build_scratch(nullptr, d->num_ops, d->num_tensors, d->nnz_in, d->nnz_out).bytes;
+    return DGN_OK;
+}
+
+int dgn_graph_from_csr(const dgn_csr_desc *d, void *graph_mem, size_t graph_bytes, void *scratch, size_t scratch_bytes,
+                       const dgn_options *options, dgn_stream stream, dgn_graph **out)
+{
+    if (!d || !out) return DGN_ERR_NULL_PTR;
+    *out = nullptr;
+    size_t need_g = 0, need_s = 0;
+    int rc = dgn_graph_from_csr_workspace(d, &need_g, &need_s);
+    if (rc) return rc;
+    rc = check_options(options);
+    if (rc) return rc;
+    if (!graph_mem || !scratch || !d->in_rowptr || !d->out_rowptr) return DGN_ERR_NULL_PTR;
+    if ((d->nnz_in > 0 && !d->in_idx) || (d->nnz_out > 0 && !d->out_idx)) return DGN_ERR_NULL_PTR;
+    if (graph_bytes < need_g || scratch_bytes < need_s) return DGN_ERR_WORKSPACE_TOO_SMALL;
+    if (((uintptr_t)graph_mem | (uintptr_t)scratch) & 7) return DGN_ERR_INVALID_ARG;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t P = d->num_ops, T = d->num_tensors, Ein = d->nnz_in, Eout = d->nnz_out;
+    const GraphLayout L = graph_layout(graph_mem, P, T, Ein, Eout, d->num_graphs, false);
+    const BuildScratch S = build_scratch(scratch, P, T, Ein, Eout);
+
+    FillRegion clr[2] = {{L.prod_rowptr, align256((T + 1) * 4)}, {S.status, 256}};
+    DGN_HIP(launch_clear(clr, 2, s));
+    // the borrowed arrays are checked before any kernel trusts them
+    DGN_HIP(launch_check_csr(d->in_rowptr, d->in_idx, (int32_t)P, (int32_t)Ein, (int32_t)T, S.status, s));
+    DGN_HIP(launch_check_csr(d->out_rowptr, d->out_idx, (int32_t)P, (int32_t)Eout, (int32_t)T, S.status, s));
+    void *pin = nullptr;
+    rc = pinned_buffer(&pin);
+    if (rc) return rc;
+    DGN_HIP(hipMemcpyAsync(pin, S.status, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    DGN_HIP(hipStreamSynchronize(s));
+    rc = error_bits_to_code(*static_cast<int32_t *>(pin));
+    if (rc) return rc;
+
+    DGN_HIP(launch_expand_rows(d->out_rowptr, (int32_t)P, S.sorted_ops, s));
+    DGN_HIP(launch_degree_hist(d->out_idx, nullptr, Eout, (int32_t)T, 1, L.prod_rowptr, S.status, s));
+    DGN_HIP(launch_exclusive_scan(L.prod_rowptr, L.prod_rowptr, T, S.scan_tmp, s));
+    DGN_HIP(launch_sort_pairs(d->out_idx, S.sorted_ops, nullptr, L.prod_idx, Eout, key_bits_for(T), S.sort_tmp, s));
+
+    dgn_graph *h = new (std::nothrow) dgn_graph();
+    if (!h) return DGN_ERR_INVALID_ARG;
+    h->P = P; h->T = T; h->Ein = Ein; h->Eout = Eout; h->G = d->num_graphs;
+    h->v = GraphView{(int32_t)P, (int32_t)T, (int32_t)Ein, (int32_t)Eout, d->num_graphs, d->in_rowptr, d->in_idx,
+                     d->out_rowptr, d->out_idx, L.prod_rowptr, L.prod_idx, nullptr, nullptr};
+    rc = finish_build(h, L, d->graph_op_offsets, d->graph_tensor_offsets, S.status, options, s, out);
+    if (rc) delete h;
+    return rc;
+}
+
+int dgn_graph_get_csr(const dgn_graph *g, const int32_t **in_rowptr, const int32_t **in_idx, const int32_t **out_rowptr,
+                      const int32_t **out_idx, const int32_t **prod_rowptr, const int32_t **prod_idx)
+{
+    if (!g) return DGN_ERR_NULL_PTR;
+    if (in_rowptr) *in_rowptr = g->v.in_rowptr;
+    if (in_idx) *in_idx = g->v.in_idx;
+    if (out_rowptr) *out_rowptr = g->v.out_rowptr;
+    if (out_idx) *out_idx = g->v.out_idx;
+    if (prod_rowptr) *prod_rowptr = g->v.prod_rowptr;
+    if (prod_idx) *prod_idx = g->v.prod_idx;
+    return DGN_OK;
+}
+
+int dgn_graph_get_sizes(const dgn_graph *g, int64_t *num_ops, int64_t *num_tensors, int64_t *nnz_in, int64_t *nnz_out,
+                        int32_t *num_graphs)
+{
+    if (!g) return DGN_ERR_NULL_PTR;
+    if (num_ops) *num_ops = g->P;
+    if (num_tensors) *num_tensors = g->T;
+    if (nnz_in) *nnz_in = g->Ein;
+    if (nnz_out) *nnz_out = g->Eout;
+    if (num_graphs) *num_graphs = g->G;
+    return DGN_OK;
+}
+
+void dgn_graph_destroy(dgn_graph *g) { delete g; }
+
+int dgn_prune_workspace(const dgn_graph *g, int32_t num_sets, size_t *scratch_bytes)
+{
+    if (!g || !scratch_bytes) return DGN_ERR_NULL_PTR;
+    if (num_sets < 1 || num_sets > DGN_MAX_SETS) return DGN_ERR_TOO_MANY_SETS;
+    *scratch_bytes = prune_scratch(nullptr, g->P, g->T).bytes;
+    return DGN_OK;
+}
+
+int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const int32_t *tgt_rowptr,
+              const int32_t *tgt_idx, uint64_t *tensor_mask, uint64_t *op_mask, uint8_t *op_flag, int32_t *kept_ops,
+              uint64_t *kept_masks, int64_t *kept_count, int64_t *per_query_count, void *scratch, size_t scratch_bytes,
+              const dgn_options *options, dgn_stats *stats, dgn_stream stream)
+{
+    if (!g) return DGN_ERR_NULL_PTR;
+    if (num_sets < 1 || num_sets > DGN_MAX_SETS) return DGN_ERR_TOO_MANY_SETS;
+    if (num_targets < 0) return DGN_ERR_INVALID_ARG;
+    if (num_targets > kMaxCount) return DGN_ERR_TOO_LARGE;
+    int rc = check_options(options);
+    if (rc) return rc;
+    if (!tgt_rowptr || (num_targets > 0 && !tgt_idx) || !kept_count || !scratch) return DGN_ERR_NULL_PTR;
+    if ((g->T > 0 && !tensor_mask) || (g->P > 0 && (!op_mask || !kept_ops))) return DGN_ERR_NULL_PTR;
+    const PruneScratch S = prune_scratch(scratch, g->P, g->T);
+    if (scratch_bytes < S.bytes) return DGN_ERR_WORKSPACE_TOO_SMALL;
+    if (((uintptr_t)scratch | (uintptr_t)tensor_mask | (uintptr_t)op_mask | (uintptr_t)kept_masks |
+         (uintptr_t)kept_count | (uintptr_t)per_query_count) & 7)
+        return DGN_ERR_INVALID_ARG;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    u64 *M = reinterpret_cast<u64 *>(tensor_mask);
+    u64 *K = reinterpret_cast<u64 *>(op_mask);
+    const size_t pq_bytes = per_query_count ? sizeof(int64_t) * 64 * (size_t)(g->G > 1 ? g->G : 1) : 0;
+    int64_t launches = 0;
+
+    // nothing marked yet: clear outputs, frontier bitmaps and traversal state
+    FillRegion clr[6] = {{M, (size_t)g->T * 8}, {K, (size_t)g->P * 8},  {S.bm0, S.bm_bytes},
+                         {S.bm1, S.bm_bytes},   {S.state, 256},         {per_query_count, pq_bytes}};
+    DGN_HIP(launch_clear(clr, 6, s));
+    DGN_HIP(launch_seed(g->v, num_sets, num_targets, tgt_rowptr, tgt_idx, M, S.state, S.q0, S.bm0, s));
+    launches += 2;
+
+    CompactArgs ca{};
+    ca.g = g->v;
+    ca.M = M;
+    ca.K = K;
+    ca.op_flag = op_flag;
+    ca.kept_ops = kept_ops;
+    ca.kept_masks = reinterpret_cast<u64 *>(kept_masks);
+    ca.kept_count = kept_count;
+    ca.per_query_count = per_query_count;
+    ca.opbits = S.opbits;
+    ca.block_counts = S.block_counts;
+    ca.from_tensor_mask = options && options->recompute_keep;
+
+    void *pin = nullptr;
+    rc = pinned_buffer(&pin);
+    if (rc) return rc;
+    const TravState *hst = static_cast<const TravState *>(pin);
+
+    // Level loop.  The number of levels depends on the data, so levels are enqueued in batches and the
+    // state is read back after each batch; the removal-rule/compaction passes are enqueued right behind
+    // the first batch (almost always enough) and simply redone if the traversal turns out unfinished.
+    int grid = g->num_cus * 8;
+    const int64_t max_useful = (g->T + 255) / 256;
+    if (grid > max_useful) grid = (int)(max_useful > 0 ? max_useful : 1);
+    int launch_no = 0;
+    int batch = 48;
+    bool compacted = false;
+    for (;;) {
+        for (int i = 0; i < batch; ++i, ++launch_no)
+            DGN_HIP(launch_level(g->v, S.state, launch_no, S.q0, S.q1, S.bm0, S.bm1, M, K, grid, s));
+        launches += batch;
+        if (!compacted) {
+            DGN_HIP(launch_keep_compact(ca, s));
+            launches += 3 + (g->G > 1);
+        }
+        DGN_HIP(hipMemcpyAsync(pin, S.state, sizeof(TravState), hipMemcpyDeviceToHost, s));
+        DGN_HIP(hipStreamSynchronize(s));
+        const bool done = hst->slot[launch_no & 1].n == 0;
+        if (done && !compacted) { compacted = true; break; }
+        if (done) {
+            FillRegion pq[1] = {{per_query_count, pq_bytes}};
+            DGN_HIP(launch_clear(pq, 1, s));
+            DGN_HIP(launch_keep_compact(ca, s));
+            DGN_HIP(hipStreamSynchronize(s));
+            launches += 4 + (g->G > 1);
+            break;
+        }
+        compacted = true;          // the speculative pass ran on unfinished masks; it will be redone
+        if (batch < 1024) batch *= 2;
+    }
+    if (stats) {
+        memset(stats, 0, sizeof(*stats));
+        stats->levels = hst->slot[launch_no & 1].level;
+        stats->tensor_visits = (int64_t)hst->tensor_visits;
+        stats->max_frontier = (int64_t)hst->max_frontier;
+        stats->launches = launches;
+    }
+    return error_bits_to_code(hst->error);
+}
+
+int dgn_keep_compact(const dgn_graph *g, const uint64_t *tensor_mask_in, uint64_t *op_mask, uint8_t *op_flag,
+                     int32_t *kept_ops, uint64_t *kept_masks, int64_t *kept_count, int64_t *per_query_count,
+                     void *scratch, size_t scratch_bytes, dgn_stream stream)
+{
+    if (!g) return DGN_ERR_NULL_PTR;
+    if (!kept_count || !scratch) return DGN_ERR_NULL_PTR;
+    if ((g->T > 0 && !tensor_mask_in) || (g->P > 0 && (!op_mask || !kept_ops))) return DGN_ERR_NULL_PTR;
+    const PruneScratch S = prune_scratch(scratch, g->P, g->T);
+    if (scratch_bytes < S.bytes) return DGN_ERR_WORKSPACE_TOO_SMALL;
+    if (((uintptr_t)scratch | (uintptr_t)tensor_mask_in | (uintptr_t)op_mask | (uintptr_t)kept_masks |
+         (uintptr_t)kept_count | (uintptr_t)per_query_count) & 7)
+        return DGN_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t pq_bytes = per_query_count ? sizeof(int64_t) * 64 * (size_t)(g->G > 1 ? g->G : 1) : 0;
+    FillRegion pq[1] = {{per_query_count, pq_bytes}};
+    DGN_HIP(launch_clear(pq, 1, s));
+    CompactArgs ca{};
+    ca.g = g->v;
+    ca.M = reinterpret_cast<const u64 *>(tensor_mask_in);
+    ca.K = reinterpret_cast<u64 *>(op_mask);
+    ca.op_flag = op_flag;
+    ca.kept_ops = kept_ops;
+    ca.kept_masks = reinterpret_cast<u64 *>(kept_masks);
+    ca.kept_count = kept_count;
+    ca.per_query_count = per_query_count;
+    ca.opbits = S.opbits;
+    ca.block_counts = S.block_counts;
+    ca.from_tensor_mask = true;
+    DGN_HIP(launch_keep_compact(ca, s));
+    return DGN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,148 @@
+// Internal declarations shared by the translation units of libdgn (gfx950, wave64 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dgn.h"
+
+typedef unsigned long long u64;   // matches the operand type of HIP's 64-bit atomics
+static_assert(sizeof(u64) == sizeof(uint64_t), "u64 must be 64 bits");
+
+namespace dgn {
+
+constexpr int kWave = 64;
+
+// Sticky device-side error bits (TravState::error, BuildStatus::error).
+enum : int32_t {
+    kErrIdRange = 1,      // operator / tensor / target id out of range
+    kErrTopo = 2,         // producer id >= consumer id
+    kErrCsr = 4,          // row pointers not monotone / not ending at nnz
+    kErrCrossGraph = 8,   // target or edge outside its own packed graph
+};
+
+// Adjacency of a built graph as the kernels see it (device pointers).
+struct GraphView {
+    int32_t num_ops, num_tensors;
+    int32_t nnz_in, nnz_out;
+    int32_t num_graphs;
+    const int32_t *in_rowptr, *in_idx;
+    const int32_t *out_rowptr, *out_idx;
+    const int32_t *prod_rowptr, *prod_idx;
+    const int64_t *op_off, *t_off;    // [G+1] device copies, NULL when num_graphs == 1
+};
+
+// One slot of traversal state.  Launch number e reads slot e&1 and its finishing block writes
+// slot (e+1)&1, so a block of launch e that starts late never sees state of the next level.
+struct LevelSlot {
+    int32_t level;   // levels completed so far; queue parity = level & 1
+    int32_t n;       // entries in the frontier to process (the *other* slot's n collects pushes)
+};
+
+struct TravState {
+    LevelSlot slot[2];
+    int32_t ticket;          // working blocks that have finished the current launch
+    int32_t error;           // sticky kErr* bits
+    int32_t pad[2];
+    u64 tensor_visits;       // sum of frontier sizes
+    u64 max_frontier;
+    u64 pad2[2];
+};
+static_assert(sizeof(TravState) == 64, "TravState is read back as 64 bytes");
+
+// ---- wave64 helpers ---------------------------------------------------------------------------
+__device__ __forceinline__ int lane_id() { return (int)__lane_id(); }
+__device__ __forceinline__ u64 lanemask_lt() { return ((u64)1 << lane_id()) - 1; }
+__device__ __forceinline__ u64 ballot64(bool p) { return __ballot(p); }
+
+__device__ __forceinline__ int wave_incl_scan(int v)
+{
+    const int l = lane_id();
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        int t = __shfl_up(v, d, kWave);
+        if (l >= d) v += t;
+    }
+    return v;
+}
+__device__ __forceinline__ int wave_max(int v)
+{
+#pragma unroll
+    for (int d = kWave / 2; d >= 1; d >>= 1) v = max(v, __shfl_xor(v, d, kWave));
+    return v;
+}
+__device__ __forceinline__ int wave_sum(int v)
+{
+#pragma unroll
+    for (int d = kWave / 2; d >= 1; d >>= 1) v += __shfl_xor(v, d, kWave);
+    return v;
+}
+__device__ __forceinline__ u64 wave_or(u64 v)
+{
+#pragma unroll
+    for (int d = kWave / 2; d >= 1; d >>= 1) v |= (u64)__shfl_xor((long long)v, d, kWave);
+    return v;
+}
+__device__ __forceinline__ u64 shfl64(u64 v, int src) { return (u64)__shfl((long long)v, src, kWave); }
+
+// Loads that must observe atomics performed by other workgroups / earlier levels: go to the
+// device-coherent level instead of a possibly stale per-CU cache line.
+__device__ __forceinline__ u64 load_coherent(const u64 *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int32_t load_coherent(const int32_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// ---- launch wrappers (each returns a hipError_t; nothing synchronises) -------------------------
+struct FillRegion { void *ptr; size_t bytes; };   // ptr 8-byte aligned, bytes multiple of 8
+hipError_t launch_clear(const FillRegion *regions, int num_regions, hipStream_t s);
+
+// out[i] = sum_{j<i} in[j], i = 0..n (n+1 outputs; out[n] = total).  in/out may alias when `in`
+// holds n+1 entries.  tmp: scratch of scan_tmp_bytes(n) bytes.
+size_t scan_tmp_bytes(int64_t n);
+hipError_t launch_exclusive_scan(const int32_t *in, int32_t *out, int64_t n, void *tmp, hipStream_t s);
+
+// Stable LSD radix sort of (key, val) pairs on the low `key_bits` bits of the keys.
+// Result: vals_out (always) and keys_out (when not NULL).  keys_in / vals_in are not modified.
+// tmp: scratch of sort_tmp_bytes(n) bytes.
+size_t sort_tmp_bytes(int64_t n);
+hipError_t launch_sort_pairs(const int32_t *keys_in, const int32_t *vals_in, int32_t *keys_out,
+                             int32_t *vals_out, int64_t n, int key_bits, void *tmp, hipStream_t s);
+
+// deg[key[e]] += 1 for keys in [0, n_rows); flags keys / vals outside their ranges in *error.
+hipError_t launch_degree_hist(const int32_t *keys, const int32_t *vals, int64_t nnz, int32_t n_rows,
+                              int32_t n_vals, int32_t *deg, int32_t *error, hipStream_t s);
+hipError_t launch_check_csr(const int32_t *rowptr, const int32_t *idx, int32_t n_rows, int32_t nnz,
+                            int32_t n_vals, int32_t *error, hipStream_t s);
+hipError_t launch_expand_rows(const int32_t *rowptr, int32_t n_rows, int32_t *row_of, hipStream_t s);
+hipError_t launch_check_topological(const GraphView &g, int32_t *error, hipStream_t s);
+hipError_t launch_check_graph_ranges(const GraphView &g, int32_t *error, hipStream_t s);
+
+// Traversal.
+hipError_t launch_seed(const GraphView &g, int32_t Q, int64_t num_targets, const int32_t *tgt_rowptr,
+                       const int32_t *tgt_idx, u64 *M, TravState *st, int32_t *q0, u64 *bm0,
+                       hipStream_t s);
+hipError_t launch_level(const GraphView &g, TravState *st, int launch_no, int32_t *q0, int32_t *q1,
+                        u64 *bm0, u64 *bm1, u64 *M, u64 *K, int grid_blocks, hipStream_t s);
+
+// Removal rule + compaction.
+constexpr int kCompactTile = 2048;   // operators per workgroup in the count / scatter passes
+struct CompactArgs {
+    GraphView g;
+    const u64 *M;            // used when from_tensor_mask
+    u64 *K;
+    uint8_t *op_flag;        // may be NULL
+    int32_t *kept_ops;
+    u64 *kept_masks;         // may be NULL
+    int64_t *kept_count;
+    int64_t *per_query_count;   // may be NULL
+    u64 *opbits;             // [ceil(P/64)] scratch
+    int32_t *block_counts;   // [num_tiles + 1] scratch
+    bool from_tensor_mask;   // K := OR M[out] (true) or read K as accumulated by the traversal
+};
+hipError_t launch_keep_compact(const CompactArgs &a, hipStream_t s);
+
+}  // namespace dgn

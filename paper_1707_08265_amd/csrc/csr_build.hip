@@ -1,0 +1,145 @@
+// CSR builder support: row-degree histograms with id range checks, and the validation passes.
+// The adjacency follows the edge definition of Sec. 2.2 of the paper: an operator with the tensors it
+// reads and the tensors it writes; Parent(x) of Algorithm 1 = inputs of every operator that writes x.
+#include "common.h"
+
+namespace dgn {
+
+// deg[key] += 1.  Ids outside their range are reported and skipped, so later passes never index
+// out of bounds with them (the sort itself only ever uses masked digits of the keys).
+__global__ __launch_bounds__(256) void k_degree_hist(const int32_t *keys, const int32_t *vals, int64_t nnz,
+                                                      int32_t n_rows, int32_t n_vals, int32_t *deg, int32_t *error)
+{
+    const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
+    bool bad = false;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < nnz; e += gsize) {
+        const int32_t k = keys[e];
+        const int32_t v = vals ? vals[e] : 0;
+        if (k < 0 || k >= n_rows) { bad = true; continue; }
+        if (v < 0 || v >= n_vals) bad = true;
+        atomicAdd(&deg[k], 1);
+    }
+    if (ballot64(bad) != 0 && lane_id() == 0) atomicOr(error, kErrIdRange);
+}
+
+hipError_t launch_degree_hist(const int32_t *keys, const int32_t *vals, int64_t nnz, int32_t n_rows,
+                              int32_t n_vals, int32_t *deg, int32_t *error, hipStream_t s)
+{
+    if (nnz == 0) return hipSuccess;
+    int64_t blocks = (nnz + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(k_degree_hist, dim3((unsigned)blocks), dim3(256), 0, s, keys, vals, nnz, n_rows, n_vals,
+                       deg, error);
+    return hipGetLastError();
+}
+
+// Borrowed CSR: rowptr[0] == 0, monotone, rowptr[n_rows] == nnz, every idx in [0, n_vals).
+__global__ __launch_bounds__(256) void k_check_csr(const int32_t *rowptr, const int32_t *idx, int32_t n_rows,
+                                                    int32_t nnz, int32_t n_vals, int32_t *error)
+{
+    const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
+    const int64_t gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int bad = 0;
+    for (int64_t r = gtid; r <= n_rows; r += gsize) {
+        const int32_t a = rowptr[r];
+        if (a < 0 || a > nnz) bad |= kErrCsr;
+        if (r == 0 && a != 0) bad |= kErrCsr;
+        if (r == n_rows && a != nnz) bad |= kErrCsr;
+        if (r < n_rows && rowptr[r + 1] < a) bad |= kErrCsr;
+    }
+    for (int64_t e = gtid; e < nnz; e += gsize) {
+        const int32_t v = idx[e];
+        if (v < 0 || v >= n_vals) bad |= kErrIdRange;
+    }
+    if (bad) atomicOr(error, bad);
+}
+
+hipError_t launch_check_csr(const int32_t *rowptr, const int32_t *idx, int32_t n_rows, int32_t nnz,
+                            int32_t n_vals, int32_t *error, hipStream_t s)
+{
+    int64_t work = (int64_t)n_rows + 1 > nnz ? (int64_t)n_rows + 1 : nnz;
+    int64_t blocks = (work + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(k_check_csr, dim3((unsigned)blocks), dim3(256), 0, s, rowptr, idx, n_rows, nnz, n_vals, error);
+    return hipGetLastError();
+}
+
+// row_of[e] = r for every entry e of row r (operator id of every entry of a borrowed out CSR)
+__global__ __launch_bounds__(256) void k_expand_rows(const int32_t *rowptr, int32_t n_rows, int32_t *row_of)
+{
+    const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n_rows; r += gsize)
+        for (int32_t e = rowptr[r]; e < rowptr[r + 1]; ++e) row_of[e] = (int32_t)r;
+}
+
+hipError_t launch_expand_rows(const int32_t *rowptr, int32_t n_rows, int32_t *row_of, hipStream_t s)
+{
+    if (n_rows == 0) return hipSuccess;
+    int64_t blocks = ((int64_t)n_rows + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(k_expand_rows, dim3((unsigned)blocks), dim3(256), 0, s, rowptr, n_rows, row_of);
+    return hipGetLastError();
+}
+
+// Topological precondition (Sec. 3.2: operators run in creation order): every producer of an
+// operator's input was created before the operator.
+__global__ __launch_bounds__(256) void k_check_topological(GraphView g, int32_t *error)
+{
+    const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
+    bool bad = false;
+    for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < g.num_ops; o += gsize) {
+        for (int32_t e = g.in_rowptr[o]; e < g.in_rowptr[o + 1]; ++e) {
+            const int32_t t = g.in_idx[e];
+            if (t < 0 || t >= g.num_tensors) continue;      // reported by the range check
+            for (int32_t p = g.prod_rowptr[t]; p < g.prod_rowptr[t + 1]; ++p)
+                if (g.prod_idx[p] >= o) bad = true;
+        }
+    }
+    if (bad) atomicOr(error, kErrTopo);
+}
+
+hipError_t launch_check_topological(const GraphView &g, int32_t *error, hipStream_t s)
+{
+    if (g.num_ops == 0) return hipSuccess;
+    int64_t blocks = ((int64_t)g.num_ops + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(k_check_topological, dim3((unsigned)blocks), dim3(256), 0, s, g, error);
+    return hipGetLastError();
+}
+
+// Packed batch: every edge of an operator of graph g must touch a tensor of graph g.
+__device__ __forceinline__ int find_graph(const int64_t *off, int num_graphs, int64_t id)
+{
+    int lo = 0, hi = num_graphs;          // largest g with off[g] <= id
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (off[mid] <= id) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ __launch_bounds__(256) void k_check_graph_ranges(GraphView g, int32_t *error)
+{
+    const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
+    bool bad = false;
+    for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < g.num_ops; o += gsize) {
+        const int gi = find_graph(g.op_off, g.num_graphs, o);
+        const int64_t lo = g.t_off[gi], hi = g.t_off[gi + 1];
+        for (int32_t e = g.in_rowptr[o]; e < g.in_rowptr[o + 1]; ++e)
+            if (g.in_idx[e] < lo || g.in_idx[e] >= hi) bad = true;
+        for (int32_t e = g.out_rowptr[o]; e < g.out_rowptr[o + 1]; ++e)
+            if (g.out_idx[e] < lo || g.out_idx[e] >= hi) bad = true;
+    }
+    if (bad) atomicOr(error, kErrCrossGraph);
+}
+
+hipError_t launch_check_graph_ranges(const GraphView &g, int32_t *error, hipStream_t s)
+{
+    if (g.num_ops == 0 || g.num_graphs <= 1) return hipSuccess;
+    int64_t blocks = ((int64_t)g.num_ops + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(k_check_graph_ranges, dim3((unsigned)blocks), dim3(256), 0, s, g, error);
+    return hipGetLastError();
+}
+
+}  // namespace dgn

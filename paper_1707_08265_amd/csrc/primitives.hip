@@ -1,0 +1,167 @@
+// Streaming primitives: multi-region clear and device-wide exclusive prefix sum.
+// Both are pure HBM streams; the scan reads its input twice (reduce, then scan-with-offset) so that
+// no workgroup ever waits on another.
+#include "common.h"
+
+namespace dgn {
+
+// ------------------------------------------------------------------------------------------------
+// clear: the output masks must start at zero before the seeds are scattered (main loop of
+// Algorithm 1 starts from "nothing marked").  16-byte stores, grid-stride, up to 8 regions per launch.
+// ------------------------------------------------------------------------------------------------
+constexpr int kMaxClearRegions = 8;
+struct ClearArgs {
+    u64 *ptr[kMaxClearRegions];
+    size_t words[kMaxClearRegions];
+    int n;
+};
+
+__global__ __launch_bounds__(256) void k_clear(ClearArgs a)
+{
+    const size_t gtid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t gsize = (size_t)gridDim.x * blockDim.x;
+    for (int r = 0; r < a.n; ++r) {
+        u64 *p = a.ptr[r];
+        size_t w = a.words[r];
+        if (w == 0) continue;
+        if (((uintptr_t)p & 8) != 0) {          // make the bulk 16-byte aligned
+            if (gtid == 0) p[0] = 0;
+            ++p; --w;
+        }
+        ulonglong2 *p2 = reinterpret_cast<ulonglong2 *>(p);
+        const size_t pairs = w >> 1;
+        const ulonglong2 z = make_ulonglong2(0, 0);
+        for (size_t i = gtid; i < pairs; i += gsize) p2[i] = z;
+        if ((w & 1) && gtid == 0) p[w - 1] = 0;
+    }
+}
+
+hipError_t launch_clear(const FillRegion *regions, int num_regions, hipStream_t s)
+{
+    for (int base = 0; base < num_regions; base += kMaxClearRegions) {
+        ClearArgs a{};
+        size_t total = 0;
+        a.n = 0;
+        for (int r = base; r < num_regions && a.n < kMaxClearRegions; ++r) {
+            if (regions[r].bytes == 0 || regions[r].ptr == nullptr) continue;
+            a.ptr[a.n] = static_cast<u64 *>(regions[r].ptr);
+            a.words[a.n] = regions[r].bytes / 8;
+            total += a.words[a.n];
+            ++a.n;
+        }
+        if (a.n == 0) continue;
+        size_t blocks = (total / 2 + 255) / 256;
+        if (blocks < 1) blocks = 1;
+        if (blocks > 4096) blocks = 4096;     // 16 workgroups per CU, then grid-stride
+        hipLaunchKernelGGL(k_clear, dim3((unsigned)blocks), dim3(256), 0, s, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// ------------------------------------------------------------------------------------------------
+// exclusive scan (int32), n+1 outputs
+// ------------------------------------------------------------------------------------------------
+constexpr int kScanThreads = 256;
+constexpr int kScanItems = 8;
+constexpr int kScanTile = kScanThreads * kScanItems;
+
+__device__ __forceinline__ int block_excl_scan_256(int v, int *total, int *lds /* >= 5 ints */)
+{
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    int incl = wave_incl_scan(v);
+    if (lane == kWave - 1) lds[wave] = incl;
+    __syncthreads();
+    int woff = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kScanThreads / kWave; ++w) {
+        int c = lds[w];
+        if (w < wave) woff += c;
+        tot += c;
+    }
+    __syncthreads();
+    *total = tot;
+    return woff + incl - v;
+}
+
+__global__ __launch_bounds__(kScanThreads) void k_scan_reduce(const int32_t *in, int64_t n, int32_t *sums)
+{
+    __shared__ int lds[8];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+    int acc = 0;
+#pragma unroll
+    for (int k = 0; k < kScanItems; ++k)
+        if (base + k < n) acc += in[base + k];
+    acc = wave_sum(acc);
+    if (lane_id() == 0) lds[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) sums[blockIdx.x] = lds[0] + lds[1] + lds[2] + lds[3];
+}
+
+// One workgroup scans m entries in place (exclusive) and writes the total to v[m].
+__global__ __launch_bounds__(1024) void k_scan_single(int32_t *v, int64_t m)
+{
+    __shared__ int wtot[16];
+    __shared__ int carry_s;
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    for (int64_t base = 0; base < m; base += 1024) {
+        const int64_t i = base + threadIdx.x;
+        const int x = i < m ? v[i] : 0;
+        const int incl = wave_incl_scan(x);
+        if (lane == kWave - 1) wtot[wave] = incl;
+        __syncthreads();
+        int woff = 0, tot = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const int c = wtot[w];
+            if (w < wave) woff += c;
+            tot += c;
+        }
+        const int carry = carry_s;
+        if (i < m) v[i] = carry + woff + incl - x;
+        __syncthreads();
+        if (threadIdx.x == 0) carry_s = carry + tot;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) v[m] = carry_s;
+}
+
+__global__ __launch_bounds__(kScanThreads) void k_scan_apply(const int32_t *in, int32_t *out, int64_t n,
+                                                              const int32_t *offsets)
+{
+    __shared__ int lds[8];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+    int x[kScanItems];
+    int tsum = 0;
+#pragma unroll
+    for (int k = 0; k < kScanItems; ++k) {
+        x[k] = (base + k < n) ? in[base + k] : 0;
+        tsum += x[k];
+    }
+    int tot;
+    int run = offsets[blockIdx.x] + block_excl_scan_256(tsum, &tot, lds);   // barriers inside: all loads done
+#pragma unroll
+    for (int k = 0; k < kScanItems; ++k) {
+        if (base + k <= n) out[base + k] = run;     // position n receives the grand total
+        run += x[k];
+    }
+}
+
+static inline int64_t scan_blocks(int64_t n) { return (n + 1 + kScanTile - 1) / kScanTile; }
+
+size_t scan_tmp_bytes(int64_t n) { return (size_t)(scan_blocks(n) + 1) * sizeof(int32_t); }
+
+hipError_t launch_exclusive_scan(const int32_t *in, int32_t *out, int64_t n, void *tmp, hipStream_t s)
+{
+    const int64_t nb = scan_blocks(n);
+    int32_t *sums = static_cast<int32_t *>(tmp);
+    hipLaunchKernelGGL(k_scan_reduce, dim3((unsigned)nb), dim3(kScanThreads), 0, s, in, n, sums);
+    hipLaunchKernelGGL(k_scan_single, dim3(1), dim3(1024), 0, s, sums, nb);
+    hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)nb), dim3(kScanThreads), 0, s, in, out, n, sums);
+    return hipGetLastError();
+}
+
+}  // namespace dgn

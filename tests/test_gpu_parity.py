@@ -1,0 +1,209 @@
+"""GPU parity: the HIP path, called through the C ABI binding, against the CPU oracle, bit for bit
+(all arithmetic is integer / bitwise, so the bar is exact equality of masks, flags, counts and the
+compacted order)."""
+import numpy as np
+import pytest
+
+import graphgen as gg
+from helpers import graph_from_ops, load_worked_example, random_small_graph, targets_from_sets
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dgn():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_1707_08265_amd as d
+    return d
+
+
+def gpu_prune(d, g, tg, recompute_keep=False, validate=False, stats=None):
+    import torch
+    dg = d.DeviceGraph.from_coo(g, validate=validate)
+    buf = d.PruneBuffers(dg, tg.num_sets)
+    rowptr = torch.from_numpy(tg.tgt_rowptr).cuda()
+    idx = torch.from_numpy(tg.tgt_idx).cuda()
+    opts = d.dgn_options(recompute_keep=1 if recompute_keep else 0)
+    rc = buf.prune(rowptr, idx, options=opts, stats=stats)
+    assert rc == 0, d.dgn_strerror(rc)
+    out = buf.to_host()
+    return dg, buf, out
+
+
+def oracle_prune(orc, g, tg):
+    adj = orc.build_adjacency(g.num_ops, g.num_tensors, g.in_op, g.in_tensor, g.out_op, g.out_tensor)
+    return adj, orc.forward_prune(adj, tg.num_sets, tg.tgt_rowptr, tg.tgt_idx, g.num_graphs, g.graph_op_offsets)
+
+
+def assert_same(out, r, what=""):
+    assert np.array_equal(out["tensor_mask"], r.tensor_mask), f"{what}: coloured-tensor masks differ"
+    assert np.array_equal(out["op_mask"], r.op_mask), f"{what}: operator keep masks differ"
+    assert np.array_equal(out["op_flag"], r.op_flag), f"{what}: keep flags differ"
+    assert np.array_equal(out["kept_count"], r.kept_count), f"{what}: kept counts differ"
+    assert np.array_equal(out["kept_ops"], r.kept_ops), f"{what}: compacted order differs"
+    assert np.array_equal(out["kept_masks"], r.kept_masks), f"{what}: compacted masks differ"
+    assert np.array_equal(out["per_query_count"], r.per_query_count), f"{what}: per-set counts differ"
+
+
+def test_worked_example(dgn, oracle):
+    g, tid, cases = load_worked_example()
+    for c in cases:
+        _, _, out = gpu_prune(dgn, g, c["targets"])
+        assert np.array_equal(out["tensor_mask"], c["M"]), c["name"]
+        assert np.array_equal(out["op_mask"], c["K"]), c["name"]
+        assert np.array_equal(out["kept_ops"], c["kept"]), c["name"]
+        assert np.array_equal(out["per_query_count"][: len(c["pq"])], c["pq"]), c["name"]
+    _, _, out = gpu_prune(dgn, g, cases[0]["targets"])
+    assert out["tensor_mask"][tid["b"]] == 0          # Sec. 2.2: b must not be marked
+
+
+# sizes the oracle finishes in seconds, spanning many tiles and ragged tails
+CASES = [(0, 1.0), (1, 1.0), (2, 0.02), (3, 0.02), (4, 0.002)]
+
+
+@pytest.mark.parametrize("k,scale", CASES)
+def test_parity_configs(dgn, oracle, k, scale):
+    g, tg = gg.config(k, scale)
+    print(f"config {k} scale {scale}: P={g.num_ops} T={g.num_tensors} E={g.nnz_in}+{g.nnz_out}", flush=True)
+    st = dgn.dgn_stats()
+    dg, buf, out = gpu_prune(dgn, g, tg, stats=st)
+    adj, r = oracle_prune(oracle, g, tg)
+    assert_same(out, r, f"cfg{k}")
+    assert st.levels > 0 and st.tensor_visits >= int((r.tensor_mask != 0).sum())
+    # stand-alone removal-rule pass gives the same K as the traversal accumulated
+    _, _, out2 = gpu_prune(dgn, g, tg, recompute_keep=True)
+    assert_same(out2, r, f"cfg{k} recompute_keep")
+
+
+@pytest.mark.parametrize("k,scale", [(1, 0.2), (3, 0.004), (4, 0.001)])
+def test_csr_builder_parity_on_shuffled_coo(dgn, oracle, k, scale):
+    g, tg = gg.config(k, scale)
+    gs = gg.shuffle_coo(g, 11 + k)
+    adj = oracle.build_adjacency(gs.num_ops, gs.num_tensors, gs.in_op, gs.in_tensor, gs.out_op, gs.out_tensor)
+    dg = dgn.DeviceGraph.from_coo(gs, validate=True)
+    csr = {n: v.cpu().numpy() for n, v in dg.csr().items()}
+    for name in ("in_rowptr", "in_idx", "out_rowptr", "out_idx", "prod_rowptr", "prod_idx"):
+        assert np.array_equal(csr[name], getattr(adj, name)), name
+    # and the prune result on the shuffled input is the same
+    _, _, out = gpu_prune(dgn, gs, tg)
+    _, r = oracle_prune(oracle, g, tg)
+    assert_same(out, r, "shuffled")
+
+
+def test_from_csr_and_keep_compact(dgn, oracle):
+    import torch
+    g, tg = gg.config(1, 0.3)
+    adj, r = oracle_prune(oracle, g, tg)
+    c = lambda a: torch.from_numpy(a).cuda()
+    dg = dgn.DeviceGraph.from_csr(g.num_ops, g.num_tensors, c(adj.in_rowptr), c(adj.in_idx), c(adj.out_rowptr),
+                                  c(adj.out_idx), validate=True)
+    csr = dg.csr()
+    assert np.array_equal(csr["prod_rowptr"].cpu().numpy(), adj.prod_rowptr)
+    assert np.array_equal(csr["prod_idx"].cpu().numpy(), adj.prod_idx)
+    buf = dgn.PruneBuffers(dg, tg.num_sets)
+    assert buf.prune(c(tg.tgt_rowptr), c(tg.tgt_idx)) == 0
+    assert_same(buf.to_host(), r, "from_csr")
+    # removal rule + compaction alone, from the oracle's coloured masks
+    buf2 = dgn.PruneBuffers(dg, tg.num_sets)
+    M = torch.from_numpy(r.tensor_mask.view(np.int64)).cuda()
+    assert buf2.keep_compact(M) == 0
+    out = buf2.to_host()
+    for name, ref in (("op_mask", r.op_mask), ("op_flag", r.op_flag), ("kept_ops", r.kept_ops),
+                      ("kept_masks", r.kept_masks), ("kept_count", r.kept_count),
+                      ("per_query_count", r.per_query_count)):
+        assert np.array_equal(out[name], ref), name
+
+
+@pytest.mark.parametrize("multi", [False, True])
+def test_random_small_graphs(dgn, oracle, multi):
+    rng = np.random.default_rng(77 + multi)
+    for trial in range(25):
+        P = int(rng.integers(1, 300))
+        g, ops = random_small_graph(rng, P, num_inputs=int(rng.integers(1, 6)), multi_producer=multi)
+        Q = int(rng.integers(1, 65))
+        sets = [[int(rng.integers(0, g.num_tensors)) for _ in range(int(rng.integers(0, 5)))] for _ in range(Q)]
+        tg = targets_from_sets(sets)
+        _, _, out = gpu_prune(dgn, g, tg)
+        _, r = oracle_prune(oracle, g, tg)
+        assert_same(out, r, f"trial {trial} multi={multi}")
+
+
+def test_edge_cases(dgn, oracle):
+    import torch
+    # empty target sets: everything zero, nothing kept
+    g, _ = gg.config(0)
+    tg = targets_from_sets([[], [], []])
+    _, _, out = gpu_prune(dgn, g, tg)
+    assert not out["tensor_mask"].any() and not out["op_mask"].any() and out["kept_count"][0] == 0
+    assert not out["per_query_count"].any() and len(out["kept_ops"]) == 0
+    # a graph with no operators at all
+    g0 = gg.Graph(0, 5, *(np.zeros(0, np.int32) for _ in range(4)))
+    _, _, out = gpu_prune(dgn, g0, targets_from_sets([[3], [3, 4]]))
+    assert list(out["tensor_mask"]) == [0, 0, 0, 3, 2] and out["kept_count"][0] == 0
+    # 64 sets all holding the same tensor; zero-input and zero-output operators; duplicate edges
+    gz = graph_from_ops([([], [1]), ([1, 1], [2]), ([2], []), ([0, 2], [3])], 4)
+    tz = targets_from_sets([[3]] * 64)
+    _, _, out = gpu_prune(dgn, gz, tz)
+    _, r = oracle_prune(oracle, gz, tz)
+    assert_same(out, r, "all-64-sets")
+    assert out["tensor_mask"][3] == np.uint64(0xFFFFFFFFFFFFFFFF) and list(out["kept_ops"]) == [0, 1, 3]
+    # target id out of range is reported, the valid ones are still processed
+    dg = dgn.DeviceGraph.from_coo(gz)
+    buf = dgn.PruneBuffers(dg, 1)
+    rc = buf.prune(torch.tensor([0, 2], dtype=torch.int32).cuda(), torch.tensor([3, 99], dtype=torch.int32).cuda())
+    assert rc == dgn.DGN_ERR_ID_OUT_OF_RANGE
+    # an edge naming a tensor that does not exist is refused at build time
+    bad = gg.Graph(1, 2, np.array([0], np.int32), np.array([5], np.int32), np.array([0], np.int32),
+                   np.array([1], np.int32))
+    with pytest.raises(dgn.DgnError) as ei:
+        dgn.DeviceGraph.from_coo(bad)
+    assert ei.value.code == dgn.DGN_ERR_ID_OUT_OF_RANGE
+    # non-topological operator order is caught by validation
+    cyc = graph_from_ops([([2], [1]), ([1], [2])], 3)
+    with pytest.raises(dgn.DgnError) as ei:
+        dgn.DeviceGraph.from_coo(cyc, validate=True)
+    assert ei.value.code == dgn.DGN_ERR_NOT_TOPOLOGICAL
+
+
+def test_deep_chain_many_levels(dgn, oracle):
+    n = 3000                      # one frontier level per operator
+    ops = np.arange(n, dtype=np.int32)
+    g = gg.Graph(n, n + 1, ops, ops, ops, ops + 1)
+    tg = targets_from_sets([[n], [n // 2]])
+    st = dgn.dgn_stats()
+    _, _, out = gpu_prune(dgn, g, tg, stats=st)
+    _, r = oracle_prune(oracle, g, tg)
+    assert_same(out, r, "chain")
+    assert st.levels >= n
+
+
+def test_relabelled_tensors(dgn, oracle):
+    g, tg = gg.config(1, 0.1)
+    g2, tg2, perm = gg.relabel_tensors(g, tg, 5)
+    _, _, out = gpu_prune(dgn, g2, tg2)
+    _, r = oracle_prune(oracle, g, tg)
+    assert np.array_equal(out["tensor_mask"][perm], r.tensor_mask)
+    assert np.array_equal(out["op_mask"], r.op_mask) and np.array_equal(out["kept_ops"], r.kept_ops)
+
+
+def test_buffers_are_reusable_and_outputs_fully_rewritten(dgn, oracle):
+    import torch
+    g, tg = gg.config(1, 0.1)
+    dg = dgn.DeviceGraph.from_coo(g)
+    buf = dgn.PruneBuffers(dg, tg.num_sets)
+    for t in (buf.tensor_mask, buf.op_mask, buf.kept_masks, buf.per_query_count, buf.kept_count):
+        t.fill_(-1)
+    buf.op_flag.fill_(7)
+    buf.scratch.fill_(0xAB)
+    c = lambda a: torch.from_numpy(a).cuda()
+    _, r = oracle_prune(oracle, g, tg)
+    for _ in range(3):                         # same buffers, dirty from the previous call
+        assert buf.prune(c(tg.tgt_rowptr), c(tg.tgt_idx)) == 0
+        assert_same(buf.to_host(), r, "reuse")
+    # then a different, smaller query in the same buffers
+    tg1 = targets_from_sets([[int(tg.tgt_idx[0])]])
+    buf1 = dgn.PruneBuffers(dg, 1)
+    assert buf1.prune(c(tg1.tgt_rowptr), c(tg1.tgt_idx)) == 0
+    adj = oracle.build_adjacency(g.num_ops, g.num_tensors, g.in_op, g.in_tensor, g.out_op, g.out_tensor)
+    assert_same(buf1.to_host(), oracle.forward_prune(adj, 1, tg1.tgt_rowptr, tg1.tgt_idx), "single")
