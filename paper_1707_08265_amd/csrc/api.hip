@@ -437,28 +437,32 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     if (grid > max_useful) grid = (int)(max_useful > 0 ? max_useful : 1);
     int launch_no = 0;
     int batch = 48;
-    bool compacted = false;
+    // the stand-alone removal-rule pass rewrites K, which the traversal still needs while unfinished
+    const bool speculate = !ca.from_tensor_mask;
+    bool first = true;
     for (;;) {
         for (int i = 0; i < batch; ++i, ++launch_no)
             DGN_HIP(launch_level(g->v, S.state, launch_no, S.q0, S.q1, S.bm0, S.bm1, M, K, grid, s));
         launches += batch;
-        if (!compacted) {
+        const bool speculated = first && speculate;
+        if (speculated) {
             DGN_HIP(launch_keep_compact(ca, s));
             launches += 3 + (g->G > 1);
         }
         DGN_HIP(hipMemcpyAsync(pin, S.state, sizeof(TravState), hipMemcpyDeviceToHost, s));
         DGN_HIP(hipStreamSynchronize(s));
         const bool done = hst->slot[launch_no & 1].n == 0;
-        if (done && !compacted) { compacted = true; break; }
         if (done) {
-            FillRegion pq[1] = {{per_query_count, pq_bytes}};
-            DGN_HIP(launch_clear(pq, 1, s));
-            DGN_HIP(launch_keep_compact(ca, s));
-            DGN_HIP(hipStreamSynchronize(s));
-            launches += 4 + (g->G > 1);
+            if (!speculated) {
+                FillRegion pq[1] = {{per_query_count, pq_bytes}};
+                DGN_HIP(launch_clear(pq, 1, s));
+                DGN_HIP(launch_keep_compact(ca, s));
+                DGN_HIP(hipStreamSynchronize(s));
+                launches += 4 + (g->G > 1);
+            }
             break;
         }
-        compacted = true;          // the speculative pass ran on unfinished masks; it will be redone
+        first = false;
         if (batch < 1024) batch *= 2;
     }
     if (stats) {
