@@ -90,8 +90,22 @@ typedef struct dgn_options {
     int32_t recompute_keep;  /* prune: recompute K from M with the stand-alone removal-rule pass
                                 instead of using the K the traversal accumulated (same values)   */
     int32_t traversal;       /* 0 = automatic; 1 = force the generic one-launch-per-level path   */
-    int32_t reserved[5];     /* must be zero */
+    int32_t profile;         /* prune: bracket each phase with HIP events on `stream` and report
+                                the elapsed times in dgn_stats.phase_ms (needs stats != NULL)      */
+    int32_t reserved[4];     /* must be zero */
 } dgn_options;
+
+/* Indices into dgn_stats.phase_ms */
+enum {
+    DGN_PHASE_CLEAR = 0,     /* clear of M, K, frontier bitmaps and state (one kernel)            */
+    DGN_PHASE_SEED = 1,      /* target bits scattered, first frontier built (one kernel)          */
+    DGN_PHASE_TRAVERSE = 2,  /* all frontier levels                                               */
+    DGN_PHASE_COUNT = 3,     /* removal rule / flags / per-tile and per-set counts (one kernel)   */
+    DGN_PHASE_SCAN = 4,      /* prefix sum of the tile counts (one kernel)                        */
+    DGN_PHASE_SCATTER = 5,   /* ordered scatter of the kept operators (+ per-graph offsets)       */
+    DGN_PHASE_TOTAL = 6,     /* first kernel start to last kernel end                             */
+    DGN_NUM_PHASES = 8
+};
 
 /* Schedule-dependent counters (not part of the result; excluded from parity). HOST struct. */
 typedef struct dgn_stats {
@@ -99,7 +113,9 @@ typedef struct dgn_stats {
     int64_t tensor_visits;   /* frontier entries processed, summed over levels                   */
     int64_t max_frontier;    /* largest frontier                                                 */
     int64_t launches;        /* kernels enqueued by the call                                     */
-    int64_t reserved[4];
+    int64_t level_launches;  /* of which frontier-level kernels                                  */
+    int64_t reserved[3];
+    float phase_ms[DGN_NUM_PHASES];   /* filled when options->profile; zero otherwise           */
 } dgn_stats;
 
 /* ---- graph construction -------------------------------------------------------------------- */

@@ -48,12 +48,15 @@ class dgn_csr_desc(ctypes.Structure):
 
 class dgn_options(ctypes.Structure):
     _fields_ = [("validate", c_int32), ("recompute_keep", c_int32), ("traversal", c_int32),
-                ("reserved", c_int32 * 5)]
+                ("profile", c_int32), ("reserved", c_int32 * 4)]
 
 
 class dgn_stats(ctypes.Structure):
     _fields_ = [("levels", c_int64), ("tensor_visits", c_int64), ("max_frontier", c_int64),
-                ("launches", c_int64), ("reserved", c_int64 * 4)]
+                ("launches", c_int64), ("level_launches", c_int64), ("reserved", c_int64 * 3),
+                ("phase_ms", ctypes.c_float * 8)]
+
+PHASES = ["clear", "seed", "traverse", "count", "scan", "scatter", "total"]
 
 
 class DgnError(RuntimeError):

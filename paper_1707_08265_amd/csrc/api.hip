@@ -146,6 +146,19 @@ int pinned_buffer(void **out)
     return DGN_OK;
 }
 
+// Events for options->profile, created once per host thread.
+int profile_events(hipEvent_t **out)
+{
+    thread_local hipEvent_t ev[8];
+    thread_local bool ready = false;
+    if (!ready) {
+        for (int i = 0; i < 8; ++i) DGN_HIP(hipEventCreate(&ev[i]));
+        ready = true;
+    }
+    *out = ev;
+    return DGN_OK;
+}
+
 int error_bits_to_code(int32_t bits)
 {
     if (bits & kErrCsr) return DGN_ERR_BAD_CSR;
@@ -157,7 +170,7 @@ int error_bits_to_code(int32_t bits)
 int check_options(const dgn_options *o)
 {
     if (!o) return DGN_OK;
-    for (int i = 0; i < 5; ++i)
+    for (int i = 0; i < 4; ++i)
         if (o->reserved[i] != 0) return DGN_ERR_INVALID_ARG;
     if (o->traversal < 0 || o->traversal > 1) return DGN_ERR_INVALID_ARG;
     return DGN_OK;
@@ -402,13 +415,21 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     u64 *M = reinterpret_cast<u64 *>(tensor_mask);
     u64 *K = reinterpret_cast<u64 *>(op_mask);
     const size_t pq_bytes = per_query_count ? sizeof(int64_t) * 64 * (size_t)(g->G > 1 ? g->G : 1) : 0;
-    int64_t launches = 0;
+    int64_t launches = 0, level_launches = 0;
+    hipEvent_t *ev = nullptr;       // 0 start, 1 cleared, 2 seeded, 3 traversed, 4 counted, 5 scanned, 6 scattered
+    if (options && options->profile && stats) {
+        rc = profile_events(&ev);
+        if (rc) return rc;
+        DGN_HIP(hipEventRecord(ev[0], s));
+    }
 
     // nothing marked yet: clear outputs, frontier bitmaps and traversal state
     FillRegion clr[6] = {{M, (size_t)g->T * 8}, {K, (size_t)g->P * 8},  {S.bm0, S.bm_bytes},
                          {S.bm1, S.bm_bytes},   {S.state, 256},         {per_query_count, pq_bytes}};
     DGN_HIP(launch_clear(clr, 6, s));
+    if (ev) DGN_HIP(hipEventRecord(ev[1], s));
     DGN_HIP(launch_seed(g->v, num_sets, num_targets, tgt_rowptr, tgt_idx, M, S.state, S.q0, S.bm0, s));
+    if (ev) DGN_HIP(hipEventRecord(ev[2], s));
     launches += 2;
 
     CompactArgs ca{};
@@ -444,9 +465,11 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
         for (int i = 0; i < batch; ++i, ++launch_no)
             DGN_HIP(launch_level(g->v, S.state, launch_no, S.q0, S.q1, S.bm0, S.bm1, M, K, grid, s));
         launches += batch;
+        level_launches += batch;
         const bool speculated = first && speculate;
+        if (ev && first) DGN_HIP(hipEventRecord(ev[3], s));
         if (speculated) {
-            DGN_HIP(launch_keep_compact(ca, s));
+            DGN_HIP(launch_keep_compact(ca, s, ev ? ev + 4 : nullptr));
             launches += 3 + (g->G > 1);
         }
         DGN_HIP(hipMemcpyAsync(pin, S.state, sizeof(TravState), hipMemcpyDeviceToHost, s));
@@ -456,7 +479,8 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
             if (!speculated) {
                 FillRegion pq[1] = {{per_query_count, pq_bytes}};
                 DGN_HIP(launch_clear(pq, 1, s));
-                DGN_HIP(launch_keep_compact(ca, s));
+                if (ev) DGN_HIP(hipEventRecord(ev[3], s));
+                DGN_HIP(launch_keep_compact(ca, s, ev ? ev + 4 : nullptr));
                 DGN_HIP(hipStreamSynchronize(s));
                 launches += 4 + (g->G > 1);
             }
@@ -471,6 +495,11 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
         stats->tensor_visits = (int64_t)hst->tensor_visits;
         stats->max_frontier = (int64_t)hst->max_frontier;
         stats->launches = launches;
+        stats->level_launches = level_launches;
+        if (ev) {
+            for (int i = 0; i < 6; ++i) DGN_HIP(hipEventElapsedTime(&stats->phase_ms[i], ev[i], ev[i + 1]));
+            DGN_HIP(hipEventElapsedTime(&stats->phase_ms[DGN_PHASE_TOTAL], ev[0], ev[6]));
+        }
     }
     return error_bits_to_code(hst->error);
 }

@@ -143,6 +143,7 @@ struct CompactArgs {
     int32_t *block_counts;   // [num_tiles + 1] scratch
     bool from_tensor_mask;   // K := OR M[out] (true) or read K as accumulated by the traversal
 };
-hipError_t launch_keep_compact(const CompactArgs &a, hipStream_t s);
+// ev (may be NULL): three events recorded after the count, scan and scatter passes.
+hipError_t launch_keep_compact(const CompactArgs &a, hipStream_t s, hipEvent_t *ev = nullptr);
 
 }  // namespace dgn

@@ -194,7 +194,7 @@ __global__ __launch_bounds__(256) void k_graph_offsets(CompactArgs a)
     a.kept_count[1 + gi] = c;
 }
 
-hipError_t launch_keep_compact(const CompactArgs &a, hipStream_t s)
+hipError_t launch_keep_compact(const CompactArgs &a, hipStream_t s, hipEvent_t *ev)
 {
     const int64_t P = a.g.num_ops;
     const int64_t tiles = (P + kCompactTile - 1) / kCompactTile;
@@ -204,10 +204,13 @@ hipError_t launch_keep_compact(const CompactArgs &a, hipStream_t s)
         else
             hipLaunchKernelGGL(k_keep_count<false>, dim3((unsigned)tiles), dim3(kCThreads), 0, s, a);
     }
+    if (ev) (void)hipEventRecord(ev[0], s);
     hipLaunchKernelGGL(k_scan_tiles, dim3(1), dim3(1024), 0, s, a.block_counts, tiles, a.kept_count);
+    if (ev) (void)hipEventRecord(ev[1], s);
     if (tiles > 0) hipLaunchKernelGGL(k_scatter, dim3((unsigned)tiles), dim3(kCThreads), 0, s, a);
     if (a.g.num_graphs > 1)
         hipLaunchKernelGGL(k_graph_offsets, dim3((unsigned)((a.g.num_graphs + 1 + 255) / 256)), dim3(256), 0, s, a);
+    if (ev) (void)hipEventRecord(ev[2], s);
     return hipGetLastError();
 }
 
