@@ -46,19 +46,31 @@ __global__ __launch_bounds__(kCThreads) void k_keep_count(CompactArgs a)
         g_hi = g.op_off[cur_graph + 1];
     }
 
+    // all loads of the tile are issued before anything is consumed (8 independent loads per lane)
+    u64 kk[kCRounds];
+#pragma unroll
+    for (int r = 0; r < kCRounds; ++r) {
+        const int64_t o = tile_base + (int64_t)r * kCThreads + threadIdx.x;
+        kk[r] = 0;
+        if (o < g.num_ops) {
+            if (kFromM) {
+                const int32_t b = g.out_rowptr[o], e = g.out_rowptr[o + 1];
+                u64 k = 0;
+                for (int32_t j = b; j < e; ++j) k |= a.M[g.out_idx[j]];
+                kk[r] = k;
+            } else {
+                kk[r] = a.K[o];
+            }
+        }
+    }
+#pragma unroll
     for (int r = 0; r < kCRounds; ++r) {
         const int64_t o0 = tile_base + (int64_t)r * kCThreads + wave * kWave;   // first operator of this wave-round
         const int64_t o = o0 + lane;
         const bool valid = o < g.num_ops;
-        u64 k = 0;
+        const u64 k = kk[r];
         if (valid) {
-            if (kFromM) {
-                const int32_t b = g.out_rowptr[o], e = g.out_rowptr[o + 1];
-                for (int32_t j = b; j < e; ++j) k |= a.M[g.out_idx[j]];
-                a.K[o] = k;
-            } else {
-                k = a.K[o];
-            }
+            if (kFromM) a.K[o] = k;
             if (a.op_flag) a.op_flag[o] = (uint8_t)(k != 0);
         }
         const u64 word = ballot64(k != 0);
