@@ -33,6 +33,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--recompute-keep", action="store_true",
                     help="run the stand-alone removal-rule pass instead of reusing the traversal's K")
+    ap.add_argument("--defer-percent", type=int, default=0, help="traversal schedule knob (0 = library default)")
+    ap.add_argument("--generic", action="store_true", help="force the one-launch-per-level traversal")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path runs on ONE GPU only (no sharding or collectives are built); "
@@ -85,7 +87,8 @@ def main():
     # ---- prune --------------------------------------------------------------------------------
     buf = d.PruneBuffers(dg, tg.num_sets)
     rowptr, idx = up(tg.tgt_rowptr), up(tg.tgt_idx)
-    opts = d.dgn_options(profile=1, recompute_keep=1 if args.recompute_keep else 0)
+    opts = d.dgn_options(profile=1, recompute_keep=1 if args.recompute_keep else 0,
+                         defer_percent=args.defer_percent, traversal=1 if args.generic else 0)
     st = d.dgn_stats()
     for _ in range(args.warmup):
         rc = buf.prune(rowptr, idx, options=opts, stats=st)

@@ -92,7 +92,10 @@ typedef struct dgn_options {
     int32_t traversal;       /* 0 = automatic; 1 = force the generic one-launch-per-level path   */
     int32_t profile;         /* prune: bracket each phase with HIP events on `stream` and report
                                 the elapsed times in dgn_stats.phase_ms (needs stats != NULL)      */
-    int32_t reserved[4];     /* must be zero */
+    int32_t defer_percent;   /* prune: geometric decay (percent, 1..99) of the producer-id threshold
+                                below which frontier entries wait for more bits; 100 = never defer,
+                                0 = library default.  A schedule only: results do not depend on it */
+    int32_t reserved[3];     /* must be zero */
 } dgn_options;
 
 /* Indices into dgn_stats.phase_ms */

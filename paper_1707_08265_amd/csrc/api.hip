@@ -24,6 +24,10 @@ inline int hip_fail(hipError_t e)
     } while (0)
 
 constexpr int64_t kMaxCount = 2147483646;   // counts must stay below 2^31 - 1
+constexpr int kNarrowCap = 2048;            // frontiers up to this size are walked by one workgroup
+constexpr int kWidePerGroup = 12;           // wide level launches between two single-workgroup launches
+constexpr int kWideGroups = 5;              // groups per batch (one state read-back per batch)
+constexpr int kDefaultDeferPercent = 75;
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -63,6 +67,7 @@ int check_sizes(int64_t P, int64_t T, int64_t Ein, int64_t Eout, int32_t G, cons
 
 struct GraphLayout {
     int32_t *in_rowptr, *in_idx, *out_rowptr, *out_idx, *prod_rowptr, *prod_idx;
+    int4 *pinfo;
     int64_t *op_off, *t_off;
     size_t bytes;
 };
@@ -79,6 +84,7 @@ GraphLayout graph_layout(void *mem, int64_t P, int64_t T, int64_t Ein, int64_t E
     }
     L.prod_rowptr = c.take<int32_t>(T + 1);
     L.prod_idx = c.take<int32_t>(Eout);
+    L.pinfo = c.take<int4>(T);
     if (G > 1) {
         L.op_off = c.take<int64_t>(G + 1);
         L.t_off = c.take<int64_t>(G + 1);
@@ -110,7 +116,7 @@ BuildScratch build_scratch(void *mem, int64_t P, int64_t T, int64_t Ein, int64_t
 
 struct PruneScratch {
     TravState *state;
-    int32_t *q0, *q1;
+    void *q0, *q1;          // frontier queues, kQueueEntryBytes per tensor each
     u64 *bm0, *bm1;
     u64 *opbits;
     int32_t *block_counts;
@@ -123,8 +129,8 @@ PruneScratch prune_scratch(void *mem, int64_t P, int64_t T)
     Carver c(mem);
     PruneScratch S{};
     S.state = c.take<TravState>(4);
-    S.q0 = c.take<int32_t>(T);
-    S.q1 = c.take<int32_t>(T);
+    S.q0 = c.take<char>((size_t)T * kQueueEntryBytes);
+    S.q1 = c.take<char>((size_t)T * kQueueEntryBytes);
     const size_t bmw = (size_t)((T + 63) / 64);
     S.bm0 = c.take<u64>(bmw);
     S.bm1 = c.take<u64>(bmw);
@@ -170,9 +176,10 @@ int error_bits_to_code(int32_t bits)
 int check_options(const dgn_options *o)
 {
     if (!o) return DGN_OK;
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 3; ++i)
         if (o->reserved[i] != 0) return DGN_ERR_INVALID_ARG;
     if (o->traversal < 0 || o->traversal > 1) return DGN_ERR_INVALID_ARG;
+    if (o->defer_percent < 0 || o->defer_percent > 100) return DGN_ERR_INVALID_ARG;
     return DGN_OK;
 }
 
@@ -190,6 +197,7 @@ namespace {
 int finish_build(dgn_graph *h, const GraphLayout &L, const int64_t *op_off_host, const int64_t *t_off_host,
                  int32_t *status, const dgn_options *options, hipStream_t s, dgn_graph **out)
 {
+    DGN_HIP(launch_build_pinfo(h->v, L.pinfo, s));
     if (h->G > 1) {
         DGN_HIP(hipMemcpyAsync(L.op_off, op_off_host, sizeof(int64_t) * (h->G + 1), hipMemcpyHostToDevice, s));
         DGN_HIP(hipMemcpyAsync(L.t_off, t_off_host, sizeof(int64_t) * (h->G + 1), hipMemcpyHostToDevice, s));
@@ -292,7 +300,7 @@ int dgn_graph_build(const dgn_coo_desc *d, void *graph_mem, size_t graph_bytes, 
     if (!h) return DGN_ERR_INVALID_ARG;
     h->P = P; h->T = T; h->Ein = Ein; h->Eout = Eout; h->G = d->num_graphs;
     h->v = GraphView{(int32_t)P, (int32_t)T, (int32_t)Ein, (int32_t)Eout, d->num_graphs, L.in_rowptr, L.in_idx,
-                     L.out_rowptr, L.out_idx, L.prod_rowptr, L.prod_idx, nullptr, nullptr};
+                     L.out_rowptr, L.out_idx, L.prod_rowptr, L.prod_idx, nullptr, nullptr, L.pinfo};
     rc = finish_build(h, L, d->graph_op_offsets, d->graph_tensor_offsets, S.status, options, s, out);
     if (rc) delete h;
     return rc;
@@ -351,7 +359,7 @@ int dgn_graph_from_csr(const dgn_csr_desc *d, void *graph_mem, size_t graph_byte
     if (!h) return DGN_ERR_INVALID_ARG;
     h->P = P; h->T = T; h->Ein = Ein; h->Eout = Eout; h->G = d->num_graphs;
     h->v = GraphView{(int32_t)P, (int32_t)T, (int32_t)Ein, (int32_t)Eout, d->num_graphs, d->in_rowptr, d->in_idx,
-                     d->out_rowptr, d->out_idx, L.prod_rowptr, L.prod_idx, nullptr, nullptr};
+                     d->out_rowptr, d->out_idx, L.prod_rowptr, L.prod_idx, nullptr, nullptr, L.pinfo};
     rc = finish_build(h, L, d->graph_op_offsets, d->graph_tensor_offsets, S.status, options, s, out);
     if (rc) delete h;
     return rc;
@@ -428,7 +436,11 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
                          {S.bm1, S.bm_bytes},   {S.state, 256},         {per_query_count, pq_bytes}};
     DGN_HIP(launch_clear(clr, 6, s));
     if (ev) DGN_HIP(hipEventRecord(ev[1], s));
-    DGN_HIP(launch_seed(g->v, num_sets, num_targets, tgt_rowptr, tgt_idx, M, S.state, S.q0, S.bm0, s));
+    // deferral schedule: threshold on the producer id, starting at decay*P and decaying geometrically
+    int defer_percent = options && options->defer_percent ? options->defer_percent : kDefaultDeferPercent;
+    const float decay = defer_percent >= 100 ? 1.0f : (float)defer_percent / 100.0f;
+    const int32_t theta0 = defer_percent >= 100 ? 0 : (int32_t)((double)g->P * decay);
+    DGN_HIP(launch_seed(g->v, num_sets, num_targets, tgt_rowptr, tgt_idx, M, S.state, S.q0, S.bm0, theta0, s));
     if (ev) DGN_HIP(hipEventRecord(ev[2], s));
     launches += 2;
 
@@ -450,44 +462,66 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     if (rc) return rc;
     const TravState *hst = static_cast<const TravState *>(pin);
 
-    // Level loop.  The number of levels depends on the data, so levels are enqueued in batches and the
-    // state is read back after each batch; the removal-rule/compaction passes are enqueued right behind
-    // the first batch (almost always enough) and simply redone if the traversal turns out unfinished.
+    // Level loop.  The number of levels depends on the data, so the host enqueues kernels ahead and
+    // reads the 64-byte state back at a few points:
+    //   1. one single-workgroup launch walks all leading small levels (deep, thin graphs finish here);
+    //   2. otherwise batches of wide levels with a single-workgroup launch after every few of them; the
+    //      removal-rule/compaction passes are enqueued right behind the first batch and redone only if
+    //      the traversal turns out unfinished.
     int grid = g->num_cus * 8;
     const int64_t max_useful = (g->T + 255) / 256;
     if (grid > max_useful) grid = (int)(max_useful > 0 ? max_useful : 1);
+    const bool generic_only = options && options->traversal == 1;
+    const int narrow_cap = generic_only ? 0 : kNarrowCap;
     int launch_no = 0;
-    int batch = 48;
     // the stand-alone removal-rule pass rewrites K, which the traversal still needs while unfinished
     const bool speculate = !ca.from_tensor_mask;
-    bool first = true;
-    for (;;) {
-        for (int i = 0; i < batch; ++i, ++launch_no)
-            DGN_HIP(launch_level(g->v, S.state, launch_no, S.q0, S.q1, S.bm0, S.bm1, M, K, grid, s));
-        launches += batch;
-        level_launches += batch;
-        const bool speculated = first && speculate;
-        if (ev && first) DGN_HIP(hipEventRecord(ev[3], s));
-        if (speculated) {
-            DGN_HIP(launch_keep_compact(ca, s, ev ? ev + 4 : nullptr));
-            launches += 3 + (g->G > 1);
-        }
+    bool done = false, compacted = false;
+    auto read_state = [&]() -> int {
         DGN_HIP(hipMemcpyAsync(pin, S.state, sizeof(TravState), hipMemcpyDeviceToHost, s));
         DGN_HIP(hipStreamSynchronize(s));
-        const bool done = hst->slot[launch_no & 1].n == 0;
-        if (done) {
-            if (!speculated) {
-                FillRegion pq[1] = {{per_query_count, pq_bytes}};
-                DGN_HIP(launch_clear(pq, 1, s));
-                if (ev) DGN_HIP(hipEventRecord(ev[3], s));
-                DGN_HIP(launch_keep_compact(ca, s, ev ? ev + 4 : nullptr));
-                DGN_HIP(hipStreamSynchronize(s));
-                launches += 4 + (g->G > 1);
+        done = hst->slot[launch_no & 1].n == 0;
+        return DGN_OK;
+    };
+    if (!generic_only) {
+        DGN_HIP(launch_narrow(g->v, S.state, launch_no, S.q0, S.q1, S.bm0, S.bm1, M, K, narrow_cap, s));
+        ++launch_no; ++launches;
+        rc = read_state();
+        if (rc) return rc;
+    }
+    bool first = true;
+    while (!done) {
+        for (int r = 0; r < kWideGroups; ++r) {
+            for (int i = 0; i < kWidePerGroup; ++i, ++launch_no)
+                DGN_HIP(launch_level(g->v, S.state, launch_no, S.q0, S.q1, S.bm0, S.bm1, M, K, grid, narrow_cap, decay, s));
+            launches += kWidePerGroup;
+            level_launches += kWidePerGroup;
+            if (!generic_only) {
+                DGN_HIP(launch_narrow(g->v, S.state, launch_no, S.q0, S.q1, S.bm0, S.bm1, M, K, narrow_cap, s));
+                ++launch_no; ++launches;
             }
-            break;
         }
+        if (first && speculate) {
+            if (ev) DGN_HIP(hipEventRecord(ev[3], s));
+            DGN_HIP(launch_keep_compact(ca, s, ev ? ev + 4 : nullptr));
+            launches += 3 + (g->G > 1);
+            compacted = true;
+        }
+        rc = read_state();
+        if (rc) return rc;
+        if (!done) compacted = false;      // the speculative pass ran on unfinished masks
         first = false;
-        if (batch < 1024) batch *= 2;
+    }
+    if (!compacted) {
+        if (pq_bytes) {
+            FillRegion pq[1] = {{per_query_count, pq_bytes}};
+            DGN_HIP(launch_clear(pq, 1, s));
+            ++launches;
+        }
+        if (ev) DGN_HIP(hipEventRecord(ev[3], s));
+        DGN_HIP(launch_keep_compact(ca, s, ev ? ev + 4 : nullptr));
+        launches += 3 + (g->G > 1);
+        if (ev) DGN_HIP(hipStreamSynchronize(s));    // the phase events below must have completed
     }
     if (stats) {
         memset(stats, 0, sizeof(*stats));

@@ -30,23 +30,32 @@ struct GraphView {
     const int32_t *out_rowptr, *out_idx;
     const int32_t *prod_rowptr, *prod_idx;
     const int64_t *op_off, *t_off;    // [G+1] device copies, NULL when num_graphs == 1
+    const int4 *pinfo;                // [T] producer record of every tensor: (o, eb, deg, 0), see traverse.hip
 };
+
+// producer-record / frontier-entry tags (values of the `o` field below zero)
+constexpr int32_t kFresh = -1;        // entry not looked up yet
+constexpr int32_t kMulti = -2;        // several producers: (eb, deg) index prod_idx
+constexpr int32_t kNoProducer = -3;   // graph input
+constexpr int32_t kThetaFloor = 64;   // deferral thresholds below this are treated as 0
 
 // One slot of traversal state.  Launch number e reads slot e&1 and its finishing block writes
 // slot (e+1)&1, so a block of launch e that starts late never sees state of the next level.
 struct LevelSlot {
     int32_t level;   // levels completed so far; queue parity = level & 1
     int32_t n;       // entries in the frontier to process (the *other* slot's n collects pushes)
+    int32_t theta;   // entries whose producer id is below this are deferred at this level
+    int32_t pad;
 };
 
 struct TravState {
     LevelSlot slot[2];
-    int32_t ticket;          // working blocks that have finished the current launch
-    int32_t error;           // sticky kErr* bits
-    int32_t pad[2];
-    u64 tensor_visits;       // sum of frontier sizes
+    int32_t ticket;            // working blocks that have finished the current launch
+    int32_t error;             // sticky kErr* bits
+    int32_t processed;         // entries expanded (not deferred) in the current launch
+    int32_t max_deferred_key;  // largest producer id among the entries deferred in the current launch
+    u64 tensor_visits;         // entries expanded, summed over levels
     u64 max_frontier;
-    u64 pad2[2];
 };
 static_assert(sizeof(TravState) == 64, "TravState is read back as 64 bytes");
 
@@ -122,11 +131,18 @@ hipError_t launch_check_topological(const GraphView &g, int32_t *error, hipStrea
 hipError_t launch_check_graph_ranges(const GraphView &g, int32_t *error, hipStream_t s);
 
 // Traversal.
+// Frontier queues hold 16-byte entries (kQueueEntryBytes per tensor, two queues).
+constexpr size_t kQueueEntryBytes = 16;
+hipError_t launch_build_pinfo(const GraphView &g, int4 *pinfo, hipStream_t s);
 hipError_t launch_seed(const GraphView &g, int32_t Q, int64_t num_targets, const int32_t *tgt_rowptr,
-                       const int32_t *tgt_idx, u64 *M, TravState *st, int32_t *q0, u64 *bm0,
+                       const int32_t *tgt_idx, u64 *M, TravState *st, void *q0, u64 *bm0, int32_t theta0,
                        hipStream_t s);
-hipError_t launch_level(const GraphView &g, TravState *st, int launch_no, int32_t *q0, int32_t *q1,
-                        u64 *bm0, u64 *bm1, u64 *M, u64 *K, int grid_blocks, hipStream_t s);
+// One wide level (whole chip); a frontier of at most narrow_cap entries is left to launch_narrow.
+hipError_t launch_level(const GraphView &g, TravState *st, int launch_no, void *q0, void *q1, u64 *bm0,
+                        u64 *bm1, u64 *M, u64 *K, int grid_blocks, int narrow_cap, float decay, hipStream_t s);
+// One workgroup runs level after level while 0 < frontier <= narrow_cap.
+hipError_t launch_narrow(const GraphView &g, TravState *st, int launch_no, void *q0, void *q1, u64 *bm0,
+                         u64 *bm1, u64 *M, u64 *K, int narrow_cap, hipStream_t s);
 
 // Removal rule + compaction.
 constexpr int kCompactTile = 2048;   // operators per workgroup in the count / scatter passes
