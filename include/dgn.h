@@ -95,7 +95,10 @@ typedef struct dgn_options {
     int32_t defer_percent;   /* prune: geometric decay (percent, 1..99) of the producer-id threshold
                                 below which frontier entries wait for more bits; 100 = never defer,
                                 0 = library default.  A schedule only: results do not depend on it */
-    int32_t reserved[3];     /* must be zero */
+    int32_t max_queue_entries; /* prune: cap on the frontier queues (0 = one entry per tensor).  A
+                                smaller cap only forces the overflow fix-up path (testing aid);
+                                results do not depend on it */
+    int32_t reserved[2];     /* must be zero */
 } dgn_options;
 
 /* Indices into dgn_stats.phase_ms */

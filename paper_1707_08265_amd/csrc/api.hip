@@ -117,10 +117,10 @@ BuildScratch build_scratch(void *mem, int64_t P, int64_t T, int64_t Ein, int64_t
 struct PruneScratch {
     TravState *state;
     void *q0, *q1;          // frontier queues, kQueueEntryBytes per tensor each
-    u64 *bm0, *bm1;
+    u64 *DB;                // deferred-operator bitmap
     u64 *opbits;
     int32_t *block_counts;
-    size_t bm_bytes, opbits_bytes;
+    size_t db_bytes, opbits_bytes;
     size_t bytes;
 };
 
@@ -131,11 +131,9 @@ PruneScratch prune_scratch(void *mem, int64_t P, int64_t T)
     S.state = c.take<TravState>(4);
     S.q0 = c.take<char>((size_t)T * kQueueEntryBytes);
     S.q1 = c.take<char>((size_t)T * kQueueEntryBytes);
-    const size_t bmw = (size_t)((T + 63) / 64);
-    S.bm0 = c.take<u64>(bmw);
-    S.bm1 = c.take<u64>(bmw);
-    S.bm_bytes = bmw * 8;
     const size_t obw = (size_t)((P + 63) / 64);
+    S.DB = c.take<u64>(obw);
+    S.db_bytes = obw * 8;
     S.opbits = c.take<u64>(obw);
     S.opbits_bytes = obw * 8;
     S.block_counts = c.take<int32_t>((P + kCompactTile - 1) / kCompactTile + 1);
@@ -176,10 +174,11 @@ int error_bits_to_code(int32_t bits)
 int check_options(const dgn_options *o)
 {
     if (!o) return DGN_OK;
-    for (int i = 0; i < 3; ++i)
+    for (int i = 0; i < 2; ++i)
         if (o->reserved[i] != 0) return DGN_ERR_INVALID_ARG;
     if (o->traversal < 0 || o->traversal > 1) return DGN_ERR_INVALID_ARG;
     if (o->defer_percent < 0 || o->defer_percent > 100) return DGN_ERR_INVALID_ARG;
+    if (o->max_queue_entries < 0) return DGN_ERR_INVALID_ARG;
     return DGN_OK;
 }
 
@@ -432,15 +431,18 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     }
 
     // nothing marked yet: clear outputs, frontier bitmaps and traversal state
-    FillRegion clr[6] = {{M, (size_t)g->T * 8}, {K, (size_t)g->P * 8},  {S.bm0, S.bm_bytes},
-                         {S.bm1, S.bm_bytes},   {S.state, 256},         {per_query_count, pq_bytes}};
-    DGN_HIP(launch_clear(clr, 6, s));
+    FillRegion clr[5] = {{M, (size_t)g->T * 8}, {K, (size_t)g->P * 8}, {S.DB, S.db_bytes},
+                         {S.state, 256},        {per_query_count, pq_bytes}};
+    DGN_HIP(launch_clear(clr, 5, s));
     if (ev) DGN_HIP(hipEventRecord(ev[1], s));
     // deferral schedule: threshold on the producer id, starting at decay*P and decaying geometrically
     int defer_percent = options && options->defer_percent ? options->defer_percent : kDefaultDeferPercent;
     const float decay = defer_percent >= 100 ? 1.0f : (float)defer_percent / 100.0f;
     const int32_t theta0 = defer_percent >= 100 ? 0 : (int32_t)((double)g->P * decay);
-    DGN_HIP(launch_seed(g->v, num_sets, num_targets, tgt_rowptr, tgt_idx, M, S.state, S.q0, S.bm0, theta0, s));
+    int64_t qcap64 = g->T;
+    if (options && options->max_queue_entries > 0 && options->max_queue_entries < qcap64) qcap64 = options->max_queue_entries;
+    const int queue_cap = (int)qcap64;
+    DGN_HIP(launch_seed(g->v, num_sets, num_targets, tgt_rowptr, tgt_idx, M, S.state, S.q0, queue_cap, theta0, s));
     if (ev) DGN_HIP(hipEventRecord(ev[2], s));
     launches += 2;
 
@@ -480,11 +482,12 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     auto read_state = [&]() -> int {
         DGN_HIP(hipMemcpyAsync(pin, S.state, sizeof(TravState), hipMemcpyDeviceToHost, s));
         DGN_HIP(hipStreamSynchronize(s));
-        done = hst->slot[launch_no & 1].n == 0;
+        const LevelSlot &sl = hst->slot[launch_no & 1];
+        done = sl.n == 0 && !(sl.deferred_seen && sl.theta_hi > 0);
         return DGN_OK;
     };
     if (!generic_only) {
-        DGN_HIP(launch_narrow(g->v, S.state, launch_no, S.q0, S.q1, S.bm0, S.bm1, M, K, narrow_cap, s));
+        DGN_HIP(launch_narrow(g->v, S.state, launch_no, S.q0, S.q1, S.DB, M, K, queue_cap, narrow_cap, s));
         ++launch_no; ++launches;
         rc = read_state();
         if (rc) return rc;
@@ -493,11 +496,11 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     while (!done) {
         for (int r = 0; r < kWideGroups; ++r) {
             for (int i = 0; i < kWidePerGroup; ++i, ++launch_no)
-                DGN_HIP(launch_level(g->v, S.state, launch_no, S.q0, S.q1, S.bm0, S.bm1, M, K, grid, narrow_cap, decay, s));
+                DGN_HIP(launch_level(g->v, S.state, launch_no, S.q0, S.q1, S.DB, M, K, grid, queue_cap, narrow_cap, decay, s));
             launches += kWidePerGroup;
             level_launches += kWidePerGroup;
             if (!generic_only) {
-                DGN_HIP(launch_narrow(g->v, S.state, launch_no, S.q0, S.q1, S.bm0, S.bm1, M, K, narrow_cap, s));
+                DGN_HIP(launch_narrow(g->v, S.state, launch_no, S.q0, S.q1, S.DB, M, K, queue_cap, narrow_cap, s));
                 ++launch_no; ++launches;
             }
         }
@@ -511,6 +514,21 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
         if (rc) return rc;
         if (!done) compacted = false;      // the speculative pass ran on unfinished masks
         first = false;
+    }
+    if (hst->error & kErrOverflow) {
+        // A frontier queue overflowed and dropped entries: restore the fixed point with whole-graph
+        // sweeps (each operator re-derives K from its outputs) until one of them changes nothing.
+        compacted = false;
+        int32_t *changed = &S.state->changed;
+        for (;;) {
+            FillRegion cz[1] = {{changed, 8}};
+            DGN_HIP(launch_clear(cz, 1, s));
+            DGN_HIP(launch_fix_sweep(g->v, M, K, changed, grid, s));
+            ++launches;
+            DGN_HIP(hipMemcpyAsync(pin, S.state, sizeof(TravState), hipMemcpyDeviceToHost, s));
+            DGN_HIP(hipStreamSynchronize(s));
+            if (!hst->changed) break;
+        }
     }
     if (!compacted) {
         if (pq_bytes) {
@@ -535,7 +553,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
             DGN_HIP(hipEventElapsedTime(&stats->phase_ms[DGN_PHASE_TOTAL], ev[0], ev[6]));
         }
     }
-    return error_bits_to_code(hst->error);
+    return error_bits_to_code(hst->error & ~kErrOverflow);
 }
 
 int dgn_keep_compact(const dgn_graph *g, const uint64_t *tensor_mask_in, uint64_t *op_mask, uint8_t *op_flag,

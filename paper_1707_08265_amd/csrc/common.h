@@ -19,6 +19,7 @@ enum : int32_t {
     kErrTopo = 2,         // producer id >= consumer id
     kErrCsr = 4,          // row pointers not monotone / not ending at nnz
     kErrCrossGraph = 8,   // target or edge outside its own packed graph
+    kErrOverflow = 16,    // internal: a frontier queue overflowed, the fix-up sweep must run
 };
 
 // Adjacency of a built graph as the kernels see it (device pointers).
@@ -42,22 +43,26 @@ constexpr int32_t kThetaFloor = 64;   // deferral thresholds below this are trea
 // One slot of traversal state.  Launch number e reads slot e&1 and its finishing block writes
 // slot (e+1)&1, so a block of launch e that starts late never sees state of the next level.
 struct LevelSlot {
-    int32_t level;   // levels completed so far; queue parity = level & 1
-    int32_t n;       // entries in the frontier to process (the *other* slot's n collects pushes)
-    int32_t theta;   // entries whose producer id is below this are deferred at this level
-    int32_t pad;
+    int32_t level;          // levels completed so far; queue parity = level & 1
+    int32_t n;              // entries in the frontier to process (the *other* slot's n collects pushes)
+    int32_t theta;          // entries whose producer id is below this are deferred at this level
+    int32_t theta_hi;       // deferred operators with id in [theta, theta_hi) are expanded at this level
+    int32_t deferred_seen;  // some operator has been deferred so far
+    int32_t pad[3];
 };
 
 struct TravState {
     LevelSlot slot[2];
     int32_t ticket;            // working blocks that have finished the current launch
     int32_t error;             // sticky kErr* bits
-    int32_t processed;         // entries expanded (not deferred) in the current launch
-    int32_t max_deferred_key;  // largest producer id among the entries deferred in the current launch
-    u64 tensor_visits;         // entries expanded, summed over levels
+    int32_t processed;         // entries / operators expanded in the current launch
+    int32_t max_deferred_key;  // largest operator id deferred so far (-1: none)
+    u64 tensor_visits;         // expansions, summed over levels
     u64 max_frontier;
+    int32_t changed;           // fix-up sweep: some operator gained bits
+    int32_t pad[7];
 };
-static_assert(sizeof(TravState) == 64, "TravState is read back as 64 bytes");
+static_assert(sizeof(TravState) == 128, "TravState is read back as 128 bytes");
 
 // ---- wave64 helpers ---------------------------------------------------------------------------
 __device__ __forceinline__ int lane_id() { return (int)__lane_id(); }
@@ -135,14 +140,17 @@ hipError_t launch_check_graph_ranges(const GraphView &g, int32_t *error, hipStre
 constexpr size_t kQueueEntryBytes = 16;
 hipError_t launch_build_pinfo(const GraphView &g, int4 *pinfo, hipStream_t s);
 hipError_t launch_seed(const GraphView &g, int32_t Q, int64_t num_targets, const int32_t *tgt_rowptr,
-                       const int32_t *tgt_idx, u64 *M, TravState *st, void *q0, u64 *bm0, int32_t theta0,
+                       const int32_t *tgt_idx, u64 *M, TravState *st, void *q0, int32_t queue_cap, int32_t theta0,
                        hipStream_t s);
-// One wide level (whole chip); a frontier of at most narrow_cap entries is left to launch_narrow.
-hipError_t launch_level(const GraphView &g, TravState *st, int launch_no, void *q0, void *q1, u64 *bm0,
-                        u64 *bm1, u64 *M, u64 *K, int grid_blocks, int narrow_cap, float decay, hipStream_t s);
-// One workgroup runs level after level while 0 < frontier <= narrow_cap.
-hipError_t launch_narrow(const GraphView &g, TravState *st, int launch_no, void *q0, void *q1, u64 *bm0,
-                         u64 *bm1, u64 *M, u64 *K, int narrow_cap, hipStream_t s);
+// One wide level (whole chip); a frontier of at most narrow_cap entries is left to launch_narrow unless
+// deferred operators are waiting.  DB: deferred-operator bitmap, one bit per operator.
+hipError_t launch_level(const GraphView &g, TravState *st, int launch_no, void *q0, void *q1, u64 *DB, u64 *M,
+                        u64 *K, int grid_blocks, int queue_cap, int narrow_cap, float decay, hipStream_t s);
+// One workgroup runs level after level while 0 < frontier <= narrow_cap and nothing is deferred.
+hipError_t launch_narrow(const GraphView &g, TravState *st, int launch_no, void *q0, void *q1, u64 *DB, u64 *M,
+                         u64 *K, int queue_cap, int narrow_cap, hipStream_t s);
+// One sweep over all operators re-deriving K and pushing new bits to the inputs; *changed |= 1 if any.
+hipError_t launch_fix_sweep(const GraphView &g, u64 *M, u64 *K, int32_t *changed, int grid_blocks, hipStream_t s);
 
 // Removal rule + compaction.
 constexpr int kCompactTile = 2048;   // operators per workgroup in the count / scatter passes

@@ -9,15 +9,21 @@
 // Invariants maintained by every kernel in this file (u64 masks, bit q = flag of set q):
 //   (I1)  K[o] only receives bits that some output of o holds in M;
 //   (I2)  whenever K[o] gains bits n, the same thread ORs n into M[i] of every input i of o;
-//   (I3)  whenever M[t] gains bits, t is in a later frontier (once per level: a bitmap dedupes);
-//   (I4)  processing frontier entry t ORs the *whole* current M[t] into K of every producer of t;
-//   (I5)  an entry that is deferred stays in the frontier until it is processed.
-// At an empty frontier: K[o] = OR M[out(o)] and M[t] = S[t] | OR_{o reads t} K[o].
+//   (I3)  whenever M[t] gains bits, t is queued for the next level, or (queue full) an overflow
+//         flag is raised and a fix-up sweep restores the fixed point afterwards;
+//   (I4)  processing frontier entry t ORs the whole current M[t] into K of every producer of t;
+//   (I5)  instead of (I4), an entry whose single producer o is below the level's threshold may set
+//         bit o of the deferred-operator bitmap; when the threshold passes o, K[o] receives the OR
+//         of M over all outputs of o (which covers every entry deferred to o).
+// At an empty frontier with no deferred operator left: K[o] = OR M[out(o)] and
+// M[t] = S[t] | OR_{o reads t} K[o].
 //
-// Deferral (I5) is only a schedule: operator ids are a topological order, so an entry whose producer
-// id is still below the level's threshold is likely to receive more bits from operators with higher
-// ids; it waits (re-queued, 16 sequential bytes) while the threshold decays geometrically, and is
-// then expanded once with all of its bits instead of once per arrival.
+// Why defer: 64-bit atomics retire at roughly 25 G/s on this chip whatever their locality, so the
+// traversal is bound by the number of atomics.  Operator ids are a topological order, hence a tensor
+// whose producer id is low keeps receiving bits from higher-numbered operators for many levels;
+// expanding it once, after the geometrically decaying threshold has passed it, replaces several
+// expansions (each costing 1 + fan-in atomics) by one.  The frontier itself is not deduplicated:
+// a duplicate entry finds its bits already in K and costs one atomic.
 #include "common.h"
 
 namespace dgn {
@@ -25,8 +31,9 @@ namespace dgn {
 // Frontier entry: tensor id plus its producer record once that has been looked up.
 //   o >= 0 : single producer o with inputs in_idx[eb .. eb+deg)
 //   o == kFresh : not looked up yet         o == kMulti : several producers, prod_idx[eb .. eb+deg)
-//   o == kNoProducer : graph input (never queued again)
+//   o == kNoProducer : graph input
 struct __align__(16) Entry { int32_t t, o, eb, deg; };
+static_assert(sizeof(Entry) == kQueueEntryBytes, "queue entry size");
 
 __device__ __forceinline__ Entry load_entry(const Entry *q, int i)
 {
@@ -78,10 +85,14 @@ hipError_t launch_build_pinfo(const GraphView &g, int4 *pinfo, hipStream_t s)
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_seed(GraphView g, int32_t Q, int64_t num_targets, int64_t num_sets_total,
                                                const int32_t *tgt_rowptr, const int32_t *tgt_idx, u64 *M,
-                                               TravState *st, Entry *q0, u64 *bm0, int32_t theta0)
+                                               TravState *st, Entry *q0, int32_t queue_cap, int32_t theta0)
 {
     const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (j == 0) st->slot[0].theta = theta0;
+    if (j == 0) {
+        st->slot[0].theta = theta0;
+        st->slot[0].theta_hi = g.num_ops;
+        st->max_deferred_key = -1;
+    }
     bool push = false, bad = false, cross = false;
     int32_t t = 0;
     if (j < num_targets) {
@@ -102,32 +113,36 @@ __global__ __launch_bounds__(256) void k_seed(GraphView g, int32_t Q, int64_t nu
                     if (t < g.t_off[gi] || t >= g.t_off[gi + 1]) cross = true;
                 }
                 const u64 bit = (u64)1 << (lo % Q);
-                atomicOr(&M[t], bit);
-                const u64 tb = (u64)1 << (t & 63);
-                const u64 was = atomicOr(&bm0[t >> 6], tb);
-                push = (was & tb) == 0;
+                const u64 old = atomicOr(&M[t], bit);
+                push = (old & bit) == 0;                    // a duplicate target adds nothing new
             }
         }
     }
     // wave-aggregated slot reservation: one counter update per wave
     const u64 pm = ballot64(push);
+    bool overflow = false;
     if (pm) {
         int base = 0;
         if (lane_id() == 0) base = atomicAdd(&st->slot[0].n, __popcll(pm));
         base = __builtin_amdgcn_readfirstlane(base);
-        if (push) q0[base + __popcll(pm & lanemask_lt())] = Entry{t, kFresh, 0, 0};
+        const int pos = base + __popcll(pm & lanemask_lt());
+        if (push) {
+            if (pos < queue_cap) q0[pos] = Entry{t, kFresh, 0, 0};
+            else overflow = true;
+        }
     }
-    const int err = (bad ? kErrIdRange : 0) | (cross ? kErrCrossGraph : 0);
+    const int err = (bad ? kErrIdRange : 0) | (cross ? kErrCrossGraph : 0) | (overflow ? kErrOverflow : 0);
     if (err) atomicOr(&st->error, err);
 }
 
 hipError_t launch_seed(const GraphView &g, int32_t Q, int64_t num_targets, const int32_t *tgt_rowptr,
-                       const int32_t *tgt_idx, u64 *M, TravState *st, void *q0, u64 *bm0, int32_t theta0,
+                       const int32_t *tgt_idx, u64 *M, TravState *st, void *q0, int32_t queue_cap, int32_t theta0,
                        hipStream_t s)
 {
     const int64_t blocks = num_targets > 0 ? (num_targets + 255) / 256 : 1;
     hipLaunchKernelGGL(k_seed, dim3((unsigned)blocks), dim3(256), 0, s, g, Q, num_targets,
-                       (int64_t)g.num_graphs * Q, tgt_rowptr, tgt_idx, M, st, static_cast<Entry *>(q0), bm0, theta0);
+                       (int64_t)g.num_graphs * Q, tgt_rowptr, tgt_idx, M, st, static_cast<Entry *>(q0), queue_cap,
+                       theta0);
     return hipGetLastError();
 }
 
@@ -145,28 +160,33 @@ struct WaveStage {
 
 struct Frontier {     // one level's output side
     Entry *qout;
-    int32_t *n_out;   // global or LDS counter
-    u64 *bm_out;
+    int32_t *n_out;   // global or LDS counter (may run past cap: readers clamp)
+    int32_t cap;      // queue capacity in entries
+    int32_t *error;   // sticky error word of the traversal state
 };
 
 __device__ __forceinline__ void stage_flush(WaveStage &ws, const Frontier &f)
 {
     if (ws.cnt > 0) {
         int base = 0;
-        if (lane_id() == 0) base = atomicAdd(f.n_out, ws.cnt);
+        if (lane_id() == 0) {
+            base = atomicAdd(f.n_out, ws.cnt);
+            if (base + ws.cnt > f.cap) atomicOr(f.error, kErrOverflow);     // (I3): fix-up sweep will follow
+        }
         base = __builtin_amdgcn_readfirstlane(base);
-        for (int k = lane_id(); k < ws.cnt; k += kWave) f.qout[base + k] = ws.buf[k];
+        for (int k = lane_id(); k < ws.cnt; k += kWave)
+            if (base + k < f.cap) f.qout[base + k] = ws.buf[k];
         ws.cnt = 0;
     }
 }
 
-__device__ __forceinline__ void stage_push(WaveStage &ws, bool push, const Entry &v, const Frontier &f)
+__device__ __forceinline__ void stage_push(WaveStage &ws, bool push, int32_t t, const Frontier &f)
 {
     const u64 pm = ballot64(push);
     if (pm) {                                   // wave-uniform branch
         const int np = __popcll(pm);
         if (ws.cnt + np > kStageCap) stage_flush(ws, f);
-        if (push) ws.buf[ws.cnt + __popcll(pm & lanemask_lt())] = v;
+        if (push) ws.buf[ws.cnt + __popcll(pm & lanemask_lt())] = Entry{t, kFresh, 0, 0};
         ws.cnt += np;
     }
 }
@@ -202,13 +222,9 @@ __device__ __forceinline__ void expand_edges(const GraphView &g, int eb, int deg
         if (ev) {
             u = g.in_idx[o_eb + (e - o_excl)];
             const u64 old = atomicOr(&M[u], b);             // (I2)
-            if (b & ~old) {                                 // (I3)
-                const u64 ub = (u64)1 << (u & 63);
-                const u64 was = atomicOr(&f.bm_out[u >> 6], ub);
-                push = (was & ub) == 0;
-            }
+            push = (b & ~old) != 0;                         // (I3)
         }
-        stage_push(ws, push, Entry{u, kFresh, 0, 0}, f);
+        stage_push(ws, push, u, f);
     }
     __builtin_amdgcn_wave_barrier();
 }
@@ -218,35 +234,28 @@ struct LevelCounters {   // per-lane tallies, reduced by the caller
     int max_deferred_key;
 };
 
-// Process 64 frontier entries held one per lane (valid lanes only).
-__device__ __forceinline__ void process_wave(const GraphView &g, bool valid, Entry e, int32_t theta, u64 *bm_in,
-                                             u64 *M, u64 *K, int *s_incl, WaveStage &ws, const Frontier &f,
-                                             LevelCounters &lc)
+// Tensor-side step: 64 frontier entries held one per lane (valid lanes only).
+__device__ __forceinline__ void process_entries(const GraphView &g, bool valid, Entry e, int32_t theta, u64 *DB,
+                                                u64 *M, u64 *K, int *s_incl, WaveStage &ws, const Frontier &f,
+                                                LevelCounters &lc)
 {
     u64 m = 0;
-    bool defer = false;
+    bool active = false;
     if (valid) {
-        atomicAnd(&bm_in[e.t >> 6], ~((u64)1 << (e.t & 63)));   // leave the bitmap clean for its next use
         if (e.o == kFresh) {
             const int4 pi = g.pinfo[e.t];
             e.o = pi.x; e.eb = pi.y; e.deg = pi.z;
         }
-        defer = e.o >= 0 && e.o < theta;                    // (I5); multi-producer tensors are never deferred
-        if (!defer && e.o != kNoProducer) m = load_coherent(&M[e.t]);   // (I4): everything t holds right now
-    }
-    // deferred entries go back into the frontier (unless a push of this level already put t there)
-    {
-        bool push = false;
-        if (defer) {
-            const u64 tb = (u64)1 << (e.t & 63);
-            const u64 was = atomicOr(&f.bm_out[e.t >> 6], tb);
-            push = (was & tb) == 0;
+        if (e.o >= 0 && e.o < theta) {                      // (I5): wait for the threshold to pass o
+            const u64 ob = (u64)1 << (e.o & 63);
+            if ((load_coherent(&DB[e.o >> 6]) & ob) == 0) atomicOr(&DB[e.o >> 6], ob);
             lc.max_deferred_key = max(lc.max_deferred_key, e.o);
+        } else if (e.o != kNoProducer) {
+            active = true;
+            m = load_coherent(&M[e.t]);                     // (I4): everything t holds right now
+            lc.processed++;
         }
-        stage_push(ws, push, e, f);
     }
-    const bool active = valid && !defer && e.o != kNoProducer;
-    if (active) lc.processed++;
     // single-producer tensors (the common case)
     {
         u64 nb = 0;
@@ -277,11 +286,40 @@ __device__ __forceinline__ void process_wave(const GraphView &g, bool valid, Ent
     }
 }
 
-__device__ __forceinline__ int32_t next_theta(int32_t theta, float decay, int processed, int max_deferred_key)
+// Operator-side step: 64 operators held one per lane; K[o] |= OR of M over the outputs of o, new bits
+// go to the inputs.  Used for deferred operators (I5) and by the fix-up sweep.  Returns whether this
+// lane's operator gained bits.
+__device__ __forceinline__ bool process_ops(const GraphView &g, bool valid, int32_t o, u64 *M, u64 *K, int *s_incl,
+                                            WaveStage &ws, const Frontier &f)
+{
+    int ob = 0, n_out = 0, ib = 0, n_in = 0;
+    if (valid) {
+        ob = g.out_rowptr[o];
+        n_out = g.out_rowptr[o + 1] - ob;
+        ib = g.in_rowptr[o];
+        n_in = g.in_rowptr[o + 1] - ib;
+    }
+    u64 k = 0;
+    const int max_out = wave_max(n_out);
+    for (int r = 0; r < max_out; ++r)
+        if (r < n_out) k |= load_coherent(&M[g.out_idx[ob + r]]);
+    u64 nb = 0;
+    if (valid && k) {
+        const u64 cur = load_coherent(&K[o]);
+        if (k & ~cur) {
+            const u64 old = atomicOr(&K[o], k);             // (I1)
+            nb = k & ~old;
+        }
+    }
+    expand_edges(g, ib, nb ? n_in : 0, nb, M, s_incl, ws, f);
+    return nb != 0;
+}
+
+__device__ __forceinline__ int32_t next_theta(int32_t theta, float decay, bool idle, int max_deferred_key)
 {
     if (theta <= 0) return 0;
     float base = (float)theta;
-    if (processed == 0 && max_deferred_key >= 0) base = (float)max_deferred_key + 1.0f;   // jump to the work
+    if (idle && max_deferred_key >= 0 && max_deferred_key + 1 < theta) base = (float)max_deferred_key + 1.0f;
     const int32_t t = (int32_t)(base * decay);
     return t < kThetaFloor ? 0 : t;
 }
@@ -291,36 +329,43 @@ __device__ __forceinline__ int32_t next_theta(int32_t theta, float decay, int pr
 // ------------------------------------------------------------------------------------------------
 constexpr int kLevelThreads = 256;
 constexpr int kLevelWaves = kLevelThreads / kWave;
+constexpr int kChunkWords = 16;                   // deferred-bitmap words expanded per wave step
+constexpr int kChunkOps = kChunkWords * 64;
 
 __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState *st, int launch_no, Entry *q0,
-                                                          Entry *q1, u64 *bm0, u64 *bm1, u64 *M, u64 *K,
+                                                          Entry *q1, u64 *DB, u64 *M, u64 *K, int queue_cap,
                                                           int narrow_cap, float decay)
 {
     __shared__ Entry s_stage[kLevelWaves][kStageCap];
     __shared__ int s_incl[kLevelWaves][kWave];
+    __shared__ int32_t s_ops[kLevelWaves][kChunkOps];
     __shared__ int s_proc[kLevelWaves], s_maxkey[kLevelWaves];
 
     const LevelSlot in = st->slot[launch_no & 1];
     LevelSlot *out = &st->slot[(launch_no + 1) & 1];
-    const int n = in.n;
-    if (n <= narrow_cap) {       // finished, or small enough for the single-workgroup kernel: pass the state on
+    const int n = min(in.n, queue_cap);
+    const bool ranges_left = in.deferred_seen && in.theta_hi > 0;
+    if (n <= narrow_cap && !ranges_left) {   // finished, or small enough for the single-workgroup kernel
         if (blockIdx.x == 0 && threadIdx.x == 0) {
-            out->level = in.level;
-            out->theta = in.theta;
+            *out = in;
             out->n = n;
             st->slot[launch_no & 1].n = 0;
         }
         return;
     }
-    const int nwork = min((int)gridDim.x, (n + kLevelThreads - 1) / kLevelThreads);
+    // deferred operators whose range [theta, theta_hi) opens at this level
+    const int w_lo = ranges_left ? in.theta >> 6 : 0;
+    const int w_hi = ranges_left ? (in.theta_hi + 63) >> 6 : 0;
+    const int chunks = (w_hi - w_lo + kChunkWords - 1) / kChunkWords;
+    const int need = max((n + kLevelThreads - 1) / kLevelThreads, (chunks + kLevelWaves - 1) / kLevelWaves);
+    const int nwork = max(1, min((int)gridDim.x, need));
     if ((int)blockIdx.x >= nwork) return;
 
     const int cur = in.level & 1;
     const Entry *qin = cur ? q1 : q0;
-    u64 *bm_in = cur ? bm1 : bm0;
-    const Frontier f{cur ? q0 : q1, &out->n, cur ? bm0 : bm1};
+    const Frontier f{cur ? q0 : q1, &out->n, queue_cap, &st->error};
 
-    const int wave = threadIdx.x >> 6;
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
     WaveStage ws{&s_stage[wave][0], 0};
     LevelCounters lc{0, -1};
     for (int base = blockIdx.x * kLevelThreads; base < n; base += nwork * kLevelThreads) {
@@ -328,12 +373,44 @@ __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState 
         const bool valid = i < n;
         Entry e{0, kNoProducer, 0, 0};
         if (valid) e = load_entry(qin, i);
-        process_wave(g, valid, e, in.theta, bm_in, M, K, &s_incl[wave][0], ws, f, lc);
+        process_entries(g, valid, e, in.theta, DB, M, K, &s_incl[wave][0], ws, f, lc);
+    }
+    // expand the bitmap words of the newly opened range into dense operator lists, 64 per step
+    for (int c = blockIdx.x * kLevelWaves + wave; c < chunks; c += nwork * kLevelWaves) {
+        const int w0 = w_lo + c * kChunkWords;
+        u64 word = 0;
+        if (lane < kChunkWords && w0 + lane < w_hi) {
+            word = load_coherent(&DB[w0 + lane]);
+            const int64_t first = (int64_t)(w0 + lane) * 64;             // keep only ids in [theta, theta_hi)
+            if (first < in.theta) word &= ~(((u64)1 << (in.theta - first)) - 1);
+            if (first + 64 > in.theta_hi) word &= ((u64)1 << (in.theta_hi - first)) - 1;
+        }
+        // lane L expands quarter (L >> 4) of word (L & 15)
+        const u64 wsel = shfl64(word, lane & (kChunkWords - 1));
+        uint32_t bits16 = (uint32_t)(wsel >> (16 * (lane >> 4))) & 0xffffu;
+        const int cnt = __popc(bits16);
+        const int incl = wave_incl_scan(cnt);
+        const int total = __shfl(incl, kWave - 1, kWave);
+        int pos = incl - cnt;
+        const int32_t op_base = (w0 + (lane & (kChunkWords - 1))) * 64 + 16 * (lane >> 4);
+        while (bits16) {
+            const int b = __builtin_ctz(bits16);
+            bits16 &= bits16 - 1;
+            s_ops[wave][pos++] = op_base + b;
+        }
+        __builtin_amdgcn_wave_barrier();
+        for (int i0 = 0; i0 < total; i0 += kWave) {
+            const bool valid = i0 + lane < total;
+            const int32_t o = valid ? s_ops[wave][i0 + lane] : 0;
+            process_ops(g, valid, o, M, K, &s_incl[wave][0], ws, f);
+            if (valid) lc.processed++;
+        }
+        __builtin_amdgcn_wave_barrier();
     }
     stage_flush(ws, f);
 
     const int wproc = wave_sum(lc.processed), wkey = wave_max(lc.max_deferred_key);
-    if (lane_id() == 0) { s_proc[wave] = wproc; s_maxkey[wave] = wkey; }
+    if (lane == 0) { s_proc[wave] = wproc; s_maxkey[wave] = wkey; }
     // the last working block to finish publishes the next level
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -347,23 +424,26 @@ __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState 
             __threadfence();
             const int tot_proc = load_coherent(&st->processed);
             const int tot_key = load_coherent(&st->max_deferred_key);
+            const int n_next = load_coherent(&out->n);
             st->ticket = 0;
             st->processed = 0;
-            st->max_deferred_key = -1;
             st->slot[launch_no & 1].n = 0;                  // becomes the push counter of the next launch
             out->level = in.level + 1;
-            out->theta = next_theta(in.theta, decay, tot_proc, tot_key);
+            out->deferred_seen = tot_key >= 0;
+            out->theta_hi = ranges_left ? in.theta : in.theta_hi;   // [theta, theta_hi) has been scanned
+            out->theta = (ranges_left || tot_key >= 0) ? next_theta(in.theta, decay, tot_proc == 0 && n_next == 0, tot_key)
+                                                       : in.theta;
             st->tensor_visits += (u64)tot_proc;
             if ((u64)n > st->max_frontier) st->max_frontier = (u64)n;
         }
     }
 }
 
-hipError_t launch_level(const GraphView &g, TravState *st, int launch_no, void *q0, void *q1, u64 *bm0, u64 *bm1,
-                        u64 *M, u64 *K, int grid_blocks, int narrow_cap, float decay, hipStream_t s)
+hipError_t launch_level(const GraphView &g, TravState *st, int launch_no, void *q0, void *q1, u64 *DB, u64 *M, u64 *K,
+                        int grid_blocks, int queue_cap, int narrow_cap, float decay, hipStream_t s)
 {
     hipLaunchKernelGGL(k_level, dim3((unsigned)grid_blocks), dim3(kLevelThreads), 0, s, g, st, launch_no,
-                       static_cast<Entry *>(q0), static_cast<Entry *>(q1), bm0, bm1, M, K, narrow_cap, decay);
+                       static_cast<Entry *>(q0), static_cast<Entry *>(q1), DB, M, K, queue_cap, narrow_cap, decay);
     return hipGetLastError();
 }
 
@@ -375,7 +455,7 @@ constexpr int kNarrowThreads = 1024;
 constexpr int kNarrowWaves = kNarrowThreads / kWave;
 
 __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravState *st, int launch_no, Entry *q0,
-                                                            Entry *q1, u64 *bm0, u64 *bm1, u64 *M, u64 *K,
+                                                            Entry *q1, u64 *DB, u64 *M, u64 *K, int queue_cap,
                                                             int narrow_cap)
 {
     __shared__ Entry s_stage[kNarrowWaves][kStageCap];
@@ -383,39 +463,39 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
     __shared__ int s_nout;
 
     const LevelSlot in = st->slot[launch_no & 1];
-    int level = in.level, n = in.n;
+    int level = in.level, n = min(in.n, queue_cap);
+    const bool ranges_left = in.deferred_seen && in.theta_hi > 0;   // then the wide kernel must go on
     const int wave = threadIdx.x >> 6;
     WaveStage ws{&s_stage[wave][0], 0};
     LevelCounters lc{0, -1};
     u64 visits = 0, maxf = 0;
-    while (n > 0 && n <= narrow_cap) {
+    while (n > 0 && n <= narrow_cap && !ranges_left) {
         if (threadIdx.x == 0) s_nout = 0;
         __syncthreads();
         const int cur = level & 1;
         const Entry *qin = cur ? q1 : q0;
-        u64 *bm_in = cur ? bm1 : bm0;
-        const Frontier f{cur ? q0 : q1, &s_nout, cur ? bm0 : bm1};
+        const Frontier f{cur ? q0 : q1, &s_nout, queue_cap, &st->error};
         for (int base = 0; base < n; base += kNarrowThreads) {
             const int i = base + threadIdx.x;
             const bool valid = i < n;
             Entry e{0, kNoProducer, 0, 0};
             if (valid) e = load_entry(qin, i);
             // threshold 0: a small frontier is latency bound, so nothing is gained by deferring
-            process_wave(g, valid, e, 0, bm_in, M, K, &s_incl[wave][0], ws, f, lc);
+            process_entries(g, valid, e, 0, DB, M, K, &s_incl[wave][0], ws, f, lc);
         }
         stage_flush(ws, f);
-        __threadfence();          // queue entries and bitmap updates reach the device-coherent level
+        __threadfence();          // queue entries reach the device-coherent level before they are re-read
         __syncthreads();
         visits += (u64)n;
         if ((u64)n > maxf) maxf = (u64)n;
-        n = s_nout;
+        n = min(s_nout, queue_cap);
         ++level;
         __syncthreads();          // everyone has read s_nout before it is reset
     }
     if (threadIdx.x == 0) {
         LevelSlot *out = &st->slot[(launch_no + 1) & 1];
+        *out = in;
         out->level = level;
-        out->theta = in.theta;
         out->n = n;
         st->slot[launch_no & 1].n = 0;
         st->tensor_visits += visits;
@@ -423,11 +503,44 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
     }
 }
 
-hipError_t launch_narrow(const GraphView &g, TravState *st, int launch_no, void *q0, void *q1, u64 *bm0, u64 *bm1,
-                         u64 *M, u64 *K, int narrow_cap, hipStream_t s)
+hipError_t launch_narrow(const GraphView &g, TravState *st, int launch_no, void *q0, void *q1, u64 *DB, u64 *M,
+                         u64 *K, int queue_cap, int narrow_cap, hipStream_t s)
 {
     hipLaunchKernelGGL(k_narrow, dim3(1), dim3(kNarrowThreads), 0, s, g, st, launch_no, static_cast<Entry *>(q0),
-                       static_cast<Entry *>(q1), bm0, bm1, M, K, narrow_cap);
+                       static_cast<Entry *>(q1), DB, M, K, queue_cap, narrow_cap);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// fix-up sweep (only after a frontier queue overflowed): every operator re-derives K from its outputs
+// and pushes what is new to its inputs; repeated by the host until a sweep changes nothing
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kLevelThreads) void k_fix_sweep(GraphView g, u64 *M, u64 *K, int32_t *changed)
+{
+    __shared__ Entry s_stage[kLevelWaves][kStageCap];
+    __shared__ int s_incl[kLevelWaves][kWave];
+    __shared__ int32_t s_sink, s_err;
+    const int wave = threadIdx.x >> 6;
+    if (threadIdx.x == 0) { s_sink = 0; s_err = 0; }
+    __syncthreads();
+    WaveStage ws{&s_stage[wave][0], 0};
+    const Frontier f{nullptr, &s_sink, 0, &s_err};          // capacity 0: pushes are counted and dropped
+    bool any = false;
+    // descending ids: most of a sweep then sees its consumers' results (ids are a topological order)
+    const int64_t tiles = ((int64_t)g.num_ops + kLevelThreads - 1) / kLevelThreads;
+    for (int64_t tile = tiles - 1 - blockIdx.x; tile >= 0; tile -= gridDim.x) {
+        const int64_t o = tile * kLevelThreads + threadIdx.x;
+        const bool valid = o < g.num_ops;
+        any |= process_ops(g, valid, valid ? (int32_t)o : 0, M, K, &s_incl[wave][0], ws, f);
+        ws.cnt = 0;
+    }
+    if (ballot64(any) != 0 && lane_id() == 0) atomicOr(changed, 1);
+}
+
+hipError_t launch_fix_sweep(const GraphView &g, u64 *M, u64 *K, int32_t *changed, int grid_blocks, hipStream_t s)
+{
+    if (g.num_ops == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_fix_sweep, dim3((unsigned)grid_blocks), dim3(kLevelThreads), 0, s, g, M, K, changed);
     return hipGetLastError();
 }
 

@@ -18,13 +18,13 @@ def dgn():
     return d
 
 
-def gpu_prune(d, g, tg, recompute_keep=False, validate=False, stats=None):
+def gpu_prune(d, g, tg, recompute_keep=False, validate=False, stats=None, **knobs):
     import torch
     dg = d.DeviceGraph.from_coo(g, validate=validate)
     buf = d.PruneBuffers(dg, tg.num_sets)
     rowptr = torch.from_numpy(tg.tgt_rowptr).cuda()
     idx = torch.from_numpy(tg.tgt_idx).cuda()
-    opts = d.dgn_options(recompute_keep=1 if recompute_keep else 0)
+    opts = d.dgn_options(recompute_keep=1 if recompute_keep else 0, **knobs)
     rc = buf.prune(rowptr, idx, options=opts, stats=stats)
     assert rc == 0, d.dgn_strerror(rc)
     out = buf.to_host()
@@ -207,3 +207,17 @@ def test_buffers_are_reusable_and_outputs_fully_rewritten(dgn, oracle):
     assert buf1.prune(c(tg1.tgt_rowptr), c(tg1.tgt_idx)) == 0
     adj = oracle.build_adjacency(g.num_ops, g.num_tensors, g.in_op, g.in_tensor, g.out_op, g.out_tensor)
     assert_same(buf1.to_host(), oracle.forward_prune(adj, 1, tg1.tgt_rowptr, tg1.tgt_idx), "single")
+
+
+@pytest.mark.parametrize("k,scale", [(1, 0.5), (3, 0.01), (4, 0.001)])
+def test_schedule_knobs_do_not_change_results(dgn, oracle, k, scale):
+    """Deferral decay, forced one-launch-per-level traversal and a tiny frontier queue (which forces
+    the overflow fix-up sweeps) are schedules only: the fixed point is unique."""
+    g, tg = gg.config(k, scale)
+    _, r = oracle_prune(oracle, g, tg)
+    for knobs in (dict(defer_percent=100), dict(defer_percent=50), dict(defer_percent=95),
+                  dict(traversal=1), dict(traversal=1, defer_percent=60),
+                  dict(max_queue_entries=1000), dict(max_queue_entries=37, traversal=1)):
+        st = dgn.dgn_stats()
+        _, _, out = gpu_prune(dgn, g, tg, stats=st, **knobs)
+        assert_same(out, r, f"cfg{k} {knobs}")
