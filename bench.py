@@ -35,6 +35,7 @@ def main():
                     help="run the stand-alone removal-rule pass instead of reusing the traversal's K")
     ap.add_argument("--defer-percent", type=int, default=0, help="traversal schedule knob (0 = library default)")
     ap.add_argument("--generic", action="store_true", help="force the one-launch-per-level traversal")
+    ap.add_argument("--trace-levels", action="store_true", help="print the per-level trace of the last step")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path runs on ONE GPU only (no sharding or collectives are built); "
@@ -90,6 +91,9 @@ def main():
     opts = d.dgn_options(profile=1, recompute_keep=1 if args.recompute_keep else 0,
                          defer_percent=args.defer_percent, traversal=1 if args.generic else 0)
     st = d.dgn_stats()
+    trace = np.zeros((4096, 4), dtype=np.int32)
+    if args.trace_levels:
+        st.level_trace, st.level_trace_cap = trace.ctypes.data, trace.shape[0]
     for _ in range(args.warmup):
         rc = buf.prune(rowptr, idx, options=opts, stats=st)
         assert rc == 0, d.dgn_strerror(rc)
@@ -109,6 +113,9 @@ def main():
         f"visits={st.tensor_visits} max_frontier={st.max_frontier}")
     log("phase ms (HIP events, mean over timed steps): " + ", ".join(f"{k}={v:.3f}" for k, v in ph.items()))
 
+    if args.trace_levels:
+        for lv in range(min(int(st.levels), trace.shape[0])):
+            log(f"level {lv}: frontier={trace[lv, 0]} expanded={trace[lv, 1]} theta={trace[lv, 2]} range_top={trace[lv, 3]}")
     out = buf.to_host()
     P, T = g.num_ops, g.num_tensors
     P_k = int(out["kept_count"][0])

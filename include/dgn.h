@@ -120,7 +120,11 @@ typedef struct dgn_stats {
     int64_t max_frontier;    /* largest frontier                                                 */
     int64_t launches;        /* kernels enqueued by the call                                     */
     int64_t level_launches;  /* of which frontier-level kernels                                  */
-    int64_t reserved[3];
+    int32_t *level_trace;    /* IN, optional HOST buffer: per level 4 ints (frontier size, entries and
+                                operators expanded, deferral threshold, top of the operator range opened
+                                or -1), for the first level_trace_cap levels (at most 4096)               */
+    int64_t level_trace_cap; /* IN: capacity of level_trace in levels                                     */
+    int64_t reserved;
     float phase_ms[DGN_NUM_PHASES];   /* filled when options->profile; zero otherwise           */
 } dgn_stats;
 

@@ -53,7 +53,8 @@ class dgn_options(ctypes.Structure):
 
 class dgn_stats(ctypes.Structure):
     _fields_ = [("levels", c_int64), ("tensor_visits", c_int64), ("max_frontier", c_int64),
-                ("launches", c_int64), ("level_launches", c_int64), ("reserved", c_int64 * 3),
+                ("launches", c_int64), ("level_launches", c_int64), ("level_trace", c_void_p),
+                ("level_trace_cap", c_int64), ("reserved", c_int64),
                 ("phase_ms", ctypes.c_float * 8)]
 
 PHASES = ["clear", "seed", "traverse", "count", "scan", "scatter", "total"]

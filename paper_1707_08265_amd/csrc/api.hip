@@ -116,27 +116,48 @@ BuildScratch build_scratch(void *mem, int64_t P, int64_t T, int64_t Ein, int64_t
 
 struct PruneScratch {
     TravState *state;
-    void *q0, *q1;          // frontier queues, kQueueEntryBytes per tensor each
+    TravCounters *ctr;
+    int32_t *q0, *q1;       // frontier queues: qg.S segments of qg.seg_cap tensor ids each
+    QueueGeom qg;
     u64 *DB;                // deferred-operator bitmap
     u64 *opbits;
     int32_t *block_counts;
+    int4 *trace;            // per-level trace records (profiling only)
     size_t db_bytes, opbits_bytes;
     size_t bytes;
 };
 
-PruneScratch prune_scratch(void *mem, int64_t P, int64_t T)
+// Segments: enough of them that no push counter sees more than a few hundred waves per level, few
+// enough that tiny graphs do not pay for empty segments.  Total capacity 2T + slack: a level can hold
+// more than T entries because the frontier is not deduplicated (beyond that, the overflow path runs).
+QueueGeom queue_geometry(int64_t T, int64_t max_entries)
+{
+    int S = 1;
+    while (S < kMaxSeg && (int64_t)S * 16384 < T) S *= 2;
+    int64_t total = 2 * T + 1024;
+    if (max_entries > 0 && max_entries < total) total = max_entries;
+    int64_t seg = (total + S - 1) / S;
+    if (seg < 1) seg = 1;
+    return QueueGeom{S, (int32_t)seg};
+}
+
+PruneScratch prune_scratch(void *mem, int64_t P, int64_t T, int64_t max_entries)
 {
     Carver c(mem);
     PruneScratch S{};
-    S.state = c.take<TravState>(4);
-    S.q0 = c.take<char>((size_t)T * kQueueEntryBytes);
-    S.q1 = c.take<char>((size_t)T * kQueueEntryBytes);
+    S.state = c.take<TravState>(2);
+    S.ctr = c.take<TravCounters>(1);
+    S.qg = queue_geometry(T, max_entries);
+    const size_t qn = (size_t)S.qg.S * (size_t)S.qg.seg_cap;
+    S.q0 = c.take<int32_t>(qn);
+    S.q1 = c.take<int32_t>(qn);
     const size_t obw = (size_t)((P + 63) / 64);
     S.DB = c.take<u64>(obw);
     S.db_bytes = obw * 8;
     S.opbits = c.take<u64>(obw);
     S.opbits_bytes = obw * 8;
     S.block_counts = c.take<int32_t>((P + kCompactTile - 1) / kCompactTile + 1);
+    S.trace = c.take<int4>(kTraceLevels);
     S.bytes = c.off;
     return S;
 }
@@ -395,7 +416,7 @@ int dgn_prune_workspace(const dgn_graph *g, int32_t num_sets, size_t *scratch_by
 {
     if (!g || !scratch_bytes) return DGN_ERR_NULL_PTR;
     if (num_sets < 1 || num_sets > DGN_MAX_SETS) return DGN_ERR_TOO_MANY_SETS;
-    *scratch_bytes = prune_scratch(nullptr, g->P, g->T).bytes;
+    *scratch_bytes = prune_scratch(nullptr, g->P, g->T, 0).bytes;
     return DGN_OK;
 }
 
@@ -412,7 +433,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     if (rc) return rc;
     if (!tgt_rowptr || (num_targets > 0 && !tgt_idx) || !kept_count || !scratch) return DGN_ERR_NULL_PTR;
     if ((g->T > 0 && !tensor_mask) || (g->P > 0 && (!op_mask || !kept_ops))) return DGN_ERR_NULL_PTR;
-    const PruneScratch S = prune_scratch(scratch, g->P, g->T);
+    const PruneScratch S = prune_scratch(scratch, g->P, g->T, options ? options->max_queue_entries : 0);
     if (scratch_bytes < S.bytes) return DGN_ERR_WORKSPACE_TOO_SMALL;
     if (((uintptr_t)scratch | (uintptr_t)tensor_mask | (uintptr_t)op_mask | (uintptr_t)kept_masks |
          (uintptr_t)kept_count | (uintptr_t)per_query_count) & 7)
@@ -432,17 +453,14 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
 
     // nothing marked yet: clear outputs, frontier bitmaps and traversal state
     FillRegion clr[5] = {{M, (size_t)g->T * 8}, {K, (size_t)g->P * 8}, {S.DB, S.db_bytes},
-                         {S.state, 256},        {per_query_count, pq_bytes}};
+                         {S.state, 256 + sizeof(TravCounters)}, {per_query_count, pq_bytes}};
     DGN_HIP(launch_clear(clr, 5, s));
     if (ev) DGN_HIP(hipEventRecord(ev[1], s));
     // deferral schedule: threshold on the producer id, starting at decay*P and decaying geometrically
     int defer_percent = options && options->defer_percent ? options->defer_percent : kDefaultDeferPercent;
     const float decay = defer_percent >= 100 ? 1.0f : (float)defer_percent / 100.0f;
     const int32_t theta0 = defer_percent >= 100 ? 0 : (int32_t)((double)g->P * decay);
-    int64_t qcap64 = g->T;
-    if (options && options->max_queue_entries > 0 && options->max_queue_entries < qcap64) qcap64 = options->max_queue_entries;
-    const int queue_cap = (int)qcap64;
-    DGN_HIP(launch_seed(g->v, num_sets, num_targets, tgt_rowptr, tgt_idx, M, S.state, S.q0, queue_cap, theta0, s));
+    DGN_HIP(launch_seed(g->v, num_sets, num_targets, tgt_rowptr, tgt_idx, M, S.state, S.ctr, S.q0, S.qg, theta0, s));
     if (ev) DGN_HIP(hipEventRecord(ev[2], s));
     launches += 2;
 
@@ -476,6 +494,9 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     const bool generic_only = options && options->traversal == 1;
     const int narrow_cap = generic_only ? 0 : kNarrowCap;
     int launch_no = 0;
+    int32_t *user_trace = stats ? stats->level_trace : nullptr;
+    const int64_t user_trace_cap = stats ? stats->level_trace_cap : 0;
+    int4 *trace = (user_trace && user_trace_cap > 0) ? S.trace : nullptr;
     // the stand-alone removal-rule pass rewrites K, which the traversal still needs while unfinished
     const bool speculate = !ca.from_tensor_mask;
     bool done = false, compacted = false;
@@ -487,7 +508,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
         return DGN_OK;
     };
     if (!generic_only) {
-        DGN_HIP(launch_narrow(g->v, S.state, launch_no, S.q0, S.q1, S.DB, M, K, queue_cap, narrow_cap, s));
+        DGN_HIP(launch_narrow(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, narrow_cap, trace, s));
         ++launch_no; ++launches;
         rc = read_state();
         if (rc) return rc;
@@ -496,11 +517,11 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     while (!done) {
         for (int r = 0; r < kWideGroups; ++r) {
             for (int i = 0; i < kWidePerGroup; ++i, ++launch_no)
-                DGN_HIP(launch_level(g->v, S.state, launch_no, S.q0, S.q1, S.DB, M, K, grid, queue_cap, narrow_cap, decay, s));
+                DGN_HIP(launch_level(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, grid, narrow_cap, decay, trace, s));
             launches += kWidePerGroup;
             level_launches += kWidePerGroup;
             if (!generic_only) {
-                DGN_HIP(launch_narrow(g->v, S.state, launch_no, S.q0, S.q1, S.DB, M, K, queue_cap, narrow_cap, s));
+                DGN_HIP(launch_narrow(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, narrow_cap, trace, s));
                 ++launch_no; ++launches;
             }
         }
@@ -543,7 +564,17 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     }
     if (stats) {
         memset(stats, 0, sizeof(*stats));
+        stats->level_trace = user_trace;
+        stats->level_trace_cap = user_trace_cap;
         stats->levels = hst->slot[launch_no & 1].level;
+        if (trace) {
+            int64_t nrec = stats->levels < user_trace_cap ? stats->levels : user_trace_cap;
+            if (nrec > kTraceLevels) nrec = kTraceLevels;
+            if (nrec > 0) {
+                DGN_HIP(hipMemcpyAsync(user_trace, S.trace, (size_t)nrec * sizeof(int4), hipMemcpyDeviceToHost, s));
+                DGN_HIP(hipStreamSynchronize(s));
+            }
+        }
         stats->tensor_visits = (int64_t)hst->tensor_visits;
         stats->max_frontier = (int64_t)hst->max_frontier;
         stats->launches = launches;
@@ -563,7 +594,7 @@ int dgn_keep_compact(const dgn_graph *g, const uint64_t *tensor_mask_in, uint64_
     if (!g) return DGN_ERR_NULL_PTR;
     if (!kept_count || !scratch) return DGN_ERR_NULL_PTR;
     if ((g->T > 0 && !tensor_mask_in) || (g->P > 0 && (!op_mask || !kept_ops))) return DGN_ERR_NULL_PTR;
-    const PruneScratch S = prune_scratch(scratch, g->P, g->T);
+    const PruneScratch S = prune_scratch(scratch, g->P, g->T, 0);
     if (scratch_bytes < S.bytes) return DGN_ERR_WORKSPACE_TOO_SMALL;
     if (((uintptr_t)scratch | (uintptr_t)tensor_mask_in | (uintptr_t)op_mask | (uintptr_t)kept_masks |
          (uintptr_t)kept_count | (uintptr_t)per_query_count) & 7)

@@ -51,17 +51,31 @@ struct LevelSlot {
     int32_t pad[3];
 };
 
-struct TravState {
+struct TravState {            // header of the traversal state; the host reads these 128 bytes back
     LevelSlot slot[2];
-    int32_t ticket;            // working blocks that have finished the current launch
+    u64 ticket;                // low half: block groups that have finished the current launch;
+                               // high half: entries / operators they expanded
     int32_t error;             // sticky kErr* bits
-    int32_t processed;         // entries / operators expanded in the current launch
-    int32_t max_deferred_key;  // largest operator id deferred so far (-1: none)
+    int32_t max_deferred_key1; // 1 + largest operator id deferred so far (0: none)
     u64 tensor_visits;         // expansions, summed over levels
     u64 max_frontier;
     int32_t changed;           // fix-up sweep: some operator gained bits
     int32_t pad[7];
 };
+
+// Contended words live 64 bytes apart, one per queue segment / block group.
+constexpr int kMaxSeg = 64;
+// Optional per-level trace (frontier size, expansions, threshold, range top), first kTraceLevels levels.
+constexpr int kTraceLevels = 4096;
+struct SegCounter { int32_t v; int32_t pad[15]; };
+struct SegTicket { u64 v; u64 pad[7]; };
+struct TravCounters {
+    SegCounter cnt[2][kMaxSeg];      // push counters of the frontier queues, indexed by launch parity
+    SegTicket subticket[kMaxSeg];    // first-level tickets
+    SegCounter submax[kMaxSeg];      // per-group 1 + largest deferred operator id
+};
+// A frontier queue: S segments (power of two, <= kMaxSeg) of seg_cap entries each.
+struct QueueGeom { int32_t S; int32_t seg_cap; };
 static_assert(sizeof(TravState) == 128, "TravState is read back as 128 bytes");
 
 // ---- wave64 helpers ---------------------------------------------------------------------------
@@ -136,19 +150,18 @@ hipError_t launch_check_topological(const GraphView &g, int32_t *error, hipStrea
 hipError_t launch_check_graph_ranges(const GraphView &g, int32_t *error, hipStream_t s);
 
 // Traversal.
-// Frontier queues hold 16-byte entries (kQueueEntryBytes per tensor, two queues).
-constexpr size_t kQueueEntryBytes = 16;
 hipError_t launch_build_pinfo(const GraphView &g, int4 *pinfo, hipStream_t s);
 hipError_t launch_seed(const GraphView &g, int32_t Q, int64_t num_targets, const int32_t *tgt_rowptr,
-                       const int32_t *tgt_idx, u64 *M, TravState *st, void *q0, int32_t queue_cap, int32_t theta0,
-                       hipStream_t s);
+                       const int32_t *tgt_idx, u64 *M, TravState *st, TravCounters *ctr, int32_t *q0,
+                       const QueueGeom &qg, int32_t theta0, hipStream_t s);
 // One wide level (whole chip); a frontier of at most narrow_cap entries is left to launch_narrow unless
 // deferred operators are waiting.  DB: deferred-operator bitmap, one bit per operator.
-hipError_t launch_level(const GraphView &g, TravState *st, int launch_no, void *q0, void *q1, u64 *DB, u64 *M,
-                        u64 *K, int grid_blocks, int queue_cap, int narrow_cap, float decay, hipStream_t s);
+hipError_t launch_level(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
+                        const QueueGeom &qg, u64 *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap, float decay,
+                        int4 *trace, hipStream_t s);
 // One workgroup runs level after level while 0 < frontier <= narrow_cap and nothing is deferred.
-hipError_t launch_narrow(const GraphView &g, TravState *st, int launch_no, void *q0, void *q1, u64 *DB, u64 *M,
-                         u64 *K, int queue_cap, int narrow_cap, hipStream_t s);
+hipError_t launch_narrow(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
+                         const QueueGeom &qg, u64 *DB, u64 *M, u64 *K, int narrow_cap, int4 *trace, hipStream_t s);
 // One sweep over all operators re-deriving K and pushing new bits to the inputs; *changed |= 1 if any.
 hipError_t launch_fix_sweep(const GraphView &g, u64 *M, u64 *K, int32_t *changed, int grid_blocks, hipStream_t s);
 

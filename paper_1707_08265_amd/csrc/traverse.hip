@@ -28,26 +28,9 @@
 
 namespace dgn {
 
-// Frontier entry: tensor id plus its producer record once that has been looked up.
-//   o >= 0 : single producer o with inputs in_idx[eb .. eb+deg)
-//   o == kFresh : not looked up yet         o == kMulti : several producers, prod_idx[eb .. eb+deg)
-//   o == kNoProducer : graph input
-struct __align__(16) Entry { int32_t t, o, eb, deg; };
-static_assert(sizeof(Entry) == kQueueEntryBytes, "queue entry size");
-
-__device__ __forceinline__ Entry load_entry(const Entry *q, int i)
-{
-    // two 8-byte loads that bypass the per-CU cache: a persistent workgroup re-reads queue slots that
-    // it wrote itself two levels earlier
-    const u64 *p = reinterpret_cast<const u64 *>(q + i);
-    const u64 a = load_coherent(p), b = load_coherent(p + 1);
-    Entry e;
-    e.t = (int32_t)(a & 0xffffffffu);
-    e.o = (int32_t)(a >> 32);
-    e.eb = (int32_t)(b & 0xffffffffu);
-    e.deg = (int32_t)(b >> 32);
-    return e;
-}
+// Frontier queues hold tensor ids.  A queue is split into S segments with one push counter each
+// (64 bytes apart): atomics on ONE address retire at about 11 ns each on this chip, so a single
+// counter bumped by every wave of a wide level would cost more than the level's real work.
 
 // ------------------------------------------------------------------------------------------------
 // producer records, built once per graph
@@ -81,17 +64,90 @@ hipError_t launch_build_pinfo(const GraphView &g, int4 *pinfo, hipStream_t s)
 }
 
 // ------------------------------------------------------------------------------------------------
+// segmented frontier queues
+// ------------------------------------------------------------------------------------------------
+constexpr int kStageCap = 512;     // staged pushes per wave before a flush
+
+// Per-wave staging of next-frontier entries in LDS: slots are reserved with ballot + popcount, a
+// segment counter is touched once per flush instead of once per push.
+struct WaveStage {
+    int32_t *buf;     // this wave's kStageCap ints in LDS
+    int cnt;          // wave-uniform
+};
+
+struct Frontier {     // where one wave pushes
+    int32_t *seg;     // start of the wave's segment in the output queue
+    int32_t *cnt;     // that segment's push counter, global or LDS (may run past seg_cap: readers clamp)
+    int32_t seg_cap;
+    int32_t *error;   // sticky error word of the traversal state
+};
+
+__device__ __forceinline__ void stage_flush(WaveStage &ws, const Frontier &f)
+{
+    if (ws.cnt > 0) {
+        int base = 0;
+        if (lane_id() == 0) {
+            base = atomicAdd(f.cnt, ws.cnt);
+            if (base + ws.cnt > f.seg_cap) atomicOr(f.error, kErrOverflow);   // (I3): fix-up sweep will follow
+        }
+        base = __builtin_amdgcn_readfirstlane(base);
+        for (int k = lane_id(); k < ws.cnt; k += kWave)
+            if (base + k < f.seg_cap) f.seg[base + k] = ws.buf[k];
+        ws.cnt = 0;
+    }
+}
+
+__device__ __forceinline__ void stage_push(WaveStage &ws, bool push, int32_t t, const Frontier &f)
+{
+    const u64 pm = ballot64(push);
+    if (pm) {                                   // wave-uniform branch
+        const int np = __popcll(pm);
+        if (ws.cnt + np > kStageCap) stage_flush(ws, f);
+        if (push) ws.buf[ws.cnt + __popcll(pm & lanemask_lt())] = t;
+        ws.cnt += np;
+    }
+}
+
+// Reader side: prefix sums of the (clamped) segment counts, computed by wave 0 into s_pref[0..S].
+// Must be called by the whole block; returns the frontier size.
+__device__ __forceinline__ int load_segments(const SegCounter *cnt, const QueueGeom &qg, int *s_pref)
+{
+    if (threadIdx.x < kWave) {
+        const int lane = lane_id();
+        int c = 0;
+        if (lane < qg.S) c = min(load_coherent(&cnt[lane].v), qg.seg_cap);
+        const int incl = wave_incl_scan(c);
+        if (lane == 0) s_pref[0] = 0;
+        s_pref[lane + 1] = incl;
+    }
+    __syncthreads();
+    return s_pref[kMaxSeg];
+}
+
+__device__ __forceinline__ int32_t load_item(const int32_t *q, const QueueGeom &qg, const int *s_pref, int i)
+{
+    int lo = 0, hi = kMaxSeg - 1;               // segment holding item i: last s with s_pref[s] <= i
+#pragma unroll
+    for (int it = 0; it < 6; ++it) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (s_pref[mid] <= i) lo = mid; else hi = mid - 1;
+    }
+    // bypass the per-CU cache: a persistent workgroup re-reads queue slots it wrote two levels earlier
+    return load_coherent(&q[(int64_t)lo * qg.seg_cap + (i - s_pref[lo])]);
+}
+
+// ------------------------------------------------------------------------------------------------
 // seed: main loop of Algorithm 1 ("for t in T: if not m_t: ...") -- scatter the target bits
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_seed(GraphView g, int32_t Q, int64_t num_targets, int64_t num_sets_total,
                                                const int32_t *tgt_rowptr, const int32_t *tgt_idx, u64 *M,
-                                               TravState *st, Entry *q0, int32_t queue_cap, int32_t theta0)
+                                               TravState *st, TravCounters *ctr, int32_t *q0, QueueGeom qg,
+                                               int32_t theta0)
 {
     const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (j == 0) {
         st->slot[0].theta = theta0;
         st->slot[0].theta_hi = g.num_ops;
-        st->max_deferred_key = -1;
     }
     bool push = false, bad = false, cross = false;
     int32_t t = 0;
@@ -118,16 +174,17 @@ __global__ __launch_bounds__(256) void k_seed(GraphView g, int32_t Q, int64_t nu
             }
         }
     }
-    // wave-aggregated slot reservation: one counter update per wave
+    // wave-aggregated slot reservation: one counter update per wave, counters spread over segments
     const u64 pm = ballot64(push);
     bool overflow = false;
     if (pm) {
+        const int seg = (int)((j >> 6) & (qg.S - 1));
         int base = 0;
-        if (lane_id() == 0) base = atomicAdd(&st->slot[0].n, __popcll(pm));
+        if (lane_id() == 0) base = atomicAdd(&ctr->cnt[0][seg].v, __popcll(pm));
         base = __builtin_amdgcn_readfirstlane(base);
         const int pos = base + __popcll(pm & lanemask_lt());
         if (push) {
-            if (pos < queue_cap) q0[pos] = Entry{t, kFresh, 0, 0};
+            if (pos < qg.seg_cap) q0[(int64_t)seg * qg.seg_cap + pos] = t;
             else overflow = true;
         }
     }
@@ -136,60 +193,18 @@ __global__ __launch_bounds__(256) void k_seed(GraphView g, int32_t Q, int64_t nu
 }
 
 hipError_t launch_seed(const GraphView &g, int32_t Q, int64_t num_targets, const int32_t *tgt_rowptr,
-                       const int32_t *tgt_idx, u64 *M, TravState *st, void *q0, int32_t queue_cap, int32_t theta0,
-                       hipStream_t s)
+                       const int32_t *tgt_idx, u64 *M, TravState *st, TravCounters *ctr, int32_t *q0,
+                       const QueueGeom &qg, int32_t theta0, hipStream_t s)
 {
     const int64_t blocks = num_targets > 0 ? (num_targets + 255) / 256 : 1;
     hipLaunchKernelGGL(k_seed, dim3((unsigned)blocks), dim3(256), 0, s, g, Q, num_targets,
-                       (int64_t)g.num_graphs * Q, tgt_rowptr, tgt_idx, M, st, static_cast<Entry *>(q0), queue_cap,
-                       theta0);
+                       (int64_t)g.num_graphs * Q, tgt_rowptr, tgt_idx, M, st, ctr, q0, qg, theta0);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------------
 // frontier expansion shared by the level kernels
 // ------------------------------------------------------------------------------------------------
-constexpr int kStageCap = 192;     // staged pushes per wave before a flush (16-byte entries)
-
-// Per-wave staging of next-frontier entries in LDS: slots are reserved with ballot + popcount, the
-// queue counter is touched once per flush instead of once per push.
-struct WaveStage {
-    Entry *buf;       // this wave's kStageCap entries in LDS
-    int cnt;          // wave-uniform
-};
-
-struct Frontier {     // one level's output side
-    Entry *qout;
-    int32_t *n_out;   // global or LDS counter (may run past cap: readers clamp)
-    int32_t cap;      // queue capacity in entries
-    int32_t *error;   // sticky error word of the traversal state
-};
-
-__device__ __forceinline__ void stage_flush(WaveStage &ws, const Frontier &f)
-{
-    if (ws.cnt > 0) {
-        int base = 0;
-        if (lane_id() == 0) {
-            base = atomicAdd(f.n_out, ws.cnt);
-            if (base + ws.cnt > f.cap) atomicOr(f.error, kErrOverflow);     // (I3): fix-up sweep will follow
-        }
-        base = __builtin_amdgcn_readfirstlane(base);
-        for (int k = lane_id(); k < ws.cnt; k += kWave)
-            if (base + k < f.cap) f.qout[base + k] = ws.buf[k];
-        ws.cnt = 0;
-    }
-}
-
-__device__ __forceinline__ void stage_push(WaveStage &ws, bool push, int32_t t, const Frontier &f)
-{
-    const u64 pm = ballot64(push);
-    if (pm) {                                   // wave-uniform branch
-        const int np = __popcll(pm);
-        if (ws.cnt + np > kStageCap) stage_flush(ws, f);
-        if (push) ws.buf[ws.cnt + __popcll(pm & lanemask_lt())] = Entry{t, kFresh, 0, 0};
-        ws.cnt += np;
-    }
-}
 
 // Lane l holds operator-side work (eb, deg, bits): OR `bits` into M of the deg inputs starting at
 // in_idx[eb].  The edges of all 64 lanes are spread evenly over the wave (prefix sum + search), so a
@@ -234,25 +249,23 @@ struct LevelCounters {   // per-lane tallies, reduced by the caller
     int max_deferred_key;
 };
 
-// Tensor-side step: 64 frontier entries held one per lane (valid lanes only).
-__device__ __forceinline__ void process_entries(const GraphView &g, bool valid, Entry e, int32_t theta, u64 *DB,
+// Tensor-side step: 64 frontier tensors held one per lane (valid lanes only).
+__device__ __forceinline__ void process_entries(const GraphView &g, bool valid, int32_t t, int32_t theta, u64 *DB,
                                                 u64 *M, u64 *K, int *s_incl, WaveStage &ws, const Frontier &f,
                                                 LevelCounters &lc)
 {
     u64 m = 0;
     bool active = false;
+    int4 pi = make_int4(kNoProducer, 0, 0, 0);
     if (valid) {
-        if (e.o == kFresh) {
-            const int4 pi = g.pinfo[e.t];
-            e.o = pi.x; e.eb = pi.y; e.deg = pi.z;
-        }
-        if (e.o >= 0 && e.o < theta) {                      // (I5): wait for the threshold to pass o
-            const u64 ob = (u64)1 << (e.o & 63);
-            if ((load_coherent(&DB[e.o >> 6]) & ob) == 0) atomicOr(&DB[e.o >> 6], ob);
-            lc.max_deferred_key = max(lc.max_deferred_key, e.o);
-        } else if (e.o != kNoProducer) {
+        pi = g.pinfo[t];                                    // (o, eb, deg): producer record
+        if (pi.x >= 0 && pi.x < theta) {                    // (I5): wait for the threshold to pass o
+            const u64 ob = (u64)1 << (pi.x & 63);
+            if ((load_coherent(&DB[pi.x >> 6]) & ob) == 0) atomicOr(&DB[pi.x >> 6], ob);
+            lc.max_deferred_key = max(lc.max_deferred_key, pi.x);
+        } else if (pi.x != kNoProducer) {
             active = true;
-            m = load_coherent(&M[e.t]);                     // (I4): everything t holds right now
+            m = load_coherent(&M[t]);                       // (I4): everything t holds right now
             lc.processed++;
         }
     }
@@ -260,21 +273,21 @@ __device__ __forceinline__ void process_entries(const GraphView &g, bool valid, 
     {
         u64 nb = 0;
         int deg = 0;
-        if (active && e.o >= 0) {
-            const u64 old = atomicOr(&K[e.o], m);           // (I1)
+        if (active && pi.x >= 0) {
+            const u64 old = atomicOr(&K[pi.x], m);          // (I1)
             nb = m & ~old;                                  // bits o did not have yet
-            if (nb) deg = e.deg;
+            if (nb) deg = pi.z;
         }
-        expand_edges(g, e.eb, deg, nb, M, s_incl, ws, f);
+        expand_edges(g, pi.y, deg, nb, M, s_incl, ws, f);
     }
     // tensors with several producers: one pass per producer rank
-    const bool multi = active && e.o == kMulti;
-    const int max_prod = wave_max(multi ? e.deg : 0);
+    const bool multi = active && pi.x == kMulti;
+    const int max_prod = wave_max(multi ? pi.z : 0);
     for (int r = 0; r < max_prod; ++r) {
         u64 nb = 0;
         int eb = 0, deg = 0;
-        if (multi && r < e.deg) {
-            const int32_t o = g.prod_idx[e.eb + r];
+        if (multi && r < pi.z) {
+            const int32_t o = g.prod_idx[pi.y + r];
             const u64 old = atomicOr(&K[o], m);
             nb = m & ~old;
             if (nb) {
@@ -329,70 +342,83 @@ __device__ __forceinline__ int32_t next_theta(int32_t theta, float decay, bool i
 // ------------------------------------------------------------------------------------------------
 constexpr int kLevelThreads = 256;
 constexpr int kLevelWaves = kLevelThreads / kWave;
-constexpr int kChunkWords = 16;                   // deferred-bitmap words expanded per wave step
-constexpr int kChunkOps = kChunkWords * 64;
+constexpr int kChunkOps = 16 * 64;                 // at most 16 deferred-bitmap words are expanded per wave step
 
-__global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState *st, int launch_no, Entry *q0,
-                                                          Entry *q1, u64 *DB, u64 *M, u64 *K, int queue_cap,
-                                                          int narrow_cap, float decay)
+__global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState *st, TravCounters *ctr, int launch_no,
+                                                          int32_t *q0, int32_t *q1, QueueGeom qg, u64 *DB, u64 *M,
+                                                          u64 *K, int narrow_cap, float decay, int4 *trace)
 {
-    __shared__ Entry s_stage[kLevelWaves][kStageCap];
+    __shared__ int32_t s_stage[kLevelWaves][kStageCap];
     __shared__ int s_incl[kLevelWaves][kWave];
     __shared__ int32_t s_ops[kLevelWaves][kChunkOps];
+    __shared__ int s_pref[kMaxSeg + 1];
     __shared__ int s_proc[kLevelWaves], s_maxkey[kLevelWaves];
+    __shared__ int s_last;
 
-    const LevelSlot in = st->slot[launch_no & 1];
-    LevelSlot *out = &st->slot[(launch_no + 1) & 1];
-    const int n = min(in.n, queue_cap);
+    const int in_slot = launch_no & 1, out_slot = in_slot ^ 1;
+    const LevelSlot in = st->slot[in_slot];
+    LevelSlot *out = &st->slot[out_slot];
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int n = load_segments(ctr->cnt[in_slot], qg, s_pref);
     const bool ranges_left = in.deferred_seen && in.theta_hi > 0;
     if (n <= narrow_cap && !ranges_left) {   // finished, or small enough for the single-workgroup kernel
-        if (blockIdx.x == 0 && threadIdx.x == 0) {
-            *out = in;
-            out->n = n;
-            st->slot[launch_no & 1].n = 0;
+        if (blockIdx.x == 0 && threadIdx.x < kMaxSeg) {     // hand the frontier (its counters) to the next launch
+            const int c = s_pref[lane + 1] - s_pref[lane];
+            ctr->cnt[out_slot][lane].v = c;
+            ctr->cnt[in_slot][lane].v = 0;
+            if (lane == 0) {
+                *out = in;
+                out->n = n;
+            }
         }
         return;
     }
-    // deferred operators whose range [theta, theta_hi) opens at this level
+    // deferred operators whose range [theta, theta_hi) opens at this level; the bitmap words of the
+    // range are dealt to the waves in chunks of cw words (a power of two, 1..16): small enough that a
+    // dense range is spread over many waves, large enough that a sparse one needs few steps per wave
     const int w_lo = ranges_left ? in.theta >> 6 : 0;
     const int w_hi = ranges_left ? (in.theta_hi + 63) >> 6 : 0;
-    const int chunks = (w_hi - w_lo + kChunkWords - 1) / kChunkWords;
+    int cw_log = 0;
+    while (cw_log < 4 && ((w_hi - w_lo) >> cw_log) > (int)gridDim.x * kLevelWaves) ++cw_log;
+    const int cw = 1 << cw_log;
+    const int chunks = (w_hi - w_lo + cw - 1) >> cw_log;
     const int need = max((n + kLevelThreads - 1) / kLevelThreads, (chunks + kLevelWaves - 1) / kLevelWaves);
     const int nwork = max(1, min((int)gridDim.x, need));
     if ((int)blockIdx.x >= nwork) return;
 
     const int cur = in.level & 1;
-    const Entry *qin = cur ? q1 : q0;
-    const Frontier f{cur ? q0 : q1, &out->n, queue_cap, &st->error};
+    const int32_t *qin = cur ? q1 : q0;
+    int32_t *qout = cur ? q0 : q1;
+    const int seg = (blockIdx.x * kLevelWaves + wave) & (qg.S - 1);
+    const Frontier f{qout + (int64_t)seg * qg.seg_cap, &ctr->cnt[out_slot][seg].v, qg.seg_cap, &st->error};
 
-    const int lane = lane_id(), wave = threadIdx.x >> 6;
     WaveStage ws{&s_stage[wave][0], 0};
     LevelCounters lc{0, -1};
     for (int base = blockIdx.x * kLevelThreads; base < n; base += nwork * kLevelThreads) {
         const int i = base + threadIdx.x;
         const bool valid = i < n;
-        Entry e{0, kNoProducer, 0, 0};
-        if (valid) e = load_entry(qin, i);
-        process_entries(g, valid, e, in.theta, DB, M, K, &s_incl[wave][0], ws, f, lc);
+        const int32_t t = valid ? load_item(qin, qg, s_pref, i) : 0;
+        process_entries(g, valid, t, in.theta, DB, M, K, &s_incl[wave][0], ws, f, lc);
     }
     // expand the bitmap words of the newly opened range into dense operator lists, 64 per step
     for (int c = blockIdx.x * kLevelWaves + wave; c < chunks; c += nwork * kLevelWaves) {
-        const int w0 = w_lo + c * kChunkWords;
+        const int w0 = w_lo + (c << cw_log);
         u64 word = 0;
-        if (lane < kChunkWords && w0 + lane < w_hi) {
+        if (lane < cw && w0 + lane < w_hi) {
             word = load_coherent(&DB[w0 + lane]);
             const int64_t first = (int64_t)(w0 + lane) * 64;             // keep only ids in [theta, theta_hi)
             if (first < in.theta) word &= ~(((u64)1 << (in.theta - first)) - 1);
             if (first + 64 > in.theta_hi) word &= ((u64)1 << (in.theta_hi - first)) - 1;
         }
-        // lane L expands quarter (L >> 4) of word (L & 15)
-        const u64 wsel = shfl64(word, lane & (kChunkWords - 1));
-        uint32_t bits16 = (uint32_t)(wsel >> (16 * (lane >> 4))) & 0xffffu;
+        // lane L expands part (L >> cw_log) of word (L & (cw-1)); a part is cw bits wide
+        const u64 wsel = shfl64(word, lane & (cw - 1));
+        const int part = lane >> cw_log;
+        uint32_t bits16 = (uint32_t)(wsel >> (part << cw_log)) & ((1u << cw) - 1u);
         const int cnt = __popc(bits16);
         const int incl = wave_incl_scan(cnt);
         const int total = __shfl(incl, kWave - 1, kWave);
         int pos = incl - cnt;
-        const int32_t op_base = (w0 + (lane & (kChunkWords - 1))) * 64 + 16 * (lane >> 4);
+        const int32_t op_base = (w0 + (lane & (cw - 1))) * 64 + (part << cw_log);
         while (bits16) {
             const int b = __builtin_ctz(bits16);
             bits16 &= bits16 - 1;
@@ -411,39 +437,65 @@ __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState 
 
     const int wproc = wave_sum(lc.processed), wkey = wave_max(lc.max_deferred_key);
     if (lane == 0) { s_proc[wave] = wproc; s_maxkey[wave] = wkey; }
-    // the last working block to finish publishes the next level
+    if (threadIdx.x == 0) s_last = 0;
     __syncthreads();
+    // Two-level ticket (groups of blocks, then groups): the last working block publishes the next level.
+    // Everything a block contributed is an atomic performed at the device-coherent level, and queue
+    // entries only have to be visible to the *next launch*, so no cache write-back is needed here.
     if (threadIdx.x == 0) {
         int proc = 0, mk = -1;
         for (int w = 0; w < kLevelWaves; ++w) { proc += s_proc[w]; mk = max(mk, s_maxkey[w]); }
-        if (proc) atomicAdd(&st->processed, proc);
-        if (mk >= 0) atomicMax(&st->max_deferred_key, mk);
-        __threadfence();
-        const int tk = atomicAdd(&st->ticket, 1);
-        if (tk == nwork - 1) {
-            __threadfence();
-            const int tot_proc = load_coherent(&st->processed);
-            const int tot_key = load_coherent(&st->max_deferred_key);
-            const int n_next = load_coherent(&out->n);
+        const int groups = min(kMaxSeg, nwork);
+        const int grp = blockIdx.x & (kMaxSeg - 1);          // groups == kMaxSeg whenever nwork >= kMaxSeg
+        const int gsize = (nwork - grp + kMaxSeg - 1) / kMaxSeg;
+        if (mk >= 0) atomicMax(&ctr->submax[grp].v, mk + 1);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        const u64 tk = atomicAdd(&ctr->subticket[grp].v, ((u64)(uint32_t)proc << 32) | 1u);
+        if ((int)(tk & 0xffffffffu) == gsize - 1) {          // last block of its group
+            const int gproc = (int)(tk >> 32) + proc;
+            const int gmax = load_coherent(&ctr->submax[grp].v);
+            ctr->subticket[grp].v = 0;
+            if (gmax > 0) atomicMax(&st->max_deferred_key1, gmax);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            const u64 tk2 = atomicAdd(&st->ticket, ((u64)(uint32_t)gproc << 32) | 1u);
+            if ((int)(tk2 & 0xffffffffu) == groups - 1) {
+                s_last = 1;
+                s_proc[0] = (int)(tk2 >> 32) + gproc;
+            }
+        }
+    }
+    __syncthreads();
+    if (s_last && threadIdx.x < kWave) {                      // wave 0 of the last block
+        int c = 0;
+        if (lane < qg.S) {
+            c = load_coherent(&ctr->cnt[out_slot][lane].v);
+            if (c > qg.seg_cap) c = qg.seg_cap;
+        }
+        ctr->cnt[in_slot][lane].v = 0;                       // becomes the push target of the next launch
+        const int n_next = wave_sum(c);
+        if (lane == 0) {
+            const int tot_proc = s_proc[0];
+            const int tot_key = load_coherent(&st->max_deferred_key1) - 1;
             st->ticket = 0;
-            st->processed = 0;
-            st->slot[launch_no & 1].n = 0;                  // becomes the push counter of the next launch
             out->level = in.level + 1;
+            out->n = n_next;
             out->deferred_seen = tot_key >= 0;
             out->theta_hi = ranges_left ? in.theta : in.theta_hi;   // [theta, theta_hi) has been scanned
             out->theta = (ranges_left || tot_key >= 0) ? next_theta(in.theta, decay, tot_proc == 0 && n_next == 0, tot_key)
                                                        : in.theta;
             st->tensor_visits += (u64)tot_proc;
             if ((u64)n > st->max_frontier) st->max_frontier = (u64)n;
+            if (trace && in.level < kTraceLevels) trace[in.level] = make_int4(n, tot_proc, in.theta, ranges_left ? in.theta_hi : -1);
         }
     }
 }
 
-hipError_t launch_level(const GraphView &g, TravState *st, int launch_no, void *q0, void *q1, u64 *DB, u64 *M, u64 *K,
-                        int grid_blocks, int queue_cap, int narrow_cap, float decay, hipStream_t s)
+hipError_t launch_level(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
+                        const QueueGeom &qg, u64 *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap, float decay,
+                        int4 *trace, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_level, dim3((unsigned)grid_blocks), dim3(kLevelThreads), 0, s, g, st, launch_no,
-                       static_cast<Entry *>(q0), static_cast<Entry *>(q1), DB, M, K, queue_cap, narrow_cap, decay);
+    hipLaunchKernelGGL(k_level, dim3((unsigned)grid_blocks), dim3(kLevelThreads), 0, s, g, st, ctr, launch_no, q0, q1,
+                       qg, DB, M, K, narrow_cap, decay, trace);
     return hipGetLastError();
 }
 
@@ -454,60 +506,73 @@ hipError_t launch_level(const GraphView &g, TravState *st, int launch_no, void *
 constexpr int kNarrowThreads = 1024;
 constexpr int kNarrowWaves = kNarrowThreads / kWave;
 
-__global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravState *st, int launch_no, Entry *q0,
-                                                            Entry *q1, u64 *DB, u64 *M, u64 *K, int queue_cap,
-                                                            int narrow_cap)
+__global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravState *st, TravCounters *ctr, int launch_no,
+                                                            int32_t *q0, int32_t *q1, QueueGeom qg, u64 *DB, u64 *M,
+                                                            u64 *K, int narrow_cap, int4 *trace)
 {
-    __shared__ Entry s_stage[kNarrowWaves][kStageCap];
+    __shared__ int32_t s_stage[kNarrowWaves][kStageCap];
     __shared__ int s_incl[kNarrowWaves][kWave];
+    __shared__ int s_pref[kMaxSeg + 1];
     __shared__ int s_nout;
 
-    const LevelSlot in = st->slot[launch_no & 1];
-    int level = in.level, n = min(in.n, queue_cap);
+    const int in_slot = launch_no & 1, out_slot = in_slot ^ 1;
+    const LevelSlot in = st->slot[in_slot];
+    int level = in.level;
+    int n = load_segments(ctr->cnt[in_slot], qg, s_pref);
     const bool ranges_left = in.deferred_seen && in.theta_hi > 0;   // then the wide kernel must go on
-    const int wave = threadIdx.x >> 6;
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
     WaveStage ws{&s_stage[wave][0], 0};
     LevelCounters lc{0, -1};
     u64 visits = 0, maxf = 0;
+    bool moved = false;
     while (n > 0 && n <= narrow_cap && !ranges_left) {
         if (threadIdx.x == 0) s_nout = 0;
         __syncthreads();
         const int cur = level & 1;
-        const Entry *qin = cur ? q1 : q0;
-        const Frontier f{cur ? q0 : q1, &s_nout, queue_cap, &st->error};
+        const int32_t *qin = cur ? q1 : q0;
+        const Frontier f{cur ? q0 : q1, &s_nout, qg.seg_cap, &st->error};   // everything goes to segment 0
         for (int base = 0; base < n; base += kNarrowThreads) {
             const int i = base + threadIdx.x;
             const bool valid = i < n;
-            Entry e{0, kNoProducer, 0, 0};
-            if (valid) e = load_entry(qin, i);
+            const int32_t t = valid ? load_item(qin, qg, s_pref, i) : 0;
             // threshold 0: a small frontier is latency bound, so nothing is gained by deferring
-            process_entries(g, valid, e, 0, DB, M, K, &s_incl[wave][0], ws, f, lc);
+            process_entries(g, valid, t, 0, DB, M, K, &s_incl[wave][0], ws, f, lc);
         }
         stage_flush(ws, f);
-        __threadfence();          // queue entries reach the device-coherent level before they are re-read
+        // the block's queue stores must have completed before they are re-read (with cache-bypassing
+        // loads) by other waves of this same block; no other block reads them before the kernel ends
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __syncthreads();
         visits += (u64)n;
         if ((u64)n > maxf) maxf = (u64)n;
-        n = min(s_nout, queue_cap);
+        if (trace && threadIdx.x == 0 && level < kTraceLevels) trace[level] = make_int4(n, n, -1, -1);
+        n = min(s_nout, qg.seg_cap);
         ++level;
-        __syncthreads();          // everyone has read s_nout before it is reset
+        moved = true;
+        // the next frontier lives in segment 0 only
+        if (threadIdx.x <= kMaxSeg) s_pref[threadIdx.x] = threadIdx.x == 0 ? 0 : n;
+        __syncthreads();          // everyone has read s_nout before it is reset; s_pref is in place
     }
-    if (threadIdx.x == 0) {
-        LevelSlot *out = &st->slot[(launch_no + 1) & 1];
-        *out = in;
-        out->level = level;
-        out->n = n;
-        st->slot[launch_no & 1].n = 0;
-        st->tensor_visits += visits;
-        if (maxf > st->max_frontier) st->max_frontier = maxf;
+    if (threadIdx.x < kMaxSeg) {                             // publish the frontier's counters for the next launch
+        const int c = moved ? (lane == 0 ? n : 0) : s_pref[lane + 1] - s_pref[lane];
+        ctr->cnt[out_slot][lane].v = c;
+        ctr->cnt[in_slot][lane].v = 0;
+        if (lane == 0) {
+            LevelSlot *out = &st->slot[out_slot];
+            *out = in;
+            out->level = level;
+            out->n = n;
+            st->tensor_visits += visits;
+            if (maxf > st->max_frontier) st->max_frontier = maxf;
+        }
     }
 }
 
-hipError_t launch_narrow(const GraphView &g, TravState *st, int launch_no, void *q0, void *q1, u64 *DB, u64 *M,
-                         u64 *K, int queue_cap, int narrow_cap, hipStream_t s)
+hipError_t launch_narrow(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
+                         const QueueGeom &qg, u64 *DB, u64 *M, u64 *K, int narrow_cap, int4 *trace, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_narrow, dim3(1), dim3(kNarrowThreads), 0, s, g, st, launch_no, static_cast<Entry *>(q0),
-                       static_cast<Entry *>(q1), DB, M, K, queue_cap, narrow_cap);
+    hipLaunchKernelGGL(k_narrow, dim3(1), dim3(kNarrowThreads), 0, s, g, st, ctr, launch_no, q0, q1, qg, DB, M, K,
+                       narrow_cap, trace);
     return hipGetLastError();
 }
 
@@ -517,7 +582,7 @@ hipError_t launch_narrow(const GraphView &g, TravState *st, int launch_no, void 
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kLevelThreads) void k_fix_sweep(GraphView g, u64 *M, u64 *K, int32_t *changed)
 {
-    __shared__ Entry s_stage[kLevelWaves][kStageCap];
+    __shared__ int32_t s_stage[kLevelWaves][kStageCap];
     __shared__ int s_incl[kLevelWaves][kWave];
     __shared__ int32_t s_sink, s_err;
     const int wave = threadIdx.x >> 6;
