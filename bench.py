@@ -34,6 +34,8 @@ def main():
     ap.add_argument("--recompute-keep", action="store_true",
                     help="run the stand-alone removal-rule pass instead of reusing the traversal's K")
     ap.add_argument("--defer-percent", type=int, default=0, help="traversal schedule knob (0 = library default)")
+    ap.add_argument("--defer-start-shift", type=int, default=0)
+    ap.add_argument("--defer-floor-shift", type=int, default=0)
     ap.add_argument("--generic", action="store_true", help="force the one-launch-per-level traversal")
     ap.add_argument("--trace-levels", action="store_true", help="print the per-level trace of the last step")
     args = ap.parse_args()
@@ -89,7 +91,8 @@ def main():
     buf = d.PruneBuffers(dg, tg.num_sets)
     rowptr, idx = up(tg.tgt_rowptr), up(tg.tgt_idx)
     opts = d.dgn_options(profile=1, recompute_keep=1 if args.recompute_keep else 0,
-                         defer_percent=args.defer_percent, traversal=1 if args.generic else 0)
+                         defer_percent=args.defer_percent, traversal=1 if args.generic else 0,
+                         defer_start_shift=args.defer_start_shift, defer_floor_shift=args.defer_floor_shift)
     st = d.dgn_stats()
     trace = np.zeros((4096, 4), dtype=np.int32)
     if args.trace_levels:

@@ -98,7 +98,9 @@ typedef struct dgn_options {
     int32_t max_queue_entries; /* prune: cap on the frontier queues (0 = one entry per tensor).  A
                                 smaller cap only forces the overflow fix-up path (testing aid);
                                 results do not depend on it */
-    int32_t reserved[2];     /* must be zero */
+    int32_t defer_start_shift; /* prune: the threshold starts at num_ops >> this (0 = default)          */
+    int32_t defer_floor_shift; /* prune: deferral stops once the threshold is below num_ops >> this
+                                (0 = default).  Schedule knobs only: results do not depend on them   */
 } dgn_options;
 
 /* Indices into dgn_stats.phase_ms */

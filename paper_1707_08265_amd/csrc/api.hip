@@ -28,6 +28,8 @@ constexpr int kNarrowCap = 2048;            // frontiers up to this size are wal
 constexpr int kWidePerGroup = 12;           // wide level launches between two single-workgroup launches
 constexpr int kWideGroups = 5;              // groups per batch (one state read-back per batch)
 constexpr int kDefaultDeferPercent = 75;
+constexpr int kDefaultStartShift = 1;       // deferral threshold starts at P >> 1 ...
+constexpr int kDefaultFloorShift = 10;      // ... and stops (drops to 0) below P >> 10
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -195,11 +197,11 @@ int error_bits_to_code(int32_t bits)
 int check_options(const dgn_options *o)
 {
     if (!o) return DGN_OK;
-    for (int i = 0; i < 2; ++i)
-        if (o->reserved[i] != 0) return DGN_ERR_INVALID_ARG;
     if (o->traversal < 0 || o->traversal > 1) return DGN_ERR_INVALID_ARG;
     if (o->defer_percent < 0 || o->defer_percent > 100) return DGN_ERR_INVALID_ARG;
     if (o->max_queue_entries < 0) return DGN_ERR_INVALID_ARG;
+    if (o->defer_start_shift < 0 || o->defer_start_shift > 30) return DGN_ERR_INVALID_ARG;
+    if (o->defer_floor_shift < 0 || o->defer_floor_shift > 30) return DGN_ERR_INVALID_ARG;
     return DGN_OK;
 }
 
@@ -457,10 +459,18 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     DGN_HIP(launch_clear(clr, 5, s));
     if (ev) DGN_HIP(hipEventRecord(ev[1], s));
     // deferral schedule: threshold on the producer id, starting at decay*P and decaying geometrically
-    int defer_percent = options && options->defer_percent ? options->defer_percent : kDefaultDeferPercent;
-    const float decay = defer_percent >= 100 ? 1.0f : (float)defer_percent / 100.0f;
-    const int32_t theta0 = defer_percent >= 100 ? 0 : (int32_t)((double)g->P * decay);
-    DGN_HIP(launch_seed(g->v, num_sets, num_targets, tgt_rowptr, tgt_idx, M, S.state, S.ctr, S.q0, S.qg, theta0, s));
+    const int defer_percent = options && options->defer_percent ? options->defer_percent : kDefaultDeferPercent;
+    const int start_shift = options && options->defer_start_shift ? options->defer_start_shift : kDefaultStartShift;
+    const int floor_shift = options && options->defer_floor_shift ? options->defer_floor_shift : kDefaultFloorShift;
+    Schedule sch{1.0f, 0, 0};
+    if (defer_percent < 100) {
+        sch.decay = (float)defer_percent / 100.0f;
+        sch.theta0 = (int32_t)(g->P >> start_shift);
+        sch.theta_floor = (int32_t)(g->P >> floor_shift);
+        if (sch.theta_floor < 64) sch.theta_floor = 64;
+        if (sch.theta0 < sch.theta_floor) sch.theta0 = 0;
+    }
+    DGN_HIP(launch_seed(g->v, num_sets, num_targets, tgt_rowptr, tgt_idx, M, S.state, S.ctr, S.q0, S.qg, sch.theta0, s));
     if (ev) DGN_HIP(hipEventRecord(ev[2], s));
     launches += 2;
 
@@ -517,7 +527,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     while (!done) {
         for (int r = 0; r < kWideGroups; ++r) {
             for (int i = 0; i < kWidePerGroup; ++i, ++launch_no)
-                DGN_HIP(launch_level(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, grid, narrow_cap, decay, trace, s));
+                DGN_HIP(launch_level(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, grid, narrow_cap, sch, trace, s));
             launches += kWidePerGroup;
             level_launches += kWidePerGroup;
             if (!generic_only) {

@@ -38,7 +38,6 @@ struct GraphView {
 constexpr int32_t kFresh = -1;        // entry not looked up yet
 constexpr int32_t kMulti = -2;        // several producers: (eb, deg) index prod_idx
 constexpr int32_t kNoProducer = -3;   // graph input
-constexpr int32_t kThetaFloor = 64;   // deferral thresholds below this are treated as 0
 
 // One slot of traversal state.  Launch number e reads slot e&1 and its finishing block writes
 // slot (e+1)&1, so a block of launch e that starts late never sees state of the next level.
@@ -74,6 +73,9 @@ struct TravCounters {
     SegTicket subticket[kMaxSeg];    // first-level tickets
     SegCounter submax[kMaxSeg];      // per-group 1 + largest deferred operator id
 };
+// Deferral schedule: the threshold starts at theta0, is multiplied by decay after every wide level and
+// drops to 0 (nothing deferred any more) once it falls below theta_floor.
+struct Schedule { float decay; int32_t theta0; int32_t theta_floor; };
 // A frontier queue: S segments (power of two, <= kMaxSeg) of seg_cap entries each.
 struct QueueGeom { int32_t S; int32_t seg_cap; };
 static_assert(sizeof(TravState) == 128, "TravState is read back as 128 bytes");
@@ -157,8 +159,8 @@ hipError_t launch_seed(const GraphView &g, int32_t Q, int64_t num_targets, const
 // One wide level (whole chip); a frontier of at most narrow_cap entries is left to launch_narrow unless
 // deferred operators are waiting.  DB: deferred-operator bitmap, one bit per operator.
 hipError_t launch_level(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
-                        const QueueGeom &qg, u64 *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap, float decay,
-                        int4 *trace, hipStream_t s);
+                        const QueueGeom &qg, u64 *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
+                        const Schedule &sch, int4 *trace, hipStream_t s);
 // One workgroup runs level after level while 0 < frontier <= narrow_cap and nothing is deferred.
 hipError_t launch_narrow(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
                          const QueueGeom &qg, u64 *DB, u64 *M, u64 *K, int narrow_cap, int4 *trace, hipStream_t s);

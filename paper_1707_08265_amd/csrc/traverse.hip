@@ -259,13 +259,15 @@ __device__ __forceinline__ void process_entries(const GraphView &g, bool valid, 
     int4 pi = make_int4(kNoProducer, 0, 0, 0);
     if (valid) {
         pi = g.pinfo[t];                                    // (o, eb, deg): producer record
+        const u64 mt = load_coherent(&M[t]);                // (I4): everything t holds right now (issued
+                                                            // together with the record: no dependency)
         if (pi.x >= 0 && pi.x < theta) {                    // (I5): wait for the threshold to pass o
             const u64 ob = (u64)1 << (pi.x & 63);
             if ((load_coherent(&DB[pi.x >> 6]) & ob) == 0) atomicOr(&DB[pi.x >> 6], ob);
             lc.max_deferred_key = max(lc.max_deferred_key, pi.x);
         } else if (pi.x != kNoProducer) {
             active = true;
-            m = load_coherent(&M[t]);                       // (I4): everything t holds right now
+            m = mt;
             lc.processed++;
         }
     }
@@ -318,23 +320,20 @@ __device__ __forceinline__ bool process_ops(const GraphView &g, bool valid, int3
         if (r < n_out) k |= load_coherent(&M[g.out_idx[ob + r]]);
     u64 nb = 0;
     if (valid && k) {
-        const u64 cur = load_coherent(&K[o]);
-        if (k & ~cur) {
-            const u64 old = atomicOr(&K[o], k);             // (I1)
-            nb = k & ~old;
-        }
+        const u64 old = atomicOr(&K[o], k);                 // (I1)
+        nb = k & ~old;
     }
     expand_edges(g, ib, nb ? n_in : 0, nb, M, s_incl, ws, f);
     return nb != 0;
 }
 
-__device__ __forceinline__ int32_t next_theta(int32_t theta, float decay, bool idle, int max_deferred_key)
+__device__ __forceinline__ int32_t next_theta(int32_t theta, const Schedule &sch, bool idle, int max_deferred_key)
 {
     if (theta <= 0) return 0;
     float base = (float)theta;
     if (idle && max_deferred_key >= 0 && max_deferred_key + 1 < theta) base = (float)max_deferred_key + 1.0f;
-    const int32_t t = (int32_t)(base * decay);
-    return t < kThetaFloor ? 0 : t;
+    const int32_t t = (int32_t)(base * sch.decay);
+    return t < sch.theta_floor ? 0 : t;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -346,7 +345,7 @@ constexpr int kChunkOps = 16 * 64;                 // at most 16 deferred-bitmap
 
 __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState *st, TravCounters *ctr, int launch_no,
                                                           int32_t *q0, int32_t *q1, QueueGeom qg, u64 *DB, u64 *M,
-                                                          u64 *K, int narrow_cap, float decay, int4 *trace)
+                                                          u64 *K, int narrow_cap, Schedule sch, int4 *trace)
 {
     __shared__ int32_t s_stage[kLevelWaves][kStageCap];
     __shared__ int s_incl[kLevelWaves][kWave];
@@ -359,8 +358,12 @@ __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState 
     const LevelSlot in = st->slot[in_slot];
     LevelSlot *out = &st->slot[out_slot];
     const int lane = lane_id(), wave = threadIdx.x >> 6;
-    const int n = load_segments(ctr->cnt[in_slot], qg, s_pref);
     const bool ranges_left = in.deferred_seen && in.theta_hi > 0;
+    if (launch_no > 0 && in.n == 0 && !ranges_left) {       // traversal finished: carry the state on, cheaply
+        if (blockIdx.x == 0 && threadIdx.x == 0) *out = in;
+        return;
+    }
+    const int n = load_segments(ctr->cnt[in_slot], qg, s_pref);
     if (n <= narrow_cap && !ranges_left) {   // finished, or small enough for the single-workgroup kernel
         if (blockIdx.x == 0 && threadIdx.x < kMaxSeg) {     // hand the frontier (its counters) to the next launch
             const int c = s_pref[lane + 1] - s_pref[lane];
@@ -382,9 +385,17 @@ __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState 
     while (cw_log < 4 && ((w_hi - w_lo) >> cw_log) > (int)gridDim.x * kLevelWaves) ++cw_log;
     const int cw = 1 << cw_log;
     const int chunks = (w_hi - w_lo + cw - 1) >> cw_log;
-    const int need = max((n + kLevelThreads - 1) / kLevelThreads, (chunks + kLevelWaves - 1) / kLevelWaves);
-    const int nwork = max(1, min((int)gridDim.x, need));
+    // Frontier entries and range chunks go to different blocks when the grid has room for both, so
+    // the two dependent-access chains of a small level overlap instead of following each other.
+    const int nb_e = (n + kLevelThreads - 1) / kLevelThreads;
+    const int nb_s = (chunks + kLevelWaves - 1) / kLevelWaves;
+    const bool split = nb_e + nb_s <= (int)gridDim.x;
+    const int nwork = split ? max(1, nb_e + nb_s) : (int)gridDim.x;
     if ((int)blockIdx.x >= nwork) return;
+    const bool do_entries = !split || (int)blockIdx.x < nb_e;
+    const bool do_scan = !split || (int)blockIdx.x >= nb_e;
+    const int e_blocks = split ? nb_e : nwork, e_first = blockIdx.x;
+    const int s_blocks = split ? nb_s : nwork, s_first = split ? (int)blockIdx.x - nb_e : (int)blockIdx.x;
 
     const int cur = in.level & 1;
     const int32_t *qin = cur ? q1 : q0;
@@ -394,14 +405,14 @@ __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState 
 
     WaveStage ws{&s_stage[wave][0], 0};
     LevelCounters lc{0, -1};
-    for (int base = blockIdx.x * kLevelThreads; base < n; base += nwork * kLevelThreads) {
+    for (int base = e_first * kLevelThreads; do_entries && base < n; base += e_blocks * kLevelThreads) {
         const int i = base + threadIdx.x;
         const bool valid = i < n;
         const int32_t t = valid ? load_item(qin, qg, s_pref, i) : 0;
         process_entries(g, valid, t, in.theta, DB, M, K, &s_incl[wave][0], ws, f, lc);
     }
     // expand the bitmap words of the newly opened range into dense operator lists, 64 per step
-    for (int c = blockIdx.x * kLevelWaves + wave; c < chunks; c += nwork * kLevelWaves) {
+    for (int c = s_first * kLevelWaves + wave; do_scan && c < chunks; c += s_blocks * kLevelWaves) {
         const int w0 = w_lo + (c << cw_log);
         u64 word = 0;
         if (lane < cw && w0 + lane < w_hi) {
@@ -446,15 +457,22 @@ __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState 
         int proc = 0, mk = -1;
         for (int w = 0; w < kLevelWaves; ++w) { proc += s_proc[w]; mk = max(mk, s_maxkey[w]); }
         const int groups = min(kMaxSeg, nwork);
-        const int grp = blockIdx.x & (kMaxSeg - 1);          // groups == kMaxSeg whenever nwork >= kMaxSeg
-        const int gsize = (nwork - grp + kMaxSeg - 1) / kMaxSeg;
-        if (mk >= 0) atomicMax(&ctr->submax[grp].v, mk + 1);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        const u64 tk = atomicAdd(&ctr->subticket[grp].v, ((u64)(uint32_t)proc << 32) | 1u);
-        if ((int)(tk & 0xffffffffu) == gsize - 1) {          // last block of its group
-            const int gproc = (int)(tk >> 32) + proc;
-            const int gmax = load_coherent(&ctr->submax[grp].v);
-            ctr->subticket[grp].v = 0;
+        int gproc = proc, gmax = mk + 1;
+        bool group_done = true;
+        if (nwork > kMaxSeg) {                               // first level: blocks of one group
+            const int grp = blockIdx.x & (kMaxSeg - 1);
+            const int gsize = (nwork - grp + kMaxSeg - 1) / kMaxSeg;
+            if (mk >= 0) atomicMax(&ctr->submax[grp].v, mk + 1);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            const u64 tk = atomicAdd(&ctr->subticket[grp].v, ((u64)(uint32_t)proc << 32) | 1u);
+            group_done = (int)(tk & 0xffffffffu) == gsize - 1;
+            if (group_done) {
+                gproc = (int)(tk >> 32) + proc;
+                gmax = load_coherent(&ctr->submax[grp].v);
+                ctr->subticket[grp].v = 0;
+            }
+        }
+        if (group_done) {                                    // second level: one ticket per group
             if (gmax > 0) atomicMax(&st->max_deferred_key1, gmax);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             const u64 tk2 = atomicAdd(&st->ticket, ((u64)(uint32_t)gproc << 32) | 1u);
@@ -481,7 +499,7 @@ __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState 
             out->n = n_next;
             out->deferred_seen = tot_key >= 0;
             out->theta_hi = ranges_left ? in.theta : in.theta_hi;   // [theta, theta_hi) has been scanned
-            out->theta = (ranges_left || tot_key >= 0) ? next_theta(in.theta, decay, tot_proc == 0 && n_next == 0, tot_key)
+            out->theta = (ranges_left || tot_key >= 0) ? next_theta(in.theta, sch, tot_proc == 0 && n_next == 0, tot_key)
                                                        : in.theta;
             st->tensor_visits += (u64)tot_proc;
             if ((u64)n > st->max_frontier) st->max_frontier = (u64)n;
@@ -491,11 +509,11 @@ __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState 
 }
 
 hipError_t launch_level(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
-                        const QueueGeom &qg, u64 *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap, float decay,
-                        int4 *trace, hipStream_t s)
+                        const QueueGeom &qg, u64 *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
+                        const Schedule &sch, int4 *trace, hipStream_t s)
 {
     hipLaunchKernelGGL(k_level, dim3((unsigned)grid_blocks), dim3(kLevelThreads), 0, s, g, st, ctr, launch_no, q0, q1,
-                       qg, DB, M, K, narrow_cap, decay, trace);
+                       qg, DB, M, K, narrow_cap, sch, trace);
     return hipGetLastError();
 }
 

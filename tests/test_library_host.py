@@ -77,8 +77,7 @@ def test_build_rejects_bad_arguments_before_any_device_work(d):
     desc2 = d.make_coo_desc(4, 8, None, None, None, None, nnz_in=3, nnz_out=0)                  # edges but no arrays
     rc, gb2, sb2 = d.dgn_graph_build_workspace(desc2)
     assert d.dgn_graph_build(desc2, 256, gb2, 512, sb2, stream=0)[0] == d.DGN_ERR_NULL_PTR
-    opts = d.dgn_options()
-    opts.reserved[1] = 1
+    opts = d.dgn_options(defer_percent=101)
     assert d.dgn_graph_build(desc, 256, gb, 512, sb, options=opts, stream=0)[0] == d.DGN_ERR_INVALID_ARG
 
 
