@@ -125,6 +125,9 @@ struct PruneScratch {
     u64 *opbits;
     int32_t *block_counts;
     int4 *trace;            // per-level trace records (profiling only)
+    int64_t *pq_part;       // replicated per-set counters (few graphs only), NULL otherwise
+    int pq_replicas;
+    size_t pq_part_bytes;
     size_t db_bytes, opbits_bytes;
     size_t bytes;
 };
@@ -143,7 +146,7 @@ QueueGeom queue_geometry(int64_t T, int64_t max_entries)
     return QueueGeom{S, (int32_t)seg};
 }
 
-PruneScratch prune_scratch(void *mem, int64_t P, int64_t T, int64_t max_entries)
+PruneScratch prune_scratch(void *mem, int64_t P, int64_t T, int32_t G, int64_t max_entries)
 {
     Carver c(mem);
     PruneScratch S{};
@@ -160,6 +163,12 @@ PruneScratch prune_scratch(void *mem, int64_t P, int64_t T, int64_t max_entries)
     S.opbits_bytes = obw * 8;
     S.block_counts = c.take<int32_t>((P + kCompactTile - 1) / kCompactTile + 1);
     S.trace = c.take<int4>(kTraceLevels);
+    // with fewer than 64 graphs the 64*G per-set counters would be hot words: replicate them
+    S.pq_replicas = 1;
+    while (S.pq_replicas * 2 * (int64_t)G <= 64) S.pq_replicas *= 2;
+    S.pq_part_bytes = S.pq_replicas > 1 ? sizeof(int64_t) * 64 * (size_t)G * S.pq_replicas * kPqStride : 0;
+    S.pq_part = c.take<int64_t>(S.pq_part_bytes / sizeof(int64_t));
+    if (S.pq_replicas == 1) S.pq_part = nullptr;
     S.bytes = c.off;
     return S;
 }
@@ -418,7 +427,7 @@ int dgn_prune_workspace(const dgn_graph *g, int32_t num_sets, size_t *scratch_by
 {
     if (!g || !scratch_bytes) return DGN_ERR_NULL_PTR;
     if (num_sets < 1 || num_sets > DGN_MAX_SETS) return DGN_ERR_TOO_MANY_SETS;
-    *scratch_bytes = prune_scratch(nullptr, g->P, g->T, 0).bytes;
+    *scratch_bytes = prune_scratch(nullptr, g->P, g->T, g->G, 0).bytes;
     return DGN_OK;
 }
 
@@ -435,7 +444,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     if (rc) return rc;
     if (!tgt_rowptr || (num_targets > 0 && !tgt_idx) || !kept_count || !scratch) return DGN_ERR_NULL_PTR;
     if ((g->T > 0 && !tensor_mask) || (g->P > 0 && (!op_mask || !kept_ops))) return DGN_ERR_NULL_PTR;
-    const PruneScratch S = prune_scratch(scratch, g->P, g->T, options ? options->max_queue_entries : 0);
+    const PruneScratch S = prune_scratch(scratch, g->P, g->T, g->G, options ? options->max_queue_entries : 0);
     if (scratch_bytes < S.bytes) return DGN_ERR_WORKSPACE_TOO_SMALL;
     if (((uintptr_t)scratch | (uintptr_t)tensor_mask | (uintptr_t)op_mask | (uintptr_t)kept_masks |
          (uintptr_t)kept_count | (uintptr_t)per_query_count) & 7)
@@ -454,9 +463,10 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     }
 
     // nothing marked yet: clear outputs, frontier bitmaps and traversal state
-    FillRegion clr[5] = {{M, (size_t)g->T * 8}, {K, (size_t)g->P * 8}, {S.DB, S.db_bytes},
-                         {S.state, 256 + sizeof(TravCounters)}, {per_query_count, pq_bytes}};
-    DGN_HIP(launch_clear(clr, 5, s));
+    FillRegion clr[6] = {{M, (size_t)g->T * 8}, {K, (size_t)g->P * 8}, {S.DB, S.db_bytes},
+                         {S.state, 256 + sizeof(TravCounters)}, {per_query_count, pq_bytes},
+                         {S.pq_part, per_query_count ? S.pq_part_bytes : 0}};
+    DGN_HIP(launch_clear(clr, 6, s));
     if (ev) DGN_HIP(hipEventRecord(ev[1], s));
     // deferral schedule: threshold on the producer id, starting at decay*P and decaying geometrically
     const int defer_percent = options && options->defer_percent ? options->defer_percent : kDefaultDeferPercent;
@@ -485,6 +495,8 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     ca.per_query_count = per_query_count;
     ca.opbits = S.opbits;
     ca.block_counts = S.block_counts;
+    ca.pq_part = S.pq_part;
+    ca.pq_replicas = S.pq_replicas;
     ca.from_tensor_mask = options && options->recompute_keep;
 
     void *pin = nullptr;
@@ -563,8 +575,8 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     }
     if (!compacted) {
         if (pq_bytes) {
-            FillRegion pq[1] = {{per_query_count, pq_bytes}};
-            DGN_HIP(launch_clear(pq, 1, s));
+            FillRegion pq[2] = {{per_query_count, pq_bytes}, {S.pq_part, S.pq_part_bytes}};
+            DGN_HIP(launch_clear(pq, 2, s));
             ++launches;
         }
         if (ev) DGN_HIP(hipEventRecord(ev[3], s));
@@ -604,15 +616,15 @@ int dgn_keep_compact(const dgn_graph *g, const uint64_t *tensor_mask_in, uint64_
     if (!g) return DGN_ERR_NULL_PTR;
     if (!kept_count || !scratch) return DGN_ERR_NULL_PTR;
     if ((g->T > 0 && !tensor_mask_in) || (g->P > 0 && (!op_mask || !kept_ops))) return DGN_ERR_NULL_PTR;
-    const PruneScratch S = prune_scratch(scratch, g->P, g->T, 0);
+    const PruneScratch S = prune_scratch(scratch, g->P, g->T, g->G, 0);
     if (scratch_bytes < S.bytes) return DGN_ERR_WORKSPACE_TOO_SMALL;
     if (((uintptr_t)scratch | (uintptr_t)tensor_mask_in | (uintptr_t)op_mask | (uintptr_t)kept_masks |
          (uintptr_t)kept_count | (uintptr_t)per_query_count) & 7)
         return DGN_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const size_t pq_bytes = per_query_count ? sizeof(int64_t) * 64 * (size_t)(g->G > 1 ? g->G : 1) : 0;
-    FillRegion pq[1] = {{per_query_count, pq_bytes}};
-    DGN_HIP(launch_clear(pq, 1, s));
+    FillRegion pq[2] = {{per_query_count, pq_bytes}, {S.pq_part, per_query_count ? S.pq_part_bytes : 0}};
+    DGN_HIP(launch_clear(pq, 2, s));
     CompactArgs ca{};
     ca.g = g->v;
     ca.M = reinterpret_cast<const u64 *>(tensor_mask_in);
@@ -624,6 +636,8 @@ int dgn_keep_compact(const dgn_graph *g, const uint64_t *tensor_mask_in, uint64_
     ca.per_query_count = per_query_count;
     ca.opbits = S.opbits;
     ca.block_counts = S.block_counts;
+    ca.pq_part = S.pq_part;
+    ca.pq_replicas = S.pq_replicas;
     ca.from_tensor_mask = true;
     DGN_HIP(launch_keep_compact(ca, s));
     return DGN_OK;

@@ -168,6 +168,7 @@ hipError_t launch_narrow(const GraphView &g, TravState *st, TravCounters *ctr, i
 hipError_t launch_fix_sweep(const GraphView &g, u64 *M, u64 *K, int32_t *changed, int grid_blocks, hipStream_t s);
 
 // Removal rule + compaction.
+constexpr int kPqStride = 8;         // int64 words between two replicated per-set counters (64 bytes)
 constexpr int kCompactTile = 2048;   // operators per workgroup in the count / scatter passes
 struct CompactArgs {
     GraphView g;
@@ -178,6 +179,8 @@ struct CompactArgs {
     u64 *kept_masks;         // may be NULL
     int64_t *kept_count;
     int64_t *per_query_count;   // may be NULL
+    int64_t *pq_part;           // [pq_replicas][G*64][kPqStride] zeroed scratch, or NULL: add straight into per_query_count
+    int pq_replicas;            // power of two
     u64 *opbits;             // [ceil(P/64)] scratch
     int32_t *block_counts;   // [num_tiles + 1] scratch
     bool from_tensor_mask;   // K := OR M[out] (true) or read K as accumulated by the traversal

@@ -36,6 +36,15 @@ __global__ __launch_bounds__(kCThreads) void k_keep_count(CompactArgs a)
     const int64_t tile_base = (int64_t)blockIdx.x * kCompactTile;
     const bool batched = g.num_graphs > 1;
 
+    // Per-set counters are hot words (every wave of the grid adds to the same 64 of them when there is
+    // one graph), so waves add into one of pq_replicas private copies that a tiny kernel sums up later.
+    int64_t *pq = a.per_query_count;
+    int pqs = 1;                  // replica counters sit 64 bytes apart (no two hot words in one line half)
+    if (pq && a.pq_part) {
+        pqs = kPqStride;
+        pq = a.pq_part + (int64_t)((blockIdx.x * kCWaves + wave) & (a.pq_replicas - 1)) * 64 * g.num_graphs * kPqStride;
+    }
+
     int kept = 0;                 // wave-uniform
     u64 qcount = 0;               // lane q: operators of the current graph whose K has bit q
     int cur_graph = 0;
@@ -77,11 +86,11 @@ __global__ __launch_bounds__(kCThreads) void k_keep_count(CompactArgs a)
         if (lane == 0 && o0 < g.num_ops) a.opbits[o0 >> 6] = word;
         kept += __popcll(word);
 
-        if (a.per_query_count && word) {
+        if (pq && word) {
             const int64_t o_last = min(o0 + kWave, (int64_t)g.num_ops) - 1;
             if (batched && (o0 < g_lo || o_last >= g_hi)) {
                 // this wave-round leaves the current graph: flush, then either move on or go lane by lane
-                if (qcount) atomicAdd((u64 *)&a.per_query_count[(int64_t)cur_graph * 64 + lane], qcount);
+                if (qcount) atomicAdd((u64 *)&pq[((int64_t)cur_graph * 64 + lane) * pqs], qcount);
                 qcount = 0;
                 const int ga = graph_of(g.op_off, g.num_graphs, o0);
                 const int gb = graph_of(g.op_off, g.num_graphs, o_last);
@@ -96,7 +105,7 @@ __global__ __launch_bounds__(kCThreads) void k_keep_count(CompactArgs a)
                         while (kk) {
                             const int q = __builtin_ctzll(kk);
                             kk &= kk - 1;
-                            atomicAdd((u64 *)&a.per_query_count[(int64_t)gi * 64 + q], (u64)1);
+                            atomicAdd((u64 *)&pq[((int64_t)gi * 64 + q) * pqs], (u64)1);
                         }
                     }
                     continue;      // wave-uniform: every lane of the round takes this path
@@ -111,8 +120,7 @@ __global__ __launch_bounds__(kCThreads) void k_keep_count(CompactArgs a)
             }
         }
     }
-    if (a.per_query_count && qcount)
-        atomicAdd((u64 *)&a.per_query_count[(int64_t)cur_graph * 64 + lane], qcount);
+    if (pq && qcount) atomicAdd((u64 *)&pq[((int64_t)cur_graph * 64 + lane) * pqs], qcount);
 
     if (lane == 0) s_wcount[wave] = kept;
     __syncthreads();
@@ -122,6 +130,17 @@ __global__ __launch_bounds__(kCThreads) void k_keep_count(CompactArgs a)
         for (int w = 0; w < kCWaves; ++w) tot += s_wcount[w];
         a.block_counts[blockIdx.x] = tot;
     }
+}
+
+// per_query_count[i] = sum over the replicas of pq_part[r][i]
+__global__ __launch_bounds__(256) void k_reduce_pq(CompactArgs a)
+{
+    const int n = 64 * a.g.num_graphs;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    int64_t sum = 0;
+    for (int r = 0; r < a.pq_replicas; ++r) sum += a.pq_part[((int64_t)r * n + i) * kPqStride];
+    a.per_query_count[i] = sum;
 }
 
 // Single workgroup: exclusive scan of the tile counts in place, total -> counts[m] and kept_count[0].
@@ -216,6 +235,8 @@ hipError_t launch_keep_compact(const CompactArgs &a, hipStream_t s, hipEvent_t *
         else
             hipLaunchKernelGGL(k_keep_count<false>, dim3((unsigned)tiles), dim3(kCThreads), 0, s, a);
     }
+    if (a.per_query_count && a.pq_part)
+        hipLaunchKernelGGL(k_reduce_pq, dim3((unsigned)((64 * a.g.num_graphs + 255) / 256)), dim3(256), 0, s, a);
     if (ev) (void)hipEventRecord(ev[0], s);
     hipLaunchKernelGGL(k_scan_tiles, dim3(1), dim3(1024), 0, s, a.block_counts, tiles, a.kept_count);
     if (ev) (void)hipEventRecord(ev[1], s);
