@@ -24,9 +24,10 @@ inline int hip_fail(hipError_t e)
     } while (0)
 
 constexpr int64_t kMaxCount = 2147483646;   // counts must stay below 2^31 - 1
-constexpr int kNarrowCap = 2048;            // frontiers up to this size are walked by one workgroup
+constexpr int kNarrowCap = 4096;            // frontiers up to this size are walked by one workgroup
 constexpr int kWidePerGroup = 12;           // wide level launches between two single-workgroup launches
-constexpr int kWideGroups = 5;              // groups per batch (one state read-back per batch)
+constexpr int kWideGroupsFirst = 3;         // groups in the first batch (one state read-back per batch) ...
+constexpr int kWideGroups = 6;              // ... and in the following ones
 constexpr int kDefaultDeferPercent = 75;
 constexpr int kDefaultStartShift = 1;       // deferral threshold starts at P >> 1 ...
 constexpr int kDefaultFloorShift = 10;      // ... and stops (drops to 0) below P >> 10
@@ -537,7 +538,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     }
     bool first = true;
     while (!done) {
-        for (int r = 0; r < kWideGroups; ++r) {
+        for (int r = 0; r < (first ? kWideGroupsFirst : kWideGroups); ++r) {
             for (int i = 0; i < kWidePerGroup; ++i, ++launch_no)
                 DGN_HIP(launch_level(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, grid, narrow_cap, sch, trace, s));
             launches += kWidePerGroup;

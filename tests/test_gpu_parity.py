@@ -221,3 +221,52 @@ def test_schedule_knobs_do_not_change_results(dgn, oracle, k, scale):
         st = dgn.dgn_stats()
         _, _, out = gpu_prune(dgn, g, tg, stats=st, **knobs)
         assert_same(out, r, f"cfg{k} {knobs}")
+
+
+# ---- the workloads at their full sizes, in the launch configuration bench.py times ---------------
+def _full_size_check(dgn, oracle, k, sampled_graphs=None):
+    import torch
+    g, tg = gg.config(k, 1.0)
+    print(f"config {k} full size: P={g.num_ops} T={g.num_tensors} E={g.nnz_in}+{g.nnz_out}", flush=True)
+    dg, buf, out = gpu_prune(dgn, g, tg)
+    del dg, buf
+    torch.cuda.empty_cache()
+    adj = oracle.build_adjacency(g.num_ops, g.num_tensors, g.in_op, g.in_tensor, g.out_op, g.out_tensor)
+    # (1) the O(E) fixed-point certificate proves M and K as a whole (unique solution on a DAG)
+    S = oracle.seed_masks(g.num_tensors, tg.num_sets, tg.tgt_rowptr, tg.tgt_idx)
+    assert oracle.certificate(adj, S, out["tensor_mask"], out["op_mask"]) == 0
+    # (2) properties of the compacted outputs that hold at any size
+    assert np.array_equal(out["op_flag"], (out["op_mask"] != 0).astype(np.uint8))
+    assert np.array_equal(out["kept_ops"], np.nonzero(out["op_mask"])[0].astype(np.int32))
+    assert np.array_equal(out["kept_masks"], out["op_mask"][out["kept_ops"]])
+    assert out["kept_count"][0] == len(out["kept_ops"])
+    if sampled_graphs is None:
+        # (3) element by element against Algorithm 1 itself
+        r = oracle.forward_prune(adj, tg.num_sets, tg.tgt_rowptr, tg.tgt_idx, g.num_graphs, g.graph_op_offsets)
+        assert_same(out, r, f"cfg{k} full size")
+    else:
+        # (3') Algorithm 1 on sampled graphs of the packed batch, one by one
+        Q = tg.num_sets
+        for gi in sampled_graphs:
+            one = gg.layered(20000, gg.BASE_SEED + 4000 + gi)
+            t1 = gg.targets_tail(one, gg.BASE_SEED + 4000 + gi, Q, 4, 4, 0.10)
+            _, r1 = oracle_prune(oracle, one, t1)
+            ta, tb = g.graph_tensor_offsets[gi], g.graph_tensor_offsets[gi + 1]
+            oa, ob = g.graph_op_offsets[gi], g.graph_op_offsets[gi + 1]
+            assert np.array_equal(out["tensor_mask"][ta:tb], r1.tensor_mask), gi
+            assert np.array_equal(out["op_mask"][oa:ob], r1.op_mask), gi
+            assert np.array_equal(out["per_query_count"][gi * 64:(gi + 1) * 64], r1.per_query_count), gi
+            a, b = out["kept_count"][1 + gi], out["kept_count"][2 + gi]
+            assert np.array_equal(out["kept_ops"][a:b] - oa, r1.kept_ops), gi
+
+
+def test_full_size_config2_unrolled_rnn(dgn, oracle):
+    _full_size_check(dgn, oracle, 2)
+
+
+def test_full_size_config3_power_law_50m(dgn, oracle):
+    _full_size_check(dgn, oracle, 3)
+
+
+def test_full_size_config4_packed_batch(dgn, oracle):
+    _full_size_check(dgn, oracle, 4, sampled_graphs=[0, 1, 777, 2048, 4095])
