@@ -24,10 +24,12 @@ inline int hip_fail(hipError_t e)
     } while (0)
 
 constexpr int64_t kMaxCount = 2147483646;   // counts must stay below 2^31 - 1
-constexpr int kNarrowCap = 4096;            // frontiers up to this size are walked by one workgroup
+constexpr int kNarrowCap = 3072;            // frontiers up to this size are walked by one workgroup
 constexpr int kWidePerGroup = 12;           // wide level launches between two single-workgroup launches
 constexpr int kWideGroupsFirst = 3;         // groups in the first batch (one state read-back per batch) ...
 constexpr int kWideGroups = 6;              // ... and in the following ones
+constexpr int kSweepMinGraphs = 64;         // packed batches with at least this many graphs ...
+constexpr int64_t kSweepMaxGraphOps = 1 << 18;   // ... none larger than this use the per-graph sweep
 constexpr int kDefaultDeferPercent = 75;
 constexpr int kDefaultStartShift = 1;       // deferral threshold starts at P >> 1 ...
 constexpr int kDefaultFloorShift = 10;      // ... and stops (drops to 0) below P >> 10
@@ -222,6 +224,8 @@ struct dgn_graph {
     int64_t P, T, Ein, Eout;
     int32_t G;
     int num_cus;
+    bool topological;       // operator ids verified to be a topological order at build time
+    int64_t max_graph_ops;  // largest graph of a packed batch (P for a single graph)
 };
 
 namespace {
@@ -237,14 +241,25 @@ int finish_build(dgn_graph *h, const GraphLayout &L, const int64_t *op_off_host,
         h->v.t_off = L.t_off;
         DGN_HIP(launch_check_graph_ranges(h->v, status, s));
     }
-    if (options && options->validate) DGN_HIP(launch_check_topological(h->v, status, s));
+    // the topological precondition is always checked (schedules that rely on it are only chosen when it
+    // holds); it is an error only when the caller asked for validation
+    DGN_HIP(launch_check_topological(h->v, status, s));
     void *pin = nullptr;
     int rc = pinned_buffer(&pin);
     if (rc) return rc;
     DGN_HIP(hipMemcpyAsync(pin, status, sizeof(int32_t), hipMemcpyDeviceToHost, s));
     DGN_HIP(hipStreamSynchronize(s));
-    rc = error_bits_to_code(*static_cast<int32_t *>(pin));
+    int32_t bits = *static_cast<int32_t *>(pin);
+    h->topological = (bits & kErrTopo) == 0;
+    if (!(options && options->validate)) bits &= ~kErrTopo;
+    rc = error_bits_to_code(bits);
     if (rc) return rc;
+    h->max_graph_ops = h->P;
+    if (h->G > 1) {
+        h->max_graph_ops = 0;
+        for (int32_t i = 0; i < h->G; ++i)
+            if (op_off_host[i + 1] - op_off_host[i] > h->max_graph_ops) h->max_graph_ops = op_off_host[i + 1] - op_off_host[i];
+    }
     int dev = 0;
     hipDeviceProp_t prop;
     DGN_HIP(hipGetDevice(&dev));
@@ -481,7 +496,10 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
         if (sch.theta_floor < 64) sch.theta_floor = 64;
         if (sch.theta0 < sch.theta_floor) sch.theta0 = 0;
     }
-    DGN_HIP(launch_seed(g->v, num_sets, num_targets, tgt_rowptr, tgt_idx, M, S.state, S.ctr, S.q0, S.qg, sch.theta0, s));
+    const bool sweep = !(options && options->traversal == 1) && g->G >= kSweepMinGraphs && g->topological &&
+                       g->max_graph_ops <= kSweepMaxGraphOps;
+    DGN_HIP(launch_seed(g->v, num_sets, num_targets, tgt_rowptr, tgt_idx, M, S.state, S.ctr, sweep ? nullptr : S.q0, S.qg,
+                        sch.theta0, s));
     if (ev) DGN_HIP(hipEventRecord(ev[2], s));
     launches += 2;
 
@@ -504,6 +522,33 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     rc = pinned_buffer(&pin);
     if (rc) return rc;
     const TravState *hst = static_cast<const TravState *>(pin);
+
+    // Packed batch of many small graphs in topological order: one wave sweeps each graph once (see
+    // k_sweep_graphs); no frontier, no level loop, per-set counts come out of the sweep itself.
+    if (sweep) {
+        DGN_HIP(launch_sweep_graphs(g->v, M, K, ca.from_tensor_mask ? nullptr : per_query_count, s));
+        ++launches;
+        if (ev) DGN_HIP(hipEventRecord(ev[3], s));
+        if (!ca.from_tensor_mask) ca.per_query_count = nullptr;   // already written by the sweep
+        DGN_HIP(launch_keep_compact(ca, s, ev ? ev + 4 : nullptr));
+        launches += 3 + (g->G > 1);
+        DGN_HIP(hipMemcpyAsync(pin, S.state, sizeof(TravState), hipMemcpyDeviceToHost, s));
+        DGN_HIP(hipStreamSynchronize(s));
+        if (stats) {
+            int32_t *user_trace = stats->level_trace;
+            const int64_t user_cap = stats->level_trace_cap;
+            memset(stats, 0, sizeof(*stats));
+            stats->level_trace = user_trace;
+            stats->level_trace_cap = user_cap;
+            stats->launches = launches;
+            stats->tensor_visits = g->P;
+            if (ev) {
+                for (int i = 0; i < 6; ++i) DGN_HIP(hipEventElapsedTime(&stats->phase_ms[i], ev[i], ev[i + 1]));
+                DGN_HIP(hipEventElapsedTime(&stats->phase_ms[DGN_PHASE_TOTAL], ev[0], ev[6]));
+            }
+        }
+        return error_bits_to_code(hst->error & ~kErrOverflow);
+    }
 
     // Level loop.  The number of levels depends on the data, so the host enqueues kernels ahead and
     // reads the 64-byte state back at a few points:

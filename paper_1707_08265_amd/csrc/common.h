@@ -115,6 +115,26 @@ __device__ __forceinline__ u64 wave_or(u64 v)
 }
 __device__ __forceinline__ u64 shfl64(u64 v, int src) { return (u64)__shfl((long long)v, src, kWave); }
 
+// Lanes hold 64-bit rows of a 64x64 bit matrix (row = lane); returns its transpose (lane q receives
+// bit q of every lane's word, bit i coming from lane i).  Six butterfly steps.
+template <int J>
+__device__ __forceinline__ u64 transpose_step(u64 x, u64 lo_mask /* bit positions whose index has bit J clear */)
+{
+    const u64 other = (u64)__shfl_xor((long long)x, J, kWave);
+    return (lane_id() & J) == 0 ? (x & lo_mask) | ((other & lo_mask) << J)
+                                : (x & ~lo_mask) | ((other & ~lo_mask) >> J);
+}
+__device__ __forceinline__ u64 wave_transpose64(u64 x)
+{
+    x = transpose_step<32>(x, 0x00000000ffffffffull);
+    x = transpose_step<16>(x, 0x0000ffff0000ffffull);
+    x = transpose_step<8>(x, 0x00ff00ff00ff00ffull);
+    x = transpose_step<4>(x, 0x0f0f0f0f0f0f0f0full);
+    x = transpose_step<2>(x, 0x3333333333333333ull);
+    x = transpose_step<1>(x, 0x5555555555555555ull);
+    return x;
+}
+
 // Loads that must observe atomics performed by other workgroups / earlier levels: go to the
 // device-coherent level instead of a possibly stale per-CU cache line.
 __device__ __forceinline__ u64 load_coherent(const u64 *p)
@@ -164,6 +184,10 @@ hipError_t launch_level(const GraphView &g, TravState *st, TravCounters *ctr, in
 // One workgroup runs level after level while 0 < frontier <= narrow_cap and nothing is deferred.
 hipError_t launch_narrow(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
                          const QueueGeom &qg, u64 *DB, u64 *M, u64 *K, int narrow_cap, int4 *trace, hipStream_t s);
+// Packed batches of small graphs whose operator ids are a topological order: one wave per graph sweeps
+// its operators once, highest ids first (no frontier at all); fills K and, when pq is not NULL, the
+// per-graph per-set counts.
+hipError_t launch_sweep_graphs(const GraphView &g, u64 *M, u64 *K, int64_t *per_query_count, hipStream_t s);
 // One sweep over all operators re-deriving K and pushing new bits to the inputs; *changed |= 1 if any.
 hipError_t launch_fix_sweep(const GraphView &g, u64 *M, u64 *K, int32_t *changed, int grid_blocks, hipStream_t s);
 

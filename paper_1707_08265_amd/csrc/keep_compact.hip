@@ -132,47 +132,54 @@ __global__ __launch_bounds__(kCThreads) void k_keep_count(CompactArgs a)
     }
 }
 
-// per_query_count[i] = sum over the replicas of pq_part[r][i]
+// per_query_count[i] = sum over the replicas of pq_part[r][i]: one wave per output, one lane per replica
 __global__ __launch_bounds__(256) void k_reduce_pq(CompactArgs a)
 {
     const int n = 64 * a.g.num_graphs;
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    const int i = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x >> 6);
     if (i >= n) return;
-    int64_t sum = 0;
-    for (int r = 0; r < a.pq_replicas; ++r) sum += a.pq_part[((int64_t)r * n + i) * kPqStride];
-    a.per_query_count[i] = sum;
+    const int lane = lane_id();
+    long long v = 0;
+    if (lane < a.pq_replicas) v = a.pq_part[((int64_t)lane * n + i) * kPqStride];
+#pragma unroll
+    for (int d = kWave / 2; d >= 1; d >>= 1) v += __shfl_xor(v, d, kWave);
+    if (lane == 0) a.per_query_count[i] = v;
 }
 
 // Single workgroup: exclusive scan of the tile counts in place, total -> counts[m] and kept_count[0].
+// 4096 entries per round (four consecutive ones per thread).
 __global__ __launch_bounds__(1024) void k_scan_tiles(int32_t *counts, int64_t m, int64_t *kept_count)
 {
-    __shared__ int wtot[16];
-    __shared__ int carry_s;
+    __shared__ int wtot[2][16];
     const int lane = lane_id(), wave = threadIdx.x >> 6;
-    if (threadIdx.x == 0) carry_s = 0;
-    __syncthreads();
-    for (int64_t base = 0; base < m; base += 1024) {
-        const int64_t i = base + threadIdx.x;
-        const int x = i < m ? counts[i] : 0;
-        const int incl = wave_incl_scan(x);
-        if (lane == kWave - 1) wtot[wave] = incl;
-        __syncthreads();
+    int carry = 0, buf = 0;
+    for (int64_t base = 0; base < m; base += 4096, buf ^= 1) {
+        const int64_t i = base + (int64_t)threadIdx.x * 4;
+        int x[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) x[c] = i + c < m ? counts[i + c] : 0;
+        const int sum = x[0] + x[1] + x[2] + x[3];
+        const int incl = wave_incl_scan(sum);
+        if (lane == kWave - 1) wtot[buf][wave] = incl;
+        __syncthreads();                      // double-buffered totals: one barrier per round is enough
         int woff = 0, tot = 0;
 #pragma unroll
         for (int w = 0; w < 16; ++w) {
-            const int c = wtot[w];
+            const int c = wtot[buf][w];
             if (w < wave) woff += c;
             tot += c;
         }
-        const int carry = carry_s;
-        if (i < m) counts[i] = carry + woff + incl - x;
-        __syncthreads();
-        if (threadIdx.x == 0) carry_s = carry + tot;
-        __syncthreads();
+        int run = carry + woff + incl - sum;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (i + c < m) counts[i + c] = run;
+            run += x[c];
+        }
+        carry += tot;
     }
     if (threadIdx.x == 0) {
-        counts[m] = carry_s;
-        kept_count[0] = carry_s;
+        counts[m] = carry;
+        kept_count[0] = carry;
     }
 }
 
@@ -236,7 +243,7 @@ hipError_t launch_keep_compact(const CompactArgs &a, hipStream_t s, hipEvent_t *
             hipLaunchKernelGGL(k_keep_count<false>, dim3((unsigned)tiles), dim3(kCThreads), 0, s, a);
     }
     if (a.per_query_count && a.pq_part)
-        hipLaunchKernelGGL(k_reduce_pq, dim3((unsigned)((64 * a.g.num_graphs + 255) / 256)), dim3(256), 0, s, a);
+        hipLaunchKernelGGL(k_reduce_pq, dim3((unsigned)((64 * a.g.num_graphs + 3) / 4)), dim3(256), 0, s, a);
     if (ev) (void)hipEventRecord(ev[0], s);
     hipLaunchKernelGGL(k_scan_tiles, dim3(1), dim3(1024), 0, s, a.block_counts, tiles, a.kept_count);
     if (ev) (void)hipEventRecord(ev[1], s);

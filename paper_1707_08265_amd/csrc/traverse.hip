@@ -175,7 +175,7 @@ __global__ __launch_bounds__(256) void k_seed(GraphView g, int32_t Q, int64_t nu
         }
     }
     // wave-aggregated slot reservation: one counter update per wave, counters spread over segments
-    const u64 pm = ballot64(push);
+    const u64 pm = q0 ? ballot64(push) : 0;    // no queue in the per-graph sweep mode: the bits in M are all it needs
     bool overflow = false;
     if (pm) {
         const int seg = (int)((j >> 6) & (qg.S - 1));
@@ -624,6 +624,74 @@ hipError_t launch_fix_sweep(const GraphView &g, u64 *M, u64 *K, int32_t *changed
 {
     if (g.num_ops == 0) return hipSuccess;
     hipLaunchKernelGGL(k_fix_sweep, dim3((unsigned)grid_blocks), dim3(kLevelThreads), 0, s, g, M, K, changed);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// per-graph descending sweep (packed batches of small graphs, operator ids topological)
+//
+// A tensor's consumers all have larger operator ids than its producer.  Walking one graph's operators
+// from the highest id down, 64 at a time, every operator therefore meets the final M of its outputs,
+// except for dependencies *inside* the group of 64, which the group repeats until nothing changes.
+// Each operator is expanded once with all 64 sets' bits (a level-synchronous traversal revisits the
+// operators of such deep, thin graphs tens of times), K needs no atomics (one lane owns an operator),
+// and nothing is queued.  One wave per graph; waves of different graphs never touch the same words.
+// ------------------------------------------------------------------------------------------------
+constexpr int kSweepThreads = 256;
+
+__global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64 *M, u64 *K, int64_t *pq)
+{
+    const int lane = lane_id();
+    const int gi = blockIdx.x * (kSweepThreads / kWave) + (threadIdx.x >> 6);
+    if (gi >= g.num_graphs) return;                          // wave-uniform
+    const int64_t o_lo = g.op_off[gi], o_hi = g.op_off[gi + 1];
+    u64 qcount = 0;                                          // lane q: operators of this graph kept for set q
+    for (int64_t top = o_hi; top > o_lo; top -= kWave) {
+        const int64_t o = top - 1 - lane;                    // lane 0 holds the highest id of the group
+        const bool valid = o >= o_lo;
+        int ob = 0, n_out = 0, ib = 0, n_in = 0;
+        if (valid) {
+            ob = g.out_rowptr[o];
+            n_out = g.out_rowptr[o + 1] - ob;
+            ib = g.in_rowptr[o];
+            n_in = g.in_rowptr[o + 1] - ib;
+        }
+        const int max_out = wave_max(n_out);
+        u64 kprev = 0;
+        for (;;) {
+            u64 k = 0;
+            for (int r = 0; r < max_out; ++r)
+                if (r < n_out) k |= load_coherent(&M[g.out_idx[ob + r]]);
+            const u64 nb = k & ~kprev;                       // bits this operator has not pushed to its inputs yet
+            kprev = k;
+            if (ballot64(nb != 0) == 0) break;
+            u64 fresh = 0;                                   // did any input word change?
+            const int max_in = wave_max(nb ? n_in : 0);
+            for (int r0 = 0; r0 < max_in; r0 += 4) {         // four independent atomics in flight per lane
+                u64 old[4] = {~(u64)0, ~(u64)0, ~(u64)0, ~(u64)0};
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (nb && r0 + c < n_in) old[c] = atomicOr(&M[g.in_idx[ib + r0 + c]], nb);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) fresh |= nb & ~old[c];
+            }
+            if (ballot64(fresh != 0) == 0) break;            // no word changed: a re-read would find nothing new
+        }
+        if (valid) K[o] = kprev;
+        if (pq) {
+            const u64 col = wave_transpose64(kprev);         // lane q: bit q of the 64 operators' masks
+            qcount += (u64)__popcll(col);
+        }
+    }
+    if (pq) pq[(int64_t)gi * 64 + lane] = (int64_t)qcount;
+}
+
+hipError_t launch_sweep_graphs(const GraphView &g, u64 *M, u64 *K, int64_t *per_query_count, hipStream_t s)
+{
+    if (g.num_graphs <= 0) return hipSuccess;
+    const int per_block = kSweepThreads / kWave;
+    hipLaunchKernelGGL(k_sweep_graphs, dim3((unsigned)((g.num_graphs + per_block - 1) / per_block)), dim3(kSweepThreads),
+                       0, s, g, M, K, per_query_count);
     return hipGetLastError();
 }
 

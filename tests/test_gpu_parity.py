@@ -270,3 +270,57 @@ def test_full_size_config3_power_law_50m(dgn, oracle):
 
 def test_full_size_config4_packed_batch(dgn, oracle):
     _full_size_check(dgn, oracle, 4, sampled_graphs=[0, 1, 777, 2048, 4095])
+
+
+def _pack(graphs_and_sets, Q):
+    """Concatenate (Graph, list-of-Q-target-lists) pairs into one packed batch with global ids."""
+    in_op, in_t, out_op, out_t, sets = [], [], [], [], []
+    op_off, t_off = [0], [0]
+    for g, s in graphs_and_sets:
+        in_op.append(g.in_op.astype(np.int64) + op_off[-1]); in_t.append(g.in_tensor.astype(np.int64) + t_off[-1])
+        out_op.append(g.out_op.astype(np.int64) + op_off[-1]); out_t.append(g.out_tensor.astype(np.int64) + t_off[-1])
+        sets += [[t + t_off[-1] for t in one] for one in s]
+        op_off.append(op_off[-1] + g.num_ops); t_off.append(t_off[-1] + g.num_tensors)
+    cat = lambda xs: np.concatenate(xs).astype(np.int32) if xs else np.zeros(0, np.int32)
+    g = gg.Graph(op_off[-1], t_off[-1], cat(in_op), cat(in_t), cat(out_op), cat(out_t), len(graphs_and_sets),
+                 np.asarray(op_off, np.int64), np.asarray(t_off, np.int64), "packed")
+    return g, targets_from_sets(sets, Q)
+
+
+def test_packed_batches_use_the_per_graph_sweep(dgn, oracle):
+    """Batches of >= 64 topologically numbered graphs take the one-wave-per-graph sweep; same results."""
+    # equal-sized layered graphs
+    g, tg = gg.batch_layered(96, 700, 4242, num_sets=64)
+    st = dgn.dgn_stats()
+    _, _, out = gpu_prune(dgn, g, tg, stats=st)
+    _, r = oracle_prune(oracle, g, tg)
+    assert_same(out, r, "batch 96x700")
+    assert st.levels == 0                     # no frontier levels were run
+    _, _, out = gpu_prune(dgn, g, tg, recompute_keep=True)
+    assert_same(out, r, "batch 96x700 recompute_keep")
+    _, _, out = gpu_prune(dgn, g, tg, traversal=1)          # and the generic traversal agrees
+    assert_same(out, r, "batch 96x700 generic")
+    # ragged graphs with awkward operators (no inputs, no outputs, duplicate edges), some graphs empty
+    rng = np.random.default_rng(5)
+    Q = 7
+    parts = []
+    for i in range(130):
+        P = int(rng.integers(0, 200))
+        gi, _ = random_small_graph(rng, P, num_inputs=int(rng.integers(1, 5)), multi_producer=False)
+        parts.append((gi, [[int(rng.integers(0, gi.num_tensors)) for _ in range(int(rng.integers(0, 4)))]
+                           for _ in range(Q)]))
+    g, tg = _pack(parts, Q)
+    st = dgn.dgn_stats()
+    _, _, out = gpu_prune(dgn, g, tg, validate=True, stats=st)
+    _, r = oracle_prune(oracle, g, tg)
+    assert_same(out, r, "ragged batch")
+    assert st.levels == 0
+    # graphs whose operator order is NOT topological fall back to the frontier traversal
+    parts = []
+    for i in range(70):
+        gi, _ = random_small_graph(rng, int(rng.integers(1, 80)), num_inputs=3, multi_producer=True)
+        parts.append((gi, [[int(rng.integers(0, gi.num_tensors))] for _ in range(3)]))
+    g, tg = _pack(parts, 3)
+    _, _, out = gpu_prune(dgn, g, tg)
+    _, r = oracle_prune(oracle, g, tg)
+    assert_same(out, r, "non-topological batch")
