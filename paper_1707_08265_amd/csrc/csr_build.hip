@@ -91,8 +91,13 @@ __global__ __launch_bounds__(256) void k_check_topological(GraphView g, int32_t 
         for (int32_t e = g.in_rowptr[o]; e < g.in_rowptr[o + 1]; ++e) {
             const int32_t t = g.in_idx[e];
             if (t < 0 || t >= g.num_tensors) continue;      // reported by the range check
-            for (int32_t p = g.prod_rowptr[t]; p < g.prod_rowptr[t + 1]; ++p)
-                if (g.prod_idx[p] >= o) bad = true;
+            const int4 pi = g.pinfo[t];                     // one record instead of two CSR hops
+            if (pi.x >= 0) {
+                if (pi.x >= o) bad = true;
+            } else if (pi.x == kMulti) {
+                for (int32_t p = pi.y; p < pi.y + pi.z; ++p)
+                    if (g.prod_idx[p] >= o) bad = true;
+            }
         }
     }
     if (bad) atomicOr(error, kErrTopo);

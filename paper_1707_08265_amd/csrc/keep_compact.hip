@@ -112,11 +112,16 @@ __global__ __launch_bounds__(kCThreads) void k_keep_count(CompactArgs a)
                 }
             }
             u64 any = wave_or(k);
-            while (any) {                                   // wave-uniform loop over the sets present
-                const int q = __builtin_ctzll(any);
-                any &= any - 1;
-                const int c = __popcll(ballot64((k >> q) & 1));
-                if (lane == q) qcount += (u64)c;
+            if (__popcll(any) > 6) {
+                // many sets present: transpose the 64x64 bit matrix, lane q then holds column q
+                qcount += (u64)__popcll(wave_transpose64(k));
+            } else {
+                while (any) {                               // wave-uniform loop over the few sets present
+                    const int q = __builtin_ctzll(any);
+                    any &= any - 1;
+                    const int c = __popcll(ballot64((k >> q) & 1));
+                    if (lane == q) qcount += (u64)c;
+                }
             }
         }
     }
