@@ -55,7 +55,8 @@ enum {
     DGN_ERR_WORKSPACE_TOO_SMALL = -6, /* graph_bytes or scratch_bytes below the queried size      */
     DGN_ERR_NOT_TOPOLOGICAL = -7,     /* validation found a producer id >= its consumer id        */
     DGN_ERR_HIP = -8,                 /* a HIP call failed; see dgn_last_hip_error()              */
-    DGN_ERR_BAD_CSR = -9              /* row pointers not monotone or not ending at nnz           */
+    DGN_ERR_BAD_CSR = -9,             /* row pointers not monotone or not ending at nnz           */
+    DGN_ERR_INTERNAL = -10            /* a device-side wait gave up (results are not valid)       */
 };
 
 /* Operators as two COO edge lists, in any order (Sec. 2.2: an operator with its inputs and its
@@ -89,7 +90,9 @@ typedef struct dgn_options {
     int32_t validate;        /* build: also check the topological precondition (one extra pass)   */
     int32_t recompute_keep;  /* prune: recompute K from M with the stand-alone removal-rule pass
                                 instead of using the K the traversal accumulated (same values)   */
-    int32_t traversal;       /* 0 = automatic; 1 = force the generic one-launch-per-level path   */
+    int32_t traversal;       /* 0 = automatic; 1 = one kernel launch per frontier level, nothing else;
+                                2 = one launch per wide level plus the single-workgroup kernel for
+                                small frontiers (no cooperative launch, no per-graph sweep)        */
     int32_t profile;         /* prune: bracket each phase with HIP events on `stream` and report
                                 the elapsed times in dgn_stats.phase_ms (needs stats != NULL)      */
     int32_t defer_percent;   /* prune: geometric decay (percent, 1..99) of the producer-id threshold

@@ -30,6 +30,9 @@ constexpr int kWideGroupsFirst = 3;         // groups in the first batch (one st
 constexpr int kWideGroups = 6;              // ... and in the following ones
 constexpr int kSweepMinGraphs = 64;         // packed batches with at least this many graphs ...
 constexpr int64_t kSweepMaxGraphOps = 1 << 18;   // ... none larger than this use the per-graph sweep
+constexpr int kPersistRounds = 2;           // cooperative launches (each followed by a single-workgroup one) per batch
+constexpr int kBarrierMaxSpins = 1 << 22;   // polls (about 0.5 us each) before a block gives up at the grid barrier
+constexpr int kSmallLevel = 16384;           // levels expanding fewer entries than this decay the threshold faster
 constexpr int kDefaultDeferPercent = 75;
 constexpr int kDefaultStartShift = 1;       // deferral threshold starts at P >> 1 ...
 constexpr int kDefaultFloorShift = 10;      // ... and stops (drops to 0) below P >> 10
@@ -209,7 +212,7 @@ int error_bits_to_code(int32_t bits)
 int check_options(const dgn_options *o)
 {
     if (!o) return DGN_OK;
-    if (o->traversal < 0 || o->traversal > 1) return DGN_ERR_INVALID_ARG;
+    if (o->traversal < 0 || o->traversal > 2) return DGN_ERR_INVALID_ARG;
     if (o->defer_percent < 0 || o->defer_percent > 100) return DGN_ERR_INVALID_ARG;
     if (o->max_queue_entries < 0) return DGN_ERR_INVALID_ARG;
     if (o->defer_start_shift < 0 || o->defer_start_shift > 30) return DGN_ERR_INVALID_ARG;
@@ -224,6 +227,7 @@ struct dgn_graph {
     int64_t P, T, Ein, Eout;
     int32_t G;
     int num_cus;
+    int persist_grid;       // blocks of the cooperative traversal kernel (0: not available)
     bool topological;       // operator ids verified to be a topological order at build time
     int64_t max_graph_ops;  // largest graph of a packed batch (P for a single graph)
 };
@@ -265,6 +269,12 @@ int finish_build(dgn_graph *h, const GraphLayout &L, const int64_t *op_off_host,
     DGN_HIP(hipGetDevice(&dev));
     DGN_HIP(hipGetDeviceProperties(&prop, dev));
     h->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    h->persist_grid = 0;
+    if (prop.cooperativeLaunch) {
+        int pg = 0;
+        if (persist_max_grid(h->num_cus, &pg) == hipSuccess && pg >= h->num_cus) h->persist_grid = pg;
+        else (void)hipGetLastError();
+    }
     *out = h;
     return DGN_OK;
 }
@@ -289,6 +299,7 @@ const char *dgn_strerror(int code)
         case DGN_ERR_NOT_TOPOLOGICAL: return "operator ids are not a topological order";
         case DGN_ERR_HIP: return "HIP runtime error";
         case DGN_ERR_BAD_CSR: return "malformed CSR row pointers";
+        case DGN_ERR_INTERNAL: return "a device-side wait gave up";
         default: return "unknown error";
     }
 }
@@ -488,7 +499,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     const int defer_percent = options && options->defer_percent ? options->defer_percent : kDefaultDeferPercent;
     const int start_shift = options && options->defer_start_shift ? options->defer_start_shift : kDefaultStartShift;
     const int floor_shift = options && options->defer_floor_shift ? options->defer_floor_shift : kDefaultFloorShift;
-    Schedule sch{1.0f, 0, 0};
+    Schedule sch{1.0f, 0, 0, kSmallLevel};
     if (defer_percent < 100) {
         sch.decay = (float)defer_percent / 100.0f;
         sch.theta0 = (int32_t)(g->P >> start_shift);
@@ -496,7 +507,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
         if (sch.theta_floor < 64) sch.theta_floor = 64;
         if (sch.theta0 < sch.theta_floor) sch.theta0 = 0;
     }
-    const bool sweep = !(options && options->traversal == 1) && g->G >= kSweepMinGraphs && g->topological &&
+    const bool sweep = !(options && options->traversal != 0) && g->G >= kSweepMinGraphs && g->topological &&
                        g->max_graph_ops <= kSweepMaxGraphOps;
     DGN_HIP(launch_seed(g->v, num_sets, num_targets, tgt_rowptr, tgt_idx, M, S.state, S.ctr, sweep ? nullptr : S.q0, S.qg,
                         sch.theta0, s));
@@ -581,16 +592,35 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
         rc = read_state();
         if (rc) return rc;
     }
+    // Wide levels: preferably all of them in one cooperative launch (grid barrier between levels, no
+    // host involvement); otherwise one launch per level.
+    bool persistent = !(options && options->traversal != 0) && g->persist_grid > 0;
     bool first = true;
     while (!done) {
-        for (int r = 0; r < (first ? kWideGroupsFirst : kWideGroups); ++r) {
-            for (int i = 0; i < kWidePerGroup; ++i, ++launch_no)
-                DGN_HIP(launch_level(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, grid, narrow_cap, sch, trace, s));
-            launches += kWidePerGroup;
-            level_launches += kWidePerGroup;
-            if (!generic_only) {
+        if (persistent) {
+            for (int r = 0; r < kPersistRounds && persistent; ++r) {
+                const hipError_t e = launch_persist(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K,
+                                                    g->persist_grid, narrow_cap, sch, trace, kBarrierMaxSpins, s);
+                if (e != hipSuccess) {                      // cooperative launch refused: use plain launches
+                    (void)hipGetLastError();
+                    persistent = false;
+                    break;
+                }
+                ++launch_no; ++launches; ++level_launches;
                 DGN_HIP(launch_narrow(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, narrow_cap, trace, s));
                 ++launch_no; ++launches;
+            }
+        }
+        if (!persistent) {
+            for (int r = 0; r < (first ? kWideGroupsFirst : kWideGroups); ++r) {
+                for (int i = 0; i < kWidePerGroup; ++i, ++launch_no)
+                    DGN_HIP(launch_level(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, grid, narrow_cap, sch, trace, s));
+                launches += kWidePerGroup;
+                level_launches += kWidePerGroup;
+                if (!generic_only) {
+                    DGN_HIP(launch_narrow(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, narrow_cap, trace, s));
+                    ++launch_no; ++launches;
+                }
             }
         }
         if (first && speculate) {
@@ -601,6 +631,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
         }
         rc = read_state();
         if (rc) return rc;
+        if (hst->error & kErrBarrier) return DGN_ERR_INTERNAL;
         if (!done) compacted = false;      // the speculative pass ran on unfinished masks
         first = false;
     }

@@ -20,6 +20,7 @@ enum : int32_t {
     kErrCsr = 4,          // row pointers not monotone / not ending at nnz
     kErrCrossGraph = 8,   // target or edge outside its own packed graph
     kErrOverflow = 16,    // internal: a frontier queue overflowed, the fix-up sweep must run
+    kErrBarrier = 32,     // a block of the persistent kernel waited too long at the grid barrier
 };
 
 // Adjacency of a built graph as the kernels see it (device pointers).
@@ -59,7 +60,10 @@ struct TravState {            // header of the traversal state; the host reads t
     u64 tensor_visits;         // expansions, summed over levels
     u64 max_frontier;
     int32_t changed;           // fix-up sweep: some operator gained bits
-    int32_t pad[7];
+    int32_t gen;               // grid-barrier generation of the persistent kernel
+    int32_t go;                // persistent kernel: the level just published is another wide one
+    int32_t abort;             // persistent kernel: a block gave up waiting at the barrier
+    int32_t pad[4];
 };
 
 // Contended words live 64 bytes apart, one per queue segment / block group.
@@ -75,7 +79,7 @@ struct TravCounters {
 };
 // Deferral schedule: the threshold starts at theta0, is multiplied by decay after every wide level and
 // drops to 0 (nothing deferred any more) once it falls below theta_floor.
-struct Schedule { float decay; int32_t theta0; int32_t theta_floor; };
+struct Schedule { float decay; int32_t theta0; int32_t theta_floor; int32_t small_level; };
 // A frontier queue: S segments (power of two, <= kMaxSeg) of seg_cap entries each.
 struct QueueGeom { int32_t S; int32_t seg_cap; };
 static_assert(sizeof(TravState) == 128, "TravState is read back as 128 bytes");
@@ -146,6 +150,12 @@ __device__ __forceinline__ int32_t load_coherent(const int32_t *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Stores that other workgroups read within the same kernel: written through to the device-coherent level.
+__device__ __forceinline__ void store_coherent(int32_t *p, int32_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // ---- launch wrappers (each returns a hipError_t; nothing synchronises) -------------------------
 struct FillRegion { void *ptr; size_t bytes; };   // ptr 8-byte aligned, bytes multiple of 8
 hipError_t launch_clear(const FillRegion *regions, int num_regions, hipStream_t s);
@@ -181,6 +191,12 @@ hipError_t launch_seed(const GraphView &g, int32_t Q, int64_t num_targets, const
 hipError_t launch_level(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
                         const QueueGeom &qg, u64 *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
                         const Schedule &sch, int4 *trace, hipStream_t s);
+// All consecutive wide levels in one cooperative launch (grid barrier between levels); grid_blocks must
+// not exceed persist_max_grid().  A waiting block gives up after max_spins polls (kErrBarrier).
+hipError_t launch_persist(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
+                          const QueueGeom &qg, u64 *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
+                          const Schedule &sch, int4 *trace, int max_spins, hipStream_t s);
+hipError_t persist_max_grid(int num_cus, int *grid_blocks);
 // One workgroup runs level after level while 0 < frontier <= narrow_cap and nothing is deferred.
 hipError_t launch_narrow(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
                          const QueueGeom &qg, u64 *DB, u64 *M, u64 *K, int narrow_cap, int4 *trace, hipStream_t s);

@@ -92,7 +92,7 @@ __device__ __forceinline__ void stage_flush(WaveStage &ws, const Frontier &f)
         }
         base = __builtin_amdgcn_readfirstlane(base);
         for (int k = lane_id(); k < ws.cnt; k += kWave)
-            if (base + k < f.seg_cap) f.seg[base + k] = ws.buf[k];
+            if (base + k < f.seg_cap) store_coherent(&f.seg[base + k], ws.buf[k]);   // read by other blocks
         ws.cnt = 0;
     }
 }
@@ -327,12 +327,19 @@ __device__ __forceinline__ bool process_ops(const GraphView &g, bool valid, int3
     return nb != 0;
 }
 
-__device__ __forceinline__ int32_t next_theta(int32_t theta, const Schedule &sch, bool idle, int max_deferred_key)
+// A level that expanded little is latency bound, not atomics bound: the threshold then takes two or
+// four decay steps at once, trading a few repeated expansions for fewer such levels.
+__device__ __forceinline__ int32_t next_theta(int32_t theta, const Schedule &sch, int expanded, int n_next,
+                                              int max_deferred_key)
 {
     if (theta <= 0) return 0;
     float base = (float)theta;
-    if (idle && max_deferred_key >= 0 && max_deferred_key + 1 < theta) base = (float)max_deferred_key + 1.0f;
-    const int32_t t = (int32_t)(base * sch.decay);
+    if (expanded == 0 && n_next == 0 && max_deferred_key >= 0 && max_deferred_key + 1 < theta)
+        base = (float)max_deferred_key + 1.0f;               // nothing to do above the highest deferred operator
+    float d = sch.decay;
+    if (expanded < sch.small_level) d *= d;
+    if (expanded < sch.small_level / 8) d *= d;
+    const int32_t t = (int32_t)(base * d);
     return t < sch.theta_floor ? 0 : t;
 }
 
@@ -343,17 +350,176 @@ constexpr int kLevelThreads = 256;
 constexpr int kLevelWaves = kLevelThreads / kWave;
 constexpr int kChunkOps = 16 * 64;                 // at most 16 deferred-bitmap words are expanded per wave step
 
+struct LevelShared {
+    int32_t stage[kLevelWaves][kStageCap];
+    int incl[kLevelWaves][kWave];
+    int32_t ops[kLevelWaves][kChunkOps];
+    int pref[kMaxSeg + 1];
+    int proc[kLevelWaves], maxkey[kLevelWaves];
+    int last, go;
+};
+
+// How one level's work is dealt to `grid` blocks.
+struct LevelPlan {
+    int w_lo, w_hi;      // deferred-bitmap words of the range [theta, theta_hi) that opens at this level
+    int cw_log, chunks;  // the words are dealt to the waves in chunks of 1 << cw_log (1..16) words: small
+                         // enough that a dense range is spread over many waves, large enough that a
+                         // sparse one needs few steps per wave
+    int nb_e, nb_s;      // blocks wanted by the frontier entries / by the range chunks
+    bool split;          // entries and chunks go to different blocks when the grid has room for both, so
+                         // the two dependent-access chains of a small level overlap
+    int nwork;           // blocks that have something to do
+};
+
+__device__ __forceinline__ LevelPlan plan_level(const LevelSlot &in, int n, bool ranges_left, int grid)
+{
+    LevelPlan p;
+    p.w_lo = ranges_left ? in.theta >> 6 : 0;
+    p.w_hi = ranges_left ? (in.theta_hi + 63) >> 6 : 0;
+    p.cw_log = 0;
+    while (p.cw_log < 4 && ((p.w_hi - p.w_lo) >> p.cw_log) > grid * kLevelWaves) ++p.cw_log;
+    const int cw = 1 << p.cw_log;
+    p.chunks = (p.w_hi - p.w_lo + cw - 1) >> p.cw_log;
+    p.nb_e = (n + kLevelThreads - 1) / kLevelThreads;
+    p.nb_s = (p.chunks + kLevelWaves - 1) / kLevelWaves;
+    p.split = p.nb_e + p.nb_s <= grid;
+    p.nwork = p.split ? max(1, p.nb_e + p.nb_s) : grid;
+    return p;
+}
+
+// The work of block `blk` (< p.nwork) in one level: its share of the frontier entries and of the
+// newly opened operator range.  Leaves the block's tallies in sh.proc / sh.maxkey (one per wave).
+__device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &in, int n, const LevelPlan &p, int blk,
+                                          const int32_t *qin, const QueueGeom &qg, const Frontier &f, u64 *DB, u64 *M,
+                                          u64 *K, LevelShared &sh)
+{
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const bool do_entries = !p.split || blk < p.nb_e;
+    const bool do_scan = !p.split || blk >= p.nb_e;
+    const int e_blocks = p.split ? p.nb_e : p.nwork, e_first = blk;
+    const int s_blocks = p.split ? p.nb_s : p.nwork, s_first = p.split ? blk - p.nb_e : blk;
+    const int cw = 1 << p.cw_log;
+
+    WaveStage ws{&sh.stage[wave][0], 0};
+    LevelCounters lc{0, -1};
+    for (int base = e_first * kLevelThreads; do_entries && base < n; base += e_blocks * kLevelThreads) {
+        const int i = base + threadIdx.x;
+        const bool valid = i < n;
+        const int32_t t = valid ? load_item(qin, qg, sh.pref, i) : 0;
+        process_entries(g, valid, t, in.theta, DB, M, K, &sh.incl[wave][0], ws, f, lc);
+    }
+    // expand the bitmap words of the newly opened range into dense operator lists, 64 per step
+    for (int c = s_first * kLevelWaves + wave; do_scan && c < p.chunks; c += s_blocks * kLevelWaves) {
+        const int w0 = p.w_lo + (c << p.cw_log);
+        u64 word = 0;
+        if (lane < cw && w0 + lane < p.w_hi) {
+            word = load_coherent(&DB[w0 + lane]);
+            const int64_t first = (int64_t)(w0 + lane) * 64;             // keep only ids in [theta, theta_hi)
+            if (first < in.theta) word &= ~(((u64)1 << (in.theta - first)) - 1);
+            if (first + 64 > in.theta_hi) word &= ((u64)1 << (in.theta_hi - first)) - 1;
+        }
+        // lane L expands part (L >> cw_log) of word (L & (cw-1)); a part is cw bits wide
+        const u64 wsel = shfl64(word, lane & (cw - 1));
+        const int part = lane >> p.cw_log;
+        uint32_t bits16 = (uint32_t)(wsel >> (part << p.cw_log)) & ((1u << cw) - 1u);
+        const int cnt = __popc(bits16);
+        const int incl = wave_incl_scan(cnt);
+        const int total = __shfl(incl, kWave - 1, kWave);
+        int pos = incl - cnt;
+        const int32_t op_base = (w0 + (lane & (cw - 1))) * 64 + (part << p.cw_log);
+        while (bits16) {
+            const int b = __builtin_ctz(bits16);
+            bits16 &= bits16 - 1;
+            sh.ops[wave][pos++] = op_base + b;
+        }
+        __builtin_amdgcn_wave_barrier();
+        for (int i0 = 0; i0 < total; i0 += kWave) {
+            const bool valid = i0 + lane < total;
+            const int32_t o = valid ? sh.ops[wave][i0 + lane] : 0;
+            process_ops(g, valid, o, M, K, &sh.incl[wave][0], ws, f);
+            if (valid) lc.processed++;
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+    stage_flush(ws, f);
+    const int wproc = wave_sum(lc.processed), wkey = wave_max(lc.max_deferred_key);
+    if (lane == 0) { sh.proc[wave] = wproc; sh.maxkey[wave] = wkey; }
+}
+
+// Two-level ticket (groups of blocks, then groups) taken by thread 0 of each of the `nwork` participating
+// blocks after __syncthreads.  Returns true in the last block to arrive; *total_proc then holds the sum
+// of all blocks' tallies.  Everything a block contributed is an atomic performed at the device-coherent
+// level (or a write-through queue store), so only completion of the block's own memory operations is
+// awaited here, no cache write-back.
+__device__ __forceinline__ bool take_ticket(TravState *st, TravCounters *ctr, int blk, int nwork, LevelShared &sh,
+                                            int *total_proc)
+{
+    int proc = 0, mk = -1;
+    for (int w = 0; w < kLevelWaves; ++w) { proc += sh.proc[w]; mk = max(mk, sh.maxkey[w]); }
+    const int groups = min(kMaxSeg, nwork);
+    int gproc = proc, gmax = mk + 1;
+    bool group_done = true;
+    if (nwork > kMaxSeg) {                               // first level: blocks of one group
+        const int grp = blk & (kMaxSeg - 1);
+        const int gsize = (nwork - grp + kMaxSeg - 1) / kMaxSeg;
+        if (mk >= 0) atomicMax(&ctr->submax[grp].v, mk + 1);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        const u64 tk = atomicAdd(&ctr->subticket[grp].v, ((u64)(uint32_t)proc << 32) | 1u);
+        group_done = (int)(tk & 0xffffffffu) == gsize - 1;
+        if (group_done) {
+            gproc = (int)(tk >> 32) + proc;
+            gmax = load_coherent(&ctr->submax[grp].v);
+            __hip_atomic_store(&ctr->subticket[grp].v, (u64)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    if (!group_done) return false;
+    if (gmax > 0) atomicMax(&st->max_deferred_key1, gmax);   // second level: one ticket per group
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    const u64 tk2 = atomicAdd(&st->ticket, ((u64)(uint32_t)gproc << 32) | 1u);
+    if ((int)(tk2 & 0xffffffffu) != groups - 1) return false;
+    *total_proc = (int)(tk2 >> 32) + gproc;
+    return true;
+}
+
+// Wave 0 of the last block of a level: totals of the push counters, next level's state.  The new state
+// goes to slot `dst` (and its counters to cnt[dst]); cnt[1 - dst] ends up zeroed as the next push target.
+__device__ __forceinline__ void publish_level(TravState *st, TravCounters *ctr, const LevelSlot &in, int n,
+                                              bool ranges_left, int out_slot, int dst, const QueueGeom &qg,
+                                              const Schedule &sch, int tot_proc, int4 *trace)
+{
+    const int lane = lane_id();
+    int c = 0;
+    if (lane < qg.S) {
+        c = load_coherent(&ctr->cnt[out_slot][lane].v);
+        if (c > qg.seg_cap) c = qg.seg_cap;
+    }
+    store_coherent(&ctr->cnt[out_slot ^ 1][lane].v, 0);
+    if (dst != out_slot) {                               // the pushes were counted in the other slot: move them
+        store_coherent(&ctr->cnt[dst][lane].v, c);
+        store_coherent(&ctr->cnt[out_slot][lane].v, 0);
+    }
+    const int n_next = wave_sum(c);
+    if (lane == 0) {
+        const int tot_key = load_coherent(&st->max_deferred_key1) - 1;
+        LevelSlot *out = &st->slot[dst];
+        __hip_atomic_store(&st->ticket, (u64)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        store_coherent(&out->level, in.level + 1);
+        store_coherent(&out->n, n_next);
+        store_coherent(&out->deferred_seen, tot_key >= 0);
+        store_coherent(&out->theta_hi, ranges_left ? in.theta : in.theta_hi);   // [theta, theta_hi) has been scanned
+        store_coherent(&out->theta, (ranges_left || tot_key >= 0) ? next_theta(in.theta, sch, tot_proc, n_next, tot_key)
+                                                                  : in.theta);
+        atomicAdd(&st->tensor_visits, (u64)tot_proc);
+        atomicMax(&st->max_frontier, (u64)n);
+        if (trace && in.level < kTraceLevels) trace[in.level] = make_int4(n, tot_proc, in.theta, ranges_left ? in.theta_hi : -1);
+    }
+}
+
 __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState *st, TravCounters *ctr, int launch_no,
                                                           int32_t *q0, int32_t *q1, QueueGeom qg, u64 *DB, u64 *M,
                                                           u64 *K, int narrow_cap, Schedule sch, int4 *trace)
 {
-    __shared__ int32_t s_stage[kLevelWaves][kStageCap];
-    __shared__ int s_incl[kLevelWaves][kWave];
-    __shared__ int32_t s_ops[kLevelWaves][kChunkOps];
-    __shared__ int s_pref[kMaxSeg + 1];
-    __shared__ int s_proc[kLevelWaves], s_maxkey[kLevelWaves];
-    __shared__ int s_last;
-
+    __shared__ LevelShared sh;
     const int in_slot = launch_no & 1, out_slot = in_slot ^ 1;
     const LevelSlot in = st->slot[in_slot];
     LevelSlot *out = &st->slot[out_slot];
@@ -363,10 +529,10 @@ __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState 
         if (blockIdx.x == 0 && threadIdx.x == 0) *out = in;
         return;
     }
-    const int n = load_segments(ctr->cnt[in_slot], qg, s_pref);
+    const int n = load_segments(ctr->cnt[in_slot], qg, sh.pref);
     if (n <= narrow_cap && !ranges_left) {   // finished, or small enough for the single-workgroup kernel
         if (blockIdx.x == 0 && threadIdx.x < kMaxSeg) {     // hand the frontier (its counters) to the next launch
-            const int c = s_pref[lane + 1] - s_pref[lane];
+            const int c = sh.pref[lane + 1] - sh.pref[lane];
             ctr->cnt[out_slot][lane].v = c;
             ctr->cnt[in_slot][lane].v = 0;
             if (lane == 0) {
@@ -376,136 +542,26 @@ __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState 
         }
         return;
     }
-    // deferred operators whose range [theta, theta_hi) opens at this level; the bitmap words of the
-    // range are dealt to the waves in chunks of cw words (a power of two, 1..16): small enough that a
-    // dense range is spread over many waves, large enough that a sparse one needs few steps per wave
-    const int w_lo = ranges_left ? in.theta >> 6 : 0;
-    const int w_hi = ranges_left ? (in.theta_hi + 63) >> 6 : 0;
-    int cw_log = 0;
-    while (cw_log < 4 && ((w_hi - w_lo) >> cw_log) > (int)gridDim.x * kLevelWaves) ++cw_log;
-    const int cw = 1 << cw_log;
-    const int chunks = (w_hi - w_lo + cw - 1) >> cw_log;
-    // Frontier entries and range chunks go to different blocks when the grid has room for both, so
-    // the two dependent-access chains of a small level overlap instead of following each other.
-    const int nb_e = (n + kLevelThreads - 1) / kLevelThreads;
-    const int nb_s = (chunks + kLevelWaves - 1) / kLevelWaves;
-    const bool split = nb_e + nb_s <= (int)gridDim.x;
-    const int nwork = split ? max(1, nb_e + nb_s) : (int)gridDim.x;
-    if ((int)blockIdx.x >= nwork) return;
-    const bool do_entries = !split || (int)blockIdx.x < nb_e;
-    const bool do_scan = !split || (int)blockIdx.x >= nb_e;
-    const int e_blocks = split ? nb_e : nwork, e_first = blockIdx.x;
-    const int s_blocks = split ? nb_s : nwork, s_first = split ? (int)blockIdx.x - nb_e : (int)blockIdx.x;
+    const LevelPlan p = plan_level(in, n, ranges_left, (int)gridDim.x);
+    if ((int)blockIdx.x >= p.nwork) return;
 
     const int cur = in.level & 1;
     const int32_t *qin = cur ? q1 : q0;
     int32_t *qout = cur ? q0 : q1;
     const int seg = (blockIdx.x * kLevelWaves + wave) & (qg.S - 1);
     const Frontier f{qout + (int64_t)seg * qg.seg_cap, &ctr->cnt[out_slot][seg].v, qg.seg_cap, &st->error};
+    run_level(g, in, n, p, (int)blockIdx.x, qin, qg, f, DB, M, K, sh);
 
-    WaveStage ws{&s_stage[wave][0], 0};
-    LevelCounters lc{0, -1};
-    for (int base = e_first * kLevelThreads; do_entries && base < n; base += e_blocks * kLevelThreads) {
-        const int i = base + threadIdx.x;
-        const bool valid = i < n;
-        const int32_t t = valid ? load_item(qin, qg, s_pref, i) : 0;
-        process_entries(g, valid, t, in.theta, DB, M, K, &s_incl[wave][0], ws, f, lc);
-    }
-    // expand the bitmap words of the newly opened range into dense operator lists, 64 per step
-    for (int c = s_first * kLevelWaves + wave; do_scan && c < chunks; c += s_blocks * kLevelWaves) {
-        const int w0 = w_lo + (c << cw_log);
-        u64 word = 0;
-        if (lane < cw && w0 + lane < w_hi) {
-            word = load_coherent(&DB[w0 + lane]);
-            const int64_t first = (int64_t)(w0 + lane) * 64;             // keep only ids in [theta, theta_hi)
-            if (first < in.theta) word &= ~(((u64)1 << (in.theta - first)) - 1);
-            if (first + 64 > in.theta_hi) word &= ((u64)1 << (in.theta_hi - first)) - 1;
-        }
-        // lane L expands part (L >> cw_log) of word (L & (cw-1)); a part is cw bits wide
-        const u64 wsel = shfl64(word, lane & (cw - 1));
-        const int part = lane >> cw_log;
-        uint32_t bits16 = (uint32_t)(wsel >> (part << cw_log)) & ((1u << cw) - 1u);
-        const int cnt = __popc(bits16);
-        const int incl = wave_incl_scan(cnt);
-        const int total = __shfl(incl, kWave - 1, kWave);
-        int pos = incl - cnt;
-        const int32_t op_base = (w0 + (lane & (cw - 1))) * 64 + (part << cw_log);
-        while (bits16) {
-            const int b = __builtin_ctz(bits16);
-            bits16 &= bits16 - 1;
-            s_ops[wave][pos++] = op_base + b;
-        }
-        __builtin_amdgcn_wave_barrier();
-        for (int i0 = 0; i0 < total; i0 += kWave) {
-            const bool valid = i0 + lane < total;
-            const int32_t o = valid ? s_ops[wave][i0 + lane] : 0;
-            process_ops(g, valid, o, M, K, &s_incl[wave][0], ws, f);
-            if (valid) lc.processed++;
-        }
-        __builtin_amdgcn_wave_barrier();
-    }
-    stage_flush(ws, f);
-
-    const int wproc = wave_sum(lc.processed), wkey = wave_max(lc.max_deferred_key);
-    if (lane == 0) { s_proc[wave] = wproc; s_maxkey[wave] = wkey; }
-    if (threadIdx.x == 0) s_last = 0;
+    // the last working block to finish publishes the next level
+    if (threadIdx.x == 0) sh.last = 0;
     __syncthreads();
-    // Two-level ticket (groups of blocks, then groups): the last working block publishes the next level.
-    // Everything a block contributed is an atomic performed at the device-coherent level, and queue
-    // entries only have to be visible to the *next launch*, so no cache write-back is needed here.
     if (threadIdx.x == 0) {
-        int proc = 0, mk = -1;
-        for (int w = 0; w < kLevelWaves; ++w) { proc += s_proc[w]; mk = max(mk, s_maxkey[w]); }
-        const int groups = min(kMaxSeg, nwork);
-        int gproc = proc, gmax = mk + 1;
-        bool group_done = true;
-        if (nwork > kMaxSeg) {                               // first level: blocks of one group
-            const int grp = blockIdx.x & (kMaxSeg - 1);
-            const int gsize = (nwork - grp + kMaxSeg - 1) / kMaxSeg;
-            if (mk >= 0) atomicMax(&ctr->submax[grp].v, mk + 1);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            const u64 tk = atomicAdd(&ctr->subticket[grp].v, ((u64)(uint32_t)proc << 32) | 1u);
-            group_done = (int)(tk & 0xffffffffu) == gsize - 1;
-            if (group_done) {
-                gproc = (int)(tk >> 32) + proc;
-                gmax = load_coherent(&ctr->submax[grp].v);
-                ctr->subticket[grp].v = 0;
-            }
-        }
-        if (group_done) {                                    // second level: one ticket per group
-            if (gmax > 0) atomicMax(&st->max_deferred_key1, gmax);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            const u64 tk2 = atomicAdd(&st->ticket, ((u64)(uint32_t)gproc << 32) | 1u);
-            if ((int)(tk2 & 0xffffffffu) == groups - 1) {
-                s_last = 1;
-                s_proc[0] = (int)(tk2 >> 32) + gproc;
-            }
-        }
+        int tot = 0;
+        if (take_ticket(st, ctr, (int)blockIdx.x, p.nwork, sh, &tot)) { sh.last = 1; sh.proc[0] = tot; }
     }
     __syncthreads();
-    if (s_last && threadIdx.x < kWave) {                      // wave 0 of the last block
-        int c = 0;
-        if (lane < qg.S) {
-            c = load_coherent(&ctr->cnt[out_slot][lane].v);
-            if (c > qg.seg_cap) c = qg.seg_cap;
-        }
-        ctr->cnt[in_slot][lane].v = 0;                       // becomes the push target of the next launch
-        const int n_next = wave_sum(c);
-        if (lane == 0) {
-            const int tot_proc = s_proc[0];
-            const int tot_key = load_coherent(&st->max_deferred_key1) - 1;
-            st->ticket = 0;
-            out->level = in.level + 1;
-            out->n = n_next;
-            out->deferred_seen = tot_key >= 0;
-            out->theta_hi = ranges_left ? in.theta : in.theta_hi;   // [theta, theta_hi) has been scanned
-            out->theta = (ranges_left || tot_key >= 0) ? next_theta(in.theta, sch, tot_proc == 0 && n_next == 0, tot_key)
-                                                       : in.theta;
-            st->tensor_visits += (u64)tot_proc;
-            if ((u64)n > st->max_frontier) st->max_frontier = (u64)n;
-            if (trace && in.level < kTraceLevels) trace[in.level] = make_int4(n, tot_proc, in.theta, ranges_left ? in.theta_hi : -1);
-        }
-    }
+    if (sh.last && threadIdx.x < kWave)
+        publish_level(st, ctr, in, n, ranges_left, out_slot, out_slot, qg, sch, sh.proc[0], trace);
 }
 
 hipError_t launch_level(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
@@ -515,6 +571,138 @@ hipError_t launch_level(const GraphView &g, TravState *st, TravCounters *ctr, in
     hipLaunchKernelGGL(k_level, dim3((unsigned)grid_blocks), dim3(kLevelThreads), 0, s, g, st, ctr, launch_no, q0, q1,
                        qg, DB, M, K, narrow_cap, sch, trace);
     return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// persistent wide levels: the whole run of wide levels in ONE cooperative launch.  All blocks are
+// resident; between levels they meet at a grid barrier built from the same two-level ticket (the last
+// block to arrive publishes the next level, then releases the others by bumping a generation word).
+// Everything blocks exchange goes through atomics, write-through stores and cache-bypassing loads, so the
+// barrier needs no cache write-back or invalidation.  A block that waits longer than max_spins polls
+// raises kErrBarrier and every block leaves: the kernel cannot hang.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ LevelSlot load_slot_coherent(const LevelSlot *s)
+{
+    LevelSlot r;
+    r.level = load_coherent(&s->level);
+    r.n = load_coherent(&s->n);
+    r.theta = load_coherent(&s->theta);
+    r.theta_hi = load_coherent(&s->theta_hi);
+    r.deferred_seen = load_coherent(&s->deferred_seen);
+    return r;
+}
+
+__global__ __launch_bounds__(kLevelThreads) void k_persist(GraphView g, TravState *st, TravCounters *ctr, int launch_no,
+                                                            int32_t *q0, int32_t *q1, QueueGeom qg, u64 *DB, u64 *M,
+                                                            u64 *K, int narrow_cap, Schedule sch, int4 *trace,
+                                                            int max_spins)
+{
+    __shared__ LevelShared sh;
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int grid = (int)gridDim.x, blk = (int)blockIdx.x;
+    const int final_slot = (launch_no + 1) & 1;              // where the next launch expects the state
+    int slot = launch_no & 1;
+    int gen = load_coherent(&st->gen);                       // nobody bumps it before every block has arrived once
+    for (;;) {
+        const LevelSlot in = load_slot_coherent(&st->slot[slot]);
+        const bool ranges_left = in.deferred_seen && in.theta_hi > 0;
+        const int n = load_segments(ctr->cnt[slot], qg, sh.pref);
+        const bool stop = n <= narrow_cap && !ranges_left;   // same state, same decision in every block
+        if (stop) {
+            // Only reachable in the first round (later rounds stop through sh.go below).  Hand the
+            // untouched frontier to the next launch, as k_level does.
+            if (blk == 0 && threadIdx.x < kMaxSeg) {
+                const int c = sh.pref[lane + 1] - sh.pref[lane];
+                ctr->cnt[final_slot][lane].v = c;
+                ctr->cnt[slot][lane].v = 0;
+                if (lane == 0) {
+                    st->slot[final_slot] = in;
+                    st->slot[final_slot].n = n;
+                }
+            }
+            return;
+        }
+        const LevelPlan p = plan_level(in, n, ranges_left, grid);
+        const int cur = in.level & 1;
+        const int32_t *qin = cur ? q1 : q0;
+        int32_t *qout = cur ? q0 : q1;
+        const int out_slot = slot ^ 1;
+        const int seg = (blk * kLevelWaves + wave) & (qg.S - 1);
+        const Frontier f{qout + (int64_t)seg * qg.seg_cap, &ctr->cnt[out_slot][seg].v, qg.seg_cap, &st->error};
+        if (blk < p.nwork) {
+            run_level(g, in, n, p, blk, qin, qg, f, DB, M, K, sh);
+        } else if (lane == 0) {
+            sh.proc[wave] = 0;
+            sh.maxkey[wave] = -1;
+        }
+        // ---- grid barrier: every block takes a ticket; the last one publishes and releases ----
+        if (threadIdx.x == 0) { sh.last = 0; sh.go = 1; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int tot = 0;
+            if (take_ticket(st, ctr, blk, grid, sh, &tot)) { sh.last = 1; sh.proc[0] = tot; }
+        }
+        __syncthreads();
+        if (sh.last) {
+            // Will the next level still be a wide one?  If not, the state is left where the next launch
+            // looks for it and everybody leaves.
+            if (threadIdx.x < kWave) {
+                int c = 0;
+                if (lane < qg.S) c = min(load_coherent(&ctr->cnt[out_slot][lane].v), qg.seg_cap);
+                const int n_next = wave_sum(c);
+                // exactly the test the blocks would make on the state about to be published
+                const int theta_hi_next = ranges_left ? in.theta : in.theta_hi;
+                const bool more_ranges = load_coherent(&st->max_deferred_key1) > 0 && theta_hi_next > 0;
+                const bool go = n_next > narrow_cap || more_ranges;
+                publish_level(st, ctr, in, n, ranges_left, out_slot, go ? out_slot : final_slot, qg, sch, sh.proc[0], trace);
+                if (lane == 0) {
+                    sh.go = go;
+                    store_coherent(&st->go, go ? 1 : 0);
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");     // state written before the release
+                    __hip_atomic_store(&st->gen, gen + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        } else if (threadIdx.x == 0) {
+            int spins = 0;
+            while (load_coherent(&st->gen) == gen) {
+                __builtin_amdgcn_s_sleep(8);
+                if (++spins > max_spins || load_coherent(&st->abort)) {
+                    atomicOr(&st->error, kErrBarrier);
+                    store_coherent(&st->abort, 1);
+                    sh.go = 0;
+                    break;
+                }
+            }
+            if (sh.go) sh.go = load_coherent(&st->go);
+        }
+        __syncthreads();
+        if (!sh.go) return;
+        slot ^= 1;
+        ++gen;
+    }
+}
+
+hipError_t launch_persist(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
+                          const QueueGeom &qg, u64 *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
+                          const Schedule &sch, int4 *trace, int max_spins, hipStream_t s)
+{
+    GraphView gv = g;
+    QueueGeom q = qg;
+    Schedule sc = sch;
+    void *args[] = {&gv, &st, &ctr, &launch_no, &q0, &q1, &q, &DB, &M, &K, &narrow_cap, &sc, &trace, &max_spins};
+    return hipLaunchCooperativeKernel(reinterpret_cast<void *>(k_persist), dim3((unsigned)grid_blocks),
+                                      dim3(kLevelThreads), args, 0, s);
+}
+
+// Largest grid whose blocks are all resident at once (what a cooperative launch accepts).
+hipError_t persist_max_grid(int num_cus, int *grid_blocks)
+{
+    int per_cu = 0;
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_persist, kLevelThreads, 0);
+    if (e != hipSuccess) return e;
+    if (per_cu > 4) per_cu = 4;
+    *grid_blocks = per_cu * num_cus;
+    return hipSuccess;
 }
 
 // ------------------------------------------------------------------------------------------------
