@@ -118,7 +118,8 @@ def main():
 
     if args.trace_levels:
         for lv in range(min(int(st.levels), trace.shape[0])):
-            log(f"level {lv}: frontier={trace[lv, 0]} expanded={trace[lv, 1]} theta={trace[lv, 2]} range_top={trace[lv, 3]}")
+            dt = ((int(trace[lv, 3]) - int(trace[lv - 1, 3])) & 0xFFFFFFFF) / 100.0 if lv else 0.0
+            log(f"level {lv}: frontier={trace[lv, 0]} expanded={trace[lv, 1]} theta={trace[lv, 2]} us_since_prev={dt:.1f}")
     out = buf.to_host()
     P, T = g.num_ops, g.num_tensors
     P_k = int(out["kept_count"][0])

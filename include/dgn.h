@@ -92,7 +92,9 @@ typedef struct dgn_options {
                                 instead of using the K the traversal accumulated (same values)   */
     int32_t traversal;       /* 0 = automatic; 1 = one kernel launch per frontier level, nothing else;
                                 2 = one launch per wide level plus the single-workgroup kernel for
-                                small frontiers (no cooperative launch, no per-graph sweep)        */
+                                small frontiers (what 0 chooses for a single graph);
+                                3 = all wide levels in one cooperative launch with a grid barrier
+                                between levels (falls back to 2 where such launches are refused)   */
     int32_t profile;         /* prune: bracket each phase with HIP events on `stream` and report
                                 the elapsed times in dgn_stats.phase_ms (needs stats != NULL)      */
     int32_t defer_percent;   /* prune: geometric decay (percent, 1..99) of the producer-id threshold
@@ -126,8 +128,9 @@ typedef struct dgn_stats {
     int64_t launches;        /* kernels enqueued by the call                                     */
     int64_t level_launches;  /* of which frontier-level kernels                                  */
     int32_t *level_trace;    /* IN, optional HOST buffer: per level 4 ints (frontier size, entries and
-                                operators expanded, deferral threshold, top of the operator range opened
-                                or -1), for the first level_trace_cap levels (at most 4096)               */
+                                operators expanded, deferral threshold or -1, low 32 bits of the device
+                                wall clock in 10 ns ticks when the level was finished), for the first
+                                level_trace_cap levels (at most 4096)                                    */
     int64_t level_trace_cap; /* IN: capacity of level_trace in levels                                     */
     int64_t reserved;
     float phase_ms[DGN_NUM_PHASES];   /* filled when options->profile; zero otherwise           */

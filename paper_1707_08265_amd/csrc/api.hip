@@ -26,14 +26,14 @@ inline int hip_fail(hipError_t e)
 constexpr int64_t kMaxCount = 2147483646;   // counts must stay below 2^31 - 1
 constexpr int kNarrowCap = 3072;            // frontiers up to this size are walked by one workgroup
 constexpr int kWidePerGroup = 12;           // wide level launches between two single-workgroup launches
-constexpr int kWideGroupsFirst = 3;         // groups in the first batch (one state read-back per batch) ...
+constexpr int kWideGroupsFirst = 4;         // groups in the first batch (one state read-back per batch) ...
 constexpr int kWideGroups = 6;              // ... and in the following ones
 constexpr int kSweepMinGraphs = 64;         // packed batches with at least this many graphs ...
 constexpr int64_t kSweepMaxGraphOps = 1 << 18;   // ... none larger than this use the per-graph sweep
 constexpr int kPersistRounds = 2;           // cooperative launches (each followed by a single-workgroup one) per batch
 constexpr int kBarrierMaxSpins = 1 << 22;   // polls (about 0.5 us each) before a block gives up at the grid barrier
 constexpr int kSmallLevel = 16384;           // levels expanding fewer entries than this decay the threshold faster
-constexpr int kDefaultDeferPercent = 75;
+constexpr int kDefaultDeferPercent = 85;
 constexpr int kDefaultStartShift = 1;       // deferral threshold starts at P >> 1 ...
 constexpr int kDefaultFloorShift = 10;      // ... and stops (drops to 0) below P >> 10
 
@@ -212,7 +212,7 @@ int error_bits_to_code(int32_t bits)
 int check_options(const dgn_options *o)
 {
     if (!o) return DGN_OK;
-    if (o->traversal < 0 || o->traversal > 2) return DGN_ERR_INVALID_ARG;
+    if (o->traversal < 0 || o->traversal > 3) return DGN_ERR_INVALID_ARG;
     if (o->defer_percent < 0 || o->defer_percent > 100) return DGN_ERR_INVALID_ARG;
     if (o->max_queue_entries < 0) return DGN_ERR_INVALID_ARG;
     if (o->defer_start_shift < 0 || o->defer_start_shift > 30) return DGN_ERR_INVALID_ARG;
@@ -594,7 +594,9 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     }
     // Wide levels: preferably all of them in one cooperative launch (grid barrier between levels, no
     // host involvement); otherwise one launch per level.
-    bool persistent = !(options && options->traversal != 0) && g->persist_grid > 0;
+    // (measured slower than plain launches on this chip: a launch costs ~2 us back to back, the barrier
+    // with its state hand-over more; kept as option 3)
+    bool persistent = options && options->traversal == 3 && g->persist_grid > 0;
     bool first = true;
     while (!done) {
         if (persistent) {

@@ -511,7 +511,7 @@ __device__ __forceinline__ void publish_level(TravState *st, TravCounters *ctr, 
                                                                   : in.theta);
         atomicAdd(&st->tensor_visits, (u64)tot_proc);
         atomicMax(&st->max_frontier, (u64)n);
-        if (trace && in.level < kTraceLevels) trace[in.level] = make_int4(n, tot_proc, in.theta, ranges_left ? in.theta_hi : -1);
+        if (trace && in.level < kTraceLevels) trace[in.level] = make_int4(n, tot_proc, in.theta, (int)(uint32_t)wall_clock64());
     }
 }
 
@@ -751,7 +751,7 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
         __syncthreads();
         visits += (u64)n;
         if ((u64)n > maxf) maxf = (u64)n;
-        if (trace && threadIdx.x == 0 && level < kTraceLevels) trace[level] = make_int4(n, n, -1, -1);
+        if (trace && threadIdx.x == 0 && level < kTraceLevels) trace[level] = make_int4(n, n, -1, (int)(uint32_t)wall_clock64());
         n = min(s_nout, qg.seg_cap);
         ++level;
         moved = true;
