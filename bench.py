@@ -19,6 +19,24 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, vendor figure
 
 
+def measured_traffic(kernel):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, or None when the kernels have
+    changed since the counters were taken (or the workload is not the one they were taken on)."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "prune_config3_hbm_counters.txt")
+    try:
+        vals = dict(line.split(": ", 1) for line in open(path).read().splitlines()
+                    if ": " in line and not line.startswith("#"))
+        h = hashlib.sha256()
+        for f in ("traverse.hip", "keep_compact.hip", "primitives.hip"):
+            h.update(open(os.path.join(ROOT, "paper_1707_08265_amd", "csrc", f), "rb").read())
+        if h.hexdigest()[:16] != vals.get("source_hash", "").strip():
+            return None
+        return int(vals[kernel + "_traffic_bytes"])
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
@@ -37,6 +55,8 @@ def main():
     ap.add_argument("--defer-start-shift", type=int, default=0)
     ap.add_argument("--defer-floor-shift", type=int, default=0)
     ap.add_argument("--generic", action="store_true", help="force the one-launch-per-level traversal")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (known size, to scale profiler byte counters)")
     ap.add_argument("--trace-levels", action="store_true", help="print the per-level trace of the last step")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -116,6 +136,13 @@ def main():
         f"visits={st.tensor_visits} max_frontier={st.max_frontier}")
     log("phase ms (HIP events, mean over timed steps): " + ", ".join(f"{k}={v:.3f}" for k, v in ph.items()))
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                       # one elementwise copy kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     if args.trace_levels:
         for lv in range(min(int(st.levels), trace.shape[0])):
             dt = ((int(trace[lv, 3]) - int(trace[lv - 1, 3])) & 0xFFFFFFFF) / 100.0 if lv else 0.0
@@ -150,7 +177,8 @@ def main():
     b_alg_total = alg["k_clear"] + alg["k_level"] * levels + alg["k_keep_count"] + alg["k_scatter"]
     roofline = {
         "bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "traffic": measured_traffic(dominant) if (args.config == 3 and args.scale == 1.0 and not args.recompute_keep) else None,
         "launch_ms": round(dur_ms[dominant], 4), "launches_per_step": 1 if dominant != "k_level" else int(st.level_launches),
         "per_kernel_GBs": {k: round(alg[k] / (dur_ms[k] * 1e-3) / 1e9, 1) if dur_ms[k] > 0 else None for k in alg},
         "whole_path_algorithmic_GBs": round(b_alg_total / (ms_per_step * 1e-3) / 1e9, 1),

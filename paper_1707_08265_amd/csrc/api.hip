@@ -661,7 +661,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
         if (ev) DGN_HIP(hipEventRecord(ev[3], s));
         DGN_HIP(launch_keep_compact(ca, s, ev ? ev + 4 : nullptr));
         launches += 3 + (g->G > 1);
-        if (ev) DGN_HIP(hipStreamSynchronize(s));    // the phase events below must have completed
+        DGN_HIP(hipStreamSynchronize(s));    // outputs are complete (and the phase events recorded) on return
     }
     if (stats) {
         memset(stats, 0, sizeof(*stats));
