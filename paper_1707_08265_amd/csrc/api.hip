@@ -245,16 +245,18 @@ int finish_build(dgn_graph *h, const GraphLayout &L, const int64_t *op_off_host,
         h->v.t_off = L.t_off;
         DGN_HIP(launch_check_graph_ranges(h->v, status, s));
     }
-    // the topological precondition is always checked (schedules that rely on it are only chosen when it
-    // holds); it is an error only when the caller asked for validation
-    DGN_HIP(launch_check_topological(h->v, status, s));
+    // The topological precondition is checked when the caller asks for validation, and for packed
+    // batches, whose per-graph sweep is only chosen when it holds.  (One random access per edge: not
+    // worth paying on every build of a big single graph, whose traversal does not depend on it.)
+    const bool check_topo = (options && options->validate) || h->G >= kSweepMinGraphs;
+    if (check_topo) DGN_HIP(launch_check_topological(h->v, status, s));
     void *pin = nullptr;
     int rc = pinned_buffer(&pin);
     if (rc) return rc;
     DGN_HIP(hipMemcpyAsync(pin, status, sizeof(int32_t), hipMemcpyDeviceToHost, s));
     DGN_HIP(hipStreamSynchronize(s));
     int32_t bits = *static_cast<int32_t *>(pin);
-    h->topological = (bits & kErrTopo) == 0;
+    h->topological = check_topo && (bits & kErrTopo) == 0;
     if (!(options && options->validate)) bits &= ~kErrTopo;
     rc = error_bits_to_code(bits);
     if (rc) return rc;

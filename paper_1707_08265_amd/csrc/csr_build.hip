@@ -10,16 +10,30 @@ namespace dgn {
 __global__ __launch_bounds__(256) void k_degree_hist(const int32_t *keys, const int32_t *vals, int64_t nnz,
                                                       int32_t n_rows, int32_t n_vals, int32_t *deg, int32_t *error)
 {
+    // Runs of equal keys inside a wave (operator-major COO is one long sequence of such runs) are added
+    // with ONE atomic by the run's first lane: atomics on one address serialise, and an operator with
+    // fan-in 64 would otherwise be 64 of them.
     const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
+    const int lane = lane_id();
     bool bad = false;
-    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < nnz; e += gsize) {
-        const int32_t k = keys[e];
-        const int32_t v = vals ? vals[e] : 0;
-        if (k < 0 || k >= n_rows) { bad = true; continue; }
-        if (v < 0 || v >= n_vals) bad = true;
-        atomicAdd(&deg[k], 1);
+    for (int64_t base = (int64_t)blockIdx.x * blockDim.x + (threadIdx.x & ~(kWave - 1)); base < nnz; base += gsize) {
+        const int64_t e = base + lane;                      // wave-uniform loop, lanes past the end idle
+        const bool valid = e < nnz;
+        const int32_t k = valid ? keys[e] : -1;
+        const int32_t v = (valid && vals) ? vals[e] : 0;
+        const bool good = valid && k >= 0 && k < n_rows;
+        if (valid && (!good || v < 0 || v >= n_vals)) bad = true;
+        const int32_t prev = __shfl_up(k, 1, kWave);
+        const u64 gmask = ballot64(good);
+        const bool leader = good && (lane == 0 || !((gmask >> (lane - 1)) & 1) || prev != k);
+        const u64 boundaries = ballot64(leader) | ~gmask;   // a run ends at the next leader or the next bad lane
+        if (leader) {
+            const u64 above = lane == kWave - 1 ? 0 : boundaries >> (lane + 1);
+            const int run = above ? __builtin_ctzll(above) + 1 : kWave - lane;
+            atomicAdd(&deg[k], run);
+        }
     }
-    if (ballot64(bad) != 0 && lane_id() == 0) atomicOr(error, kErrIdRange);
+    if (ballot64(bad) != 0 && lane == 0) atomicOr(error, kErrIdRange);
 }
 
 hipError_t launch_degree_hist(const int32_t *keys, const int32_t *vals, int64_t nnz, int32_t n_rows,
