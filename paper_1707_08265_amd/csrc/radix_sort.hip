@@ -42,12 +42,16 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_scatter(const int32_t *ke
                                                                 int64_t num_tiles)
 {
     __shared__ int wcount[kSortWaves][kRadix];
+    __shared__ int s_delta[kRadix];          // global slot of a key = its slot in the locally sorted tile + this
+    __shared__ int s_wtot[kSortWaves];
+    __shared__ int32_t s_keys[kSortTile], s_vals[kSortTile];
     const int lane = lane_id(), wave = threadIdx.x >> 6;
     for (int i = threadIdx.x; i < kSortWaves * kRadix; i += kSortThreads) (&wcount[0][0])[i] = 0;
     __syncthreads();
 
     // wave w owns keys [base + w*1024, base + (w+1)*1024) of the tile, visited 64 at a time
-    const int64_t wbase = (int64_t)blockIdx.x * kSortTile + (int64_t)wave * (kSortRounds * kWave);
+    const int64_t tbase = (int64_t)blockIdx.x * kSortTile;
+    const int64_t wbase = tbase + (int64_t)wave * (kSortRounds * kWave);
     int32_t key[kSortRounds], val[kSortRounds];
     int rank[kSortRounds];
     const u64 lt = lanemask_lt();
@@ -73,9 +77,20 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_scatter(const int32_t *ke
         rank[r] = c + before;
     }
     __syncthreads();
-    {   // digit d: turn the per-wave counts into per-wave first slots
+    {   // digit d (one per thread): per-wave counts -> first slot of each wave's keys in the locally sorted tile
         const int d = threadIdx.x;
-        int run = table[(int64_t)d * num_tiles + blockIdx.x];
+        int cnt = 0;
+#pragma unroll
+        for (int w = 0; w < kSortWaves; ++w) cnt += wcount[w][d];
+        const int incl = wave_incl_scan(cnt);
+        if (lane == kWave - 1) s_wtot[wave] = incl;
+        __syncthreads();
+        int lbase = incl - cnt;
+#pragma unroll
+        for (int w = 0; w < kSortWaves; ++w)
+            if (w < wave) lbase += s_wtot[w];
+        s_delta[d] = table[(int64_t)d * num_tiles + blockIdx.x] - lbase;
+        int run = lbase;
 #pragma unroll
         for (int w = 0; w < kSortWaves; ++w) {
             const int c = wcount[w][d];
@@ -84,14 +99,23 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_scatter(const int32_t *ke
         }
     }
     __syncthreads();
+    // sort the tile inside LDS, so that the global writes below go out in long contiguous runs per digit
 #pragma unroll
     for (int r = 0; r < kSortRounds; ++r) {
         const int64_t i = wbase + r * kWave + lane;
         if (i < n) {
-            const int pos = wcount[wave][digit_of(key[r], shift)] + rank[r];
-            if (kWriteKeys) keys_out[pos] = key[r];
-            vals_out[pos] = val[r];
+            const int li = wcount[wave][digit_of(key[r], shift)] + rank[r];
+            s_keys[li] = key[r];
+            s_vals[li] = val[r];
         }
+    }
+    __syncthreads();
+    const int count = (int)min((int64_t)kSortTile, n - tbase);
+    for (int li = threadIdx.x; li < count; li += kSortThreads) {
+        const int32_t k = s_keys[li];
+        const int pos = li + s_delta[digit_of(k, shift)];
+        if (kWriteKeys) keys_out[pos] = k;
+        vals_out[pos] = s_vals[li];
     }
 }
 
