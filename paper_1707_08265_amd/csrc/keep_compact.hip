@@ -16,6 +16,8 @@ constexpr int kCThreads = 256;
 constexpr int kCWaves = kCThreads / kWave;
 constexpr int kCRounds = kCompactTile / kCThreads;   // 8 operators per lane
 constexpr int kCWords = kCompactTile / kWave;        // 32 bitmap words per tile
+constexpr int kCountGrid = 2048;                      // workgroups of the count pass (8 per compute unit)
+constexpr int kTransposeAbove = 16;                  // kept operators per 64 above which per-set counting transposes
 
 __device__ __forceinline__ int graph_of(const int64_t *off, int num_graphs, int64_t id)
 {
@@ -30,110 +32,149 @@ __device__ __forceinline__ int graph_of(const int64_t *off, int num_graphs, int6
 template <bool kFromM>
 __global__ __launch_bounds__(kCThreads) void k_keep_count(CompactArgs a)
 {
-    __shared__ int s_wcount[kCWaves];
+    __shared__ int s_wcount[2][kCWaves];
+    __shared__ uint32_t s_q[kCWaves][kWave];
     const GraphView &g = a.g;
     const int lane = lane_id(), wave = threadIdx.x >> 6;
-    const int64_t tile_base = (int64_t)blockIdx.x * kCompactTile;
     const bool batched = g.num_graphs > 1;
+    const int64_t tiles = ((int64_t)g.num_ops + kCompactTile - 1) / kCompactTile;
 
-    // Per-set counters are hot words (every wave of the grid adds to the same 64 of them when there is
-    // one graph), so waves add into one of pq_replicas private copies that a tiny kernel sums up later.
+    // Per-set counters are hot words, so a workgroup walks over many tiles with the counts in
+    // registers and adds them, once, into one of pq_replicas private copies that a tiny kernel sums up.
     int64_t *pq = a.per_query_count;
     int pqs = 1;                  // replica counters sit 64 bytes apart (no two hot words in one line half)
     if (pq && a.pq_part) {
         pqs = kPqStride;
-        pq = a.pq_part + (int64_t)((blockIdx.x * kCWaves + wave) & (a.pq_replicas - 1)) * 64 * g.num_graphs * kPqStride;
+        const int user = batched ? blockIdx.x * kCWaves + wave : blockIdx.x;    // who adds: a wave, or the workgroup
+        pq = a.pq_part + (int64_t)(user & (a.pq_replicas - 1)) * 64 * g.num_graphs * kPqStride;
     }
 
-    int kept = 0;                 // wave-uniform
-    u64 qcount = 0;               // lane q: operators of the current graph whose K has bit q
+    uint32_t qcount = 0;          // lane q: operators of the current graph whose K has bit q
     int cur_graph = 0;
     int64_t g_lo = 0, g_hi = g.num_ops;
     if (batched) {
+        const int64_t tile_base = (int64_t)blockIdx.x * kCompactTile;
         cur_graph = graph_of(g.op_off, g.num_graphs, tile_base < g.num_ops ? tile_base : g.num_ops - 1);
         g_lo = g.op_off[cur_graph];
         g_hi = g.op_off[cur_graph + 1];
     }
 
-    // all loads of the tile are issued before anything is consumed (8 independent loads per lane)
-    u64 kk[kCRounds];
+    int buf = 0;
+    for (int64_t tile = blockIdx.x; tile < tiles; tile += gridDim.x, buf ^= 1) {
+        // a wave owns 512 consecutive operators, 64 per round; all loads of the tile are issued before
+        // anything is consumed (8 independent loads per lane)
+        const int64_t wave_base = tile * kCompactTile + (int64_t)wave * (kCRounds * kWave);
+        int kept = 0;                 // wave-uniform
+        u64 kk[kCRounds];
 #pragma unroll
-    for (int r = 0; r < kCRounds; ++r) {
-        const int64_t o = tile_base + (int64_t)r * kCThreads + threadIdx.x;
-        kk[r] = 0;
-        if (o < g.num_ops) {
-            if (kFromM) {
-                const int32_t b = g.out_rowptr[o], e = g.out_rowptr[o + 1];
-                u64 k = 0;
-                for (int32_t j = b; j < e; ++j) k |= a.M[g.out_idx[j]];
-                kk[r] = k;
-            } else {
-                kk[r] = a.K[o];
-            }
-        }
-    }
-#pragma unroll
-    for (int r = 0; r < kCRounds; ++r) {
-        const int64_t o0 = tile_base + (int64_t)r * kCThreads + wave * kWave;   // first operator of this wave-round
-        const int64_t o = o0 + lane;
-        const bool valid = o < g.num_ops;
-        const u64 k = kk[r];
-        if (valid) {
-            if (kFromM) a.K[o] = k;
-            if (a.op_flag) a.op_flag[o] = (uint8_t)(k != 0);
-        }
-        const u64 word = ballot64(k != 0);
-        if (lane == 0 && o0 < g.num_ops) a.opbits[o0 >> 6] = word;
-        kept += __popcll(word);
-
-        if (pq && word) {
-            const int64_t o_last = min(o0 + kWave, (int64_t)g.num_ops) - 1;
-            if (batched && (o0 < g_lo || o_last >= g_hi)) {
-                // this wave-round leaves the current graph: flush, then either move on or go lane by lane
-                if (qcount) atomicAdd((u64 *)&pq[((int64_t)cur_graph * 64 + lane) * pqs], qcount);
-                qcount = 0;
-                const int ga = graph_of(g.op_off, g.num_graphs, o0);
-                const int gb = graph_of(g.op_off, g.num_graphs, o_last);
-                if (ga == gb) {
-                    cur_graph = ga;
-                    g_lo = g.op_off[ga];
-                    g_hi = g.op_off[ga + 1];
+        for (int r = 0; r < kCRounds; ++r) {
+            const int64_t o = wave_base + r * kWave + lane;
+            kk[r] = 0;
+            if (o < g.num_ops) {
+                if (kFromM) {
+                    const int32_t b = g.out_rowptr[o], e = g.out_rowptr[o + 1];
+                    u64 k = 0;
+                    for (int32_t j = b; j < e; ++j) k |= a.M[g.out_idx[j]];
+                    kk[r] = k;
                 } else {
-                    if (valid && k) {
-                        const int gi = graph_of(g.op_off, g.num_graphs, o);
-                        u64 kk = k;
-                        while (kk) {
-                            const int q = __builtin_ctzll(kk);
-                            kk &= kk - 1;
-                            atomicAdd((u64 *)&pq[((int64_t)gi * 64 + q) * pqs], (u64)1);
-                        }
-                    }
-                    continue;      // wave-uniform: every lane of the round takes this path
-                }
-            }
-            u64 any = wave_or(k);
-            if (__popcll(any) > 6) {
-                // many sets present: transpose the 64x64 bit matrix, lane q then holds column q
-                qcount += (u64)__popcll(wave_transpose64(k));
-            } else {
-                while (any) {                               // wave-uniform loop over the few sets present
-                    const int q = __builtin_ctzll(any);
-                    any &= any - 1;
-                    const int c = __popcll(ballot64((k >> q) & 1));
-                    if (lane == q) qcount += (u64)c;
+                    kk[r] = a.K[o];
                 }
             }
         }
-    }
-    if (pq && qcount) atomicAdd((u64 *)&pq[((int64_t)cur_graph * 64 + lane) * pqs], qcount);
-
-    if (lane == 0) s_wcount[wave] = kept;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int tot = 0;
+        u64 bword = 0;                // lane r < 8: bitmap word of round r
+        u64 fword = 0;                // lane l: bitmap word of round l / 8, the one holding operators 8l .. 8l+7
 #pragma unroll
-        for (int w = 0; w < kCWaves; ++w) tot += s_wcount[w];
-        a.block_counts[blockIdx.x] = tot;
+        for (int r = 0; r < kCRounds; ++r) {
+            const int64_t o0 = wave_base + r * kWave;            // first operator of this wave-round
+            const int64_t o = o0 + lane;
+            const bool valid = o < g.num_ops;
+            const u64 k = kk[r];
+            if (kFromM && valid) a.K[o] = k;
+            const u64 word = ballot64(k != 0);
+            if (lane == r) bword = word;
+            if ((lane >> 3) == r) fword = word;
+            kept += __popcll(word);
+
+            if (pq && word) {
+                const int64_t o_last = min(o0 + kWave, (int64_t)g.num_ops) - 1;
+                if (batched && (o0 < g_lo || o_last >= g_hi)) {
+                    // this wave-round leaves the current graph: flush, then either move on or go lane by lane
+                    if (qcount) atomicAdd((u64 *)&pq[((int64_t)cur_graph * 64 + lane) * pqs], (u64)qcount);
+                    qcount = 0;
+                    const int ga = graph_of(g.op_off, g.num_graphs, o0);
+                    const int gb = graph_of(g.op_off, g.num_graphs, o_last);
+                    if (ga == gb) {
+                        cur_graph = ga;
+                        g_lo = g.op_off[ga];
+                        g_hi = g.op_off[ga + 1];
+                    } else {
+                        if (valid && k) {
+                            const int gi = graph_of(g.op_off, g.num_graphs, o);
+                            u64 rest = k;
+                            while (rest) {
+                                const int q = __builtin_ctzll(rest);
+                                rest &= rest - 1;
+                                atomicAdd((u64 *)&pq[((int64_t)gi * 64 + q) * pqs], (u64)1);
+                            }
+                        }
+                        continue;      // wave-uniform: every lane of the round takes this path
+                    }
+                }
+                if (__popcll(word) > kTransposeAbove) {
+                    // many operators kept: transpose the 64x64 bit matrix, lane q then holds column q
+                    qcount += (uint32_t)__popcll(wave_transpose64(k));
+                } else {
+                    // few kept: broadcast each kept operator's mask, lane q picks its bit out of it
+                    u64 rest = word;
+                    while (rest) {                              // wave-uniform
+                        const int l = __builtin_ctzll(rest);
+                        rest &= rest - 1;
+                        const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)k, l);
+                        const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(k >> 32), l);
+                        qcount += (uint32_t)(((((u64)hi << 32) | lo) >> lane) & 1);
+                    }
+                }
+            }
+        }
+        if (lane < kCRounds && wave_base + lane * kWave < g.num_ops) a.opbits[(wave_base >> 6) + lane] = bword;
+        if (a.op_flag) {
+            // bits 8(l%8) .. 8(l%8)+7 of fword -> eight 0/1 bytes, one 8-byte store per lane
+            const u64 b = (fword >> ((lane & 7) * 8)) & 0xff;
+            u64 bytes = (b * 0x0101010101010101ull) & 0x8040201008040201ull;
+            bytes = ((bytes + 0x7f7f7f7f7f7f7f7full) >> 7) & 0x0101010101010101ull;
+            const int64_t o = wave_base + 8 * lane;
+            uint8_t *dst = a.op_flag + o;
+            if (o + 8 <= g.num_ops && ((uintptr_t)a.op_flag & 7) == 0) {
+                *reinterpret_cast<u64 *>(dst) = bytes;
+            } else {
+                for (int i = 0; i < 8; ++i)
+                    if (o + i < g.num_ops) dst[i] = (uint8_t)(bytes >> (8 * i));
+            }
+        }
+
+        // tile total; the totals are double-buffered, so one barrier per tile is enough
+        if (lane == 0) s_wcount[buf][wave] = kept;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int tot = 0;
+#pragma unroll
+            for (int w = 0; w < kCWaves; ++w) tot += s_wcount[buf][w];
+            a.block_counts[tile] = tot;
+        }
+    }
+
+    if (!pq) return;
+    if (batched) {                // waves may be in different graphs
+        if (qcount) atomicAdd((u64 *)&pq[((int64_t)cur_graph * 64 + lane) * pqs], (u64)qcount);
+        return;
+    }
+    s_q[wave][lane] = qcount;
+    __syncthreads();
+    if (wave == 0) {
+        uint32_t c = 0;
+#pragma unroll
+        for (int w = 0; w < kCWaves; ++w) c += s_q[w][lane];
+        if (c) atomicAdd((u64 *)&pq[(int64_t)lane * pqs], (u64)c);
     }
 }
 
@@ -241,11 +282,12 @@ hipError_t launch_keep_compact(const CompactArgs &a, hipStream_t s, hipEvent_t *
 {
     const int64_t P = a.g.num_ops;
     const int64_t tiles = (P + kCompactTile - 1) / kCompactTile;
+    const int64_t count_grid = tiles < kCountGrid ? tiles : kCountGrid;
     if (tiles > 0) {
         if (a.from_tensor_mask)
-            hipLaunchKernelGGL(k_keep_count<true>, dim3((unsigned)tiles), dim3(kCThreads), 0, s, a);
+            hipLaunchKernelGGL(k_keep_count<true>, dim3((unsigned)count_grid), dim3(kCThreads), 0, s, a);
         else
-            hipLaunchKernelGGL(k_keep_count<false>, dim3((unsigned)tiles), dim3(kCThreads), 0, s, a);
+            hipLaunchKernelGGL(k_keep_count<false>, dim3((unsigned)count_grid), dim3(kCThreads), 0, s, a);
     }
     if (a.per_query_count && a.pq_part)
         hipLaunchKernelGGL(k_reduce_pq, dim3((unsigned)((64 * a.g.num_graphs + 3) / 4)), dim3(256), 0, s, a);
