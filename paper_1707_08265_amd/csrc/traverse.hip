@@ -820,21 +820,104 @@ hipError_t launch_fix_sweep(const GraphView &g, u64 *M, u64 *K, int32_t *changed
 //
 // A tensor's consumers all have larger operator ids than its producer.  Walking one graph's operators
 // from the highest id down, 64 at a time, every operator therefore meets the final M of its outputs,
-// except for dependencies *inside* the group of 64, which the group repeats until nothing changes.
+// except for dependencies *inside* the group of 64.  Those are resolved without touching memory: the
+// group's output tensors go into a small hash table in LDS, every input edge looks its tensor up
+// there, which gives each lane the set of lanes (larger operator ids) it depends on, and the masks
+// are then passed along lane by lane in descending operator order.
 // Each operator is expanded once with all 64 sets' bits (a level-synchronous traversal revisits the
 // operators of such deep, thin graphs tens of times), K needs no atomics (one lane owns an operator),
 // and nothing is queued.  One wave per graph; waves of different graphs never touch the same words.
 // ------------------------------------------------------------------------------------------------
 constexpr int kSweepThreads = 256;
+constexpr int kSweepSlots = 256;                    // hash slots per wave
+constexpr int kSweepMaxKeys = kSweepSlots * 3 / 4;  // output tensors of a group beyond this: iterate instead
+
+struct SweepShared {
+    int32_t key[kSweepSlots];                       // tensor id, -1 = empty
+    uint8_t owner[kSweepSlots];                     // lane of the operator that writes the tensor
+};
+
+__device__ __forceinline__ int sweep_slot(int32_t t) { return (int)(((uint32_t)t * 0x9E3779B1u) >> 24); }
+
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+__device__ __forceinline__ u64 readlane64(u64 v, int l)     // l wave-uniform
+{
+    const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)v, l);
+    const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), l);
+    return ((u64)hi << 32) | lo;
+}
+
+// pushes `bits` of every lane to the operator's inputs; returns the bits that were new to some input
+__device__ __forceinline__ u64 sweep_push(const GraphView &g, u64 *M, int ib, int n_in, u64 bits)
+{
+    u64 fresh = 0;
+    const int max_in = wave_max(bits ? n_in : 0);
+    for (int r0 = 0; r0 < max_in; r0 += 4) {                 // four independent atomics in flight per lane
+        u64 old[4] = {~(u64)0, ~(u64)0, ~(u64)0, ~(u64)0};
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (bits && r0 + c < n_in) old[c] = atomicOr(&M[g.in_idx[ib + r0 + c]], bits);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) fresh |= bits & ~old[c];
+    }
+    return fresh;
+}
+
+// Per-set counts of one graph without a transpose per group: every lane counts, for its own
+// operators, how often each of the 64 bits was set, in bit-sliced form (plane i holds bit i of all
+// 64 counters).  Four masks are folded at a time with full adders; only the resulting carry of
+// weight 4 ripples through the higher planes.
+constexpr int kCountPlanes = 13;                    // counters up to 2^13 - 1 groups of one graph
+
+struct SlicedCount {
+    u64 plane[kCountPlanes];
+    u64 x0, x1, x2;                                 // masks waiting for the fourth
+};
+
+__device__ __forceinline__ void full_add(u64 a, u64 b, u64 c, u64 &sum, u64 &carry)
+{
+    const u64 ab = a ^ b;
+    sum = ab ^ c;
+    carry = (ab & c) | (a & b);
+}
+
+__device__ __forceinline__ void sliced_fold(SlicedCount &c, u64 x3, int planes_used)
+{
+    u64 s, ca, cb, cc;
+    full_add(c.plane[0], c.x0, c.x1, s, ca);
+    full_add(s, c.x2, x3, c.plane[0], cb);
+    full_add(c.plane[1], ca, cb, c.plane[1], cc);
+#pragma unroll
+    for (int i = 2; i < kCountPlanes; ++i) {
+        if (i < planes_used) {                      // wave-uniform
+            const u64 t = c.plane[i] & cc;
+            c.plane[i] ^= cc;
+            cc = t;
+        }
+    }
+}
 
 __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64 *M, u64 *K, int64_t *pq)
 {
+    __shared__ SweepShared s_all[kSweepThreads / kWave];
+    SweepShared &sh = s_all[threadIdx.x >> 6];
     const int lane = lane_id();
     const int gi = blockIdx.x * (kSweepThreads / kWave) + (threadIdx.x >> 6);
     if (gi >= g.num_graphs) return;                          // wave-uniform
     const int64_t o_lo = g.op_off[gi], o_hi = g.op_off[gi + 1];
-    u64 qcount = 0;                                          // lane q: operators of this graph kept for set q
-    for (int64_t top = o_hi; top > o_lo; top -= kWave) {
+    const int n_groups = (int)((o_hi - o_lo + kWave - 1) / kWave);
+    const int planes_used = 33 - __builtin_clz((unsigned)n_groups | 1u);   // bit length of n_groups, plus one
+    SlicedCount cnt;
+#pragma unroll
+    for (int i = 0; i < kCountPlanes; ++i) cnt.plane[i] = 0;
+    cnt.x0 = cnt.x1 = cnt.x2 = 0;
+    int group = 0;
+    for (int64_t top = o_hi; top > o_lo; top -= kWave, ++group) {
         const int64_t o = top - 1 - lane;                    // lane 0 holds the highest id of the group
         const bool valid = o >= o_lo;
         int ob = 0, n_out = 0, ib = 0, n_in = 0;
@@ -845,33 +928,85 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64
             n_in = g.in_rowptr[o + 1] - ib;
         }
         const int max_out = wave_max(n_out);
-        u64 kprev = 0;
-        for (;;) {
-            u64 k = 0;
-            for (int r = 0; r < max_out; ++r)
-                if (r < n_out) k |= load_coherent(&M[g.out_idx[ob + r]]);
-            const u64 nb = k & ~kprev;                       // bits this operator has not pushed to its inputs yet
-            kprev = k;
-            if (ballot64(nb != 0) == 0) break;
-            u64 fresh = 0;                                   // did any input word change?
-            const int max_in = wave_max(nb ? n_in : 0);
-            for (int r0 = 0; r0 < max_in; r0 += 4) {         // four independent atomics in flight per lane
-                u64 old[4] = {~(u64)0, ~(u64)0, ~(u64)0, ~(u64)0};
-#pragma unroll
-                for (int c = 0; c < 4; ++c)
-                    if (nb && r0 + c < n_in) old[c] = atomicOr(&M[g.in_idx[ib + r0 + c]], nb);
-#pragma unroll
-                for (int c = 0; c < 4; ++c) fresh |= nb & ~old[c];
+        u64 k = 0;
+        if (wave_sum(n_out) <= kSweepMaxKeys) {
+            for (int i = lane; i < kSweepSlots; i += kWave) sh.key[i] = -1;
+            wave_lds_sync();
+            for (int r = 0; r < max_out; ++r) {
+                if (r < n_out) {
+                    const int32_t t = g.out_idx[ob + r];
+                    k |= load_coherent(&M[t]);
+                    int slot = sweep_slot(t);
+                    while (atomicCAS(&sh.key[slot], -1, t) != -1) slot = (slot + 1) & (kSweepSlots - 1);
+                    sh.owner[slot] = (uint8_t)lane;
+                }
             }
-            if (ballot64(fresh != 0) == 0) break;            // no word changed: a re-read would find nothing new
+            wave_lds_sync();
+            u64 feeds = 0;                                   // lanes whose operators write a tensor this lane's operator reads
+            const int max_in = wave_max(n_in);
+            for (int r = 0; r < max_in; ++r) {
+                if (r < n_in) {
+                    const int32_t t = g.in_idx[ib + r];
+                    for (int slot = sweep_slot(t);; slot = (slot + 1) & (kSweepSlots - 1)) {
+                        const int32_t key = sh.key[slot];
+                        if (key == -1) break;
+                        if (key == t) {
+                            const int b = sh.owner[slot];
+                            if (b > lane) feeds |= (u64)1 << b;
+                        }
+                    }
+                }
+            }
+            u64 live = ballot64(feeds != 0);
+            while (live) {                                   // ascending lanes = descending operator ids
+                const int src = __builtin_ctzll(live);
+                live &= live - 1;
+                const u64 ks = readlane64(k, src);           // final: every lane that feeds lane src came earlier
+                if (ks == 0) continue;
+                if (__builtin_amdgcn_inverse_ballot_w64(readlane64(feeds, src))) k |= ks;
+            }
+            const u64 fresh = sweep_push(g, M, ib, n_in, k);
+            // the atomics' results must have arrived before the next group reads M
+            asm volatile("" ::"v"((uint32_t)fresh), "v"((uint32_t)(fresh >> 32)) : "memory");
+            wave_lds_sync();                                 // the table is cleared only after every lane is done with it
+        } else {
+            // too many output tensors for the table: repeat the group until nothing changes
+            u64 kprev = 0;
+            for (;;) {
+                k = 0;
+                for (int r = 0; r < max_out; ++r)
+                    if (r < n_out) k |= load_coherent(&M[g.out_idx[ob + r]]);
+                const u64 nb = k & ~kprev;                   // bits this operator has not pushed to its inputs yet
+                kprev = k;
+                if (ballot64(nb != 0) == 0) break;
+                const u64 fresh = sweep_push(g, M, ib, n_in, nb);
+                if (ballot64(fresh != 0) == 0) break;        // no word changed: a re-read would find nothing new
+            }
+            k = kprev;
         }
-        if (valid) K[o] = kprev;
+        if (valid) K[o] = k;
         if (pq) {
-            const u64 col = wave_transpose64(kprev);         // lane q: bit q of the 64 operators' masks
-            qcount += (u64)__popcll(col);
+            switch (group & 3) {                             // wave-uniform
+            case 0: cnt.x0 = k; break;
+            case 1: cnt.x1 = k; break;
+            case 2: cnt.x2 = k; break;
+            default: sliced_fold(cnt, k, planes_used); break;
+            }
         }
     }
-    if (pq) pq[(int64_t)gi * 64 + lane] = (int64_t)qcount;
+    if (pq) {
+        if (group & 3) {                                     // masks still waiting: fold them with zeros for the rest
+            if ((group & 3) < 3) cnt.x2 = 0;
+            if ((group & 3) < 2) cnt.x1 = 0;
+            sliced_fold(cnt, 0, planes_used);
+        }
+        u64 total = 0;                                       // lane q: operators of this graph kept for set q
+#pragma unroll
+        for (int i = 0; i < kCountPlanes; ++i)
+            if (i < planes_used)                             // wave-uniform
+                total += (u64)__popcll(wave_transpose64(cnt.plane[i])) << i;
+        pq[(int64_t)gi * 64 + lane] = (int64_t)total;
+    }
 }
 
 hipError_t launch_sweep_graphs(const GraphView &g, u64 *M, u64 *K, int64_t *per_query_count, hipStream_t s)
