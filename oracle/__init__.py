@@ -1,10 +1,11 @@
-"""ctypes front end of the CPU oracle (``forward_prune.c``) -- TEST INFRASTRUCTURE.
+"""ctypes front end of the CPU oracle (``forward_prune.c``, ``inplace.c``) -- TEST INFRASTRUCTURE.
 
 Only tests, the smoke check and the bench's ``cpu_baseline`` leg may import this package; the
 product path never does.  It imports nothing from the GPU package.
 
-Every function here is a thin marshalling layer: all arithmetic is in the C file, which follows
-Algorithm 1, the removal rule of Sec. 2.1 and the creation-order rule of Sec. 3.2 of the paper.
+Every function here is a thin marshalling layer: all arithmetic is in the C files, which follow
+Algorithm 1, the removal rule of Sec. 2.1, the creation-order rule of Sec. 3.2 and Algorithm 3
+(Sec. 2.4) of the paper.
 """
 from __future__ import annotations
 
@@ -17,17 +18,17 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "forward_prune.c")
+_SRCS = [os.path.join(_HERE, "forward_prune.c"), os.path.join(_HERE, "inplace.c")]
 _LIB = os.path.join(_HERE, "liboracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (plain -O2, no threading)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(f) for f in _SRCS):
         tmp = _LIB + f".tmp{os.getpid()}"
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fPIC", "-shared",
-                               _SRC, "-o", tmp])
+                               *_SRCS, "-o", tmp])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -38,6 +39,7 @@ def _load():
         build()
         _lib = ctypes.CDLL(_LIB)
         _lib.orc_certificate.restype = ctypes.c_int64
+        _lib.orc_child_sets.restype = ctypes.c_int64
     return _lib
 
 
@@ -168,3 +170,32 @@ def forward_prune(adj: Adjacency, num_sets: int, tgt_rowptr, tgt_idx, num_graphs
     K, flag = keep(adj, M)
     kept_ops, kept_masks, kept_count, pq = compact(K, num_graphs, graph_op_offsets)
     return PruneResult(M, K, flag, kept_ops, kept_masks, kept_count, pq, edges)
+
+
+def child_sets(adj: Adjacency, K: np.ndarray, select: int = 2**64 - 1):
+    """Child(x) of every tensor in the graph left by the prune (Sec. 2.2 graph model, Sec. 2.4):
+    (child_rowptr, child_idx, in_graph)."""
+    K = _c(K, np.uint64)
+    cap = 0
+    kept = (K & np.uint64(select)) != 0
+    din = np.diff(adj.in_rowptr).astype(np.int64)
+    dout = np.diff(adj.out_rowptr).astype(np.int64)
+    cap = int((din[kept] * dout[kept]).sum())
+    child_rowptr = np.empty(adj.num_tensors + 1, np.int32)
+    child_idx = np.empty(max(cap, 1), np.int32)
+    in_graph = np.empty(adj.num_tensors, np.uint8)
+    n = _load().orc_child_sets(i64(adj.num_ops), i64(adj.num_tensors), _p(adj.in_rowptr), _p(adj.in_idx),
+                               _p(adj.out_rowptr), _p(adj.out_idx), _p(K), ctypes.c_uint64(select),
+                               _p(child_rowptr), _p(child_idx), i64(cap), _p(in_graph))
+    if n < 0:
+        raise MemoryError("orc_child_sets")
+    return child_rowptr, child_idx[:n].copy(), in_graph
+
+
+def inplace(adj: Adjacency, K: np.ndarray, select: int = 2**64 - 1) -> np.ndarray:
+    """Algorithm 3 on the pruned graph: rename dictionary RD as an int32 array over tensors
+    (ancestor id, -1 for tensors outside the graph)."""
+    child_rowptr, child_idx, in_graph = child_sets(adj, K, select)
+    RD = np.empty(adj.num_tensors, np.int32)
+    _load().orc_inplace(i64(adj.num_tensors), _p(child_rowptr), _p(child_idx), _p(in_graph), _p(RD))
+    return RD

@@ -125,3 +125,58 @@ def naive_forward_marks(ops, num_tensors):
                         marked.add(y)
                         changed = True
     return marked
+
+
+def load_inplace_examples():
+    """Hand-worked cases for Algorithm 3: list of dicts with graph, op_mask, select, expected RD."""
+    with open(os.path.join(GOLDEN, "inplace_examples.json")) as f:
+        ex = json.load(f)
+    out = []
+    for c in ex["cases"]:
+        names = c["tensors"]
+        tid = {n: i for i, n in enumerate(names)}
+        ops = [([tid[t] for t in op["in"]], [tid[t] for t in op["out"]]) for op in c["ops"]]
+        g = graph_from_ops(ops, len(names), c["name"])
+        rd = np.asarray([-1 if c["rename"][n] is None else tid[c["rename"][n]] for n in names], np.int32)
+        out.append(dict(name=c["name"], graph=g, K=np.asarray(c["op_mask"], np.uint64), select=int(c["select"]),
+                        rename=rd))
+    return out
+
+
+def single_child_links(g: gg.Graph, kept):
+    """(in_graph, link) of the pruned graph, from the definition: link[x] = c when the surviving
+    operators that read x write exactly one distinct tensor c, else -1."""
+    children = [set() for _ in range(g.num_tensors)]
+    in_graph = np.zeros(g.num_tensors, bool)
+    outs = [[] for _ in range(g.num_ops)]
+    for o, t in zip(g.out_op.tolist(), g.out_tensor.tolist()):
+        outs[o].append(t)
+    for o, t in zip(g.out_op.tolist(), g.out_tensor.tolist()):
+        if kept[o]:
+            in_graph[t] = True
+    for o, t in zip(g.in_op.tolist(), g.in_tensor.tolist()):
+        if kept[o]:
+            in_graph[t] = True
+            children[t].update(outs[o])
+    link = np.asarray([next(iter(c)) if len(c) == 1 else -1 for c in children], np.int64)
+    return in_graph, link
+
+
+def rename_by_reachability(g: gg.Graph, kept):
+    """What Algorithm 3 must produce on an acyclic graph, stated without walking in node order: the
+    ancestor of v is the smallest id among the nodes from which v is reached over single-child links
+    (v included).  Proof idea: that node is not entered by any earlier walk (an earlier start that
+    reached it would also reach v), so it starts its own walk, and nothing on its way to v has been
+    entered before, for the same reason."""
+    in_graph, link = single_child_links(g, kept)
+    rd = np.full(g.num_tensors, -1, np.int64)
+    for u in range(g.num_tensors):          # walk down from every node, keep the minimum start per node
+        if not in_graph[u]:
+            continue
+        v, steps = u, 0
+        while v != -1 and steps <= g.num_tensors:
+            if rd[v] == -1 or u < rd[v]:
+                rd[v] = u
+            v = link[v]
+            steps += 1
+    return rd.astype(np.int32)
