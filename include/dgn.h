@@ -216,6 +216,32 @@ int dgn_keep_compact(const dgn_graph *g, const uint64_t *tensor_mask_in, uint64_
                      uint8_t *op_flag, int32_t *kept_ops, uint64_t *kept_masks, int64_t *kept_count,
                      int64_t *per_query_count, void *scratch, size_t scratch_bytes, dgn_stream stream);
 
+/* ---- In-place structures ----------------------------------------------------------------- */
+
+/* Scratch bytes dgn_inplace needs for this graph. */
+int dgn_inplace_workspace(const dgn_graph *g, size_t *scratch_bytes);
+
+/* Algorithm 3 (Sec. 2.4) on the graph left by the prune: the rename dictionary.
+ *
+ * The nodes are the tensors that a surviving operator reads or writes; an operator survives when
+ * (op_mask[o] & select) != 0, so select = 1 << q gives the graph pruned for target set q and
+ * select = ~0 the union over all sets.  Child(x) = the distinct tensors written by surviving
+ * operators that read x.  Nodes are taken in ascending id; a node not yet renamed becomes its own
+ * ancestor and passes that ancestor on while the current node has exactly one child.
+ *
+ *   op_mask [num_ops]      in : K as written by dgn_prune / dgn_keep_compact (DEVICE).
+ *   rename  [num_tensors]  out: ancestor id of every node, -1 for tensors outside the graph (DEVICE).
+ *   renamed_count          out: int64 [1], nodes whose ancestor is another tensor (DEVICE); may be NULL.
+ *   rounds_out             out: HOST int32, pointer-doubling rounds that were run; may be NULL.
+ *
+ * The pruned graph must be acyclic (tensor ids need not be topological); on a cyclic one the call
+ * still ends, after 32 rounds, with unspecified ancestors for the nodes on the cycle.  Kernels run on
+ * `stream`; the call reads one status word back every four rounds and has synchronised the stream
+ * when it returns.  For a packed batch the graphs are handled together (ids are global). */
+int dgn_inplace(const dgn_graph *g, const uint64_t *op_mask, uint64_t select, int32_t *rename,
+                int64_t *renamed_count, void *scratch, size_t scratch_bytes, int32_t *rounds_out,
+                dgn_stream stream);
+
 /* ---- misc ---------------------------------------------------------------------------------- */
 const char *dgn_strerror(int code);
 int dgn_version(void);

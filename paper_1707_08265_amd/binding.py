@@ -31,7 +31,8 @@ DGN_ERR_INTERNAL = -10
 EXPORTS = [
     "dgn_graph_build_workspace", "dgn_graph_build", "dgn_graph_from_csr_workspace", "dgn_graph_from_csr",
     "dgn_graph_get_csr", "dgn_graph_get_sizes", "dgn_graph_destroy", "dgn_prune_workspace", "dgn_prune",
-    "dgn_keep_compact", "dgn_strerror", "dgn_version", "dgn_last_hip_error",
+    "dgn_keep_compact", "dgn_inplace_workspace", "dgn_inplace", "dgn_strerror", "dgn_version",
+    "dgn_last_hip_error",
 ]
 
 
@@ -90,6 +91,9 @@ def _load() -> ctypes.CDLL:
     lib.dgn_prune.argtypes = [c_void_p, c_int32, c_int64] + [c_void_p] * 9 + [c_void_p, c_size_t,
                               POINTER(dgn_options), POINTER(dgn_stats), c_void_p]
     lib.dgn_keep_compact.argtypes = [c_void_p] + [c_void_p] * 7 + [c_void_p, c_size_t, c_void_p]
+    lib.dgn_inplace_workspace.argtypes = [c_void_p, POINTER(c_size_t)]
+    lib.dgn_inplace.argtypes = [c_void_p, c_void_p, ctypes.c_uint64, c_void_p, c_void_p, c_void_p, c_size_t,
+                                POINTER(c_int32), c_void_p]
     return lib
 
 
@@ -229,6 +233,20 @@ def dgn_keep_compact(handle, tensor_mask_in, op_mask, op_flag, kept_ops, kept_ma
                                  scratch_bytes, _stream(stream))
 
 
+def dgn_inplace_workspace(handle):
+    s = c_size_t(0)
+    rc = _lib.dgn_inplace_workspace(handle, ctypes.byref(s))
+    return rc, s.value
+
+
+def dgn_inplace(handle, op_mask, select, rename, renamed_count, scratch, scratch_bytes, stream=None):
+    """Returns (return code, pointer-doubling rounds run)."""
+    rounds = c_int32(0)
+    rc = _lib.dgn_inplace(handle, _dp(op_mask), ctypes.c_uint64(select & (2**64 - 1)), _dp(rename),
+                          _dp(renamed_count), _dp(scratch), scratch_bytes, ctypes.byref(rounds), _stream(stream))
+    return rc, rounds.value
+
+
 # ------------------------------------------------------------------------------------------------
 # Buffer owners (allocation and marshalling only -- no arithmetic of the method happens here)
 # ------------------------------------------------------------------------------------------------
@@ -355,3 +373,24 @@ class PruneBuffers:
         return dict(tensor_mask=u(self.tensor_mask), op_mask=u(self.op_mask), op_flag=self.op_flag.cpu().numpy(),
                     kept_ops=self.kept_ops[:n].cpu().numpy(), kept_masks=u(self.kept_masks[:n]),
                     kept_count=self.kept_count.cpu().numpy(), per_query_count=self.per_query_count.cpu().numpy())
+
+
+class InplaceBuffers:
+    """Caller-owned buffers of one ``dgn_inplace`` call (rename dictionary, count, scratch)."""
+
+    def __init__(self, graph: DeviceGraph, device=None):
+        dev = graph.graph_mem.device if device is None else torch.device(device)
+        rc, sb = dgn_inplace_workspace(graph.handle)
+        _check(rc, "dgn_inplace_workspace")
+        self.graph = graph
+        self.scratch_bytes = sb
+        self.scratch = torch.empty(sb, dtype=torch.uint8, device=dev)
+        self.rename = torch.empty(graph.num_tensors, dtype=torch.int32, device=dev)
+        self.renamed_count = torch.empty(1, dtype=torch.int64, device=dev)
+        self.rounds = 0
+
+    def run(self, op_mask, select: int = 2**64 - 1, stream=None) -> int:
+        """``op_mask``: device int64 tensor holding K (as written by ``PruneBuffers.prune``)."""
+        rc, self.rounds = dgn_inplace(self.graph.handle, op_mask, select, self.rename, self.renamed_count,
+                                      self.scratch, self.scratch_bytes, stream)
+        return rc

@@ -724,4 +724,38 @@ int dgn_keep_compact(const dgn_graph *g, const uint64_t *tensor_mask_in, uint64_
     return DGN_OK;
 }
 
+int dgn_inplace_workspace(const dgn_graph *g, size_t *scratch_bytes)
+{
+    if (!g || !scratch_bytes) return DGN_ERR_NULL_PTR;
+    *scratch_bytes = inplace_scratch_bytes(g->T);
+    return DGN_OK;
+}
+
+int dgn_inplace(const dgn_graph *g, const uint64_t *op_mask, uint64_t select, int32_t *rename, int64_t *renamed_count,
+                void *scratch, size_t scratch_bytes, int32_t *rounds_out, dgn_stream stream)
+{
+    if (!g || !scratch) return DGN_ERR_NULL_PTR;
+    if ((g->P > 0 && !op_mask) || (g->T > 0 && !rename)) return DGN_ERR_NULL_PTR;
+    if (scratch_bytes < inplace_scratch_bytes(g->T)) return DGN_ERR_WORKSPACE_TOO_SMALL;
+    if (((uintptr_t)scratch | (uintptr_t)op_mask | (uintptr_t)renamed_count) & 7) return DGN_ERR_INVALID_ARG;
+    if ((uintptr_t)rename & 3) return DGN_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const InplaceBuffers B = inplace_buffers(scratch, g->T);
+    const int grid = g->num_cus * 8;
+    DGN_HIP(launch_inplace_setup(g->v, reinterpret_cast<const u64 *>(op_mask), select, rename, renamed_count, B, grid, s));
+    void *pin = nullptr;
+    int rc = pinned_buffer(&pin);
+    if (rc != DGN_OK) return rc;
+    int round = 0;
+    for (;;) {                                       // four rounds per read-back of the "still alive" word
+        for (int i = 0; i < 4 && round < kInplaceMaxRounds; ++i, ++round)
+            DGN_HIP(launch_inplace_round(round, rename, renamed_count, B, grid, s));
+        DGN_HIP(hipMemcpyAsync(pin, B.counters + round, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+        DGN_HIP(hipStreamSynchronize(s));
+        if (*static_cast<int32_t *>(pin) == 0 || round >= kInplaceMaxRounds) break;
+    }
+    if (rounds_out) *rounds_out = round;
+    return DGN_OK;
+}
+
 }  // extern "C"

@@ -228,4 +228,21 @@ struct CompactArgs {
 // ev (may be NULL): three events recorded after the count, scan and scatter passes.
 hipError_t launch_keep_compact(const CompactArgs &a, hipStream_t s, hipEvent_t *ev = nullptr);
 
+// In-place structures (Algorithm 3).  counters: [0] = number of nodes with exactly one child,
+// [1 + r] = doubling round r left some jump pointer alive.
+constexpr int kInplaceMaxRounds = 32;               // 2^32 links: longer than any chain of int32 ids
+struct InplaceBuffers {
+    int2 *child_range;                              // smallest / largest child id per tensor
+    int32_t *J[2];                                  // jump pointers, double buffered
+    int32_t *linkers;                               // nodes with exactly one child
+    int32_t *counters;
+};
+size_t inplace_scratch_bytes(int64_t T);
+InplaceBuffers inplace_buffers(void *scratch, int64_t T);
+// init, child ranges, links (the state before round 0)
+hipError_t launch_inplace_setup(const GraphView &g, const u64 *K, u64 select, int32_t *rename, int64_t *renamed_count,
+                                const InplaceBuffers &b, int grid_blocks, hipStream_t s);
+hipError_t launch_inplace_round(int round, int32_t *rename, int64_t *renamed_count, const InplaceBuffers &b,
+                                int grid_blocks, hipStream_t s);
+
 }  // namespace dgn
