@@ -149,6 +149,25 @@ def main():
             log(f"level {lv}: frontier={trace[lv, 0]} expanded={trace[lv, 1]} theta={trace[lv, 2]} us_since_prev={dt:.1f}")
     out = buf.to_host()
     P, T = g.num_ops, g.num_tensors
+
+    # ---- in-place pass on the pruned graph (Algorithm 3), timed on its own, not part of `value` ---
+    ip = d.InplaceBuffers(dg)
+    ip_ms = []
+    for _ in range(1 + max(3, min(args.steps, 10))):
+        torch.cuda.synchronize()
+        tb = time.perf_counter()
+        rc = ip.run(buf.op_mask)
+        torch.cuda.synchronize()
+        ip_ms.append((time.perf_counter() - tb) * 1e3)
+        assert rc == 0, d.dgn_strerror(rc)
+    ip_ms = float(np.median(ip_ms[1:]))
+    ip_rename = ip.rename.cpu().numpy()
+    inplace = {"ms": round(ip_ms, 4), "rounds": int(ip.rounds), "renamed_tensors": int(ip.renamed_count.item()),
+               "graph_tensors": int((ip_rename >= 0).sum()), "select": "all sets (union graph)",
+               "cpu_oracle_ms": None, "bit_exact_vs_oracle": None}
+    log(f"in-place pass: {ip_ms:.3f} ms, {inplace['rounds']} rounds, {inplace['renamed_tensors']} of "
+        f"{inplace['graph_tensors']} tensors renamed")
+    del ip
     P_k = int(out["kept_count"][0])
     T_c = int(np.count_nonzero(out["tensor_mask"]))
     fan_in = np.bincount(g.in_op, minlength=P)
@@ -209,6 +228,13 @@ def main():
                      ("tensor_mask", "op_mask", "op_flag", "kept_ops", "kept_masks", "kept_count", "per_query_count"))
         log(f"oracle: {cpu_s:.2f}s -> {cpu['value']} GTEPS on 1 core; GPU output bit-exact vs oracle: {parity}")
         assert parity, "GPU result differs from the oracle"
+        tb = time.perf_counter()
+        ref_rd = orc.inplace(adj, ref.op_mask)
+        inplace["cpu_oracle_ms"] = round((time.perf_counter() - tb) * 1e3, 1)
+        inplace["bit_exact_vs_oracle"] = bool(np.array_equal(ip_rename, ref_rd))
+        log(f"oracle in-place pass: {inplace['cpu_oracle_ms']:.0f} ms; GPU rename dictionary bit-exact: "
+            f"{inplace['bit_exact_vs_oracle']}")
+        assert inplace["bit_exact_vs_oracle"], "GPU rename dictionary differs from the oracle"
 
     line = {
         "metric": "pruned edges/sec (GTEPS), 64-query batched prune", "value": round(gteps, 2), "unit": "GTEPS",
@@ -222,6 +248,7 @@ def main():
         "cpu_baseline": cpu,
         "phase_ms": {k: round(v, 4) for k, v in ph.items()},
         "build_ms": round(build_ms, 3),
+        "inplace": inplace,
         "build_plus_prune_gteps": round(E / ((build_ms + ms_per_step) * 1e-3) / 1e9, 2),
         "result": {"kept_ops": P_k, "coloured_tensors": T_c, "kept_in_edges": E_k, "kept_out_edges": Eo_k,
                    "levels": int(st.levels), "tensor_visits": int(st.tensor_visits),

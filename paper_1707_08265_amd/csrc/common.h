@@ -232,7 +232,7 @@ hipError_t launch_keep_compact(const CompactArgs &a, hipStream_t s, hipEvent_t *
 // [1 + r] = doubling round r left some jump pointer alive.
 constexpr int kInplaceMaxRounds = 32;               // 2^32 links: longer than any chain of int32 ids
 struct InplaceBuffers {
-    int2 *child_range;                              // smallest / largest child id per tensor
+    int32_t *child;                                 // the only child of a tensor, -1 none, -2 several
     int32_t *J[2];                                  // jump pointers, double buffered
     int32_t *linkers;                               // nodes with exactly one child
     int32_t *counters;

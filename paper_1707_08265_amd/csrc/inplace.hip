@@ -13,79 +13,163 @@
 //
 // Nodes are tensors; Child(x) = distinct tensors written by surviving operators that read x, where an
 // operator survives when (K[o] & select) != 0.  "Exactly one child" is decided without building the
-// sets: the smallest and the largest child id of x are kept with atomicMin / atomicMax and compared.
+// sets: child[x] holds the only child seen so far and is set to "many" by whoever brings a second one.
 #include "common.h"
 
 namespace dgn {
 
 constexpr int kIpThreads = 256;
-constexpr int kNoChildLo = 0x7fffffff;
+constexpr int kManyChildren = -2;                   // child[x]: -1 none yet, >= 0 the only child so far
 
-__global__ __launch_bounds__(kIpThreads) void k_inplace_init(int32_t *rename, int2 *child_range, int64_t T,
+// p[0..n) = -1, with 16-byte stores over the aligned bulk
+__device__ __forceinline__ void fill_minus_one(int32_t *p, int64_t n, int64_t gtid, int64_t gsize)
+{
+    int64_t head = (int64_t)(((16 - ((uintptr_t)p & 15)) & 15) >> 2);
+    if (head > n) head = n;
+    if (gtid < head) p[gtid] = -1;
+    int4 *bulk = reinterpret_cast<int4 *>(p + head);
+    const int64_t quads = (n - head) >> 2;
+    const int4 m = make_int4(-1, -1, -1, -1);
+    for (int64_t i = gtid; i < quads; i += gsize) bulk[i] = m;
+    const int64_t done = head + (quads << 2);
+    if (gtid < n - done) p[done + gtid] = -1;
+}
+
+__global__ __launch_bounds__(kIpThreads) void k_inplace_init(int32_t *rename, int32_t *child, int64_t T,
                                                               int32_t *counters, int num_counters,
                                                               int64_t *renamed_count)
 {
+    const int64_t gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; x < T; x += gsize) {
-        rename[x] = -1;
-        child_range[x] = make_int2(kNoChildLo, -1);
-    }
+    fill_minus_one(rename, T, gtid, gsize);
+    fill_minus_one(child, T, gtid, gsize);
     if (blockIdx.x == 0) {
         if ((int)threadIdx.x < num_counters) counters[threadIdx.x] = 0;
         if (threadIdx.x == 0 && renamed_count) *renamed_count = 0;
     }
 }
 
-// Every surviving operator marks the tensors it touches as nodes of the graph (rename[x] = x) and
-// offers its smallest / largest output as child of each of its inputs.
-__global__ __launch_bounds__(kIpThreads) void k_inplace_children(GraphView g, const u64 *K, u64 select,
-                                                                  int32_t *rename, int2 *child_range)
+// One surviving operator: the tensors it touches become nodes of the graph (rename[x] = x), and each
+// input learns the operator's output(s) as child.  child[x] only moves -1 -> id -> kManyChildren.
+__device__ __forceinline__ void offer_children(const GraphView &g, int64_t o, int32_t *rename, int32_t *child)
 {
-    const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < g.num_ops; o += gsize) {
-        if ((K[o] & select) == 0) continue;
-        int lo = kNoChildLo, hi = -1;
-        for (int32_t e = g.out_rowptr[o]; e < g.out_rowptr[o + 1]; ++e) {
-            const int32_t u = g.out_idx[e];
-            rename[u] = u;
-            lo = min(lo, u);
-            hi = max(hi, u);
+    int lo = 0x7fffffff, hi = -1;
+    for (int32_t e = g.out_rowptr[o]; e < g.out_rowptr[o + 1]; ++e) {
+        const int32_t u = g.out_idx[e];
+        rename[u] = u;
+        lo = min(lo, u);
+        hi = max(hi, u);
+    }
+    for (int32_t e = g.in_rowptr[o]; e < g.in_rowptr[o + 1]; ++e) {
+        const int32_t x = g.in_idx[e];
+        rename[x] = x;
+        if (hi < 0) continue;                               // an operator without outputs offers nothing
+        if (lo != hi) {                                     // two distinct children at once
+            __hip_atomic_store(&child[x], kManyChildren, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            continue;
         }
-        for (int32_t e = g.in_rowptr[o]; e < g.in_rowptr[o + 1]; ++e) {
-            const int32_t x = g.in_idx[e];
-            rename[x] = x;
-            if (hi >= 0) {
-                atomicMin(&child_range[x].x, lo);
-                atomicMax(&child_range[x].y, hi);
-            }
-        }
+        const int32_t seen = child[x];                      // a stale value only costs an atomic
+        if (seen == lo || seen == kManyChildren) continue;
+        const int32_t old = atomicCAS(&child[x], -1, lo);
+        if (old != -1 && old != lo && old != kManyChildren)
+            __hip_atomic_store(&child[x], kManyChildren, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
-// link[x] = the only child of x, or -1; nodes with a link are listed.  Both jump buffers are set for
-// every node, so that a later round may read the pointer of a node that has no link.
-__global__ __launch_bounds__(kIpThreads) void k_inplace_links(const int32_t *rename, const int2 *child_range,
+// Surviving operators can be a few percent of all: a wave reads 512 masks, packs the ids of the
+// survivors into LDS and works on them 64 at a time, so that the dependent loads of the expansion
+// run with all lanes busy.
+constexpr int kIpWaves = kIpThreads / kWave;
+constexpr int kMaskRounds = 8;                      // masks per lane and step
+
+__global__ __launch_bounds__(kIpThreads) void k_inplace_children(GraphView g, const u64 *K, u64 select,
+                                                                  int32_t *rename, int32_t *child)
+{
+    __shared__ int32_t s_ops[kIpWaves][kWave * (kMaskRounds + 1)];
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    int32_t *ops = s_ops[wave];
+    int count = 0;                                          // wave-uniform
+    const int64_t step = (int64_t)kWave * kMaskRounds;
+    const int64_t steps = ((int64_t)g.num_ops + step - 1) / step;
+    const int64_t wave_id = (int64_t)blockIdx.x * kIpWaves + wave, num_waves = (int64_t)gridDim.x * kIpWaves;
+    for (int64_t st = wave_id; st < steps; st += num_waves) {
+        u64 k[kMaskRounds];
+#pragma unroll
+        for (int r = 0; r < kMaskRounds; ++r) {
+            const int64_t o = st * step + r * kWave + lane;
+            k[r] = o < g.num_ops ? K[o] : 0;
+        }
+#pragma unroll
+        for (int r = 0; r < kMaskRounds; ++r) {
+            const bool kept = (k[r] & select) != 0;
+            const u64 m = ballot64(kept);
+            if (kept) ops[count + __popcll(m & lanemask_lt())] = (int32_t)(st * step + r * kWave + lane);
+            count += __popcll(m);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        while (count >= kWave) {
+            count -= kWave;
+            offer_children(g, ops[count + lane], rename, child);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+    if (lane < count) offer_children(g, ops[lane], rename, child);
+}
+
+// link[x] = the only child of x, or -1; nodes with a link are listed (gathered per workgroup in LDS, so
+// that the list's counter is bumped once per thousand entries, not once per wave).  Both jump buffers
+// are set for every node, so that a later round may read the pointer of a node that has no link.
+constexpr int kLinkItems = 4;                       // independent loads per thread and step
+constexpr int kLinkTile = kIpThreads * kLinkItems;
+
+__global__ __launch_bounds__(kIpThreads) void k_inplace_links(const int32_t *rename, const int32_t *child,
                                                                int64_t T, int32_t *J0, int32_t *J1,
                                                                int32_t *linkers, int32_t *num_linkers)
 {
+    __shared__ int32_t s_list[2 * kLinkTile];
+    __shared__ int s_count, s_base;
     const int lane = lane_id();
-    const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
-    const int64_t rounds = (T + gsize - 1) / gsize;
-    for (int64_t r = 0; r < rounds; ++r) {                  // whole waves stay in the loop (ballot below)
-        const int64_t x = r * gsize + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-        int32_t link = -1;
-        if (x < T && rename[x] >= 0) {
-            const int2 c = child_range[x];
-            if (c.x == c.y) link = c.x;
-            J0[x] = link;
-            J1[x] = -1;
+    if (threadIdx.x == 0) s_count = 0;
+    __syncthreads();
+    const int64_t tiles = (T + kLinkTile - 1) / kLinkTile;
+    for (int64_t t = blockIdx.x; t < tiles; t += gridDim.x) {          // whole workgroups stay in the loop
+        int32_t r[kLinkItems];
+#pragma unroll
+        for (int k = 0; k < kLinkItems; ++k) {
+            const int64_t x = t * kLinkTile + k * kIpThreads + threadIdx.x;
+            r[k] = x < T ? rename[x] : -1;
         }
-        const u64 has = ballot64(link >= 0);
-        if (has) {
-            int base = 0;
-            if (lane == 0) base = atomicAdd(num_linkers, __popcll(has));
-            base = __shfl(base, 0, kWave);
-            if (link >= 0) linkers[base + __popcll(has & lanemask_lt())] = (int32_t)x;
+#pragma unroll
+        for (int k = 0; k < kLinkItems; ++k) {
+            const int64_t x = t * kLinkTile + k * kIpThreads + threadIdx.x;
+            int32_t link = -1;
+            if (r[k] >= 0) {
+                const int32_t c = child[x];
+                if (c >= 0) link = c;
+                J0[x] = link;
+                J1[x] = -1;
+            }
+            const u64 has = ballot64(link >= 0);
+            if (has) {
+                int base = 0;
+                if (lane == 0) base = atomicAdd(&s_count, __popcll(has));
+                base = __shfl(base, 0, kWave);
+                if (link >= 0) s_list[base + __popcll(has & lanemask_lt())] = (int32_t)x;
+            }
+        }
+        __syncthreads();                                    // this tile's entries are in the list
+        const int n = s_count;                              // at most one tile's worth is added per step
+        __syncthreads();                                    // everyone has read the count before it changes again
+        if (n >= kLinkTile || t + gridDim.x >= tiles) {     // flush: the next tile needs the room, or this was the last
+            if (threadIdx.x == 0) {
+                s_base = n ? atomicAdd(num_linkers, n) : 0;
+                s_count = 0;
+            }
+            __syncthreads();
+            for (int i = threadIdx.x; i < n; i += kIpThreads) linkers[s_base + i] = s_list[i];
+            __syncthreads();
         }
     }
 }
@@ -119,7 +203,7 @@ __global__ __launch_bounds__(kIpThreads) void k_inplace_round(const int32_t *lin
 size_t inplace_scratch_bytes(int64_t T)
 {
     const size_t t = (size_t)(T > 0 ? T : 1);
-    return ((t * 8 + 255) & ~(size_t)255) + 3 * ((t * 4 + 255) & ~(size_t)255) + 256;
+    return 4 * ((t * 4 + 255) & ~(size_t)255) + 256;
 }
 
 InplaceBuffers inplace_buffers(void *scratch, int64_t T)
@@ -127,7 +211,7 @@ InplaceBuffers inplace_buffers(void *scratch, int64_t T)
     const size_t t = (size_t)(T > 0 ? T : 1);
     char *p = static_cast<char *>(scratch);
     InplaceBuffers b;
-    b.child_range = reinterpret_cast<int2 *>(p); p += (t * 8 + 255) & ~(size_t)255;
+    b.child = reinterpret_cast<int32_t *>(p); p += (t * 4 + 255) & ~(size_t)255;
     b.J[0] = reinterpret_cast<int32_t *>(p); p += (t * 4 + 255) & ~(size_t)255;
     b.J[1] = reinterpret_cast<int32_t *>(p); p += (t * 4 + 255) & ~(size_t)255;
     b.linkers = reinterpret_cast<int32_t *>(p); p += (t * 4 + 255) & ~(size_t)255;
@@ -141,14 +225,14 @@ hipError_t launch_inplace_setup(const GraphView &g, const u64 *K, u64 select, in
     const int64_t T = g.num_tensors, P = g.num_ops;
     auto blocks_for = [&](int64_t n) {
         int64_t nb = (n + kIpThreads - 1) / kIpThreads;
-        if (nb > (int64_t)grid_blocks * 4) nb = (int64_t)grid_blocks * 4;
+        if (nb > (int64_t)grid_blocks) nb = (int64_t)grid_blocks;
         return dim3((unsigned)(nb > 0 ? nb : 1));
     };
-    hipLaunchKernelGGL(k_inplace_init, blocks_for(T), dim3(kIpThreads), 0, s, rename, b.child_range, T, b.counters,
+    hipLaunchKernelGGL(k_inplace_init, blocks_for(T), dim3(kIpThreads), 0, s, rename, b.child, T, b.counters,
                        kInplaceMaxRounds + 1, renamed_count);
-    if (P > 0) hipLaunchKernelGGL(k_inplace_children, blocks_for(P), dim3(kIpThreads), 0, s, g, K, select, rename, b.child_range);
+    if (P > 0) hipLaunchKernelGGL(k_inplace_children, blocks_for(P), dim3(kIpThreads), 0, s, g, K, select, rename, b.child);
     if (T > 0)
-        hipLaunchKernelGGL(k_inplace_links, blocks_for(T), dim3(kIpThreads), 0, s, rename, b.child_range, T, b.J[0], b.J[1],
+        hipLaunchKernelGGL(k_inplace_links, blocks_for(T), dim3(kIpThreads), 0, s, rename, b.child, T, b.J[0], b.J[1],
                            b.linkers, b.counters);
     return hipGetLastError();
 }
