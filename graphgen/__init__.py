@@ -32,6 +32,7 @@ _STREAM_MUL = _U64(0xD6E8FEB86659FD93)
 
 # stream ids: one per random quantity
 S_NOUT, S_FANIN, S_SRC, S_SKIP, S_SKIPLEN, S_REC, S_TGT_N, S_TGT, S_PERM = range(1, 10)
+S_PAIR_OBJ, S_PAIR_WRT = 10, 11
 
 
 def rng_u64(seed: int, stream: int, counters) -> np.ndarray:
@@ -303,6 +304,19 @@ def config(k: int, scale: float = 1.0):
         ng = max(1, int(4096 * scale))
         return batch_layered(ng, 20000, BASE_SEED + 4000, name="cfg4-batch")
     raise ValueError(f"no such config: {k}")
+
+
+def backward_pairs(g: Graph, seed: int, num_pairs: int = 64, num_sources: int = 16,
+                   tail_fraction: float = 0.05):
+    """(objective, derivative target) pairs for the backward prune: the objective of pair i is one of
+    the first ``num_sources`` tensors of the graph (its graph inputs: every route starts at one),
+    the derivative target is uniform over the last ``tail_fraction`` of the tensor ids.  Returns two
+    int32 arrays of ``num_pairs`` ids."""
+    i = np.arange(num_pairs, dtype=np.int64)
+    obj = rng_below(seed, S_PAIR_OBJ, i, max(1, min(num_sources, g.num_tensors)))
+    span = max(1, int(g.num_tensors * tail_fraction))
+    wrt = g.num_tensors - span + rng_below(seed, S_PAIR_WRT, i, span)
+    return _i32(obj), _i32(wrt)
 
 
 # --------------------------------------------------------------------------

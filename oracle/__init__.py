@@ -1,11 +1,12 @@
-"""ctypes front end of the CPU oracle (``forward_prune.c``, ``inplace.c``) -- TEST INFRASTRUCTURE.
+"""ctypes front end of the CPU oracle (``forward_prune.c``, ``backward_prune.c``, ``inplace.c``) -- TEST
+INFRASTRUCTURE.
 
 Only tests, the smoke check and the bench's ``cpu_baseline`` leg may import this package; the
 product path never does.  It imports nothing from the GPU package.
 
 Every function here is a thin marshalling layer: all arithmetic is in the C files, which follow
-Algorithm 1, the removal rule of Sec. 2.1, the creation-order rule of Sec. 3.2 and Algorithm 3
-(Sec. 2.4) of the paper.
+Algorithm 1, the removal rule of Sec. 2.1, the creation-order rule of Sec. 3.2, Algorithm 2
+(Sec. 2.3) and Algorithm 3 (Sec. 2.4) of the paper.
 """
 from __future__ import annotations
 
@@ -18,7 +19,7 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRCS = [os.path.join(_HERE, "forward_prune.c"), os.path.join(_HERE, "inplace.c")]
+_SRCS = [os.path.join(_HERE, f) for f in ("forward_prune.c", "backward_prune.c", "inplace.c")]
 _LIB = os.path.join(_HERE, "liboracle.so")
 _lib = None
 
@@ -199,3 +200,31 @@ def inplace(adj: Adjacency, K: np.ndarray, select: int = 2**64 - 1) -> np.ndarra
     RD = np.empty(adj.num_tensors, np.int32)
     _load().orc_inplace(i64(adj.num_tensors), _p(child_rowptr), _p(child_idx), _p(in_graph), _p(RD))
     return RD
+
+
+def consumers(adj: Adjacency):
+    """tensor -> consumer operators (ascending operator id), as a CSR: the transpose of the input CSR."""
+    op_of_edge = np.repeat(np.arange(adj.num_ops, dtype=np.int32), np.diff(adj.in_rowptr))
+    return build_csr(adj.num_tensors, adj.in_idx, op_of_edge)
+
+
+def backward_mark(adj: Adjacency, obj, wrt) -> np.ndarray:
+    """Algorithm 2 for up to 64 (objective, derivative target) pairs: bit i of M[x] = m_x of pair i."""
+    obj, wrt = _c(obj, np.int32), _c(wrt, np.int32)
+    assert obj.shape == wrt.shape
+    cons_rowptr, cons_idx = consumers(adj)
+    M = np.zeros(adj.num_tensors, np.uint64)
+    V = np.empty(max(adj.num_tensors, 1), np.uint8)
+    rc = _load().orc_backward_prune(i64(adj.num_tensors), _p(cons_rowptr), _p(cons_idx), _p(adj.out_rowptr),
+                                    _p(adj.out_idx), i32(obj.shape[0]), _p(obj), _p(wrt), _p(M), _p(V))
+    if rc:
+        raise ValueError("orc_backward_prune: bad argument")
+    return M
+
+
+def backward_prune(adj: Adjacency, obj, wrt, num_graphs: int = 1, graph_op_offsets=None) -> PruneResult:
+    """Algorithm 2, then the same removal rule and ordered compaction as the forward prune."""
+    M = backward_mark(adj, obj, wrt)
+    K, flag = keep(adj, M)
+    kept_ops, kept_masks, kept_count, pq = compact(K, num_graphs, graph_op_offsets)
+    return PruneResult(M, K, flag, kept_ops, kept_masks, kept_count, pq, np.zeros(0, np.int64))

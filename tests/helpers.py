@@ -180,3 +180,68 @@ def rename_by_reachability(g: gg.Graph, kept):
             v = link[v]
             steps += 1
     return rd.astype(np.int32)
+
+
+def load_backward_examples():
+    """Hand-worked cases for Algorithm 2: graph, pairs, expected marked masks and kept operators."""
+    with open(os.path.join(GOLDEN, "backward_examples.json")) as f:
+        ex = json.load(f)
+    out = []
+    for c in ex["cases"]:
+        names = c["tensors"]
+        tid = {n: i for i, n in enumerate(names)}
+        ops = [([tid[t] for t in op["in"]], [tid[t] for t in op["out"]]) for op in c["ops"]]
+        g = graph_from_ops(ops, len(names), c["name"])
+        obj = np.asarray([tid[p[0]] for p in c["pairs"]], np.int32)
+        wrt = np.asarray([tid[p[1]] for p in c["pairs"]], np.int32)
+        M = np.zeros(len(names), np.uint64)
+        for i, marked in enumerate(c["marked"]):
+            for n in marked:
+                M[tid[n]] |= np.uint64(1 << i)
+        out.append(dict(name=c["name"], graph=g, ops=ops, obj=obj, wrt=wrt, M=M,
+                        kept=np.asarray(c["kept_ops"], np.int32)))
+    return out
+
+
+def marks_by_route_enumeration(ops, num_tensors, obj, wrt):
+    """Definition, not algorithm: bit i of M[x] iff x lies on some route x_obj -> ... -> x_wrt of at
+    least one edge; every route is enumerated explicitly (tiny graphs only)."""
+    children = [set() for _ in range(num_tensors)]
+    for ins, outs in ops:
+        for x in ins:
+            children[x].update(outs)
+    M = np.zeros(num_tensors, dtype=np.uint64)
+    for i, (a, b) in enumerate(zip(obj.tolist(), wrt.tolist())):
+        path = [a]
+
+        def walk(x):
+            for c in children[x]:
+                path.append(c)
+                if c == b:
+                    for n in path:
+                        M[n] |= np.uint64(1 << i)
+                else:
+                    walk(c)
+                path.pop()
+        walk(a)
+    return M
+
+
+def marks_by_closure(ops, num_tensors, obj, wrt):
+    """Second statement of the same set: x is marked for pair (a, b), a != b, iff a reaches x and x
+    reaches b, reachability being the reflexive-transitive closure of the child relation (boolean
+    matrix powers)."""
+    R = np.eye(num_tensors, dtype=bool)
+    for ins, outs in ops:
+        for x in ins:
+            for y in outs:
+                R[x, y] = True
+    for _ in range(max(1, int(np.ceil(np.log2(max(2, num_tensors)))))):
+        R = R | ((R.astype(np.int64) @ R.astype(np.int64)) > 0)
+    M = np.zeros(num_tensors, dtype=np.uint64)
+    for i, (a, b) in enumerate(zip(obj.tolist(), wrt.tolist())):
+        if a == b:
+            continue
+        on = R[a, :] & R[:, b]
+        M[on] |= np.uint64(1 << i)
+    return M
