@@ -216,6 +216,31 @@ int dgn_keep_compact(const dgn_graph *g, const uint64_t *tensor_mask_in, uint64_
                      uint8_t *op_flag, int32_t *kept_ops, uint64_t *kept_masks, int64_t *kept_count,
                      int64_t *per_query_count, void *scratch, size_t scratch_bytes, dgn_stream stream);
 
+/* ---- Backward Prune ---------------------------------------------------------------------- */
+
+/* Scratch bytes dgn_backward_prune needs for this graph. */
+int dgn_backward_prune_workspace(const dgn_graph *g, size_t *scratch_bytes);
+
+/* Algorithm 2 (Sec. 2.3) for num_pairs (1..64) pairs (x_obj, x_wrt) at once, then the removal rule
+ * of Sec. 2.1 and the creation-order compaction of Sec. 3.2, exactly as dgn_prune applies them.
+ *
+ *   obj [num_pairs], wrt [num_pairs]: DEVICE int32 tensor ids; pair i owns bit i.
+ *   tensor_mask [num_tensors] out: bit i set iff the tensor lies on a route from obj[i] to wrt[i]
+ *       (Child(x) = tensors written by operators that read x); a pair with obj[i] == wrt[i], or
+ *       whose target cannot be reached, marks nothing.
+ *   op_mask, op_flag, kept_ops, kept_masks, kept_count, per_query_count: as for dgn_prune, derived
+ *       from tensor_mask (an operator is kept for pair i iff one of its outputs is marked for i).
+ *   options, stats: HOST, may be NULL; stats describes the first stage (the traversal from the
+ *       derivative targets), stats->reserved = passes of the forward stage.
+ *
+ * Single graphs only (DGN_ERR_INVALID_ARG for a packed batch).  An id outside [0, num_tensors) is
+ * reported as DGN_ERR_ID_OUT_OF_RANGE.  All outputs are rewritten in full; the call synchronises the
+ * stream several times (the number of passes depends on the data). */
+int dgn_backward_prune(const dgn_graph *g, int32_t num_pairs, const int32_t *obj, const int32_t *wrt,
+                       uint64_t *tensor_mask, uint64_t *op_mask, uint8_t *op_flag, int32_t *kept_ops,
+                       uint64_t *kept_masks, int64_t *kept_count, int64_t *per_query_count, void *scratch,
+                       size_t scratch_bytes, const dgn_options *options, dgn_stats *stats, dgn_stream stream);
+
 /* ---- In-place structures ----------------------------------------------------------------- */
 
 /* Scratch bytes dgn_inplace needs for this graph. */

@@ -31,7 +31,8 @@ DGN_ERR_INTERNAL = -10
 EXPORTS = [
     "dgn_graph_build_workspace", "dgn_graph_build", "dgn_graph_from_csr_workspace", "dgn_graph_from_csr",
     "dgn_graph_get_csr", "dgn_graph_get_sizes", "dgn_graph_destroy", "dgn_prune_workspace", "dgn_prune",
-    "dgn_keep_compact", "dgn_inplace_workspace", "dgn_inplace", "dgn_strerror", "dgn_version",
+    "dgn_keep_compact", "dgn_backward_prune_workspace", "dgn_backward_prune", "dgn_inplace_workspace",
+    "dgn_inplace", "dgn_strerror", "dgn_version",
     "dgn_last_hip_error",
 ]
 
@@ -91,6 +92,9 @@ def _load() -> ctypes.CDLL:
     lib.dgn_prune.argtypes = [c_void_p, c_int32, c_int64] + [c_void_p] * 9 + [c_void_p, c_size_t,
                               POINTER(dgn_options), POINTER(dgn_stats), c_void_p]
     lib.dgn_keep_compact.argtypes = [c_void_p] + [c_void_p] * 7 + [c_void_p, c_size_t, c_void_p]
+    lib.dgn_backward_prune_workspace.argtypes = [c_void_p, POINTER(c_size_t)]
+    lib.dgn_backward_prune.argtypes = [c_void_p, c_int32] + [c_void_p] * 9 + [c_void_p, c_size_t,
+                                       POINTER(dgn_options), POINTER(dgn_stats), c_void_p]
     lib.dgn_inplace_workspace.argtypes = [c_void_p, POINTER(c_size_t)]
     lib.dgn_inplace.argtypes = [c_void_p, c_void_p, ctypes.c_uint64, c_void_p, c_void_p, c_void_p, c_size_t,
                                 POINTER(c_int32), c_void_p]
@@ -231,6 +235,21 @@ def dgn_keep_compact(handle, tensor_mask_in, op_mask, op_flag, kept_ops, kept_ma
     return _lib.dgn_keep_compact(handle, _dp(tensor_mask_in), _dp(op_mask), _dp(op_flag), _dp(kept_ops),
                                  _dp(kept_masks), _dp(kept_count), _dp(per_query_count), _dp(scratch),
                                  scratch_bytes, _stream(stream))
+
+
+def dgn_backward_prune_workspace(handle):
+    s = c_size_t(0)
+    rc = _lib.dgn_backward_prune_workspace(handle, ctypes.byref(s))
+    return rc, s.value
+
+
+def dgn_backward_prune(handle, num_pairs, obj, wrt, tensor_mask, op_mask, op_flag, kept_ops, kept_masks,
+                       kept_count, per_query_count, scratch, scratch_bytes, options=None, stats=None,
+                       stream=None) -> int:
+    return _lib.dgn_backward_prune(handle, num_pairs, _dp(obj), _dp(wrt), _dp(tensor_mask), _dp(op_mask),
+                                   _dp(op_flag), _dp(kept_ops), _dp(kept_masks), _dp(kept_count),
+                                   _dp(per_query_count), _dp(scratch), scratch_bytes, _opt(options),
+                                   ctypes.byref(stats) if stats is not None else None, _stream(stream))
 
 
 def dgn_inplace_workspace(handle):
@@ -394,3 +413,20 @@ class InplaceBuffers:
         rc, self.rounds = dgn_inplace(self.graph.handle, op_mask, select, self.rename, self.renamed_count,
                                       self.scratch, self.scratch_bytes, stream)
         return rc
+
+
+class BackwardPruneBuffers(PruneBuffers):
+    """Buffers of one ``dgn_backward_prune`` call: the same outputs as ``PruneBuffers``, larger scratch."""
+
+    def __init__(self, graph: DeviceGraph, num_pairs: int = 64, device=None):
+        super().__init__(graph, num_pairs, device)
+        rc, sb = dgn_backward_prune_workspace(graph.handle)
+        _check(rc, "dgn_backward_prune_workspace")
+        self.scratch_bytes = sb
+        self.scratch = torch.empty(sb, dtype=torch.uint8, device=self.scratch.device)
+
+    def backward_prune(self, obj, wrt, options=None, stats=None, stream=None) -> int:
+        """``obj`` / ``wrt``: device int32 tensors of equal length (the pairs)."""
+        return dgn_backward_prune(self.graph.handle, int(obj.numel()), obj, wrt, self.tensor_mask, self.op_mask,
+                                  self.op_flag, self.kept_ops, self.kept_masks, self.kept_count,
+                                  self.per_query_count, self.scratch, self.scratch_bytes, options, stats, stream)

@@ -724,6 +724,93 @@ int dgn_keep_compact(const dgn_graph *g, const uint64_t *tensor_mask_in, uint64_
     return DGN_OK;
 }
 
+// ---- Backward Prune: scratch = [prune scratch][B: 8T][K of stage one: 8P][its kept list: 4P][small] ----
+struct BackwardScratch {
+    size_t prune_bytes;
+    u64 *B, *KB;
+    int32_t *kept, *tgt_rowptr, *flags;
+    int64_t *kept_count;
+    size_t bytes;
+};
+
+static BackwardScratch backward_scratch(void *mem, int64_t P, int64_t T, int32_t G)
+{
+    BackwardScratch b{};
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    b.prune_bytes = up(prune_scratch(nullptr, P, T, G, 0).bytes);
+    char *p = static_cast<char *>(mem) + b.prune_bytes;
+    b.B = reinterpret_cast<u64 *>(p); p += up((size_t)(T > 0 ? T : 1) * 8);
+    b.KB = reinterpret_cast<u64 *>(p); p += up((size_t)(P > 0 ? P : 1) * 8);
+    b.kept = reinterpret_cast<int32_t *>(p); p += up((size_t)(P > 0 ? P : 1) * 4);
+    b.tgt_rowptr = reinterpret_cast<int32_t *>(p); p += 512;
+    b.kept_count = reinterpret_cast<int64_t *>(p); p += up(sizeof(int64_t) * (size_t)(G > 1 ? G + 2 : 1));
+    b.flags = reinterpret_cast<int32_t *>(p); p += 256;
+    b.bytes = (size_t)(p - static_cast<char *>(mem));
+    return b;
+}
+
+int dgn_backward_prune_workspace(const dgn_graph *g, size_t *scratch_bytes)
+{
+    if (!g || !scratch_bytes) return DGN_ERR_NULL_PTR;
+    *scratch_bytes = backward_scratch(nullptr, g->P, g->T, g->G).bytes;
+    return DGN_OK;
+}
+
+int dgn_backward_prune(const dgn_graph *g, int32_t num_pairs, const int32_t *obj, const int32_t *wrt,
+                       uint64_t *tensor_mask, uint64_t *op_mask, uint8_t *op_flag, int32_t *kept_ops,
+                       uint64_t *kept_masks, int64_t *kept_count, int64_t *per_query_count, void *scratch,
+                       size_t scratch_bytes, const dgn_options *options, dgn_stats *stats, dgn_stream stream)
+{
+    if (!g) return DGN_ERR_NULL_PTR;
+    if (num_pairs < 1 || num_pairs > DGN_MAX_SETS) return DGN_ERR_TOO_MANY_SETS;
+    if (g->G > 1) return DGN_ERR_INVALID_ARG;        // pairs are not tied to the graphs of a packed batch
+    if (!obj || !wrt || !kept_count || !scratch) return DGN_ERR_NULL_PTR;
+    if ((g->T > 0 && !tensor_mask) || (g->P > 0 && (!op_mask || !kept_ops))) return DGN_ERR_NULL_PTR;
+    const BackwardScratch S = backward_scratch(scratch, g->P, g->T, g->G);
+    if (scratch_bytes < S.bytes) return DGN_ERR_WORKSPACE_TOO_SMALL;
+    if (((uintptr_t)scratch | (uintptr_t)tensor_mask | (uintptr_t)op_mask | (uintptr_t)kept_masks |
+         (uintptr_t)kept_count | (uintptr_t)per_query_count) & 7)
+        return DGN_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    u64 *F = reinterpret_cast<u64 *>(tensor_mask);
+
+    // stage one: what every x_wrt depends on (bit i for pair i), and the operators kept for that
+    DGN_HIP(launch_backward_seed(g->T, num_pairs, obj, wrt, S.tgt_rowptr, nullptr, nullptr, nullptr, true, s));
+    dgn_options o1{};
+    if (options) o1 = *options;
+    o1.profile = 0;
+    int rc = dgn_prune(g, num_pairs, num_pairs, S.tgt_rowptr, wrt, reinterpret_cast<uint64_t *>(S.B),
+                       reinterpret_cast<uint64_t *>(S.KB), nullptr, S.kept, nullptr, S.kept_count, nullptr, scratch,
+                       S.prune_bytes, &o1, stats, stream);
+    if (rc != DGN_OK) return rc;
+
+    // stage two: forwards from every x_obj, inside the coloured set of stage one
+    FillRegion clr[2] = {{F, (size_t)g->T * 8}, {S.flags, 256}};
+    DGN_HIP(launch_clear(clr, 2, s));
+    DGN_HIP(launch_backward_seed(g->T, num_pairs, obj, wrt, nullptr, S.B, F, S.flags, false, s));
+    void *pin = nullptr;
+    rc = pinned_buffer(&pin);
+    if (rc != DGN_OK) return rc;
+    int32_t *host_flags = static_cast<int32_t *>(pin);
+    const int grid = g->num_cus * 8;
+    int64_t passes = 0;
+    for (;;) {                                       // three passes per read-back; flags[1..3] = "pass added something"
+        FillRegion again[1] = {{S.flags + 2, 16}};
+        if (passes) DGN_HIP(launch_clear(again, 1, s));
+        for (int i = 0; i < 3; ++i, ++passes)
+            DGN_HIP(launch_forward_within(g->v, S.kept, S.kept_count, S.B, F, S.flags + 2 + i, grid, s));
+        DGN_HIP(hipMemcpyAsync(host_flags, S.flags, 32, hipMemcpyDeviceToHost, s));
+        DGN_HIP(hipStreamSynchronize(s));
+        if (host_flags[0] & kErrIdRange) return DGN_ERR_ID_OUT_OF_RANGE;
+        if (host_flags[4] == 0) break;               // the last pass of the batch changed nothing
+    }
+    if (stats) stats->reserved = (int32_t)passes;
+
+    // removal rule and ordered compaction on the marked set
+    return dgn_keep_compact(g, tensor_mask, op_mask, op_flag, kept_ops, kept_masks, kept_count, per_query_count, scratch,
+                            S.prune_bytes, stream);
+}
+
 int dgn_inplace_workspace(const dgn_graph *g, size_t *scratch_bytes)
 {
     if (!g || !scratch_bytes) return DGN_ERR_NULL_PTR;

@@ -228,6 +228,13 @@ struct CompactArgs {
 // ev (may be NULL): three events recorded after the count, scan and scatter passes.
 hipError_t launch_keep_compact(const CompactArgs &a, hipStream_t s, hipEvent_t *ev = nullptr);
 
+// Backward Prune (Algorithm 2): target row pointers 0..n (rowptr_only) or the seeds of the forward stage;
+// one pass of the forward stage over the kept operators of the first stage.
+hipError_t launch_backward_seed(int64_t T, int num_pairs, const int32_t *obj, const int32_t *wrt, int32_t *tgt_rowptr,
+                                const u64 *B, u64 *F, int32_t *flags, bool rowptr_only, hipStream_t s);
+hipError_t launch_forward_within(const GraphView &g, const int32_t *kept, const int64_t *kept_count, const u64 *B, u64 *F,
+                                 int32_t *changed, int grid_blocks, hipStream_t s);
+
 // In-place structures (Algorithm 3).  counters: [0] = number of nodes with exactly one child,
 // [1 + r] = doubling round r left some jump pointer alive.
 constexpr int kInplaceMaxRounds = 32;               // 2^32 links: longer than any chain of int32 ids
