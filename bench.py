@@ -168,6 +168,35 @@ def main():
     log(f"in-place pass: {ip_ms:.3f} ms, {inplace['rounds']} rounds, {inplace['renamed_tensors']} of "
         f"{inplace['graph_tensors']} tensors renamed")
     del ip
+
+    # ---- backward prune (Algorithm 2) on the same graph, 64 pairs, timed on its own ---------------
+    backward = None
+    if g.num_graphs == 1:
+        n_src = 400 if args.config == 1 else 16
+        obj_h, wrt_h = gg.backward_pairs(g, gg.BASE_SEED + 1000 * args.config, 64, n_src)
+        bb = d.BackwardPruneBuffers(dg, 64)
+        obj_d, wrt_d = up(obj_h), up(wrt_h)
+        bst = d.dgn_stats()
+        bw_ms = []
+        for _ in range(1 + max(3, min(args.steps, 10))):
+            torch.cuda.synchronize()
+            tb = time.perf_counter()
+            rc = bb.backward_prune(obj_d, wrt_d, stats=bst)
+            torch.cuda.synchronize()
+            bw_ms.append((time.perf_counter() - tb) * 1e3)
+            assert rc == 0, d.dgn_strerror(rc)
+        bw_ms = float(np.median(bw_ms[1:]))
+        bw_out = bb.to_host()
+        backward = {"ms": round(bw_ms, 4), "gteps": round(E / (bw_ms * 1e-3) / 1e9, 2), "pairs": 64,
+                    "forward_passes": int(bst.reserved), "first_stage_levels": int(bst.levels),
+                    "marked_tensors": int(np.count_nonzero(bw_out["tensor_mask"])),
+                    "kept_ops": int(bw_out["kept_count"][0]),
+                    "connected_pairs": int(np.count_nonzero(bw_out["per_query_count"])),
+                    "cpu_oracle_ms_per_pair": None, "bit_exact_vs_oracle_sampled_pair": None}
+        log(f"backward prune: {bw_ms:.3f} ms ({backward['gteps']} GTEPS), {backward['forward_passes']} forward passes, "
+            f"{backward['marked_tensors']} tensors marked, {backward['kept_ops']} operators kept, "
+            f"{backward['connected_pairs']} of 64 pairs connected")
+        del bb
     P_k = int(out["kept_count"][0])
     T_c = int(np.count_nonzero(out["tensor_mask"]))
     fan_in = np.bincount(g.in_op, minlength=P)
@@ -235,6 +264,15 @@ def main():
         log(f"oracle in-place pass: {inplace['cpu_oracle_ms']:.0f} ms; GPU rename dictionary bit-exact: "
             f"{inplace['bit_exact_vs_oracle']}")
         assert inplace["bit_exact_vs_oracle"], "GPU rename dictionary differs from the oracle"
+        if backward is not None:                 # one pair (a graph-wide search each): the bounded sample
+            i = int(np.flatnonzero(bw_out["per_query_count"])[0]) if backward["connected_pairs"] else 0
+            tb = time.perf_counter()
+            ref_m = orc.backward_mark(adj, obj_h[i:i + 1], wrt_h[i:i + 1])
+            backward["cpu_oracle_ms_per_pair"] = round((time.perf_counter() - tb) * 1e3, 1)
+            same = bool(np.array_equal((bw_out["tensor_mask"] >> np.uint64(i)) & np.uint64(1), ref_m))
+            backward["bit_exact_vs_oracle_sampled_pair"] = same
+            log(f"oracle backward prune, pair {i}: {backward['cpu_oracle_ms_per_pair']:.0f} ms; GPU marks bit-exact: {same}")
+            assert same, "GPU backward-prune marks differ from the oracle"
 
     line = {
         "metric": "pruned edges/sec (GTEPS), 64-query batched prune", "value": round(gteps, 2), "unit": "GTEPS",
@@ -249,6 +287,7 @@ def main():
         "phase_ms": {k: round(v, 4) for k, v in ph.items()},
         "build_ms": round(build_ms, 3),
         "inplace": inplace,
+        "backward_prune": backward,
         "build_plus_prune_gteps": round(E / ((build_ms + ms_per_step) * 1e-3) / 1e9, 2),
         "result": {"kept_ops": P_k, "coloured_tensors": T_c, "kept_in_edges": E_k, "kept_out_edges": Eo_k,
                    "levels": int(st.levels), "tensor_visits": int(st.tensor_visits),

@@ -1,5 +1,5 @@
-"""ctypes front end of the CPU oracle (``forward_prune.c``, ``backward_prune.c``, ``inplace.c``) -- TEST
-INFRASTRUCTURE.
+"""ctypes front end of the CPU oracle (``forward_prune.c``, ``backward_prune.c``, ``inplace.c``,
+``postprocess.c``) -- TEST INFRASTRUCTURE.
 
 Only tests, the smoke check and the bench's ``cpu_baseline`` leg may import this package; the
 product path never does.  It imports nothing from the GPU package.
@@ -19,7 +19,8 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRCS = [os.path.join(_HERE, f) for f in ("forward_prune.c", "backward_prune.c", "inplace.c")]
+_SRCS = [os.path.join(_HERE, f) for f in ("forward_prune.c", "backward_prune.c", "inplace.c",
+                                             "postprocess.c")]
 _LIB = os.path.join(_HERE, "liboracle.so")
 _lib = None
 
@@ -41,6 +42,7 @@ def _load():
         _lib = ctypes.CDLL(_LIB)
         _lib.orc_certificate.restype = ctypes.c_int64
         _lib.orc_child_sets.restype = ctypes.c_int64
+        _lib.orc_per_set_lists.restype = ctypes.c_int64
     return _lib
 
 
@@ -228,3 +230,22 @@ def backward_prune(adj: Adjacency, obj, wrt, num_graphs: int = 1, graph_op_offse
     K, flag = keep(adj, M)
     kept_ops, kept_masks, kept_count, pq = compact(K, num_graphs, graph_op_offsets)
     return PruneResult(M, K, flag, kept_ops, kept_masks, kept_count, pq, np.zeros(0, np.int64))
+
+
+def ignore_mask(adj: Adjacency, K: np.ndarray, M: np.ndarray) -> np.ndarray:
+    """Sec. 3.2: bit q of ignore[t] iff t is written by an operator kept for set q and is not coloured for q."""
+    out = np.empty(adj.num_tensors, np.uint64)
+    _load().orc_ignore_mask(i64(adj.num_ops), i64(adj.num_tensors), _p(adj.out_rowptr), _p(adj.out_idx),
+                            _p(_c(K, np.uint64)), _p(_c(M, np.uint64)), _p(out))
+    return out
+
+
+def per_set_lists(K: np.ndarray):
+    """Sec. 3.2: for every set q the ascending ids of the operators kept for it: (set_rowptr[65], set_ops)."""
+    K = _c(K, np.uint64)
+    total = int(sum(int(np.count_nonzero((K >> np.uint64(q)) & np.uint64(1))) for q in range(64)))
+    rowptr = np.empty(65, np.int64)
+    ops = np.empty(max(total, 1), np.int32)
+    n = _load().orc_per_set_lists(i64(K.shape[0]), _p(K), _p(rowptr), _p(ops))
+    assert n == total
+    return rowptr, ops[:n].copy()
