@@ -241,6 +241,36 @@ int dgn_backward_prune(const dgn_graph *g, int32_t num_pairs, const int32_t *obj
                        uint64_t *kept_masks, int64_t *kept_count, int64_t *per_query_count, void *scratch,
                        size_t scratch_bytes, const dgn_options *options, dgn_stats *stats, dgn_stream stream);
 
+/* ---- Reading a prune result (Sec. 3.2) --------------------------------------------------- */
+
+/* Tensors to rename "ignore": bit q of ignore_mask[t] is set iff t is written by an operator that
+ * survives for set q (bit q of its K) while t itself is not coloured for q.  Works from the compacted
+ * list, so it costs the pruned graph plus clearing the mask.
+ *   tensor_mask [num_tensors] in (DEVICE): M.   kept_ops / kept_masks / kept_count in (DEVICE): as
+ *       written by dgn_prune, dgn_keep_compact or dgn_backward_prune (kept_count[0] is read on the device).
+ *   ignore_mask [num_tensors] out (DEVICE), rewritten in full.
+ *   ignore_count out (DEVICE int64 [1]): tensors with a non-zero ignore mask; may be NULL.
+ * Asynchronous on `stream`: nothing is read back. */
+int dgn_ignore_mask(const dgn_graph *g, const uint64_t *tensor_mask, const int32_t *kept_ops,
+                    const uint64_t *kept_masks, const int64_t *kept_count, uint64_t *ignore_mask,
+                    int64_t *ignore_count, dgn_stream stream);
+
+/* Scratch bytes dgn_per_set_lists needs for a kept list of num_kept entries. */
+int dgn_per_set_lists_workspace(int64_t num_kept, size_t *scratch_bytes);
+
+/* For every bit q = 0..63 the operators of the kept list whose mask has bit q, in creation order
+ * (what the function of target set q executes, Sec. 3.2), laid out set after set.
+ *   kept_ops / kept_masks [num_kept] in (DEVICE); num_kept is a HOST value (kept_count[0] read back).
+ *   set_rowptr out (DEVICE int64 [65]): list q is set_ops[set_rowptr[q] .. set_rowptr[q+1]);
+ *       set_rowptr[64] is the total number of entries.
+ *   set_ops out (DEVICE int32 [set_ops_capacity]): entries beyond the capacity are dropped, so the
+ *       caller compares set_rowptr[64] with the capacity (the sum of per_query_count is enough).
+ * num_kept above 2^31 / 64 is DGN_ERR_TOO_LARGE (slots are counted in int32).  For a packed batch bit
+ * q mixes the graphs' q-th sets; kept_count[1 + g] cuts every list by graph.  Asynchronous. */
+int dgn_per_set_lists(const int32_t *kept_ops, const uint64_t *kept_masks, int64_t num_kept,
+                      int64_t *set_rowptr, int32_t *set_ops, int64_t set_ops_capacity, void *scratch,
+                      size_t scratch_bytes, dgn_stream stream);
+
 /* ---- In-place structures ----------------------------------------------------------------- */
 
 /* Scratch bytes dgn_inplace needs for this graph. */

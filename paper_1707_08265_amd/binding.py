@@ -32,7 +32,8 @@ EXPORTS = [
     "dgn_graph_build_workspace", "dgn_graph_build", "dgn_graph_from_csr_workspace", "dgn_graph_from_csr",
     "dgn_graph_get_csr", "dgn_graph_get_sizes", "dgn_graph_destroy", "dgn_prune_workspace", "dgn_prune",
     "dgn_keep_compact", "dgn_backward_prune_workspace", "dgn_backward_prune", "dgn_inplace_workspace",
-    "dgn_inplace", "dgn_strerror", "dgn_version",
+    "dgn_inplace", "dgn_ignore_mask", "dgn_per_set_lists_workspace", "dgn_per_set_lists", "dgn_strerror",
+    "dgn_version",
     "dgn_last_hip_error",
 ]
 
@@ -95,6 +96,10 @@ def _load() -> ctypes.CDLL:
     lib.dgn_backward_prune_workspace.argtypes = [c_void_p, POINTER(c_size_t)]
     lib.dgn_backward_prune.argtypes = [c_void_p, c_int32] + [c_void_p] * 9 + [c_void_p, c_size_t,
                                        POINTER(dgn_options), POINTER(dgn_stats), c_void_p]
+    lib.dgn_ignore_mask.argtypes = [c_void_p] * 8
+    lib.dgn_per_set_lists_workspace.argtypes = [c_int64, POINTER(c_size_t)]
+    lib.dgn_per_set_lists.argtypes = [c_void_p, c_void_p, c_int64, c_void_p, c_void_p, c_int64, c_void_p, c_size_t,
+                                      c_void_p]
     lib.dgn_inplace_workspace.argtypes = [c_void_p, POINTER(c_size_t)]
     lib.dgn_inplace.argtypes = [c_void_p, c_void_p, ctypes.c_uint64, c_void_p, c_void_p, c_void_p, c_size_t,
                                 POINTER(c_int32), c_void_p]
@@ -250,6 +255,24 @@ def dgn_backward_prune(handle, num_pairs, obj, wrt, tensor_mask, op_mask, op_fla
                                    _dp(op_flag), _dp(kept_ops), _dp(kept_masks), _dp(kept_count),
                                    _dp(per_query_count), _dp(scratch), scratch_bytes, _opt(options),
                                    ctypes.byref(stats) if stats is not None else None, _stream(stream))
+
+
+def dgn_ignore_mask(handle, tensor_mask, kept_ops, kept_masks, kept_count, ignore_mask, ignore_count,
+                    stream=None) -> int:
+    return _lib.dgn_ignore_mask(handle, _dp(tensor_mask), _dp(kept_ops), _dp(kept_masks), _dp(kept_count),
+                                _dp(ignore_mask), _dp(ignore_count), _stream(stream))
+
+
+def dgn_per_set_lists_workspace(num_kept: int):
+    s = c_size_t(0)
+    rc = _lib.dgn_per_set_lists_workspace(num_kept, ctypes.byref(s))
+    return rc, s.value
+
+
+def dgn_per_set_lists(kept_ops, kept_masks, num_kept, set_rowptr, set_ops, set_ops_capacity, scratch,
+                      scratch_bytes, stream=None) -> int:
+    return _lib.dgn_per_set_lists(_dp(kept_ops), _dp(kept_masks), num_kept, _dp(set_rowptr), _dp(set_ops),
+                                  set_ops_capacity, _dp(scratch), scratch_bytes, _stream(stream))
 
 
 def dgn_inplace_workspace(handle):
@@ -430,3 +453,36 @@ class BackwardPruneBuffers(PruneBuffers):
         return dgn_backward_prune(self.graph.handle, int(obj.numel()), obj, wrt, self.tensor_mask, self.op_mask,
                                   self.op_flag, self.kept_ops, self.kept_masks, self.kept_count,
                                   self.per_query_count, self.scratch, self.scratch_bytes, options, stats, stream)
+
+
+class ReadoutBuffers:
+    """Buffers for ``dgn_ignore_mask`` and ``dgn_per_set_lists`` on the result held by a ``PruneBuffers``."""
+
+    def __init__(self, result: PruneBuffers):
+        dev = result.tensor_mask.device
+        self.result = result
+        self.ignore_mask = torch.empty(result.graph.num_tensors, dtype=torch.int64, device=dev)
+        self.ignore_count = torch.empty(1, dtype=torch.int64, device=dev)
+        self.set_rowptr = torch.empty(65, dtype=torch.int64, device=dev)
+        self.set_ops = None
+        self._scratch = None
+
+    def ignore(self, stream=None) -> int:
+        r = self.result
+        return dgn_ignore_mask(r.graph.handle, r.tensor_mask, r.kept_ops, r.kept_masks, r.kept_count,
+                               self.ignore_mask, self.ignore_count, stream)
+
+    def per_set_lists(self, stream=None) -> int:
+        """Sizes ``set_ops`` from the result's counts (two small read-backs), then runs the call."""
+        r = self.result
+        num_kept = int(r.kept_count[0].item())
+        total = int(r.per_query_count.sum().item())
+        rc, sb = dgn_per_set_lists_workspace(num_kept)
+        if rc:
+            return rc
+        if self._scratch is None or self._scratch.numel() < sb:
+            self._scratch = torch.empty(sb, dtype=torch.uint8, device=self.set_rowptr.device)
+        if self.set_ops is None or self.set_ops.numel() < max(total, 1):
+            self.set_ops = torch.empty(max(total, 1), dtype=torch.int32, device=self.set_rowptr.device)
+        return dgn_per_set_lists(r.kept_ops, r.kept_masks, num_kept, self.set_rowptr, self.set_ops, total,
+                                 self._scratch, self._scratch.numel(), stream)

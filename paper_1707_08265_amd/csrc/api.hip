@@ -811,6 +811,47 @@ int dgn_backward_prune(const dgn_graph *g, int32_t num_pairs, const int32_t *obj
                             S.prune_bytes, stream);
 }
 
+int dgn_ignore_mask(const dgn_graph *g, const uint64_t *tensor_mask, const int32_t *kept_ops, const uint64_t *kept_masks,
+                    const int64_t *kept_count, uint64_t *ignore_mask, int64_t *ignore_count, dgn_stream stream)
+{
+    if (!g || !kept_count) return DGN_ERR_NULL_PTR;
+    if (g->T > 0 && (!tensor_mask || !ignore_mask)) return DGN_ERR_NULL_PTR;
+    if (g->P > 0 && (!kept_ops || !kept_masks)) return DGN_ERR_NULL_PTR;
+    if (((uintptr_t)tensor_mask | (uintptr_t)kept_masks | (uintptr_t)kept_count | (uintptr_t)ignore_mask |
+         (uintptr_t)ignore_count) & 7)
+        return DGN_ERR_INVALID_ARG;
+    DGN_HIP(launch_ignore_mask(g->v, kept_ops, reinterpret_cast<const u64 *>(kept_masks), kept_count,
+                               reinterpret_cast<const u64 *>(tensor_mask), reinterpret_cast<u64 *>(ignore_mask),
+                               ignore_count, g->num_cus * 8, static_cast<hipStream_t>(stream)));
+    return DGN_OK;
+}
+
+constexpr int kSetListBlocks = 2048;     // no graph handle here to ask for the number of compute units
+
+int dgn_per_set_lists_workspace(int64_t num_kept, size_t *scratch_bytes)
+{
+    if (!scratch_bytes) return DGN_ERR_NULL_PTR;
+    if (num_kept < 0) return DGN_ERR_INVALID_ARG;
+    if (num_kept > kMaxCount / 64) return DGN_ERR_TOO_LARGE;
+    *scratch_bytes = set_lists_scratch_bytes(num_kept);
+    return DGN_OK;
+}
+
+int dgn_per_set_lists(const int32_t *kept_ops, const uint64_t *kept_masks, int64_t num_kept, int64_t *set_rowptr,
+                      int32_t *set_ops, int64_t set_ops_capacity, void *scratch, size_t scratch_bytes, dgn_stream stream)
+{
+    if (num_kept < 0 || set_ops_capacity < 0) return DGN_ERR_INVALID_ARG;
+    if (num_kept > kMaxCount / 64) return DGN_ERR_TOO_LARGE;      // slots are counted in int32
+    if (!set_rowptr || !scratch) return DGN_ERR_NULL_PTR;
+    if (num_kept > 0 && (!kept_ops || !kept_masks)) return DGN_ERR_NULL_PTR;
+    if (set_ops_capacity > 0 && !set_ops) return DGN_ERR_NULL_PTR;
+    if (scratch_bytes < set_lists_scratch_bytes(num_kept)) return DGN_ERR_WORKSPACE_TOO_SMALL;
+    if (((uintptr_t)kept_masks | (uintptr_t)set_rowptr | (uintptr_t)scratch) & 7) return DGN_ERR_INVALID_ARG;
+    DGN_HIP(launch_set_lists(kept_ops, reinterpret_cast<const u64 *>(kept_masks), num_kept, set_rowptr, set_ops,
+                             set_ops_capacity, scratch, kSetListBlocks, static_cast<hipStream_t>(stream)));
+    return DGN_OK;
+}
+
 int dgn_inplace_workspace(const dgn_graph *g, size_t *scratch_bytes)
 {
     if (!g || !scratch_bytes) return DGN_ERR_NULL_PTR;

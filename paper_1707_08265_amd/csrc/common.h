@@ -228,6 +228,13 @@ struct CompactArgs {
 // ev (may be NULL): three events recorded after the count, scan and scatter passes.
 hipError_t launch_keep_compact(const CompactArgs &a, hipStream_t s, hipEvent_t *ev = nullptr);
 
+// Read-outs of a prune result (Sec. 3.2): ignore mask from the kept list; per-set operator lists.
+hipError_t launch_ignore_mask(const GraphView &g, const int32_t *kept_ops, const u64 *kept_masks, const int64_t *kept_count,
+                              const u64 *M, u64 *ignore, int64_t *ignore_count, int grid_blocks, hipStream_t s);
+size_t set_lists_scratch_bytes(int64_t num_kept);
+hipError_t launch_set_lists(const int32_t *kept_ops, const u64 *kept_masks, int64_t num_kept, int64_t *set_rowptr,
+                            int32_t *set_ops, int64_t capacity, void *scratch, int grid_blocks, hipStream_t s);
+
 // Backward Prune (Algorithm 2): target row pointers 0..n (rowptr_only) or the seeds of the forward stage;
 // one pass of the forward stage over the kept operators of the first stage.
 hipError_t launch_backward_seed(int64_t T, int num_pairs, const int32_t *obj, const int32_t *wrt, int32_t *tgt_rowptr,
