@@ -169,6 +169,32 @@ def main():
         f"{inplace['graph_tensors']} tensors renamed")
     del ip
 
+    # ---- read-outs of the result (Sec. 3.2): ignore mask, per-set operator lists; timed on their own --
+    ro = d.ReadoutBuffers(buf)
+    ro_ms = {"ignore": [], "lists": []}
+    for _ in range(1 + max(3, min(args.steps, 10))):
+        torch.cuda.synchronize()
+        tb = time.perf_counter()
+        rc = ro.ignore()
+        torch.cuda.synchronize()
+        ro_ms["ignore"].append((time.perf_counter() - tb) * 1e3)
+        assert rc == 0, d.dgn_strerror(rc)
+        tb = time.perf_counter()
+        rc = ro.per_set_lists()
+        torch.cuda.synchronize()
+        ro_ms["lists"].append((time.perf_counter() - tb) * 1e3)
+        assert rc == 0, d.dgn_strerror(rc)
+    ro_rowptr = ro.set_rowptr.cpu().numpy()
+    ro_ignore = ro.ignore_mask.cpu().numpy().view(np.uint64)
+    ro_ops = ro.set_ops[: int(ro_rowptr[64])].cpu().numpy()
+    readout = {"ignore_ms": round(float(np.median(ro_ms["ignore"][1:])), 4),
+               "ignored_tensors": int(ro.ignore_count.item()),
+               "per_set_lists_ms": round(float(np.median(ro_ms["lists"][1:])), 4),
+               "list_entries": int(ro_rowptr[64]), "bit_exact_vs_oracle": None}
+    log(f"read-outs: ignore mask {readout['ignore_ms']:.3f} ms ({readout['ignored_tensors']} tensors), per-set lists "
+        f"{readout['per_set_lists_ms']:.3f} ms ({readout['list_entries']} entries; includes two small read-backs)")
+    del ro
+
     # ---- backward prune (Algorithm 2) on the same graph, 64 pairs, timed on its own ---------------
     backward = None
     if g.num_graphs == 1:
@@ -264,6 +290,11 @@ def main():
         log(f"oracle in-place pass: {inplace['cpu_oracle_ms']:.0f} ms; GPU rename dictionary bit-exact: "
             f"{inplace['bit_exact_vs_oracle']}")
         assert inplace["bit_exact_vs_oracle"], "GPU rename dictionary differs from the oracle"
+        ref_ig = orc.ignore_mask(adj, ref.op_mask, ref.tensor_mask)
+        ref_rowptr, ref_ops = orc.per_set_lists(ref.op_mask)
+        readout["bit_exact_vs_oracle"] = bool(np.array_equal(ro_ignore, ref_ig) and np.array_equal(ro_rowptr, ref_rowptr)
+                                              and np.array_equal(ro_ops, ref_ops))
+        assert readout["bit_exact_vs_oracle"], "GPU read-outs differ from the oracle"
         if backward is not None:                 # one pair (a graph-wide search each): the bounded sample
             i = int(np.flatnonzero(bw_out["per_query_count"])[0]) if backward["connected_pairs"] else 0
             tb = time.perf_counter()
@@ -287,6 +318,7 @@ def main():
         "phase_ms": {k: round(v, 4) for k, v in ph.items()},
         "build_ms": round(build_ms, 3),
         "inplace": inplace,
+        "readout": readout,
         "backward_prune": backward,
         "build_plus_prune_gteps": round(E / ((build_ms + ms_per_step) * 1e-3) / 1e9, 2),
         "result": {"kept_ops": P_k, "coloured_tensors": T_c, "kept_in_edges": E_k, "kept_out_edges": Eo_k,
