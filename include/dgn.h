@@ -209,6 +209,21 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
               void *scratch, size_t scratch_bytes, const dgn_options *options, dgn_stats *stats,
               dgn_stream stream);
 
+/* More than 64 target sets on one graph: dgn_prune once per word of 64 sets, one after the other.
+ *   num_sets: any number >= 1; W = ceil(num_sets / 64) words; set s owns bit s % 64 of word s / 64.
+ *   tgt_rowptr [num_sets+1], tgt_idx [num_targets]: as for dgn_prune.
+ *   Outputs are word-major: tensor_mask [W][num_tensors], op_mask [W][num_ops], op_flag [W][num_ops],
+ *   kept_ops [W][num_ops], kept_masks [W][num_ops], kept_count [W], per_query_count [W][64]
+ *   (the same pointers may be NULL as for dgn_prune).  scratch: as for dgn_prune (reused by every word).
+ *   stats: sums over the words (max_frontier: the maximum).
+ * Single graphs only (DGN_ERR_INVALID_ARG for a packed batch).  The call synchronises the stream at
+ * least once per word. */
+int dgn_prune_words(const dgn_graph *g, int64_t num_sets, int64_t num_targets, const int32_t *tgt_rowptr,
+                    const int32_t *tgt_idx, uint64_t *tensor_mask, uint64_t *op_mask, uint8_t *op_flag,
+                    int32_t *kept_ops, uint64_t *kept_masks, int64_t *kept_count, int64_t *per_query_count,
+                    void *scratch, size_t scratch_bytes, const dgn_options *options, dgn_stats *stats,
+                    dgn_stream stream);
+
 /* Removal rule + compaction only (Sec. 2.1, Sec. 3.2), for a caller that supplies the coloured
  * masks: K[o] = OR of tensor_mask_in over the outputs of o, then the same outputs as dgn_prune.
  * Asynchronous on `stream`: nothing is read back. */

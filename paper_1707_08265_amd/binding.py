@@ -31,7 +31,7 @@ DGN_ERR_INTERNAL = -10
 EXPORTS = [
     "dgn_graph_build_workspace", "dgn_graph_build", "dgn_graph_from_csr_workspace", "dgn_graph_from_csr",
     "dgn_graph_get_csr", "dgn_graph_get_sizes", "dgn_graph_destroy", "dgn_prune_workspace", "dgn_prune",
-    "dgn_keep_compact", "dgn_backward_prune_workspace", "dgn_backward_prune", "dgn_inplace_workspace",
+    "dgn_prune_words", "dgn_keep_compact", "dgn_backward_prune_workspace", "dgn_backward_prune", "dgn_inplace_workspace",
     "dgn_inplace", "dgn_ignore_mask", "dgn_per_set_lists_workspace", "dgn_per_set_lists", "dgn_strerror",
     "dgn_version",
     "dgn_last_hip_error",
@@ -92,6 +92,8 @@ def _load() -> ctypes.CDLL:
     lib.dgn_prune_workspace.argtypes = [c_void_p, c_int32, POINTER(c_size_t)]
     lib.dgn_prune.argtypes = [c_void_p, c_int32, c_int64] + [c_void_p] * 9 + [c_void_p, c_size_t,
                               POINTER(dgn_options), POINTER(dgn_stats), c_void_p]
+    lib.dgn_prune_words.argtypes = [c_void_p, c_int64, c_int64] + [c_void_p] * 9 + [c_void_p, c_size_t,
+                                    POINTER(dgn_options), POINTER(dgn_stats), c_void_p]
     lib.dgn_keep_compact.argtypes = [c_void_p] + [c_void_p] * 7 + [c_void_p, c_size_t, c_void_p]
     lib.dgn_backward_prune_workspace.argtypes = [c_void_p, POINTER(c_size_t)]
     lib.dgn_backward_prune.argtypes = [c_void_p, c_int32] + [c_void_p] * 9 + [c_void_p, c_size_t,
@@ -233,6 +235,15 @@ def dgn_prune(handle, num_sets, num_targets, tgt_rowptr, tgt_idx, tensor_mask, o
                           _dp(op_mask), _dp(op_flag), _dp(kept_ops), _dp(kept_masks), _dp(kept_count),
                           _dp(per_query_count), _dp(scratch), scratch_bytes, _opt(options),
                           ctypes.byref(stats) if stats is not None else None, _stream(stream))
+
+
+def dgn_prune_words(handle, num_sets, num_targets, tgt_rowptr, tgt_idx, tensor_mask, op_mask, op_flag, kept_ops,
+                    kept_masks, kept_count, per_query_count, scratch, scratch_bytes, options=None, stats=None,
+                    stream=None) -> int:
+    return _lib.dgn_prune_words(handle, num_sets, num_targets, _dp(tgt_rowptr), _dp(tgt_idx), _dp(tensor_mask),
+                                _dp(op_mask), _dp(op_flag), _dp(kept_ops), _dp(kept_masks), _dp(kept_count),
+                                _dp(per_query_count), _dp(scratch), scratch_bytes, _opt(options),
+                                ctypes.byref(stats) if stats is not None else None, _stream(stream))
 
 
 def dgn_keep_compact(handle, tensor_mask_in, op_mask, op_flag, kept_ops, kept_masks, kept_count,

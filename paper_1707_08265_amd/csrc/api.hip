@@ -724,6 +724,48 @@ int dgn_keep_compact(const dgn_graph *g, const uint64_t *tensor_mask_in, uint64_
     return DGN_OK;
 }
 
+int dgn_prune_words(const dgn_graph *g, int64_t num_sets, int64_t num_targets, const int32_t *tgt_rowptr,
+                    const int32_t *tgt_idx, uint64_t *tensor_mask, uint64_t *op_mask, uint8_t *op_flag, int32_t *kept_ops,
+                    uint64_t *kept_masks, int64_t *kept_count, int64_t *per_query_count, void *scratch,
+                    size_t scratch_bytes, const dgn_options *options, dgn_stats *stats, dgn_stream stream)
+{
+    if (!g) return DGN_ERR_NULL_PTR;
+    if (num_sets < 1 || num_sets > kMaxCount) return DGN_ERR_TOO_MANY_SETS;
+    if (g->G > 1) return DGN_ERR_INVALID_ARG;        // a packed batch already numbers its sets graph by graph
+    if (!tgt_rowptr) return DGN_ERR_NULL_PTR;
+    const int64_t words = (num_sets + DGN_MAX_SETS - 1) / DGN_MAX_SETS;
+    const size_t P = (size_t)g->P, T = (size_t)g->T;
+    dgn_stats total{};
+    if (stats) total = *stats;
+    total.levels = total.tensor_visits = total.launches = total.level_launches = 0;
+    total.max_frontier = 0;
+    for (int64_t w = 0; w < words; ++w) {
+        const int32_t q = (int32_t)((num_sets - w * DGN_MAX_SETS) < DGN_MAX_SETS ? (num_sets - w * DGN_MAX_SETS) : DGN_MAX_SETS);
+        // the sets of this word own entries [tgt_rowptr[64w], tgt_rowptr[64w + q]) of tgt_idx: the row
+        // pointers hold absolute positions, so the slice is passed as it is and the seed step skips
+        // every entry that lies outside it
+        dgn_stats one{};
+        if (stats) one = *stats;
+        const int rc = dgn_prune(g, q, num_targets, tgt_rowptr + w * DGN_MAX_SETS, tgt_idx,
+                                 tensor_mask ? tensor_mask + w * T : nullptr, op_mask ? op_mask + w * P : nullptr,
+                                 op_flag ? op_flag + w * P : nullptr, kept_ops ? kept_ops + w * P : nullptr,
+                                 kept_masks ? kept_masks + w * P : nullptr, kept_count ? kept_count + w : nullptr,
+                                 per_query_count ? per_query_count + w * 64 : nullptr, scratch, scratch_bytes, options,
+                                 stats ? &one : nullptr, stream);
+        if (rc != DGN_OK) return rc;
+        if (stats) {
+            total.levels += one.levels;
+            total.tensor_visits += one.tensor_visits;
+            total.launches += one.launches;
+            total.level_launches += one.level_launches;
+            if (one.max_frontier > total.max_frontier) total.max_frontier = one.max_frontier;
+            for (int i = 0; i < 8; ++i) total.phase_ms[i] = (w ? total.phase_ms[i] : 0.0f) + one.phase_ms[i];
+        }
+    }
+    if (stats) *stats = total;
+    return DGN_OK;
+}
+
 // ---- Backward Prune: scratch = [prune scratch][B: 8T][K of stage one: 8P][its kept list: 4P][small] ----
 struct BackwardScratch {
     size_t prune_bytes;

@@ -325,3 +325,52 @@ def test_packed_batches_use_the_per_graph_sweep(dgn, oracle):
     _, _, out = gpu_prune(dgn, g, tg)
     _, r = oracle_prune(oracle, g, tg)
     assert_same(out, r, "non-topological batch")
+
+
+def test_more_than_64_sets_run_word_by_word(dgn, oracle):
+    """150 target sets on one graph: three words of 64, 64 and 22 sets, each equal to the oracle's run
+    of Algorithm 1 on exactly those sets."""
+    import torch
+    g, _ = gg.config(1, 0.3)
+    n_sets = 150
+    tg = gg.targets_tail(g, 4242, n_sets, 1, 5, 0.2)
+    dg = dgn.DeviceGraph.from_coo(g)
+    P, T, W = g.num_ops, g.num_tensors, 3
+    rc, sb = dgn.dgn_prune_workspace(dg.handle, 64)
+    assert rc == 0
+    dev = "cuda"
+    M = torch.empty(W * T, dtype=torch.int64, device=dev)
+    K = torch.empty(W * P, dtype=torch.int64, device=dev)
+    flag = torch.empty(W * P, dtype=torch.uint8, device=dev)
+    kept = torch.empty(W * P, dtype=torch.int32, device=dev)
+    kmask = torch.empty(W * P, dtype=torch.int64, device=dev)
+    count = torch.empty(W, dtype=torch.int64, device=dev)
+    pq = torch.empty(W * 64, dtype=torch.int64, device=dev)
+    scratch = torch.empty(sb, dtype=torch.uint8, device=dev)
+    st = dgn.dgn_stats()
+    rc = dgn.dgn_prune_words(dg.handle, n_sets, int(tg.tgt_idx.shape[0]), torch.from_numpy(tg.tgt_rowptr).cuda(),
+                             torch.from_numpy(tg.tgt_idx).cuda(), M, K, flag, kept, kmask, count, pq, scratch, sb,
+                             None, st)
+    assert rc == 0, dgn.dgn_strerror(rc)
+    torch.cuda.synchronize()
+    adj = oracle.build_adjacency(g.num_ops, g.num_tensors, g.in_op, g.in_tensor, g.out_op, g.out_tensor)
+    u = lambda t: t.cpu().numpy().view(np.uint64)
+    levels = 0
+    for w in range(W):
+        lo, hi = 64 * w, min(64 * (w + 1), n_sets)
+        rowptr = (tg.tgt_rowptr[lo:hi + 1] - tg.tgt_rowptr[lo]).astype(np.int32)
+        idx = tg.tgt_idx[tg.tgt_rowptr[lo]:tg.tgt_rowptr[hi]]
+        ref = oracle.forward_prune(adj, hi - lo, rowptr, idx)
+        n = int(count[w].item())
+        assert n == int(ref.kept_count[0])
+        assert np.array_equal(u(M[w * T:(w + 1) * T]), ref.tensor_mask), f"word {w}"
+        assert np.array_equal(u(K[w * P:(w + 1) * P]), ref.op_mask), f"word {w}"
+        assert np.array_equal(flag[w * P:(w + 1) * P].cpu().numpy(), ref.op_flag), f"word {w}"
+        assert np.array_equal(kept[w * P:w * P + n].cpu().numpy(), ref.kept_ops), f"word {w}"
+        assert np.array_equal(u(kmask[w * P:w * P + n]), ref.kept_masks), f"word {w}"
+        assert np.array_equal(pq[w * 64:(w + 1) * 64].cpu().numpy(), ref.per_query_count), f"word {w}"
+    assert st.levels > 3 and st.launches > 3
+    # a packed batch is refused, and so is a set count below one
+    rc = dgn.dgn_prune_words(dg.handle, 0, 0, torch.from_numpy(tg.tgt_rowptr).cuda(), None, M, K, flag, kept, kmask,
+                             count, pq, scratch, sb)
+    assert rc == dgn.DGN_ERR_TOO_MANY_SETS
