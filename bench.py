@@ -57,6 +57,8 @@ def main():
     ap.add_argument("--generic", action="store_true", help="force the one-launch-per-level traversal")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known size, to scale profiler byte counters)")
+    ap.add_argument("--prune-only", action="store_true",
+                    help="skip the separately timed in-place, read-out and backward-prune legs (for profiling runs)")
     ap.add_argument("--trace-levels", action="store_true", help="print the per-level trace of the last step")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -150,79 +152,86 @@ def main():
     out = buf.to_host()
     P, T = g.num_ops, g.num_tensors
 
-    # ---- in-place pass on the pruned graph (Algorithm 3), timed on its own, not part of `value` ---
-    ip = d.InplaceBuffers(dg)
-    ip_ms = []
-    for _ in range(1 + max(3, min(args.steps, 10))):
-        torch.cuda.synchronize()
-        tb = time.perf_counter()
-        rc = ip.run(buf.op_mask)
-        torch.cuda.synchronize()
-        ip_ms.append((time.perf_counter() - tb) * 1e3)
-        assert rc == 0, d.dgn_strerror(rc)
-    ip_ms = float(np.median(ip_ms[1:]))
-    ip_rename = ip.rename.cpu().numpy()
-    inplace = {"ms": round(ip_ms, 4), "rounds": int(ip.rounds), "renamed_tensors": int(ip.renamed_count.item()),
-               "graph_tensors": int((ip_rename >= 0).sum()), "select": "all sets (union graph)",
-               "cpu_oracle_ms": None, "bit_exact_vs_oracle": None}
-    log(f"in-place pass: {ip_ms:.3f} ms, {inplace['rounds']} rounds, {inplace['renamed_tensors']} of "
-        f"{inplace['graph_tensors']} tensors renamed")
-    del ip
-
-    # ---- read-outs of the result (Sec. 3.2): ignore mask, per-set operator lists; timed on their own --
-    ro = d.ReadoutBuffers(buf)
-    ro_ms = {"ignore": [], "lists": []}
-    for _ in range(1 + max(3, min(args.steps, 10))):
-        torch.cuda.synchronize()
-        tb = time.perf_counter()
-        rc = ro.ignore()
-        torch.cuda.synchronize()
-        ro_ms["ignore"].append((time.perf_counter() - tb) * 1e3)
-        assert rc == 0, d.dgn_strerror(rc)
-        tb = time.perf_counter()
-        rc = ro.per_set_lists()
-        torch.cuda.synchronize()
-        ro_ms["lists"].append((time.perf_counter() - tb) * 1e3)
-        assert rc == 0, d.dgn_strerror(rc)
-    ro_rowptr = ro.set_rowptr.cpu().numpy()
-    ro_ignore = ro.ignore_mask.cpu().numpy().view(np.uint64)
-    ro_ops = ro.set_ops[: int(ro_rowptr[64])].cpu().numpy()
-    readout = {"ignore_ms": round(float(np.median(ro_ms["ignore"][1:])), 4),
-               "ignored_tensors": int(ro.ignore_count.item()),
-               "per_set_lists_ms": round(float(np.median(ro_ms["lists"][1:])), 4),
-               "list_entries": int(ro_rowptr[64]), "bit_exact_vs_oracle": None}
-    log(f"read-outs: ignore mask {readout['ignore_ms']:.3f} ms ({readout['ignored_tensors']} tensors), per-set lists "
-        f"{readout['per_set_lists_ms']:.3f} ms ({readout['list_entries']} entries; includes two small read-backs)")
-    del ro
-
-    # ---- backward prune (Algorithm 2) on the same graph, 64 pairs, timed on its own ---------------
-    backward = None
-    if g.num_graphs == 1:
-        n_src = 400 if args.config == 1 else 16
-        obj_h, wrt_h = gg.backward_pairs(g, gg.BASE_SEED + 1000 * args.config, 64, n_src)
-        bb = d.BackwardPruneBuffers(dg, 64)
-        obj_d, wrt_d = up(obj_h), up(wrt_h)
-        bst = d.dgn_stats()
-        bw_ms = []
+    inplace = readout = backward = None
+    extras = {}
+    if not args.prune_only:
+        # ---- in-place pass on the pruned graph (Algorithm 3), timed on its own, not part of `value` ---
+        ip = d.InplaceBuffers(dg)
+        ip_ms = []
         for _ in range(1 + max(3, min(args.steps, 10))):
             torch.cuda.synchronize()
             tb = time.perf_counter()
-            rc = bb.backward_prune(obj_d, wrt_d, stats=bst)
+            rc = ip.run(buf.op_mask)
             torch.cuda.synchronize()
-            bw_ms.append((time.perf_counter() - tb) * 1e3)
+            ip_ms.append((time.perf_counter() - tb) * 1e3)
             assert rc == 0, d.dgn_strerror(rc)
-        bw_ms = float(np.median(bw_ms[1:]))
-        bw_out = bb.to_host()
-        backward = {"ms": round(bw_ms, 4), "gteps": round(E / (bw_ms * 1e-3) / 1e9, 2), "pairs": 64,
-                    "forward_passes": int(bst.reserved), "first_stage_levels": int(bst.levels),
-                    "marked_tensors": int(np.count_nonzero(bw_out["tensor_mask"])),
-                    "kept_ops": int(bw_out["kept_count"][0]),
-                    "connected_pairs": int(np.count_nonzero(bw_out["per_query_count"])),
-                    "cpu_oracle_ms_per_pair": None, "bit_exact_vs_oracle_sampled_pair": None}
-        log(f"backward prune: {bw_ms:.3f} ms ({backward['gteps']} GTEPS), {backward['forward_passes']} forward passes, "
-            f"{backward['marked_tensors']} tensors marked, {backward['kept_ops']} operators kept, "
-            f"{backward['connected_pairs']} of 64 pairs connected")
-        del bb
+        ip_ms = float(np.median(ip_ms[1:]))
+        ip_rename = ip.rename.cpu().numpy()
+        inplace = {"ms": round(ip_ms, 4), "rounds": int(ip.rounds), "renamed_tensors": int(ip.renamed_count.item()),
+                   "graph_tensors": int((ip_rename >= 0).sum()), "select": "all sets (union graph)",
+                   "cpu_oracle_ms": None, "bit_exact_vs_oracle": None}
+        log(f"in-place pass: {ip_ms:.3f} ms, {inplace['rounds']} rounds, {inplace['renamed_tensors']} of "
+            f"{inplace['graph_tensors']} tensors renamed")
+        del ip
+
+        # ---- read-outs of the result (Sec. 3.2): ignore mask, per-set operator lists; timed on their own --
+        ro = d.ReadoutBuffers(buf)
+        ro_ms = {"ignore": [], "lists": []}
+        for _ in range(1 + max(3, min(args.steps, 10))):
+            torch.cuda.synchronize()
+            tb = time.perf_counter()
+            rc = ro.ignore()
+            torch.cuda.synchronize()
+            ro_ms["ignore"].append((time.perf_counter() - tb) * 1e3)
+            assert rc == 0, d.dgn_strerror(rc)
+            tb = time.perf_counter()
+            rc = ro.per_set_lists()
+            torch.cuda.synchronize()
+            ro_ms["lists"].append((time.perf_counter() - tb) * 1e3)
+            assert rc == 0, d.dgn_strerror(rc)
+        ro_rowptr = ro.set_rowptr.cpu().numpy()
+        ro_ignore = ro.ignore_mask.cpu().numpy().view(np.uint64)
+        ro_ops = ro.set_ops[: int(ro_rowptr[64])].cpu().numpy()
+        readout = {"ignore_ms": round(float(np.median(ro_ms["ignore"][1:])), 4),
+                   "ignored_tensors": int(ro.ignore_count.item()),
+                   "per_set_lists_ms": round(float(np.median(ro_ms["lists"][1:])), 4),
+                   "list_entries": int(ro_rowptr[64]), "bit_exact_vs_oracle": None}
+        log(f"read-outs: ignore mask {readout['ignore_ms']:.3f} ms ({readout['ignored_tensors']} tensors), per-set lists "
+            f"{readout['per_set_lists_ms']:.3f} ms ({readout['list_entries']} entries; includes two small read-backs)")
+        del ro
+
+        # ---- backward prune (Algorithm 2) on the same graph, 64 pairs, timed on its own ---------------
+        backward = None
+        if g.num_graphs == 1:
+            n_src = 400 if args.config == 1 else 16
+            obj_h, wrt_h = gg.backward_pairs(g, gg.BASE_SEED + 1000 * args.config, 64, n_src)
+            bb = d.BackwardPruneBuffers(dg, 64)
+            obj_d, wrt_d = up(obj_h), up(wrt_h)
+            bst = d.dgn_stats()
+            bw_ms = []
+            for _ in range(1 + max(3, min(args.steps, 10))):
+                torch.cuda.synchronize()
+                tb = time.perf_counter()
+                rc = bb.backward_prune(obj_d, wrt_d, stats=bst)
+                torch.cuda.synchronize()
+                bw_ms.append((time.perf_counter() - tb) * 1e3)
+                assert rc == 0, d.dgn_strerror(rc)
+            bw_ms = float(np.median(bw_ms[1:]))
+            bw_out = bb.to_host()
+            backward = {"ms": round(bw_ms, 4), "gteps": round(E / (bw_ms * 1e-3) / 1e9, 2), "pairs": 64,
+                        "forward_passes": int(bst.reserved), "first_stage_levels": int(bst.levels),
+                        "marked_tensors": int(np.count_nonzero(bw_out["tensor_mask"])),
+                        "kept_ops": int(bw_out["kept_count"][0]),
+                        "connected_pairs": int(np.count_nonzero(bw_out["per_query_count"])),
+                        "cpu_oracle_ms_per_pair": None, "bit_exact_vs_oracle_sampled_pair": None}
+            log(f"backward prune: {bw_ms:.3f} ms ({backward['gteps']} GTEPS), {backward['forward_passes']} forward passes, "
+                f"{backward['marked_tensors']} tensors marked, {backward['kept_ops']} operators kept, "
+                f"{backward['connected_pairs']} of 64 pairs connected")
+            del bb
+        extras = dict(ip_rename=ip_rename, ro_rowptr=ro_rowptr, ro_ignore=ro_ignore, ro_ops=ro_ops)
+        if backward is not None:
+            extras.update(bw_out=bw_out, obj_h=obj_h, wrt_h=wrt_h)
+
     P_k = int(out["kept_count"][0])
     T_c = int(np.count_nonzero(out["tensor_mask"]))
     fan_in = np.bincount(g.in_op, minlength=P)
@@ -283,6 +292,8 @@ def main():
                      ("tensor_mask", "op_mask", "op_flag", "kept_ops", "kept_masks", "kept_count", "per_query_count"))
         log(f"oracle: {cpu_s:.2f}s -> {cpu['value']} GTEPS on 1 core; GPU output bit-exact vs oracle: {parity}")
         assert parity, "GPU result differs from the oracle"
+    if cpu is not None and inplace is not None:
+        ip_rename, ro_rowptr, ro_ignore, ro_ops = (extras[k] for k in ("ip_rename", "ro_rowptr", "ro_ignore", "ro_ops"))
         tb = time.perf_counter()
         ref_rd = orc.inplace(adj, ref.op_mask)
         inplace["cpu_oracle_ms"] = round((time.perf_counter() - tb) * 1e3, 1)
@@ -296,6 +307,7 @@ def main():
                                               and np.array_equal(ro_ops, ref_ops))
         assert readout["bit_exact_vs_oracle"], "GPU read-outs differ from the oracle"
         if backward is not None:                 # one pair (a graph-wide search each): the bounded sample
+            bw_out, obj_h, wrt_h = extras["bw_out"], extras["obj_h"], extras["wrt_h"]
             i = int(np.flatnonzero(bw_out["per_query_count"])[0]) if backward["connected_pairs"] else 0
             tb = time.perf_counter()
             ref_m = orc.backward_mark(adj, obj_h[i:i + 1], wrt_h[i:i + 1])

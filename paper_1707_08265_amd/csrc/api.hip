@@ -127,7 +127,7 @@ struct PruneScratch {
     TravCounters *ctr;
     int32_t *q0, *q1;       // frontier queues: qg.S segments of qg.seg_cap tensor ids each
     QueueGeom qg;
-    u64 *DB;                // deferred-operator bitmap
+    uint8_t *DB;            // deferred-operator markers, one byte per operator
     u64 *opbits;
     int32_t *block_counts;
     int4 *trace;            // per-level trace records (profiling only)
@@ -163,8 +163,8 @@ PruneScratch prune_scratch(void *mem, int64_t P, int64_t T, int32_t G, int64_t m
     S.q0 = c.take<int32_t>(qn);
     S.q1 = c.take<int32_t>(qn);
     const size_t obw = (size_t)((P + 63) / 64);
-    S.DB = c.take<u64>(obw);
-    S.db_bytes = obw * 8;
+    S.DB = c.take<uint8_t>(obw * 64);         // a whole number of 64-operator words, so chunk loads stay inside
+    S.db_bytes = obw * 64;
     S.opbits = c.take<u64>(obw);
     S.opbits_bytes = obw * 8;
     S.block_counts = c.take<int32_t>((P + kCompactTile - 1) / kCompactTile + 1);

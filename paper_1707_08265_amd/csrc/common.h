@@ -155,6 +155,14 @@ __device__ __forceinline__ void store_coherent(int32_t *p, int32_t v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ void store_coherent(uint8_t *p, uint8_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t load_coherent(const uint32_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 // ---- launch wrappers (each returns a hipError_t; nothing synchronises) -------------------------
 struct FillRegion { void *ptr; size_t bytes; };   // ptr 8-byte aligned, bytes multiple of 8
@@ -189,17 +197,17 @@ hipError_t launch_seed(const GraphView &g, int32_t Q, int64_t num_targets, const
 // One wide level (whole chip); a frontier of at most narrow_cap entries is left to launch_narrow unless
 // deferred operators are waiting.  DB: deferred-operator bitmap, one bit per operator.
 hipError_t launch_level(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
-                        const QueueGeom &qg, u64 *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
+                        const QueueGeom &qg, uint8_t *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
                         const Schedule &sch, int4 *trace, hipStream_t s);
 // All consecutive wide levels in one cooperative launch (grid barrier between levels); grid_blocks must
 // not exceed persist_max_grid().  A waiting block gives up after max_spins polls (kErrBarrier).
 hipError_t launch_persist(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
-                          const QueueGeom &qg, u64 *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
+                          const QueueGeom &qg, uint8_t *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
                           const Schedule &sch, int4 *trace, int max_spins, hipStream_t s);
 hipError_t persist_max_grid(int num_cus, int *grid_blocks);
 // One workgroup runs level after level while 0 < frontier <= narrow_cap and nothing is deferred.
 hipError_t launch_narrow(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
-                         const QueueGeom &qg, u64 *DB, u64 *M, u64 *K, int narrow_cap, int4 *trace, hipStream_t s);
+                         const QueueGeom &qg, uint8_t *DB, u64 *M, u64 *K, int narrow_cap, int4 *trace, hipStream_t s);
 // Packed batches of small graphs whose operator ids are a topological order: one wave per graph sweeps
 // its operators once, highest ids first (no frontier at all); fills K and, when pq is not NULL, the
 // per-graph per-set counts.

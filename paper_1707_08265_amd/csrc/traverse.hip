@@ -250,7 +250,7 @@ struct LevelCounters {   // per-lane tallies, reduced by the caller
 };
 
 // Tensor-side step: 64 frontier tensors held one per lane (valid lanes only).
-__device__ __forceinline__ void process_entries(const GraphView &g, bool valid, int32_t t, int32_t theta, u64 *DB,
+__device__ __forceinline__ void process_entries(const GraphView &g, bool valid, int32_t t, int32_t theta, uint8_t *DB,
                                                 u64 *M, u64 *K, int *s_incl, WaveStage &ws, const Frontier &f,
                                                 LevelCounters &lc)
 {
@@ -262,8 +262,7 @@ __device__ __forceinline__ void process_entries(const GraphView &g, bool valid, 
         const u64 mt = load_coherent(&M[t]);                // (I4): everything t holds right now (issued
                                                             // together with the record: no dependency)
         if (pi.x >= 0 && pi.x < theta) {                    // (I5): wait for the threshold to pass o
-            const u64 ob = (u64)1 << (pi.x & 63);
-            if ((load_coherent(&DB[pi.x >> 6]) & ob) == 0) atomicOr(&DB[pi.x >> 6], ob);
+            store_coherent(&DB[pi.x], (uint8_t)1);          // a byte per operator: a plain store, no atomic
             lc.max_deferred_key = max(lc.max_deferred_key, pi.x);
         } else if (pi.x != kNoProducer) {
             active = true;
@@ -390,7 +389,7 @@ __device__ __forceinline__ LevelPlan plan_level(const LevelSlot &in, int n, bool
 // The work of block `blk` (< p.nwork) in one level: its share of the frontier entries and of the
 // newly opened operator range.  Leaves the block's tallies in sh.proc / sh.maxkey (one per wave).
 __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &in, int n, const LevelPlan &p, int blk,
-                                          const int32_t *qin, const QueueGeom &qg, const Frontier &f, u64 *DB, u64 *M,
+                                          const int32_t *qin, const QueueGeom &qg, const Frontier &f, uint8_t *DB, u64 *M,
                                           u64 *K, LevelShared &sh)
 {
     const int lane = lane_id(), wave = threadIdx.x >> 6;
@@ -411,22 +410,28 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
     // expand the bitmap words of the newly opened range into dense operator lists, 64 per step
     for (int c = s_first * kLevelWaves + wave; do_scan && c < p.chunks; c += s_blocks * kLevelWaves) {
         const int w0 = p.w_lo + (c << p.cw_log);
-        u64 word = 0;
-        if (lane < cw && w0 + lane < p.w_hi) {
-            word = load_coherent(&DB[w0 + lane]);
-            const int64_t first = (int64_t)(w0 + lane) * 64;             // keep only ids in [theta, theta_hi)
-            if (first < in.theta) word &= ~(((u64)1 << (in.theta - first)) - 1);
-            if (first + 64 > in.theta_hi) word &= ((u64)1 << (in.theta_hi - first)) - 1;
+        // lane L looks at the cw operators from op0 on (cw = 1..16 marker bytes, aligned to cw)
+        const int64_t op0 = (int64_t)w0 * 64 + (lane << p.cw_log);
+        uint32_t bits16 = 0;
+        if (op0 < (int64_t)p.w_hi * 64) {
+            const uint32_t *src = reinterpret_cast<const uint32_t *>(DB + (op0 & ~(int64_t)3));
+            if (cw >= 4) {
+                for (int k = 0; k < (cw >> 2); ++k)         // bytes are 0 or 1: gather bit 0 of each
+                    bits16 |= (((load_coherent(src + k) & 0x01010101u) * 0x01020408u) >> 24) << (4 * k);
+            } else {
+                const uint32_t x = load_coherent(src) >> ((int)(op0 & 3) * 8);
+                bits16 = (((x & 0x01010101u) * 0x01020408u) >> 24) & ((1u << cw) - 1u);
+            }
+            // keep only ids in [theta, theta_hi)
+            const int64_t lo_cut = in.theta - op0, hi_cut = in.theta_hi - op0;
+            if (lo_cut > 0) bits16 &= lo_cut >= cw ? 0u : ~((1u << lo_cut) - 1u);
+            if (hi_cut < cw) bits16 &= hi_cut <= 0 ? 0u : (1u << hi_cut) - 1u;
         }
-        // lane L expands part (L >> cw_log) of word (L & (cw-1)); a part is cw bits wide
-        const u64 wsel = shfl64(word, lane & (cw - 1));
-        const int part = lane >> p.cw_log;
-        uint32_t bits16 = (uint32_t)(wsel >> (part << p.cw_log)) & ((1u << cw) - 1u);
         const int cnt = __popc(bits16);
         const int incl = wave_incl_scan(cnt);
         const int total = __shfl(incl, kWave - 1, kWave);
         int pos = incl - cnt;
-        const int32_t op_base = (w0 + (lane & (cw - 1))) * 64 + (part << p.cw_log);
+        const int32_t op_base = (int32_t)op0;
         while (bits16) {
             const int b = __builtin_ctz(bits16);
             bits16 &= bits16 - 1;
@@ -516,7 +521,7 @@ __device__ __forceinline__ void publish_level(TravState *st, TravCounters *ctr, 
 }
 
 __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState *st, TravCounters *ctr, int launch_no,
-                                                          int32_t *q0, int32_t *q1, QueueGeom qg, u64 *DB, u64 *M,
+                                                          int32_t *q0, int32_t *q1, QueueGeom qg, uint8_t *DB, u64 *M,
                                                           u64 *K, int narrow_cap, Schedule sch, int4 *trace)
 {
     __shared__ LevelShared sh;
@@ -565,7 +570,7 @@ __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState 
 }
 
 hipError_t launch_level(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
-                        const QueueGeom &qg, u64 *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
+                        const QueueGeom &qg, uint8_t *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
                         const Schedule &sch, int4 *trace, hipStream_t s)
 {
     hipLaunchKernelGGL(k_level, dim3((unsigned)grid_blocks), dim3(kLevelThreads), 0, s, g, st, ctr, launch_no, q0, q1,
@@ -593,7 +598,7 @@ __device__ __forceinline__ LevelSlot load_slot_coherent(const LevelSlot *s)
 }
 
 __global__ __launch_bounds__(kLevelThreads) void k_persist(GraphView g, TravState *st, TravCounters *ctr, int launch_no,
-                                                            int32_t *q0, int32_t *q1, QueueGeom qg, u64 *DB, u64 *M,
+                                                            int32_t *q0, int32_t *q1, QueueGeom qg, uint8_t *DB, u64 *M,
                                                             u64 *K, int narrow_cap, Schedule sch, int4 *trace,
                                                             int max_spins)
 {
@@ -683,7 +688,7 @@ __global__ __launch_bounds__(kLevelThreads) void k_persist(GraphView g, TravStat
 }
 
 hipError_t launch_persist(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
-                          const QueueGeom &qg, u64 *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
+                          const QueueGeom &qg, uint8_t *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
                           const Schedule &sch, int4 *trace, int max_spins, hipStream_t s)
 {
     GraphView gv = g;
@@ -713,7 +718,7 @@ constexpr int kNarrowThreads = 1024;
 constexpr int kNarrowWaves = kNarrowThreads / kWave;
 
 __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravState *st, TravCounters *ctr, int launch_no,
-                                                            int32_t *q0, int32_t *q1, QueueGeom qg, u64 *DB, u64 *M,
+                                                            int32_t *q0, int32_t *q1, QueueGeom qg, uint8_t *DB, u64 *M,
                                                             u64 *K, int narrow_cap, int4 *trace)
 {
     __shared__ int32_t s_stage[kNarrowWaves][kStageCap];
@@ -775,7 +780,7 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
 }
 
 hipError_t launch_narrow(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
-                         const QueueGeom &qg, u64 *DB, u64 *M, u64 *K, int narrow_cap, int4 *trace, hipStream_t s)
+                         const QueueGeom &qg, uint8_t *DB, u64 *M, u64 *K, int narrow_cap, int4 *trace, hipStream_t s)
 {
     hipLaunchKernelGGL(k_narrow, dim3(1), dim3(kNarrowThreads), 0, s, g, st, ctr, launch_no, q0, q1, qg, DB, M, K,
                        narrow_cap, trace);
