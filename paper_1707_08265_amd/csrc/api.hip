@@ -6,6 +6,8 @@
 
 #include "common.h"
 
+#include <atomic>
+
 using namespace dgn;
 
 namespace {
@@ -230,6 +232,10 @@ struct dgn_graph {
     int persist_grid;       // blocks of the cooperative traversal kernel (0: not available)
     bool topological;       // operator ids verified to be a topological order at build time
     int64_t max_graph_ops;  // largest graph of a packed batch (P for a single graph)
+    // Hint only: the last prune of this graph needed wide levels, so the next one enqueues them behind the
+    // first single-workgroup launch without waiting for its outcome (a wrong hint costs a few dozen
+    // launches that return at once, and corrects itself).
+    mutable std::atomic<int> wide_hint{0};
 };
 
 namespace {
@@ -591,8 +597,10 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     if (!generic_only) {
         DGN_HIP(launch_narrow(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, narrow_cap, trace, s));
         ++launch_no; ++launches;
-        rc = read_state();
-        if (rc) return rc;
+        if (!g->wide_hint.load(std::memory_order_relaxed)) {
+            rc = read_state();
+            if (rc) return rc;
+        }
     }
     // Wide levels: preferably all of them in one cooperative launch (grid barrier between levels, no
     // host involvement); otherwise one launch per level.
@@ -639,6 +647,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
         if (!done) compacted = false;      // the speculative pass ran on unfinished masks
         first = false;
     }
+    g->wide_hint.store(hst->max_frontier > (u64)kNarrowCap ? 1 : 0, std::memory_order_relaxed);
     if (hst->error & kErrOverflow) {
         // A frontier queue overflowed and dropped entries: restore the fixed point with whole-graph
         // sweeps (each operator re-derives K from its outputs) until one of them changes nothing.
