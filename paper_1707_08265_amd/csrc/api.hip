@@ -699,13 +699,14 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     return error_bits_to_code(hst->error & ~kErrOverflow);
 }
 
-int dgn_keep_compact(const dgn_graph *g, const uint64_t *tensor_mask_in, uint64_t *op_mask, uint8_t *op_flag,
-                     int32_t *kept_ops, uint64_t *kept_masks, int64_t *kept_count, int64_t *per_query_count,
-                     void *scratch, size_t scratch_bytes, dgn_stream stream)
+// Removal rule + compaction: K computed from tensor_mask_in (from_tensor_mask), or taken as it stands in op_mask.
+static int keep_compact_impl(const dgn_graph *g, const uint64_t *tensor_mask_in, bool from_tensor_mask, uint64_t *op_mask,
+                             uint8_t *op_flag, int32_t *kept_ops, uint64_t *kept_masks, int64_t *kept_count,
+                             int64_t *per_query_count, void *scratch, size_t scratch_bytes, dgn_stream stream)
 {
     if (!g) return DGN_ERR_NULL_PTR;
     if (!kept_count || !scratch) return DGN_ERR_NULL_PTR;
-    if ((g->T > 0 && !tensor_mask_in) || (g->P > 0 && (!op_mask || !kept_ops))) return DGN_ERR_NULL_PTR;
+    if ((g->T > 0 && from_tensor_mask && !tensor_mask_in) || (g->P > 0 && (!op_mask || !kept_ops))) return DGN_ERR_NULL_PTR;
     const PruneScratch S = prune_scratch(scratch, g->P, g->T, g->G, 0);
     if (scratch_bytes < S.bytes) return DGN_ERR_WORKSPACE_TOO_SMALL;
     if (((uintptr_t)scratch | (uintptr_t)tensor_mask_in | (uintptr_t)op_mask | (uintptr_t)kept_masks |
@@ -728,9 +729,17 @@ int dgn_keep_compact(const dgn_graph *g, const uint64_t *tensor_mask_in, uint64_
     ca.block_counts = S.block_counts;
     ca.pq_part = S.pq_part;
     ca.pq_replicas = S.pq_replicas;
-    ca.from_tensor_mask = true;
+    ca.from_tensor_mask = from_tensor_mask;
     DGN_HIP(launch_keep_compact(ca, s));
     return DGN_OK;
+}
+
+int dgn_keep_compact(const dgn_graph *g, const uint64_t *tensor_mask_in, uint64_t *op_mask, uint8_t *op_flag,
+                     int32_t *kept_ops, uint64_t *kept_masks, int64_t *kept_count, int64_t *per_query_count,
+                     void *scratch, size_t scratch_bytes, dgn_stream stream)
+{
+    return keep_compact_impl(g, tensor_mask_in, true, op_mask, op_flag, kept_ops, kept_masks, kept_count, per_query_count,
+                             scratch, scratch_bytes, stream);
 }
 
 int dgn_prune_words(const dgn_graph *g, int64_t num_sets, int64_t num_targets, const int32_t *tgt_rowptr,
@@ -857,9 +866,13 @@ int dgn_backward_prune(const dgn_graph *g, int32_t num_pairs, const int32_t *obj
     }
     if (stats) stats->reserved = (int32_t)passes;
 
-    // removal rule and ordered compaction on the marked set
-    return dgn_keep_compact(g, tensor_mask, op_mask, op_flag, kept_ops, kept_masks, kept_count, per_query_count, scratch,
-                            S.prune_bytes, stream);
+    // Removal rule and ordered compaction on the marked set.  A marked tensor lies in stage one's coloured set,
+    // so only operators of stage one's kept list can have a marked output: K is cleared and written for those.
+    FillRegion kz[1] = {{op_mask, (size_t)g->P * 8}};
+    DGN_HIP(launch_clear(kz, 1, s));
+    DGN_HIP(launch_keep_from_list(g->v, S.kept, S.kept_count, F, reinterpret_cast<u64 *>(op_mask), grid, s));
+    return keep_compact_impl(g, tensor_mask, false, op_mask, op_flag, kept_ops, kept_masks, kept_count, per_query_count,
+                             scratch, S.prune_bytes, stream);
 }
 
 int dgn_ignore_mask(const dgn_graph *g, const uint64_t *tensor_mask, const int32_t *kept_ops, const uint64_t *kept_masks,

@@ -82,6 +82,27 @@ __global__ __launch_bounds__(kFwThreads) void k_forward_within(GraphView g, cons
     if (ballot64(added) && lane == 0) *changed = 1;         // same value from every writer
 }
 
+// K[o] = OR of F over the outputs of o (removal rule of Sec. 2.1), for the operators of a kept list only
+__global__ __launch_bounds__(kFwThreads) void k_keep_from_list(GraphView g, const int32_t *kept, const int64_t *kept_count,
+                                                                const u64 *F, u64 *K)
+{
+    const int64_t n = *kept_count;
+    const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gsize) {
+        const int32_t o = kept[i];
+        u64 k = 0;
+        for (int32_t e = g.out_rowptr[o]; e < g.out_rowptr[o + 1]; ++e) k |= F[g.out_idx[e]];
+        K[o] = k;
+    }
+}
+
+hipError_t launch_keep_from_list(const GraphView &g, const int32_t *kept, const int64_t *kept_count, const u64 *F, u64 *K,
+                                 int grid_blocks, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_keep_from_list, dim3((unsigned)grid_blocks), dim3(kFwThreads), 0, s, g, kept, kept_count, F, K);
+    return hipGetLastError();
+}
+
 hipError_t launch_backward_seed(int64_t T, int num_pairs, const int32_t *obj, const int32_t *wrt, int32_t *tgt_rowptr,
                                 const u64 *B, u64 *F, int32_t *flags, bool rowptr_only, hipStream_t s)
 {

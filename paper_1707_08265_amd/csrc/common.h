@@ -247,6 +247,8 @@ hipError_t launch_set_lists(const int32_t *kept_ops, const u64 *kept_masks, int6
 // one pass of the forward stage over the kept operators of the first stage.
 hipError_t launch_backward_seed(int64_t T, int num_pairs, const int32_t *obj, const int32_t *wrt, int32_t *tgt_rowptr,
                                 const u64 *B, u64 *F, int32_t *flags, bool rowptr_only, hipStream_t s);
+hipError_t launch_keep_from_list(const GraphView &g, const int32_t *kept, const int64_t *kept_count, const u64 *F, u64 *K,
+                                 int grid_blocks, hipStream_t s);
 hipError_t launch_forward_within(const GraphView &g, const int32_t *kept, const int64_t *kept_count, const u64 *B, u64 *F,
                                  int32_t *changed, int grid_blocks, hipStream_t s);
 
@@ -261,7 +263,7 @@ struct InplaceBuffers {
 };
 size_t inplace_scratch_bytes(int64_t T);
 InplaceBuffers inplace_buffers(void *scratch, int64_t T);
-// init, child ranges, links (the state before round 0)
+// init, children, links (the state before the first doubling round)
 hipError_t launch_inplace_setup(const GraphView &g, const u64 *K, u64 select, int32_t *rename, int64_t *renamed_count,
                                 const InplaceBuffers &b, int grid_blocks, hipStream_t s);
 hipError_t launch_inplace_round(int round, int32_t *rename, int64_t *renamed_count, const InplaceBuffers &b,
