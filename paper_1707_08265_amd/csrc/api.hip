@@ -350,17 +350,43 @@ int dgn_graph_build(const dgn_coo_desc *d, void *graph_mem, size_t graph_bytes, 
                          {L.prod_rowptr, align256((T + 1) * 4)},
                          {S.status, 256}};
     DGN_HIP(launch_clear(clr, 4, s));
-    DGN_HIP(launch_degree_hist(d->in_op, d->in_tensor, Ein, (int32_t)P, (int32_t)T, L.in_rowptr, S.status, s));
-    DGN_HIP(launch_degree_hist(d->out_op, d->out_tensor, Eout, (int32_t)P, (int32_t)T, L.out_rowptr, S.status, s));
-    DGN_HIP(launch_degree_hist(d->out_tensor, d->out_op, Eout, (int32_t)T, (int32_t)P, L.prod_rowptr, S.status, s));
+    // status[1..3]: "keys decrease somewhere" for the three edge orders (COO order in all three passes)
+    DGN_HIP(launch_degree_hist(d->in_op, d->in_tensor, Ein, (int32_t)P, (int32_t)T, L.in_rowptr, S.status, S.status + 1, s));
+    DGN_HIP(launch_degree_hist(d->out_op, d->out_tensor, Eout, (int32_t)P, (int32_t)T, L.out_rowptr, S.status, S.status + 2, s));
+    DGN_HIP(launch_degree_hist(d->out_tensor, d->out_op, Eout, (int32_t)T, (int32_t)P, L.prod_rowptr, S.status, S.status + 3, s));
     DGN_HIP(launch_exclusive_scan(L.in_rowptr, L.in_rowptr, P, S.scan_tmp, s));
     DGN_HIP(launch_exclusive_scan(L.out_rowptr, L.out_rowptr, P, S.scan_tmp, s));
     DGN_HIP(launch_exclusive_scan(L.prod_rowptr, L.prod_rowptr, T, S.scan_tmp, s));
+    // Edges that already come in row order (a graph recorded operator by operator does) need no sort: the
+    // row's entries are the COO entries as they stand.  Reading the three flags costs one synchronisation.
+    void *pin = nullptr;
+    rc = pinned_buffer(&pin);
+    if (rc != DGN_OK) return rc;
+    DGN_HIP(hipMemcpyAsync(pin, S.status, 4 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    DGN_HIP(hipStreamSynchronize(s));
+    const int32_t *flags = static_cast<const int32_t *>(pin);
+    if (flags[0]) return error_bits_to_code(flags[0]);       // bad ids: nothing further is built from them
+    const bool in_sorted = !flags[1], out_sorted = !flags[2];
+    const bool prod_sorted = out_sorted && !flags[3];         // the third sort reads the outputs in operator order
     // stable sorts: edges by operator (rows keep COO order), then outputs by tensor, which leaves each
     // tensor's producers ascending in operator id
-    DGN_HIP(launch_sort_pairs(d->in_op, d->in_tensor, nullptr, L.in_idx, Ein, key_bits_for(P), S.sort_tmp, s));
-    DGN_HIP(launch_sort_pairs(d->out_op, d->out_tensor, S.sorted_ops, L.out_idx, Eout, key_bits_for(P), S.sort_tmp, s));
-    DGN_HIP(launch_sort_pairs(L.out_idx, S.sorted_ops, nullptr, L.prod_idx, Eout, key_bits_for(T), S.sort_tmp, s));
+    if (in_sorted) {
+        if (Ein > 0) DGN_HIP(hipMemcpyAsync(L.in_idx, d->in_tensor, (size_t)Ein * 4, hipMemcpyDeviceToDevice, s));
+    } else {
+        DGN_HIP(launch_sort_pairs(d->in_op, d->in_tensor, nullptr, L.in_idx, Ein, key_bits_for(P), S.sort_tmp, s));
+    }
+    const int32_t *ops_of_out = d->out_op;                    // operator of every entry of out_idx
+    if (out_sorted) {
+        if (Eout > 0) DGN_HIP(hipMemcpyAsync(L.out_idx, d->out_tensor, (size_t)Eout * 4, hipMemcpyDeviceToDevice, s));
+    } else {
+        DGN_HIP(launch_sort_pairs(d->out_op, d->out_tensor, S.sorted_ops, L.out_idx, Eout, key_bits_for(P), S.sort_tmp, s));
+        ops_of_out = S.sorted_ops;
+    }
+    if (prod_sorted) {
+        if (Eout > 0) DGN_HIP(hipMemcpyAsync(L.prod_idx, d->out_op, (size_t)Eout * 4, hipMemcpyDeviceToDevice, s));
+    } else {
+        DGN_HIP(launch_sort_pairs(L.out_idx, ops_of_out, nullptr, L.prod_idx, Eout, key_bits_for(T), S.sort_tmp, s));
+    }
 
     dgn_graph *h = new (std::nothrow) dgn_graph();
     if (!h) return DGN_ERR_INVALID_ARG;
@@ -417,7 +443,7 @@ int dgn_graph_from_csr(const dgn_csr_desc *d, void *graph_mem, size_t graph_byte
     if (rc) return rc;
 
     DGN_HIP(launch_expand_rows(d->out_rowptr, (int32_t)P, S.sorted_ops, s));
-    DGN_HIP(launch_degree_hist(d->out_idx, nullptr, Eout, (int32_t)T, 1, L.prod_rowptr, S.status, s));
+    DGN_HIP(launch_degree_hist(d->out_idx, nullptr, Eout, (int32_t)T, 1, L.prod_rowptr, S.status, S.status + 3, s));
     DGN_HIP(launch_exclusive_scan(L.prod_rowptr, L.prod_rowptr, T, S.scan_tmp, s));
     DGN_HIP(launch_sort_pairs(d->out_idx, S.sorted_ops, nullptr, L.prod_idx, Eout, key_bits_for(T), S.sort_tmp, s));
 

@@ -7,15 +7,19 @@ namespace dgn {
 
 // deg[key] += 1.  Ids outside their range are reported and skipped, so later passes never index
 // out of bounds with them (the sort itself only ever uses masked digits of the keys).
+//
+// The same pass notes whether the keys ever decrease (*unsorted = 1): recorded graphs are usually handed
+// over operator by operator, and edges that are already in row order need no sort at all.
 __global__ __launch_bounds__(256) void k_degree_hist(const int32_t *keys, const int32_t *vals, int64_t nnz,
-                                                      int32_t n_rows, int32_t n_vals, int32_t *deg, int32_t *error)
+                                                      int32_t n_rows, int32_t n_vals, int32_t *deg, int32_t *error,
+                                                      int32_t *unsorted)
 {
     // Runs of equal keys inside a wave (operator-major COO is one long sequence of such runs) are added
     // with ONE atomic by the run's first lane: atomics on one address serialise, and an operator with
     // fan-in 64 would otherwise be 64 of them.
     const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
     const int lane = lane_id();
-    bool bad = false;
+    bool bad = false, descends = false;
     for (int64_t base = (int64_t)blockIdx.x * blockDim.x + (threadIdx.x & ~(kWave - 1)); base < nnz; base += gsize) {
         const int64_t e = base + lane;                      // wave-uniform loop, lanes past the end idle
         const bool valid = e < nnz;
@@ -23,7 +27,9 @@ __global__ __launch_bounds__(256) void k_degree_hist(const int32_t *keys, const 
         const int32_t v = (valid && vals) ? vals[e] : 0;
         const bool good = valid && k >= 0 && k < n_rows;
         if (valid && (!good || v < 0 || v >= n_vals)) bad = true;
-        const int32_t prev = __shfl_up(k, 1, kWave);
+        int32_t prev = __shfl_up(k, 1, kWave);
+        if (lane == 0) prev = base > 0 ? keys[base - 1] : k;    // the key just before this wave's first one
+        if (valid && prev > k) descends = true;
         const u64 gmask = ballot64(good);
         const bool leader = good && (lane == 0 || !((gmask >> (lane - 1)) & 1) || prev != k);
         const u64 boundaries = ballot64(leader) | ~gmask;   // a run ends at the next leader or the next bad lane
@@ -34,16 +40,18 @@ __global__ __launch_bounds__(256) void k_degree_hist(const int32_t *keys, const 
         }
     }
     if (ballot64(bad) != 0 && lane == 0) atomicOr(error, kErrIdRange);
+    // shuffled input would have every wave report: look first, and store (same value from everyone) only if needed
+    if (ballot64(descends) != 0 && lane == 0 && load_coherent(unsorted) == 0) store_coherent(unsorted, 1);
 }
 
 hipError_t launch_degree_hist(const int32_t *keys, const int32_t *vals, int64_t nnz, int32_t n_rows,
-                              int32_t n_vals, int32_t *deg, int32_t *error, hipStream_t s)
+                              int32_t n_vals, int32_t *deg, int32_t *error, int32_t *unsorted, hipStream_t s)
 {
     if (nnz == 0) return hipSuccess;
     int64_t blocks = (nnz + 255) / 256;
     if (blocks > 8192) blocks = 8192;
     hipLaunchKernelGGL(k_degree_hist, dim3((unsigned)blocks), dim3(256), 0, s, keys, vals, nnz, n_rows, n_vals,
-                       deg, error);
+                       deg, error, unsorted);
     return hipGetLastError();
 }
 
