@@ -57,6 +57,8 @@ def main():
     ap.add_argument("--generic", action="store_true", help="force the one-launch-per-level traversal")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known size, to scale profiler byte counters)")
+    ap.add_argument("--shuffled-build", action="store_true",
+                    help="also time the CSR build on the same edges in shuffled COO order (every sort runs)")
     ap.add_argument("--prune-only", action="store_true",
                     help="skip the separately timed in-place, read-out and backward-prune legs (for profiling runs)")
     ap.add_argument("--trace-levels", action="store_true", help="print the per-level trace of the last step")
@@ -102,9 +104,29 @@ def main():
         torch.cuda.synchronize()
         build_ms.append((time.perf_counter() - tb) * 1e3)
         assert rc == 0, d.dgn_strerror(rc)
-    del scratch
     build_ms = float(np.median(build_ms[1:]))
     log(f"CSR build: {build_ms:.2f} ms ({E / build_ms / 1e6:.1f} GTEPS)")
+    build_shuffled_ms = None
+    if args.shuffled_build:
+        gs = gg.shuffle_coo(g, 12345)
+        s_in_op, s_in_t, s_out_op, s_out_t = up(gs.in_op), up(gs.in_tensor), up(gs.out_op), up(gs.out_tensor)
+        del gs
+        sdesc = d.make_coo_desc(g.num_ops, g.num_tensors, s_in_op, s_in_t, s_out_op, s_out_t, g.num_graphs,
+                                g.graph_op_offsets, g.graph_tensor_offsets)
+        smem = torch.empty(gb, dtype=torch.uint8, device=dev)
+        times = []
+        for _ in range(3):
+            torch.cuda.synchronize()
+            tb = time.perf_counter()
+            rc, sh = d.dgn_graph_build(sdesc, smem, gb, scratch, sb)
+            torch.cuda.synchronize()
+            times.append((time.perf_counter() - tb) * 1e3)
+            assert rc == 0, d.dgn_strerror(rc)
+            d.dgn_graph_destroy(sh)
+        build_shuffled_ms = float(np.median(times[1:]))
+        log(f"CSR build, shuffled COO: {build_shuffled_ms:.2f} ms ({E / build_shuffled_ms / 1e6:.1f} GTEPS)")
+        del smem, s_in_op, s_in_t, s_out_op, s_out_t
+    del scratch
     rc, sizes = d.dgn_graph_get_sizes(handle)
     dg = d.DeviceGraph(handle, graph_mem, (), sizes)
     del in_op, in_t, out_op, out_t
@@ -329,6 +351,7 @@ def main():
         "cpu_baseline": cpu,
         "phase_ms": {k: round(v, 4) for k, v in ph.items()},
         "build_ms": round(build_ms, 3),
+        "build_shuffled_ms": None if build_shuffled_ms is None else round(build_shuffled_ms, 3),
         "inplace": inplace,
         "readout": readout,
         "backward_prune": backward,
