@@ -174,7 +174,7 @@ def main():
     out = buf.to_host()
     P, T = g.num_ops, g.num_tensors
 
-    inplace = readout = backward = None
+    inplace = readout = backward = incremental = None
     extras = {}
     if not args.prune_only:
         # ---- in-place pass on the pruned graph (Algorithm 3), timed on its own, not part of `value` ---
@@ -221,6 +221,33 @@ def main():
         log(f"read-outs: ignore mask {readout['ignore_ms']:.3f} ms ({readout['ignored_tensors']} tensors), per-set lists "
             f"{readout['per_set_lists_ms']:.3f} ms ({readout['list_entries']} entries; includes two small read-backs)")
         del ro
+
+        # ---- incremental prune: the last target set added to a finished prune of the others --------------
+        incremental = None
+        if g.num_graphs == 1 and tg.num_sets > 1:
+            last = tg.num_sets - 1
+            rp_part = tg.tgt_rowptr.copy()
+            rp_part[last + 1:] = rp_part[last]                 # the last set is empty in the first call
+            rp_part_d = up(rp_part)
+            inc_ms = []
+            inc_st = d.dgn_stats()
+            for _ in range(1 + max(3, min(args.steps, 10))):
+                rc = buf.prune(rp_part_d, idx)
+                assert rc == 0, d.dgn_strerror(rc)
+                torch.cuda.synchronize()
+                tb = time.perf_counter()
+                rc = buf.prune(rowptr, idx, options=d.dgn_options(incremental=1), stats=inc_st)
+                torch.cuda.synchronize()
+                inc_ms.append((time.perf_counter() - tb) * 1e3)
+                assert rc == 0, d.dgn_strerror(rc)
+            inc_out = buf.to_host()
+            same = all(np.array_equal(inc_out[k], out[k]) for k in out)
+            incremental = {"ms": round(float(np.median(inc_ms[1:])), 4), "added_sets": 1,
+                           "tensor_visits": int(inc_st.tensor_visits), "levels": int(inc_st.levels),
+                           "equals_one_shot_result": bool(same)}
+            log(f"incremental prune (set {last} added to the other {last}): {incremental['ms']:.3f} ms, "
+                f"{incremental['tensor_visits']} visits in {incremental['levels']} levels; equals the one-shot result: {same}")
+            assert same, "incremental prune differs from the one-shot prune"
 
         # ---- backward prune (Algorithm 2) on the same graph, 64 pairs, timed on its own ---------------
         backward = None
@@ -355,6 +382,7 @@ def main():
         "inplace": inplace,
         "readout": readout,
         "backward_prune": backward,
+        "incremental_prune": incremental,
         "build_plus_prune_gteps": round(E / ((build_ms + ms_per_step) * 1e-3) / 1e9, 2),
         "result": {"kept_ops": P_k, "coloured_tensors": T_c, "kept_in_edges": E_k, "kept_out_edges": Eo_k,
                    "levels": int(st.levels), "tensor_visits": int(st.tensor_visits),

@@ -106,6 +106,13 @@ typedef struct dgn_options {
     int32_t defer_start_shift; /* prune: the threshold starts at num_ops >> this (0 = default)          */
     int32_t defer_floor_shift; /* prune: deferral stops once the threshold is below num_ops >> this
                                 (0 = default).  Schedule knobs only: results do not depend on them   */
+    int32_t incremental;     /* prune: tensor_mask and op_mask are IN/OUT.  On entry they hold the result of
+                                an earlier prune of a graph that this one extends (the same graph, or a
+                                prefix of its operators with the masks zero-extended by the caller) for
+                                some of the target sets; the call colours what the given targets add and
+                                leaves the fixed point for the union.  Nothing is cleared, only the new
+                                bits are traversed; every other output is rewritten in full.  The masks
+                                must be such a result: anything else gives unspecified masks             */
 } dgn_options;
 
 /* Indices into dgn_stats.phase_ms */

@@ -52,7 +52,8 @@ class dgn_csr_desc(ctypes.Structure):
 
 class dgn_options(ctypes.Structure):
     _fields_ = [("validate", c_int32), ("recompute_keep", c_int32), ("traversal", c_int32),
-                ("profile", c_int32), ("defer_percent", c_int32), ("max_queue_entries", c_int32), ("defer_start_shift", c_int32), ("defer_floor_shift", c_int32)]
+                ("profile", c_int32), ("defer_percent", c_int32), ("max_queue_entries", c_int32),
+                ("defer_start_shift", c_int32), ("defer_floor_shift", c_int32), ("incremental", c_int32)]
 
 
 class dgn_stats(ctypes.Structure):

@@ -523,8 +523,10 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
         DGN_HIP(hipEventRecord(ev[0], s));
     }
 
-    // nothing marked yet: clear outputs, frontier bitmaps and traversal state
-    FillRegion clr[6] = {{M, (size_t)g->T * 8}, {K, (size_t)g->P * 8}, {S.DB, S.db_bytes},
+    // nothing marked yet: clear outputs, deferral markers and traversal state (an incremental call keeps
+    // M and K: they hold a fixed point that the new target bits only add to)
+    const bool incremental = options && options->incremental;
+    FillRegion clr[6] = {{M, incremental ? 0 : (size_t)g->T * 8}, {K, incremental ? 0 : (size_t)g->P * 8}, {S.DB, S.db_bytes},
                          {S.state, 256 + sizeof(TravCounters)}, {per_query_count, pq_bytes},
                          {S.pq_part, per_query_count ? S.pq_part_bytes : 0}};
     DGN_HIP(launch_clear(clr, 6, s));
@@ -865,6 +867,7 @@ int dgn_backward_prune(const dgn_graph *g, int32_t num_pairs, const int32_t *obj
     dgn_options o1{};
     if (options) o1 = *options;
     o1.profile = 0;
+    o1.incremental = 0;                              // stage one starts from nothing, in scratch memory
     int rc = dgn_prune(g, num_pairs, num_pairs, S.tgt_rowptr, wrt, reinterpret_cast<uint64_t *>(S.B),
                        reinterpret_cast<uint64_t *>(S.KB), nullptr, S.kept, nullptr, S.kept_count, nullptr, scratch,
                        S.prune_bytes, &o1, stats, stream);

@@ -374,3 +374,75 @@ def test_more_than_64_sets_run_word_by_word(dgn, oracle):
     rc = dgn.dgn_prune_words(dg.handle, 0, 0, torch.from_numpy(tg.tgt_rowptr).cuda(), None, M, K, flag, kept, kmask,
                              count, pq, scratch, sb)
     assert rc == dgn.DGN_ERR_TOO_MANY_SETS
+
+
+def _prefix_graph(g, num_ops):
+    """The first num_ops operators of g (creation order) as a graph of their own, with the tensors they use."""
+    keep_in, keep_out = g.in_op < num_ops, g.out_op < num_ops
+    T = int(max(g.in_tensor[keep_in].max(initial=0), g.out_tensor[keep_out].max(initial=0))) + 1
+    return gg.Graph(num_ops, T, g.in_op[keep_in].copy(), g.in_tensor[keep_in].copy(), g.out_op[keep_out].copy(),
+                    g.out_tensor[keep_out].copy(), name=g.name + "-prefix")
+
+
+@pytest.mark.parametrize("k,scale", [(0, 1.0), (1, 0.5), (2, 0.02), (3, 0.02), (4, 0.002)])
+def test_incremental_prune_adds_target_sets(dgn, oracle, k, scale):
+    """Pruning for some sets and then adding the others incrementally gives the one-shot result."""
+    import torch
+    g, tg = gg.config(k, scale)
+    Q = tg.num_sets
+    n_sets = len(tg.tgt_rowptr) - 1
+    # first call: every other set is empty; second call (incremental): all sets
+    rowptr1 = tg.tgt_rowptr.copy()
+    cnt = np.diff(tg.tgt_rowptr)
+    cnt1 = cnt.copy()
+    cnt1[1::2] = 0
+    if n_sets == 1:
+        cnt1[0] = max(1, cnt[0] // 2)                       # a single set: only some of its targets first
+    rowptr1 = np.concatenate([[0], np.cumsum(cnt1)]).astype(np.int32)
+    idx1 = np.concatenate([tg.tgt_idx[tg.tgt_rowptr[s]:tg.tgt_rowptr[s] + cnt1[s]] for s in range(n_sets)] +
+                          [np.zeros(0, np.int32)]).astype(np.int32)
+    dg = dgn.DeviceGraph.from_coo(g)
+    buf = dgn.PruneBuffers(dg, Q)
+    rc = buf.prune(torch.from_numpy(rowptr1).cuda(), torch.from_numpy(idx1).cuda())
+    assert rc == 0
+    adj, _ = oracle_prune(oracle, g, tg)
+    part = oracle.forward_prune(adj, Q, rowptr1, idx1, g.num_graphs, g.graph_op_offsets)
+    assert_same(buf.to_host(), part, f"cfg{k} first part")
+    st = dgn.dgn_stats()
+    rc = buf.prune(torch.from_numpy(tg.tgt_rowptr).cuda(), torch.from_numpy(tg.tgt_idx).cuda(),
+                   options=dgn.dgn_options(incremental=1), stats=st)
+    assert rc == 0
+    _, full = oracle_prune(oracle, g, tg)
+    assert_same(buf.to_host(), full, f"cfg{k} incremental")
+    # adding nothing new changes nothing and traverses nothing
+    rc = buf.prune(torch.from_numpy(tg.tgt_rowptr).cuda(), torch.from_numpy(tg.tgt_idx).cuda(),
+                   options=dgn.dgn_options(incremental=1, recompute_keep=1), stats=st)
+    assert rc == 0 and (st.tensor_visits == 0 or g.num_graphs > 1)
+    assert_same(buf.to_host(), full, f"cfg{k} incremental, nothing new")
+
+
+def test_incremental_prune_of_an_extended_graph(dgn, oracle):
+    """A recorded graph grows by appended operators (an unrolled loop gets one more step): the result for
+    the shorter graph, zero-extended, plus the new targets gives the result of pruning the longer graph."""
+    import torch
+    g, tg = gg.config(2, 0.02)                              # 200 steps of 1000 operators
+    P_old = g.num_ops - 3000                                # the graph before its last three steps
+    g_old = _prefix_graph(g, P_old)
+    old_targets = gg.targets_range(777, 1, 20, 20, 16, g_old.num_tensors)
+    dg_old = dgn.DeviceGraph.from_coo(g_old)
+    b_old = dgn.PruneBuffers(dg_old, 1)
+    assert b_old.prune(torch.from_numpy(old_targets.tgt_rowptr).cuda(), torch.from_numpy(old_targets.tgt_idx).cuda()) == 0
+    dg = dgn.DeviceGraph.from_coo(g)
+    buf = dgn.PruneBuffers(dg, 1)
+    buf.tensor_mask.zero_()
+    buf.op_mask.zero_()
+    buf.tensor_mask[: g_old.num_tensors] = b_old.tensor_mask
+    buf.op_mask[:P_old] = b_old.op_mask
+    new_idx = np.asarray([g.num_tensors - 1, g.num_tensors - 500], np.int32)        # targets in the appended steps
+    rc = buf.prune(torch.from_numpy(np.asarray([0, 2], np.int32)).cuda(), torch.from_numpy(new_idx).cuda(),
+                   options=dgn.dgn_options(incremental=1))
+    assert rc == 0
+    all_idx = np.concatenate([old_targets.tgt_idx, new_idx]).astype(np.int32)
+    adj = oracle.build_adjacency(g.num_ops, g.num_tensors, g.in_op, g.in_tensor, g.out_op, g.out_tensor)
+    ref = oracle.forward_prune(adj, 1, np.asarray([0, len(all_idx)], np.int32), all_idx)
+    assert_same(buf.to_host(), ref, "extended graph")

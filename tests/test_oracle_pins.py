@@ -286,3 +286,24 @@ def test_generators_are_topological_and_seeded():
             gi_in = np.searchsorted(g.graph_tensor_offsets, g.in_tensor, side="right") - 1
             go_in = np.searchsorted(g.graph_op_offsets, g.in_op, side="right") - 1
             assert np.array_equal(gi_in, go_in)
+
+
+@pytest.mark.parametrize("cfg,scale", [(0, 1.0), (1, 0.2), (3, 0.002)])
+def test_adding_targets_to_finished_marks_is_incremental(oracle, cfg, scale):
+    """Algorithm 1 skips what is already marked ("if not m_x"), so running it for more targets on top of
+    finished marks gives the marks of all targets together: what an incremental prune relies on."""
+    g, tg = gg.config(cfg, scale)
+    adj = oracle.build_adjacency(g.num_ops, g.num_tensors, g.in_op, g.in_tensor, g.out_op, g.out_tensor)
+    Q = tg.num_sets
+    cnt = np.diff(tg.tgt_rowptr)
+    first = cnt.copy()
+    first[1::2] = 0
+    if len(cnt) == 1:
+        first[0] = cnt[0] // 2
+    rp1 = np.concatenate([[0], np.cumsum(first)]).astype(np.int32)
+    idx1 = np.concatenate([tg.tgt_idx[tg.tgt_rowptr[s]:tg.tgt_rowptr[s] + first[s]] for s in range(len(cnt))]).astype(np.int32)
+    M1, _ = oracle.mark(adj, Q, rp1, idx1)
+    M2, _ = oracle.mark(adj, Q, tg.tgt_rowptr, tg.tgt_idx, M=M1.copy())
+    Mfull, _ = oracle.mark(adj, Q, tg.tgt_rowptr, tg.tgt_idx)
+    assert np.array_equal(M2, Mfull)
+    assert not np.any(M1 & ~Mfull) and np.any(M1 != Mfull)
