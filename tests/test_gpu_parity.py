@@ -446,3 +446,25 @@ def test_incremental_prune_of_an_extended_graph(dgn, oracle):
     adj = oracle.build_adjacency(g.num_ops, g.num_tensors, g.in_op, g.in_tensor, g.out_op, g.out_tensor)
     ref = oracle.forward_prune(adj, 1, np.asarray([0, len(all_idx)], np.int32), all_idx)
     assert_same(buf.to_host(), ref, "extended graph")
+
+
+@pytest.mark.parametrize("which", ["in", "out", "none"])
+def test_csr_builder_skips_only_the_sorts_it_may_skip(dgn, oracle, which):
+    """Edges that already come in row order are copied, not sorted; any mix of ordered and shuffled edge
+    lists must give the same adjacency as the oracle's stable sort."""
+    g, tg = gg.config(3, 0.004)
+    gs = gg.shuffle_coo(g, 5)
+    if which == "in":                                       # only the input edges are shuffled
+        mixed = gg.Graph(g.num_ops, g.num_tensors, gs.in_op, gs.in_tensor, g.out_op, g.out_tensor, name="mixed")
+    elif which == "out":                                    # only the output edges are shuffled
+        mixed = gg.Graph(g.num_ops, g.num_tensors, g.in_op, g.in_tensor, gs.out_op, gs.out_tensor, name="mixed")
+    else:                                                   # nothing shuffled, but tensor ids permuted: the
+        mixed, tg, _ = gg.relabel_tensors(g, tg, 3)         # producer lists still need their sort
+    adj = oracle.build_adjacency(mixed.num_ops, mixed.num_tensors, mixed.in_op, mixed.in_tensor, mixed.out_op,
+                                 mixed.out_tensor)
+    dg = dgn.DeviceGraph.from_coo(mixed, validate=True)
+    csr = {n: v.cpu().numpy() for n, v in dg.csr().items()}
+    for name in ("in_rowptr", "in_idx", "out_rowptr", "out_idx", "prod_rowptr", "prod_idx"):
+        assert np.array_equal(csr[name], getattr(adj, name)), f"{which}: {name}"
+    _, _, out = gpu_prune(dgn, mixed, tg)
+    assert_same(out, oracle.forward_prune(adj, tg.num_sets, tg.tgt_rowptr, tg.tgt_idx), which)
