@@ -836,10 +836,13 @@ hipError_t launch_fix_sweep(const GraphView &g, u64 *M, u64 *K, int32_t *changed
 constexpr int kSweepThreads = 256;
 constexpr int kSweepSlots = 256;                    // hash slots per wave
 constexpr int kSweepMaxKeys = kSweepSlots * 3 / 4;  // output tensors of a group beyond this: iterate instead
+constexpr int kSweepDeps = 4;                       // in-group consumers per operator handled by the relaxation
 
 struct SweepShared {
     int32_t key[kSweepSlots];                       // tensor id, -1 = empty
     uint8_t owner[kSweepSlots];                     // lane of the operator that writes the tensor
+    int ndep[kWave];                                // per lane: in-group consumers of its operator's outputs ...
+    uint8_t dep[kWave][kSweepDeps];                 // ... and the first few of them (their lanes)
 };
 
 __device__ __forceinline__ int sweep_slot(int32_t t) { return (int)(((uint32_t)t * 0x9E3779B1u) >> 24); }
@@ -858,21 +861,6 @@ __device__ __forceinline__ u64 readlane64(u64 v, int l)     // l wave-uniform
 }
 
 // pushes `bits` of every lane to the operator's inputs; returns the bits that were new to some input
-__device__ __forceinline__ u64 sweep_push(const GraphView &g, u64 *M, int ib, int n_in, u64 bits)
-{
-    u64 fresh = 0;
-    const int max_in = wave_max(bits ? n_in : 0);
-    for (int r0 = 0; r0 < max_in; r0 += 4) {                 // four independent atomics in flight per lane
-        u64 old[4] = {~(u64)0, ~(u64)0, ~(u64)0, ~(u64)0};
-#pragma unroll
-        for (int c = 0; c < 4; ++c)
-            if (bits && r0 + c < n_in) old[c] = atomicOr(&M[g.in_idx[ib + r0 + c]], bits);
-#pragma unroll
-        for (int c = 0; c < 4; ++c) fresh |= bits & ~old[c];
-    }
-    return fresh;
-}
-
 // Per-set counts of one graph without a transpose per group: every lane counts, for its own
 // operators, how often each of the 64 bits was set, in bit-sliced form (plane i holds bit i of all
 // 64 counters).  Four masks are folded at a time with full adders; only the resulting carry of
@@ -907,6 +895,60 @@ __device__ __forceinline__ void sliced_fold(SlicedCount &c, u64 x3, int planes_u
     }
 }
 
+// Row bounds and the first few edge targets of one lane's operator.  They do not depend on M, so they
+// are fetched ahead: the row bounds two groups early, the targets one group early.  What remains on a
+// group's critical path is M itself: load, resolve, push.
+struct SweepRow {
+    int ob, n_out, ib, n_in;
+    int32_t to[2], ti[4];
+};
+
+__device__ __forceinline__ SweepRow sweep_row_bounds(const GraphView &g, int64_t o, bool valid)
+{
+    SweepRow r{};
+    if (valid) {
+        r.ob = g.out_rowptr[o];
+        r.n_out = g.out_rowptr[o + 1] - r.ob;
+        r.ib = g.in_rowptr[o];
+        r.n_in = g.in_rowptr[o + 1] - r.ib;
+    }
+    return r;
+}
+
+__device__ __forceinline__ void sweep_row_targets(const GraphView &g, SweepRow &r)
+{
+#pragma unroll
+    for (int j = 0; j < 2; ++j) r.to[j] = j < r.n_out ? g.out_idx[r.ob + j] : -1;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) r.ti[j] = j < r.n_in ? g.in_idx[r.ib + j] : -1;
+}
+
+__device__ __forceinline__ int32_t sweep_out(const GraphView &g, const SweepRow &r, int j)
+{
+    return j == 0 ? r.to[0] : j == 1 ? r.to[1] : g.out_idx[r.ob + j];
+}
+
+__device__ __forceinline__ int32_t sweep_in(const GraphView &g, const SweepRow &r, int j)
+{
+    return j == 0 ? r.ti[0] : j == 1 ? r.ti[1] : j == 2 ? r.ti[2] : j == 3 ? r.ti[3] : g.in_idx[r.ib + j];
+}
+
+// pushes `bits` of every lane to the operator's inputs; returns the bits that were new to some input
+__device__ __forceinline__ u64 sweep_push(const GraphView &g, u64 *M, const SweepRow &row, u64 bits)
+{
+    u64 fresh = 0;
+    const int max_in = wave_max(bits ? row.n_in : 0);
+    for (int r0 = 0; r0 < max_in; r0 += 4) {                 // four independent atomics in flight per lane
+        u64 old[4] = {~(u64)0, ~(u64)0, ~(u64)0, ~(u64)0};
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (bits && r0 + c < row.n_in) old[c] = atomicOr(&M[r0 == 0 ? row.ti[c] : g.in_idx[row.ib + r0 + c]], bits);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) fresh |= bits & ~old[c];
+    }
+    return fresh;
+}
+
 __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64 *M, u64 *K, int64_t *pq)
 {
     __shared__ SweepShared s_all[kSweepThreads / kWave];
@@ -922,24 +964,27 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64
     for (int i = 0; i < kCountPlanes; ++i) cnt.plane[i] = 0;
     cnt.x0 = cnt.x1 = cnt.x2 = 0;
     int group = 0;
+    SweepRow cur = sweep_row_bounds(g, o_hi - 1 - lane, o_hi - 1 - lane >= o_lo);
+    sweep_row_targets(g, cur);
+    SweepRow nxt = sweep_row_bounds(g, o_hi - kWave - 1 - lane, o_hi - kWave - 1 - lane >= o_lo);
     for (int64_t top = o_hi; top > o_lo; top -= kWave, ++group) {
         const int64_t o = top - 1 - lane;                    // lane 0 holds the highest id of the group
         const bool valid = o >= o_lo;
-        int ob = 0, n_out = 0, ib = 0, n_in = 0;
-        if (valid) {
-            ob = g.out_rowptr[o];
-            n_out = g.out_rowptr[o + 1] - ob;
-            ib = g.in_rowptr[o];
-            n_in = g.in_rowptr[o + 1] - ib;
-        }
+        // fetch ahead: targets of the next group (its row bounds have arrived), row bounds of the one after
+        sweep_row_targets(g, nxt);
+        const int64_t o2 = top - 2 * kWave - 1 - lane;
+        const SweepRow nxt2 = sweep_row_bounds(g, o2, o2 >= o_lo);
+        const SweepRow row = cur;
+        const int ob = row.ob, n_out = row.n_out, n_in = row.n_in;
         const int max_out = wave_max(n_out);
         u64 k = 0;
         if (wave_sum(n_out) <= kSweepMaxKeys) {
             for (int i = lane; i < kSweepSlots; i += kWave) sh.key[i] = -1;
+            sh.ndep[lane] = 0;
             wave_lds_sync();
             for (int r = 0; r < max_out; ++r) {
                 if (r < n_out) {
-                    const int32_t t = g.out_idx[ob + r];
+                    const int32_t t = sweep_out(g, row, r);
                     k |= load_coherent(&M[t]);
                     int slot = sweep_slot(t);
                     while (atomicCAS(&sh.key[slot], -1, t) != -1) slot = (slot + 1) & (kSweepSlots - 1);
@@ -951,26 +996,51 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64
             const int max_in = wave_max(n_in);
             for (int r = 0; r < max_in; ++r) {
                 if (r < n_in) {
-                    const int32_t t = g.in_idx[ib + r];
+                    const int32_t t = sweep_in(g, row, r);
                     for (int slot = sweep_slot(t);; slot = (slot + 1) & (kSweepSlots - 1)) {
                         const int32_t key = sh.key[slot];
                         if (key == -1) break;
                         if (key == t) {
                             const int b = sh.owner[slot];
-                            if (b > lane) feeds |= (u64)1 << b;
+                            if (b > lane && !((feeds >> b) & 1)) {   // first time this lane meets producer b
+                                feeds |= (u64)1 << b;
+                                const int at = atomicAdd(&sh.ndep[b], 1);
+                                if (at < kSweepDeps) sh.dep[b][at] = (uint8_t)lane;
+                            }
                         }
                     }
                 }
             }
-            u64 live = ballot64(feeds != 0);
-            while (live) {                                   // ascending lanes = descending operator ids
-                const int src = __builtin_ctzll(live);
-                live &= live - 1;
-                const u64 ks = readlane64(k, src);           // final: every lane that feeds lane src came earlier
-                if (ks == 0) continue;
-                if (__builtin_amdgcn_inverse_ballot_w64(readlane64(feeds, src))) k |= ks;
+            wave_lds_sync();
+            const int nd = sh.ndep[lane];
+            const int max_nd = wave_max(nd);
+            if (max_nd <= kSweepDeps) {
+                // Relaxation: every lane ORs in the masks of the (few) lanes that read its outputs, all lanes
+                // at once, until nothing changes: as many steps as the longest dependency chain inside the
+                // group, usually a handful.
+                int d[kSweepDeps];
+#pragma unroll
+                for (int j = 0; j < kSweepDeps; ++j) d[j] = j < nd ? sh.dep[lane][j] : lane;
+                for (int it = 0; it < kWave; ++it) {
+                    u64 add = 0;
+#pragma unroll
+                    for (int j = 0; j < kSweepDeps; ++j)
+                        if (j < max_nd) add |= shfl64(k, d[j]);      // wave-uniform bound; own lane when unused
+                    const bool grew = (add & ~k) != 0;
+                    k |= add;
+                    if (ballot64(grew) == 0) break;
+                }
+            } else {
+                u64 live = ballot64(feeds != 0);
+                while (live) {                               // ascending lanes = descending operator ids
+                    const int src = __builtin_ctzll(live);
+                    live &= live - 1;
+                    const u64 ks = readlane64(k, src);       // final: every lane that feeds lane src came earlier
+                    if (ks == 0) continue;
+                    if (__builtin_amdgcn_inverse_ballot_w64(readlane64(feeds, src))) k |= ks;
+                }
             }
-            const u64 fresh = sweep_push(g, M, ib, n_in, k);
+            const u64 fresh = sweep_push(g, M, row, k);
             // the atomics' results must have arrived before the next group reads M
             asm volatile("" ::"v"((uint32_t)fresh), "v"((uint32_t)(fresh >> 32)) : "memory");
             wave_lds_sync();                                 // the table is cleared only after every lane is done with it
@@ -984,12 +1054,14 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64
                 const u64 nb = k & ~kprev;                   // bits this operator has not pushed to its inputs yet
                 kprev = k;
                 if (ballot64(nb != 0) == 0) break;
-                const u64 fresh = sweep_push(g, M, ib, n_in, nb);
+                const u64 fresh = sweep_push(g, M, row, nb);
                 if (ballot64(fresh != 0) == 0) break;        // no word changed: a re-read would find nothing new
             }
             k = kprev;
         }
         if (valid) K[o] = k;
+        cur = nxt;
+        nxt = nxt2;
         if (pq) {
             switch (group & 3) {                             // wave-uniform
             case 0: cnt.x0 = k; break;
