@@ -823,34 +823,60 @@ hipError_t launch_fix_sweep(const GraphView &g, u64 *M, u64 *K, int32_t *changed
 // ------------------------------------------------------------------------------------------------
 // per-graph descending sweep (packed batches of small graphs, operator ids topological)
 //
-// A tensor's consumers all have larger operator ids than its producer.  Walking one graph's operators
-// from the highest id down, 64 at a time, every operator therefore meets the final M of its outputs,
-// except for dependencies *inside* the group of 64.  Those are resolved without touching memory: the
-// group's output tensors go into a small hash table in LDS, every input edge looks its tensor up
-// there, which gives each lane the set of lanes (larger operator ids) it depends on, and the masks
-// are then passed along lane by lane in descending operator order.
+// A tensor's consumers all have larger operator ids than its producer.  One wave walks one graph's
+// operators from the highest id down, 64 at a time, so when a group is reached every consumer outside
+// the group has already been handled.  Nothing of the graph's M is shared with another wave, which
+// allows a scheme without a single global atomic (the atomic version ran at the chip's atomic rate:
+// 75 M pushes at about 20 G/s):
+//   - what consumers push to a tensor whose producer has not been reached yet is gathered in a hash table
+//     in LDS ("pending"); the producer's group takes it from there, ORs it with the tensor's word in
+//     memory (its seed bits), and WRITES the tensor's final M with a plain store;
+//   - dependencies inside the group are resolved in LDS and registers: the group's output tensors go
+//     into a second small table; an input edge that finds its tensor there registers its lane with the
+//     producer's lane, the masks are then relaxed (every lane ORs in the masks of the lanes that read its
+//     outputs, all lanes at once, until nothing changes), and the pushes to in-group tensors go to that
+//     table's accumulators;
+//   - when the pending table fills up it is written to memory (plain read-modify-write: its keys are
+//     distinct) and emptied; a later producer finds those bits in the tensor's word.
+// Loads and stores of M are ordinary cached ones: only this wave touches these words during the kernel.
+// Row bounds and edge targets do not depend on M and are fetched one and two groups ahead, so a
+// group's critical path is: load M of its outputs, resolve, store.
 // Each operator is expanded once with all 64 sets' bits (a level-synchronous traversal revisits the
-// operators of such deep, thin graphs tens of times), K needs no atomics (one lane owns an operator),
-// and nothing is queued.  One wave per graph; waves of different graphs never touch the same words.
+// operators of such deep, thin graphs tens of times) and nothing is queued.  A group with too many
+// edges for the tables, or with a tensor written twice inside the group, is walked one operator at a time.
 // ------------------------------------------------------------------------------------------------
 constexpr int kSweepThreads = 256;
-constexpr int kSweepSlots = 256;                    // hash slots per wave
-constexpr int kSweepMaxKeys = kSweepSlots * 3 / 4;  // output tensors of a group beyond this: iterate instead
+constexpr int kOutSlots = 256;                      // table of the group's output tensors
+constexpr int kOutMax = kOutSlots * 3 / 4;
+constexpr int kPendSlots = 512;                     // pending pushes, kept across groups
+constexpr int kPendMax = kPendSlots * 3 / 4;
+constexpr int kInMax = 256;                         // input edges of a group handled through the tables
 constexpr int kSweepDeps = 4;                       // in-group consumers per operator handled by the relaxation
 
 struct SweepShared {
-    int32_t key[kSweepSlots];                       // tensor id, -1 = empty
-    uint8_t owner[kSweepSlots];                     // lane of the operator that writes the tensor
+    int32_t okey[kOutSlots];                        // tensor id, -1 = empty
+    u64 oacc[kOutSlots];                            // M of that tensor as far as known
+    uint8_t oowner[kOutSlots];                      // lane of the operator that writes the tensor
+    int32_t pkey[kPendSlots];
+    u64 pval[kPendSlots];
     int ndep[kWave];                                // per lane: in-group consumers of its operator's outputs ...
     uint8_t dep[kWave][kSweepDeps];                 // ... and the first few of them (their lanes)
 };
 
-__device__ __forceinline__ int sweep_slot(int32_t t) { return (int)(((uint32_t)t * 0x9E3779B1u) >> 24); }
+__device__ __forceinline__ int out_slot_of(int32_t t) { return (int)(((uint32_t)t * 0x9E3779B1u) >> 24); }
+__device__ __forceinline__ int pend_slot_of(int32_t t) { return (int)(((uint32_t)t * 0x9E3779B1u) >> 23); }
 
 __device__ __forceinline__ void wave_lds_sync()
 {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
+}
+
+// every earlier store of this wave has reached the cache that its later loads read
+__device__ __forceinline__ void wave_stores_done()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 }
 
 __device__ __forceinline__ u64 readlane64(u64 v, int l)     // l wave-uniform
@@ -860,44 +886,34 @@ __device__ __forceinline__ u64 readlane64(u64 v, int l)     // l wave-uniform
     return ((u64)hi << 32) | lo;
 }
 
-// pushes `bits` of every lane to the operator's inputs; returns the bits that were new to some input
-// Per-set counts of one graph without a transpose per group: every lane counts, for its own
-// operators, how often each of the 64 bits was set, in bit-sliced form (plane i holds bit i of all
-// 64 counters).  Four masks are folded at a time with full adders; only the resulting carry of
-// weight 4 ripples through the higher planes.
-constexpr int kCountPlanes = 13;                    // counters up to 2^13 - 1 groups of one graph
-
-struct SlicedCount {
-    u64 plane[kCountPlanes];
-    u64 x0, x1, x2;                                 // masks waiting for the fourth
-};
-
-__device__ __forceinline__ void full_add(u64 a, u64 b, u64 c, u64 &sum, u64 &carry)
+// position of tensor t in the table of output tensors, or -1
+__device__ __forceinline__ int find_out(const SweepShared &sh, int32_t t)
 {
-    const u64 ab = a ^ b;
-    sum = ab ^ c;
-    carry = (ab & c) | (a & b);
-}
-
-__device__ __forceinline__ void sliced_fold(SlicedCount &c, u64 x3, int planes_used)
-{
-    u64 s, ca, cb, cc;
-    full_add(c.plane[0], c.x0, c.x1, s, ca);
-    full_add(s, c.x2, x3, c.plane[0], cb);
-    full_add(c.plane[1], ca, cb, c.plane[1], cc);
-#pragma unroll
-    for (int i = 2; i < kCountPlanes; ++i) {
-        if (i < planes_used) {                      // wave-uniform
-            const u64 t = c.plane[i] & cc;
-            c.plane[i] ^= cc;
-            cc = t;
-        }
+    for (int slot = out_slot_of(t);; slot = (slot + 1) & (kOutSlots - 1)) {
+        const int32_t key = sh.okey[slot];
+        if (key == t) return slot;
+        if (key == -1) return -1;
     }
 }
 
-// Row bounds and the first few edge targets of one lane's operator.  They do not depend on M, so they
-// are fetched ahead: the row bounds two groups early, the targets one group early.  What remains on a
-// group's critical path is M itself: load, resolve, push.
+// writes the pending pushes to memory and empties the table (keys are distinct: plain read-modify-write)
+__device__ __forceinline__ void flush_pending(SweepShared &sh, u64 *M)
+{
+    wave_lds_sync();
+    for (int i = lane_id(); i < kPendSlots; i += kWave) {
+        const int32_t key = sh.pkey[i];
+        if (key != -1) {
+            const u64 v = sh.pval[i];
+            if (v) M[key] |= v;
+            sh.pkey[i] = -1;
+            sh.pval[i] = 0;
+        }
+    }
+    wave_lds_sync();
+    wave_stores_done();
+}
+
+// Row bounds and the first few edge targets of one lane's operator.
 struct SweepRow {
     int ob, n_out, ib, n_in;
     int32_t to[2], ti[4];
@@ -933,20 +949,38 @@ __device__ __forceinline__ int32_t sweep_in(const GraphView &g, const SweepRow &
     return j == 0 ? r.ti[0] : j == 1 ? r.ti[1] : j == 2 ? r.ti[2] : j == 3 ? r.ti[3] : g.in_idx[r.ib + j];
 }
 
-// pushes `bits` of every lane to the operator's inputs; returns the bits that were new to some input
-__device__ __forceinline__ u64 sweep_push(const GraphView &g, u64 *M, const SweepRow &row, u64 bits)
+// Per-set counts of one graph without a transpose per group: every lane counts, for its own
+// operators, how often each of the 64 bits was set, in bit-sliced form (plane i holds bit i of all
+// 64 counters).  Four masks are folded at a time with full adders; only the resulting carry of
+// weight 4 ripples through the higher planes.
+constexpr int kCountPlanes = 13;                    // counters up to 2^13 - 1 groups of one graph
+
+struct SlicedCount {
+    u64 plane[kCountPlanes];
+    u64 x0, x1, x2;                                 // masks waiting for the fourth
+};
+
+__device__ __forceinline__ void full_add(u64 a, u64 b, u64 c, u64 &sum, u64 &carry)
 {
-    u64 fresh = 0;
-    const int max_in = wave_max(bits ? row.n_in : 0);
-    for (int r0 = 0; r0 < max_in; r0 += 4) {                 // four independent atomics in flight per lane
-        u64 old[4] = {~(u64)0, ~(u64)0, ~(u64)0, ~(u64)0};
+    const u64 ab = a ^ b;
+    sum = ab ^ c;
+    carry = (ab & c) | (a & b);
+}
+
+__device__ __forceinline__ void sliced_fold(SlicedCount &c, u64 x3, int planes_used)
+{
+    u64 s, ca, cb, cc;
+    full_add(c.plane[0], c.x0, c.x1, s, ca);
+    full_add(s, c.x2, x3, c.plane[0], cb);
+    full_add(c.plane[1], ca, cb, c.plane[1], cc);
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
-            if (bits && r0 + c < row.n_in) old[c] = atomicOr(&M[r0 == 0 ? row.ti[c] : g.in_idx[row.ib + r0 + c]], bits);
-#pragma unroll
-        for (int c = 0; c < 4; ++c) fresh |= bits & ~old[c];
+    for (int i = 2; i < kCountPlanes; ++i) {
+        if (i < planes_used) {                      // wave-uniform
+            const u64 t = c.plane[i] & cc;
+            c.plane[i] ^= cc;
+            cc = t;
+        }
     }
-    return fresh;
 }
 
 __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64 *M, u64 *K, int64_t *pq)
@@ -963,6 +997,11 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64
 #pragma unroll
     for (int i = 0; i < kCountPlanes; ++i) cnt.plane[i] = 0;
     cnt.x0 = cnt.x1 = cnt.x2 = 0;
+    for (int i = lane; i < kPendSlots; i += kWave) {
+        sh.pkey[i] = -1;
+        sh.pval[i] = 0;
+    }
+    int pending = 0;                                         // occupied slots of the pending table (wave-uniform)
     int group = 0;
     SweepRow cur = sweep_row_bounds(g, o_hi - 1 - lane, o_hi - 1 - lane >= o_lo);
     sweep_row_targets(g, cur);
@@ -975,38 +1014,64 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64
         const int64_t o2 = top - 2 * kWave - 1 - lane;
         const SweepRow nxt2 = sweep_row_bounds(g, o2, o2 >= o_lo);
         const SweepRow row = cur;
-        const int ob = row.ob, n_out = row.n_out, n_in = row.n_in;
-        const int max_out = wave_max(n_out);
-        u64 k = 0;
-        if (wave_sum(n_out) <= kSweepMaxKeys) {
-            for (int i = lane; i < kSweepSlots; i += kWave) sh.key[i] = -1;
+        const int n_out = row.n_out, n_in = row.n_in;
+        const int max_out = wave_max(n_out), max_in = wave_max(n_in);
+        const int total_in = wave_sum(n_in);
+        bool tables = wave_sum(n_out) <= kOutMax && total_in <= kInMax;
+        if (tables) {                                        // the group's output tensors and who writes them
+            for (int i = lane; i < kOutSlots; i += kWave) sh.okey[i] = -1;
             sh.ndep[lane] = 0;
             wave_lds_sync();
+            bool twice = false;
             for (int r = 0; r < max_out; ++r) {
                 if (r < n_out) {
                     const int32_t t = sweep_out(g, row, r);
-                    k |= load_coherent(&M[t]);
-                    int slot = sweep_slot(t);
-                    while (atomicCAS(&sh.key[slot], -1, t) != -1) slot = (slot + 1) & (kSweepSlots - 1);
-                    sh.owner[slot] = (uint8_t)lane;
+                    for (int slot = out_slot_of(t);; slot = (slot + 1) & (kOutSlots - 1)) {
+                        const int32_t old = atomicCAS(&sh.okey[slot], -1, t);
+                        if (old == -1) { sh.oowner[slot] = (uint8_t)lane; break; }
+                        if (old == t) { twice = true; break; }
+                    }
                 }
             }
+            if (ballot64(twice) != 0) tables = false;        // a tensor written twice inside the group
+        }
+        u64 k = 0;
+        if (tables) {
+            if (pending + total_in > kPendMax) {
+                flush_pending(sh, M);
+                pending = 0;
+            }
+            wave_stores_done();                              // M words stored by earlier groups are readable
             wave_lds_sync();
-            u64 feeds = 0;                                   // lanes whose operators write a tensor this lane's operator reads
-            const int max_in = wave_max(n_in);
-            for (int r = 0; r < max_in; ++r) {
-                if (r < n_in) {
-                    const int32_t t = sweep_in(g, row, r);
-                    for (int slot = sweep_slot(t);; slot = (slot + 1) & (kSweepSlots - 1)) {
-                        const int32_t key = sh.key[slot];
+            // the tensor's word in memory (seed bits, flushed pushes) plus what is pending for it
+            for (int r = 0; r < max_out; ++r) {
+                if (r < n_out) {
+                    const int32_t t = sweep_out(g, row, r);
+                    u64 m = M[t];
+                    for (int slot = pend_slot_of(t);; slot = (slot + 1) & (kPendSlots - 1)) {
+                        const int32_t key = sh.pkey[slot];
                         if (key == -1) break;
                         if (key == t) {
-                            const int b = sh.owner[slot];
-                            if (b > lane && !((feeds >> b) & 1)) {   // first time this lane meets producer b
-                                feeds |= (u64)1 << b;
-                                const int at = atomicAdd(&sh.ndep[b], 1);
-                                if (at < kSweepDeps) sh.dep[b][at] = (uint8_t)lane;
-                            }
+                            m |= sh.pval[slot];
+                            sh.pval[slot] = 0;               // taken: a later flush has nothing to write for it
+                            break;
+                        }
+                    }
+                    sh.oacc[find_out(sh, t)] = m;
+                    k |= m;
+                }
+            }
+            // in-group consumers register with the lane that writes the tensor they read
+            u64 feeds = 0;
+            for (int r = 0; r < max_in; ++r) {
+                if (r < n_in) {
+                    const int slot = find_out(sh, sweep_in(g, row, r));
+                    if (slot >= 0) {
+                        const int b = sh.oowner[slot];
+                        if (b > lane && !((feeds >> b) & 1)) {       // first time this lane meets producer b
+                            feeds |= (u64)1 << b;
+                            const int at = atomicAdd(&sh.ndep[b], 1);
+                            if (at < kSweepDeps) sh.dep[b][at] = (uint8_t)lane;
                         }
                     }
                 }
@@ -1015,9 +1080,7 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64
             const int nd = sh.ndep[lane];
             const int max_nd = wave_max(nd);
             if (max_nd <= kSweepDeps) {
-                // Relaxation: every lane ORs in the masks of the (few) lanes that read its outputs, all lanes
-                // at once, until nothing changes: as many steps as the longest dependency chain inside the
-                // group, usually a handful.
+                // Relaxation: as many steps as the longest dependency chain inside the group.
                 int d[kSweepDeps];
 #pragma unroll
                 for (int j = 0; j < kSweepDeps; ++j) d[j] = j < nd ? sh.dep[lane][j] : lane;
@@ -1040,24 +1103,53 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64
                     if (__builtin_amdgcn_inverse_ballot_w64(readlane64(feeds, src))) k |= ks;
                 }
             }
-            const u64 fresh = sweep_push(g, M, row, k);
-            // the atomics' results must have arrived before the next group reads M
-            asm volatile("" ::"v"((uint32_t)fresh), "v"((uint32_t)(fresh >> 32)) : "memory");
-            wave_lds_sync();                                 // the table is cleared only after every lane is done with it
-        } else {
-            // too many output tensors for the table: repeat the group until nothing changes
-            u64 kprev = 0;
-            for (;;) {
-                k = 0;
-                for (int r = 0; r < max_out; ++r)
-                    if (r < n_out) k |= load_coherent(&M[g.out_idx[ob + r]]);
-                const u64 nb = k & ~kprev;                   // bits this operator has not pushed to its inputs yet
-                kprev = k;
-                if (ballot64(nb != 0) == 0) break;
-                const u64 fresh = sweep_push(g, M, row, nb);
-                if (ballot64(fresh != 0) == 0) break;        // no word changed: a re-read would find nothing new
+            // pushes: to the group's own tensors in their accumulators, to all others in the pending table
+            int fresh_keys = 0;
+            for (int r = 0; r < max_in; ++r) {
+                if (r < n_in && k) {
+                    const int32_t t = sweep_in(g, row, r);
+                    const int os = find_out(sh, t);
+                    if (os >= 0) {
+                        atomicOr(&sh.oacc[os], k);
+                    } else {
+                        int slot = pend_slot_of(t);
+                        for (;; slot = (slot + 1) & (kPendSlots - 1)) {
+                            const int32_t old = atomicCAS(&sh.pkey[slot], -1, t);
+                            if (old == -1) { ++fresh_keys; break; }
+                            if (old == t) break;
+                        }
+                        atomicOr(&sh.pval[slot], k);
+                    }
+                }
             }
-            k = kprev;
+            pending += wave_sum(fresh_keys);
+            wave_lds_sync();
+            for (int r = 0; r < max_out; ++r)                // the group's tensors are final
+                if (r < n_out) {
+                    const int32_t t = sweep_out(g, row, r);
+                    M[t] = sh.oacc[find_out(sh, t)];
+                }
+            wave_lds_sync();
+        } else {
+            // One operator at a time, its edges spread over the lanes.  Pushes go straight to memory with
+            // plain read-modify-writes: lanes that meet the same tensor write the same value.
+            if (pending) {
+                flush_pending(sh, M);
+                pending = 0;
+            }
+            const int n_valid = (int)min((int64_t)kWave, top - o_lo);
+            for (int src = 0; src < n_valid; ++src) {
+                wave_stores_done();
+                const int s_ob = __shfl(row.ob, src, kWave), s_no = __shfl(n_out, src, kWave);
+                const int s_ib = __shfl(row.ib, src, kWave), s_ni = __shfl(n_in, src, kWave);
+                u64 part = 0;
+                for (int e = lane; e < s_no; e += kWave) part |= M[g.out_idx[s_ob + e]];
+                const u64 ks = wave_or(part);
+                if (lane == src) k = ks;
+                if (ks)
+                    for (int e = lane; e < s_ni; e += kWave) M[g.in_idx[s_ib + e]] |= ks;
+            }
+            wave_stores_done();
         }
         if (valid) K[o] = k;
         cur = nxt;
@@ -1071,6 +1163,7 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64
             }
         }
     }
+    flush_pending(sh, M);                                    // tensors no operator of the graph writes (its inputs)
     if (pq) {
         if (group & 3) {                                     // masks still waiting: fold them with zeros for the rest
             if ((group & 3) < 3) cnt.x2 = 0;
