@@ -30,6 +30,7 @@ constexpr int kNarrowCap = 3072;            // frontiers up to this size are wal
 constexpr int kWidePerGroup = 12;           // wide level launches between two single-workgroup launches
 constexpr int kWideGroupsFirst = 4;         // groups in the first batch (one state read-back per batch) ...
 constexpr int kWideGroups = 6;              // ... and in the following ones
+constexpr int kHintMargin = 5;              // launches enqueued beyond what the previous prune of the graph needed
 constexpr int kSweepMinGraphs = 64;         // packed batches with at least this many graphs ...
 constexpr int64_t kSweepMaxGraphOps = 1 << 18;   // ... none larger than this use the per-graph sweep
 constexpr int kPersistRounds = 2;           // cooperative launches (each followed by a single-workgroup one) per batch
@@ -236,6 +237,9 @@ struct dgn_graph {
     // first single-workgroup launch without waiting for its outcome (a wrong hint costs a few dozen
     // launches that return at once, and corrects itself).
     mutable std::atomic<int> wide_hint{0};
+    // Hint only: launches the last prune of this graph needed (0: unknown).  The next prune enqueues that many
+    // plus a margin before it reads the state back, instead of a fixed four groups of wide levels.
+    mutable std::atomic<int> launch_hint{0};
 };
 
 namespace {
@@ -636,6 +640,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     // with its state hand-over more; kept as option 3)
     bool persistent = options && options->traversal == 3 && g->persist_grid > 0;
     bool first = true;
+    int wide_pos = 0;                                 // position in the launch pattern of the wide phase
     while (!done) {
         if (persistent) {
             for (int r = 0; r < kPersistRounds && persistent; ++r) {
@@ -652,15 +657,22 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
             }
         }
         if (!persistent) {
-            for (int r = 0; r < (first ? kWideGroupsFirst : kWideGroups); ++r) {
-                for (int i = 0; i < kWidePerGroup; ++i, ++launch_no)
+            // launches follow the pattern (kWidePerGroup wide levels, one single-workgroup launch)*; the first
+            // batch is sized from what the previous prune of this graph needed, when that is known
+            int count = (first ? kWideGroupsFirst : kWideGroups) * (kWidePerGroup + (generic_only ? 0 : 1));
+            const int hint = g->launch_hint.load(std::memory_order_relaxed);
+            if (first && hint > 0 && !generic_only) {
+                const int want = hint - launch_no + kHintMargin;
+                if (want < count) count = want > kHintMargin ? want : kHintMargin;
+            }
+            for (int i = 0; i < count; ++i, ++launch_no, ++launches) {
+                if (generic_only || wide_pos % (kWidePerGroup + 1) != kWidePerGroup) {
                     DGN_HIP(launch_level(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, grid, narrow_cap, sch, trace, s));
-                launches += kWidePerGroup;
-                level_launches += kWidePerGroup;
-                if (!generic_only) {
+                    ++level_launches;
+                } else {
                     DGN_HIP(launch_narrow(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, narrow_cap, trace, s));
-                    ++launch_no; ++launches;
                 }
+                ++wide_pos;
             }
         }
         if (first && speculate) {
@@ -676,6 +688,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
         first = false;
     }
     g->wide_hint.store(hst->max_frontier > (u64)kNarrowCap ? 1 : 0, std::memory_order_relaxed);
+    g->launch_hint.store(hst->finished_at, std::memory_order_relaxed);
     if (hst->error & kErrOverflow) {
         // A frontier queue overflowed and dropped entries: restore the fixed point with whole-graph
         // sweeps (each operator re-derives K from its outputs) until one of them changes nothing.

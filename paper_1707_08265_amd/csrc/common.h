@@ -63,7 +63,8 @@ struct TravState {            // header of the traversal state; the host reads t
     int32_t gen;               // grid-barrier generation of the persistent kernel
     int32_t go;                // persistent kernel: the level just published is another wide one
     int32_t abort;             // persistent kernel: a block gave up waiting at the barrier
-    int32_t pad[4];
+    int32_t finished_at;       // number of launches after which the traversal was complete (0: not yet known)
+    int32_t pad[3];
 };
 
 // Contended words live 64 bytes apart, one per queue segment / block group.

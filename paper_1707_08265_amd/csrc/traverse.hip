@@ -531,7 +531,10 @@ __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState 
     const int lane = lane_id(), wave = threadIdx.x >> 6;
     const bool ranges_left = in.deferred_seen && in.theta_hi > 0;
     if (launch_no > 0 && in.n == 0 && !ranges_left) {       // traversal finished: carry the state on, cheaply
-        if (blockIdx.x == 0 && threadIdx.x == 0) *out = in;
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            *out = in;
+            if (st->finished_at == 0) st->finished_at = launch_no;     // the launches before this one sufficed
+        }
         return;
     }
     const int n = load_segments(ctr->cnt[in_slot], qg, sh.pref);
@@ -775,6 +778,7 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
             out->n = n;
             st->tensor_visits += visits;
             if (maxf > st->max_frontier) st->max_frontier = maxf;
+            if (n == 0 && !ranges_left && st->finished_at == 0) st->finished_at = launch_no + (moved ? 1 : 0);
         }
     }
 }
