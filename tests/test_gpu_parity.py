@@ -468,3 +468,29 @@ def test_csr_builder_skips_only_the_sorts_it_may_skip(dgn, oracle, which):
         assert np.array_equal(csr[name], getattr(adj, name)), f"{which}: {name}"
     _, _, out = gpu_prune(dgn, mixed, tg)
     assert_same(out, oracle.forward_prune(adj, tg.num_sets, tg.tgt_rowptr, tg.tgt_idx), which)
+
+
+@pytest.mark.parametrize("offset", [1, 3, 4])
+def test_flag_bytes_at_unaligned_addresses_and_ragged_sizes(dgn, oracle, offset):
+    """The flag bytes leave the count pass eight at a time when they can; a flag buffer that is not 8-byte
+    aligned and an operator count that is not a multiple of 8 (or of the tile) must give the same bytes."""
+    import torch
+    g, tg = gg.config(1, 0.3)
+    keep_in, keep_out = g.in_op < g.num_ops - 3, g.out_op < g.num_ops - 3        # drop three operators: ragged count
+    g = gg.Graph(g.num_ops - 3, g.num_tensors, g.in_op[keep_in].copy(), g.in_tensor[keep_in].copy(),
+                 g.out_op[keep_out].copy(), g.out_tensor[keep_out].copy(), name="ragged")
+    dg = dgn.DeviceGraph.from_coo(g)
+    buf = dgn.PruneBuffers(dg, tg.num_sets)
+    big = torch.full((g.num_ops + 16,), 77, dtype=torch.uint8, device="cuda")
+    flags = big[offset:offset + g.num_ops]
+    rc = dgn.dgn_prune(dg.handle, tg.num_sets, int(tg.tgt_idx.shape[0]), torch.from_numpy(tg.tgt_rowptr).cuda(),
+                       torch.from_numpy(tg.tgt_idx).cuda(), buf.tensor_mask, buf.op_mask, flags, buf.kept_ops,
+                       buf.kept_masks, buf.kept_count, buf.per_query_count, buf.scratch, buf.scratch_bytes)
+    assert rc == 0
+    torch.cuda.synchronize()
+    adj = oracle.build_adjacency(g.num_ops, g.num_tensors, g.in_op, g.in_tensor, g.out_op, g.out_tensor)
+    ref = oracle.forward_prune(adj, tg.num_sets, tg.tgt_rowptr, tg.tgt_idx)
+    assert np.array_equal(flags.cpu().numpy(), ref.op_flag)
+    assert (big[:offset] == 77).all().item() and (big[offset + g.num_ops:] == 77).all().item()   # nothing written outside
+    out = buf.to_host()
+    assert np.array_equal(out["op_mask"], ref.op_mask) and np.array_equal(out["kept_ops"], ref.kept_ops)
