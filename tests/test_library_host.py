@@ -99,3 +99,25 @@ def test_product_package_does_not_import_the_oracle():
     subprocess.check_call([sys.executable, "-c", code], cwd=ROOT)
     src = open(os.path.join(ROOT, "paper_1707_08265_amd", "binding.py")).read()
     assert "import oracle" not in src and "from oracle" not in src
+
+
+def test_other_entry_points_reject_bad_arguments_before_any_device_work(d):
+    """Backward prune, in-place pass and read-outs: NULL handles and impossible sizes are refused on the host."""
+    rc, _ = d.dgn_backward_prune_workspace(None)
+    assert rc == d.DGN_ERR_NULL_PTR
+    assert d.dgn_backward_prune(None, 4, None, None, None, None, None, None, None, None, None, None, 0) == d.DGN_ERR_NULL_PTR
+    rc, _ = d.dgn_inplace_workspace(None)
+    assert rc == d.DGN_ERR_NULL_PTR
+    rc, _ = d.dgn_inplace(None, None, 1, None, None, None, 0, stream=0)
+    assert rc == d.DGN_ERR_NULL_PTR
+    assert d.dgn_ignore_mask(None, None, None, None, None, None, None, stream=0) == d.DGN_ERR_NULL_PTR
+    rc, _ = d.dgn_per_set_lists_workspace(-1)
+    assert rc == d.DGN_ERR_INVALID_ARG
+    rc, _ = d.dgn_per_set_lists_workspace(2**31)
+    assert rc == d.DGN_ERR_TOO_LARGE
+    rc, nbytes = d.dgn_per_set_lists_workspace(0)
+    assert rc == 0 and nbytes > 0
+    assert d.dgn_per_set_lists(None, None, -1, None, None, 0, None, 0, stream=0) == d.DGN_ERR_INVALID_ARG
+    assert d.dgn_per_set_lists(None, None, 0, None, None, 0, None, 0, stream=0) == d.DGN_ERR_NULL_PTR
+    assert d.dgn_prune_words(None, 100, 0, None, None, None, None, None, None, None, None, None, None, 0, stream=0) == d.DGN_ERR_NULL_PTR
+    assert d.dgn_options(incremental=1).incremental == 1
