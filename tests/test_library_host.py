@@ -105,7 +105,7 @@ def test_other_entry_points_reject_bad_arguments_before_any_device_work(d):
     """Backward prune, in-place pass and read-outs: NULL handles and impossible sizes are refused on the host."""
     rc, _ = d.dgn_backward_prune_workspace(None)
     assert rc == d.DGN_ERR_NULL_PTR
-    assert d.dgn_backward_prune(None, 4, None, None, None, None, None, None, None, None, None, None, 0) == d.DGN_ERR_NULL_PTR
+    assert d.dgn_backward_prune(None, 4, None, None, None, None, None, None, None, None, None, None, 0, stream=0) == d.DGN_ERR_NULL_PTR
     rc, _ = d.dgn_inplace_workspace(None)
     assert rc == d.DGN_ERR_NULL_PTR
     rc, _ = d.dgn_inplace(None, None, 1, None, None, None, 0, stream=0)
