@@ -55,6 +55,70 @@ hipError_t launch_degree_hist(const int32_t *keys, const int32_t *vals, int64_t 
     return hipGetLastError();
 }
 
+// Range check of both ids of every edge, and whether the keys ever decrease (*unsorted = 1), in one pass
+// and without a single atomic in the common case: recorded graphs are usually handed over operator by
+// operator, and edges that are already in row order need no sort at all.
+__global__ __launch_bounds__(256) void k_check_edges(const int32_t *keys, const int32_t *vals, int64_t nnz,
+                                                      int32_t n_rows, int32_t n_vals, int32_t *error, int32_t *unsorted)
+{
+    const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
+    bool bad = false, descends = false;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < nnz; e += gsize) {
+        const int32_t k = keys[e], v = vals[e];
+        if (k < 0 || k >= n_rows || v < 0 || v >= n_vals) bad = true;
+        if (e > 0 && keys[e - 1] > k) descends = true;
+    }
+    if (ballot64(bad) != 0 && lane_id() == 0) atomicOr(error, kErrIdRange);
+    // shuffled input would have every wave report: look first, and store (same value from everyone) only if needed
+    if (ballot64(descends) != 0 && lane_id() == 0 && load_coherent(unsorted) == 0) store_coherent(unsorted, 1);
+}
+
+hipError_t launch_check_edges(const int32_t *keys, const int32_t *vals, int64_t nnz, int32_t n_rows, int32_t n_vals,
+                              int32_t *error, int32_t *unsorted, hipStream_t s)
+{
+    if (nnz == 0) return hipSuccess;
+    int64_t blocks = (nnz + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(k_check_edges, dim3((unsigned)blocks), dim3(256), 0, s, keys, vals, nnz, n_rows, n_vals, error,
+                       unsorted);
+    return hipGetLastError();
+}
+
+// Row pointers from keys in row order: rowptr[r] = first position whose key is >= r, rowptr[n_rows] = nnz.
+// Position i writes the rows (keys[i-1], keys[i]]; gaps longer than a few rows are filled by the whole wave.
+__global__ __launch_bounds__(256) void k_row_bounds(const int32_t *keys, int64_t nnz, int32_t n_rows, int32_t *rowptr)
+{
+    const int lane = lane_id();
+    const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
+    const int64_t steps = (nnz + 1 + gsize - 1) / gsize;                // position nnz closes the last rows
+    for (int64_t st = 0; st < steps; ++st) {                            // whole waves stay in the loop
+        const int64_t i = st * gsize + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+        int lo = 0, hi = -1;                                            // rows lo..hi get the value i
+        if (i <= nnz) {
+            lo = i == 0 ? 0 : keys[i - 1] + 1;
+            hi = i == nnz ? n_rows : keys[i];
+        }
+        constexpr int kShort = 4;
+        for (int r = lo; r <= hi && r < lo + kShort; ++r) rowptr[r] = (int32_t)i;
+        u64 longer = ballot64(hi - lo >= kShort);
+        while (longer) {                                                // wave-uniform
+            const int src = __builtin_ctzll(longer);
+            longer &= longer - 1;
+            const int s_lo = __shfl(lo, src, kWave) + kShort, s_hi = __shfl(hi, src, kWave);
+            const int32_t val = (int32_t)__shfl((long long)i, src, kWave);
+            for (int r = s_lo + lane; r <= s_hi; r += kWave) rowptr[r] = val;
+        }
+    }
+}
+
+hipError_t launch_row_bounds(const int32_t *keys, int64_t nnz, int32_t n_rows, int32_t *rowptr, hipStream_t s)
+{
+    int64_t blocks = (nnz + 1 + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(k_row_bounds, dim3((unsigned)blocks), dim3(256), 0, s, keys, nnz, n_rows, rowptr);
+    return hipGetLastError();
+}
+
 // Borrowed CSR: rowptr[0] == 0, monotone, rowptr[n_rows] == nnz, every idx in [0, n_vals).
 __global__ __launch_bounds__(256) void k_check_csr(const int32_t *rowptr, const int32_t *idx, int32_t n_rows,
                                                     int32_t nnz, int32_t n_vals, int32_t *error)
