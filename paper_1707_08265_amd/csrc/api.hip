@@ -350,50 +350,47 @@ int dgn_graph_build(const dgn_coo_desc *d, void *graph_mem, size_t graph_bytes, 
     const GraphLayout L = graph_layout(graph_mem, P, T, Ein, Eout, d->num_graphs, true);
     const BuildScratch S = build_scratch(scratch, P, T, Ein, Eout);
 
-    // One pass per edge list checks the ids and notes whether the keys ever decrease
-    // (status[1..3], all three in COO order); reading the flags costs one synchronisation.
+    // One pass per edge list (all three in COO order) checks the ids, notes whether the keys ever decrease
+    // (status[1..3]) and, on the assumption that they do not, already writes the finished rows: a graph
+    // recorded operator by operator needs nothing more.  Reading the flags costs one synchronisation.
     FillRegion clr[1] = {{S.status, 256}};
     DGN_HIP(launch_clear(clr, 1, s));
-    DGN_HIP(launch_check_edges(d->in_op, d->in_tensor, Ein, (int32_t)P, (int32_t)T, S.status, S.status + 1, s));
-    DGN_HIP(launch_check_edges(d->out_op, d->out_tensor, Eout, (int32_t)P, (int32_t)T, S.status, S.status + 2, s));
-    DGN_HIP(launch_check_edges(d->out_tensor, d->out_op, Eout, (int32_t)T, (int32_t)P, S.status, S.status + 3, s));
+    DGN_HIP(launch_scan_edges(d->in_op, d->in_tensor, Ein, (int32_t)P, (int32_t)T, L.in_idx, L.in_rowptr, S.status, S.status + 1, S.status + 5, s));
+    DGN_HIP(launch_scan_edges(d->out_op, d->out_tensor, Eout, (int32_t)P, (int32_t)T, L.out_idx, L.out_rowptr, S.status, S.status + 2, S.status + 6, s));
+    DGN_HIP(launch_scan_edges(d->out_tensor, d->out_op, Eout, (int32_t)T, (int32_t)P, L.prod_idx, L.prod_rowptr, S.status, S.status + 3, S.status + 7, s));
     void *pin = nullptr;
     rc = pinned_buffer(&pin);
     if (rc != DGN_OK) return rc;
-    DGN_HIP(hipMemcpyAsync(pin, S.status, 4 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    DGN_HIP(hipMemcpyAsync(pin, S.status, 8 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
     DGN_HIP(hipStreamSynchronize(s));
     const int32_t *flags = static_cast<const int32_t *>(pin);
     if (flags[0]) return error_bits_to_code(flags[0]);       // bad ids: nothing is built from them
     const bool in_sorted = !flags[1], out_sorted = !flags[2];
     const bool prod_sorted = out_sorted && !flags[3];         // the third sort reads the outputs in operator order
-    // Edges that already come in row order (a graph recorded operator by operator does) need no sort: the
-    // row's entries are the COO entries as they stand.  Otherwise stable sorts: edges by operator (rows keep
-    // COO order), then outputs by tensor, which leaves each tensor's producers ascending in operator id.
-    // Row pointers come from the keys in row order (first position of every key): no histogram, no atomics.
-    const int32_t *in_keys = d->in_op;
-    if (in_sorted) {
-        if (Ein > 0) DGN_HIP(hipMemcpyAsync(L.in_idx, d->in_tensor, (size_t)Ein * 4, hipMemcpyDeviceToDevice, s));
-    } else {
+    // Otherwise stable sorts: edges by operator (rows keep COO order), then outputs by tensor, which leaves each
+    // tensor's producers ascending in operator id; row pointers from the sorted keys (first position of every
+    // key): no histogram, no atomics.
+    // (flags[5..7]: the pass met a long run of empty rows and left the row pointers to launch_row_bounds)
+    if (!in_sorted) {
         DGN_HIP(launch_sort_pairs(d->in_op, d->in_tensor, S.sorted_keys, L.in_idx, Ein, key_bits_for(P), S.sort_tmp, s));
-        in_keys = S.sorted_keys;
+        DGN_HIP(launch_row_bounds(S.sorted_keys, Ein, (int32_t)P, L.in_rowptr, s));
+    } else if (flags[5]) {
+        DGN_HIP(launch_row_bounds(d->in_op, Ein, (int32_t)P, L.in_rowptr, s));
     }
-    DGN_HIP(launch_row_bounds(in_keys, Ein, (int32_t)P, L.in_rowptr, s));
     const int32_t *ops_of_out = d->out_op;                    // operator of every entry of out_idx
-    if (out_sorted) {
-        if (Eout > 0) DGN_HIP(hipMemcpyAsync(L.out_idx, d->out_tensor, (size_t)Eout * 4, hipMemcpyDeviceToDevice, s));
-    } else {
+    if (!out_sorted) {
         DGN_HIP(launch_sort_pairs(d->out_op, d->out_tensor, S.sorted_ops, L.out_idx, Eout, key_bits_for(P), S.sort_tmp, s));
+        DGN_HIP(launch_row_bounds(S.sorted_ops, Eout, (int32_t)P, L.out_rowptr, s));
         ops_of_out = S.sorted_ops;
+    } else if (flags[6]) {
+        DGN_HIP(launch_row_bounds(d->out_op, Eout, (int32_t)P, L.out_rowptr, s));
     }
-    DGN_HIP(launch_row_bounds(ops_of_out, Eout, (int32_t)P, L.out_rowptr, s));
-    const int32_t *prod_keys = L.out_idx;                     // tensor of every entry of prod_idx
-    if (prod_sorted) {
-        if (Eout > 0) DGN_HIP(hipMemcpyAsync(L.prod_idx, d->out_op, (size_t)Eout * 4, hipMemcpyDeviceToDevice, s));
-    } else {
+    if (!prod_sorted) {
         DGN_HIP(launch_sort_pairs(L.out_idx, ops_of_out, S.sorted_keys, L.prod_idx, Eout, key_bits_for(T), S.sort_tmp, s));
-        prod_keys = S.sorted_keys;
+        DGN_HIP(launch_row_bounds(S.sorted_keys, Eout, (int32_t)T, L.prod_rowptr, s));
+    } else if (flags[7]) {
+        DGN_HIP(launch_row_bounds(d->out_tensor, Eout, (int32_t)T, L.prod_rowptr, s));
     }
-    DGN_HIP(launch_row_bounds(prod_keys, Eout, (int32_t)T, L.prod_rowptr, s));
 
     dgn_graph *h = new (std::nothrow) dgn_graph();
     if (!h) return DGN_ERR_INVALID_ARG;

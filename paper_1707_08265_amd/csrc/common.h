@@ -184,8 +184,10 @@ hipError_t launch_sort_pairs(const int32_t *keys_in, const int32_t *vals_in, int
 // deg[key[e]] += 1 for keys in [0, n_rows); flags keys / vals outside their ranges in *error.
 hipError_t launch_degree_hist(const int32_t *keys, const int32_t *vals, int64_t nnz, int32_t n_rows,
                               int32_t n_vals, int32_t *deg, int32_t *error, int32_t *unsorted, hipStream_t s);
-hipError_t launch_check_edges(const int32_t *keys, const int32_t *vals, int64_t nnz, int32_t n_rows, int32_t n_vals,
-                              int32_t *error, int32_t *unsorted, hipStream_t s);
+// checks an edge list and, assuming its keys are in row order, writes the finished row (idx_out, rowptr)
+hipError_t launch_scan_edges(const int32_t *keys, const int32_t *vals, int64_t nnz, int32_t n_rows, int32_t n_vals,
+                             int32_t *idx_out, int32_t *rowptr, int32_t *error, int32_t *unsorted, int32_t *wide_gap,
+                             hipStream_t s);
 // rowptr[0..n_rows] from keys that are in row order (all in range)
 hipError_t launch_row_bounds(const int32_t *keys, int64_t nnz, int32_t n_rows, int32_t *rowptr, hipStream_t s);
 hipError_t launch_check_csr(const int32_t *rowptr, const int32_t *idx, int32_t n_rows, int32_t nnz,

@@ -55,32 +55,76 @@ hipError_t launch_degree_hist(const int32_t *keys, const int32_t *vals, int64_t 
     return hipGetLastError();
 }
 
-// Range check of both ids of every edge, and whether the keys ever decrease (*unsorted = 1), in one pass
-// and without a single atomic in the common case: recorded graphs are usually handed over operator by
-// operator, and edges that are already in row order need no sort at all.
-__global__ __launch_bounds__(256) void k_check_edges(const int32_t *keys, const int32_t *vals, int64_t nnz,
-                                                      int32_t n_rows, int32_t n_vals, int32_t *error, int32_t *unsorted)
+// One pass over an edge list in the order it was handed over: range check of both ids, whether the keys
+// ever decrease (*unsorted = 1), and -- on the assumption that they do not, which holds for a graph
+// recorded operator by operator -- the finished row: idx_out = the values as they stand, rowptr = first
+// position of every key.  If the keys do decrease somewhere, what was written is simply overwritten by the
+// sort that follows.  No atomic in the common case.
+__device__ __forceinline__ void write_rows(int32_t *rowptr, int lo, int hi, int32_t val)
+{
+    // rows lo..hi get val; gaps longer than a few rows are filled by the whole wave (call wave-uniformly)
+    constexpr int kShort = 4;
+    for (int r = lo; r <= hi && r < lo + kShort; ++r) rowptr[r] = val;
+    u64 longer = ballot64(hi - lo >= kShort);
+    while (longer) {
+        const int src = __builtin_ctzll(longer);
+        longer &= longer - 1;
+        const int s_lo = __shfl(lo, src, kWave) + kShort, s_hi = __shfl(hi, src, kWave);
+        const int32_t s_val = __shfl(val, src, kWave);
+        for (int r = s_lo + lane_id(); r <= s_hi; r += kWave) rowptr[r] = s_val;
+    }
+}
+
+constexpr int kMaxGapHere = 64;
+
+__global__ __launch_bounds__(256) void k_scan_edges(const int32_t *keys, const int32_t *vals, int64_t nnz,
+                                                     int32_t n_rows, int32_t n_vals, int32_t *idx_out, int32_t *rowptr,
+                                                     int32_t *error, int32_t *unsorted, int32_t *wide_gap)
 {
     const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
-    bool bad = false, descends = false;
-    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < nnz; e += gsize) {
-        const int32_t k = keys[e], v = vals[e];
-        if (k < 0 || k >= n_rows || v < 0 || v >= n_vals) bad = true;
-        if (e > 0 && keys[e - 1] > k) descends = true;
+    const int64_t steps = (nnz + 1 + gsize - 1) / gsize;                // position nnz closes the last rows
+    bool bad = false, descends = false, wide = false;
+    for (int64_t st = 0; st < steps; ++st) {                            // whole waves stay in the loop
+        const int64_t e = st * gsize + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+        int lo = 0, hi = -1;
+        if (e <= nnz) {
+            const int32_t prev = e > 0 ? keys[e - 1] : -1;
+            int32_t k = n_rows;
+            if (e < nnz) {
+                k = keys[e];
+                const int32_t v = vals[e];
+                if (k < 0 || k >= n_rows || v < 0 || v >= n_vals) bad = true;
+                if (prev > k) descends = true;
+                idx_out[e] = v;
+            }
+            // rows (prev, k]; keys outside their range write nothing (the call fails anyway)
+            if (prev >= -1 && prev < n_rows && k >= 0 && k <= n_rows) {
+                lo = prev + 1;
+                hi = k;
+            }
+            // A long run of empty rows is left to a pass of its own (*wide_gap): keys in random order jump far
+            // at nearly every position, and filling those jumps here would cost more than the sort that follows.
+            if (hi - lo >= kMaxGapHere) {
+                wide = true;
+                hi = lo - 1;
+            }
+        }
+        write_rows(rowptr, lo, hi, (int32_t)e);
     }
+    if (ballot64(wide) != 0 && lane_id() == 0 && load_coherent(wide_gap) == 0) store_coherent(wide_gap, 1);
     if (ballot64(bad) != 0 && lane_id() == 0) atomicOr(error, kErrIdRange);
     // shuffled input would have every wave report: look first, and store (same value from everyone) only if needed
     if (ballot64(descends) != 0 && lane_id() == 0 && load_coherent(unsorted) == 0) store_coherent(unsorted, 1);
 }
 
-hipError_t launch_check_edges(const int32_t *keys, const int32_t *vals, int64_t nnz, int32_t n_rows, int32_t n_vals,
-                              int32_t *error, int32_t *unsorted, hipStream_t s)
+hipError_t launch_scan_edges(const int32_t *keys, const int32_t *vals, int64_t nnz, int32_t n_rows, int32_t n_vals,
+                             int32_t *idx_out, int32_t *rowptr, int32_t *error, int32_t *unsorted, int32_t *wide_gap,
+                             hipStream_t s)
 {
-    if (nnz == 0) return hipSuccess;
-    int64_t blocks = (nnz + 255) / 256;
+    int64_t blocks = (nnz + 1 + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(k_check_edges, dim3((unsigned)blocks), dim3(256), 0, s, keys, vals, nnz, n_rows, n_vals, error,
-                       unsorted);
+    hipLaunchKernelGGL(k_scan_edges, dim3((unsigned)blocks), dim3(256), 0, s, keys, vals, nnz, n_rows, n_vals, idx_out,
+                       rowptr, error, unsorted, wide_gap);
     return hipGetLastError();
 }
 
@@ -88,7 +132,6 @@ hipError_t launch_check_edges(const int32_t *keys, const int32_t *vals, int64_t 
 // Position i writes the rows (keys[i-1], keys[i]]; gaps longer than a few rows are filled by the whole wave.
 __global__ __launch_bounds__(256) void k_row_bounds(const int32_t *keys, int64_t nnz, int32_t n_rows, int32_t *rowptr)
 {
-    const int lane = lane_id();
     const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
     const int64_t steps = (nnz + 1 + gsize - 1) / gsize;                // position nnz closes the last rows
     for (int64_t st = 0; st < steps; ++st) {                            // whole waves stay in the loop
@@ -98,16 +141,7 @@ __global__ __launch_bounds__(256) void k_row_bounds(const int32_t *keys, int64_t
             lo = i == 0 ? 0 : keys[i - 1] + 1;
             hi = i == nnz ? n_rows : keys[i];
         }
-        constexpr int kShort = 4;
-        for (int r = lo; r <= hi && r < lo + kShort; ++r) rowptr[r] = (int32_t)i;
-        u64 longer = ballot64(hi - lo >= kShort);
-        while (longer) {                                                // wave-uniform
-            const int src = __builtin_ctzll(longer);
-            longer &= longer - 1;
-            const int s_lo = __shfl(lo, src, kWave) + kShort, s_hi = __shfl(hi, src, kWave);
-            const int32_t val = (int32_t)__shfl((long long)i, src, kWave);
-            for (int r = s_lo + lane; r <= s_hi; r += kWave) rowptr[r] = val;
-        }
+        write_rows(rowptr, lo, hi, (int32_t)i);
     }
 }
 

@@ -494,3 +494,25 @@ def test_flag_bytes_at_unaligned_addresses_and_ragged_sizes(dgn, oracle, offset)
     assert (big[:offset] == 77).all().item() and (big[offset + g.num_ops:] == 77).all().item()   # nothing written outside
     out = buf.to_host()
     assert np.array_equal(out["op_mask"], ref.op_mask) and np.array_equal(out["kept_ops"], ref.kept_ops)
+
+
+def test_csr_builder_with_long_runs_of_empty_rows(dgn, oracle):
+    """Operators without edges and tensors nobody writes leave long runs of empty rows; ordered input takes
+    the single-pass path, which hands such runs to a separate row-pointer pass."""
+    P, T = 5000, 20000
+    ops = [([], []) for _ in range(P)]
+    ops[10] = ([3, 15000], [16000])
+    ops[3000] = ([16000, 7], [16001, 19999])
+    ops[4999] = ([19999], [200])                    # writes a low-numbered tensor: producer lists need their sort
+    g = graph_from_ops(ops, T)
+    adj = oracle.build_adjacency(g.num_ops, g.num_tensors, g.in_op, g.in_tensor, g.out_op, g.out_tensor)
+    for variant in ("ordered", "shuffled"):
+        gv = g if variant == "ordered" else gg.shuffle_coo(g, 9)
+        ref = oracle.build_adjacency(gv.num_ops, gv.num_tensors, gv.in_op, gv.in_tensor, gv.out_op, gv.out_tensor)
+        dg = dgn.DeviceGraph.from_coo(gv)
+        csr = {n: v.cpu().numpy() for n, v in dg.csr().items()}
+        for name in ("in_rowptr", "in_idx", "out_rowptr", "out_idx", "prod_rowptr", "prod_idx"):
+            assert np.array_equal(csr[name], getattr(ref, name)), f"{variant}: {name}"
+    tg = targets_from_sets([[200], [16001]])
+    _, _, out = gpu_prune(dgn, g, tg)
+    assert_same(out, oracle.forward_prune(adj, 2, tg.tgt_rowptr, tg.tgt_idx), "sparse rows")
