@@ -245,10 +245,17 @@ __device__ __forceinline__ int find_graph(const int64_t *off, int num_graphs, in
 
 __global__ __launch_bounds__(256) void k_check_graph_ranges(GraphView g, int32_t *error)
 {
-    const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
+    // a wave walks a contiguous stretch of operators 64 at a time, so a lane's graph index only ever steps
+    // forward: one binary search per lane, not one per operator
+    const int64_t waves = (int64_t)gridDim.x * (blockDim.x / kWave);
+    const int64_t wave_id = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x >> 6);
+    const int64_t per = (((int64_t)g.num_ops + waves - 1) / waves + kWave - 1) / kWave * kWave;
+    const int64_t first = wave_id * per, last = min(first + per, (int64_t)g.num_ops);
     bool bad = false;
-    for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < g.num_ops; o += gsize) {
-        const int gi = find_graph(g.op_off, g.num_graphs, o);
+    int gi = -1;
+    for (int64_t o = first + lane_id(); o < last; o += kWave) {
+        if (gi < 0) gi = find_graph(g.op_off, g.num_graphs, o);
+        while (o >= g.op_off[gi + 1]) ++gi;                 // op_off[num_graphs] == num_ops > o: stops in range
         const int64_t lo = g.t_off[gi], hi = g.t_off[gi + 1];
         for (int32_t e = g.in_rowptr[o]; e < g.in_rowptr[o + 1]; ++e)
             if (g.in_idx[e] < lo || g.in_idx[e] >= hi) bad = true;

@@ -516,3 +516,28 @@ def test_csr_builder_with_long_runs_of_empty_rows(dgn, oracle):
     tg = targets_from_sets([[200], [16001]])
     _, _, out = gpu_prune(dgn, g, tg)
     assert_same(out, oracle.forward_prune(adj, 2, tg.tgt_rowptr, tg.tgt_idx), "sparse rows")
+
+
+def test_edges_and_targets_that_cross_packed_graphs_are_reported(dgn):
+    """In a packed batch every edge of an operator and every target of a set must stay inside its graph."""
+    import torch
+    parts = []
+    rng = np.random.default_rng(3)
+    for i in range(70):
+        gi, _ = random_small_graph(rng, 40, num_inputs=3)
+        parts.append((gi, [[0], [1]]))
+    g, tg = _pack(parts, 2)
+    bad = gg.Graph(g.num_ops, g.num_tensors, g.in_op.copy(), g.in_tensor.copy(), g.out_op.copy(), g.out_tensor.copy(),
+                   g.num_graphs, g.graph_op_offsets, g.graph_tensor_offsets, "crossing")
+    e = int(np.flatnonzero(bad.in_op >= g.graph_op_offsets[5])[0])          # an input edge of graph 5 ...
+    bad.in_tensor[e] = int(g.graph_tensor_offsets[9])                        # ... reads a tensor of graph 9
+    with pytest.raises(dgn.DgnError) as err:
+        dgn.DeviceGraph.from_coo(bad, validate=True)
+    assert err.value.code == dgn.DGN_ERR_ID_OUT_OF_RANGE
+    # a target of graph 0's first set that lies in graph 3
+    dg = dgn.DeviceGraph.from_coo(g, validate=True)
+    buf = dgn.PruneBuffers(dg, 2)
+    idx = tg.tgt_idx.copy()
+    idx[0] = int(g.graph_tensor_offsets[3])
+    rc = buf.prune(torch.from_numpy(tg.tgt_rowptr).cuda(), torch.from_numpy(idx).cuda())
+    assert rc == dgn.DGN_ERR_ID_OUT_OF_RANGE
