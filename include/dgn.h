@@ -92,9 +92,7 @@ typedef struct dgn_options {
                                 instead of using the K the traversal accumulated (same values)   */
     int32_t traversal;       /* 0 = automatic; 1 = one kernel launch per frontier level, nothing else;
                                 2 = one launch per wide level plus the single-workgroup kernel for
-                                small frontiers (what 0 chooses for a single graph);
-                                3 = all wide levels in one cooperative launch with a grid barrier
-                                between levels (falls back to 2 where such launches are refused)   */
+                                small frontiers (what 0 chooses for a single graph)               */
     int32_t profile;         /* prune: bracket each phase with HIP events on `stream` and report
                                 the elapsed times in dgn_stats.phase_ms (needs stats != NULL)      */
     int32_t defer_percent;   /* prune: geometric decay (percent, 1..99) of the producer-id threshold

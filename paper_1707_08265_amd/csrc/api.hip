@@ -30,11 +30,10 @@ constexpr int kNarrowCap = 3072;            // frontiers up to this size are wal
 constexpr int kWidePerGroup = 12;           // wide level launches between two single-workgroup launches
 constexpr int kWideGroupsFirst = 4;         // groups in the first batch (one state read-back per batch) ...
 constexpr int kWideGroups = 6;              // ... and in the following ones
-constexpr int kHintMargin = 5;              // launches enqueued beyond what the previous prune of the graph needed
+constexpr int kMaxBatch = 512;              // launches enqueued between two state read-backs, at most
+constexpr int kTailLevels = 2;              // wide launches enqueued beyond the layout the previous prune needed
 constexpr int kSweepMinGraphs = 64;         // packed batches with at least this many graphs ...
 constexpr int64_t kSweepMaxGraphOps = 1 << 18;   // ... none larger than this use the per-graph sweep
-constexpr int kPersistRounds = 2;           // cooperative launches (each followed by a single-workgroup one) per batch
-constexpr int kBarrierMaxSpins = 1 << 22;   // polls (about 0.5 us each) before a block gives up at the grid barrier
 constexpr int kSmallLevel = 16384;           // levels expanding fewer entries than this decay the threshold faster
 constexpr int kDefaultDeferPercent = 85;
 constexpr int kDefaultStartShift = 1;       // deferral threshold starts at P >> 1 ...
@@ -217,7 +216,7 @@ int error_bits_to_code(int32_t bits)
 int check_options(const dgn_options *o)
 {
     if (!o) return DGN_OK;
-    if (o->traversal < 0 || o->traversal > 3) return DGN_ERR_INVALID_ARG;
+    if (o->traversal < 0 || o->traversal > 2) return DGN_ERR_INVALID_ARG;
     if (o->defer_percent < 0 || o->defer_percent > 100) return DGN_ERR_INVALID_ARG;
     if (o->max_queue_entries < 0) return DGN_ERR_INVALID_ARG;
     if (o->defer_start_shift < 0 || o->defer_start_shift > 30) return DGN_ERR_INVALID_ARG;
@@ -232,16 +231,19 @@ struct dgn_graph {
     int64_t P, T, Ein, Eout;
     int32_t G;
     int num_cus;
-    int persist_grid;       // blocks of the cooperative traversal kernel (0: not available)
     bool topological;       // operator ids verified to be a topological order at build time
     int64_t max_graph_ops;  // largest graph of a packed batch (P for a single graph)
-    // Hint only: the last prune of this graph needed wide levels, so the next one enqueues them behind the
-    // first single-workgroup launch without waiting for its outcome (a wrong hint costs a few dozen
-    // launches that return at once, and corrects itself).
-    mutable std::atomic<int> wide_hint{0};
-    // Hint only: launches the last prune of this graph needed (0: unknown).  The next prune enqueues that many
-    // plus a margin before it reads the state back, instead of a fixed four groups of wide levels.
-    mutable std::atomic<int> launch_hint{0};
+    // Hints only, taken from the last prune of this graph; a wrong one costs launches that return at once,
+    // or a second batch, and corrects itself.  Kept apart for full prunes [0] and incremental ones [1],
+    // whose traversals look nothing alike.
+    //   wide_hint: wide levels were needed, so they are enqueued behind the first single-workgroup launch
+    //     without waiting for its outcome;
+    //   hint_runs, hint_run_len: how that prune alternated between stretches of wide levels and the
+    //     single-workgroup kernel (lengths of the first stretches; 0 stretches: unknown); the launches are
+    //     laid out the same way instead of in fixed groups.
+    mutable std::atomic<int> wide_hint[2] = {};
+    mutable std::atomic<int> hint_runs[2] = {};
+    mutable std::atomic<int> hint_run_len[2][dgn::kMaxRuns] = {};
 };
 
 namespace {
@@ -283,12 +285,6 @@ int finish_build(dgn_graph *h, const GraphLayout &L, const int64_t *op_off_host,
     DGN_HIP(hipGetDevice(&dev));
     DGN_HIP(hipGetDeviceProperties(&prop, dev));
     h->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-    h->persist_grid = 0;
-    if (prop.cooperativeLaunch) {
-        int pg = 0;
-        if (persist_max_grid(h->num_cus, &pg) == hipSuccess && pg >= h->num_cus) h->persist_grid = pg;
-        else (void)hipGetLastError();
-    }
     *out = h;
     return DGN_OK;
 }
@@ -611,6 +607,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     const int64_t max_useful = (g->T + 255) / 256;
     if (grid > max_useful) grid = (int)(max_useful > 0 ? max_useful : 1);
     const bool generic_only = options && options->traversal == 1;
+    const int hk = (options && options->incremental) ? 1 : 0;      // which set of layout hints
     const int narrow_cap = generic_only ? 0 : kNarrowCap;
     int launch_no = 0;
     int32_t *user_trace = stats ? stats->level_trace : nullptr;
@@ -619,62 +616,68 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     // the stand-alone removal-rule pass rewrites K, which the traversal still needs while unfinished
     const bool speculate = !ca.from_tensor_mask;
     bool done = false, compacted = false;
+    // The record of a single-workgroup launch is a complete state (it leaves no tallies to fold in), so every
+    // batch ends with one, and that record is what is read back.
+    bool last_was_narrow = false;
+    auto narrow = [&]() -> int {
+        DGN_HIP(launch_narrow(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, narrow_cap, sch, trace, s));
+        ++launch_no; ++launches;
+        last_was_narrow = true;
+        return DGN_OK;
+    };
     auto read_state = [&]() -> int {
+        if (!last_was_narrow) {
+            const int e = narrow();
+            if (e) return e;
+        }
         DGN_HIP(hipMemcpyAsync(pin, S.state, sizeof(TravState), hipMemcpyDeviceToHost, s));
         DGN_HIP(hipStreamSynchronize(s));
-        const LevelSlot &sl = hst->slot[launch_no & 1];
+        const LevelSlot &sl = hst->slot[(launch_no - 1) & 1];
         done = sl.n == 0 && !(sl.deferred_seen && sl.theta_hi > 0);
         return DGN_OK;
     };
     if (!generic_only) {
-        DGN_HIP(launch_narrow(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, narrow_cap, trace, s));
-        ++launch_no; ++launches;
-        if (!g->wide_hint.load(std::memory_order_relaxed)) {
+        rc = narrow();
+        if (rc) return rc;
+        if (!g->wide_hint[hk].load(std::memory_order_relaxed)) {
             rc = read_state();
             if (rc) return rc;
         }
     }
-    // Wide levels: preferably all of them in one cooperative launch (grid barrier between levels, no
-    // host involvement); otherwise one launch per level.
-    // (measured slower than plain launches on this chip: a launch costs ~2 us back to back, the barrier
-    // with its state hand-over more; kept as option 3)
-    bool persistent = options && options->traversal == 3 && g->persist_grid > 0;
+    auto group = [&](int levels) -> int {            // `levels` wide launches, then the single-workgroup kernel
+        for (int i = 0; i < levels; ++i) {
+            DGN_HIP(launch_level(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, grid, narrow_cap, sch, trace, s));
+            ++launch_no; ++launches; ++level_launches;
+        }
+        last_was_narrow = false;
+        return narrow();
+    };
     bool first = true;
-    int wide_pos = 0;                                 // position in the launch pattern of the wide phase
+    int batch = 0;
     while (!done) {
-        if (persistent) {
-            for (int r = 0; r < kPersistRounds && persistent; ++r) {
-                const hipError_t e = launch_persist(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K,
-                                                    g->persist_grid, narrow_cap, sch, trace, kBarrierMaxSpins, s);
-                if (e != hipSuccess) {                      // cooperative launch refused: use plain launches
-                    (void)hipGetLastError();
-                    persistent = false;
-                    break;
-                }
-                ++launch_no; ++launches; ++level_launches;
-                DGN_HIP(launch_narrow(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, narrow_cap, trace, s));
-                ++launch_no; ++launches;
+        const int hint_runs = generic_only ? 0 : g->hint_runs[hk].load(std::memory_order_relaxed);
+        if (first && hint_runs > 0) {
+            // the layout the previous prune of this graph turned out to need, plus a short tail
+            int room = kMaxBatch;
+            for (int r = 0; r < hint_runs && r < kMaxRuns && room > 0; ++r) {
+                int len = g->hint_run_len[hk][r].load(std::memory_order_relaxed);
+                len = len < 1 ? 1 : len > room ? room : len;
+                rc = group(len);
+                if (rc) return rc;
+                room -= len + 1;
+            }
+            rc = group(kTailLevels);
+            if (rc) return rc;
+        } else {
+            // unknown graph, or the layout fell short: groups of wide levels with the single-workgroup kernel
+            // after each; a batch right after a hinted one is small (the hint was nearly right)
+            const int groups = first ? kWideGroupsFirst : (hint_runs > 0 && batch == 1) ? 1 : kWideGroups;
+            for (int i = 0; i < groups; ++i) {
+                rc = group(kWidePerGroup);
+                if (rc) return rc;
             }
         }
-        if (!persistent) {
-            // launches follow the pattern (kWidePerGroup wide levels, one single-workgroup launch)*; the first
-            // batch is sized from what the previous prune of this graph needed, when that is known
-            int count = (first ? kWideGroupsFirst : kWideGroups) * (kWidePerGroup + (generic_only ? 0 : 1));
-            const int hint = g->launch_hint.load(std::memory_order_relaxed);
-            if (first && hint > 0 && !generic_only) {
-                const int want = hint - launch_no + kHintMargin;
-                if (want < count) count = want > kHintMargin ? want : kHintMargin;
-            }
-            for (int i = 0; i < count; ++i, ++launch_no, ++launches) {
-                if (generic_only || wide_pos % (kWidePerGroup + 1) != kWidePerGroup) {
-                    DGN_HIP(launch_level(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, grid, narrow_cap, sch, trace, s));
-                    ++level_launches;
-                } else {
-                    DGN_HIP(launch_narrow(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, narrow_cap, trace, s));
-                }
-                ++wide_pos;
-            }
-        }
+        ++batch;
         if (first && speculate) {
             if (ev) DGN_HIP(hipEventRecord(ev[3], s));
             DGN_HIP(launch_keep_compact(ca, s, ev ? ev + 4 : nullptr));
@@ -683,12 +686,15 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
         }
         rc = read_state();
         if (rc) return rc;
-        if (hst->error & kErrBarrier) return DGN_ERR_INTERNAL;
         if (!done) compacted = false;      // the speculative pass ran on unfinished masks
         first = false;
     }
-    g->wide_hint.store(hst->max_frontier > (u64)kNarrowCap ? 1 : 0, std::memory_order_relaxed);
-    g->launch_hint.store(hst->finished_at, std::memory_order_relaxed);
+    g->wide_hint[hk].store(hst->max_frontier > (u64)kNarrowCap ? 1 : 0, std::memory_order_relaxed);
+    {
+        const int nr = hst->n_runs < kMaxRuns ? hst->n_runs : kMaxRuns;
+        for (int r = 0; r < nr; ++r) g->hint_run_len[hk][r].store(hst->wide_runs[r], std::memory_order_relaxed);
+        g->hint_runs[hk].store(nr, std::memory_order_relaxed);
+    }
     if (hst->error & kErrOverflow) {
         // A frontier queue overflowed and dropped entries: restore the fixed point with whole-graph
         // sweeps (each operator re-derives K from its outputs) until one of them changes nothing.
@@ -719,7 +725,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
         memset(stats, 0, sizeof(*stats));
         stats->level_trace = user_trace;
         stats->level_trace_cap = user_trace_cap;
-        stats->levels = hst->slot[launch_no & 1].level;
+        stats->levels = hst->slot[(launch_no - 1) & 1].level;
         if (trace) {
             int64_t nrec = stats->levels < user_trace_cap ? stats->levels : user_trace_cap;
             if (nrec > kTraceLevels) nrec = kTraceLevels;

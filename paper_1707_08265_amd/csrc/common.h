@@ -20,7 +20,6 @@ enum : int32_t {
     kErrCsr = 4,          // row pointers not monotone / not ending at nnz
     kErrCrossGraph = 8,   // target or edge outside its own packed graph
     kErrOverflow = 16,    // internal: a frontier queue overflowed, the fix-up sweep must run
-    kErrBarrier = 32,     // a block of the persistent kernel waited too long at the grid barrier
 };
 
 // Adjacency of a built graph as the kernels see it (device pointers).
@@ -40,44 +39,49 @@ constexpr int32_t kFresh = -1;        // entry not looked up yet
 constexpr int32_t kMulti = -2;        // several producers: (eb, deg) index prod_idx
 constexpr int32_t kNoProducer = -3;   // graph input
 
-// One slot of traversal state.  Launch number e reads slot e&1 and its finishing block writes
-// slot (e+1)&1, so a block of launch e that starts late never sees state of the next level.
+// Record of one launch of the traversal: the state it started from and whether it ran a level.
+// Launch e writes record e & 1 (one thread, at its start) and reads record (e - 1) & 1, which nobody
+// writes while launch e runs.  No block ever waits for another: a launch leaves raw tallies behind
+// (push counters, expansion counts, largest deferred operator id, all spread over 64 words), and EVERY
+// block of the next launch derives the next state from the previous record and those tallies by itself.
 struct LevelSlot {
-    int32_t level;          // levels completed so far; queue parity = level & 1
-    int32_t n;              // entries in the frontier to process (the *other* slot's n collects pushes)
+    int32_t level;          // levels completed before this launch; queue parity = level & 1
+    int32_t n;              // entries in the frontier this launch started from
     int32_t theta;          // entries whose producer id is below this are deferred at this level
     int32_t theta_hi;       // deferred operators with id in [theta, theta_hi) are expanded at this level
     int32_t deferred_seen;  // some operator has been deferred so far
-    int32_t pad[3];
+    int32_t worked;         // the launch ran a level: its tallies still have to be folded into the state
+    int32_t max_key1;       // 1 + largest operator id deferred so far (0: none)
+    int32_t pad;
 };
 
+constexpr int kMaxRuns = 6;
 struct TravState {            // header of the traversal state; the host reads these 128 bytes back
     LevelSlot slot[2];
-    u64 ticket;                // low half: block groups that have finished the current launch;
-                               // high half: entries / operators they expanded
     int32_t error;             // sticky kErr* bits
-    int32_t max_deferred_key1; // 1 + largest operator id deferred so far (0: none)
+    int32_t pad0;
     u64 tensor_visits;         // expansions, summed over levels
     u64 max_frontier;
     int32_t changed;           // fix-up sweep: some operator gained bits
-    int32_t gen;               // grid-barrier generation of the persistent kernel
-    int32_t go;                // persistent kernel: the level just published is another wide one
-    int32_t abort;             // persistent kernel: a block gave up waiting at the barrier
-    int32_t finished_at;       // number of launches after which the traversal was complete (0: not yet known)
-    int32_t pad[3];
+    int32_t run_len;           // wide levels run since the frontier was last small enough for one workgroup
+    int32_t n_runs;            // such stretches completed so far; the first kMaxRuns lengths are kept
+    int32_t wide_runs[kMaxRuns];
+    int32_t pad;
 };
 
 // Contended words live 64 bytes apart, one per queue segment / block group.
 constexpr int kMaxSeg = 64;
 // Optional per-level trace (frontier size, expansions, threshold, range top), first kTraceLevels levels.
 constexpr int kTraceLevels = 4096;
-struct SegCounter { int32_t v; int32_t pad[15]; };
-struct SegTicket { u64 v; u64 pad[7]; };
-struct TravCounters {
-    SegCounter cnt[2][kMaxSeg];      // push counters of the frontier queues, indexed by launch parity
-    SegTicket subticket[kMaxSeg];    // first-level tickets
-    SegCounter submax[kMaxSeg];      // per-group 1 + largest deferred operator id
+struct SegCounter {
+    int32_t v;           // pushes into this segment of the frontier the launch produced (or handed on)
+    int32_t proc;        // entries / operators expanded by the waves that tally here
+    int32_t key1;        // 1 + largest operator id those waves deferred
+    int32_t pad[13];
 };
+// Tallies of a launch, in buffer (launch number) % 3: written by launch e, read by launch e + 1, zeroed by
+// launch e + 2 (one wave, at its start) for launch e + 3.
+struct TravCounters { SegCounter cnt[3][kMaxSeg]; };
 // Deferral schedule: the threshold starts at theta0, is multiplied by decay after every wide level and
 // drops to 0 (nothing deferred any more) once it falls below theta_floor.
 struct Schedule { float decay; int32_t theta0; int32_t theta_floor; int32_t small_level; };
@@ -202,19 +206,15 @@ hipError_t launch_seed(const GraphView &g, int32_t Q, int64_t num_targets, const
                        const int32_t *tgt_idx, u64 *M, TravState *st, TravCounters *ctr, int32_t *q0,
                        const QueueGeom &qg, int32_t theta0, hipStream_t s);
 // One wide level (whole chip); a frontier of at most narrow_cap entries is left to launch_narrow unless
-// deferred operators are waiting.  DB: deferred-operator bitmap, one bit per operator.
+// deferred operators are waiting.  DB: deferred-operator markers, one byte per operator.
 hipError_t launch_level(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
                         const QueueGeom &qg, uint8_t *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
                         const Schedule &sch, int4 *trace, hipStream_t s);
-// All consecutive wide levels in one cooperative launch (grid barrier between levels); grid_blocks must
-// not exceed persist_max_grid().  A waiting block gives up after max_spins polls (kErrBarrier).
-hipError_t launch_persist(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
-                          const QueueGeom &qg, uint8_t *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
-                          const Schedule &sch, int4 *trace, int max_spins, hipStream_t s);
-hipError_t persist_max_grid(int num_cus, int *grid_blocks);
-// One workgroup runs level after level while 0 < frontier <= narrow_cap and nothing is deferred.
+// One workgroup runs level after level while 0 < frontier <= narrow_cap and nothing is deferred.  It leaves no
+// tallies behind, so the record it writes is the state the host may read.
 hipError_t launch_narrow(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
-                         const QueueGeom &qg, uint8_t *DB, u64 *M, u64 *K, int narrow_cap, int4 *trace, hipStream_t s);
+                         const QueueGeom &qg, uint8_t *DB, u64 *M, u64 *K, int narrow_cap, const Schedule &sch,
+                         int4 *trace, hipStream_t s);
 // Packed batches of small graphs whose operator ids are a topological order: one wave per graph sweeps
 // its operators once, highest ids first (no frontier at all); fills K and, when pq is not NULL, the
 // per-graph per-set counts.

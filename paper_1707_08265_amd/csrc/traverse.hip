@@ -108,22 +108,7 @@ __device__ __forceinline__ void stage_push(WaveStage &ws, bool push, int32_t t, 
     }
 }
 
-// Reader side: prefix sums of the (clamped) segment counts, computed by wave 0 into s_pref[0..S].
-// Must be called by the whole block; returns the frontier size.
-__device__ __forceinline__ int load_segments(const SegCounter *cnt, const QueueGeom &qg, int *s_pref)
-{
-    if (threadIdx.x < kWave) {
-        const int lane = lane_id();
-        int c = 0;
-        if (lane < qg.S) c = min(load_coherent(&cnt[lane].v), qg.seg_cap);
-        const int incl = wave_incl_scan(c);
-        if (lane == 0) s_pref[0] = 0;
-        s_pref[lane + 1] = incl;
-    }
-    __syncthreads();
-    return s_pref[kMaxSeg];
-}
-
+// Reader side: item i of a frontier whose segment counts have the prefix sums s_pref[0..S].
 __device__ __forceinline__ int32_t load_item(const int32_t *q, const QueueGeom &qg, const int *s_pref, int i)
 {
     int lo = 0, hi = kMaxSeg - 1;               // segment holding item i: last s with s_pref[s] <= i
@@ -132,7 +117,7 @@ __device__ __forceinline__ int32_t load_item(const int32_t *q, const QueueGeom &
         const int mid = (lo + hi + 1) >> 1;
         if (s_pref[mid] <= i) lo = mid; else hi = mid - 1;
     }
-    // bypass the per-CU cache: a persistent workgroup re-reads queue slots it wrote two levels earlier
+    // bypass the per-CU cache: the single-workgroup kernel re-reads queue slots it wrote two levels earlier
     return load_coherent(&q[(int64_t)lo * qg.seg_cap + (i - s_pref[lo])]);
 }
 
@@ -145,9 +130,9 @@ __global__ __launch_bounds__(256) void k_seed(GraphView g, int32_t Q, int64_t nu
                                                int32_t theta0)
 {
     const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (j == 0) {
-        st->slot[0].theta = theta0;
-        st->slot[0].theta_hi = g.num_ops;
+    if (j == 0) {                                           // the record "before launch 0": nothing done yet
+        st->slot[1].theta = theta0;
+        st->slot[1].theta_hi = g.num_ops;
     }
     bool push = false, bad = false, cross = false;
     int32_t t = 0;
@@ -180,7 +165,7 @@ __global__ __launch_bounds__(256) void k_seed(GraphView g, int32_t Q, int64_t nu
     if (pm) {
         const int seg = (int)((j >> 6) & (qg.S - 1));
         int base = 0;
-        if (lane_id() == 0) base = atomicAdd(&ctr->cnt[0][seg].v, __popcll(pm));
+        if (lane_id() == 0) base = atomicAdd(&ctr->cnt[2][seg].v, __popcll(pm));   // tallies "of launch -1"
         base = __builtin_amdgcn_readfirstlane(base);
         const int pos = base + __popcll(pm & lanemask_lt());
         if (push) {
@@ -262,7 +247,7 @@ __device__ __forceinline__ void process_entries(const GraphView &g, bool valid, 
         const u64 mt = load_coherent(&M[t]);                // (I4): everything t holds right now (issued
                                                             // together with the record: no dependency)
         if (pi.x >= 0 && pi.x < theta) {                    // (I5): wait for the threshold to pass o
-            store_coherent(&DB[pi.x], (uint8_t)1);          // a byte per operator: a plain store, no atomic
+            DB[pi.x] = 1;          // a byte per operator, no atomic; read by a later launch, when theta has passed o
             lc.max_deferred_key = max(lc.max_deferred_key, pi.x);
         } else if (pi.x != kNoProducer) {
             active = true;
@@ -344,6 +329,14 @@ __device__ __forceinline__ int32_t next_theta(int32_t theta, const Schedule &sch
 
 // ------------------------------------------------------------------------------------------------
 // wide levels: one frontier level per launch, the whole chip
+//
+// No block waits for another and nobody "closes" a level.  A launch leaves behind (a) a record: the
+// state it started from, and whether it ran a level from there; (b) its tallies, spread over 64 words:
+// pushes per queue segment, expansions, largest deferred id.  Every block of the NEXT launch folds the
+// two into the state it starts from -- a few dozen loads and a wave reduction, the same arithmetic in
+// every block, so all blocks agree without talking to each other.  Records alternate between two slots
+// and tallies between three buffers (written by launch e, read by e + 1, zeroed by e + 2), so nothing a
+// launch reads is written during that launch.
 // ------------------------------------------------------------------------------------------------
 constexpr int kLevelThreads = 256;
 constexpr int kLevelWaves = kLevelThreads / kWave;
@@ -354,8 +347,7 @@ struct LevelShared {
     int incl[kLevelWaves][kWave];
     int32_t ops[kLevelWaves][kChunkOps];
     int pref[kMaxSeg + 1];
-    int proc[kLevelWaves], maxkey[kLevelWaves];
-    int last, go;
+    int derived[2];         // expansions and 1 + largest deferred id of the previous launch
 };
 
 // How one level's work is dealt to `grid` blocks.
@@ -387,10 +379,10 @@ __device__ __forceinline__ LevelPlan plan_level(const LevelSlot &in, int n, bool
 }
 
 // The work of block `blk` (< p.nwork) in one level: its share of the frontier entries and of the
-// newly opened operator range.  Leaves the block's tallies in sh.proc / sh.maxkey (one per wave).
+// newly opened operator range.  Adds the block's tallies to tally_proc / tally_key.
 __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &in, int n, const LevelPlan &p, int blk,
                                           const int32_t *qin, const QueueGeom &qg, const Frontier &f, uint8_t *DB, u64 *M,
-                                          u64 *K, LevelShared &sh)
+                                          u64 *K, LevelShared &sh, SegCounter *tally)
 {
     const int lane = lane_id(), wave = threadIdx.x >> 6;
     const bool do_entries = !p.split || blk < p.nb_e;
@@ -417,9 +409,9 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
             const uint32_t *src = reinterpret_cast<const uint32_t *>(DB + (op0 & ~(int64_t)3));
             if (cw >= 4) {
                 for (int k = 0; k < (cw >> 2); ++k)         // bytes are 0 or 1: gather bit 0 of each
-                    bits16 |= (((load_coherent(src + k) & 0x01010101u) * 0x01020408u) >> 24) << (4 * k);
+                    bits16 |= (((src[k] & 0x01010101u) * 0x01020408u) >> 24) << (4 * k);
             } else {
-                const uint32_t x = load_coherent(src) >> ((int)(op0 & 3) * 8);
+                const uint32_t x = src[0] >> ((int)(op0 & 3) * 8);
                 bits16 = (((x & 0x01010101u) * 0x01020408u) >> 24) & ((1u << cw) - 1u);
             }
             // keep only ids in [theta, theta_hi)
@@ -447,77 +439,93 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
         __builtin_amdgcn_wave_barrier();
     }
     stage_flush(ws, f);
+    // the wave's tallies go to one of 64 spread words each; nobody waits for them
     const int wproc = wave_sum(lc.processed), wkey = wave_max(lc.max_deferred_key);
-    if (lane == 0) { sh.proc[wave] = wproc; sh.maxkey[wave] = wkey; }
-}
-
-// Two-level ticket (groups of blocks, then groups) taken by thread 0 of each of the `nwork` participating
-// blocks after __syncthreads.  Returns true in the last block to arrive; *total_proc then holds the sum
-// of all blocks' tallies.  Everything a block contributed is an atomic performed at the device-coherent
-// level (or a write-through queue store), so only completion of the block's own memory operations is
-// awaited here, no cache write-back.
-__device__ __forceinline__ bool take_ticket(TravState *st, TravCounters *ctr, int blk, int nwork, LevelShared &sh,
-                                            int *total_proc)
-{
-    int proc = 0, mk = -1;
-    for (int w = 0; w < kLevelWaves; ++w) { proc += sh.proc[w]; mk = max(mk, sh.maxkey[w]); }
-    const int groups = min(kMaxSeg, nwork);
-    int gproc = proc, gmax = mk + 1;
-    bool group_done = true;
-    if (nwork > kMaxSeg) {                               // first level: blocks of one group
-        const int grp = blk & (kMaxSeg - 1);
-        const int gsize = (nwork - grp + kMaxSeg - 1) / kMaxSeg;
-        if (mk >= 0) atomicMax(&ctr->submax[grp].v, mk + 1);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        const u64 tk = atomicAdd(&ctr->subticket[grp].v, ((u64)(uint32_t)proc << 32) | 1u);
-        group_done = (int)(tk & 0xffffffffu) == gsize - 1;
-        if (group_done) {
-            gproc = (int)(tk >> 32) + proc;
-            gmax = load_coherent(&ctr->submax[grp].v);
-            __hip_atomic_store(&ctr->subticket[grp].v, (u64)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
+    if (lane == 0) {
+        const int word = (blk * kLevelWaves + wave) & (kMaxSeg - 1);
+        if (wproc) atomicAdd(&tally[word].proc, wproc);
+        if (wkey >= 0) atomicMax(&tally[word].key1, wkey + 1);
     }
-    if (!group_done) return false;
-    if (gmax > 0) atomicMax(&st->max_deferred_key1, gmax);   // second level: one ticket per group
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    const u64 tk2 = atomicAdd(&st->ticket, ((u64)(uint32_t)gproc << 32) | 1u);
-    if ((int)(tk2 & 0xffffffffu) != groups - 1) return false;
-    *total_proc = (int)(tk2 >> 32) + gproc;
-    return true;
 }
 
-// Wave 0 of the last block of a level: totals of the push counters, next level's state.  The new state
-// goes to slot `dst` (and its counters to cnt[dst]); cnt[1 - dst] ends up zeroed as the next push target.
-__device__ __forceinline__ void publish_level(TravState *st, TravCounters *ctr, const LevelSlot &in, int n,
-                                              bool ranges_left, int out_slot, int dst, const QueueGeom &qg,
-                                              const Schedule &sch, int tot_proc, int4 *trace)
+// The state a launch starts from, derived by every block on its own from the record of the previous
+// launch and, if that launch ran a level, from its tallies.  Whole block; fills s_pref (prefix sums of
+// the frontier's segment counts).  prev = tallies buffer of the previous launch.
+__device__ __forceinline__ LevelSlot derive_state(const TravState *st, const TravCounters *ctr, int launch_no,
+                                                  const QueueGeom &qg, const Schedule &sch, int *s_pref, int *s_derived,
+                                                  int *tot_proc_out)
+{
+    const int prev = (launch_no + 2) % 3;
+    const LevelSlot rec = st->slot[(launch_no + 1) & 1];
+    if (threadIdx.x < kWave) {
+        const int lane = lane_id();
+        const SegCounter *tally = &ctr->cnt[prev][lane];     // written by the previous launch: plain loads will do
+        int c = 0;
+        if (lane < qg.S) c = min(tally->v, qg.seg_cap);
+        const int pr = tally->proc;
+        const int mk = tally->key1;
+        const int incl = wave_incl_scan(c);
+        if (lane == 0) s_pref[0] = 0;
+        s_pref[lane + 1] = incl;
+        const int tot = wave_sum(pr), key1 = wave_max(mk);
+        if (lane == 0) { s_derived[0] = tot; s_derived[1] = key1; }
+    }
+    __syncthreads();
+    LevelSlot s = rec;
+    s.worked = 0;
+    s.n = s_pref[kMaxSeg];
+    *tot_proc_out = 0;
+    if (rec.worked) {                                       // fold the level the previous launch ran into the state
+        const int tot_proc = s_derived[0];
+        const int key1 = max(rec.max_key1, s_derived[1]);
+        const bool ranges_left = rec.deferred_seen && rec.theta_hi > 0;
+        s.level = rec.level + 1;
+        s.max_key1 = key1;
+        s.deferred_seen = key1 > 0;
+        s.theta_hi = ranges_left ? rec.theta : rec.theta_hi;               // [theta, theta_hi) has been scanned
+        s.theta = (ranges_left || key1 > 0) ? next_theta(rec.theta, sch, tot_proc, s.n, key1 - 1) : rec.theta;
+        *tot_proc_out = tot_proc;
+    }
+    return s;
+}
+
+// One thread per launch keeps the books: the record of this launch, running totals, the level trace; one
+// wave clears the tallies buffer of the NEXT launch (last read by the previous one).  works: this launch
+// runs a wide level; small: the state it starts from is one the single-workgroup kernel takes (or final).
+__device__ __forceinline__ void keep_books(TravState *st, TravCounters *ctr, int launch_no, const LevelSlot &prev_rec,
+                                           const LevelSlot &now, bool works, bool small, int tot_proc, int4 *trace)
 {
     const int lane = lane_id();
-    int c = 0;
-    if (lane < qg.S) {
-        c = load_coherent(&ctr->cnt[out_slot][lane].v);
-        if (c > qg.seg_cap) c = qg.seg_cap;
-    }
-    store_coherent(&ctr->cnt[out_slot ^ 1][lane].v, 0);
-    if (dst != out_slot) {                               // the pushes were counted in the other slot: move them
-        store_coherent(&ctr->cnt[dst][lane].v, c);
-        store_coherent(&ctr->cnt[out_slot][lane].v, 0);
-    }
-    const int n_next = wave_sum(c);
+    const int nxt = (launch_no + 1) % 3;
+    ctr->cnt[nxt][lane].v = 0;
+    ctr->cnt[nxt][lane].proc = 0;
+    ctr->cnt[nxt][lane].key1 = 0;
     if (lane == 0) {
-        const int tot_key = load_coherent(&st->max_deferred_key1) - 1;
-        LevelSlot *out = &st->slot[dst];
-        __hip_atomic_store(&st->ticket, (u64)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        store_coherent(&out->level, in.level + 1);
-        store_coherent(&out->n, n_next);
-        store_coherent(&out->deferred_seen, tot_key >= 0);
-        store_coherent(&out->theta_hi, ranges_left ? in.theta : in.theta_hi);   // [theta, theta_hi) has been scanned
-        store_coherent(&out->theta, (ranges_left || tot_key >= 0) ? next_theta(in.theta, sch, tot_proc, n_next, tot_key)
-                                                                  : in.theta);
-        atomicAdd(&st->tensor_visits, (u64)tot_proc);
-        atomicMax(&st->max_frontier, (u64)n);
-        if (trace && in.level < kTraceLevels) trace[in.level] = make_int4(n, tot_proc, in.theta, (int)(uint32_t)wall_clock64());
+        LevelSlot rec = now;
+        rec.worked = works ? 1 : 0;
+        st->slot[launch_no & 1] = rec;
+        if (prev_rec.worked) {
+            st->tensor_visits += (u64)tot_proc;
+            if ((u64)prev_rec.n > st->max_frontier) st->max_frontier = (u64)prev_rec.n;
+            if (trace && prev_rec.level < kTraceLevels)
+                trace[prev_rec.level] = make_int4(prev_rec.n, tot_proc, prev_rec.theta, (int)(uint32_t)wall_clock64());
+        }
+        // lengths of the stretches of wide levels, for the host to lay out the launches of the next prune
+        if (works) {
+            st->run_len++;
+        } else if (small && st->run_len > 0) {
+            if (st->n_runs < kMaxRuns) st->wide_runs[st->n_runs] = st->run_len;
+            st->n_runs++;
+            st->run_len = 0;
+        }
     }
+}
+
+// The frontier is handed to the next launch untouched: its segment counts move into this launch's tallies.
+__device__ __forceinline__ void hand_on_frontier(TravCounters *ctr, int launch_no, const int *s_pref)
+{
+    const int lane = lane_id();
+    ctr->cnt[launch_no % 3][lane].v = s_pref[lane + 1] - s_pref[lane];
 }
 
 __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState *st, TravCounters *ctr, int launch_no,
@@ -525,51 +533,29 @@ __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState 
                                                           u64 *K, int narrow_cap, Schedule sch, int4 *trace)
 {
     __shared__ LevelShared sh;
-    const int in_slot = launch_no & 1, out_slot = in_slot ^ 1;
-    const LevelSlot in = st->slot[in_slot];
-    LevelSlot *out = &st->slot[out_slot];
-    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int wave = threadIdx.x >> 6;
+    const LevelSlot prev_rec = st->slot[(launch_no + 1) & 1];
+    int tot_proc = 0;
+    const LevelSlot in = derive_state(st, ctr, launch_no, qg, sch, sh.pref, sh.derived, &tot_proc);
+    const int n = in.n;
     const bool ranges_left = in.deferred_seen && in.theta_hi > 0;
-    if (launch_no > 0 && in.n == 0 && !ranges_left) {       // traversal finished: carry the state on, cheaply
-        if (blockIdx.x == 0 && threadIdx.x == 0) {
-            *out = in;
-            if (st->finished_at == 0) st->finished_at = launch_no;     // the launches before this one sufficed
-        }
-        return;
+    // finished, or small enough for the single-workgroup kernel: nothing to do but to pass things on
+    const bool works = !(n <= narrow_cap && !ranges_left);
+    if (blockIdx.x == 0 && threadIdx.x < kWave) {
+        keep_books(st, ctr, launch_no, prev_rec, in, works, !works, tot_proc, trace);
+        if (!works) hand_on_frontier(ctr, launch_no, sh.pref);
     }
-    const int n = load_segments(ctr->cnt[in_slot], qg, sh.pref);
-    if (n <= narrow_cap && !ranges_left) {   // finished, or small enough for the single-workgroup kernel
-        if (blockIdx.x == 0 && threadIdx.x < kMaxSeg) {     // hand the frontier (its counters) to the next launch
-            const int c = sh.pref[lane + 1] - sh.pref[lane];
-            ctr->cnt[out_slot][lane].v = c;
-            ctr->cnt[in_slot][lane].v = 0;
-            if (lane == 0) {
-                *out = in;
-                out->n = n;
-            }
-        }
-        return;
-    }
+    if (!works) return;
     const LevelPlan p = plan_level(in, n, ranges_left, (int)gridDim.x);
     if ((int)blockIdx.x >= p.nwork) return;
 
     const int cur = in.level & 1;
     const int32_t *qin = cur ? q1 : q0;
     int32_t *qout = cur ? q0 : q1;
+    const int mine = launch_no % 3;
     const int seg = (blockIdx.x * kLevelWaves + wave) & (qg.S - 1);
-    const Frontier f{qout + (int64_t)seg * qg.seg_cap, &ctr->cnt[out_slot][seg].v, qg.seg_cap, &st->error};
-    run_level(g, in, n, p, (int)blockIdx.x, qin, qg, f, DB, M, K, sh);
-
-    // the last working block to finish publishes the next level
-    if (threadIdx.x == 0) sh.last = 0;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int tot = 0;
-        if (take_ticket(st, ctr, (int)blockIdx.x, p.nwork, sh, &tot)) { sh.last = 1; sh.proc[0] = tot; }
-    }
-    __syncthreads();
-    if (sh.last && threadIdx.x < kWave)
-        publish_level(st, ctr, in, n, ranges_left, out_slot, out_slot, qg, sch, sh.proc[0], trace);
+    const Frontier f{qout + (int64_t)seg * qg.seg_cap, &ctr->cnt[mine][seg].v, qg.seg_cap, &st->error};
+    run_level(g, in, n, p, (int)blockIdx.x, qin, qg, f, DB, M, K, sh, ctr->cnt[mine]);
 }
 
 hipError_t launch_level(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
@@ -582,138 +568,6 @@ hipError_t launch_level(const GraphView &g, TravState *st, TravCounters *ctr, in
 }
 
 // ------------------------------------------------------------------------------------------------
-// persistent wide levels: the whole run of wide levels in ONE cooperative launch.  All blocks are
-// resident; between levels they meet at a grid barrier built from the same two-level ticket (the last
-// block to arrive publishes the next level, then releases the others by bumping a generation word).
-// Everything blocks exchange goes through atomics, write-through stores and cache-bypassing loads, so the
-// barrier needs no cache write-back or invalidation.  A block that waits longer than max_spins polls
-// raises kErrBarrier and every block leaves: the kernel cannot hang.
-// ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ LevelSlot load_slot_coherent(const LevelSlot *s)
-{
-    LevelSlot r;
-    r.level = load_coherent(&s->level);
-    r.n = load_coherent(&s->n);
-    r.theta = load_coherent(&s->theta);
-    r.theta_hi = load_coherent(&s->theta_hi);
-    r.deferred_seen = load_coherent(&s->deferred_seen);
-    return r;
-}
-
-__global__ __launch_bounds__(kLevelThreads) void k_persist(GraphView g, TravState *st, TravCounters *ctr, int launch_no,
-                                                            int32_t *q0, int32_t *q1, QueueGeom qg, uint8_t *DB, u64 *M,
-                                                            u64 *K, int narrow_cap, Schedule sch, int4 *trace,
-                                                            int max_spins)
-{
-    __shared__ LevelShared sh;
-    const int lane = lane_id(), wave = threadIdx.x >> 6;
-    const int grid = (int)gridDim.x, blk = (int)blockIdx.x;
-    const int final_slot = (launch_no + 1) & 1;              // where the next launch expects the state
-    int slot = launch_no & 1;
-    int gen = load_coherent(&st->gen);                       // nobody bumps it before every block has arrived once
-    for (;;) {
-        const LevelSlot in = load_slot_coherent(&st->slot[slot]);
-        const bool ranges_left = in.deferred_seen && in.theta_hi > 0;
-        const int n = load_segments(ctr->cnt[slot], qg, sh.pref);
-        const bool stop = n <= narrow_cap && !ranges_left;   // same state, same decision in every block
-        if (stop) {
-            // Only reachable in the first round (later rounds stop through sh.go below).  Hand the
-            // untouched frontier to the next launch, as k_level does.
-            if (blk == 0 && threadIdx.x < kMaxSeg) {
-                const int c = sh.pref[lane + 1] - sh.pref[lane];
-                ctr->cnt[final_slot][lane].v = c;
-                ctr->cnt[slot][lane].v = 0;
-                if (lane == 0) {
-                    st->slot[final_slot] = in;
-                    st->slot[final_slot].n = n;
-                }
-            }
-            return;
-        }
-        const LevelPlan p = plan_level(in, n, ranges_left, grid);
-        const int cur = in.level & 1;
-        const int32_t *qin = cur ? q1 : q0;
-        int32_t *qout = cur ? q0 : q1;
-        const int out_slot = slot ^ 1;
-        const int seg = (blk * kLevelWaves + wave) & (qg.S - 1);
-        const Frontier f{qout + (int64_t)seg * qg.seg_cap, &ctr->cnt[out_slot][seg].v, qg.seg_cap, &st->error};
-        if (blk < p.nwork) {
-            run_level(g, in, n, p, blk, qin, qg, f, DB, M, K, sh);
-        } else if (lane == 0) {
-            sh.proc[wave] = 0;
-            sh.maxkey[wave] = -1;
-        }
-        // ---- grid barrier: every block takes a ticket; the last one publishes and releases ----
-        if (threadIdx.x == 0) { sh.last = 0; sh.go = 1; }
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            int tot = 0;
-            if (take_ticket(st, ctr, blk, grid, sh, &tot)) { sh.last = 1; sh.proc[0] = tot; }
-        }
-        __syncthreads();
-        if (sh.last) {
-            // Will the next level still be a wide one?  If not, the state is left where the next launch
-            // looks for it and everybody leaves.
-            if (threadIdx.x < kWave) {
-                int c = 0;
-                if (lane < qg.S) c = min(load_coherent(&ctr->cnt[out_slot][lane].v), qg.seg_cap);
-                const int n_next = wave_sum(c);
-                // exactly the test the blocks would make on the state about to be published
-                const int theta_hi_next = ranges_left ? in.theta : in.theta_hi;
-                const bool more_ranges = load_coherent(&st->max_deferred_key1) > 0 && theta_hi_next > 0;
-                const bool go = n_next > narrow_cap || more_ranges;
-                publish_level(st, ctr, in, n, ranges_left, out_slot, go ? out_slot : final_slot, qg, sch, sh.proc[0], trace);
-                if (lane == 0) {
-                    sh.go = go;
-                    store_coherent(&st->go, go ? 1 : 0);
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");     // state written before the release
-                    __hip_atomic_store(&st->gen, gen + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-            }
-        } else if (threadIdx.x == 0) {
-            int spins = 0;
-            while (load_coherent(&st->gen) == gen) {
-                __builtin_amdgcn_s_sleep(8);
-                if (++spins > max_spins || load_coherent(&st->abort)) {
-                    atomicOr(&st->error, kErrBarrier);
-                    store_coherent(&st->abort, 1);
-                    sh.go = 0;
-                    break;
-                }
-            }
-            if (sh.go) sh.go = load_coherent(&st->go);
-        }
-        __syncthreads();
-        if (!sh.go) return;
-        slot ^= 1;
-        ++gen;
-    }
-}
-
-hipError_t launch_persist(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
-                          const QueueGeom &qg, uint8_t *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
-                          const Schedule &sch, int4 *trace, int max_spins, hipStream_t s)
-{
-    GraphView gv = g;
-    QueueGeom q = qg;
-    Schedule sc = sch;
-    void *args[] = {&gv, &st, &ctr, &launch_no, &q0, &q1, &q, &DB, &M, &K, &narrow_cap, &sc, &trace, &max_spins};
-    return hipLaunchCooperativeKernel(reinterpret_cast<void *>(k_persist), dim3((unsigned)grid_blocks),
-                                      dim3(kLevelThreads), args, 0, s);
-}
-
-// Largest grid whose blocks are all resident at once (what a cooperative launch accepts).
-hipError_t persist_max_grid(int num_cus, int *grid_blocks)
-{
-    int per_cu = 0;
-    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_persist, kLevelThreads, 0);
-    if (e != hipSuccess) return e;
-    if (per_cu > 4) per_cu = 4;
-    *grid_blocks = per_cu * num_cus;
-    return hipSuccess;
-}
-
-// ------------------------------------------------------------------------------------------------
 // narrow levels: one workgroup walks level after level while the frontier is small, with workgroup
 // barriers instead of kernel launches (deep graphs have hundreds of small levels)
 // ------------------------------------------------------------------------------------------------
@@ -722,23 +576,24 @@ constexpr int kNarrowWaves = kNarrowThreads / kWave;
 
 __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravState *st, TravCounters *ctr, int launch_no,
                                                             int32_t *q0, int32_t *q1, QueueGeom qg, uint8_t *DB, u64 *M,
-                                                            u64 *K, int narrow_cap, int4 *trace)
+                                                            u64 *K, int narrow_cap, Schedule sch, int4 *trace)
 {
     __shared__ int32_t s_stage[kNarrowWaves][kStageCap];
     __shared__ int s_incl[kNarrowWaves][kWave];
     __shared__ int s_pref[kMaxSeg + 1];
+    __shared__ int s_derived[2];
     __shared__ int s_nout;
 
-    const int in_slot = launch_no & 1, out_slot = in_slot ^ 1;
-    const LevelSlot in = st->slot[in_slot];
+    const LevelSlot prev_rec = st->slot[(launch_no + 1) & 1];
+    int tot_proc = 0;
+    LevelSlot in = derive_state(st, ctr, launch_no, qg, sch, s_pref, s_derived, &tot_proc);
     int level = in.level;
-    int n = load_segments(ctr->cnt[in_slot], qg, s_pref);
+    int n = in.n;
     const bool ranges_left = in.deferred_seen && in.theta_hi > 0;   // then the wide kernel must go on
     const int lane = lane_id(), wave = threadIdx.x >> 6;
     WaveStage ws{&s_stage[wave][0], 0};
     LevelCounters lc{0, -1};
     u64 visits = 0, maxf = 0;
-    bool moved = false;
     while (n > 0 && n <= narrow_cap && !ranges_left) {
         if (threadIdx.x == 0) s_nout = 0;
         __syncthreads();
@@ -762,32 +617,31 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
         if (trace && threadIdx.x == 0 && level < kTraceLevels) trace[level] = make_int4(n, n, -1, (int)(uint32_t)wall_clock64());
         n = min(s_nout, qg.seg_cap);
         ++level;
-        moved = true;
         // the next frontier lives in segment 0 only
         if (threadIdx.x <= kMaxSeg) s_pref[threadIdx.x] = threadIdx.x == 0 ? 0 : n;
         __syncthreads();          // everyone has read s_nout before it is reset; s_pref is in place
     }
-    if (threadIdx.x < kMaxSeg) {                             // publish the frontier's counters for the next launch
-        const int c = moved ? (lane == 0 ? n : 0) : s_pref[lane + 1] - s_pref[lane];
-        ctr->cnt[out_slot][lane].v = c;
-        ctr->cnt[in_slot][lane].v = 0;
+    // This launch leaves no tallies to fold: its record IS the state after it.  The frontier it ends with
+    // (untouched, or the one it built in segment 0) goes to the next launch through this launch's counters.
+    if (threadIdx.x < kWave) {
+        keep_books(st, ctr, launch_no, prev_rec, in, false, in.n <= narrow_cap && !ranges_left, tot_proc, trace);
+        hand_on_frontier(ctr, launch_no, s_pref);
         if (lane == 0) {
-            LevelSlot *out = &st->slot[out_slot];
-            *out = in;
-            out->level = level;
-            out->n = n;
+            LevelSlot *rec = &st->slot[launch_no & 1];
+            rec->level = level;
+            rec->n = n;
             st->tensor_visits += visits;
             if (maxf > st->max_frontier) st->max_frontier = maxf;
-            if (n == 0 && !ranges_left && st->finished_at == 0) st->finished_at = launch_no + (moved ? 1 : 0);
         }
     }
 }
 
 hipError_t launch_narrow(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
-                         const QueueGeom &qg, uint8_t *DB, u64 *M, u64 *K, int narrow_cap, int4 *trace, hipStream_t s)
+                         const QueueGeom &qg, uint8_t *DB, u64 *M, u64 *K, int narrow_cap, const Schedule &sch,
+                         int4 *trace, hipStream_t s)
 {
     hipLaunchKernelGGL(k_narrow, dim3(1), dim3(kNarrowThreads), 0, s, g, st, ctr, launch_no, q0, q1, qg, DB, M, K,
-                       narrow_cap, trace);
+                       narrow_cap, sch, trace);
     return hipGetLastError();
 }
 

@@ -216,7 +216,7 @@ def test_schedule_knobs_do_not_change_results(dgn, oracle, k, scale):
     g, tg = gg.config(k, scale)
     _, r = oracle_prune(oracle, g, tg)
     for knobs in (dict(defer_percent=100), dict(defer_percent=50), dict(defer_percent=95),
-                  dict(traversal=1), dict(traversal=1, defer_percent=60), dict(traversal=2), dict(traversal=3), dict(traversal=3, defer_percent=70),
+                  dict(traversal=1), dict(traversal=1, defer_percent=60), dict(traversal=2), dict(traversal=2, defer_percent=70),
                   dict(traversal=2, defer_percent=90, defer_start_shift=3, defer_floor_shift=14),
                   dict(max_queue_entries=1000), dict(max_queue_entries=37, traversal=1)):
         st = dgn.dgn_stats()
