@@ -111,6 +111,19 @@ typedef struct dgn_options {
                                 leaves the fixed point for the union.  Nothing is cleared, only the new
                                 bits are traversed; every other output is rewritten in full.  The masks
                                 must be such a result: anything else gives unspecified masks             */
+    int32_t recycle;         /* prune: the caller states that nothing but dgn_prune has written to `scratch`
+                                since it last passed it to this library, and that, if the last such call
+                                was a dgn_prune of this graph with this tensor_mask, op_mask, kept_ops and
+                                kept_count, those four are still as that call left them.  The call then
+                                zeroes only the words that call set (it finds them through a log the
+                                earlier call kept in `scratch`, and checks on the device that graph and
+                                buffers are the same) instead of all of tensor_mask and op_mask, and keeps
+                                such a log itself.  Where no complete log is found (first call with this
+                                flag, other buffers, a prune that coloured more than a quarter of the
+                                tensors, packed batches swept per graph, after an incremental call)
+                                everything is cleared as without the flag.  Outputs are the same either
+                                way.  Do not set it on the first call with a scratch buffer whose contents
+                                are undefined                                                          */
 } dgn_options;
 
 /* Indices into dgn_stats.phase_ms */
@@ -137,7 +150,9 @@ typedef struct dgn_stats {
                                 wall clock in 10 ns ticks when the level was finished), for the first
                                 level_trace_cap levels (at most 4096)                                    */
     int64_t level_trace_cap; /* IN: capacity of level_trace in levels                                     */
-    int64_t reserved;
+    int64_t reserved;        /* dgn_backward_prune: passes of its forward stage; 0 otherwise                */
+    int64_t recycled;        /* 1 when options->recycle found the previous result in place and the call
+                                zeroed only what that result had set                               */
     float phase_ms[DGN_NUM_PHASES];   /* filled when options->profile; zero otherwise           */
 } dgn_stats;
 

@@ -53,13 +53,14 @@ class dgn_csr_desc(ctypes.Structure):
 class dgn_options(ctypes.Structure):
     _fields_ = [("validate", c_int32), ("recompute_keep", c_int32), ("traversal", c_int32),
                 ("profile", c_int32), ("defer_percent", c_int32), ("max_queue_entries", c_int32),
-                ("defer_start_shift", c_int32), ("defer_floor_shift", c_int32), ("incremental", c_int32)]
+                ("defer_start_shift", c_int32), ("defer_floor_shift", c_int32), ("incremental", c_int32),
+                ("recycle", c_int32)]
 
 
 class dgn_stats(ctypes.Structure):
     _fields_ = [("levels", c_int64), ("tensor_visits", c_int64), ("max_frontier", c_int64),
                 ("launches", c_int64), ("level_launches", c_int64), ("level_trace", c_void_p),
-                ("level_trace_cap", c_int64), ("reserved", c_int64),
+                ("level_trace_cap", c_int64), ("reserved", c_int64), ("recycled", c_int64),
                 ("phase_ms", ctypes.c_float * 8)]
 
 PHASES = ["clear", "seed", "traverse", "count", "scan", "scatter", "total"]
@@ -390,9 +391,13 @@ class DeviceGraph:
 class PruneBuffers:
     """All caller-owned buffers of one ``dgn_prune`` call, allocated once and reusable."""
 
-    def __init__(self, graph: DeviceGraph, num_sets: int, device=None):
+    def __init__(self, graph: DeviceGraph, num_sets: int, device=None, recycle: bool = True):
+        """``recycle``: from the second ``prune`` on, tell the library that these buffers still hold what the
+        previous call wrote (``dgn_options.recycle``), so that it zeroes only that instead of everything.
+        The outputs are then read-only for the caller; pass ``False`` to write to them between calls."""
         dev = graph.graph_mem.device if device is None else torch.device(device)
         P, T, G = graph.num_ops, graph.num_tensors, graph.num_graphs
+        self.recycle, self._scratch_defined = bool(recycle), False
         rc, sb = dgn_prune_workspace(graph.handle, num_sets)
         _check(rc, "dgn_prune_workspace")
         self.graph, self.num_sets = graph, num_sets
@@ -409,12 +414,18 @@ class PruneBuffers:
 
     def prune(self, tgt_rowptr, tgt_idx, options=None, stats=None, stream=None) -> int:
         """``tgt_rowptr`` / ``tgt_idx``: device int32 tensors. Returns the library's return code."""
+        if self.recycle and self._scratch_defined:
+            if options is None:
+                options = dgn_options()
+            options.recycle = 1
+        self._scratch_defined = True          # whatever happens, the library has written the scratch header
         return dgn_prune(self.graph.handle, self.num_sets, int(tgt_idx.numel()), tgt_rowptr, tgt_idx,
                          self.tensor_mask, self.op_mask, self.op_flag, self.kept_ops, self.kept_masks,
                          self.kept_count, self.per_query_count, self.scratch, self.scratch_bytes, options,
                          stats, stream)
 
     def keep_compact(self, tensor_mask_in, stream=None) -> int:
+        self._scratch_defined = False         # op_mask no longer goes with the log of the last prune
         return dgn_keep_compact(self.graph.handle, tensor_mask_in, self.op_mask, self.op_flag, self.kept_ops,
                                 self.kept_masks, self.kept_count, self.per_query_count, self.scratch,
                                 self.scratch_bytes, stream)
@@ -462,6 +473,7 @@ class BackwardPruneBuffers(PruneBuffers):
 
     def backward_prune(self, obj, wrt, options=None, stats=None, stream=None) -> int:
         """``obj`` / ``wrt``: device int32 tensors of equal length (the pairs)."""
+        self._scratch_defined = False         # the scratch buffer is laid out differently by this call
         return dgn_backward_prune(self.graph.handle, int(obj.numel()), obj, wrt, self.tensor_mask, self.op_mask,
                                   self.op_flag, self.kept_ops, self.kept_masks, self.kept_count,
                                   self.per_query_count, self.scratch, self.scratch_bytes, options, stats, stream)

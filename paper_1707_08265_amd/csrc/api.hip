@@ -34,6 +34,7 @@ constexpr int kMaxBatch = 512;              // launches enqueued between two sta
 constexpr int kTailLevels = 2;              // wide launches enqueued beyond the layout the previous prune needed
 constexpr int kSweepMinGraphs = 64;         // packed batches with at least this many graphs ...
 constexpr int64_t kSweepMaxGraphOps = 1 << 18;   // ... none larger than this use the per-graph sweep
+constexpr u64 kRecycleMagic = 0x44474e5f52435943ull;   // "DGN_RCYC"
 constexpr int kSmallLevel = 16384;           // levels expanding fewer entries than this decay the threshold faster
 constexpr int kDefaultDeferPercent = 85;
 constexpr int kDefaultStartShift = 1;       // deferral threshold starts at P >> 1 ...
@@ -139,6 +140,8 @@ struct PruneScratch {
     int pq_replicas;
     size_t pq_part_bytes;
     size_t db_bytes, opbits_bytes;
+    RecycleHeader *hdr;     // says which buffers hold the result of the last prune that kept a complete log
+    ColourLog log;          // tensors that prune coloured
     size_t bytes;
 };
 
@@ -160,6 +163,15 @@ PruneScratch prune_scratch(void *mem, int64_t P, int64_t T, int32_t G, int64_t m
 {
     Carver c(mem);
     PruneScratch S{};
+    // What one prune leaves for the next comes first, where no option moves it.  Log of coloured tensors: a
+    // quarter of T in all.  Recycling only pays while a prune colours a small part of the graph; one that
+    // overflows the log makes the next prune clear everything, as if there were no log.
+    S.hdr = c.take<RecycleHeader>(4);
+    S.log.cnt = c.take<SegCounter>(kMaxSeg);
+    int64_t lcap = T / (4 * kMaxSeg);
+    if (lcap < 4096) lcap = 4096;
+    S.log.seg_cap = (int32_t)lcap;
+    S.log.entries = c.take<int32_t>((size_t)kMaxSeg * (size_t)lcap);
     S.state = c.take<TravState>(2);
     S.ctr = c.take<TravCounters>(1);
     S.qg = queue_geometry(T, max_entries);
@@ -219,6 +231,7 @@ int check_options(const dgn_options *o)
     if (o->traversal < 0 || o->traversal > 2) return DGN_ERR_INVALID_ARG;
     if (o->defer_percent < 0 || o->defer_percent > 100) return DGN_ERR_INVALID_ARG;
     if (o->max_queue_entries < 0) return DGN_ERR_INVALID_ARG;
+    if (o->recycle < 0 || o->recycle > 1) return DGN_ERR_INVALID_ARG;
     if (o->defer_start_shift < 0 || o->defer_start_shift > 30) return DGN_ERR_INVALID_ARG;
     if (o->defer_floor_shift < 0 || o->defer_floor_shift > 30) return DGN_ERR_INVALID_ARG;
     return DGN_OK;
@@ -233,6 +246,7 @@ struct dgn_graph {
     int num_cus;
     bool topological;       // operator ids verified to be a topological order at build time
     int64_t max_graph_ops;  // largest graph of a packed batch (P for a single graph)
+    uint64_t serial;        // unique per handle in this process
     // Hints only, taken from the last prune of this graph; a wrong one costs launches that return at once,
     // or a second batch, and corrects itself.  Kept apart for full prunes [0] and incremental ones [1],
     // whose traversals look nothing alike.
@@ -275,6 +289,8 @@ int finish_build(dgn_graph *h, const GraphLayout &L, const int64_t *op_off_host,
     rc = error_bits_to_code(bits);
     if (rc) return rc;
     h->max_graph_ops = h->P;
+    static std::atomic<uint64_t> next_serial{1};
+    h->serial = next_serial.fetch_add(1, std::memory_order_relaxed);
     if (h->G > 1) {
         h->max_graph_ops = 0;
         for (int32_t i = 0; i < h->G; ++i)
@@ -524,12 +540,28 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     }
 
     // nothing marked yet: clear outputs, deferral markers and traversal state (an incremental call keeps
-    // M and K: they hold a fixed point that the new target bits only add to)
+    // M and K: they hold a fixed point that the new target bits only add to).  With `recycle` the scratch
+    // buffer may say that M, K and the kept list are still those of the previous prune of this graph: then
+    // only what that prune set is zeroed, and this prune keeps a log of what it colours for the next one.
     const bool incremental = options && options->incremental;
-    FillRegion clr[6] = {{M, incremental ? 0 : (size_t)g->T * 8}, {K, incremental ? 0 : (size_t)g->P * 8}, {S.DB, S.db_bytes},
-                         {S.state, 256 + sizeof(TravCounters)}, {per_query_count, pq_bytes},
-                         {S.pq_part, per_query_count ? S.pq_part_bytes : 0}};
-    DGN_HIP(launch_clear(clr, 6, s));
+    const bool sweep = !(options && options->traversal != 0) && g->G >= kSweepMinGraphs && g->topological &&
+                       g->max_graph_ops <= kSweepMaxGraphOps;
+    const bool recycle = options && options->recycle && !incremental && !sweep && g->P > 0;
+    const ColourLog log{recycle ? S.log.entries : nullptr, S.log.cnt, S.log.seg_cap};
+    const RecycleHeader want{kRecycleMagic, g->serial, M, K, kept_ops, kept_count, {0, 0}};
+    if (recycle) {
+        FillRegion big[3] = {{M, (size_t)g->T * 8}, {K, (size_t)g->P * 8}, {S.DB, S.db_bytes}};
+        DGN_HIP(launch_clear_or_reset(big, 3, S.hdr, want, reinterpret_cast<u64 *>(S.hdr + 1), S.log, kept_ops, kept_count, M, K, S.DB, s));
+        FillRegion small[5] = {{S.state, 256 + sizeof(TravCounters)}, {S.hdr, sizeof(RecycleHeader)}, {S.log.cnt, sizeof(SegCounter) * kMaxSeg},
+                               {per_query_count, pq_bytes}, {S.pq_part, per_query_count ? S.pq_part_bytes : 0}};
+        DGN_HIP(launch_clear(small, 5, s));
+        ++launches;
+    } else {
+        FillRegion clr[7] = {{M, incremental ? 0 : (size_t)g->T * 8}, {K, incremental ? 0 : (size_t)g->P * 8},
+                             {S.DB, S.db_bytes}, {S.state, 256 + sizeof(TravCounters)}, {S.hdr, 256},
+                             {per_query_count, pq_bytes}, {S.pq_part, per_query_count ? S.pq_part_bytes : 0}};
+        DGN_HIP(launch_clear(clr, 7, s));
+    }
     if (ev) DGN_HIP(hipEventRecord(ev[1], s));
     // deferral schedule: threshold on the producer id, starting at decay*P and decaying geometrically
     const int defer_percent = options && options->defer_percent ? options->defer_percent : kDefaultDeferPercent;
@@ -543,10 +575,8 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
         if (sch.theta_floor < 64) sch.theta_floor = 64;
         if (sch.theta0 < sch.theta_floor) sch.theta0 = 0;
     }
-    const bool sweep = !(options && options->traversal != 0) && g->G >= kSweepMinGraphs && g->topological &&
-                       g->max_graph_ops <= kSweepMaxGraphOps;
     DGN_HIP(launch_seed(g->v, num_sets, num_targets, tgt_rowptr, tgt_idx, M, S.state, S.ctr, sweep ? nullptr : S.q0, S.qg,
-                        sch.theta0, s));
+                        sch.theta0, log, s));
     if (ev) DGN_HIP(hipEventRecord(ev[2], s));
     launches += 2;
 
@@ -564,6 +594,9 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     ca.pq_part = S.pq_part;
     ca.pq_replicas = S.pq_replicas;
     ca.from_tensor_mask = options && options->recompute_keep;
+    ca.hdr = recycle ? S.hdr : nullptr;
+    ca.want = want;
+    ca.error = &S.state->error;
 
     void *pin = nullptr;
     rc = pinned_buffer(&pin);
@@ -620,7 +653,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     // batch ends with one, and that record is what is read back.
     bool last_was_narrow = false;
     auto narrow = [&]() -> int {
-        DGN_HIP(launch_narrow(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, narrow_cap, sch, trace, s));
+        DGN_HIP(launch_narrow(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, narrow_cap, sch, log, trace, s));
         ++launch_no; ++launches;
         last_was_narrow = true;
         return DGN_OK;
@@ -646,7 +679,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     }
     auto group = [&](int levels) -> int {            // `levels` wide launches, then the single-workgroup kernel
         for (int i = 0; i < levels; ++i) {
-            DGN_HIP(launch_level(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, grid, narrow_cap, sch, trace, s));
+            DGN_HIP(launch_level(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, grid, narrow_cap, sch, log, trace, s));
             ++launch_no; ++launches; ++level_launches;
         }
         last_was_narrow = false;
@@ -695,6 +728,12 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
         for (int r = 0; r < nr; ++r) g->hint_run_len[hk][r].store(hst->wide_runs[r], std::memory_order_relaxed);
         g->hint_runs[hk].store(nr, std::memory_order_relaxed);
     }
+    if (recycle && (hst->error & (kErrOverflow | kErrLogFull))) {
+        // the log is incomplete; a compaction enqueued ahead may have called it complete
+        FillRegion hz[1] = {{S.hdr, sizeof(RecycleHeader)}};
+        DGN_HIP(launch_clear(hz, 1, s));
+        ++launches;
+    }
     if (hst->error & kErrOverflow) {
         // A frontier queue overflowed and dropped entries: restore the fixed point with whole-graph
         // sweeps (each operator re-derives K from its outputs) until one of them changes nothing.
@@ -738,12 +777,18 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
         stats->max_frontier = (int64_t)hst->max_frontier;
         stats->launches = launches;
         stats->level_launches = level_launches;
+        if (recycle) {
+            u64 *found = reinterpret_cast<u64 *>(static_cast<char *>(pin) + 128);
+            DGN_HIP(hipMemcpyAsync(found, S.hdr + 1, sizeof(u64), hipMemcpyDeviceToHost, s));
+            DGN_HIP(hipStreamSynchronize(s));
+            stats->recycled = *found ? 1 : 0;
+        }
         if (ev) {
             for (int i = 0; i < 6; ++i) DGN_HIP(hipEventElapsedTime(&stats->phase_ms[i], ev[i], ev[i + 1]));
             DGN_HIP(hipEventElapsedTime(&stats->phase_ms[DGN_PHASE_TOTAL], ev[0], ev[6]));
         }
     }
-    return error_bits_to_code(hst->error & ~kErrOverflow);
+    return error_bits_to_code(hst->error & ~(kErrOverflow | kErrLogFull));
 }
 
 // Removal rule + compaction: K computed from tensor_mask_in (from_tensor_mask), or taken as it stands in op_mask.
@@ -800,6 +845,10 @@ int dgn_prune_words(const dgn_graph *g, int64_t num_sets, int64_t num_targets, c
     if (!tgt_rowptr) return DGN_ERR_NULL_PTR;
     const int64_t words = (num_sets + DGN_MAX_SETS - 1) / DGN_MAX_SETS;
     const size_t P = (size_t)g->P, T = (size_t)g->T;
+    dgn_options per_word{};
+    if (options) per_word = *options;
+    if (words > 1) per_word.recycle = 0;             // one scratch buffer serves every word: its log covers the last only
+    if (options) options = &per_word;
     dgn_stats total{};
     if (stats) total = *stats;
     total.levels = total.tensor_visits = total.launches = total.level_launches = 0;
@@ -887,6 +936,7 @@ int dgn_backward_prune(const dgn_graph *g, int32_t num_pairs, const int32_t *obj
     if (options) o1 = *options;
     o1.profile = 0;
     o1.incremental = 0;                              // stage one starts from nothing, in scratch memory
+    o1.recycle = 0;
     int rc = dgn_prune(g, num_pairs, num_pairs, S.tgt_rowptr, wrt, reinterpret_cast<uint64_t *>(S.B),
                        reinterpret_cast<uint64_t *>(S.KB), nullptr, S.kept, nullptr, S.kept_count, nullptr, scratch,
                        S.prune_bytes, &o1, stats, stream);

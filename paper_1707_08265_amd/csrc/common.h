@@ -20,6 +20,7 @@ enum : int32_t {
     kErrCsr = 4,          // row pointers not monotone / not ending at nnz
     kErrCrossGraph = 8,   // target or edge outside its own packed graph
     kErrOverflow = 16,    // internal: a frontier queue overflowed, the fix-up sweep must run
+    kErrLogFull = 32,     // internal: the log of coloured tensors overflowed, the next prune clears everything
 };
 
 // Adjacency of a built graph as the kernels see it (device pointers).
@@ -88,6 +89,22 @@ struct Schedule { float decay; int32_t theta0; int32_t theta_floor; int32_t smal
 // A frontier queue: S segments (power of two, <= kMaxSeg) of seg_cap entries each.
 struct QueueGeom { int32_t S; int32_t seg_cap; };
 static_assert(sizeof(TravState) == 128, "TravState is read back as 128 bytes");
+
+// Log of the tensors a prune coloured (each exactly once, when its mask left zero), in kMaxSeg segments of
+// seg_cap ids with one counter each.  entries == nullptr: no log is kept.
+struct ColourLog { int32_t *entries; SegCounter *cnt; int32_t seg_cap; };
+// What a prune that kept a complete log leaves in its scratch buffer: which buffers hold its result.  A later
+// prune that finds exactly this there zeroes only what the log and the kept list name.
+struct RecycleHeader {
+    u64 magic, graph_serial;
+    const void *M, *K, *kept_ops, *kept_count;
+    u64 pad[2];
+};
+__device__ __forceinline__ bool same_header(const RecycleHeader &a, const RecycleHeader &b)
+{
+    return a.magic == b.magic && a.graph_serial == b.graph_serial && a.M == b.M && a.K == b.K &&
+           a.kept_ops == b.kept_ops && a.kept_count == b.kept_count;
+}
 
 // ---- wave64 helpers ---------------------------------------------------------------------------
 __device__ __forceinline__ int lane_id() { return (int)__lane_id(); }
@@ -172,6 +189,12 @@ __device__ __forceinline__ uint32_t load_coherent(const uint32_t *p)
 // ---- launch wrappers (each returns a hipError_t; nothing synchronises) -------------------------
 struct FillRegion { void *ptr; size_t bytes; };   // ptr 8-byte aligned, bytes multiple of 8
 hipError_t launch_clear(const FillRegion *regions, int num_regions, hipStream_t s);
+// Zero `regions` (at most 8) -- unless *hdr equals `want`: then zero only M of the logged tensors and K and the
+// deferral marker of the kept operators (the buffers are as the prune that wrote the header left them).
+// found_out[0] = 1 when the header was found, else 0.
+hipError_t launch_clear_or_reset(const FillRegion *regions, int num_regions, const RecycleHeader *hdr,
+                                 const RecycleHeader &want, u64 *found_out, const ColourLog &log, const int32_t *kept_ops,
+                                 const int64_t *kept_count, u64 *M, u64 *K, uint8_t *DB, hipStream_t s);
 
 // out[i] = sum_{j<i} in[j], i = 0..n (n+1 outputs; out[n] = total).  in/out may alias when `in`
 // holds n+1 entries.  tmp: scratch of scan_tmp_bytes(n) bytes.
@@ -204,17 +227,17 @@ hipError_t launch_check_graph_ranges(const GraphView &g, int32_t *error, hipStre
 hipError_t launch_build_pinfo(const GraphView &g, int4 *pinfo, hipStream_t s);
 hipError_t launch_seed(const GraphView &g, int32_t Q, int64_t num_targets, const int32_t *tgt_rowptr,
                        const int32_t *tgt_idx, u64 *M, TravState *st, TravCounters *ctr, int32_t *q0,
-                       const QueueGeom &qg, int32_t theta0, hipStream_t s);
+                       const QueueGeom &qg, int32_t theta0, const ColourLog &log, hipStream_t s);
 // One wide level (whole chip); a frontier of at most narrow_cap entries is left to launch_narrow unless
 // deferred operators are waiting.  DB: deferred-operator markers, one byte per operator.
 hipError_t launch_level(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
                         const QueueGeom &qg, uint8_t *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
-                        const Schedule &sch, int4 *trace, hipStream_t s);
+                        const Schedule &sch, const ColourLog &log, int4 *trace, hipStream_t s);
 // One workgroup runs level after level while 0 < frontier <= narrow_cap and nothing is deferred.  It leaves no
 // tallies behind, so the record it writes is the state the host may read.
 hipError_t launch_narrow(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
                          const QueueGeom &qg, uint8_t *DB, u64 *M, u64 *K, int narrow_cap, const Schedule &sch,
-                         int4 *trace, hipStream_t s);
+                         const ColourLog &log, int4 *trace, hipStream_t s);
 // Packed batches of small graphs whose operator ids are a topological order: one wave per graph sweeps
 // its operators once, highest ids first (no frontier at all); fills K and, when pq is not NULL, the
 // per-graph per-set counts.
@@ -239,6 +262,9 @@ struct CompactArgs {
     u64 *opbits;             // [ceil(P/64)] scratch
     int32_t *block_counts;   // [num_tiles + 1] scratch
     bool from_tensor_mask;   // K := OR M[out] (true) or read K as accumulated by the traversal
+    RecycleHeader *hdr;      // when not NULL: the last pass writes `want` there if no error bit is set in *error
+    RecycleHeader want;
+    const int32_t *error;
 };
 // ev (may be NULL): three events recorded after the count, scan and scatter passes.
 hipError_t launch_keep_compact(const CompactArgs &a, hipStream_t s, hipEvent_t *ev = nullptr);

@@ -238,6 +238,8 @@ __global__ __launch_bounds__(kCThreads) void k_scatter(CompactArgs a)
     const int64_t n_words = ((int64_t)g.num_ops + 63) >> 6;
     const int64_t word_base = tile_base >> 6;
     const int base = a.block_counts[blockIdx.x];
+    // last pass of a prune: say in the scratch buffer which buffers now hold a result with a complete log
+    if (a.hdr && blockIdx.x == 0 && threadIdx.x == 0 && *a.error == 0) *a.hdr = a.want;
     if (a.block_counts[blockIdx.x + 1] == base) return;     // nothing kept in this tile (uniform)
 
     // exclusive prefix of the popcounts of this tile's 32 bitmap words (wave 0)

@@ -71,40 +71,63 @@ constexpr int kStageCap = 512;     // staged pushes per wave before a flush
 // Per-wave staging of next-frontier entries in LDS: slots are reserved with ballot + popcount, a
 // segment counter is touched once per flush instead of once per push.
 struct WaveStage {
-    int32_t *buf;     // this wave's kStageCap ints in LDS
+    int32_t *buf;     // this wave's kStageCap ints in LDS; bit 31 marks an entry that also goes to the log
     int cnt;          // wave-uniform
+    int nlog;         // marked entries among them, wave-uniform
 };
+constexpr int32_t kLogTag = (int32_t)0x80000000;
 
 struct Frontier {     // where one wave pushes
     int32_t *seg;     // start of the wave's segment in the output queue
     int32_t *cnt;     // that segment's push counter, global or LDS (may run past seg_cap: readers clamp)
     int32_t seg_cap;
     int32_t *error;   // sticky error word of the traversal state
+    int32_t *log;     // start of the wave's segment of the log of coloured tensors, or NULL: no log
+    int32_t *log_cnt; // that segment's counter
+    int32_t log_cap;
 };
 
 __device__ __forceinline__ void stage_flush(WaveStage &ws, const Frontier &f)
 {
     if (ws.cnt > 0) {
-        int base = 0;
-        if (lane_id() == 0) {
+        const int lane = lane_id();
+        int base = 0, lbase = 0;
+        if (lane == 0) {
             base = atomicAdd(f.cnt, ws.cnt);
             if (base + ws.cnt > f.seg_cap) atomicOr(f.error, kErrOverflow);   // (I3): fix-up sweep will follow
+            if (ws.nlog > 0) {
+                lbase = atomicAdd(f.log_cnt, ws.nlog);
+                if (lbase + ws.nlog > f.log_cap) atomicOr(f.error, kErrLogFull);
+            }
         }
         base = __builtin_amdgcn_readfirstlane(base);
-        for (int k = lane_id(); k < ws.cnt; k += kWave)
-            if (base + k < f.seg_cap) store_coherent(&f.seg[base + k], ws.buf[k]);   // read by other blocks
+        for (int k = lane; k < ws.cnt; k += kWave)
+            if (base + k < f.seg_cap) store_coherent(&f.seg[base + k], ws.buf[k] & ~kLogTag);   // read by other blocks
+        if (ws.nlog > 0) {
+            lbase = __builtin_amdgcn_readfirstlane(lbase);
+            for (int k0 = 0; k0 < ws.cnt; k0 += kWave) {
+                const int32_t v = k0 + lane < ws.cnt ? ws.buf[k0 + lane] : 0;
+                const u64 tm = ballot64(v < 0);
+                const int pos = lbase + __popcll(tm & lanemask_lt());
+                if (v < 0 && pos < f.log_cap) f.log[pos] = v & ~kLogTag;
+                lbase += __popcll(tm);
+            }
+        }
         ws.cnt = 0;
+        ws.nlog = 0;
     }
 }
 
-__device__ __forceinline__ void stage_push(WaveStage &ws, bool push, int32_t t, const Frontier &f)
+// `first`: this push is the one that coloured t (its mask was zero before), which happens once per tensor.
+__device__ __forceinline__ void stage_push(WaveStage &ws, bool push, bool first, int32_t t, const Frontier &f)
 {
     const u64 pm = ballot64(push);
     if (pm) {                                   // wave-uniform branch
         const int np = __popcll(pm);
         if (ws.cnt + np > kStageCap) stage_flush(ws, f);
-        if (push) ws.buf[ws.cnt + __popcll(pm & lanemask_lt())] = t;
+        if (push) ws.buf[ws.cnt + __popcll(pm & lanemask_lt())] = first ? (t | kLogTag) : t;
         ws.cnt += np;
+        ws.nlog += __popcll(ballot64(first));
     }
 }
 
@@ -127,14 +150,14 @@ __device__ __forceinline__ int32_t load_item(const int32_t *q, const QueueGeom &
 __global__ __launch_bounds__(256) void k_seed(GraphView g, int32_t Q, int64_t num_targets, int64_t num_sets_total,
                                                const int32_t *tgt_rowptr, const int32_t *tgt_idx, u64 *M,
                                                TravState *st, TravCounters *ctr, int32_t *q0, QueueGeom qg,
-                                               int32_t theta0)
+                                               int32_t theta0, ColourLog log)
 {
     const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (j == 0) {                                           // the record "before launch 0": nothing done yet
         st->slot[1].theta = theta0;
         st->slot[1].theta_hi = g.num_ops;
     }
-    bool push = false, bad = false, cross = false;
+    bool push = false, first = false, bad = false, cross = false;
     int32_t t = 0;
     if (j < num_targets) {
         // set s owns entries [tgt_rowptr[s], tgt_rowptr[s+1]): largest s with tgt_rowptr[s] <= j
@@ -156,6 +179,7 @@ __global__ __launch_bounds__(256) void k_seed(GraphView g, int32_t Q, int64_t nu
                 const u64 bit = (u64)1 << (lo % Q);
                 const u64 old = atomicOr(&M[t], bit);
                 push = (old & bit) == 0;                    // a duplicate target adds nothing new
+                first = old == 0;                           // this thread coloured t
             }
         }
     }
@@ -173,17 +197,31 @@ __global__ __launch_bounds__(256) void k_seed(GraphView g, int32_t Q, int64_t nu
             else overflow = true;
         }
     }
-    const int err = (bad ? kErrIdRange : 0) | (cross ? kErrCrossGraph : 0) | (overflow ? kErrOverflow : 0);
+    bool log_full = false;
+    const u64 fm = (q0 && log.entries) ? ballot64(first) : 0;
+    if (fm) {
+        const int lseg = (int)((j >> 6) & (kMaxSeg - 1));
+        int base = 0;
+        if (lane_id() == 0) base = atomicAdd(&log.cnt[lseg].v, __popcll(fm));
+        base = __builtin_amdgcn_readfirstlane(base);
+        const int pos = base + __popcll(fm & lanemask_lt());
+        if (first) {
+            if (pos < log.seg_cap) log.entries[(int64_t)lseg * log.seg_cap + pos] = t;
+            else log_full = true;
+        }
+    }
+    const int err = (bad ? kErrIdRange : 0) | (cross ? kErrCrossGraph : 0) | (overflow ? kErrOverflow : 0) |
+                    (log_full ? kErrLogFull : 0);
     if (err) atomicOr(&st->error, err);
 }
 
 hipError_t launch_seed(const GraphView &g, int32_t Q, int64_t num_targets, const int32_t *tgt_rowptr,
                        const int32_t *tgt_idx, u64 *M, TravState *st, TravCounters *ctr, int32_t *q0,
-                       const QueueGeom &qg, int32_t theta0, hipStream_t s)
+                       const QueueGeom &qg, int32_t theta0, const ColourLog &log, hipStream_t s)
 {
     const int64_t blocks = num_targets > 0 ? (num_targets + 255) / 256 : 1;
     hipLaunchKernelGGL(k_seed, dim3((unsigned)blocks), dim3(256), 0, s, g, Q, num_targets,
-                       (int64_t)g.num_graphs * Q, tgt_rowptr, tgt_idx, M, st, ctr, q0, qg, theta0);
+                       (int64_t)g.num_graphs * Q, tgt_rowptr, tgt_idx, M, st, ctr, q0, qg, theta0, log);
     return hipGetLastError();
 }
 
@@ -217,14 +255,15 @@ __device__ __forceinline__ void expand_edges(const GraphView &g, int eb, int deg
         const int o_eb = __shfl(eb, owner, kWave);
         const int o_excl = __shfl(excl, owner, kWave);
         const u64 b = shfl64(bits, owner);
-        bool push = false;
+        bool push = false, first = false;
         int32_t u = 0;
         if (ev) {
             u = g.in_idx[o_eb + (e - o_excl)];
             const u64 old = atomicOr(&M[u], b);             // (I2)
             push = (b & ~old) != 0;                         // (I3)
+            first = old == 0 && f.log != nullptr;
         }
-        stage_push(ws, push, u, f);
+        stage_push(ws, push, first, u, f);
     }
     __builtin_amdgcn_wave_barrier();
 }
@@ -391,7 +430,7 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
     const int s_blocks = p.split ? p.nb_s : p.nwork, s_first = p.split ? blk - p.nb_e : blk;
     const int cw = 1 << p.cw_log;
 
-    WaveStage ws{&sh.stage[wave][0], 0};
+    WaveStage ws{&sh.stage[wave][0], 0, 0};
     LevelCounters lc{0, -1};
     for (int base = e_first * kLevelThreads; do_entries && base < n; base += e_blocks * kLevelThreads) {
         const int i = base + threadIdx.x;
@@ -530,7 +569,8 @@ __device__ __forceinline__ void hand_on_frontier(TravCounters *ctr, int launch_n
 
 __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState *st, TravCounters *ctr, int launch_no,
                                                           int32_t *q0, int32_t *q1, QueueGeom qg, uint8_t *DB, u64 *M,
-                                                          u64 *K, int narrow_cap, Schedule sch, int4 *trace)
+                                                          u64 *K, int narrow_cap, Schedule sch, ColourLog log,
+                                                          int4 *trace)
 {
     __shared__ LevelShared sh;
     const int wave = threadIdx.x >> 6;
@@ -554,16 +594,18 @@ __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState 
     int32_t *qout = cur ? q0 : q1;
     const int mine = launch_no % 3;
     const int seg = (blockIdx.x * kLevelWaves + wave) & (qg.S - 1);
-    const Frontier f{qout + (int64_t)seg * qg.seg_cap, &ctr->cnt[mine][seg].v, qg.seg_cap, &st->error};
+    const int lseg = (blockIdx.x * kLevelWaves + wave) & (kMaxSeg - 1);
+    const Frontier f{qout + (int64_t)seg * qg.seg_cap, &ctr->cnt[mine][seg].v, qg.seg_cap, &st->error,
+                     log.entries ? log.entries + (int64_t)lseg * log.seg_cap : nullptr, &log.cnt[lseg].v, log.seg_cap};
     run_level(g, in, n, p, (int)blockIdx.x, qin, qg, f, DB, M, K, sh, ctr->cnt[mine]);
 }
 
 hipError_t launch_level(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
                         const QueueGeom &qg, uint8_t *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
-                        const Schedule &sch, int4 *trace, hipStream_t s)
+                        const Schedule &sch, const ColourLog &log, int4 *trace, hipStream_t s)
 {
     hipLaunchKernelGGL(k_level, dim3((unsigned)grid_blocks), dim3(kLevelThreads), 0, s, g, st, ctr, launch_no, q0, q1,
-                       qg, DB, M, K, narrow_cap, sch, trace);
+                       qg, DB, M, K, narrow_cap, sch, log, trace);
     return hipGetLastError();
 }
 
@@ -576,7 +618,8 @@ constexpr int kNarrowWaves = kNarrowThreads / kWave;
 
 __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravState *st, TravCounters *ctr, int launch_no,
                                                             int32_t *q0, int32_t *q1, QueueGeom qg, uint8_t *DB, u64 *M,
-                                                            u64 *K, int narrow_cap, Schedule sch, int4 *trace)
+                                                            u64 *K, int narrow_cap, Schedule sch, ColourLog log,
+                                                            int4 *trace)
 {
     __shared__ int32_t s_stage[kNarrowWaves][kStageCap];
     __shared__ int s_incl[kNarrowWaves][kWave];
@@ -591,7 +634,7 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
     int n = in.n;
     const bool ranges_left = in.deferred_seen && in.theta_hi > 0;   // then the wide kernel must go on
     const int lane = lane_id(), wave = threadIdx.x >> 6;
-    WaveStage ws{&s_stage[wave][0], 0};
+    WaveStage ws{&s_stage[wave][0], 0, 0};
     LevelCounters lc{0, -1};
     u64 visits = 0, maxf = 0;
     while (n > 0 && n <= narrow_cap && !ranges_left) {
@@ -599,7 +642,9 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
         __syncthreads();
         const int cur = level & 1;
         const int32_t *qin = cur ? q1 : q0;
-        const Frontier f{cur ? q0 : q1, &s_nout, qg.seg_cap, &st->error};   // everything goes to segment 0
+        const Frontier f{cur ? q0 : q1, &s_nout, qg.seg_cap, &st->error,    // everything goes to segment 0
+                         log.entries ? log.entries + (int64_t)wave * log.seg_cap : nullptr, &log.cnt[wave].v,
+                         log.seg_cap};
         for (int base = 0; base < n; base += kNarrowThreads) {
             const int i = base + threadIdx.x;
             const bool valid = i < n;
@@ -638,10 +683,10 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
 
 hipError_t launch_narrow(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
                          const QueueGeom &qg, uint8_t *DB, u64 *M, u64 *K, int narrow_cap, const Schedule &sch,
-                         int4 *trace, hipStream_t s)
+                         const ColourLog &log, int4 *trace, hipStream_t s)
 {
     hipLaunchKernelGGL(k_narrow, dim3(1), dim3(kNarrowThreads), 0, s, g, st, ctr, launch_no, q0, q1, qg, DB, M, K,
-                       narrow_cap, sch, trace);
+                       narrow_cap, sch, log, trace);
     return hipGetLastError();
 }
 
@@ -657,8 +702,8 @@ __global__ __launch_bounds__(kLevelThreads) void k_fix_sweep(GraphView g, u64 *M
     const int wave = threadIdx.x >> 6;
     if (threadIdx.x == 0) { s_sink = 0; s_err = 0; }
     __syncthreads();
-    WaveStage ws{&s_stage[wave][0], 0};
-    const Frontier f{nullptr, &s_sink, 0, &s_err};          // capacity 0: pushes are counted and dropped
+    WaveStage ws{&s_stage[wave][0], 0, 0};
+    const Frontier f{nullptr, &s_sink, 0, &s_err, nullptr, nullptr, 0};   // capacity 0: pushes are counted and dropped
     bool any = false;
     // descending ids: most of a sweep then sees its consumers' results (ids are a topological order)
     const int64_t tiles = ((int64_t)g.num_ops + kLevelThreads - 1) / kLevelThreads;

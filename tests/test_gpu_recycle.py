@@ -1,0 +1,157 @@
+"""GPU parity of repeated prunes that recycle their buffers (``dgn_options.recycle``): a prune that finds the
+previous result of the same graph in place zeroes only what that result set.  Every call is compared with the
+CPU oracle, bit for bit, with target sets that change from call to call so that a word left over from the
+previous result would show."""
+import numpy as np
+import pytest
+
+import graphgen as gg
+from test_gpu_parity import assert_same, oracle_prune
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dgn():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_1707_08265_amd as d
+    return d
+
+
+def _draws(g, tg, n):
+    """The config's own targets, then other draws: other tensors, other set sizes, from other parts of the graph."""
+    Q = tg.num_sets
+    out = [tg]
+    for i in range(1, n):
+        lo = (g.num_tensors * (i % 4)) // 5
+        out.append(gg.targets_range(9000 + 17 * i, Q, 1, 3 + 5 * (i % 3), lo, g.num_tensors))
+    return out
+
+
+def _prune(dgn, buf, t, **knobs):
+    import torch
+    st = dgn.dgn_stats()
+    opts = dgn.dgn_options(**knobs) if knobs else None
+    rc = buf.prune(torch.from_numpy(t.tgt_rowptr).cuda(), torch.from_numpy(t.tgt_idx).cuda(), options=opts, stats=st)
+    assert rc == 0, dgn.dgn_strerror(rc)
+    return st
+
+
+@pytest.mark.parametrize("k,scale", [(0, 1.0), (1, 0.2), (2, 0.02), (3, 0.02)])
+def test_recycled_prunes_match_the_oracle(dgn, oracle, k, scale):
+    g, tg = gg.config(k, scale)
+    dg = dgn.DeviceGraph.from_coo(g)
+    buf = dgn.PruneBuffers(dg, tg.num_sets)                 # recycles from its second call on
+    adj, _ = oracle_prune(oracle, g, tg)
+    seen = []
+    for i, t in enumerate(_draws(g, tg, 6)):
+        st = _prune(dgn, buf, t)
+        ref = oracle.forward_prune(adj, t.num_sets, t.tgt_rowptr, t.tgt_idx, g.num_graphs, g.graph_op_offsets)
+        assert_same(buf.to_host(), ref, f"cfg{k} call {i}")
+        seen.append(int(st.recycled))
+    print(f"cfg{k}: recycled per call {seen}", flush=True)
+    # call 0 has no flag, call 1 finds no log yet; from then on the previous result is found -- unless a prune
+    # coloured so much of the graph that its log did not hold it
+    assert seen[0] == 0 and seen[1] == 0
+    assert k == 0 or k == 2 or all(seen[2:]), seen
+
+
+def test_recycle_survives_schedule_knobs_and_the_standalone_keep_pass(dgn, oracle):
+    g, tg = gg.config(3, 0.02)
+    dg = dgn.DeviceGraph.from_coo(g)
+    buf = dgn.PruneBuffers(dg, tg.num_sets)
+    adj, _ = oracle_prune(oracle, g, tg)
+    knobs = [dict(), dict(), dict(defer_percent=60), dict(recompute_keep=1), dict(traversal=1), dict(traversal=2),
+             dict(defer_percent=95, defer_floor_shift=14), dict()]
+    for i, (t, kn) in enumerate(zip(_draws(g, tg, len(knobs)), knobs)):
+        st = _prune(dgn, buf, t, **kn)
+        ref = oracle.forward_prune(adj, t.num_sets, t.tgt_rowptr, t.tgt_idx, g.num_graphs, g.graph_op_offsets)
+        assert_same(buf.to_host(), ref, f"call {i} {kn}")
+        assert int(st.recycled) == (1 if i >= 2 else 0), (i, kn)
+
+
+def test_queue_overflow_and_incremental_calls_fall_back_to_a_full_clear(dgn, oracle):
+    """A prune whose frontier queue overflowed (its log misses what the fix-up sweeps coloured) and an
+    incremental prune (which keeps no log) must not be recycled from: the call after them clears everything."""
+    g, tg = gg.config(3, 0.02)
+    dg = dgn.DeviceGraph.from_coo(g)
+    buf = dgn.PruneBuffers(dg, tg.num_sets)
+    adj, _ = oracle_prune(oracle, g, tg)
+    ts = _draws(g, tg, 8)
+    plan = [dict(), dict(), dict(), dict(max_queue_entries=64), dict(), dict(), "incremental", dict(), dict()]
+    want = [0, 0, 1, 1, 0, 1, 0, 0, 1]
+    prev = None
+    for i, kn in enumerate(plan):
+        if kn == "incremental":                             # the same targets plus one more set's worth
+            t = prev
+            st = _prune(dgn, buf, t, incremental=1)
+        else:
+            t = ts[i % len(ts)]
+            st = _prune(dgn, buf, t, **kn)
+        ref = oracle.forward_prune(adj, t.num_sets, t.tgt_rowptr, t.tgt_idx, g.num_graphs, g.graph_op_offsets)
+        assert_same(buf.to_host(), ref, f"call {i} {kn}")
+        assert int(st.recycled) == want[i], (i, kn, int(st.recycled))
+        prev = t
+
+
+def test_a_prune_that_fills_the_log_is_not_recycled_from(dgn, oracle):
+    """Everything upstream of the last tensors of a long, thin graph: the prune colours most of the graph through
+    the few log segments the single-workgroup kernel writes, the log overflows, and the next call clears
+    everything; results stay exact throughout."""
+    g = gg.layered(200000, 31)                              # frontiers stay below the width of one workgroup
+    t_all = gg.targets_range(5, 1, 64, 64, g.num_tensors - 200, g.num_tensors)
+    t_few = gg.targets_range(6, 1, 2, 2, 16, 400)
+    dg = dgn.DeviceGraph.from_coo(g)
+    buf = dgn.PruneBuffers(dg, 1)
+    adj = oracle.build_adjacency(g.num_ops, g.num_tensors, g.in_op, g.in_tensor, g.out_op, g.out_tensor)
+    seq = [t_few, t_few, t_all, t_few, t_few, t_few]
+    seen = []
+    for i, t in enumerate(seq):
+        st = _prune(dgn, buf, t)
+        ref = oracle.forward_prune(adj, 1, t.tgt_rowptr, t.tgt_idx)
+        assert_same(buf.to_host(), ref, f"call {i}")
+        seen.append(int(st.recycled))
+    coloured = int(np.count_nonzero(oracle.forward_prune(adj, 1, t_all.tgt_rowptr, t_all.tgt_idx).tensor_mask))
+    print(f"recycled per call {seen}; the large prune colours {coloured} of {g.num_tensors} tensors", flush=True)
+    assert coloured > g.num_tensors // 4                    # more than the whole log holds
+    assert seen == [0, 0, 1, 0, 1, 1]                       # call 3 follows the prune that overflowed its log
+
+
+def test_other_buffers_or_another_graph_are_not_mistaken_for_the_previous_result(dgn, oracle):
+    import torch
+    g, tg = gg.config(3, 0.01)
+    g2, tg2 = gg.config(3, 0.011)
+    dg, dg2 = dgn.DeviceGraph.from_coo(g), dgn.DeviceGraph.from_coo(g2)
+    buf = dgn.PruneBuffers(dg, tg.num_sets)
+    adj, ref = oracle_prune(oracle, g, tg)
+    for _ in range(3):
+        st = _prune(dgn, buf, tg)
+    assert int(st.recycled) == 1
+    # the same scratch buffer with other output buffers: nothing to recycle, and the result is still right
+    other = dgn.PruneBuffers(dg, tg.num_sets)
+    other.scratch, other.scratch_bytes, other._scratch_defined = buf.scratch, buf.scratch_bytes, True
+    other.tensor_mask.fill_(-1)
+    other.op_mask.fill_(-1)
+    st = _prune(dgn, other, tg)
+    assert int(st.recycled) == 0
+    assert_same(other.to_host(), ref, "other buffers")
+    # the first buffers again: the header now names the other ones
+    buf.tensor_mask.fill_(-1)
+    buf.op_mask.fill_(-1)
+    st = _prune(dgn, buf, tg)
+    assert int(st.recycled) == 0
+    assert_same(buf.to_host(), ref, "first buffers again")
+    # another graph through a scratch buffer that is large enough for both
+    if g2.num_tensors >= g.num_tensors:
+        big = dgn.PruneBuffers(dg2, tg2.num_sets)
+        _prune(dgn, big, tg2)
+        _prune(dgn, big, tg2)
+        small = dgn.PruneBuffers(dg, tg.num_sets)
+        small.scratch, small.scratch_bytes, small._scratch_defined = big.scratch, big.scratch_bytes, True
+        small.tensor_mask.fill_(-1)
+        small.op_mask.fill_(-1)
+        st = _prune(dgn, small, tg)
+        assert int(st.recycled) == 0
+        assert_same(small.to_host(), ref, "scratch last used for another graph")
+    torch.cuda.synchronize()
