@@ -61,6 +61,8 @@ def main():
                     help="also time the CSR build on the same edges in shuffled COO order (every sort runs)")
     ap.add_argument("--prune-only", action="store_true",
                     help="skip the separately timed in-place, read-out and backward-prune legs (for profiling runs)")
+    ap.add_argument("--no-recycle", action="store_true",
+                    help="clear all of M and K in every step instead of only what the previous step set")
     ap.add_argument("--trace-levels", action="store_true", help="print the per-level trace of the last step")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -132,7 +134,7 @@ def main():
     del in_op, in_t, out_op, out_t
 
     # ---- prune --------------------------------------------------------------------------------
-    buf = d.PruneBuffers(dg, tg.num_sets)
+    buf = d.PruneBuffers(dg, tg.num_sets, recycle=not args.no_recycle)
     rowptr, idx = up(tg.tgt_rowptr), up(tg.tgt_idx)
     opts = d.dgn_options(profile=1, recompute_keep=1 if args.recompute_keep else 0,
                          defer_percent=args.defer_percent, traversal=1 if args.generic else 0,
@@ -156,10 +158,31 @@ def main():
     ms_per_step = elapsed / args.steps * 1e3
     gteps = E / (ms_per_step * 1e-3) / 1e9
     ph = dict(zip(d.PHASES, phases.mean(0)[:7].tolist()))
+    recycled = bool(st.recycled)
     log(f"prune: {ms_per_step:.3f} ms/step, {gteps:.1f} GTEPS; levels={st.levels} launches={st.launches} "
-        f"visits={st.tensor_visits} max_frontier={st.max_frontier}")
+        f"visits={st.tensor_visits} max_frontier={st.max_frontier} recycled={int(recycled)}")
     log("phase ms (HIP events, mean over timed steps): " + ", ".join(f"{k}={v:.3f}" for k, v in ph.items()))
 
+    # the same steps with every word of M and K cleared each time (what a caller gets who writes to the output
+    # buffers between calls, or prunes once)
+    full_clear = None
+    if recycled and not args.prune_only:
+        buf2 = d.PruneBuffers(dg, tg.num_sets, recycle=False)
+        for _ in range(2):
+            rc = buf2.prune(rowptr, idx, options=opts, stats=st)
+            assert rc == 0, d.dgn_strerror(rc)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for i in range(args.steps):
+            rc = buf2.prune(rowptr, idx, options=opts, stats=st)
+        torch.cuda.synchronize()
+        ms2 = (time.perf_counter() - t2) / args.steps * 1e3
+        assert rc == 0 and not st.recycled
+        full_clear = {"ms_per_step": round(ms2, 4), "gteps": round(E / (ms2 * 1e-3) / 1e9, 2)}
+        log(f"prune with a full clear per step: {ms2:.3f} ms/step, {full_clear['gteps']:.1f} GTEPS")
+        del buf2
+        rc = buf.prune(rowptr, idx, options=opts, stats=st)      # st describes the recycled path again
+        assert rc == 0
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -291,7 +314,8 @@ def main():
     # ---- algorithmic bytes per kernel launch (int32 ids, uint64 masks) ---------------------------
     levels = max(1, int(st.levels))
     alg = {
-        "k_clear": 8 * T + 8 * P,
+        # all of M and K, or (recycled buffers) the log and the kept list read, their M, K and marker words zeroed
+        "k_clear": (12 * T_c + 13 * P_k) if recycled else (8 * T + 8 * P),
         "k_level": (4 * T_c + 8 * P_k + 4 * E_k + 16 * E_k + 16 * P_k) / levels,
         "k_keep_count": (4 * P + 12 * g.nnz_out + 8 * P + P) if args.recompute_keep else (8 * P + P),
         "k_scatter": 12 * P_k,
@@ -373,7 +397,9 @@ def main():
         "config": {"workload": f"configs[{args.config}] {g.name}" + ("" if args.scale == 1.0 else f" x{args.scale}"),
                    "num_ops": P, "num_tensors": T, "nnz_in": g.nnz_in, "nnz_out": g.nnz_out,
                    "num_sets": tg.num_sets, "num_graphs": g.num_graphs,
-                   "keep_pass": "stand-alone" if args.recompute_keep else "fused into traversal"},
+                   "keep_pass": "stand-alone" if args.recompute_keep else "fused into traversal",
+                   "output_buffers": "recycled: each step zeroes what the previous step set" if recycled
+                                     else "every word of M and K cleared each step"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "phase_ms": {k: round(v, 4) for k, v in ph.items()},
@@ -383,6 +409,7 @@ def main():
         "readout": readout,
         "backward_prune": backward,
         "incremental_prune": incremental,
+        "full_clear_per_step": full_clear,
         "build_plus_prune_gteps": round(E / ((build_ms + ms_per_step) * 1e-3) / 1e9, 2),
         "result": {"kept_ops": P_k, "coloured_tensors": T_c, "kept_in_edges": E_k, "kept_out_edges": Eo_k,
                    "levels": int(st.levels), "tensor_visits": int(st.tensor_visits),

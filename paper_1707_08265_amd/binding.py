@@ -414,6 +414,9 @@ class PruneBuffers:
 
     def prune(self, tgt_rowptr, tgt_idx, options=None, stats=None, stream=None) -> int:
         """``tgt_rowptr`` / ``tgt_idx``: device int32 tensors. Returns the library's return code."""
+        if options is not None:
+            options = dgn_options.from_buffer_copy(options)      # the caller's object stays as it is
+            options.recycle = 0
         if self.recycle and self._scratch_defined:
             if options is None:
                 options = dgn_options()

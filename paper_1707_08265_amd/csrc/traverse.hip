@@ -276,15 +276,18 @@ struct LevelCounters {   // per-lane tallies, reduced by the caller
 // Tensor-side step: 64 frontier tensors held one per lane (valid lanes only).
 __device__ __forceinline__ void process_entries(const GraphView &g, bool valid, int32_t t, int32_t theta, uint8_t *DB,
                                                 u64 *M, u64 *K, int *s_incl, WaveStage &ws, const Frontier &f,
-                                                LevelCounters &lc)
+                                                LevelCounters &lc, bool lazy_mask)
 {
     u64 m = 0;
     bool active = false;
     int4 pi = make_int4(kNoProducer, 0, 0, 0);
     if (valid) {
         pi = g.pinfo[t];                                    // (o, eb, deg): producer record
-        const u64 mt = load_coherent(&M[t]);                // (I4): everything t holds right now (issued
-                                                            // together with the record: no dependency)
+        // (I4): everything t holds right now.  The single-workgroup kernel, bound by latency, issues the load
+        // together with the record; a wide level, where half the entries are deferred, only for the others
+        u64 mt = 0;
+        if (!lazy_mask) mt = load_coherent(&M[t]);
+        else if (!(pi.x >= 0 && pi.x < theta)) mt = load_coherent(&M[t]);
         if (pi.x >= 0 && pi.x < theta) {                    // (I5): wait for the threshold to pass o
             DB[pi.x] = 1;          // a byte per operator, no atomic; read by a later launch, when theta has passed o
             lc.max_deferred_key = max(lc.max_deferred_key, pi.x);
@@ -436,7 +439,7 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
         const int i = base + threadIdx.x;
         const bool valid = i < n;
         const int32_t t = valid ? load_item(qin, qg, sh.pref, i) : 0;
-        process_entries(g, valid, t, in.theta, DB, M, K, &sh.incl[wave][0], ws, f, lc);
+        process_entries(g, valid, t, in.theta, DB, M, K, &sh.incl[wave][0], ws, f, lc, true);
     }
     // expand the bitmap words of the newly opened range into dense operator lists, 64 per step
     for (int c = s_first * kLevelWaves + wave; do_scan && c < p.chunks; c += s_blocks * kLevelWaves) {
@@ -650,7 +653,7 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
             const bool valid = i < n;
             const int32_t t = valid ? load_item(qin, qg, s_pref, i) : 0;
             // threshold 0: a small frontier is latency bound, so nothing is gained by deferring
-            process_entries(g, valid, t, 0, DB, M, K, &s_incl[wave][0], ws, f, lc);
+            process_entries(g, valid, t, 0, DB, M, K, &s_incl[wave][0], ws, f, lc, false);
         }
         stage_flush(ws, f);
         // the block's queue stores must have completed before they are re-read (with cache-bypassing
