@@ -136,7 +136,9 @@ def main():
     # ---- prune --------------------------------------------------------------------------------
     buf = d.PruneBuffers(dg, tg.num_sets, recycle=not args.no_recycle)
     rowptr, idx = up(tg.tgt_rowptr), up(tg.tgt_idx)
-    opts = d.dgn_options(profile=1, recompute_keep=1 if args.recompute_keep else 0,
+    # timed steps: HIP events around the traversal only (every event between two kernels idles the stream for
+    # a few microseconds); the other phases are timed in a few extra steps after the timed region
+    opts = d.dgn_options(profile=2, recompute_keep=1 if args.recompute_keep else 0,
                          defer_percent=args.defer_percent, traversal=1 if args.generic else 0,
                          defer_start_shift=args.defer_start_shift, defer_floor_shift=args.defer_floor_shift)
     st = d.dgn_stats()
@@ -157,11 +159,21 @@ def main():
     assert rc == 0, d.dgn_strerror(rc)
     ms_per_step = elapsed / args.steps * 1e3
     gteps = E / (ms_per_step * 1e-3) / 1e9
-    ph = dict(zip(d.PHASES, phases.mean(0)[:7].tolist()))
     recycled = bool(st.recycled)
+    level_launches = int(st.level_launches)
+    opts.profile = 1
+    phases_all = np.zeros((5, 8))
+    for i in range(5):
+        rc = buf.prune(rowptr, idx, options=opts, stats=st)
+        assert rc == 0, d.dgn_strerror(rc)
+        phases_all[i] = list(st.phase_ms)
+    opts.profile = 2
+    ph = dict(zip(d.PHASES, phases_all.mean(0)[:7].tolist()))
+    ph["traverse"] = float(phases.mean(0)[2])              # from the timed steps themselves
     log(f"prune: {ms_per_step:.3f} ms/step, {gteps:.1f} GTEPS; levels={st.levels} launches={st.launches} "
         f"visits={st.tensor_visits} max_frontier={st.max_frontier} recycled={int(recycled)}")
-    log("phase ms (HIP events, mean over timed steps): " + ", ".join(f"{k}={v:.3f}" for k, v in ph.items()))
+    log("phase ms (HIP events; traverse: mean over the timed steps, the others: 5 extra steps with every phase "
+        "bracketed): " + ", ".join(f"{k}={v:.3f}" for k, v in ph.items()))
 
     # the same steps with every word of M and K cleared each time (what a caller gets who writes to the output
     # buffers between calls, or prunes once)
@@ -322,7 +334,7 @@ def main():
     }
     dur_ms = {
         "k_clear": ph["clear"],
-        "k_level": ph["traverse"] / max(1, int(st.level_launches)),
+        "k_level": ph["traverse"] / max(1, level_launches),
         "k_keep_count": ph["count"],
         "k_scatter": ph["scatter"],
     }
@@ -335,7 +347,7 @@ def main():
         "bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
         "traffic": measured_traffic(dominant) if (args.config == 3 and args.scale == 1.0 and not args.recompute_keep) else None,
-        "launch_ms": round(dur_ms[dominant], 4), "launches_per_step": 1 if dominant != "k_level" else int(st.level_launches),
+        "launch_ms": round(dur_ms[dominant], 4), "launches_per_step": 1 if dominant != "k_level" else level_launches,
         "per_kernel_GBs": {k: round(alg[k] / (dur_ms[k] * 1e-3) / 1e9, 1) if dur_ms[k] > 0 else None for k in alg},
         "whole_path_algorithmic_GBs": round(b_alg_total / (ms_per_step * 1e-3) / 1e9, 1),
         "whole_path_frac": round(b_alg_total / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),

@@ -93,8 +93,11 @@ typedef struct dgn_options {
     int32_t traversal;       /* 0 = automatic; 1 = one kernel launch per frontier level, nothing else;
                                 2 = one launch per wide level plus the single-workgroup kernel for
                                 small frontiers (what 0 chooses for a single graph)               */
-    int32_t profile;         /* prune: bracket each phase with HIP events on `stream` and report
-                                the elapsed times in dgn_stats.phase_ms (needs stats != NULL)      */
+    int32_t profile;         /* prune: 1 = bracket each phase with HIP events on `stream` and report
+                                the elapsed times in dgn_stats.phase_ms (needs stats != NULL); an
+                                event between two kernels leaves the stream idle for a few
+                                microseconds, so 2 = only the two events around the traversal
+                                (phase_ms[DGN_PHASE_TRAVERSE] alone is filled)                      */
     int32_t defer_percent;   /* prune: geometric decay (percent, 1..99) of the producer-id threshold
                                 below which frontier entries wait for more bits; 100 = never defer,
                                 0 = library default.  A schedule only: results do not depend on it */

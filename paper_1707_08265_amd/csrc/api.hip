@@ -232,6 +232,7 @@ int check_options(const dgn_options *o)
     if (o->defer_percent < 0 || o->defer_percent > 100) return DGN_ERR_INVALID_ARG;
     if (o->max_queue_entries < 0) return DGN_ERR_INVALID_ARG;
     if (o->recycle < 0 || o->recycle > 1) return DGN_ERR_INVALID_ARG;
+    if (o->profile < 0 || o->profile > 2) return DGN_ERR_INVALID_ARG;
     if (o->defer_start_shift < 0 || o->defer_start_shift > 30) return DGN_ERR_INVALID_ARG;
     if (o->defer_floor_shift < 0 || o->defer_floor_shift > 30) return DGN_ERR_INVALID_ARG;
     return DGN_OK;
@@ -532,11 +533,17 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     u64 *K = reinterpret_cast<u64 *>(op_mask);
     const size_t pq_bytes = per_query_count ? sizeof(int64_t) * 64 * (size_t)(g->G > 1 ? g->G : 1) : 0;
     int64_t launches = 0, level_launches = 0;
-    hipEvent_t *ev = nullptr;       // 0 start, 1 cleared, 2 seeded, 3 traversed, 4 counted, 5 scanned, 6 scattered
+    // 0 start, 1 cleared, 2 seeded, 3 traversed, 4 counted, 5 scanned, 6 scattered.  An event between two
+    // kernels costs a few microseconds of idle stream, so profile = 2 records only the two around the traversal.
+    hipEvent_t *ev = nullptr;
+    hipEvent_t *ev_trav = nullptr;
     if (options && options->profile && stats) {
-        rc = profile_events(&ev);
+        rc = profile_events(&ev_trav);
         if (rc) return rc;
-        DGN_HIP(hipEventRecord(ev[0], s));
+        if (options->profile == 1) {
+            ev = ev_trav;
+            DGN_HIP(hipEventRecord(ev[0], s));
+        }
     }
 
     // nothing marked yet: clear outputs, deferral markers and traversal state (an incremental call keeps
@@ -577,7 +584,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     }
     DGN_HIP(launch_seed(g->v, num_sets, num_targets, tgt_rowptr, tgt_idx, M, S.state, S.ctr, sweep ? nullptr : S.q0, S.qg,
                         sch.theta0, log, s));
-    if (ev) DGN_HIP(hipEventRecord(ev[2], s));
+    if (ev_trav) DGN_HIP(hipEventRecord(ev_trav[2], s));
     launches += 2;
 
     CompactArgs ca{};
@@ -608,7 +615,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     if (sweep) {
         DGN_HIP(launch_sweep_graphs(g->v, M, K, ca.from_tensor_mask ? nullptr : per_query_count, s));
         ++launches;
-        if (ev) DGN_HIP(hipEventRecord(ev[3], s));
+        if (ev_trav) DGN_HIP(hipEventRecord(ev_trav[3], s));
         if (!ca.from_tensor_mask) ca.per_query_count = nullptr;   // already written by the sweep
         DGN_HIP(launch_keep_compact(ca, s, ev ? ev + 4 : nullptr));
         launches += 3 + (g->G > 1);
@@ -625,6 +632,8 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
             if (ev) {
                 for (int i = 0; i < 6; ++i) DGN_HIP(hipEventElapsedTime(&stats->phase_ms[i], ev[i], ev[i + 1]));
                 DGN_HIP(hipEventElapsedTime(&stats->phase_ms[DGN_PHASE_TOTAL], ev[0], ev[6]));
+            } else if (ev_trav) {
+                DGN_HIP(hipEventElapsedTime(&stats->phase_ms[DGN_PHASE_TRAVERSE], ev_trav[2], ev_trav[3]));
             }
         }
         return error_bits_to_code(hst->error & ~kErrOverflow);
@@ -712,7 +721,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
         }
         ++batch;
         if (first && speculate) {
-            if (ev) DGN_HIP(hipEventRecord(ev[3], s));
+            if (ev_trav) DGN_HIP(hipEventRecord(ev_trav[3], s));
             DGN_HIP(launch_keep_compact(ca, s, ev ? ev + 4 : nullptr));
             launches += 3 + (g->G > 1);
             compacted = true;
@@ -755,7 +764,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
             DGN_HIP(launch_clear(pq, 2, s));
             ++launches;
         }
-        if (ev) DGN_HIP(hipEventRecord(ev[3], s));
+        if (ev_trav) DGN_HIP(hipEventRecord(ev_trav[3], s));
         DGN_HIP(launch_keep_compact(ca, s, ev ? ev + 4 : nullptr));
         launches += 3 + (g->G > 1);
         DGN_HIP(hipStreamSynchronize(s));    // outputs are complete (and the phase events recorded) on return
@@ -786,6 +795,8 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
         if (ev) {
             for (int i = 0; i < 6; ++i) DGN_HIP(hipEventElapsedTime(&stats->phase_ms[i], ev[i], ev[i + 1]));
             DGN_HIP(hipEventElapsedTime(&stats->phase_ms[DGN_PHASE_TOTAL], ev[0], ev[6]));
+        } else if (ev_trav) {
+            DGN_HIP(hipEventElapsedTime(&stats->phase_ms[DGN_PHASE_TRAVERSE], ev_trav[2], ev_trav[3]));
         }
     }
     return error_bits_to_code(hst->error & ~(kErrOverflow | kErrLogFull));

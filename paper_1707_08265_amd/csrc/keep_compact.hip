@@ -192,40 +192,69 @@ __global__ __launch_bounds__(256) void k_reduce_pq(CompactArgs a)
     if (lane == 0) a.per_query_count[i] = v;
 }
 
+constexpr int kFoldPqOutputs = 256;      // up to this many per-set counters are summed by the scan kernel itself
+
 // Single workgroup: exclusive scan of the tile counts in place, total -> counts[m] and kept_count[0].
-// 4096 entries per round (four consecutive ones per thread).
-__global__ __launch_bounds__(1024) void k_scan_tiles(int32_t *counts, int64_t m, int64_t *kept_count)
+// Every thread owns one contiguous run of counts: it sums the run, the block scans the 1024 sums, the thread
+// walks its run again and writes the prefixes -- two rounds of independent loads whatever m is.  With few
+// per-set counters the kernel also sums their replicas (one wave per counter), which saves a launch.
+__global__ __launch_bounds__(1024) void k_scan_tiles(int32_t *counts, int64_t m, int64_t *kept_count, CompactArgs a,
+                                                     bool fold_pq)
 {
-    __shared__ int wtot[2][16];
+    __shared__ int wtot[16];
     const int lane = lane_id(), wave = threadIdx.x >> 6;
-    int carry = 0, buf = 0;
-    for (int64_t base = 0; base < m; base += 4096, buf ^= 1) {
-        const int64_t i = base + (int64_t)threadIdx.x * 4;
-        int x[4];
+    if (fold_pq) {
+        const int n = 64 * a.g.num_graphs;
+        for (int i = wave; i < n; i += 16) {
+            long long v = 0;
+            if (lane < a.pq_replicas) v = a.pq_part[((int64_t)lane * n + i) * kPqStride];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) x[c] = i + c < m ? counts[i + c] : 0;
-        const int sum = x[0] + x[1] + x[2] + x[3];
-        const int incl = wave_incl_scan(sum);
-        if (lane == kWave - 1) wtot[buf][wave] = incl;
-        __syncthreads();                      // double-buffered totals: one barrier per round is enough
-        int woff = 0, tot = 0;
-#pragma unroll
-        for (int w = 0; w < 16; ++w) {
-            const int c = wtot[buf][w];
-            if (w < wave) woff += c;
-            tot += c;
+            for (int d = kWave / 2; d >= 1; d >>= 1) v += __shfl_xor(v, d, kWave);
+            if (lane == 0) a.per_query_count[i] = v;
         }
-        int run = carry + woff + incl - sum;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            if (i + c < m) counts[i + c] = run;
-            run += x[c];
+    }
+    // runs are a multiple of four counts long and start 16-byte aligned: int4 loads, all of them in flight at once
+    const int64_t per = (((m + 1023) / 1024) + 3) & ~(int64_t)3;
+    const int64_t lo = (int64_t)threadIdx.x * per;
+    const int64_t hi = lo + per < m ? lo + per : m;
+    int sum = 0;
+#pragma unroll 4
+    for (int64_t i = lo; i < hi; i += 4) {
+        if (i + 4 <= m) {
+            const int4 v = *reinterpret_cast<const int4 *>(counts + i);
+            sum += v.x + v.y + v.z + v.w;
+        } else {
+            for (int64_t j = i; j < m; ++j) sum += counts[j];
         }
-        carry += tot;
+    }
+    const int incl = wave_incl_scan(sum);
+    if (lane == kWave - 1) wtot[wave] = incl;
+    __syncthreads();
+    int woff = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+        const int c = wtot[w];
+        if (w < wave) woff += c;
+        tot += c;
+    }
+    int run = woff + incl - sum;
+#pragma unroll 4
+    for (int64_t i = lo; i < hi; i += 4) {
+        if (i + 4 <= m) {
+            const int4 v = *reinterpret_cast<const int4 *>(counts + i);
+            *reinterpret_cast<int4 *>(counts + i) = make_int4(run, run + v.x, run + v.x + v.y, run + v.x + v.y + v.z);
+            run += v.x + v.y + v.z + v.w;
+        } else {
+            for (int64_t j = i; j < m; ++j) {
+                const int c = counts[j];
+                counts[j] = run;
+                run += c;
+            }
+        }
     }
     if (threadIdx.x == 0) {
-        counts[m] = carry;
-        kept_count[0] = carry;
+        counts[m] = tot;
+        kept_count[0] = tot;
     }
 }
 
@@ -291,10 +320,12 @@ hipError_t launch_keep_compact(const CompactArgs &a, hipStream_t s, hipEvent_t *
         else
             hipLaunchKernelGGL(k_keep_count<false>, dim3((unsigned)count_grid), dim3(kCThreads), 0, s, a);
     }
-    if (a.per_query_count && a.pq_part)
+    const bool reduce_pq = a.per_query_count && a.pq_part;
+    const bool fold_pq = reduce_pq && 64 * a.g.num_graphs <= kFoldPqOutputs;
+    if (reduce_pq && !fold_pq)
         hipLaunchKernelGGL(k_reduce_pq, dim3((unsigned)((64 * a.g.num_graphs + 3) / 4)), dim3(256), 0, s, a);
     if (ev) (void)hipEventRecord(ev[0], s);
-    hipLaunchKernelGGL(k_scan_tiles, dim3(1), dim3(1024), 0, s, a.block_counts, tiles, a.kept_count);
+    hipLaunchKernelGGL(k_scan_tiles, dim3(1), dim3(1024), 0, s, a.block_counts, tiles, a.kept_count, a, fold_pq);
     if (ev) (void)hipEventRecord(ev[1], s);
     if (tiles > 0) hipLaunchKernelGGL(k_scatter, dim3((unsigned)tiles), dim3(kCThreads), 0, s, a);
     if (a.g.num_graphs > 1)
