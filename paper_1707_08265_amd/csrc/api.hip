@@ -133,6 +133,7 @@ struct PruneScratch {
     int32_t *q0, *q1;       // frontier queues: qg.S segments of qg.seg_cap tensor ids each
     QueueGeom qg;
     uint8_t *DB;            // deferred-operator markers, one byte per operator
+    uint8_t *flagbuf;       // keep flags (a byte per operator) when the caller's op_flag cannot take them
     u64 *opbits;
     int32_t *block_counts;
     int4 *trace;            // per-level trace records (profiling only)
@@ -181,6 +182,7 @@ PruneScratch prune_scratch(void *mem, int64_t P, int64_t T, int32_t G, int64_t m
     const size_t obw = (size_t)((P + 63) / 64);
     S.DB = c.take<uint8_t>(obw * 64);         // a whole number of 64-operator words, so chunk loads stay inside
     S.db_bytes = obw * 64;
+    S.flagbuf = c.take<uint8_t>(obw * 64);
     S.opbits = c.take<u64>(obw);
     S.opbits_bytes = obw * 8;
     S.block_counts = c.take<int32_t>((P + kCompactTile - 1) / kCompactTile + 1);
@@ -554,20 +556,30 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     const bool sweep = !(options && options->traversal != 0) && g->G >= kSweepMinGraphs && g->topological &&
                        g->max_graph_ops <= kSweepMaxGraphOps;
     const bool recycle = options && options->recycle && !incremental && !sweep && g->P > 0;
+    // The traversal sets a byte for every operator whose K leaves zero, which lets the count pass read P bytes
+    // and the K of the kept operators instead of all of K.  The bytes are the caller's op_flag when that can be
+    // cleared in whole 8-byte words, else a scratch array.  (Not for the per-graph sweep, which writes K
+    // without atomics and finds nothing out about "first"; not for incremental calls, whose K comes from outside.)
+    const bool use_flags = !sweep && !incremental && !(options && options->recompute_keep);
+    uint8_t *flags = (op_flag && ((uintptr_t)op_flag & 7) == 0 && g->P % 8 == 0) ? op_flag : S.flagbuf;
+    const size_t flag_bytes = flags == op_flag ? (size_t)g->P : S.db_bytes;
     const ColourLog log{recycle ? S.log.entries : nullptr, S.log.cnt, S.log.seg_cap};
-    const RecycleHeader want{kRecycleMagic, g->serial, M, K, kept_ops, kept_count, {0, 0}};
+    const RecycleHeader want{kRecycleMagic, g->serial, M, K, kept_ops, kept_count, flags, 0};
     if (recycle) {
-        FillRegion big[3] = {{M, (size_t)g->T * 8}, {K, (size_t)g->P * 8}, {S.DB, S.db_bytes}};
-        DGN_HIP(launch_clear_or_reset(big, 3, S.hdr, want, reinterpret_cast<u64 *>(S.hdr + 1), S.log, kept_ops, kept_count, M, K, S.DB, s));
+        FillRegion big[4] = {{M, (size_t)g->T * 8}, {K, (size_t)g->P * 8}, {S.DB, S.db_bytes},
+                             {flags, use_flags ? flag_bytes : 0}};
+        DGN_HIP(launch_clear_or_reset(big, 4, S.hdr, want, reinterpret_cast<u64 *>(S.hdr + 1), S.log, kept_ops, kept_count, M, K,
+                                      S.DB, flags, s));
         FillRegion small[5] = {{S.state, 256 + sizeof(TravCounters)}, {S.hdr, sizeof(RecycleHeader)}, {S.log.cnt, sizeof(SegCounter) * kMaxSeg},
                                {per_query_count, pq_bytes}, {S.pq_part, per_query_count ? S.pq_part_bytes : 0}};
         DGN_HIP(launch_clear(small, 5, s));
         ++launches;
     } else {
-        FillRegion clr[7] = {{M, incremental ? 0 : (size_t)g->T * 8}, {K, incremental ? 0 : (size_t)g->P * 8},
+        FillRegion clr[8] = {{M, incremental ? 0 : (size_t)g->T * 8}, {K, incremental ? 0 : (size_t)g->P * 8},
                              {S.DB, S.db_bytes}, {S.state, 256 + sizeof(TravCounters)}, {S.hdr, 256},
-                             {per_query_count, pq_bytes}, {S.pq_part, per_query_count ? S.pq_part_bytes : 0}};
-        DGN_HIP(launch_clear(clr, 7, s));
+                             {per_query_count, pq_bytes}, {S.pq_part, per_query_count ? S.pq_part_bytes : 0},
+                             {flags, use_flags ? flag_bytes : 0}};
+        DGN_HIP(launch_clear(clr, 8, s));
     }
     if (ev) DGN_HIP(hipEventRecord(ev[1], s));
     // deferral schedule: threshold on the producer id, starting at decay*P and decaying geometrically
@@ -601,6 +613,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     ca.pq_part = S.pq_part;
     ca.pq_replicas = S.pq_replicas;
     ca.from_tensor_mask = options && options->recompute_keep;
+    ca.flag_in = use_flags ? flags : nullptr;
     ca.hdr = recycle ? S.hdr : nullptr;
     ca.want = want;
     ca.error = &S.state->error;
@@ -662,7 +675,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     // batch ends with one, and that record is what is read back.
     bool last_was_narrow = false;
     auto narrow = [&]() -> int {
-        DGN_HIP(launch_narrow(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, narrow_cap, sch, log, trace, s));
+        DGN_HIP(launch_narrow(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, flags, M, K, narrow_cap, sch, log, trace, s));
         ++launch_no; ++launches;
         last_was_narrow = true;
         return DGN_OK;
@@ -688,7 +701,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     }
     auto group = [&](int levels) -> int {            // `levels` wide launches, then the single-workgroup kernel
         for (int i = 0; i < levels; ++i) {
-            DGN_HIP(launch_level(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, M, K, grid, narrow_cap, sch, log, trace, s));
+            DGN_HIP(launch_level(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, flags, M, K, grid, narrow_cap, sch, log, trace, s));
             ++launch_no; ++launches; ++level_launches;
         }
         last_was_narrow = false;
@@ -751,7 +764,7 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
         for (;;) {
             FillRegion cz[1] = {{changed, 8}};
             DGN_HIP(launch_clear(cz, 1, s));
-            DGN_HIP(launch_fix_sweep(g->v, M, K, changed, grid, s));
+            DGN_HIP(launch_fix_sweep(g->v, M, K, flags, changed, grid, s));
             ++launches;
             DGN_HIP(hipMemcpyAsync(pin, S.state, sizeof(TravState), hipMemcpyDeviceToHost, s));
             DGN_HIP(hipStreamSynchronize(s));

@@ -97,13 +97,13 @@ struct ColourLog { int32_t *entries; SegCounter *cnt; int32_t seg_cap; };
 // prune that finds exactly this there zeroes only what the log and the kept list name.
 struct RecycleHeader {
     u64 magic, graph_serial;
-    const void *M, *K, *kept_ops, *kept_count;
-    u64 pad[2];
+    const void *M, *K, *kept_ops, *kept_count, *flags;
+    u64 pad;
 };
 __device__ __forceinline__ bool same_header(const RecycleHeader &a, const RecycleHeader &b)
 {
     return a.magic == b.magic && a.graph_serial == b.graph_serial && a.M == b.M && a.K == b.K &&
-           a.kept_ops == b.kept_ops && a.kept_count == b.kept_count;
+           a.kept_ops == b.kept_ops && a.kept_count == b.kept_count && a.flags == b.flags;
 }
 
 // ---- wave64 helpers ---------------------------------------------------------------------------
@@ -140,6 +140,7 @@ __device__ __forceinline__ u64 wave_or(u64 v)
     return v;
 }
 __device__ __forceinline__ u64 shfl64(u64 v, int src) { return (u64)__shfl((long long)v, src, kWave); }
+__device__ __forceinline__ u64 shfl_xor64(u64 v, int mask) { return (u64)__shfl_xor((long long)v, mask, kWave); }
 
 // Lanes hold 64-bit rows of a 64x64 bit matrix (row = lane); returns its transpose (lane q receives
 // bit q of every lane's word, bit i coming from lane i).  Six butterfly steps.
@@ -194,7 +195,7 @@ hipError_t launch_clear(const FillRegion *regions, int num_regions, hipStream_t 
 // found_out[0] = 1 when the header was found, else 0.
 hipError_t launch_clear_or_reset(const FillRegion *regions, int num_regions, const RecycleHeader *hdr,
                                  const RecycleHeader &want, u64 *found_out, const ColourLog &log, const int32_t *kept_ops,
-                                 const int64_t *kept_count, u64 *M, u64 *K, uint8_t *DB, hipStream_t s);
+                                 const int64_t *kept_count, u64 *M, u64 *K, uint8_t *DB, uint8_t *flags, hipStream_t s);
 
 // out[i] = sum_{j<i} in[j], i = 0..n (n+1 outputs; out[n] = total).  in/out may alias when `in`
 // holds n+1 entries.  tmp: scratch of scan_tmp_bytes(n) bytes.
@@ -231,19 +232,19 @@ hipError_t launch_seed(const GraphView &g, int32_t Q, int64_t num_targets, const
 // One wide level (whole chip); a frontier of at most narrow_cap entries is left to launch_narrow unless
 // deferred operators are waiting.  DB: deferred-operator markers, one byte per operator.
 hipError_t launch_level(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
-                        const QueueGeom &qg, uint8_t *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
+                        const QueueGeom &qg, uint8_t *DB, uint8_t *flags, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
                         const Schedule &sch, const ColourLog &log, int4 *trace, hipStream_t s);
 // One workgroup runs level after level while 0 < frontier <= narrow_cap and nothing is deferred.  It leaves no
 // tallies behind, so the record it writes is the state the host may read.
 hipError_t launch_narrow(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
-                         const QueueGeom &qg, uint8_t *DB, u64 *M, u64 *K, int narrow_cap, const Schedule &sch,
+                         const QueueGeom &qg, uint8_t *DB, uint8_t *flags, u64 *M, u64 *K, int narrow_cap, const Schedule &sch,
                          const ColourLog &log, int4 *trace, hipStream_t s);
 // Packed batches of small graphs whose operator ids are a topological order: one wave per graph sweeps
 // its operators once, highest ids first (no frontier at all); fills K and, when pq is not NULL, the
 // per-graph per-set counts.
 hipError_t launch_sweep_graphs(const GraphView &g, u64 *M, u64 *K, int64_t *per_query_count, hipStream_t s);
 // One sweep over all operators re-deriving K and pushing new bits to the inputs; *changed |= 1 if any.
-hipError_t launch_fix_sweep(const GraphView &g, u64 *M, u64 *K, int32_t *changed, int grid_blocks, hipStream_t s);
+hipError_t launch_fix_sweep(const GraphView &g, u64 *M, u64 *K, uint8_t *flags, int32_t *changed, int grid_blocks, hipStream_t s);
 
 // Removal rule + compaction.
 constexpr int kPqStride = 8;         // int64 words between two replicated per-set counters (64 bytes)
@@ -262,6 +263,8 @@ struct CompactArgs {
     u64 *opbits;             // [ceil(P/64)] scratch
     int32_t *block_counts;   // [num_tiles + 1] scratch
     bool from_tensor_mask;   // K := OR M[out] (true) or read K as accumulated by the traversal
+    const uint8_t *flag_in;  // when not NULL (and not from_tensor_mask): one byte per operator, 1 where K != 0, as the
+                             // traversal left them; K is then read for those operators only
     RecycleHeader *hdr;      // when not NULL: the last pass writes `want` there if no error bit is set in *error
     RecycleHeader want;
     const int32_t *error;

@@ -29,7 +29,9 @@ __device__ __forceinline__ int graph_of(const int64_t *off, int num_graphs, int6
     return lo;
 }
 
-template <bool kFromM>
+// kFromM: K is computed from M and written.  Otherwise K is read: all of it, or (kFlags) only where the byte the
+// traversal sets when an operator first receives bits says that it is not zero -- P bytes instead of 8P.
+template <bool kFromM, bool kFlags>
 __global__ __launch_bounds__(kCThreads) void k_keep_count(CompactArgs a)
 {
     __shared__ int s_wcount[2][kCWaves];
@@ -66,11 +68,21 @@ __global__ __launch_bounds__(kCThreads) void k_keep_count(CompactArgs a)
         const int64_t wave_base = tile * kCompactTile + (int64_t)wave * (kCRounds * kWave);
         int kept = 0;                 // wave-uniform
         u64 kk[kCRounds];
+        uint8_t fl[kCRounds] = {};
+        if (kFlags) {
+#pragma unroll
+            for (int r = 0; r < kCRounds; ++r) {
+                const int64_t o = wave_base + r * kWave + lane;
+                fl[r] = o < g.num_ops ? a.flag_in[o] : 0;
+            }
+        }
 #pragma unroll
         for (int r = 0; r < kCRounds; ++r) {
             const int64_t o = wave_base + r * kWave + lane;
             kk[r] = 0;
-            if (o < g.num_ops) {
+            if (kFlags) {
+                if (fl[r]) kk[r] = a.K[o];
+            } else if (o < g.num_ops) {
                 if (kFromM) {
                     const int32_t b = g.out_rowptr[o], e = g.out_rowptr[o + 1];
                     u64 k = 0;
@@ -137,7 +149,7 @@ __global__ __launch_bounds__(kCThreads) void k_keep_count(CompactArgs a)
             }
         }
         if (lane < kCRounds && wave_base + lane * kWave < g.num_ops) a.opbits[(wave_base >> 6) + lane] = bword;
-        if (a.op_flag) {
+        if (a.op_flag && !(kFlags && a.op_flag == a.flag_in)) {
             // bits 8(l%8) .. 8(l%8)+7 of fword -> eight 0/1 bytes, one 8-byte store per lane
             const u64 b = (fword >> ((lane & 7) * 8)) & 0xff;
             u64 bytes = (b * 0x0101010101010101ull) & 0x8040201008040201ull;
@@ -178,6 +190,106 @@ __global__ __launch_bounds__(kCThreads) void k_keep_count(CompactArgs a)
     }
 }
 
+// Count pass of a single graph whose keep flags the traversal has already written (a byte per operator, 1 where
+// K != 0; they are the caller's op_flag or stand in for it).  A wave takes a whole tile: 2048 flag bytes in four
+// 8-byte loads per lane, squeezed to the tile's 32 bitmap words and its kept count without touching K.  The ids
+// of the kept operators go through a small list in LDS, and K is read for 64 of them at a time for the per-set
+// counts -- about P/8 + 8 P_kept bytes of traffic instead of 9P, and no barrier anywhere.
+constexpr int kPendCap = 128;
+// Below this many operators all of K is a few microseconds of reading, and the kernel that reads it is the
+// faster one where most operators are kept (it needs no list of kept ids).
+constexpr int64_t kFlagsCountMinOps = (int64_t)1 << 22;
+
+__device__ __forceinline__ uint32_t count_pending(const CompactArgs &a, const int32_t *ids, int n)
+{
+    const int lane = lane_id();
+    const u64 k = lane < n ? a.K[ids[lane]] : 0;
+    if (n > kTransposeAbove) return (uint32_t)__popcll(wave_transpose64(k));   // lane q: column q of the bit matrix
+    uint32_t c = 0;
+    for (int l = 0; l < n; ++l) {                                               // wave-uniform
+        const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)k, l);
+        const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(k >> 32), l);
+        c += (uint32_t)(((((u64)hi << 32) | lo) >> lane) & 1);
+    }
+    return c;
+}
+
+__global__ __launch_bounds__(kCThreads) void k_keep_count_flags(CompactArgs a)
+{
+    __shared__ int32_t s_ids[kCWaves][kPendCap];
+    __shared__ uint32_t s_q[kCWaves][kWave];
+    const GraphView &g = a.g;
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int64_t tiles = ((int64_t)g.num_ops + kCompactTile - 1) / kCompactTile;
+    const int64_t n_words = ((int64_t)g.num_ops + 63) >> 6;
+    const bool want_pq = a.per_query_count != nullptr;
+    int32_t *ids = &s_ids[wave][0];
+    int npend = 0;                // wave-uniform
+    uint32_t qcount = 0;          // lane q: kept operators whose K has bit q
+    for (int64_t tile = (int64_t)blockIdx.x * kCWaves + wave; tile < tiles; tile += (int64_t)gridDim.x * kCWaves) {
+        const int64_t base = tile * kCompactTile;
+        u64 f[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int64_t o = base + j * 512 + lane * 8;      // this lane's eight operators of stretch j
+            f[j] = o < g.num_ops ? *reinterpret_cast<const u64 *>(a.flag_in + o) : 0;
+        }
+        int kept = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            // bytes are 0 or 1: bit 0 of each into one byte
+            const uint32_t b = (uint32_t)(((f[j] & 0x0101010101010101ull) * 0x0102040810204080ull) >> 56);
+            kept += __popc(b);
+            // eight neighbouring lanes hold one bitmap word
+            u64 w = (u64)b << (8 * (lane & 7));
+            w |= shfl_xor64(w, 1);
+            w |= shfl_xor64(w, 2);
+            w |= shfl_xor64(w, 4);
+            const int64_t wi = (base >> 6) + j * 8 + (lane >> 3);
+            if ((lane & 7) == 0 && wi < n_words) a.opbits[wi] = w;
+            if (want_pq && ballot64(b != 0)) {
+                const int32_t o0 = (int32_t)(base + j * 512 + lane * 8);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const bool has = (b >> i) & 1;
+                    const u64 m = ballot64(has);
+                    if (!m) continue;                           // wave-uniform
+                    if (has) ids[npend + __popcll(m & lanemask_lt())] = o0 + i;
+                    npend += __popcll(m);
+                    if (npend >= kWave) {
+                        __builtin_amdgcn_wave_barrier();
+                        qcount += count_pending(a, ids, kWave);
+                        const int32_t rest = lane + kWave < npend ? ids[lane + kWave] : 0;
+                        __builtin_amdgcn_wave_barrier();
+                        ids[lane] = rest;
+                        npend -= kWave;
+                    }
+                }
+            }
+        }
+        kept = wave_sum(kept);
+        if (lane == 0) a.block_counts[tile] = kept;
+    }
+    if (!want_pq) return;
+    __builtin_amdgcn_wave_barrier();
+    if (npend > 0) qcount += count_pending(a, ids, npend);
+    // one add per workgroup and set into one of the replicated counters
+    int64_t *pq = a.per_query_count;
+    int pqs = 1;
+    if (a.pq_part) {
+        pqs = kPqStride;
+        pq = a.pq_part + (int64_t)(blockIdx.x & (a.pq_replicas - 1)) * 64 * kPqStride;
+    }
+    s_q[wave][lane] = qcount;
+    __syncthreads();
+    if (wave == 0) {
+        uint32_t c = 0;
+#pragma unroll
+        for (int w = 0; w < kCWaves; ++w) c += s_q[w][lane];
+        if (c) atomicAdd((u64 *)&pq[(int64_t)lane * pqs], (u64)c);
+    }
+}
+
 // per_query_count[i] = sum over the replicas of pq_part[r][i]: one wave per output, one lane per replica
 __global__ __launch_bounds__(256) void k_reduce_pq(CompactArgs a)
 {
@@ -205,12 +317,19 @@ __global__ __launch_bounds__(1024) void k_scan_tiles(int32_t *counts, int64_t m,
     const int lane = lane_id(), wave = threadIdx.x >> 6;
     if (fold_pq) {
         const int n = 64 * a.g.num_graphs;
-        for (int i = wave; i < n; i += 16) {
-            long long v = 0;
-            if (lane < a.pq_replicas) v = a.pq_part[((int64_t)lane * n + i) * kPqStride];
+        for (int i0 = wave; i0 < n; i0 += 64) {          // four counters per wave and step, their loads in flight together
+            long long v[4];
 #pragma unroll
-            for (int d = kWave / 2; d >= 1; d >>= 1) v += __shfl_xor(v, d, kWave);
-            if (lane == 0) a.per_query_count[i] = v;
+            for (int c = 0; c < 4; ++c) {
+                const int i = i0 + 16 * c;
+                v[c] = (i < n && lane < a.pq_replicas) ? a.pq_part[((int64_t)lane * n + i) * kPqStride] : 0;
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+#pragma unroll
+                for (int d = kWave / 2; d >= 1; d >>= 1) v[c] += __shfl_xor(v[c], d, kWave);
+                if (lane == 0 && i0 + 16 * c < n) a.per_query_count[i0 + 16 * c] = v[c];
+            }
         }
     }
     // runs are a multiple of four counts long and start 16-byte aligned: int4 loads, all of them in flight at once
@@ -316,9 +435,14 @@ hipError_t launch_keep_compact(const CompactArgs &a, hipStream_t s, hipEvent_t *
     const int64_t count_grid = tiles < kCountGrid ? tiles : kCountGrid;
     if (tiles > 0) {
         if (a.from_tensor_mask)
-            hipLaunchKernelGGL(k_keep_count<true>, dim3((unsigned)count_grid), dim3(kCThreads), 0, s, a);
+            hipLaunchKernelGGL((k_keep_count<true, false>), dim3((unsigned)count_grid), dim3(kCThreads), 0, s, a);
+        else if (a.flag_in && a.g.num_graphs == 1 && (a.op_flag == nullptr || a.op_flag == a.flag_in) &&
+                 P >= kFlagsCountMinOps)
+            hipLaunchKernelGGL(k_keep_count_flags, dim3((unsigned)count_grid), dim3(kCThreads), 0, s, a);
+        else if (a.flag_in)
+            hipLaunchKernelGGL((k_keep_count<false, true>), dim3((unsigned)count_grid), dim3(kCThreads), 0, s, a);
         else
-            hipLaunchKernelGGL(k_keep_count<false>, dim3((unsigned)count_grid), dim3(kCThreads), 0, s, a);
+            hipLaunchKernelGGL((k_keep_count<false, false>), dim3((unsigned)count_grid), dim3(kCThreads), 0, s, a);
     }
     const bool reduce_pq = a.per_query_count && a.pq_part;
     const bool fold_pq = reduce_pq && 64 * a.g.num_graphs <= kFoldPqOutputs;

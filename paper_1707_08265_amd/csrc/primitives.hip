@@ -40,11 +40,12 @@ __global__ __launch_bounds__(256) void k_clear(ClearArgs a) { clear_regions(a); 
 
 // The same, unless the scratch buffer says that the output buffers still hold the result of the previous
 // prune of this graph, unchanged: then only the words that prune set are zeroed -- M of the tensors in its
-// log, K and the deferral marker of its kept operators -- a few MB of scattered stores instead of 8(T + P)
+// log, K, the deferral marker and the keep flag of its kept operators -- a few MB of scattered stores instead of 8(T + P)
 // bytes of streaming ones.
 __global__ __launch_bounds__(256) void k_clear_or_reset(ClearArgs a, const RecycleHeader *hdr, RecycleHeader want,
                                                         u64 *found_out, ColourLog log, const int32_t *kept_ops,
-                                                        const int64_t *kept_count, u64 *M, u64 *K, uint8_t *DB)
+                                                        const int64_t *kept_count, u64 *M, u64 *K, uint8_t *DB,
+                                                        uint8_t *flags)
 {
     __shared__ int s_pref[kMaxSeg + 1];
     const RecycleHeader have = *hdr;
@@ -78,6 +79,7 @@ __global__ __launch_bounds__(256) void k_clear_or_reset(ClearArgs a, const Recyc
         const int32_t o = kept_ops[i];
         K[o] = 0;
         DB[o] = 0;
+        flags[o] = 0;
     }
 }
 
@@ -107,7 +109,7 @@ hipError_t launch_clear(const FillRegion *regions, int num_regions, hipStream_t 
 
 hipError_t launch_clear_or_reset(const FillRegion *regions, int num_regions, const RecycleHeader *hdr,
                                  const RecycleHeader &want, u64 *found_out, const ColourLog &log, const int32_t *kept_ops,
-                                 const int64_t *kept_count, u64 *M, u64 *K, uint8_t *DB, hipStream_t s)
+                                 const int64_t *kept_count, u64 *M, u64 *K, uint8_t *DB, uint8_t *flags, hipStream_t s)
 {
     if (num_regions > kMaxClearRegions) return hipErrorInvalidValue;
     ClearArgs a{};
@@ -123,7 +125,7 @@ hipError_t launch_clear_or_reset(const FillRegion *regions, int num_regions, con
     if (blocks < 1) blocks = 1;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(k_clear_or_reset, dim3((unsigned)blocks), dim3(256), 0, s, a, hdr, want, found_out, log, kept_ops,
-                       kept_count, M, K, DB);
+                       kept_count, M, K, DB, flags);
     return hipGetLastError();
 }
 

@@ -275,8 +275,8 @@ struct LevelCounters {   // per-lane tallies, reduced by the caller
 
 // Tensor-side step: 64 frontier tensors held one per lane (valid lanes only).
 __device__ __forceinline__ void process_entries(const GraphView &g, bool valid, int32_t t, int32_t theta, uint8_t *DB,
-                                                u64 *M, u64 *K, int *s_incl, WaveStage &ws, const Frontier &f,
-                                                LevelCounters &lc, bool lazy_mask)
+                                                uint8_t *flags, u64 *M, u64 *K, int *s_incl, WaveStage &ws,
+                                                const Frontier &f, LevelCounters &lc, bool lazy_mask)
 {
     u64 m = 0;
     bool active = false;
@@ -304,6 +304,7 @@ __device__ __forceinline__ void process_entries(const GraphView &g, bool valid, 
         if (active && pi.x >= 0) {
             const u64 old = atomicOr(&K[pi.x], m);          // (I1)
             nb = m & ~old;                                  // bits o did not have yet
+            if (old == 0 && m != 0) flags[pi.x] = 1;        // o is kept: a byte the count pass reads instead of K
             if (nb) deg = pi.z;
         }
         expand_edges(g, pi.y, deg, nb, M, s_incl, ws, f);
@@ -318,6 +319,7 @@ __device__ __forceinline__ void process_entries(const GraphView &g, bool valid, 
             const int32_t o = g.prod_idx[pi.y + r];
             const u64 old = atomicOr(&K[o], m);
             nb = m & ~old;
+            if (old == 0 && m != 0) flags[o] = 1;
             if (nb) {
                 eb = g.in_rowptr[o];
                 deg = g.in_rowptr[o + 1] - eb;
@@ -330,8 +332,8 @@ __device__ __forceinline__ void process_entries(const GraphView &g, bool valid, 
 // Operator-side step: 64 operators held one per lane; K[o] |= OR of M over the outputs of o, new bits
 // go to the inputs.  Used for deferred operators (I5) and by the fix-up sweep.  Returns whether this
 // lane's operator gained bits.
-__device__ __forceinline__ bool process_ops(const GraphView &g, bool valid, int32_t o, u64 *M, u64 *K, int *s_incl,
-                                            WaveStage &ws, const Frontier &f)
+__device__ __forceinline__ bool process_ops(const GraphView &g, bool valid, int32_t o, uint8_t *flags, u64 *M, u64 *K,
+                                            int *s_incl, WaveStage &ws, const Frontier &f)
 {
     int ob = 0, n_out = 0, ib = 0, n_in = 0;
     if (valid) {
@@ -348,6 +350,7 @@ __device__ __forceinline__ bool process_ops(const GraphView &g, bool valid, int3
     if (valid && k) {
         const u64 old = atomicOr(&K[o], k);                 // (I1)
         nb = k & ~old;
+        if (old == 0) flags[o] = 1;
     }
     expand_edges(g, ib, nb ? n_in : 0, nb, M, s_incl, ws, f);
     return nb != 0;
@@ -423,8 +426,8 @@ __device__ __forceinline__ LevelPlan plan_level(const LevelSlot &in, int n, bool
 // The work of block `blk` (< p.nwork) in one level: its share of the frontier entries and of the
 // newly opened operator range.  Adds the block's tallies to tally_proc / tally_key.
 __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &in, int n, const LevelPlan &p, int blk,
-                                          const int32_t *qin, const QueueGeom &qg, const Frontier &f, uint8_t *DB, u64 *M,
-                                          u64 *K, LevelShared &sh, SegCounter *tally)
+                                          const int32_t *qin, const QueueGeom &qg, const Frontier &f, uint8_t *DB,
+                                          uint8_t *flags, u64 *M, u64 *K, LevelShared &sh, SegCounter *tally)
 {
     const int lane = lane_id(), wave = threadIdx.x >> 6;
     const bool do_entries = !p.split || blk < p.nb_e;
@@ -439,7 +442,7 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
         const int i = base + threadIdx.x;
         const bool valid = i < n;
         const int32_t t = valid ? load_item(qin, qg, sh.pref, i) : 0;
-        process_entries(g, valid, t, in.theta, DB, M, K, &sh.incl[wave][0], ws, f, lc, true);
+        process_entries(g, valid, t, in.theta, DB, flags, M, K, &sh.incl[wave][0], ws, f, lc, true);
     }
     // expand the bitmap words of the newly opened range into dense operator lists, 64 per step
     for (int c = s_first * kLevelWaves + wave; do_scan && c < p.chunks; c += s_blocks * kLevelWaves) {
@@ -475,7 +478,7 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
         for (int i0 = 0; i0 < total; i0 += kWave) {
             const bool valid = i0 + lane < total;
             const int32_t o = valid ? sh.ops[wave][i0 + lane] : 0;
-            process_ops(g, valid, o, M, K, &sh.incl[wave][0], ws, f);
+            process_ops(g, valid, o, flags, M, K, &sh.incl[wave][0], ws, f);
             if (valid) lc.processed++;
         }
         __builtin_amdgcn_wave_barrier();
@@ -571,8 +574,9 @@ __device__ __forceinline__ void hand_on_frontier(TravCounters *ctr, int launch_n
 }
 
 __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState *st, TravCounters *ctr, int launch_no,
-                                                          int32_t *q0, int32_t *q1, QueueGeom qg, uint8_t *DB, u64 *M,
-                                                          u64 *K, int narrow_cap, Schedule sch, ColourLog log,
+                                                          int32_t *q0, int32_t *q1, QueueGeom qg, uint8_t *DB,
+                                                          uint8_t *flags, u64 *M, u64 *K, int narrow_cap, Schedule sch,
+                                                          ColourLog log,
                                                           int4 *trace)
 {
     __shared__ LevelShared sh;
@@ -600,15 +604,15 @@ __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState 
     const int lseg = (blockIdx.x * kLevelWaves + wave) & (kMaxSeg - 1);
     const Frontier f{qout + (int64_t)seg * qg.seg_cap, &ctr->cnt[mine][seg].v, qg.seg_cap, &st->error,
                      log.entries ? log.entries + (int64_t)lseg * log.seg_cap : nullptr, &log.cnt[lseg].v, log.seg_cap};
-    run_level(g, in, n, p, (int)blockIdx.x, qin, qg, f, DB, M, K, sh, ctr->cnt[mine]);
+    run_level(g, in, n, p, (int)blockIdx.x, qin, qg, f, DB, flags, M, K, sh, ctr->cnt[mine]);
 }
 
 hipError_t launch_level(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
-                        const QueueGeom &qg, uint8_t *DB, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
+                        const QueueGeom &qg, uint8_t *DB, uint8_t *flags, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
                         const Schedule &sch, const ColourLog &log, int4 *trace, hipStream_t s)
 {
     hipLaunchKernelGGL(k_level, dim3((unsigned)grid_blocks), dim3(kLevelThreads), 0, s, g, st, ctr, launch_no, q0, q1,
-                       qg, DB, M, K, narrow_cap, sch, log, trace);
+                       qg, DB, flags, M, K, narrow_cap, sch, log, trace);
     return hipGetLastError();
 }
 
@@ -620,8 +624,9 @@ constexpr int kNarrowThreads = 1024;
 constexpr int kNarrowWaves = kNarrowThreads / kWave;
 
 __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravState *st, TravCounters *ctr, int launch_no,
-                                                            int32_t *q0, int32_t *q1, QueueGeom qg, uint8_t *DB, u64 *M,
-                                                            u64 *K, int narrow_cap, Schedule sch, ColourLog log,
+                                                            int32_t *q0, int32_t *q1, QueueGeom qg, uint8_t *DB,
+                                                            uint8_t *flags, u64 *M, u64 *K, int narrow_cap, Schedule sch,
+                                                            ColourLog log,
                                                             int4 *trace)
 {
     __shared__ int32_t s_stage[kNarrowWaves][kStageCap];
@@ -653,7 +658,7 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
             const bool valid = i < n;
             const int32_t t = valid ? load_item(qin, qg, s_pref, i) : 0;
             // threshold 0: a small frontier is latency bound, so nothing is gained by deferring
-            process_entries(g, valid, t, 0, DB, M, K, &s_incl[wave][0], ws, f, lc, false);
+            process_entries(g, valid, t, 0, DB, flags, M, K, &s_incl[wave][0], ws, f, lc, false);
         }
         stage_flush(ws, f);
         // the block's queue stores must have completed before they are re-read (with cache-bypassing
@@ -685,10 +690,10 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
 }
 
 hipError_t launch_narrow(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
-                         const QueueGeom &qg, uint8_t *DB, u64 *M, u64 *K, int narrow_cap, const Schedule &sch,
+                         const QueueGeom &qg, uint8_t *DB, uint8_t *flags, u64 *M, u64 *K, int narrow_cap, const Schedule &sch,
                          const ColourLog &log, int4 *trace, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_narrow, dim3(1), dim3(kNarrowThreads), 0, s, g, st, ctr, launch_no, q0, q1, qg, DB, M, K,
+    hipLaunchKernelGGL(k_narrow, dim3(1), dim3(kNarrowThreads), 0, s, g, st, ctr, launch_no, q0, q1, qg, DB, flags, M, K,
                        narrow_cap, sch, log, trace);
     return hipGetLastError();
 }
@@ -697,7 +702,7 @@ hipError_t launch_narrow(const GraphView &g, TravState *st, TravCounters *ctr, i
 // fix-up sweep (only after a frontier queue overflowed): every operator re-derives K from its outputs
 // and pushes what is new to its inputs; repeated by the host until a sweep changes nothing
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kLevelThreads) void k_fix_sweep(GraphView g, u64 *M, u64 *K, int32_t *changed)
+__global__ __launch_bounds__(kLevelThreads) void k_fix_sweep(GraphView g, u64 *M, u64 *K, uint8_t *flags, int32_t *changed)
 {
     __shared__ int32_t s_stage[kLevelWaves][kStageCap];
     __shared__ int s_incl[kLevelWaves][kWave];
@@ -713,16 +718,16 @@ __global__ __launch_bounds__(kLevelThreads) void k_fix_sweep(GraphView g, u64 *M
     for (int64_t tile = tiles - 1 - blockIdx.x; tile >= 0; tile -= gridDim.x) {
         const int64_t o = tile * kLevelThreads + threadIdx.x;
         const bool valid = o < g.num_ops;
-        any |= process_ops(g, valid, valid ? (int32_t)o : 0, M, K, &s_incl[wave][0], ws, f);
+        any |= process_ops(g, valid, valid ? (int32_t)o : 0, flags, M, K, &s_incl[wave][0], ws, f);
         ws.cnt = 0;
     }
     if (ballot64(any) != 0 && lane_id() == 0) atomicOr(changed, 1);
 }
 
-hipError_t launch_fix_sweep(const GraphView &g, u64 *M, u64 *K, int32_t *changed, int grid_blocks, hipStream_t s)
+hipError_t launch_fix_sweep(const GraphView &g, u64 *M, u64 *K, uint8_t *flags, int32_t *changed, int grid_blocks, hipStream_t s)
 {
     if (g.num_ops == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_fix_sweep, dim3((unsigned)grid_blocks), dim3(kLevelThreads), 0, s, g, M, K, changed);
+    hipLaunchKernelGGL(k_fix_sweep, dim3((unsigned)grid_blocks), dim3(kLevelThreads), 0, s, g, M, K, flags, changed);
     return hipGetLastError();
 }
 

@@ -57,6 +57,34 @@ def test_recycled_prunes_match_the_oracle(dgn, oracle, k, scale):
     assert k == 0 or k == 2 or all(seen[2:]), seen
 
 
+def test_recycled_prunes_of_a_graph_large_enough_for_the_flag_driven_count_pass(dgn, oracle):
+    """Above four million operators the count pass reads the keep flags the traversal wrote (a byte per
+    operator) instead of all of K; recycled buffers must hand it flags with nothing left over."""
+    g, tg = gg.config(3, 0.1)                               # five million operators
+    assert g.num_ops >= 1 << 22
+    dg = dgn.DeviceGraph.from_coo(g)
+    buf = dgn.PruneBuffers(dg, tg.num_sets)
+    adj, _ = oracle_prune(oracle, g, tg)
+    seen = []
+    for i, t in enumerate(_draws(g, tg, 4)):
+        st = _prune(dgn, buf, t)
+        ref = oracle.forward_prune(adj, t.num_sets, t.tgt_rowptr, t.tgt_idx, g.num_graphs, g.graph_op_offsets)
+        assert_same(buf.to_host(), ref, f"call {i}")
+        seen.append(int(st.recycled))
+    assert seen == [0, 0, 1, 1]
+    # the same without a flag array of the caller's: the library keeps the flags in its scratch buffer
+    import torch
+    keep = buf.op_flag
+    buf.op_flag = None
+    st = _prune(dgn, buf, tg)
+    buf.op_flag = keep
+    out = buf.to_host()
+    ref = oracle.forward_prune(adj, tg.num_sets, tg.tgt_rowptr, tg.tgt_idx, g.num_graphs, g.graph_op_offsets)
+    assert np.array_equal(out["op_mask"], ref.op_mask) and np.array_equal(out["kept_ops"], ref.kept_ops)
+    assert np.array_equal(out["per_query_count"], ref.per_query_count)
+    torch.cuda.synchronize()
+
+
 def test_recycle_survives_schedule_knobs_and_the_standalone_keep_pass(dgn, oracle):
     g, tg = gg.config(3, 0.02)
     dg = dgn.DeviceGraph.from_coo(g)
