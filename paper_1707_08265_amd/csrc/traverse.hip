@@ -74,8 +74,27 @@ struct WaveStage {
     int32_t *buf;     // this wave's kStageCap ints in LDS; bit 31 marks an entry that also goes to the log
     int cnt;          // wave-uniform
     int nlog;         // marked entries among them, wave-uniform
+    int32_t *lbuf;    // NULL, or kLogStageCap ints in LDS where log entries wait across flushes (the single-workgroup
+    int lcnt;         // kernel flushes once per level: a trip to a counter in memory per level would show)
 };
 constexpr int32_t kLogTag = (int32_t)0x80000000;
+constexpr int kLogStageCap = 256;
+
+// Write the log entries waiting in LDS out to the wave's log segment.
+__device__ __forceinline__ void flush_log_stage(WaveStage &ws, int32_t *log, int32_t *log_cnt, int32_t log_cap, int32_t *error)
+{
+    if (ws.lcnt > 0) {
+        int base = 0;
+        if (lane_id() == 0) {
+            base = atomicAdd(log_cnt, ws.lcnt);
+            if (base + ws.lcnt > log_cap) atomicOr(error, kErrLogFull);
+        }
+        base = __builtin_amdgcn_readfirstlane(base);
+        for (int k = lane_id(); k < ws.lcnt; k += kWave)
+            if (base + k < log_cap) log[base + k] = ws.lbuf[k];
+        ws.lcnt = 0;
+    }
+}
 
 struct Frontier {     // where one wave pushes
     int32_t *seg;     // start of the wave's segment in the output queue
@@ -91,11 +110,13 @@ __device__ __forceinline__ void stage_flush(WaveStage &ws, const Frontier &f)
 {
     if (ws.cnt > 0) {
         const int lane = lane_id();
+        const bool log_waits = ws.lbuf != nullptr && ws.nlog <= kLogStageCap;
+        if (log_waits && ws.lcnt + ws.nlog > kLogStageCap) flush_log_stage(ws, f.log, f.log_cnt, f.log_cap, f.error);
         int base = 0, lbase = 0;
         if (lane == 0) {
             base = atomicAdd(f.cnt, ws.cnt);
             if (base + ws.cnt > f.seg_cap) atomicOr(f.error, kErrOverflow);   // (I3): fix-up sweep will follow
-            if (ws.nlog > 0) {
+            if (ws.nlog > 0 && !log_waits) {
                 lbase = atomicAdd(f.log_cnt, ws.nlog);
                 if (lbase + ws.nlog > f.log_cap) atomicOr(f.error, kErrLogFull);
             }
@@ -104,14 +125,17 @@ __device__ __forceinline__ void stage_flush(WaveStage &ws, const Frontier &f)
         for (int k = lane; k < ws.cnt; k += kWave)
             if (base + k < f.seg_cap) store_coherent(&f.seg[base + k], ws.buf[k] & ~kLogTag);   // read by other blocks
         if (ws.nlog > 0) {
-            lbase = __builtin_amdgcn_readfirstlane(lbase);
+            lbase = log_waits ? ws.lcnt : __builtin_amdgcn_readfirstlane(lbase);
+            int32_t *dst = log_waits ? ws.lbuf : f.log;
+            const int cap = log_waits ? kLogStageCap : f.log_cap;
             for (int k0 = 0; k0 < ws.cnt; k0 += kWave) {
                 const int32_t v = k0 + lane < ws.cnt ? ws.buf[k0 + lane] : 0;
                 const u64 tm = ballot64(v < 0);
                 const int pos = lbase + __popcll(tm & lanemask_lt());
-                if (v < 0 && pos < f.log_cap) f.log[pos] = v & ~kLogTag;
+                if (v < 0 && pos < cap) dst[pos] = v & ~kLogTag;
                 lbase += __popcll(tm);
             }
+            if (log_waits) ws.lcnt += ws.nlog;
         }
         ws.cnt = 0;
         ws.nlog = 0;
@@ -436,7 +460,7 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
     const int s_blocks = p.split ? p.nb_s : p.nwork, s_first = p.split ? blk - p.nb_e : blk;
     const int cw = 1 << p.cw_log;
 
-    WaveStage ws{&sh.stage[wave][0], 0, 0};
+    WaveStage ws{&sh.stage[wave][0], 0, 0, nullptr, 0};
     LevelCounters lc{0, -1};
     for (int base = e_first * kLevelThreads; do_entries && base < n; base += e_blocks * kLevelThreads) {
         const int i = base + threadIdx.x;
@@ -630,6 +654,7 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
                                                             int4 *trace)
 {
     __shared__ int32_t s_stage[kNarrowWaves][kStageCap];
+    __shared__ int32_t s_lstage[kNarrowWaves][kLogStageCap];
     __shared__ int s_incl[kNarrowWaves][kWave];
     __shared__ int s_pref[kMaxSeg + 1];
     __shared__ int s_derived[2];
@@ -642,7 +667,7 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
     int n = in.n;
     const bool ranges_left = in.deferred_seen && in.theta_hi > 0;   // then the wide kernel must go on
     const int lane = lane_id(), wave = threadIdx.x >> 6;
-    WaveStage ws{&s_stage[wave][0], 0, 0};
+    WaveStage ws{&s_stage[wave][0], 0, 0, log.entries ? &s_lstage[wave][0] : nullptr, 0};
     LevelCounters lc{0, -1};
     u64 visits = 0, maxf = 0;
     while (n > 0 && n <= narrow_cap && !ranges_left) {
@@ -674,6 +699,7 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
         if (threadIdx.x <= kMaxSeg) s_pref[threadIdx.x] = threadIdx.x == 0 ? 0 : n;
         __syncthreads();          // everyone has read s_nout before it is reset; s_pref is in place
     }
+    if (log.entries) flush_log_stage(ws, log.entries + (int64_t)wave * log.seg_cap, &log.cnt[wave].v, log.seg_cap, &st->error);
     // This launch leaves no tallies to fold: its record IS the state after it.  The frontier it ends with
     // (untouched, or the one it built in segment 0) goes to the next launch through this launch's counters.
     if (threadIdx.x < kWave) {
@@ -710,7 +736,7 @@ __global__ __launch_bounds__(kLevelThreads) void k_fix_sweep(GraphView g, u64 *M
     const int wave = threadIdx.x >> 6;
     if (threadIdx.x == 0) { s_sink = 0; s_err = 0; }
     __syncthreads();
-    WaveStage ws{&s_stage[wave][0], 0, 0};
+    WaveStage ws{&s_stage[wave][0], 0, 0, nullptr, 0};
     const Frontier f{nullptr, &s_sink, 0, &s_err, nullptr, nullptr, 0};   // capacity 0: pushes are counted and dropped
     bool any = false;
     // descending ids: most of a sweep then sees its consumers' results (ids are a topological order)
