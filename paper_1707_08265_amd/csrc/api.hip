@@ -31,14 +31,14 @@ constexpr int kWidePerGroup = 12;           // wide level launches between two s
 constexpr int kWideGroupsFirst = 4;         // groups in the first batch (one state read-back per batch) ...
 constexpr int kWideGroups = 6;              // ... and in the following ones
 constexpr int kMaxBatch = 512;              // launches enqueued between two state read-backs, at most
-constexpr int kTailLevels = 2;              // wide launches enqueued beyond the layout the previous prune needed
+constexpr int kTailLevels = 1;              // wide launches enqueued beyond the layout the previous prune needed
 constexpr int kSweepMinGraphs = 64;         // packed batches with at least this many graphs ...
 constexpr int64_t kSweepMaxGraphOps = 1 << 18;   // ... none larger than this use the per-graph sweep
 constexpr u64 kRecycleMagic = 0x44474e5f52435943ull;   // "DGN_RCYC"
 constexpr int kSmallLevel = 16384;           // levels expanding fewer entries than this decay the threshold faster
 constexpr int kDefaultDeferPercent = 85;
 constexpr int kDefaultStartShift = 1;       // deferral threshold starts at P >> 1 ...
-constexpr int kDefaultFloorShift = 10;      // ... and stops (drops to 0) below P >> 10
+constexpr int kDefaultFloorShift = 9;       // ... and stops (drops to 0) below P >> 9
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 

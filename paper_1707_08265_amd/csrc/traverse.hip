@@ -66,35 +66,20 @@ hipError_t launch_build_pinfo(const GraphView &g, int4 *pinfo, hipStream_t s)
 // ------------------------------------------------------------------------------------------------
 // segmented frontier queues
 // ------------------------------------------------------------------------------------------------
-constexpr int kStageCap = 512;     // staged pushes per wave before a flush
+constexpr int kStageCap = 256;     // staged pushes per wave before a flush (a power of two: the buffer is a ring)
+constexpr int kLogStageCap = 128;  // staged log entries per wave
 
-// Per-wave staging of next-frontier entries in LDS: slots are reserved with ballot + popcount, a
-// segment counter is touched once per flush instead of once per push.
+// Per-wave staging in LDS.  Next-frontier entries sit in a ring: slots are reserved with ballot + popcount, a
+// segment counter in memory is touched once per flush instead of once per push, and a wave may take entries
+// back out of the ring to expand them itself before they ever reach memory (see run_level).  Tensors coloured
+// for the first time are noted in a second, small buffer that is written to the log when it fills up and when
+// the kernel ends.
 struct WaveStage {
-    int32_t *buf;     // this wave's kStageCap ints in LDS; bit 31 marks an entry that also goes to the log
-    int cnt;          // wave-uniform
-    int nlog;         // marked entries among them, wave-uniform
-    int32_t *lbuf;    // NULL, or kLogStageCap ints in LDS where log entries wait across flushes (the single-workgroup
-    int lcnt;         // kernel flushes once per level: a trip to a counter in memory per level would show)
+    int32_t *buf;     // this wave's kStageCap ints
+    int head, tail;   // wave-uniform, ever growing; the pending entries are buf[head & mask .. tail & mask)
+    int32_t *lbuf;    // this wave's kLogStageCap ints, or NULL: no log is kept
+    int lcnt;         // wave-uniform
 };
-constexpr int32_t kLogTag = (int32_t)0x80000000;
-constexpr int kLogStageCap = 256;
-
-// Write the log entries waiting in LDS out to the wave's log segment.
-__device__ __forceinline__ void flush_log_stage(WaveStage &ws, int32_t *log, int32_t *log_cnt, int32_t log_cap, int32_t *error)
-{
-    if (ws.lcnt > 0) {
-        int base = 0;
-        if (lane_id() == 0) {
-            base = atomicAdd(log_cnt, ws.lcnt);
-            if (base + ws.lcnt > log_cap) atomicOr(error, kErrLogFull);
-        }
-        base = __builtin_amdgcn_readfirstlane(base);
-        for (int k = lane_id(); k < ws.lcnt; k += kWave)
-            if (base + k < log_cap) log[base + k] = ws.lbuf[k];
-        ws.lcnt = 0;
-    }
-}
 
 struct Frontier {     // where one wave pushes
     int32_t *seg;     // start of the wave's segment in the output queue
@@ -106,39 +91,37 @@ struct Frontier {     // where one wave pushes
     int32_t log_cap;
 };
 
-__device__ __forceinline__ void stage_flush(WaveStage &ws, const Frontier &f)
+// Write the pending entries out to the wave's queue segment.
+__device__ __forceinline__ void flush_entries(WaveStage &ws, const Frontier &f)
 {
-    if (ws.cnt > 0) {
-        const int lane = lane_id();
-        const bool log_waits = ws.lbuf != nullptr && ws.nlog <= kLogStageCap;
-        if (log_waits && ws.lcnt + ws.nlog > kLogStageCap) flush_log_stage(ws, f.log, f.log_cnt, f.log_cap, f.error);
-        int base = 0, lbase = 0;
-        if (lane == 0) {
-            base = atomicAdd(f.cnt, ws.cnt);
-            if (base + ws.cnt > f.seg_cap) atomicOr(f.error, kErrOverflow);   // (I3): fix-up sweep will follow
-            if (ws.nlog > 0 && !log_waits) {
-                lbase = atomicAdd(f.log_cnt, ws.nlog);
-                if (lbase + ws.nlog > f.log_cap) atomicOr(f.error, kErrLogFull);
-            }
+    const int n = ws.tail - ws.head;
+    if (n > 0) {
+        int base = 0;
+        if (lane_id() == 0) {
+            base = atomicAdd(f.cnt, n);
+            if (base + n > f.seg_cap) atomicOr(f.error, kErrOverflow);   // (I3): fix-up sweep will follow
         }
         base = __builtin_amdgcn_readfirstlane(base);
-        for (int k = lane; k < ws.cnt; k += kWave)
-            if (base + k < f.seg_cap) store_coherent(&f.seg[base + k], ws.buf[k] & ~kLogTag);   // read by other blocks
-        if (ws.nlog > 0) {
-            lbase = log_waits ? ws.lcnt : __builtin_amdgcn_readfirstlane(lbase);
-            int32_t *dst = log_waits ? ws.lbuf : f.log;
-            const int cap = log_waits ? kLogStageCap : f.log_cap;
-            for (int k0 = 0; k0 < ws.cnt; k0 += kWave) {
-                const int32_t v = k0 + lane < ws.cnt ? ws.buf[k0 + lane] : 0;
-                const u64 tm = ballot64(v < 0);
-                const int pos = lbase + __popcll(tm & lanemask_lt());
-                if (v < 0 && pos < cap) dst[pos] = v & ~kLogTag;
-                lbase += __popcll(tm);
-            }
-            if (log_waits) ws.lcnt += ws.nlog;
+        for (int k = lane_id(); k < n; k += kWave)
+            if (base + k < f.seg_cap)
+                store_coherent(&f.seg[base + k], ws.buf[(ws.head + k) & (kStageCap - 1)]);   // read by other blocks
+        ws.head = ws.tail;
+    }
+}
+
+// Write the waiting log entries out to the wave's log segment.
+__device__ __forceinline__ void flush_log(WaveStage &ws, const Frontier &f)
+{
+    if (ws.lcnt > 0) {
+        int base = 0;
+        if (lane_id() == 0) {
+            base = atomicAdd(f.log_cnt, ws.lcnt);
+            if (base + ws.lcnt > f.log_cap) atomicOr(f.error, kErrLogFull);
         }
-        ws.cnt = 0;
-        ws.nlog = 0;
+        base = __builtin_amdgcn_readfirstlane(base);
+        for (int k = lane_id(); k < ws.lcnt; k += kWave)
+            if (base + k < f.log_cap) f.log[base + k] = ws.lbuf[k];
+        ws.lcnt = 0;
     }
 }
 
@@ -148,10 +131,18 @@ __device__ __forceinline__ void stage_push(WaveStage &ws, bool push, bool first,
     const u64 pm = ballot64(push);
     if (pm) {                                   // wave-uniform branch
         const int np = __popcll(pm);
-        if (ws.cnt + np > kStageCap) stage_flush(ws, f);
-        if (push) ws.buf[ws.cnt + __popcll(pm & lanemask_lt())] = first ? (t | kLogTag) : t;
-        ws.cnt += np;
-        ws.nlog += __popcll(ballot64(first));
+        if (ws.tail - ws.head + np > kStageCap) flush_entries(ws, f);
+        if (push) ws.buf[(ws.tail + __popcll(pm & lanemask_lt())) & (kStageCap - 1)] = t;
+        ws.tail += np;
+        if (ws.lbuf) {
+            const u64 fm = ballot64(first);
+            if (fm) {
+                const int nf = __popcll(fm);
+                if (ws.lcnt + nf > kLogStageCap) flush_log(ws, f);
+                if (first) ws.lbuf[ws.lcnt + __popcll(fm & lanemask_lt())] = t;
+                ws.lcnt += nf;
+            }
+        }
     }
 }
 
@@ -285,7 +276,7 @@ __device__ __forceinline__ void expand_edges(const GraphView &g, int eb, int deg
             u = g.in_idx[o_eb + (e - o_excl)];
             const u64 old = atomicOr(&M[u], b);             // (I2)
             push = (b & ~old) != 0;                         // (I3)
-            first = old == 0 && f.log != nullptr;
+            first = old == 0;
         }
         stage_push(ws, push, first, u, f);
     }
@@ -409,10 +400,14 @@ __device__ __forceinline__ int32_t next_theta(int32_t theta, const Schedule &sch
 // ------------------------------------------------------------------------------------------------
 constexpr int kLevelThreads = 256;
 constexpr int kLevelWaves = kLevelThreads / kWave;
+constexpr int kChaseBelow = 32768;                 // frontiers up to this size get a second hop in the same launch ...
+constexpr int kChaseAlwaysBelow = 8192;            // ... or, while the deferral threshold is still coming down, up to this size
+constexpr int kChasePerWave = 8;                   // ... with about this many entries dealt to a wave
 constexpr int kChunkOps = 16 * 64;                 // at most 16 deferred-bitmap words are expanded per wave step
 
 struct LevelShared {
     int32_t stage[kLevelWaves][kStageCap];
+    int32_t lstage[kLevelWaves][kLogStageCap];
     int incl[kLevelWaves][kWave];
     int32_t ops[kLevelWaves][kChunkOps];
     int pref[kMaxSeg + 1];
@@ -429,6 +424,9 @@ struct LevelPlan {
     bool split;          // entries and chunks go to different blocks when the grid has room for both, so
                          // the two dependent-access chains of a small level overlap
     int nwork;           // blocks that have something to do
+    int per_wave;        // 0: every wave takes 64 entries at a time.  Else (small frontier) the entries are dealt
+                         // thinly, per_wave to a wave, so that what a wave pushes fits one more step of its own:
+                         // it then expands those pushes itself, a second hop within the same launch
 };
 
 __device__ __forceinline__ LevelPlan plan_level(const LevelSlot &in, int n, bool ranges_left, int grid)
@@ -442,6 +440,19 @@ __device__ __forceinline__ LevelPlan plan_level(const LevelSlot &in, int n, bool
     p.chunks = (p.w_hi - p.w_lo + cw - 1) >> p.cw_log;
     p.nb_e = (n + kLevelThreads - 1) / kLevelThreads;
     p.nb_s = (p.chunks + kLevelWaves - 1) / kLevelWaves;
+    p.per_wave = 0;
+    // (not while the threshold is still coming down: it takes one step per launch, so the number of launches is
+    // set by its schedule and a second hop would only make each of them longer)
+    if (n > 0 && (n <= kChaseAlwaysBelow || (n <= kChaseBelow && in.theta <= 0)) && p.nb_s < grid) {
+        const int room = grid - p.nb_s;
+        const int want = (n + kLevelWaves * kChasePerWave - 1) / (kLevelWaves * kChasePerWave);
+        const int nb = min(room, want);
+        const int per = (n + nb * kLevelWaves - 1) / (nb * kLevelWaves);
+        if (per <= 2 * kChasePerWave) {
+            p.nb_e = nb;
+            p.per_wave = per;
+        }
+    }
     p.split = p.nb_e + p.nb_s <= grid;
     p.nwork = p.split ? max(1, p.nb_e + p.nb_s) : grid;
     return p;
@@ -460,13 +471,22 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
     const int s_blocks = p.split ? p.nb_s : p.nwork, s_first = p.split ? blk - p.nb_e : blk;
     const int cw = 1 << p.cw_log;
 
-    WaveStage ws{&sh.stage[wave][0], 0, 0, nullptr, 0};
+    WaveStage ws{&sh.stage[wave][0], 0, 0, f.log ? &sh.lstage[wave][0] : nullptr, 0};
     LevelCounters lc{0, -1};
-    for (int base = e_first * kLevelThreads; do_entries && base < n; base += e_blocks * kLevelThreads) {
-        const int i = base + threadIdx.x;
-        const bool valid = i < n;
-        const int32_t t = valid ? load_item(qin, qg, sh.pref, i) : 0;
-        process_entries(g, valid, t, in.theta, DB, flags, M, K, &sh.incl[wave][0], ws, f, lc, true);
+    if (p.per_wave > 0) {
+        if (do_entries) {
+            const int i = (e_first * kLevelWaves + wave) * p.per_wave + lane;
+            const bool valid = lane < p.per_wave && i < n;
+            const int32_t t = valid ? load_item(qin, qg, sh.pref, i) : 0;
+            process_entries(g, valid, t, in.theta, DB, flags, M, K, &sh.incl[wave][0], ws, f, lc, true);
+        }
+    } else {
+        for (int base = e_first * kLevelThreads; do_entries && base < n; base += e_blocks * kLevelThreads) {
+            const int i = base + threadIdx.x;
+            const bool valid = i < n;
+            const int32_t t = valid ? load_item(qin, qg, sh.pref, i) : 0;
+            process_entries(g, valid, t, in.theta, DB, flags, M, K, &sh.incl[wave][0], ws, f, lc, true);
+        }
     }
     // expand the bitmap words of the newly opened range into dense operator lists, 64 per step
     for (int c = s_first * kLevelWaves + wave; do_scan && c < p.chunks; c += s_blocks * kLevelWaves) {
@@ -507,7 +527,23 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
         }
         __builtin_amdgcn_wave_barrier();
     }
-    stage_flush(ws, f);
+    // With a small frontier the level is a chain of dependent accesses plus the fixed cost of a launch: the wave
+    // then expands what it has just pushed itself, one more hop within this launch, and only what that hop pushes
+    // goes to memory (any order of expansions reaches the same fixed point; a hop done here is a launch saved
+    // wherever the levels are small).
+    if (p.per_wave > 0) {
+        int gen_end = ws.tail;                              // the entries pushed so far: this launch's second hop
+        while (gen_end - ws.head > 0) {                     // wave-uniform (a flush empties the ring: head = tail)
+            const int take = min(gen_end - ws.head, kWave);
+            const bool valid = lane < take;
+            const int32_t t = valid ? ws.buf[(ws.head + lane) & (kStageCap - 1)] : 0;
+            ws.head += take;
+            __builtin_amdgcn_wave_barrier();
+            process_entries(g, valid, t, in.theta, DB, flags, M, K, &sh.incl[wave][0], ws, f, lc, true);
+        }
+    }
+    flush_entries(ws, f);
+    flush_log(ws, f);
     // the wave's tallies go to one of 64 spread words each; nobody waits for them
     const int wproc = wave_sum(lc.processed), wkey = wave_max(lc.max_deferred_key);
     if (lane == 0) {
@@ -685,7 +721,7 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
             // threshold 0: a small frontier is latency bound, so nothing is gained by deferring
             process_entries(g, valid, t, 0, DB, flags, M, K, &s_incl[wave][0], ws, f, lc, false);
         }
-        stage_flush(ws, f);
+        flush_entries(ws, f);
         // the block's queue stores must have completed before they are re-read (with cache-bypassing
         // loads) by other waves of this same block; no other block reads them before the kernel ends
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -699,7 +735,10 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
         if (threadIdx.x <= kMaxSeg) s_pref[threadIdx.x] = threadIdx.x == 0 ? 0 : n;
         __syncthreads();          // everyone has read s_nout before it is reset; s_pref is in place
     }
-    if (log.entries) flush_log_stage(ws, log.entries + (int64_t)wave * log.seg_cap, &log.cnt[wave].v, log.seg_cap, &st->error);
+    if (log.entries) {
+        const Frontier lf{nullptr, nullptr, 0, &st->error, log.entries + (int64_t)wave * log.seg_cap, &log.cnt[wave].v, log.seg_cap};
+        flush_log(ws, lf);
+    }
     // This launch leaves no tallies to fold: its record IS the state after it.  The frontier it ends with
     // (untouched, or the one it built in segment 0) goes to the next launch through this launch's counters.
     if (threadIdx.x < kWave) {
@@ -745,7 +784,7 @@ __global__ __launch_bounds__(kLevelThreads) void k_fix_sweep(GraphView g, u64 *M
         const int64_t o = tile * kLevelThreads + threadIdx.x;
         const bool valid = o < g.num_ops;
         any |= process_ops(g, valid, valid ? (int32_t)o : 0, flags, M, K, &s_incl[wave][0], ws, f);
-        ws.cnt = 0;
+        ws.head = ws.tail;
     }
     if (ballot64(any) != 0 && lane_id() == 0) atomicOr(changed, 1);
 }
