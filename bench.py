@@ -329,7 +329,10 @@ def main():
         # all of M and K, or (recycled buffers) the log and the kept list read, their M, K and marker words zeroed
         "k_clear": (12 * T_c + 13 * P_k) if recycled else (8 * T + 8 * P),
         "k_level": (4 * T_c + 8 * P_k + 4 * E_k + 16 * E_k + 16 * P_k) / levels,
-        "k_keep_count": (4 * P + 12 * g.nnz_out + 8 * P + P) if args.recompute_keep else (8 * P + P),
+        # stand-alone: K from M; large single graphs: keep flags (P bytes) read, K of the kept operators, bitmap
+        # written; else all of K read, flags written
+        "k_keep_count": (4 * P + 12 * g.nnz_out + 8 * P + P) if args.recompute_keep
+                        else (P + 8 * P_k + P // 8) if (g.num_graphs == 1 and P >= (1 << 22)) else (8 * P + P),
         "k_scatter": 12 * P_k,
     }
     dur_ms = {
