@@ -1,5 +1,5 @@
 """ctypes front end of the CPU oracle (``forward_prune.c``, ``backward_prune.c``, ``inplace.c``,
-``postprocess.c``) -- TEST INFRASTRUCTURE.
+``postprocess.c``, ``transaction.c``) -- TEST INFRASTRUCTURE.
 
 Only tests, the smoke check and the bench's ``cpu_baseline`` leg may import this package; the
 product path never does.  It imports nothing from the GPU package.
@@ -20,7 +20,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRCS = [os.path.join(_HERE, f) for f in ("forward_prune.c", "backward_prune.c", "inplace.c",
-                                             "postprocess.c")]
+                                             "postprocess.c", "transaction.c")]
 _LIB = os.path.join(_HERE, "liboracle.so")
 _lib = None
 
@@ -43,6 +43,8 @@ def _load():
         _lib.orc_certificate.restype = ctypes.c_int64
         _lib.orc_child_sets.restype = ctypes.c_int64
         _lib.orc_per_set_lists.restype = ctypes.c_int64
+        _lib.orc_mix64.restype = ctypes.c_uint64
+        _lib.orc_mix64.argtypes = [ctypes.c_uint64]
     return _lib
 
 
@@ -249,3 +251,17 @@ def per_set_lists(K: np.ndarray):
     n = _load().orc_per_set_lists(i64(K.shape[0]), _p(K), _p(rowptr), _p(ops))
     assert n == total
     return rowptr, ops[:n].copy()
+
+
+def mix64(z: int) -> int:
+    """Output function of SplitMix64 (the digest's mixing step)."""
+    return int(_load().orc_mix64(ctypes.c_uint64(z & (2**64 - 1))))
+
+
+def target_digest(num_sets: int, tgt_rowptr, tgt_idx):
+    """128-bit digest of the target sets as ``dgn_prune`` receives them (key of a transaction, Sec. 4.1);
+    returns two Python ints."""
+    rp, ix = _c(tgt_rowptr, np.int32), _c(tgt_idx, np.int32)
+    out = np.zeros(2, dtype=np.uint64)
+    _load().orc_target_digest(i32(num_sets), i64(len(rp) - 1), _p(rp), i64(len(ix)), _p(ix), _p(out))
+    return int(out[0]), int(out[1])
