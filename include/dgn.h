@@ -293,6 +293,25 @@ int dgn_ignore_mask(const dgn_graph *g, const uint64_t *tensor_mask, const int32
                     const uint64_t *kept_masks, const int64_t *kept_count, uint64_t *ignore_mask,
                     int64_t *ignore_count, dgn_stream stream);
 
+/* Key of a transaction (Sec. 4.1: a function -- the graph pruned for one choice of fetches and feeds -- is
+ * bound to a hashing key generated from that choice, and asking for it again builds nothing new).  The paper
+ * names no hash.  The key here: the graph handle, num_sets, and this 128-bit digest of the target sets exactly as
+ * dgn_prune would receive them -- the sequence of 32-bit words
+ *     w = [ num_sets, n, tgt_rowptr[0..n], tgt_idx[0..num_targets-1] ],   n = num_sets * number of graphs,
+ *     digest_out[k] = sum over positions i of mix((i + 1) * G + w_i * C_k + S_k)  mod 2^64,
+ * mix = the output function of SplitMix64 (z ^= z >> 30; z *= 0xBF58476D1CE4E5B9; z ^= z >> 27;
+ * z *= 0x94D049BB133111EB; z ^= z >> 31), G = 0x9E3779B97F4A7C15, w_i taken as unsigned,
+ * C_0 = 0xC2B2AE3D27D4EB4F, S_0 = 0x165667B19E3779F9, C_1 = 0xD6E8FEB86659FD93, S_1 = 0x27D4EB2F165667C5.
+ * Equal target sets give equal digests; the same targets in another order, or split differently over the sets,
+ * give another one (a cache keyed by it may miss where it could have hit, it does not hit wrongly short of a
+ * 128-bit collision).
+ *   tgt_rowptr, tgt_idx: DEVICE, as for dgn_prune; digest_out: HOST, two words; scratch: DEVICE, 8-byte
+ *   aligned, dgn_target_digest_workspace bytes.  Synchronises `stream`.  Ids are not validated. */
+int dgn_target_digest_workspace(size_t *scratch_bytes);
+int dgn_target_digest(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const int32_t *tgt_rowptr,
+                      const int32_t *tgt_idx, uint64_t *digest_out, void *scratch, size_t scratch_bytes,
+                      dgn_stream stream);
+
 /* Scratch bytes dgn_per_set_lists needs for a kept list of num_kept entries. */
 int dgn_per_set_lists_workspace(int64_t num_kept, size_t *scratch_bytes);
 

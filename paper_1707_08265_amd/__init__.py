@@ -4,5 +4,6 @@ The package is a thin binding over ``libdgn.so`` (HIP kernels + C ABI, see ``inc
 Build the library first: ``python -m paper_1707_08265_amd.build``.
 """
 from .binding import *  # noqa: F401,F403
-from .binding import (DeviceGraph, PruneBuffers, BackwardPruneBuffers, InplaceBuffers, ReadoutBuffers, DgnError, EXPORTS,
+from .binding import (DeviceGraph, PruneBuffers, BackwardPruneBuffers, InplaceBuffers, ReadoutBuffers, TransactionCache,
+                      DgnError, EXPORTS,
                       LIB_PATH)  # noqa: F401

@@ -32,7 +32,8 @@ EXPORTS = [
     "dgn_graph_build_workspace", "dgn_graph_build", "dgn_graph_from_csr_workspace", "dgn_graph_from_csr",
     "dgn_graph_get_csr", "dgn_graph_get_sizes", "dgn_graph_destroy", "dgn_prune_workspace", "dgn_prune",
     "dgn_prune_words", "dgn_keep_compact", "dgn_backward_prune_workspace", "dgn_backward_prune", "dgn_inplace_workspace",
-    "dgn_inplace", "dgn_ignore_mask", "dgn_per_set_lists_workspace", "dgn_per_set_lists", "dgn_strerror",
+    "dgn_inplace", "dgn_ignore_mask", "dgn_per_set_lists_workspace", "dgn_per_set_lists",
+    "dgn_target_digest_workspace", "dgn_target_digest", "dgn_strerror",
     "dgn_version",
     "dgn_last_hip_error",
 ]
@@ -104,6 +105,9 @@ def _load() -> ctypes.CDLL:
     lib.dgn_per_set_lists_workspace.argtypes = [c_int64, POINTER(c_size_t)]
     lib.dgn_per_set_lists.argtypes = [c_void_p, c_void_p, c_int64, c_void_p, c_void_p, c_int64, c_void_p, c_size_t,
                                       c_void_p]
+    lib.dgn_target_digest_workspace.argtypes = [POINTER(c_size_t)]
+    lib.dgn_target_digest.argtypes = [c_void_p, c_int32, c_int64, c_void_p, c_void_p, POINTER(ctypes.c_uint64), c_void_p,
+                                      c_size_t, c_void_p]
     lib.dgn_inplace_workspace.argtypes = [c_void_p, POINTER(c_size_t)]
     lib.dgn_inplace.argtypes = [c_void_p, c_void_p, ctypes.c_uint64, c_void_p, c_void_p, c_void_p, c_size_t,
                                 POINTER(c_int32), c_void_p]
@@ -288,6 +292,20 @@ def dgn_per_set_lists(kept_ops, kept_masks, num_kept, set_rowptr, set_ops, set_o
                                   set_ops_capacity, _dp(scratch), scratch_bytes, _stream(stream))
 
 
+def dgn_target_digest_workspace():
+    s = c_size_t(0)
+    rc = _lib.dgn_target_digest_workspace(ctypes.byref(s))
+    return rc, s.value
+
+
+def dgn_target_digest(handle, num_sets, num_targets, tgt_rowptr, tgt_idx, scratch, scratch_bytes, stream=None):
+    """Returns (return code, (digest word 0, digest word 1))."""
+    out = (ctypes.c_uint64 * 2)()
+    rc = _lib.dgn_target_digest(handle, num_sets, num_targets, _dp(tgt_rowptr), _dp(tgt_idx), out, _dp(scratch),
+                                scratch_bytes, _stream(stream))
+    return rc, (int(out[0]), int(out[1]))
+
+
 def dgn_inplace_workspace(handle):
     s = c_size_t(0)
     rc = _lib.dgn_inplace_workspace(handle, ctypes.byref(s))
@@ -441,6 +459,47 @@ class PruneBuffers:
         return dict(tensor_mask=u(self.tensor_mask), op_mask=u(self.op_mask), op_flag=self.op_flag.cpu().numpy(),
                     kept_ops=self.kept_ops[:n].cpu().numpy(), kept_masks=u(self.kept_masks[:n]),
                     kept_count=self.kept_count.cpu().numpy(), per_query_count=self.per_query_count.cpu().numpy())
+
+
+class TransactionCache:
+    """Results of ``dgn_prune`` kept by (graph, number of sets, digest of the target sets) -- the transactions of
+    Sec. 4.1 of the paper: asking again for a function that exists builds nothing new.  The digest is computed on
+    the device (``dgn_target_digest``); a hit costs that and a dictionary look-up, a miss prunes into the least
+    recently used of at most ``capacity`` buffer sets.  Buffers handed out stay valid until ``capacity`` other
+    target sets have been asked for since."""
+
+    def __init__(self, graph: DeviceGraph, num_sets: int, capacity: int = 2, device=None):
+        self.graph, self.num_sets, self.capacity = graph, num_sets, max(1, int(capacity))
+        self._device = device
+        self._entries = {}                    # digest -> PruneBuffers, oldest first
+        rc, sb = dgn_target_digest_workspace()
+        _check(rc, "dgn_target_digest_workspace")
+        dev = graph.graph_mem.device if device is None else torch.device(device)
+        self._scratch, self._scratch_bytes = torch.empty(sb, dtype=torch.uint8, device=dev), sb
+        self.hits = self.misses = 0
+
+    def digest(self, tgt_rowptr, tgt_idx, stream=None):
+        rc, d = dgn_target_digest(self.graph.handle, self.num_sets, int(tgt_idx.numel()), tgt_rowptr, tgt_idx,
+                                  self._scratch, self._scratch_bytes, stream)
+        _check(rc, "dgn_target_digest")
+        return d
+
+    def prune(self, tgt_rowptr, tgt_idx, options=None, stream=None) -> "PruneBuffers":
+        """The buffers that hold the result for these target sets (pruned now, or found)."""
+        key = self.digest(tgt_rowptr, tgt_idx, stream)
+        buf = self._entries.pop(key, None)
+        if buf is not None:
+            self.hits += 1
+        else:
+            self.misses += 1
+            if len(self._entries) >= self.capacity:
+                _, buf = next(iter(self._entries.items()))            # least recently used: its buffers are recycled
+                del self._entries[next(iter(self._entries))]
+            else:
+                buf = PruneBuffers(self.graph, self.num_sets, self._device)
+            _check(buf.prune(tgt_rowptr, tgt_idx, options=options, stream=stream), "dgn_prune")
+        self._entries[key] = buf                                       # most recently used last
+        return buf
 
 
 class InplaceBuffers:

@@ -1038,6 +1038,36 @@ int dgn_per_set_lists(const int32_t *kept_ops, const uint64_t *kept_masks, int64
     return DGN_OK;
 }
 
+int dgn_target_digest_workspace(size_t *scratch_bytes)
+{
+    if (!scratch_bytes) return DGN_ERR_NULL_PTR;
+    *scratch_bytes = digest_scratch_bytes();
+    return DGN_OK;
+}
+
+int dgn_target_digest(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const int32_t *tgt_rowptr,
+                      const int32_t *tgt_idx, uint64_t *digest_out, void *scratch, size_t scratch_bytes, dgn_stream stream)
+{
+    if (!g || !tgt_rowptr || !digest_out || !scratch) return DGN_ERR_NULL_PTR;
+    if (num_sets < 1 || num_sets > DGN_MAX_SETS) return DGN_ERR_TOO_MANY_SETS;
+    if (num_targets < 0) return DGN_ERR_INVALID_ARG;
+    if (num_targets > kMaxCount) return DGN_ERR_TOO_LARGE;
+    if (num_targets > 0 && !tgt_idx) return DGN_ERR_NULL_PTR;
+    if (scratch_bytes < digest_scratch_bytes()) return DGN_ERR_WORKSPACE_TOO_SMALL;
+    if ((uintptr_t)scratch & 7) return DGN_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    u64 *dev = nullptr;
+    DGN_HIP(launch_target_digest(num_sets, (int64_t)num_sets * g->G, tgt_rowptr, num_targets, tgt_idx, scratch, &dev, s));
+    void *pin = nullptr;
+    const int rc = pinned_buffer(&pin);
+    if (rc != DGN_OK) return rc;
+    DGN_HIP(hipMemcpyAsync(pin, dev, 2 * sizeof(u64), hipMemcpyDeviceToHost, s));
+    DGN_HIP(hipStreamSynchronize(s));
+    digest_out[0] = static_cast<const u64 *>(pin)[0];
+    digest_out[1] = static_cast<const u64 *>(pin)[1];
+    return DGN_OK;
+}
+
 int dgn_inplace_workspace(const dgn_graph *g, size_t *scratch_bytes)
 {
     if (!g || !scratch_bytes) return DGN_ERR_NULL_PTR;

@@ -279,6 +279,12 @@ size_t set_lists_scratch_bytes(int64_t num_kept);
 hipError_t launch_set_lists(const int32_t *kept_ops, const u64 *kept_masks, int64_t num_kept, int64_t *set_rowptr,
                             int32_t *set_ops, int64_t capacity, void *scratch, int grid_blocks, hipStream_t s);
 
+// Key of a transaction (Sec. 4.1): 128-bit digest of the target sets; *digest_dev points into `scratch`.
+constexpr int kDigestMaxBlocks = 1024;
+size_t digest_scratch_bytes();
+hipError_t launch_target_digest(int32_t num_sets, int64_t n, const int32_t *tgt_rowptr, int64_t num_targets,
+                                const int32_t *tgt_idx, void *scratch, u64 **digest_dev, hipStream_t s);
+
 // Backward Prune (Algorithm 2): target row pointers 0..n (rowptr_only) or the seeds of the forward stage;
 // one pass of the forward stage over the kept operators of the first stage.
 hipError_t launch_backward_seed(int64_t T, int num_pairs, const int32_t *obj, const int32_t *wrt, int32_t *tgt_rowptr,

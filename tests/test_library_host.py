@@ -121,3 +121,9 @@ def test_other_entry_points_reject_bad_arguments_before_any_device_work(d):
     assert d.dgn_per_set_lists(None, None, 0, None, None, 0, None, 0, stream=0) == d.DGN_ERR_NULL_PTR
     assert d.dgn_prune_words(None, 100, 0, None, None, None, None, None, None, None, None, None, None, 0, stream=0) == d.DGN_ERR_NULL_PTR
     assert d.dgn_options(incremental=1).incremental == 1
+    rc, nbytes = d.dgn_target_digest_workspace()
+    assert rc == 0 and nbytes >= 16
+    rc, _ = d.dgn_target_digest(None, 4, 0, None, None, None, 0, stream=0)
+    assert rc == d.DGN_ERR_NULL_PTR
+    o = d.dgn_options(recycle=1, profile=2)
+    assert (o.recycle, o.profile) == (1, 2) and d.dgn_stats().recycled == 0
