@@ -304,6 +304,7 @@ __global__ __launch_bounds__(256) void k_reduce_pq(CompactArgs a)
     if (lane == 0) a.per_query_count[i] = v;
 }
 
+constexpr int kScanVecs = 16;             // int4 per thread that the tile scan keeps in registers
 constexpr int kFoldPqOutputs = 256;      // up to this many per-set counters are summed by the scan kernel itself
 
 // Single workgroup: exclusive scan of the tile counts in place, total -> counts[m] and kept_count[0].
@@ -332,19 +333,32 @@ __global__ __launch_bounds__(1024) void k_scan_tiles(int32_t *counts, int64_t m,
             }
         }
     }
-    // runs are a multiple of four counts long and start 16-byte aligned: int4 loads, all of them in flight at once
+    // runs are a multiple of four counts long and start 16-byte aligned.  Up to kScanVecs int4 per thread (tile
+    // counts of 134 million operators) stay in registers between the two passes: all loads in flight at once, one
+    // trip to memory in all; longer runs are read twice.
     const int64_t per = (((m + 1023) / 1024) + 3) & ~(int64_t)3;
     const int64_t lo = (int64_t)threadIdx.x * per;
     const int64_t hi = lo + per < m ? lo + per : m;
+    const bool in_regs = per <= 4 * kScanVecs;
+    int4 v[kScanVecs];
     int sum = 0;
-#pragma unroll 4
-    for (int64_t i = lo; i < hi; i += 4) {
-        if (i + 4 <= m) {
-            const int4 v = *reinterpret_cast<const int4 *>(counts + i);
-            sum += v.x + v.y + v.z + v.w;
-        } else {
-            for (int64_t j = i; j < m; ++j) sum += counts[j];
+    if (in_regs) {
+#pragma unroll
+        for (int j = 0; j < kScanVecs; ++j) {
+            const int64_t i = lo + 4 * j;
+            v[j] = make_int4(0, 0, 0, 0);
+            if (i + 4 <= hi) {
+                v[j] = *reinterpret_cast<const int4 *>(counts + i);
+            } else if (i < hi) {                         // the ragged end of the array: one by one
+                v[j].x = counts[i];
+                if (i + 1 < hi) v[j].y = counts[i + 1];
+                if (i + 2 < hi) v[j].z = counts[i + 2];
+            }
         }
+#pragma unroll
+        for (int j = 0; j < kScanVecs; ++j) sum += v[j].x + v[j].y + v[j].z + v[j].w;
+    } else {
+        for (int64_t i = lo; i < hi; ++i) sum += counts[i];
     }
     const int incl = wave_incl_scan(sum);
     if (lane == kWave - 1) wtot[wave] = incl;
@@ -357,18 +371,25 @@ __global__ __launch_bounds__(1024) void k_scan_tiles(int32_t *counts, int64_t m,
         tot += c;
     }
     int run = woff + incl - sum;
-#pragma unroll 4
-    for (int64_t i = lo; i < hi; i += 4) {
-        if (i + 4 <= m) {
-            const int4 v = *reinterpret_cast<const int4 *>(counts + i);
-            *reinterpret_cast<int4 *>(counts + i) = make_int4(run, run + v.x, run + v.x + v.y, run + v.x + v.y + v.z);
-            run += v.x + v.y + v.z + v.w;
-        } else {
-            for (int64_t j = i; j < m; ++j) {
-                const int c = counts[j];
-                counts[j] = run;
-                run += c;
+    if (in_regs) {
+#pragma unroll
+        for (int j = 0; j < kScanVecs; ++j) {
+            const int64_t i = lo + 4 * j;
+            const int4 o = make_int4(run, run + v[j].x, run + v[j].x + v[j].y, run + v[j].x + v[j].y + v[j].z);
+            run += v[j].x + v[j].y + v[j].z + v[j].w;
+            if (i + 4 <= hi) {
+                *reinterpret_cast<int4 *>(counts + i) = o;
+            } else if (i < hi) {
+                counts[i] = o.x;
+                if (i + 1 < hi) counts[i + 1] = o.y;
+                if (i + 2 < hi) counts[i + 2] = o.z;
             }
+        }
+    } else {
+        for (int64_t i = lo; i < hi; ++i) {
+            const int c = counts[i];
+            counts[i] = run;
+            run += c;
         }
     }
     if (threadIdx.x == 0) {

@@ -402,7 +402,7 @@ constexpr int kLevelThreads = 256;
 constexpr int kLevelWaves = kLevelThreads / kWave;
 constexpr int kChaseBelow = 32768;                 // frontiers up to this size get a second hop in the same launch ...
 constexpr int kChaseAlwaysBelow = 8192;            // ... or, while the deferral threshold is still coming down, up to this size
-constexpr int kChasePerWave = 8;                   // ... with about this many entries dealt to a wave
+constexpr int kThinPerWave = 8;                    // ... with about this many entries dealt to a wave
 constexpr int kChunkOps = 16 * 64;                 // at most 16 deferred-bitmap words are expanded per wave step
 
 struct LevelShared {
@@ -426,7 +426,9 @@ struct LevelPlan {
     int nwork;           // blocks that have something to do
     int per_wave;        // 0: every wave takes 64 entries at a time.  Else (small frontier) the entries are dealt
                          // thinly, per_wave to a wave, so that what a wave pushes fits one more step of its own:
-                         // it then expands those pushes itself, a second hop within the same launch
+                         // it then expands those pushes itself, a second hop within the same launch.  (Dealing
+                         // every level thinly, to shorten the rounds of 64 edges a wave goes through, was slower:
+                         // twice the waves flushing, tallying and loading half-empty.)
 };
 
 __device__ __forceinline__ LevelPlan plan_level(const LevelSlot &in, int n, bool ranges_left, int grid)
@@ -441,14 +443,14 @@ __device__ __forceinline__ LevelPlan plan_level(const LevelSlot &in, int n, bool
     p.nb_e = (n + kLevelThreads - 1) / kLevelThreads;
     p.nb_s = (p.chunks + kLevelWaves - 1) / kLevelWaves;
     p.per_wave = 0;
-    // (not while the threshold is still coming down: it takes one step per launch, so the number of launches is
-    // set by its schedule and a second hop would only make each of them longer)
+    // (no second hop for larger frontiers while the threshold is still coming down: it takes one step per launch,
+    // so the number of launches is set by its schedule and a second hop would only make each of them longer)
     if (n > 0 && (n <= kChaseAlwaysBelow || (n <= kChaseBelow && in.theta <= 0)) && p.nb_s < grid) {
         const int room = grid - p.nb_s;
-        const int want = (n + kLevelWaves * kChasePerWave - 1) / (kLevelWaves * kChasePerWave);
+        const int want = (n + kLevelWaves * kThinPerWave - 1) / (kLevelWaves * kThinPerWave);
         const int nb = min(room, want);
         const int per = (n + nb * kLevelWaves - 1) / (nb * kLevelWaves);
-        if (per <= 2 * kChasePerWave) {
+        if (per <= 2 * kThinPerWave) {
             p.nb_e = nb;
             p.per_wave = per;
         }
