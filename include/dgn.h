@@ -131,7 +131,7 @@ typedef struct dgn_options {
 
 /* Indices into dgn_stats.phase_ms */
 enum {
-    DGN_PHASE_CLEAR = 0,     /* clear of M, K, frontier bitmaps and state (one kernel)            */
+    DGN_PHASE_CLEAR = 0,     /* M, K, marker and flag bytes, state zeroed (all, or what the last call set) */
     DGN_PHASE_SEED = 1,      /* target bits scattered, first frontier built (one kernel)          */
     DGN_PHASE_TRAVERSE = 2,  /* all frontier levels                                               */
     DGN_PHASE_COUNT = 3,     /* removal rule / flags / per-tile and per-set counts (one kernel)   */
@@ -144,7 +144,7 @@ enum {
 /* Schedule-dependent counters (not part of the result; excluded from parity). HOST struct. */
 typedef struct dgn_stats {
     int64_t levels;          /* frontier levels processed                                        */
-    int64_t tensor_visits;   /* frontier entries processed, summed over levels                   */
+    int64_t tensor_visits;   /* frontier entries and deferred operators expanded, summed over levels */
     int64_t max_frontier;    /* largest frontier                                                 */
     int64_t launches;        /* kernels enqueued by the call                                     */
     int64_t level_launches;  /* of which frontier-level kernels                                  */
@@ -156,7 +156,7 @@ typedef struct dgn_stats {
     int64_t reserved;        /* dgn_backward_prune: passes of its forward stage; 0 otherwise                */
     int64_t recycled;        /* 1 when options->recycle found the previous result in place and the call
                                 zeroed only what that result had set                               */
-    float phase_ms[DGN_NUM_PHASES];   /* filled when options->profile; zero otherwise           */
+    float phase_ms[DGN_NUM_PHASES];   /* filled when options->profile is 1 (all) or 2 (traversal); zero otherwise */
 } dgn_stats;
 
 /* ---- graph construction -------------------------------------------------------------------- */
@@ -222,7 +222,8 @@ int dgn_prune_workspace(const dgn_graph *g, int32_t num_sets, size_t *scratch_by
  *       may be NULL.
  *   options, stats: HOST, may be NULL.
  *
- * All outputs are cleared and rewritten in full by the call.  Kernels run on `stream`; the call
+ * All outputs are cleared (see options->recycle) and rewritten in full by the call; op_flag may already be
+ * written while the traversal runs and is complete, like everything else, on return.  Kernels run on `stream`; the call
  * reads a few status words back and synchronises the stream before returning, because the number
  * of frontier levels depends on the data.  Calls on the same graph may run concurrently only with
  * distinct scratch and output buffers. */
