@@ -85,6 +85,33 @@ def test_recycled_prunes_of_a_graph_large_enough_for_the_flag_driven_count_pass(
     torch.cuda.synchronize()
 
 
+def test_recycled_prunes_of_a_small_packed_batch(dgn, oracle):
+    """Eight packed graphs go through the frontier traversal (the per-graph sweep starts at 64 graphs): the log,
+    the per-graph kept offsets and the per-graph set counts must all survive recycling."""
+    g, tg = gg.config(4, 0.002)
+    assert 1 < g.num_graphs < 64
+    dg = dgn.DeviceGraph.from_coo(g)
+    buf = dgn.PruneBuffers(dg, tg.num_sets)
+    adj, _ = oracle_prune(oracle, g, tg)
+    Q, G = tg.num_sets, g.num_graphs
+    draws = [tg]
+    for i in range(1, 4):                                   # other targets, each inside its own graph
+        sets = []
+        for gi in range(G):
+            lo, hi = int(g.graph_tensor_offsets[gi]), int(g.graph_tensor_offsets[gi + 1])
+            one = gg.targets_range(500 + 10 * i + gi, Q, 0, 3, lo, hi)
+            sets += [list(one.tgt_idx[one.tgt_rowptr[q]:one.tgt_rowptr[q + 1]]) for q in range(Q)]
+        rowptr = np.concatenate([[0], np.cumsum([len(x) for x in sets])]).astype(np.int32)
+        draws.append(gg.Targets(Q, rowptr, np.asarray([t for x in sets for t in x], np.int32)))
+    seen = []
+    for i, t in enumerate(draws):
+        st = _prune(dgn, buf, t)
+        ref = oracle.forward_prune(adj, Q, t.tgt_rowptr, t.tgt_idx, G, g.graph_op_offsets)
+        assert_same(buf.to_host(), ref, f"call {i}")
+        seen.append(int(st.recycled))
+    assert seen == [0, 0, 1, 1]
+
+
 def test_recycle_survives_schedule_knobs_and_the_standalone_keep_pass(dgn, oracle):
     g, tg = gg.config(3, 0.02)
     dg = dgn.DeviceGraph.from_coo(g)
