@@ -348,7 +348,9 @@ def main():
     levels = max(1, int(st.levels))
     alg = {
         # all of M and K, or (recycled buffers) the log and the kept list read, their M, K and marker words zeroed
-        "k_clear": (12 * T_c + 13 * P_k) if recycled else (8 * T + 8 * P),
+        # (a packed batch swept per graph stores K of every operator: only M is cleared)
+        "k_clear": (12 * T_c + 13 * P_k) if recycled else (8 * T) if int(st.levels) == 0 and g.num_graphs >= 64
+                   else (8 * T + 8 * P),
         "k_level": (4 * T_c + 8 * P_k + 4 * E_k + 16 * E_k + 16 * P_k) / levels,
         # stand-alone: K from M; large single graphs: keep flags (P bytes) read, K of the kept operators, bitmap
         # written; else all of K read, flags written

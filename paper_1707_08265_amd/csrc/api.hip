@@ -575,8 +575,9 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
         DGN_HIP(launch_clear(small, 5, s));
         ++launches;
     } else {
-        FillRegion clr[8] = {{M, incremental ? 0 : (size_t)g->T * 8}, {K, incremental ? 0 : (size_t)g->P * 8},
-                             {S.DB, S.db_bytes}, {S.state, 256 + sizeof(TravCounters)}, {S.hdr, 256},
+        // (the per-graph sweep stores K of every operator and uses no markers: it needs M cleared, nothing else)
+        FillRegion clr[8] = {{M, incremental ? 0 : (size_t)g->T * 8}, {K, incremental || sweep ? 0 : (size_t)g->P * 8},
+                             {S.DB, sweep ? 0 : S.db_bytes}, {S.state, 256 + sizeof(TravCounters)}, {S.hdr, 256},
                              {per_query_count, pq_bytes}, {S.pq_part, per_query_count ? S.pq_part_bytes : 0},
                              {flags, use_flags ? flag_bytes : 0}};
         DGN_HIP(launch_clear(clr, 8, s));
