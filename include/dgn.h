@@ -116,8 +116,8 @@ typedef struct dgn_options {
                                 must be such a result: anything else gives unspecified masks             */
     int32_t recycle;         /* prune: the caller states that nothing but dgn_prune has written to `scratch`
                                 since it last passed it to this library, and that, if the last such call
-                                was a dgn_prune of this graph with this tensor_mask, op_mask, kept_ops and
-                                kept_count, those four are still as that call left them.  The call then
+                                was a dgn_prune of this graph with this tensor_mask, op_mask, op_flag,
+                                kept_ops and kept_count, those are still as that call left them.  The call then
                                 zeroes only the words that call set (it finds them through a log the
                                 earlier call kept in `scratch`, and checks on the device that graph and
                                 buffers are the same) instead of all of tensor_mask and op_mask, and keeps
