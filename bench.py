@@ -193,7 +193,29 @@ def main():
         full_clear = {"ms_per_step": round(ms2, 4), "gteps": round(E / (ms2 * 1e-3) / 1e9, 2)}
         log(f"prune with a full clear per step: {ms2:.3f} ms/step, {full_clear['gteps']:.1f} GTEPS")
         del buf2
-        rc = buf.prune(rowptr, idx, options=opts, stats=st)      # st describes the recycled path again
+    # recycled buffers with target sets that change from step to step (a second draw of the same recipe, taken in
+    # turns with the workload's own): no step finds anything of its own result in place, only words to zero
+    other_targets = None
+    if recycled and not args.prune_only and g.num_graphs == 1 and args.config == 3:
+        tg2 = gg.targets_tail(g, gg.BASE_SEED + 3000 + 1, tg.num_sets, 1, 16, 0.05)
+        rowptr2, idx2 = up(tg2.tgt_rowptr), up(tg2.tgt_idx)
+        pairs = [(rowptr, idx), (rowptr2, idx2)]
+        for i in range(4):
+            rc = buf.prune(*pairs[i & 1], options=opts, stats=st)
+            assert rc == 0, d.dgn_strerror(rc)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for i in range(args.steps):
+            rc = buf.prune(*pairs[i & 1], options=opts, stats=st)
+        torch.cuda.synchronize()
+        ms3 = (time.perf_counter() - t2) / args.steps * 1e3
+        assert rc == 0 and st.recycled
+        other_targets = {"ms_per_step": round(ms3, 4), "gteps": round(E / (ms3 * 1e-3) / 1e9, 2),
+                         "targets": "the workload's and a second draw of the same recipe, in turns"}
+        log(f"prune, recycled buffers, two target draws in turns: {ms3:.3f} ms/step, {other_targets['gteps']:.1f} GTEPS")
+        del rowptr2, idx2
+    if recycled and not args.prune_only:
+        rc = buf.prune(rowptr, idx, options=opts, stats=st)      # st and the buffers describe the timed workload again
         assert rc == 0
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -448,6 +470,7 @@ def main():
         "backward_prune": backward,
         "incremental_prune": incremental,
         "full_clear_per_step": full_clear,
+        "recycled_alternating_targets": other_targets,
         "transaction_cache": transaction,
         "build_plus_prune_gteps": round(E / ((build_ms + ms_per_step) * 1e-3) / 1e9, 2),
         "result": {"kept_ops": P_k, "coloured_tensors": T_c, "kept_in_edges": E_k, "kept_out_edges": Eo_k,
