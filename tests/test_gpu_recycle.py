@@ -112,6 +112,34 @@ def test_recycled_prunes_of_a_small_packed_batch(dgn, oracle):
     assert seen == [0, 0, 1, 1]
 
 
+def test_swept_batches_ignore_the_flag_and_clear_what_they_must(dgn, oracle):
+    """64 graphs and more are swept graph by graph: no log is kept, the flag has no effect, and since the sweep
+    stores K of every operator only M is cleared -- buffers full of an earlier result, or of garbage, must not
+    show in the next one."""
+    g, tg = gg.config(4, 0.02)
+    assert g.num_graphs >= 64
+    dg = dgn.DeviceGraph.from_coo(g)
+    buf = dgn.PruneBuffers(dg, tg.num_sets)
+    adj, ref = oracle_prune(oracle, g, tg)
+    Q, G = tg.num_sets, g.num_graphs
+    # a second draw: every other set of every graph empty
+    cnt = np.diff(tg.tgt_rowptr)
+    cnt2 = cnt.copy()
+    cnt2[::2] = 0
+    rowptr2 = np.concatenate([[0], np.cumsum(cnt2)]).astype(np.int32)
+    idx2 = np.concatenate([tg.tgt_idx[tg.tgt_rowptr[s]:tg.tgt_rowptr[s] + cnt2[s]] for s in range(len(cnt))] +
+                          [np.zeros(0, np.int32)]).astype(np.int32)
+    t2 = gg.Targets(Q, rowptr2, idx2)
+    ref2 = oracle.forward_prune(adj, Q, t2.tgt_rowptr, t2.tgt_idx, G, g.graph_op_offsets)
+    for i, (t, r) in enumerate([(tg, ref), (t2, ref2), (tg, ref)]):
+        if i == 2:
+            buf.op_mask.fill_(-1)                           # K is not cleared by the library: the sweep must store all of it
+            buf.op_flag.fill_(7)
+        st = _prune(dgn, buf, t)
+        assert int(st.recycled) == 0
+        assert_same(buf.to_host(), r, f"call {i}")
+
+
 def test_recycle_survives_schedule_knobs_and_the_standalone_keep_pass(dgn, oracle):
     g, tg = gg.config(3, 0.02)
     dg = dgn.DeviceGraph.from_coo(g)
