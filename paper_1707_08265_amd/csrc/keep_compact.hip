@@ -398,7 +398,60 @@ __global__ __launch_bounds__(1024) void k_scan_tiles(int32_t *counts, int64_t m,
     }
 }
 
+// A wave takes a tile.  With few kept operators in it (the usual case on a large pruned graph: a few dozen of
+// 2 048) lane w < 32 walks the set bits of bitmap word w; with many, the 64 lanes take one word at a time, lane =
+// bit.  No shared memory, no barrier; a tile with nothing kept costs two loads.
+constexpr int kScatterByBitsBelow = 192;
+constexpr int64_t kScatterByWaveAboveTiles = 16384;     // 33 million operators
+
 __global__ __launch_bounds__(kCThreads) void k_scatter(CompactArgs a)
+{
+    const GraphView &g = a.g;
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    // last pass of a prune: say in the scratch buffer which buffers now hold a result with a complete log
+    if (a.hdr && blockIdx.x == 0 && threadIdx.x == 0 && *a.error == 0) *a.hdr = a.want;
+    const int64_t tiles = ((int64_t)g.num_ops + kCompactTile - 1) / kCompactTile;
+    const int64_t tile = (int64_t)blockIdx.x * kCWaves + wave;
+    if (tile >= tiles) return;
+    const int64_t tile_base = tile * kCompactTile;
+    const int64_t n_words = ((int64_t)g.num_ops + 63) >> 6;
+    const int64_t word_base = tile_base >> 6;
+    const int base = a.block_counts[tile];
+    const int kept = a.block_counts[tile + 1] - base;
+    if (kept == 0) return;                                  // wave-uniform
+
+    // exclusive prefix of the popcounts of the tile's 32 bitmap words
+    u64 w = 0;
+    if (lane < kCWords && word_base + lane < n_words) w = a.opbits[word_base + lane];
+    const int c = __popcll(w);
+    const int off = wave_incl_scan(c) - c;
+    if (kept < kScatterByBitsBelow) {
+        int pos = base + off;
+        while (w) {
+            const int b = __builtin_ctzll(w);
+            w &= w - 1;
+            const int64_t o = tile_base + (int64_t)lane * kWave + b;
+            a.kept_ops[pos] = (int32_t)o;
+            if (a.kept_masks) a.kept_masks[pos] = a.K[o];
+            ++pos;
+        }
+    } else {
+        for (int wi = 0; wi < kCWords; ++wi) {
+            const u64 word = shfl64(w, wi);
+            const int woff = __shfl(off, wi, kWave);
+            if ((word >> lane) & 1) {
+                const int64_t o = tile_base + (int64_t)wi * kWave + lane;
+                const int pos = base + woff + __popcll(word & lanemask_lt());
+                a.kept_ops[pos] = (int32_t)o;
+                if (a.kept_masks) a.kept_masks[pos] = a.K[o];
+            }
+        }
+    }
+}
+
+// The same with a workgroup per tile, four bitmap words in flight per step: for graphs of so few tiles that a wave
+// per tile would leave most of the chip idle.
+__global__ __launch_bounds__(kCThreads) void k_scatter_block(CompactArgs a)
 {
     __shared__ int s_off[kCWords];
     const GraphView &g = a.g;
@@ -407,12 +460,9 @@ __global__ __launch_bounds__(kCThreads) void k_scatter(CompactArgs a)
     const int64_t n_words = ((int64_t)g.num_ops + 63) >> 6;
     const int64_t word_base = tile_base >> 6;
     const int base = a.block_counts[blockIdx.x];
-    // last pass of a prune: say in the scratch buffer which buffers now hold a result with a complete log
     if (a.hdr && blockIdx.x == 0 && threadIdx.x == 0 && *a.error == 0) *a.hdr = a.want;
     if (a.block_counts[blockIdx.x + 1] == base) return;     // nothing kept in this tile (uniform)
-
-    // exclusive prefix of the popcounts of this tile's 32 bitmap words (wave 0)
-    if (wave == 0) {
+    if (wave == 0) {                                        // exclusive prefix of the popcounts of the tile's words
         u64 w = 0;
         if (lane < kCWords && word_base + lane < n_words) w = a.opbits[word_base + lane];
         const int c = __popcll(w);
@@ -472,7 +522,10 @@ hipError_t launch_keep_compact(const CompactArgs &a, hipStream_t s, hipEvent_t *
     if (ev) (void)hipEventRecord(ev[0], s);
     hipLaunchKernelGGL(k_scan_tiles, dim3(1), dim3(1024), 0, s, a.block_counts, tiles, a.kept_count, a, fold_pq);
     if (ev) (void)hipEventRecord(ev[1], s);
-    if (tiles > 0) hipLaunchKernelGGL(k_scatter, dim3((unsigned)tiles), dim3(kCThreads), 0, s, a);
+    if (tiles > kScatterByWaveAboveTiles)
+        hipLaunchKernelGGL(k_scatter, dim3((unsigned)((tiles + kCWaves - 1) / kCWaves)), dim3(kCThreads), 0, s, a);
+    else if (tiles > 0)
+        hipLaunchKernelGGL(k_scatter_block, dim3((unsigned)tiles), dim3(kCThreads), 0, s, a);
     if (a.g.num_graphs > 1)
         hipLaunchKernelGGL(k_graph_offsets, dim3((unsigned)((a.g.num_graphs + 1 + 255) / 256)), dim3(256), 0, s, a);
     if (ev) (void)hipEventRecord(ev[2], s);
