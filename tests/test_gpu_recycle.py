@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 
 import graphgen as gg
+from helpers import random_small_graph, targets_from_sets
 from test_gpu_parity import assert_same, oracle_prune
 
 pytestmark = pytest.mark.gpu
@@ -138,6 +139,47 @@ def test_swept_batches_ignore_the_flag_and_clear_what_they_must(dgn, oracle):
         st = _prune(dgn, buf, t)
         assert int(st.recycled) == 0
         assert_same(buf.to_host(), r, f"call {i}")
+
+
+@pytest.mark.parametrize("multi", [False, True])
+def test_random_graphs_random_call_sequences(dgn, oracle, multi):
+    """Small random graphs with the awkward cases (operators without inputs or outputs, duplicate edges, several
+    producers of a tensor), each pruned several times through the same buffers for random target sets and with
+    random schedule knobs, queue caps that force the overflow path, the stand-alone keep pass and incremental
+    calls mixed in: every call against the oracle."""
+    rng = np.random.default_rng(4242 + multi)
+    for trial in range(12):
+        P = int(rng.integers(1, 3000)) if trial % 3 else int(rng.integers(1, 60))
+        g, _ = random_small_graph(rng, P, num_inputs=int(rng.integers(1, 6)), multi_producer=multi)
+        Q = int(rng.integers(1, 65))
+        dg = dgn.DeviceGraph.from_coo(g)
+        buf = dgn.PruneBuffers(dg, Q)
+        adj = oracle.build_adjacency(g.num_ops, g.num_tensors, g.in_op, g.in_tensor, g.out_op, g.out_tensor)
+        prev_sets = None
+        for call in range(5):
+            incremental = prev_sets is not None and rng.random() < 0.2
+            if incremental:                                 # earlier sets plus more targets: a superset, set by set
+                sets = [s + [int(rng.integers(0, g.num_tensors)) for _ in range(int(rng.integers(0, 3)))] for s in prev_sets]
+            else:
+                sets = [[int(rng.integers(0, g.num_tensors)) for _ in range(int(rng.integers(0, 5)))] for _ in range(Q)]
+            t = targets_from_sets(sets)
+            knobs = {}
+            if incremental:
+                knobs["incremental"] = 1
+            r = rng.random()
+            if r < 0.2:
+                knobs["traversal"] = int(rng.integers(1, 3))
+            elif r < 0.4:
+                knobs["defer_percent"] = int(rng.integers(30, 99))
+                knobs["defer_floor_shift"] = int(rng.integers(1, 12))
+            elif r < 0.5:
+                knobs["max_queue_entries"] = int(rng.integers(1, 64))
+            elif r < 0.6 and not incremental:
+                knobs["recompute_keep"] = 1
+            _prune(dgn, buf, t, **knobs)
+            ref = oracle.forward_prune(adj, Q, t.tgt_rowptr, t.tgt_idx)
+            assert_same(buf.to_host(), ref, f"multi={multi} trial {trial} call {call} {knobs}")
+            prev_sets = sets
 
 
 def test_recycle_survives_schedule_knobs_and_the_standalone_keep_pass(dgn, oracle):
