@@ -196,6 +196,7 @@ __global__ __launch_bounds__(kCThreads) void k_keep_count(CompactArgs a)
 // of the kept operators go through a small list in LDS, and K is read for 64 of them at a time for the per-set
 // counts -- about P/8 + 8 P_kept bytes of traffic instead of 9P, and no barrier anywhere.
 constexpr int kPendCap = 128;
+constexpr int64_t kFlagsCountGrid = 8192;
 // Below this many operators all of K is a few microseconds of reading, and the kernel that reads it is the
 // faster one where most operators are kept (it needs no list of kept ids).
 constexpr int64_t kFlagsCountMinOps = (int64_t)1 << 22;
@@ -509,7 +510,12 @@ hipError_t launch_keep_compact(const CompactArgs &a, hipStream_t s, hipEvent_t *
             hipLaunchKernelGGL((k_keep_count<true, false>), dim3((unsigned)count_grid), dim3(kCThreads), 0, s, a);
         else if (a.flag_in && a.g.num_graphs == 1 && (a.op_flag == nullptr || a.op_flag == a.flag_in) &&
                  P >= kFlagsCountMinOps)
-            hipLaunchKernelGGL(k_keep_count_flags, dim3((unsigned)count_grid), dim3(kCThreads), 0, s, a);
+        {
+            // a wave takes whole tiles: up to kFlagsCountGrid workgroups, so that most waves have one tile only
+            const int64_t wg = (tiles + kCWaves - 1) / kCWaves;
+            const int64_t flags_grid = wg < kFlagsCountGrid ? wg : kFlagsCountGrid;
+            hipLaunchKernelGGL(k_keep_count_flags, dim3((unsigned)flags_grid), dim3(kCThreads), 0, s, a);
+        }
         else if (a.flag_in)
             hipLaunchKernelGGL((k_keep_count<false, true>), dim3((unsigned)count_grid), dim3(kCThreads), 0, s, a);
         else
