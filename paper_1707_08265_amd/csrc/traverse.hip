@@ -89,6 +89,8 @@ struct Frontier {     // where one wave pushes
     int32_t *log;     // start of the wave's segment of the log of coloured tensors, or NULL: no log
     int32_t *log_cnt; // that segment's counter
     int32_t log_cap;
+    int32_t *mirror;  // NULL, or an array in LDS that receives a copy of the first mirror_cap entries of the segment
+    int32_t mirror_cap;   // (the single-workgroup kernel reads its next frontier from there, not from memory)
 };
 
 // Write the pending entries out to the wave's queue segment.
@@ -102,9 +104,11 @@ __device__ __forceinline__ void flush_entries(WaveStage &ws, const Frontier &f)
             if (base + n > f.seg_cap) atomicOr(f.error, kErrOverflow);   // (I3): fix-up sweep will follow
         }
         base = __builtin_amdgcn_readfirstlane(base);
-        for (int k = lane_id(); k < n; k += kWave)
-            if (base + k < f.seg_cap)
-                store_coherent(&f.seg[base + k], ws.buf[(ws.head + k) & (kStageCap - 1)]);   // read by other blocks
+        for (int k = lane_id(); k < n; k += kWave) {
+            const int32_t v = ws.buf[(ws.head + k) & (kStageCap - 1)];
+            if (base + k < f.seg_cap) store_coherent(&f.seg[base + k], v);   // read by other blocks
+            if (base + k < f.mirror_cap) f.mirror[base + k] = v;
+        }
         ws.head = ws.tail;
     }
 }
@@ -665,7 +669,8 @@ __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState 
     const int seg = (blockIdx.x * kLevelWaves + wave) & (qg.S - 1);
     const int lseg = (blockIdx.x * kLevelWaves + wave) & (kMaxSeg - 1);
     const Frontier f{qout + (int64_t)seg * qg.seg_cap, &ctr->cnt[mine][seg].v, qg.seg_cap, &st->error,
-                     log.entries ? log.entries + (int64_t)lseg * log.seg_cap : nullptr, &log.cnt[lseg].v, log.seg_cap};
+                     log.entries ? log.entries + (int64_t)lseg * log.seg_cap : nullptr, &log.cnt[lseg].v, log.seg_cap,
+                     nullptr, 0};
     run_level(g, in, n, p, (int)blockIdx.x, qin, qg, f, DB, flags, M, K, sh, ctr->cnt[mine]);
 }
 
@@ -684,6 +689,7 @@ hipError_t launch_level(const GraphView &g, TravState *st, TravCounters *ctr, in
 // ------------------------------------------------------------------------------------------------
 constexpr int kNarrowThreads = 1024;
 constexpr int kNarrowWaves = kNarrowThreads / kWave;
+constexpr int kNarrowFront = 1024;      // entries of a frontier that the kernel also keeps in LDS
 
 __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravState *st, TravCounters *ctr, int launch_no,
                                                             int32_t *q0, int32_t *q1, QueueGeom qg, uint8_t *DB,
@@ -697,10 +703,15 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
     __shared__ int s_pref[kMaxSeg + 1];
     __shared__ int s_derived[2];
     __shared__ int s_nout;
+    // The frontier a level builds is also kept here: the next level -- at most kNarrowFront entries, or this
+    // kernel does not run it -- takes it from LDS and need not wait for its own queue stores to reach memory.
+    __shared__ int32_t s_front[2][kNarrowFront];
 
     const LevelSlot prev_rec = st->slot[(launch_no + 1) & 1];
     int tot_proc = 0;
     LevelSlot in = derive_state(st, ctr, launch_no, qg, sch, s_pref, s_derived, &tot_proc);
+    const bool use_mirror = narrow_cap <= kNarrowFront;
+    bool from_lds = false;
     int level = in.level;
     int n = in.n;
     const bool ranges_left = in.deferred_seen && in.theta_hi > 0;   // then the wide kernel must go on
@@ -715,30 +726,32 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
         const int32_t *qin = cur ? q1 : q0;
         const Frontier f{cur ? q0 : q1, &s_nout, qg.seg_cap, &st->error,    // everything goes to segment 0
                          log.entries ? log.entries + (int64_t)wave * log.seg_cap : nullptr, &log.cnt[wave].v,
-                         log.seg_cap};
+                         log.seg_cap, use_mirror ? &s_front[cur ^ 1][0] : nullptr, use_mirror ? kNarrowFront : 0};
         for (int base = 0; base < n; base += kNarrowThreads) {
             const int i = base + threadIdx.x;
             const bool valid = i < n;
-            const int32_t t = valid ? load_item(qin, qg, s_pref, i) : 0;
+            const int32_t t = !valid ? 0 : from_lds ? s_front[cur][i] : load_item(qin, qg, s_pref, i);
             // threshold 0: a small frontier is latency bound, so nothing is gained by deferring
             process_entries(g, valid, t, 0, DB, flags, M, K, &s_incl[wave][0], ws, f, lc, false);
         }
         flush_entries(ws, f);
-        // the block's queue stores must have completed before they are re-read (with cache-bypassing
-        // loads) by other waves of this same block; no other block reads them before the kernel ends
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        // without the copy in LDS the block's queue stores must have completed before other waves of this same
+        // block re-read them (with cache-bypassing loads); no other block reads them before the kernel ends
+        if (!use_mirror) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __syncthreads();
         visits += (u64)n;
         if ((u64)n > maxf) maxf = (u64)n;
         if (trace && threadIdx.x == 0 && level < kTraceLevels) trace[level] = make_int4(n, n, -1, (int)(uint32_t)wall_clock64());
         n = min(s_nout, qg.seg_cap);
         ++level;
+        from_lds = use_mirror;
         // the next frontier lives in segment 0 only
         if (threadIdx.x <= kMaxSeg) s_pref[threadIdx.x] = threadIdx.x == 0 ? 0 : n;
         __syncthreads();          // everyone has read s_nout before it is reset; s_pref is in place
     }
     if (log.entries) {
-        const Frontier lf{nullptr, nullptr, 0, &st->error, log.entries + (int64_t)wave * log.seg_cap, &log.cnt[wave].v, log.seg_cap};
+        const Frontier lf{nullptr, nullptr, 0, &st->error, log.entries + (int64_t)wave * log.seg_cap, &log.cnt[wave].v,
+                          log.seg_cap, nullptr, 0};
         flush_log(ws, lf);
     }
     // This launch leaves no tallies to fold: its record IS the state after it.  The frontier it ends with
@@ -778,7 +791,7 @@ __global__ __launch_bounds__(kLevelThreads) void k_fix_sweep(GraphView g, u64 *M
     if (threadIdx.x == 0) { s_sink = 0; s_err = 0; }
     __syncthreads();
     WaveStage ws{&s_stage[wave][0], 0, 0, nullptr, 0};
-    const Frontier f{nullptr, &s_sink, 0, &s_err, nullptr, nullptr, 0};   // capacity 0: pushes are counted and dropped
+    const Frontier f{nullptr, &s_sink, 0, &s_err, nullptr, nullptr, 0, nullptr, 0};   // capacity 0: pushes are counted and dropped
     bool any = false;
     // descending ids: most of a sweep then sees its consumers' results (ids are a topological order)
     const int64_t tiles = ((int64_t)g.num_ops + kLevelThreads - 1) / kLevelThreads;
