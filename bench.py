@@ -240,7 +240,7 @@ def main():
         for _ in range(1 + max(3, min(args.steps, 10))):
             torch.cuda.synchronize()
             tb = time.perf_counter()
-            rc = ip.run(buf.op_mask)
+            rc = ip.run(buf.op_mask, kept_ops=buf.kept_ops, kept_count=buf.kept_count)
             torch.cuda.synchronize()
             ip_ms.append((time.perf_counter() - tb) * 1e3)
             assert rc == 0, d.dgn_strerror(rc)

@@ -32,7 +32,7 @@ EXPORTS = [
     "dgn_graph_build_workspace", "dgn_graph_build", "dgn_graph_from_csr_workspace", "dgn_graph_from_csr",
     "dgn_graph_get_csr", "dgn_graph_get_sizes", "dgn_graph_destroy", "dgn_prune_workspace", "dgn_prune",
     "dgn_prune_words", "dgn_keep_compact", "dgn_backward_prune_workspace", "dgn_backward_prune", "dgn_inplace_workspace",
-    "dgn_inplace", "dgn_ignore_mask", "dgn_per_set_lists_workspace", "dgn_per_set_lists",
+    "dgn_inplace", "dgn_inplace_kept", "dgn_ignore_mask", "dgn_per_set_lists_workspace", "dgn_per_set_lists",
     "dgn_target_digest_workspace", "dgn_target_digest", "dgn_strerror",
     "dgn_version",
     "dgn_last_hip_error",
@@ -111,6 +111,8 @@ def _load() -> ctypes.CDLL:
     lib.dgn_inplace_workspace.argtypes = [c_void_p, POINTER(c_size_t)]
     lib.dgn_inplace.argtypes = [c_void_p, c_void_p, ctypes.c_uint64, c_void_p, c_void_p, c_void_p, c_size_t,
                                 POINTER(c_int32), c_void_p]
+    lib.dgn_inplace_kept.argtypes = [c_void_p, c_void_p, ctypes.c_uint64, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                     c_size_t, POINTER(c_int32), c_void_p]
     return lib
 
 
@@ -320,6 +322,16 @@ def dgn_inplace(handle, op_mask, select, rename, renamed_count, scratch, scratch
     return rc, rounds.value
 
 
+def dgn_inplace_kept(handle, op_mask, select, kept_ops, kept_count, rename, renamed_count, scratch, scratch_bytes,
+                     stream=None):
+    """Returns (return code, pointer-doubling rounds run)."""
+    rounds = c_int32(0)
+    rc = _lib.dgn_inplace_kept(handle, _dp(op_mask), ctypes.c_uint64(select & (2**64 - 1)), _dp(kept_ops), _dp(kept_count),
+                               _dp(rename), _dp(renamed_count), _dp(scratch), scratch_bytes, ctypes.byref(rounds),
+                               _stream(stream))
+    return rc, rounds.value
+
+
 # ------------------------------------------------------------------------------------------------
 # Buffer owners (allocation and marshalling only -- no arithmetic of the method happens here)
 # ------------------------------------------------------------------------------------------------
@@ -516,10 +528,15 @@ class InplaceBuffers:
         self.renamed_count = torch.empty(1, dtype=torch.int64, device=dev)
         self.rounds = 0
 
-    def run(self, op_mask, select: int = 2**64 - 1, stream=None) -> int:
-        """``op_mask``: device int64 tensor holding K (as written by ``PruneBuffers.prune``)."""
-        rc, self.rounds = dgn_inplace(self.graph.handle, op_mask, select, self.rename, self.renamed_count,
-                                      self.scratch, self.scratch_bytes, stream)
+    def run(self, op_mask, select: int = 2**64 - 1, stream=None, kept_ops=None, kept_count=None) -> int:
+        """``op_mask``: device int64 tensor holding K (as written by ``PruneBuffers.prune``); with ``kept_ops`` and
+        ``kept_count`` of the same prune the pass visits the kept operators only."""
+        if kept_ops is not None and kept_count is not None:
+            rc, self.rounds = dgn_inplace_kept(self.graph.handle, op_mask, select, kept_ops, kept_count, self.rename,
+                                               self.renamed_count, self.scratch, self.scratch_bytes, stream)
+        else:
+            rc, self.rounds = dgn_inplace(self.graph.handle, op_mask, select, self.rename, self.renamed_count,
+                                          self.scratch, self.scratch_bytes, stream)
         return rc
 
 

@@ -1076,8 +1076,9 @@ int dgn_inplace_workspace(const dgn_graph *g, size_t *scratch_bytes)
     return DGN_OK;
 }
 
-int dgn_inplace(const dgn_graph *g, const uint64_t *op_mask, uint64_t select, int32_t *rename, int64_t *renamed_count,
-                void *scratch, size_t scratch_bytes, int32_t *rounds_out, dgn_stream stream)
+static int inplace_impl(const dgn_graph *g, const uint64_t *op_mask, uint64_t select, const int32_t *kept_ops,
+                        const int64_t *kept_count, int32_t *rename, int64_t *renamed_count, void *scratch,
+                        size_t scratch_bytes, int32_t *rounds_out, dgn_stream stream)
 {
     if (!g || !scratch) return DGN_ERR_NULL_PTR;
     if ((g->P > 0 && !op_mask) || (g->T > 0 && !rename)) return DGN_ERR_NULL_PTR;
@@ -1087,7 +1088,8 @@ int dgn_inplace(const dgn_graph *g, const uint64_t *op_mask, uint64_t select, in
     hipStream_t s = static_cast<hipStream_t>(stream);
     const InplaceBuffers B = inplace_buffers(scratch, g->T);
     const int grid = g->num_cus * 8;
-    DGN_HIP(launch_inplace_setup(g->v, reinterpret_cast<const u64 *>(op_mask), select, rename, renamed_count, B, grid, s));
+    DGN_HIP(launch_inplace_setup(g->v, reinterpret_cast<const u64 *>(op_mask), select, kept_ops, kept_count, rename,
+                                 renamed_count, B, grid, s));
     void *pin = nullptr;
     int rc = pinned_buffer(&pin);
     if (rc != DGN_OK) return rc;
@@ -1101,6 +1103,23 @@ int dgn_inplace(const dgn_graph *g, const uint64_t *op_mask, uint64_t select, in
     }
     if (rounds_out) *rounds_out = round;
     return DGN_OK;
+}
+
+int dgn_inplace(const dgn_graph *g, const uint64_t *op_mask, uint64_t select, int32_t *rename, int64_t *renamed_count,
+                void *scratch, size_t scratch_bytes, int32_t *rounds_out, dgn_stream stream)
+{
+    return inplace_impl(g, op_mask, select, nullptr, nullptr, rename, renamed_count, scratch, scratch_bytes, rounds_out,
+                        stream);
+}
+
+int dgn_inplace_kept(const dgn_graph *g, const uint64_t *op_mask, uint64_t select, const int32_t *kept_ops,
+                     const int64_t *kept_count, int32_t *rename, int64_t *renamed_count, void *scratch,
+                     size_t scratch_bytes, int32_t *rounds_out, dgn_stream stream)
+{
+    if (g && g->P > 0 && (!kept_ops || !kept_count)) return DGN_ERR_NULL_PTR;
+    if ((uintptr_t)kept_count & 7) return DGN_ERR_INVALID_ARG;
+    return inplace_impl(g, op_mask, select, kept_ops, kept_count, rename, renamed_count, scratch, scratch_bytes,
+                        rounds_out, stream);
 }
 
 }  // extern "C"

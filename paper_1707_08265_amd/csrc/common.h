@@ -306,7 +306,8 @@ struct InplaceBuffers {
 size_t inplace_scratch_bytes(int64_t T);
 InplaceBuffers inplace_buffers(void *scratch, int64_t T);
 // init, children, links (the state before the first doubling round)
-hipError_t launch_inplace_setup(const GraphView &g, const u64 *K, u64 select, int32_t *rename, int64_t *renamed_count,
+hipError_t launch_inplace_setup(const GraphView &g, const u64 *K, u64 select, const int32_t *kept_ops,
+                                const int64_t *kept_count, int32_t *rename, int64_t *renamed_count,
                                 const InplaceBuffers &b, int grid_blocks, hipStream_t s);
 hipError_t launch_inplace_round(int round, int32_t *rename, int64_t *renamed_count, const InplaceBuffers &b,
                                 int grid_blocks, hipStream_t s);

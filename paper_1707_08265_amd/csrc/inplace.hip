@@ -118,6 +118,21 @@ __global__ __launch_bounds__(kIpThreads) void k_inplace_children(GraphView g, co
     if (lane < count) offer_children(g, ops[lane], rename, child);
 }
 
+// The same from the list of kept operators that the prune wrote (ascending ids of the operators with K != 0):
+// a pruned graph is a few percent of the recorded one, and the list spares the pass over all of K.  An entry
+// whose mask misses `select` is skipped.
+__global__ __launch_bounds__(kIpThreads) void k_inplace_children_list(GraphView g, const u64 *K, u64 select,
+                                                                       const int32_t *kept_ops, const int64_t *kept_count,
+                                                                       int32_t *rename, int32_t *child)
+{
+    const int64_t kept = kept_count[0];
+    const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < kept; i += gsize) {
+        const int32_t o = kept_ops[i];
+        if ((K[o] & select) != 0) offer_children(g, o, rename, child);
+    }
+}
+
 // link[x] = the only child of x, or -1; nodes with a link are listed (gathered per workgroup in LDS, so
 // that the list's counter is bumped once per thousand entries, not once per wave).  Both jump buffers
 // are set for every node, so that a later round may read the pointer of a node that has no link.
@@ -219,7 +234,8 @@ InplaceBuffers inplace_buffers(void *scratch, int64_t T)
     return b;
 }
 
-hipError_t launch_inplace_setup(const GraphView &g, const u64 *K, u64 select, int32_t *rename, int64_t *renamed_count,
+hipError_t launch_inplace_setup(const GraphView &g, const u64 *K, u64 select, const int32_t *kept_ops,
+                                const int64_t *kept_count, int32_t *rename, int64_t *renamed_count,
                                 const InplaceBuffers &b, int grid_blocks, hipStream_t s)
 {
     const int64_t T = g.num_tensors, P = g.num_ops;
@@ -230,7 +246,11 @@ hipError_t launch_inplace_setup(const GraphView &g, const u64 *K, u64 select, in
     };
     hipLaunchKernelGGL(k_inplace_init, blocks_for(T), dim3(kIpThreads), 0, s, rename, b.child, T, b.counters,
                        kInplaceMaxRounds + 1, renamed_count);
-    if (P > 0) hipLaunchKernelGGL(k_inplace_children, blocks_for(P), dim3(kIpThreads), 0, s, g, K, select, rename, b.child);
+    if (P > 0 && kept_ops)
+        hipLaunchKernelGGL(k_inplace_children_list, dim3((unsigned)grid_blocks), dim3(kIpThreads), 0, s, g, K, select,
+                           kept_ops, kept_count, rename, b.child);
+    else if (P > 0)
+        hipLaunchKernelGGL(k_inplace_children, blocks_for(P), dim3(kIpThreads), 0, s, g, K, select, rename, b.child);
     if (T > 0)
         hipLaunchKernelGGL(k_inplace_links, blocks_for(T), dim3(kIpThreads), 0, s, rename, b.child, T, b.J[0], b.J[1],
                            b.linkers, b.counters);

@@ -33,7 +33,20 @@ def gpu_inplace(d, dg, K, select=ALL, buf=None):
     rc = buf.run(K, select)
     assert rc == 0, d.dgn_strerror(rc)
     torch.cuda.synchronize()
-    return buf.rename.cpu().numpy(), int(buf.renamed_count.item()), buf.rounds
+    out = buf.rename.cpu().numpy(), int(buf.renamed_count.item()), buf.rounds
+    # the same from the list of kept operators (ascending ids of the operators with K != 0, as a prune leaves it):
+    # the two entry points must agree
+    kept = torch.nonzero(K != 0).flatten().to(torch.int32)
+    spare = torch.full((5,), -7, dtype=torch.int32, device=kept.device)        # entries beyond the count are not read
+    kept_ops = torch.cat([kept, spare])
+    kept_count = torch.tensor([kept.numel()], dtype=torch.int64, device=kept.device)
+    buf.rename.fill_(-99)
+    rc = buf.run(K, select, kept_ops=kept_ops, kept_count=kept_count)
+    assert rc == 0, d.dgn_strerror(rc)
+    torch.cuda.synchronize()
+    assert np.array_equal(buf.rename.cpu().numpy(), out[0]), "dgn_inplace_kept differs from dgn_inplace"
+    assert int(buf.renamed_count.item()) == out[1]
+    return out
 
 
 def check(rd, count, ref, what):

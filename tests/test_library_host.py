@@ -121,6 +121,8 @@ def test_other_entry_points_reject_bad_arguments_before_any_device_work(d):
     assert d.dgn_per_set_lists(None, None, 0, None, None, 0, None, 0, stream=0) == d.DGN_ERR_NULL_PTR
     assert d.dgn_prune_words(None, 100, 0, None, None, None, None, None, None, None, None, None, None, 0, stream=0) == d.DGN_ERR_NULL_PTR
     assert d.dgn_options(incremental=1).incremental == 1
+    rc, _ = d.dgn_inplace_kept(None, None, 1, None, None, None, None, None, 0, stream=0)
+    assert rc == d.DGN_ERR_NULL_PTR
     rc, nbytes = d.dgn_target_digest_workspace()
     assert rc == 0 and nbytes >= 16
     rc, _ = d.dgn_target_digest(None, 4, 0, None, None, None, 0, stream=0)
