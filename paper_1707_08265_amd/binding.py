@@ -451,11 +451,12 @@ class PruneBuffers:
             if options is None:
                 options = dgn_options()
             options.recycle = 1
-        self._scratch_defined = True          # whatever happens, the library has written the scratch header
-        return dgn_prune(self.graph.handle, self.num_sets, int(tgt_idx.numel()), tgt_rowptr, tgt_idx,
-                         self.tensor_mask, self.op_mask, self.op_flag, self.kept_ops, self.kept_masks,
-                         self.kept_count, self.per_query_count, self.scratch, self.scratch_bytes, options,
-                         stats, stream)
+        rc = dgn_prune(self.graph.handle, self.num_sets, int(tgt_idx.numel()), tgt_rowptr, tgt_idx,
+                       self.tensor_mask, self.op_mask, self.op_flag, self.kept_ops, self.kept_masks,
+                       self.kept_count, self.per_query_count, self.scratch, self.scratch_bytes, options,
+                       stats, stream)
+        self._scratch_defined = rc == DGN_OK  # after an error everything is cleared next time
+        return rc
 
     def keep_compact(self, tensor_mask_in, stream=None) -> int:
         self._scratch_defined = False         # op_mask no longer goes with the log of the last prune
@@ -543,19 +544,37 @@ class InplaceBuffers:
 class BackwardPruneBuffers(PruneBuffers):
     """Buffers of one ``dgn_backward_prune`` call: the same outputs as ``PruneBuffers``, larger scratch."""
 
-    def __init__(self, graph: DeviceGraph, num_pairs: int = 64, device=None):
-        super().__init__(graph, num_pairs, device)
+    def __init__(self, graph: DeviceGraph, num_pairs: int = 64, device=None, recycle: bool = True):
+        super().__init__(graph, num_pairs, device, recycle)
+        self._backward_defined = False        # the scratch buffer was last written by backward_prune
         rc, sb = dgn_backward_prune_workspace(graph.handle)
         _check(rc, "dgn_backward_prune_workspace")
         self.scratch_bytes = sb
         self.scratch = torch.empty(sb, dtype=torch.uint8, device=self.scratch.device)
 
+    def prune(self, *args, **kwargs) -> int:
+        self._backward_defined = False        # an ordinary prune lays the scratch buffer out its own way
+        return super().prune(*args, **kwargs)
+
+    def keep_compact(self, *args, **kwargs) -> int:
+        self._backward_defined = False
+        return super().keep_compact(*args, **kwargs)
+
     def backward_prune(self, obj, wrt, options=None, stats=None, stream=None) -> int:
         """``obj`` / ``wrt``: device int32 tensors of equal length (the pairs)."""
         self._scratch_defined = False         # the scratch buffer is laid out differently by this call
-        return dgn_backward_prune(self.graph.handle, int(obj.numel()), obj, wrt, self.tensor_mask, self.op_mask,
-                                  self.op_flag, self.kept_ops, self.kept_masks, self.kept_count,
-                                  self.per_query_count, self.scratch, self.scratch_bytes, options, stats, stream)
+        if options is not None:
+            options = dgn_options.from_buffer_copy(options)
+            options.recycle = 0
+        if self.recycle and self._backward_defined:
+            if options is None:
+                options = dgn_options()
+            options.recycle = 1
+        rc = dgn_backward_prune(self.graph.handle, int(obj.numel()), obj, wrt, self.tensor_mask, self.op_mask,
+                                self.op_flag, self.kept_ops, self.kept_masks, self.kept_count,
+                                self.per_query_count, self.scratch, self.scratch_bytes, options, stats, stream)
+        self._backward_defined = rc == DGN_OK     # after an error everything is cleared next time
+        return rc
 
 
 class ReadoutBuffers:

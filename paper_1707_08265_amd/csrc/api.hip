@@ -511,10 +511,14 @@ int dgn_prune_workspace(const dgn_graph *g, int32_t num_sets, size_t *scratch_by
     return DGN_OK;
 }
 
-int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const int32_t *tgt_rowptr,
-              const int32_t *tgt_idx, uint64_t *tensor_mask, uint64_t *op_mask, uint8_t *op_flag, int32_t *kept_ops,
-              uint64_t *kept_masks, int64_t *kept_count, int64_t *per_query_count, void *scratch, size_t scratch_bytes,
-              const dgn_options *options, dgn_stats *stats, dgn_stream stream)
+// dgn_prune.  also_M [T] / also_K [P] (or NULL): two more arrays that the call zeroes with M and K -- all of them,
+// or, with recycled buffers, the words that the previous call's log and kept list name (the caller vouches that
+// they hold non-zero words nowhere else).
+static int prune_impl(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const int32_t *tgt_rowptr,
+                      const int32_t *tgt_idx, uint64_t *tensor_mask, uint64_t *op_mask, uint8_t *op_flag, int32_t *kept_ops,
+                      uint64_t *kept_masks, int64_t *kept_count, int64_t *per_query_count, void *scratch,
+                      size_t scratch_bytes, const dgn_options *options, dgn_stats *stats, dgn_stream stream,
+                      uint64_t *also_M, uint64_t *also_K)
 {
     if (!g) return DGN_ERR_NULL_PTR;
     if (num_sets < 1 || num_sets > DGN_MAX_SETS) return DGN_ERR_TOO_MANY_SETS;
@@ -564,11 +568,11 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     uint8_t *flags = (op_flag && ((uintptr_t)op_flag & 7) == 0 && g->P % 8 == 0) ? op_flag : S.flagbuf;
     const size_t flag_bytes = flags == op_flag ? (size_t)g->P : S.db_bytes;
     const ColourLog log{recycle ? S.log.entries : nullptr, S.log.cnt, S.log.seg_cap};
-    const RecycleHeader want{kRecycleMagic, g->serial, M, K, kept_ops, kept_count, flags, 0};
+    const RecycleHeader want{kRecycleMagic, g->serial, M, K, kept_ops, kept_count, flags, also_M, also_K, {0, 0, 0}};
     if (recycle) {
-        FillRegion big[4] = {{M, (size_t)g->T * 8}, {K, (size_t)g->P * 8}, {S.DB, S.db_bytes},
-                             {flags, use_flags ? flag_bytes : 0}};
-        DGN_HIP(launch_clear_or_reset(big, 4, S.hdr, want, reinterpret_cast<u64 *>(S.hdr + 1), S.log, kept_ops, kept_count, M, K,
+        FillRegion big[6] = {{M, (size_t)g->T * 8}, {K, (size_t)g->P * 8}, {S.DB, S.db_bytes},
+                             {flags, use_flags ? flag_bytes : 0}, {also_M, (size_t)g->T * 8}, {also_K, (size_t)g->P * 8}};
+        DGN_HIP(launch_clear_or_reset(big, 6, S.hdr, want, reinterpret_cast<u64 *>(S.hdr + 1), S.log, kept_ops, kept_count, M, K,
                                       S.DB, flags, s));
         FillRegion small[5] = {{S.state, 256 + sizeof(TravCounters)}, {S.hdr, sizeof(RecycleHeader)}, {S.log.cnt, sizeof(SegCounter) * kMaxSeg},
                                {per_query_count, pq_bytes}, {S.pq_part, per_query_count ? S.pq_part_bytes : 0}};
@@ -581,6 +585,11 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
                              {per_query_count, pq_bytes}, {S.pq_part, per_query_count ? S.pq_part_bytes : 0},
                              {flags, use_flags ? flag_bytes : 0}};
         DGN_HIP(launch_clear(clr, 8, s));
+        if (also_M || also_K) {
+            FillRegion more[2] = {{also_M, (size_t)g->T * 8}, {also_K, (size_t)g->P * 8}};
+            DGN_HIP(launch_clear(more, 2, s));
+            ++launches;
+        }
     }
     if (ev) DGN_HIP(hipEventRecord(ev[1], s));
     // deferral schedule: threshold on the producer id, starting at decay*P and decaying geometrically
@@ -816,6 +825,15 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
     return error_bits_to_code(hst->error & ~(kErrOverflow | kErrLogFull));
 }
 
+int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const int32_t *tgt_rowptr,
+              const int32_t *tgt_idx, uint64_t *tensor_mask, uint64_t *op_mask, uint8_t *op_flag, int32_t *kept_ops,
+              uint64_t *kept_masks, int64_t *kept_count, int64_t *per_query_count, void *scratch, size_t scratch_bytes,
+              const dgn_options *options, dgn_stats *stats, dgn_stream stream)
+{
+    return prune_impl(g, num_sets, num_targets, tgt_rowptr, tgt_idx, tensor_mask, op_mask, op_flag, kept_ops, kept_masks,
+                      kept_count, per_query_count, scratch, scratch_bytes, options, stats, stream, nullptr, nullptr);
+}
+
 // Removal rule + compaction: K computed from tensor_mask_in (from_tensor_mask), or taken as it stands in op_mask.
 static int keep_compact_impl(const dgn_graph *g, const uint64_t *tensor_mask_in, bool from_tensor_mask, uint64_t *op_mask,
                              uint8_t *op_flag, int32_t *kept_ops, uint64_t *kept_masks, int64_t *kept_count,
@@ -961,15 +979,17 @@ int dgn_backward_prune(const dgn_graph *g, int32_t num_pairs, const int32_t *obj
     if (options) o1 = *options;
     o1.profile = 0;
     o1.incremental = 0;                              // stage one starts from nothing, in scratch memory
-    o1.recycle = 0;
-    int rc = dgn_prune(g, num_pairs, num_pairs, S.tgt_rowptr, wrt, reinterpret_cast<uint64_t *>(S.B),
-                       reinterpret_cast<uint64_t *>(S.KB), nullptr, S.kept, nullptr, S.kept_count, nullptr, scratch,
-                       S.prune_bytes, &o1, stats, stream);
+    // The marked masks F (the caller's tensor_mask) and the final K (its op_mask) are non-zero only inside stage
+    // one's coloured set and kept list, so stage one zeroes them along with its own M and K: everything, or, when
+    // the caller recycles the buffers, what the previous call's log and kept list name.
+    int rc = prune_impl(g, num_pairs, num_pairs, S.tgt_rowptr, wrt, reinterpret_cast<uint64_t *>(S.B),
+                        reinterpret_cast<uint64_t *>(S.KB), nullptr, S.kept, nullptr, S.kept_count, nullptr, scratch,
+                        S.prune_bytes, &o1, stats, stream, tensor_mask, op_mask);
     if (rc != DGN_OK) return rc;
 
     // stage two: forwards from every x_obj, inside the coloured set of stage one
-    FillRegion clr[2] = {{F, (size_t)g->T * 8}, {S.flags, 256}};
-    DGN_HIP(launch_clear(clr, 2, s));
+    FillRegion clr[1] = {{S.flags, 256}};
+    DGN_HIP(launch_clear(clr, 1, s));
     DGN_HIP(launch_backward_seed(g->T, num_pairs, obj, wrt, nullptr, S.B, F, S.flags, false, s));
     void *pin = nullptr;
     rc = pinned_buffer(&pin);
@@ -991,8 +1011,6 @@ int dgn_backward_prune(const dgn_graph *g, int32_t num_pairs, const int32_t *obj
 
     // Removal rule and ordered compaction on the marked set.  A marked tensor lies in stage one's coloured set,
     // so only operators of stage one's kept list can have a marked output: K is cleared and written for those.
-    FillRegion kz[1] = {{op_mask, (size_t)g->P * 8}};
-    DGN_HIP(launch_clear(kz, 1, s));
     DGN_HIP(launch_keep_from_list(g->v, S.kept, S.kept_count, F, reinterpret_cast<u64 *>(op_mask), grid, s));
     return keep_compact_impl(g, tensor_mask, false, op_mask, op_flag, kept_ops, kept_masks, kept_count, per_query_count,
                              scratch, S.prune_bytes, stream);

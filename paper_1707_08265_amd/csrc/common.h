@@ -98,12 +98,14 @@ struct ColourLog { int32_t *entries; SegCounter *cnt; int32_t seg_cap; };
 struct RecycleHeader {
     u64 magic, graph_serial;
     const void *M, *K, *kept_ops, *kept_count, *flags;
-    u64 pad;
+    const void *also_M, *also_K;   // two more arrays that hold non-zero words only where M / K do (or NULL)
+    u64 pad[3];
 };
 __device__ __forceinline__ bool same_header(const RecycleHeader &a, const RecycleHeader &b)
 {
     return a.magic == b.magic && a.graph_serial == b.graph_serial && a.M == b.M && a.K == b.K &&
-           a.kept_ops == b.kept_ops && a.kept_count == b.kept_count && a.flags == b.flags;
+           a.kept_ops == b.kept_ops && a.kept_count == b.kept_count && a.flags == b.flags && a.also_M == b.also_M &&
+           a.also_K == b.also_K;
 }
 
 // ---- wave64 helpers ---------------------------------------------------------------------------
@@ -191,7 +193,8 @@ __device__ __forceinline__ uint32_t load_coherent(const uint32_t *p)
 struct FillRegion { void *ptr; size_t bytes; };   // ptr 8-byte aligned, bytes multiple of 8
 hipError_t launch_clear(const FillRegion *regions, int num_regions, hipStream_t s);
 // Zero `regions` (at most 8) -- unless *hdr equals `want`: then zero only M of the logged tensors and K and the
-// deferral marker of the kept operators (the buffers are as the prune that wrote the header left them).
+// deferral marker of the kept operators (the buffers are as the prune that wrote the header left them), and
+// the same words of want.also_M / want.also_K where those are given.
 // found_out[0] = 1 when the header was found, else 0.
 hipError_t launch_clear_or_reset(const FillRegion *regions, int num_regions, const RecycleHeader *hdr,
                                  const RecycleHeader &want, u64 *found_out, const ColourLog &log, const int32_t *kept_ops,

@@ -48,6 +48,8 @@ __global__ __launch_bounds__(256) void k_clear_or_reset(ClearArgs a, const Recyc
                                                         uint8_t *flags)
 {
     __shared__ int s_pref[kMaxSeg + 1];
+    u64 *also_M = static_cast<u64 *>(const_cast<void *>(want.also_M));
+    u64 *also_K = static_cast<u64 *>(const_cast<void *>(want.also_K));
     const RecycleHeader have = *hdr;
     const bool found = same_header(have, want);             // the same answer in every block
     if (blockIdx.x == 0 && threadIdx.x == 0) found_out[0] = found ? 1 : 0;
@@ -72,7 +74,9 @@ __global__ __launch_bounds__(256) void k_clear_or_reset(ClearArgs a, const Recyc
             const int mid = (lo + hi + 1) >> 1;
             if (s_pref[mid] <= (int)i) lo = mid; else hi = mid - 1;
         }
-        M[log.entries[(int64_t)lo * log.seg_cap + ((int)i - s_pref[lo])]] = 0;
+        const int32_t t = log.entries[(int64_t)lo * log.seg_cap + ((int)i - s_pref[lo])];
+        M[t] = 0;
+        if (also_M) also_M[t] = 0;
     }
     const int64_t kept = kept_count[0];
     for (int64_t i = gtid; i < kept; i += gsize) {
@@ -80,6 +84,7 @@ __global__ __launch_bounds__(256) void k_clear_or_reset(ClearArgs a, const Recyc
         K[o] = 0;
         DB[o] = 0;
         flags[o] = 0;
+        if (also_K) also_K[o] = 0;
     }
 }
 

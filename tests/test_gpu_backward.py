@@ -72,6 +72,36 @@ def test_parity_configs(dgn, oracle, k, scale):
     assert_same(out2, oracle.backward_prune(_adj(oracle, g), obj2, wrt2), f"cfg{k} second call")
 
 
+def test_recycled_buffers_over_a_sequence_of_calls(dgn, oracle):
+    """The buffers of a backward prune recycle like those of a prune: stage one zeroes what the previous call set
+    -- its own masks and, through the same log and kept list, the caller's marked masks and K.  Other pairs every
+    time, an ordinary prune and a failed call in between; every result against the oracle."""
+    import torch
+    g, tg = gg.config(3, 0.01)
+    adj = _adj(oracle, g)
+    dg = dgn.DeviceGraph.from_coo(g)
+    buf = dgn.BackwardPruneBuffers(dg, 64)
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    def run(seed, n):
+        obj, wrt = gg.backward_pairs(g, seed, n, 16, tail_fraction=0.3)
+        rc = buf.backward_prune(up(obj), up(wrt))
+        assert rc == 0, dgn.dgn_strerror(rc)
+        assert_same(buf.to_host(), oracle.backward_prune(adj, obj, wrt), f"pairs seed {seed}")
+    run(1, 64)
+    run(2, 64)
+    run(3, 17)
+    run(4, 64)
+    # an ordinary prune through the same object lays the scratch buffer out differently
+    assert buf.prune(up(tg.tgt_rowptr), up(tg.tgt_idx)) == 0
+    run(5, 64)
+    run(6, 64)
+    # a call that fails half way (an objective out of range is found after stage one)
+    bad = np.asarray([0, g.num_tensors + 5], np.int32)
+    assert buf.backward_prune(up(bad), up(np.asarray([3, 4], np.int32))) == dgn.DGN_ERR_ID_OUT_OF_RANGE
+    run(7, 64)
+    run(8, 64)
+
+
 def test_deep_chain_and_edge_cases(dgn, oracle):
     import torch
     n = 20_000
