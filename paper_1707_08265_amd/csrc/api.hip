@@ -31,7 +31,8 @@ constexpr int kWidePerGroup = 12;           // wide level launches between two s
 constexpr int kWideGroupsFirst = 4;         // groups in the first batch (one state read-back per batch) ...
 constexpr int kWideGroups = 6;              // ... and in the following ones
 constexpr int kMaxBatch = 512;              // launches enqueued between two state read-backs, at most
-constexpr int kTailLevels = 1;              // wide launches enqueued beyond the layout the previous prune needed
+constexpr int kTailLevels = 1;              // wide launches enqueued beyond the layout the previous prune needed ...
+constexpr int kExactStreak = 3;             // ... until that layout has fitted exactly this many prunes in a row
 constexpr int kSweepMinGraphs = 64;         // packed batches with at least this many graphs ...
 constexpr int64_t kSweepMaxGraphOps = 1 << 18;   // ... none larger than this use the per-graph sweep
 constexpr u64 kRecycleMagic = 0x44474e5f52435943ull;   // "DGN_RCYC"
@@ -261,6 +262,9 @@ struct dgn_graph {
     mutable std::atomic<int> wide_hint[2] = {};
     mutable std::atomic<int> hint_runs[2] = {};
     mutable std::atomic<int> hint_run_len[2][dgn::kMaxRuns] = {};
+    //   exact_streak: prunes in a row whose traversal followed the hinted layout to the launch; after a few the
+    //     spare launches at its end are dropped (a miss then costs one more batch, and brings them back)
+    mutable std::atomic<int> exact_streak[2] = {};
 };
 
 namespace {
@@ -719,6 +723,7 @@ static int prune_impl(const dgn_graph *g, int32_t num_sets, int64_t num_targets,
     };
     bool first = true;
     int batch = 0;
+    int used_runs = 0, used_len[kMaxRuns] = {};       // the layout enqueued from the hints, if any
     while (!done) {
         const int hint_runs = generic_only ? 0 : g->hint_runs[hk].load(std::memory_order_relaxed);
         if (first && hint_runs > 0) {
@@ -730,9 +735,12 @@ static int prune_impl(const dgn_graph *g, int32_t num_sets, int64_t num_targets,
                 rc = group(len);
                 if (rc) return rc;
                 room -= len + 1;
+                used_len[used_runs++] = len;
             }
-            rc = group(kTailLevels);
-            if (rc) return rc;
+            if (g->exact_streak[hk].load(std::memory_order_relaxed) < kExactStreak) {
+                rc = group(kTailLevels);
+                if (rc) return rc;
+            }
         } else {
             // unknown graph, or the layout fell short: groups of wide levels with the single-workgroup kernel
             // after each; a batch right after a hinted one is small (the hint was nearly right)
@@ -757,8 +765,14 @@ static int prune_impl(const dgn_graph *g, int32_t num_sets, int64_t num_targets,
     g->wide_hint[hk].store(hst->max_frontier > (u64)kNarrowCap ? 1 : 0, std::memory_order_relaxed);
     {
         const int nr = hst->n_runs < kMaxRuns ? hst->n_runs : kMaxRuns;
-        for (int r = 0; r < nr; ++r) g->hint_run_len[hk][r].store(hst->wide_runs[r], std::memory_order_relaxed);
+        bool exact = batch == 1 && used_runs > 0 && hst->n_runs == used_runs;
+        for (int r = 0; r < nr; ++r) {
+            if (exact && hst->wide_runs[r] != used_len[r]) exact = false;
+            g->hint_run_len[hk][r].store(hst->wide_runs[r], std::memory_order_relaxed);
+        }
         g->hint_runs[hk].store(nr, std::memory_order_relaxed);
+        g->exact_streak[hk].store(exact ? g->exact_streak[hk].load(std::memory_order_relaxed) + 1 : 0,
+                                  std::memory_order_relaxed);
     }
     if (recycle && (hst->error & (kErrOverflow | kErrLogFull))) {
         // the log is incomplete; a compaction enqueued ahead may have called it complete
