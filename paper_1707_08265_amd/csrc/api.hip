@@ -576,11 +576,13 @@ static int prune_impl(const dgn_graph *g, int32_t num_sets, int64_t num_targets,
     if (recycle) {
         FillRegion big[6] = {{M, (size_t)g->T * 8}, {K, (size_t)g->P * 8}, {S.DB, S.db_bytes},
                              {flags, use_flags ? flag_bytes : 0}, {also_M, (size_t)g->T * 8}, {also_K, (size_t)g->P * 8}};
-        DGN_HIP(launch_clear_or_reset(big, 6, S.hdr, want, reinterpret_cast<u64 *>(S.hdr + 1), S.log, kept_ops, kept_count, M, K,
+        DGN_HIP(launch_clear_or_reset(big, 6, S.hdr, want, reinterpret_cast<u64 *>(S.state + 1), S.log, kept_ops, kept_count, M, K,
                                       S.DB, flags, s));
-        FillRegion small[5] = {{S.state, 256 + sizeof(TravCounters)}, {S.hdr, sizeof(RecycleHeader)}, {S.log.cnt, sizeof(SegCounter) * kMaxSeg},
-                               {per_query_count, pq_bytes}, {S.pq_part, per_query_count ? S.pq_part_bytes : 0}};
-        DGN_HIP(launch_clear(small, 5, s));
+        // (the word behind the state header says which way the kernel above went: it comes back with the header)
+        FillRegion small[6] = {{S.state, sizeof(TravState)}, {S.ctr, sizeof(TravCounters)}, {S.hdr, sizeof(RecycleHeader)},
+                               {S.log.cnt, sizeof(SegCounter) * kMaxSeg}, {per_query_count, pq_bytes},
+                               {S.pq_part, per_query_count ? S.pq_part_bytes : 0}};
+        DGN_HIP(launch_clear(small, 6, s));
         ++launches;
     } else {
         // (the per-graph sweep stores K of every operator and uses no markers: it needs M cleared, nothing else)
@@ -699,7 +701,7 @@ static int prune_impl(const dgn_graph *g, int32_t num_sets, int64_t num_targets,
             const int e = narrow();
             if (e) return e;
         }
-        DGN_HIP(hipMemcpyAsync(pin, S.state, sizeof(TravState), hipMemcpyDeviceToHost, s));
+        DGN_HIP(hipMemcpyAsync(pin, S.state, 2 * sizeof(TravState), hipMemcpyDeviceToHost, s));
         DGN_HIP(hipStreamSynchronize(s));
         const LevelSlot &sl = hst->slot[(launch_no - 1) & 1];
         done = sl.n == 0 && !(sl.deferred_seen && sl.theta_hi > 0);
@@ -823,12 +825,7 @@ static int prune_impl(const dgn_graph *g, int32_t num_sets, int64_t num_targets,
         stats->max_frontier = (int64_t)hst->max_frontier;
         stats->launches = launches;
         stats->level_launches = level_launches;
-        if (recycle) {
-            u64 *found = reinterpret_cast<u64 *>(static_cast<char *>(pin) + 128);
-            DGN_HIP(hipMemcpyAsync(found, S.hdr + 1, sizeof(u64), hipMemcpyDeviceToHost, s));
-            DGN_HIP(hipStreamSynchronize(s));
-            stats->recycled = *found ? 1 : 0;
-        }
+        if (recycle) stats->recycled = *reinterpret_cast<const u64 *>(static_cast<const char *>(pin) + sizeof(TravState)) ? 1 : 0;
         if (ev) {
             for (int i = 0; i < 6; ++i) DGN_HIP(hipEventElapsedTime(&stats->phase_ms[i], ev[i], ev[i + 1]));
             DGN_HIP(hipEventElapsedTime(&stats->phase_ms[DGN_PHASE_TOTAL], ev[0], ev[6]));
