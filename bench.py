@@ -217,6 +217,32 @@ def main():
     if recycled and not args.prune_only:
         rc = buf.prune(rowptr, idx, options=opts, stats=st)      # st and the buffers describe the timed workload again
         assert rc == 0
+    # the same steps once more, each one timed on its own (a synchronisation after every step): median and minimum
+    per_step = copy_gbs = None
+    if not args.prune_only:
+        one = []
+        for _ in range(max(args.steps, 20)):
+            torch.cuda.synchronize()
+            t2 = time.perf_counter()
+            rc = buf.prune(rowptr, idx, options=opts, stats=st)
+            torch.cuda.synchronize()
+            one.append((time.perf_counter() - t2) * 1e3)
+            assert rc == 0, d.dgn_strerror(rc)
+        per_step = {"median": round(float(np.median(one)), 4), "min": round(float(np.min(one)), 4), "steps": len(one)}
+        # what a plain device-to-device copy reaches on this GPU: the practical ceiling beside the published peak
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        dst.copy_(src)
+        e0.record()
+        for _ in range(5):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_gbs = round(5 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+        del src, dst
+        log(f"steps timed one by one: median {per_step['median']:.3f} ms, min {per_step['min']:.3f} ms; "
+            f"1 GiB device copy: {copy_gbs} GB/s (read + write)")
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -365,6 +391,9 @@ def main():
     E_k = int(fan_in[out["kept_ops"]].sum())
     n_out = np.bincount(g.out_op, minlength=P)
     Eo_k = int(n_out[out["kept_ops"]].sum())
+    # edges that one run of Algorithm 1 per target set would have gone through, summed over the sets
+    sets_of = np.bitwise_count(out["kept_masks"][:P_k]).astype(np.int64)
+    E_query = int(((fan_in[out["kept_ops"][:P_k]] + n_out[out["kept_ops"][:P_k]]) * sets_of).sum())
 
     # ---- algorithmic bytes per kernel launch (int32 ids, uint64 masks) ---------------------------
     levels = max(1, int(st.levels))
@@ -399,6 +428,7 @@ def main():
         "per_kernel_GBs": {k: round(alg[k] / (dur_ms[k] * 1e-3) / 1e9, 1) if dur_ms[k] > 0 else None for k in alg},
         "whole_path_algorithmic_GBs": round(b_alg_total / (ms_per_step * 1e-3) / 1e9, 1),
         "whole_path_frac": round(b_alg_total / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "measured_copy_GBs": copy_gbs,
     }
 
     # ---- CPU baseline: the oracle as it stands, on this machine's host cores -------------------------
@@ -454,6 +484,7 @@ def main():
         "metric": "pruned edges/sec (GTEPS), 64-query batched prune", "value": round(gteps, 2), "unit": "GTEPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u64", "data": "synthetic",
+        "query_gteps": round(E_query / (ms_per_step * 1e-3) / 1e9, 2), "per_step_ms": per_step,
         "config": {"workload": f"configs[{args.config}] {g.name}" + ("" if args.scale == 1.0 else f" x{args.scale}"),
                    "num_ops": P, "num_tensors": T, "nnz_in": g.nnz_in, "nnz_out": g.nnz_out,
                    "num_sets": tg.num_sets, "num_graphs": g.num_graphs,

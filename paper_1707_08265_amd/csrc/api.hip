@@ -303,11 +303,10 @@ int finish_build(dgn_graph *h, const GraphLayout &L, const int64_t *op_off_host,
         for (int32_t i = 0; i < h->G; ++i)
             if (op_off_host[i + 1] - op_off_host[i] > h->max_graph_ops) h->max_graph_ops = op_off_host[i + 1] - op_off_host[i];
     }
-    int dev = 0;
-    hipDeviceProp_t prop;
+    int dev = 0, cus = 0;
     DGN_HIP(hipGetDevice(&dev));
-    DGN_HIP(hipGetDeviceProperties(&prop, dev));
-    h->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    DGN_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    h->num_cus = cus > 0 ? cus : 256;
     *out = h;
     return DGN_OK;
 }
