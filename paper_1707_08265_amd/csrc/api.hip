@@ -33,6 +33,7 @@ constexpr int kWideGroups = 6;              // ... and in the following ones
 constexpr int kMaxBatch = 512;              // launches enqueued between two state read-backs, at most
 constexpr int kTailLevels = 1;              // wide launches enqueued beyond the layout the previous prune needed ...
 constexpr int kExactStreak = 3;             // ... until that layout has fitted exactly this many prunes in a row
+constexpr int kStatusMulti = 16;            // word of the build's status block that says "a tensor has several producers"
 constexpr int kSweepMinGraphs = 64;         // packed batches with at least this many graphs ...
 constexpr int64_t kSweepMaxGraphOps = 1 << 18;   // ... none larger than this use the per-graph sweep
 constexpr u64 kRecycleMagic = 0x44474e5f52435943ull;   // "DGN_RCYC"
@@ -249,6 +250,7 @@ struct dgn_graph {
     int32_t G;
     int num_cus;
     bool topological;       // operator ids verified to be a topological order at build time
+    bool multi_producer;    // some tensor is written by more than one operator
     int64_t max_graph_ops;  // largest graph of a packed batch (P for a single graph)
     uint64_t serial;        // unique per handle in this process
     // Hints only, taken from the last prune of this graph; a wrong one costs launches that return at once,
@@ -272,7 +274,7 @@ namespace {
 int finish_build(dgn_graph *h, const GraphLayout &L, const int64_t *op_off_host, const int64_t *t_off_host,
                  int32_t *status, const dgn_options *options, hipStream_t s, dgn_graph **out)
 {
-    DGN_HIP(launch_build_pinfo(h->v, L.pinfo, s));
+    DGN_HIP(launch_build_pinfo(h->v, L.pinfo, status + kStatusMulti, s));
     if (h->G > 1) {
         DGN_HIP(hipMemcpyAsync(L.op_off, op_off_host, sizeof(int64_t) * (h->G + 1), hipMemcpyHostToDevice, s));
         DGN_HIP(hipMemcpyAsync(L.t_off, t_off_host, sizeof(int64_t) * (h->G + 1), hipMemcpyHostToDevice, s));
@@ -288,10 +290,11 @@ int finish_build(dgn_graph *h, const GraphLayout &L, const int64_t *op_off_host,
     void *pin = nullptr;
     int rc = pinned_buffer(&pin);
     if (rc) return rc;
-    DGN_HIP(hipMemcpyAsync(pin, status, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    DGN_HIP(hipMemcpyAsync(pin, status, (kStatusMulti + 1) * sizeof(int32_t), hipMemcpyDeviceToHost, s));
     DGN_HIP(hipStreamSynchronize(s));
     int32_t bits = *static_cast<int32_t *>(pin);
     h->topological = check_topo && (bits & kErrTopo) == 0;
+    h->multi_producer = static_cast<int32_t *>(pin)[kStatusMulti] != 0;
     if (!(options && options->validate)) bits &= ~kErrTopo;
     rc = error_bits_to_code(bits);
     if (rc) return rc;
@@ -641,7 +644,7 @@ static int prune_impl(const dgn_graph *g, int32_t num_sets, int64_t num_targets,
     // Packed batch of many small graphs in topological order: one wave sweeps each graph once (see
     // k_sweep_graphs); no frontier, no level loop, per-set counts come out of the sweep itself.
     if (sweep) {
-        DGN_HIP(launch_sweep_graphs(g->v, M, K, ca.from_tensor_mask ? nullptr : per_query_count, s));
+        DGN_HIP(launch_sweep_graphs(g->v, M, K, ca.from_tensor_mask ? nullptr : per_query_count, g->multi_producer, s));
         ++launches;
         if (ev_trav) DGN_HIP(hipEventRecord(ev_trav[3], s));
         if (!ca.from_tensor_mask) ca.per_query_count = nullptr;   // already written by the sweep

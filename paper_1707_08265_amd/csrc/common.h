@@ -228,7 +228,7 @@ hipError_t launch_check_topological(const GraphView &g, int32_t *error, hipStrea
 hipError_t launch_check_graph_ranges(const GraphView &g, int32_t *error, hipStream_t s);
 
 // Traversal.
-hipError_t launch_build_pinfo(const GraphView &g, int4 *pinfo, hipStream_t s);
+hipError_t launch_build_pinfo(const GraphView &g, int4 *pinfo, int32_t *multi, hipStream_t s);
 hipError_t launch_seed(const GraphView &g, int32_t Q, int64_t num_targets, const int32_t *tgt_rowptr,
                        const int32_t *tgt_idx, u64 *M, TravState *st, TravCounters *ctr, int32_t *q0,
                        const QueueGeom &qg, int32_t theta0, const ColourLog &log, hipStream_t s);
@@ -245,7 +245,8 @@ hipError_t launch_narrow(const GraphView &g, TravState *st, TravCounters *ctr, i
 // Packed batches of small graphs whose operator ids are a topological order: one wave per graph sweeps
 // its operators once, highest ids first (no frontier at all); fills K and, when pq is not NULL, the
 // per-graph per-set counts.
-hipError_t launch_sweep_graphs(const GraphView &g, u64 *M, u64 *K, int64_t *per_query_count, hipStream_t s);
+hipError_t launch_sweep_graphs(const GraphView &g, u64 *M, u64 *K, int64_t *per_query_count, bool multi_producer,
+                               hipStream_t s);
 // One sweep over all operators re-deriving K and pushing new bits to the inputs; *changed |= 1 if any.
 hipError_t launch_fix_sweep(const GraphView &g, u64 *M, u64 *K, uint8_t *flags, int32_t *changed, int grid_blocks, hipStream_t s);
 

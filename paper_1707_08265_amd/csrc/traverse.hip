@@ -35,7 +35,8 @@ namespace dgn {
 // ------------------------------------------------------------------------------------------------
 // producer records, built once per graph
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_build_pinfo(GraphView g, int4 *pinfo)
+// *multi is set when some tensor has more than one producer (same value from every writer).
+__global__ __launch_bounds__(256) void k_build_pinfo(GraphView g, int4 *pinfo, int32_t *multi)
 {
     const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
     for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < g.num_tensors; t += gsize) {
@@ -49,17 +50,18 @@ __global__ __launch_bounds__(256) void k_build_pinfo(GraphView g, int4 *pinfo)
             r = make_int4(o, eb, g.in_rowptr[o + 1] - eb, 0);
         } else {
             r = make_int4(kMulti, pb, pe - pb, 0);
+            *multi = 1;
         }
         pinfo[t] = r;
     }
 }
 
-hipError_t launch_build_pinfo(const GraphView &g, int4 *pinfo, hipStream_t s)
+hipError_t launch_build_pinfo(const GraphView &g, int4 *pinfo, int32_t *multi, hipStream_t s)
 {
     if (g.num_tensors == 0) return hipSuccess;
     int64_t blocks = ((int64_t)g.num_tensors + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(k_build_pinfo, dim3((unsigned)blocks), dim3(256), 0, s, g, pinfo);
+    hipLaunchKernelGGL(k_build_pinfo, dim3((unsigned)blocks), dim3(256), 0, s, g, pinfo, multi);
     return hipGetLastError();
 }
 
@@ -830,8 +832,10 @@ hipError_t launch_fix_sweep(const GraphView &g, u64 *M, u64 *K, uint8_t *flags, 
 //   - when the pending table fills up it is written to memory (plain read-modify-write: its keys are
 //     distinct) and emptied; a later producer finds those bits in the tensor's word.
 // Loads and stores of M are ordinary cached ones: only this wave touches these words during the kernel.
-// Row bounds and edge targets do not depend on M and are fetched one and two groups ahead, so a
-// group's critical path is: load M of its outputs, resolve, store.
+// Row bounds and edge targets do not depend on M and are fetched one and two groups ahead, and M of a
+// group's first two outputs at the end of the group before it (behind that group's flush of the pending
+// table), so a group's critical path is: resolve, store.  The stores need no waiting for while every
+// tensor has one producer; the graph build says whether some tensor of the batch has several.
 // Each operator is expanded once with all 64 sets' bits (a level-synchronous traversal revisits the
 // operators of such deep, thin graphs tens of times) and nothing is queued.  A group with too many
 // edges for the tables, or with a tensor written twice inside the group, is walked one operator at a time.
@@ -840,9 +844,10 @@ constexpr int kSweepThreads = 256;
 constexpr int kOutSlots = 256;                      // table of the group's output tensors
 constexpr int kOutMax = kOutSlots * 3 / 4;
 constexpr int kPendSlots = 512;                     // pending pushes, kept across groups
-constexpr int kPendMax = kPendSlots * 3 / 4;
+constexpr int kPendMax = kPendSlots / 2;
 constexpr int kInMax = 256;                         // input edges of a group handled through the tables
-constexpr int kSweepDeps = 4;                       // in-group consumers per operator handled by the relaxation
+constexpr int kSweepDeps = 8;                       // in-group consumers per operator handled by the relaxation
+static_assert(kSweepDeps == 8, "a lane's consumers are read as one 64-bit word");
 
 struct SweepShared {
     int32_t okey[kOutSlots];                        // tensor id, -1 = empty
@@ -851,7 +856,7 @@ struct SweepShared {
     int32_t pkey[kPendSlots];
     u64 pval[kPendSlots];
     int ndep[kWave];                                // per lane: in-group consumers of its operator's outputs ...
-    uint8_t dep[kWave][kSweepDeps];                 // ... and the first few of them (their lanes)
+    alignas(8) uint8_t dep[kWave][kSweepDeps];      // ... and the first few of them (their lanes)
 };
 
 __device__ __forceinline__ int out_slot_of(int32_t t) { return (int)(((uint32_t)t * 0x9E3779B1u) >> 24); }
@@ -904,30 +909,32 @@ __device__ __forceinline__ void flush_pending(SweepShared &sh, u64 *M)
     wave_stores_done();
 }
 
-// Row bounds and the first few edge targets of one lane's operator.
+// Row bounds and the first few edge targets of one lane's operator.  The bounds are kept as loaded (no
+// arithmetic on them where they are fetched, and no branch around the loads: lanes past the graph's first
+// operator read its row instead), so that nothing waits for them before the group that uses them.
 struct SweepRow {
-    int ob, n_out, ib, n_in;
+    int ob, oe, ib, ie;
     int32_t to[2], ti[4];
 };
 
-__device__ __forceinline__ SweepRow sweep_row_bounds(const GraphView &g, int64_t o, bool valid)
+__device__ __forceinline__ SweepRow sweep_row_bounds(const GraphView &g, int64_t o, int64_t o_lo)
 {
+    const int64_t oc = o >= o_lo ? o : o_lo;
     SweepRow r{};
-    if (valid) {
-        r.ob = g.out_rowptr[o];
-        r.n_out = g.out_rowptr[o + 1] - r.ob;
-        r.ib = g.in_rowptr[o];
-        r.n_in = g.in_rowptr[o + 1] - r.ib;
-    }
+    r.ob = g.out_rowptr[oc];
+    r.oe = g.out_rowptr[oc + 1];
+    r.ib = g.in_rowptr[oc];
+    r.ie = g.in_rowptr[oc + 1];
     return r;
 }
 
-__device__ __forceinline__ void sweep_row_targets(const GraphView &g, SweepRow &r)
+__device__ __forceinline__ void sweep_row_targets(const GraphView &g, SweepRow &r, bool valid)
 {
+    const int n_out = valid ? r.oe - r.ob : 0, n_in = valid ? r.ie - r.ib : 0;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) r.to[j] = j < r.n_out ? g.out_idx[r.ob + j] : -1;
+    for (int j = 0; j < 2; ++j) r.to[j] = j < n_out ? g.out_idx[r.ob + j] : -1;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) r.ti[j] = j < r.n_in ? g.in_idx[r.ib + j] : -1;
+    for (int j = 0; j < 4; ++j) r.ti[j] = j < n_in ? g.in_idx[r.ib + j] : -1;
 }
 
 __device__ __forceinline__ int32_t sweep_out(const GraphView &g, const SweepRow &r, int j)
@@ -974,7 +981,7 @@ __device__ __forceinline__ void sliced_fold(SlicedCount &c, u64 x3, int planes_u
     }
 }
 
-__global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64 *M, u64 *K, int64_t *pq)
+__global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64 *M, u64 *K, int64_t *pq, int multi_producer)
 {
     __shared__ SweepShared s_all[kSweepThreads / kWave];
     SweepShared &sh = s_all[threadIdx.x >> 6];
@@ -982,6 +989,10 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64
     const int gi = blockIdx.x * (kSweepThreads / kWave) + (threadIdx.x >> 6);
     if (gi >= g.num_graphs) return;                          // wave-uniform
     const int64_t o_lo = g.op_off[gi], o_hi = g.op_off[gi + 1];
+    if (o_hi <= o_lo) {                                      // a graph without operators
+        if (pq) pq[(int64_t)gi * 64 + lane] = 0;
+        return;
+    }
     const int n_groups = (int)((o_hi - o_lo + kWave - 1) / kWave);
     const int planes_used = 33 - __builtin_clz((unsigned)n_groups | 1u);   // bit length of n_groups, plus one
     SlicedCount cnt;
@@ -994,18 +1005,21 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64
     }
     int pending = 0;                                         // occupied slots of the pending table (wave-uniform)
     int group = 0;
-    SweepRow cur = sweep_row_bounds(g, o_hi - 1 - lane, o_hi - 1 - lane >= o_lo);
-    sweep_row_targets(g, cur);
-    SweepRow nxt = sweep_row_bounds(g, o_hi - kWave - 1 - lane, o_hi - kWave - 1 - lane >= o_lo);
+    SweepRow cur = sweep_row_bounds(g, o_hi - 1 - lane, o_lo);
+    sweep_row_targets(g, cur, o_hi - 1 - lane >= o_lo);
+    SweepRow nxt = sweep_row_bounds(g, o_hi - kWave - 1 - lane, o_lo);
+    // M of a group's first two outputs is fetched while the group before it is worked on
+    u64 m_ahead0 = 0, m_ahead1 = 0;
+    if (o_hi - 1 - lane >= o_lo) {
+        if (cur.oe - cur.ob > 0) m_ahead0 = M[cur.to[0]];
+        if (cur.oe - cur.ob > 1) m_ahead1 = M[cur.to[1]];
+    }
     for (int64_t top = o_hi; top > o_lo; top -= kWave, ++group) {
         const int64_t o = top - 1 - lane;                    // lane 0 holds the highest id of the group
         const bool valid = o >= o_lo;
-        // fetch ahead: targets of the next group (its row bounds have arrived), row bounds of the one after
-        sweep_row_targets(g, nxt);
-        const int64_t o2 = top - 2 * kWave - 1 - lane;
-        const SweepRow nxt2 = sweep_row_bounds(g, o2, o2 >= o_lo);
         const SweepRow row = cur;
-        const int n_out = row.n_out, n_in = row.n_in;
+        const u64 m_row0 = m_ahead0, m_row1 = m_ahead1;
+        const int n_out = valid ? row.oe - row.ob : 0, n_in = valid ? row.ie - row.ib : 0;
         const int max_out = wave_max(n_out), max_in = wave_max(n_in);
         const int total_in = wave_sum(n_in);
         bool tables = wave_sum(n_out) <= kOutMax && total_in <= kInMax;
@@ -1026,19 +1040,19 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64
             }
             if (ballot64(twice) != 0) tables = false;        // a tensor written twice inside the group
         }
+        // Fetch ahead, here where the wait for this group's own targets is over: targets of the next group (its
+        // row bounds arrived with them), row bounds of the one after.
+        sweep_row_targets(g, nxt, o - kWave >= o_lo);
+        const SweepRow nxt2 = sweep_row_bounds(g, o - 2 * kWave, o_lo);
         u64 k = 0;
         if (tables) {
-            if (pending + total_in > kPendMax) {
-                flush_pending(sh, M);
-                pending = 0;
-            }
-            wave_stores_done();                              // M words stored by earlier groups are readable
             wave_lds_sync();
-            // the tensor's word in memory (seed bits, flushed pushes) plus what is pending for it
+            // the tensor's word in memory (seed bits, flushed pushes: fetched at the end of the previous
+            // group, behind its flush) plus what is pending for it
             for (int r = 0; r < max_out; ++r) {
                 if (r < n_out) {
                     const int32_t t = sweep_out(g, row, r);
-                    u64 m = M[t];
+                    u64 m = r == 0 ? m_row0 : r == 1 ? m_row1 : M[t];
                     for (int slot = pend_slot_of(t);; slot = (slot + 1) & (kPendSlots - 1)) {
                         const int32_t key = sh.pkey[slot];
                         if (key == -1) break;
@@ -1073,8 +1087,9 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64
             if (max_nd <= kSweepDeps) {
                 // Relaxation: as many steps as the longest dependency chain inside the group.
                 int d[kSweepDeps];
+                const u64 row_of_deps = *reinterpret_cast<const u64 *>(&sh.dep[lane][0]);     // all eight in one read
 #pragma unroll
-                for (int j = 0; j < kSweepDeps; ++j) d[j] = j < nd ? sh.dep[lane][j] : lane;
+                for (int j = 0; j < kSweepDeps; ++j) d[j] = j < nd ? (int)((row_of_deps >> (8 * j)) & 0xFF) : lane;
                 for (int it = 0; it < kWave; ++it) {
                     u64 add = 0;
 #pragma unroll
@@ -1145,6 +1160,22 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64
         if (valid) K[o] = k;
         cur = nxt;
         nxt = nxt2;
+        // Room in the pending table for everything the next group may push.  The words of M that the next
+        // group reads are fetched behind this flush, so they hold what it wrote; the stores of finished
+        // groups need no waiting for, because a tensor with one producer is never read again -- with
+        // several producers somewhere in the batch every group waits for them.
+        const bool valid_next = o - kWave >= o_lo;
+        if (pending + wave_sum(valid_next ? cur.ie - cur.ib : 0) > kPendMax) {
+            flush_pending(sh, M);
+            pending = 0;
+        } else if (multi_producer) {
+            wave_stores_done();
+        }
+        m_ahead0 = m_ahead1 = 0;
+        if (valid_next) {
+            if (cur.oe - cur.ob > 0) m_ahead0 = M[cur.to[0]];
+            if (cur.oe - cur.ob > 1) m_ahead1 = M[cur.to[1]];
+        }
         if (pq) {
             switch (group & 3) {                             // wave-uniform
             case 0: cnt.x0 = k; break;
@@ -1170,12 +1201,13 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64
     }
 }
 
-hipError_t launch_sweep_graphs(const GraphView &g, u64 *M, u64 *K, int64_t *per_query_count, hipStream_t s)
+hipError_t launch_sweep_graphs(const GraphView &g, u64 *M, u64 *K, int64_t *per_query_count, bool multi_producer,
+                               hipStream_t s)
 {
     if (g.num_graphs <= 0) return hipSuccess;
     const int per_block = kSweepThreads / kWave;
     hipLaunchKernelGGL(k_sweep_graphs, dim3((unsigned)((g.num_graphs + per_block - 1) / per_block)), dim3(kSweepThreads),
-                       0, s, g, M, K, per_query_count);
+                       0, s, g, M, K, per_query_count, multi_producer ? 1 : 0);
     return hipGetLastError();
 }
 

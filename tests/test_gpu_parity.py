@@ -327,6 +327,52 @@ def test_packed_batches_use_the_per_graph_sweep(dgn, oracle):
     assert_same(out, r, "non-topological batch")
 
 
+def _rewriting_graph(rng, num_ops, num_inputs):
+    """Operators in topological order where some tensors have several producers: an operator may write again to a
+    tensor that nobody has read yet (so every reader still comes after every writer), often one created many
+    operators earlier."""
+    ops, n_t, unread = [], num_inputs, []
+    for _ in range(num_ops):
+        ins = [int(rng.integers(max(0, n_t - 40), n_t)) for _ in range(int(rng.integers(1, 4)))]
+        unread = [t for t in unread if t not in ins]
+        outs = []
+        for _ in range(int(rng.integers(1, 3))):
+            if unread and rng.random() < 0.3:
+                y = unread[int(rng.integers(0, len(unread)))]
+                if y not in outs:
+                    outs.append(y)
+                    continue
+            outs.append(n_t)
+            unread.append(n_t)
+            n_t += 1
+        ops.append((ins, outs))
+    return graph_from_ops(ops, n_t, "rewriting"), ops
+
+
+def test_swept_batches_with_tensors_written_by_several_operators(dgn, oracle):
+    """The per-graph sweep fetches a group's tensor words while the group before it is still being worked on; a
+    tensor written again by an operator of an earlier group is the case where that word was stored by this very
+    sweep.  Graphs of several groups each, re-written tensors in the same and in different groups."""
+    rng = np.random.default_rng(77)
+    Q = 5
+    parts, rewritten = [], 0
+    for i in range(80):
+        gi, ops = _rewriting_graph(rng, int(rng.integers(100, 700)), 4)
+        writers = np.bincount(np.concatenate([np.asarray(o[1], np.int64) for o in ops]), minlength=gi.num_tensors)
+        rewritten += int((writers > 1).sum())
+        parts.append((gi, [[int(rng.integers(gi.num_tensors // 2, gi.num_tensors)) for _ in range(int(rng.integers(1, 4)))]
+                           for _ in range(Q)]))
+    assert rewritten > 1000
+    g, tg = _pack(parts, Q)
+    st = dgn.dgn_stats()
+    _, _, out = gpu_prune(dgn, g, tg, validate=True, stats=st)       # the order is topological: validation passes
+    _, r = oracle_prune(oracle, g, tg)
+    assert_same(out, r, "swept batch with re-written tensors")
+    assert st.levels == 0                                            # and the sweep was taken
+    _, _, out = gpu_prune(dgn, g, tg, traversal=1)
+    assert_same(out, r, "the same through the frontier traversal")
+
+
 def test_more_than_64_sets_run_word_by_word(dgn, oracle):
     """150 target sets on one graph: three words of 64, 64 and 22 sets, each equal to the oracle's run
     of Algorithm 1 on exactly those sets."""
