@@ -373,6 +373,47 @@ def test_swept_batches_with_tensors_written_by_several_operators(dgn, oracle):
     assert_same(out, r, "the same through the frontier traversal")
 
 
+def _hub_graph(rng, num_ops, num_inputs, wide):
+    """Topological operator list with hub tensors (each read by dozens of the operators that follow it, far more
+    than the sweep registers per producer) and, with ``wide``, operators of up to 12 inputs, so that 64
+    consecutive operators can have more input edges than the sweep's tables take."""
+    ops, n_t, hub = [], num_inputs, 0
+    for o in range(num_ops):
+        n_in = int(rng.choice([6, 9, 12])) if wide and rng.random() < 0.6 else int(rng.integers(1, 4))
+        ins = [hub if rng.random() < 0.45 else int(rng.integers(max(0, n_t - 40), n_t)) for _ in range(n_in)]
+        outs = list(range(n_t, n_t + int(rng.integers(1, 3))))
+        n_t += len(outs)
+        if o % 37 == 0:
+            hub = outs[0]
+        ops.append((ins, outs))
+    return graph_from_ops(ops, n_t, "hubs"), ops
+
+
+@pytest.mark.parametrize("wide", [False, True])
+def test_swept_batches_with_hub_tensors_and_wide_operators(dgn, oracle, wide):
+    """The sweep's side paths: a producer with more in-group readers than it registers (masks resolved lane by
+    lane instead of by relaxation) and groups with too many input edges for the tables (walked one operator at
+    a time, straight to memory), mixed with ordinary groups in the same graphs."""
+    rng = np.random.default_rng(91 + wide)
+    Q = 64
+    parts = []
+    for i in range(72):
+        gi, ops = _hub_graph(rng, int(rng.integers(130, 500)), 3, wide)
+        parts.append((gi, [[int(rng.integers(gi.num_tensors // 3, gi.num_tensors)) for _ in range(int(rng.integers(0, 3)))]
+                           for _ in range(Q)]))
+    readers = np.bincount(parts[0][0].in_tensor, minlength=parts[0][0].num_tensors)
+    assert readers.max() > 12                                        # hubs exist
+    if wide:
+        fan_in = np.bincount(parts[0][0].in_op, minlength=parts[0][0].num_ops)
+        assert max(fan_in[i:i + 64].sum() for i in range(0, len(fan_in) - 63)) > 256
+    g, tg = _pack(parts, Q)
+    st = dgn.dgn_stats()
+    _, _, out = gpu_prune(dgn, g, tg, validate=True, stats=st)
+    _, r = oracle_prune(oracle, g, tg)
+    assert_same(out, r, f"swept batch with hubs (wide={wide})")
+    assert st.levels == 0
+
+
 def test_more_than_64_sets_run_word_by_word(dgn, oracle):
     """150 target sets on one graph: three words of 64, 64 and 22 sets, each equal to the oracle's run
     of Algorithm 1 on exactly those sets."""
