@@ -34,6 +34,7 @@ constexpr int kMaxBatch = 512;              // launches enqueued between two sta
 constexpr int kTailLevels = 1;              // wide launches enqueued beyond the layout the previous prune needed ...
 constexpr int kExactStreak = 3;             // ... until that layout has fitted exactly this many prunes in a row
 constexpr int kStatusMulti = 16;            // word of the build's status block that says "a tensor has several producers"
+constexpr int kBackwardMaxBatch = 60;       // forward passes of the backward prune between two read-backs, at most
 constexpr int kSweepMinGraphs = 64;         // packed batches with at least this many graphs ...
 constexpr int64_t kSweepMaxGraphOps = 1 << 18;   // ... none larger than this use the per-graph sweep
 constexpr u64 kRecycleMagic = 0x44474e5f52435943ull;   // "DGN_RCYC"
@@ -267,6 +268,9 @@ struct dgn_graph {
     //   exact_streak: prunes in a row whose traversal followed the hinted layout to the launch; after a few the
     //     spare launches at its end are dropped (a miss then costs one more batch, and brings them back)
     mutable std::atomic<int> exact_streak[2] = {};
+    //   backward_passes: forward passes the last backward prune of this graph needed; the next one enqueues that many
+    //     before it looks at their outcome
+    mutable std::atomic<int> backward_passes = {};
 };
 
 namespace {
@@ -1009,16 +1013,29 @@ int dgn_backward_prune(const dgn_graph *g, int32_t num_pairs, const int32_t *obj
     if (rc != DGN_OK) return rc;
     int32_t *host_flags = static_cast<int32_t *>(pin);
     const int grid = g->num_cus * 8;
+    // Passes in batches, flags[2 + i] = "pass i of the batch added something", read back after each batch (a read-back
+    // idles the GPU for about as long as half a pass takes).  The first batch is as long as the previous call's whole
+    // run of passes, the following ones three passes each.
     int64_t passes = 0;
-    for (;;) {                                       // three passes per read-back; flags[1..3] = "pass added something"
-        FillRegion again[1] = {{S.flags + 2, 16}};
+    int batch = g->backward_passes.load(std::memory_order_relaxed) + 1;      // (how far a pass gets varies a little)
+    batch = batch < 3 ? 3 : batch > kBackwardMaxBatch ? kBackwardMaxBatch : batch;
+    for (;;) {
+        FillRegion again[1] = {{S.flags + 2, sizeof(int32_t) * (size_t)kBackwardMaxBatch}};
         if (passes) DGN_HIP(launch_clear(again, 1, s));
-        for (int i = 0; i < 3; ++i, ++passes)
+        for (int i = 0; i < batch; ++i)
             DGN_HIP(launch_forward_within(g->v, S.kept, S.kept_count, S.B, F, S.flags + 2 + i, grid, s));
-        DGN_HIP(hipMemcpyAsync(host_flags, S.flags, 32, hipMemcpyDeviceToHost, s));
+        DGN_HIP(hipMemcpyAsync(host_flags, S.flags, 256, hipMemcpyDeviceToHost, s));
         DGN_HIP(hipStreamSynchronize(s));
         if (host_flags[0] & kErrIdRange) return DGN_ERR_ID_OUT_OF_RANGE;
-        if (host_flags[4] == 0) break;               // the last pass of the batch changed nothing
+        int quiet = 0;                               // the first pass of the batch that changed nothing
+        while (quiet < batch && host_flags[2 + quiet] != 0) ++quiet;
+        if (quiet < batch) {
+            g->backward_passes.store((int)(passes + quiet + 1), std::memory_order_relaxed);
+            passes += batch;
+            break;
+        }
+        passes += batch;
+        batch = 3;
     }
     if (stats) stats->reserved = (int32_t)passes;
 
