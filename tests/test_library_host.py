@@ -101,6 +101,14 @@ def test_product_package_does_not_import_the_oracle():
     assert "import oracle" not in src and "from oracle" not in src
 
 
+def test_a_missing_library_is_an_import_error_not_a_fallback(monkeypatch, tmp_path):
+    """Without libdgn.so the package must refuse to load: there is no CPU path behind it."""
+    import paper_1707_08265_amd.binding as b
+    monkeypatch.setattr(b, "LIB_PATH", str(tmp_path / "libdgn.so"))
+    with pytest.raises(ImportError, match="no fallback"):
+        b._load()
+
+
 def test_other_entry_points_reject_bad_arguments_before_any_device_work(d):
     """Backward prune, in-place pass and read-outs: NULL handles and impossible sizes are refused on the host."""
     rc, _ = d.dgn_backward_prune_workspace(None)
