@@ -280,3 +280,41 @@ def test_other_buffers_or_another_graph_are_not_mistaken_for_the_previous_result
         assert int(st.recycled) == 0
         assert_same(small.to_host(), ref, "scratch last used for another graph")
     torch.cuda.synchronize()
+
+
+def test_two_host_threads_prune_the_same_graph_on_their_own_streams(dgn, oracle):
+    """The graph handle is shared (its launch-layout hints are the only thing calls write to it), buffers,
+    scratch and stream are each thread's own: the calls may overlap on the GPU and every result must still be
+    the oracle's."""
+    import threading
+    import torch
+    g, tg = gg.config(1, 0.3)
+    dg = dgn.DeviceGraph.from_coo(g)
+    adj, _ = oracle_prune(oracle, g, tg)
+    draws = _draws(g, tg, 5)
+    refs = [oracle.forward_prune(adj, t.num_sets, t.tgt_rowptr, t.tgt_idx, g.num_graphs, g.graph_op_offsets) for t in draws]
+    dev_targets = [(torch.from_numpy(t.tgt_rowptr).cuda(), torch.from_numpy(t.tgt_idx).cuda()) for t in draws]
+    torch.cuda.synchronize()
+    failures = []
+
+    def worker(k):
+        try:
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                buf = dgn.PruneBuffers(dg, tg.num_sets)
+                order = list(range(len(draws))) if k == 0 else list(reversed(range(len(draws))))
+                for rep in range(3):
+                    for i in order:
+                        rc = buf.prune(*dev_targets[i], stream=stream)
+                        assert rc == 0, dgn.dgn_strerror(rc)
+                        stream.synchronize()
+                        assert_same(buf.to_host(), refs[i], f"thread {k} rep {rep} draw {i}")
+        except Exception as e:      # noqa: BLE001 -- reported by the main thread
+            failures.append(f"thread {k}: {e!r}")
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not failures, failures
