@@ -28,6 +28,9 @@
  *     "ascending id = topological order" meaning of the kept list needs this precondition.
  *     Duplicate edges, tensors with several producers, and operators with no inputs or no
  *     outputs are legal.
+ *   - Host threads: calls on one dgn_graph may run at the same time from several threads as long as each
+ *     has output buffers, scratch and stream of its own (the handle only keeps launch-layout hints, which
+ *     any call may overwrite); two calls that share a scratch or output buffer must not overlap.
  */
 #ifndef DGN_H
 #define DGN_H
