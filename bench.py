@@ -74,6 +74,8 @@ def main():
     import torch
 
     import graphgen as gg
+    import __graft_entry__
+    __graft_entry__.ensure_built()          # a fresh checkout: build once; otherwise what is built is loaded
     import paper_1707_08265_amd as d
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"

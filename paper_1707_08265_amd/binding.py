@@ -76,7 +76,7 @@ class DgnError(RuntimeError):
 def _load() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with __graft_entry__.build() "
-                          f"(python -m paper_1707_08265_amd.build); there is no fallback path")
+                          f"(python __graft_entry__.py at the repository root); there is no fallback path")
     lib = ctypes.CDLL(LIB_PATH)
     lib.dgn_strerror.restype = c_char_p
     lib.dgn_strerror.argtypes = [c_int]

@@ -10,6 +10,8 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    import __graft_entry__
+    __graft_entry__.ensure_built()      # a fresh checkout has no libdgn.so yet: the package cannot be imported without it
 
 
 @pytest.fixture(scope="session")
