@@ -431,7 +431,17 @@ def main():
         "whole_path_algorithmic_GBs": round(b_alg_total / (ms_per_step * 1e-3) / 1e9, 1),
         "whole_path_frac": round(b_alg_total / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "measured_copy_GBs": copy_gbs,
+        "whole_path_measured_GBs": None, "whole_path_measured_frac": None,
     }
+
+    # bytes that crossed the HBM interface in one prune according to the committed counter runs (every kernel of the
+    # step: the level kernel once per launch), over the step time
+    if roofline["traffic"] is not None and recycled and dominant == "k_level":
+        per_step = [measured_traffic(k) for k in ("k_clear", "k_keep_count", "k_scatter")]
+        if all(v is not None for v in per_step):
+            moved = sum(per_step) + roofline["traffic"] * level_launches
+            roofline["whole_path_measured_GBs"] = round(moved / (ms_per_step * 1e-3) / 1e9, 1)
+            roofline["whole_path_measured_frac"] = round(moved / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
 
     # ---- CPU baseline: the oracle as it stands, on this machine's host cores -------------------------
     cpu = None
