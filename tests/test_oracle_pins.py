@@ -288,6 +288,82 @@ def test_generators_are_topological_and_seeded():
             assert np.array_equal(gi_in, go_in)
 
 
+def test_generators_follow_the_stated_recipes():
+    """Sizes, fan-in and fan-out distributions, edge spans and target draws of the five workloads, as their
+    recipes state them (checked on the small config at full size and on scaled-down copies of the others)."""
+    def fan(g):
+        return np.bincount(g.in_op, minlength=g.num_ops), np.bincount(g.out_op, minlength=g.num_ops)
+
+    # config 0: 2 000 operators, fan-in uniform 1..3 from the last 64 produced tensors + 16 inputs, 1..2 outputs
+    g, tg = gg.config(0, 1.0)
+    fi, fo = fan(g)
+    assert g.num_ops == 2000 and tg.num_sets == 1 and np.diff(tg.tgt_rowptr).tolist() == [4]
+    assert set(np.unique(fi)) == {1, 2, 3} and set(np.unique(fo)) == {1, 2}
+    assert abs(fi.mean() - 2.0) < 0.1 and abs(fo.mean() - 1.5) < 0.05
+    first_out = np.full(g.num_ops, g.num_tensors, np.int64)
+    np.minimum.at(first_out, g.out_op, g.out_tensor)
+    reach = first_out[g.in_op] - g.in_tensor                  # how far back an input lies, in tensor ids
+    from_inputs = g.in_tensor < 16
+    assert np.all(reach[~from_inputs] >= 1) and np.all(reach[~from_inputs] <= 64)
+    assert 0.1 < from_inputs.mean() < 0.3                    # 16 of 80 pool entries are graph inputs
+    assert tg.tgt_idx.min() >= int(0.9 * g.num_tensors) - 1   # targets from the last 10 % of the tensors
+
+    # config 1: layers of 400 operators, fan-in 1..3, a fifth of the inputs are skips of 2..32 layers, 64 sets of 1..8
+    g, tg = gg.config(1, 0.2)
+    fi, fo = fan(g)
+    assert g.num_ops % 400 == 0 and tg.num_sets == 64
+    assert set(np.unique(fi)) == {1, 2, 3} and set(np.unique(fo)) == {1, 2}
+    n_t = np.diff(tg.tgt_rowptr)
+    assert n_t.min() >= 1 and n_t.max() <= 8
+    prod_of = np.full(g.num_tensors, -400, np.int64)          # graph inputs: "layer -1"
+    prod_of[g.out_tensor] = g.out_op
+    span = g.in_op // 400 - prod_of[g.in_tensor] // 400       # layers between consumer and producer
+    inner = g.in_op // 400 >= 33                              # (near the bottom, skips are clamped to layer -1)
+    assert span[inner].min() == 1 and span[inner].max() <= 32
+    assert abs((span[inner] > 1).mean() - 0.2) < 0.02
+
+    # config 2: 1 000 operators per step, one output each, intra-step fan-in 1..3 plus a recurrent edge with prob. 0.1
+    g, tg = gg.config(2, 0.02)
+    fi, fo = fan(g)
+    assert g.num_ops % 1000 == 0 and np.all(fo == 1) and tg.num_sets == 1
+    assert np.diff(tg.tgt_rowptr).tolist() == [33]            # the loss tensor and 32 others
+    later = g.in_op >= 1000                                   # from the second step on
+    assert set(np.unique(fi[1000:])) <= {1, 2, 3, 4}
+    prod_of = np.full(g.num_tensors, -1, np.int64)
+    prod_of[g.out_tensor] = g.out_op
+    p = prod_of[g.in_tensor]
+    recurrent = later & (p >= 0) & (p == g.in_op - 1000)
+    assert abs(recurrent.sum() / (g.num_ops - 1000) - 0.1) < 0.01
+
+    # config 3: fan-in ~ k^-2.1 on 1..64 (truncated: P(1) = 0.645, mean 2.57), sources uniform over everything
+    # earlier, 1..3 outputs, 64 sets of 1..16 tensors from the last 5 %
+    g, tg = gg.config(3, 0.01)
+    fi, fo = fan(g)
+    w = np.arange(1, 65, dtype=np.float64) ** -2.1
+    w /= w.sum()
+    assert fi.min() == 1 and fi.max() <= 64 and set(np.unique(fo)) == {1, 2, 3}
+    assert abs((fi == 1).mean() - w[0]) < 0.01 and abs(fi.mean() - (w * np.arange(1, 65)).sum()) < 0.05
+    assert abs((fi == 2).mean() - w[1]) < 0.01 and abs(fo.mean() - 2.0) < 0.02
+    first_out = np.full(g.num_ops, g.num_tensors, np.int64)
+    np.minimum.at(first_out, g.out_op, g.out_tensor)
+    rel = g.in_tensor / np.maximum(first_out[g.in_op], 1)     # uniform over [0, first own output): mean one half
+    big = g.in_op > g.num_ops // 10
+    assert np.all(g.in_tensor < first_out[g.in_op]) and abs(rel[big].mean() - 0.5) < 0.01
+    n_t = np.diff(tg.tgt_rowptr)
+    assert tg.num_sets == 64 and n_t.min() >= 1 and n_t.max() <= 16
+    assert tg.tgt_idx.min() >= int(0.95 * g.num_tensors) - 1
+
+    # config 4: independent graphs of 20 000 operators, each as config 0, 64 sets of 4 targets per graph
+    g, tg = gg.config(4, 0.002)
+    assert g.num_graphs >= 2 and np.all(np.diff(g.graph_op_offsets) == 20000) and tg.num_sets == 64
+    assert np.all(np.diff(tg.tgt_rowptr) == 4) and len(tg.tgt_rowptr) == 64 * g.num_graphs + 1
+    fi, fo = fan(g)
+    assert set(np.unique(fi)) == {1, 2, 3} and set(np.unique(fo)) == {1, 2}
+    g0 = slice(int(g.graph_op_offsets[0]), int(g.graph_op_offsets[1]))
+    g1 = slice(int(g.graph_op_offsets[1]), int(g.graph_op_offsets[2]))
+    assert not np.array_equal(fi[g0], fi[g1])                 # every graph has its own seed
+
+
 @pytest.mark.parametrize("cfg,scale", [(0, 1.0), (1, 0.2), (3, 0.002)])
 def test_adding_targets_to_finished_marks_is_incremental(oracle, cfg, scale):
     """Algorithm 1 skips what is already marked ("if not m_x"), so running it for more targets on top of
