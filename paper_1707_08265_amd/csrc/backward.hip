@@ -62,8 +62,18 @@ __global__ __launch_bounds__(kFwThreads) void k_forward_within(GraphView g, cons
             oe = g.out_rowptr[o + 1];
         }
         for (int iter = 0; iter < kWave; ++iter) {          // a chain inside the group is at most 64 long
+            // four inputs at a time, their ids and then their marks in flight together (past the row's end the last
+            // input is read again): an operator with dozens of inputs would otherwise hold its wave for two dependent
+            // accesses per input
             u64 fin = 0;
-            for (int e = ib; e < ie; ++e) fin |= load_coherent(&F[g.in_idx[e]]);
+            for (int e = ib; e < ie; e += 4) {
+                const int last = ie - 1;
+                const int32_t x0 = g.in_idx[e], x1 = g.in_idx[min(e + 1, last)], x2 = g.in_idx[min(e + 2, last)],
+                              x3 = g.in_idx[min(e + 3, last)];
+                const u64 f0 = load_coherent(&F[x0]), f1 = load_coherent(&F[x1]), f2 = load_coherent(&F[x2]),
+                          f3 = load_coherent(&F[x3]);
+                fin |= (f0 | f1) | (f2 | f3);
+            }
             bool any_new = false;
             if (fin) {
                 for (int e = ob; e < oe; ++e) {
