@@ -60,19 +60,41 @@ __device__ __forceinline__ void offer_children(const GraphView &g, int64_t o, in
         lo = min(lo, u);
         hi = max(hi, u);
     }
-    for (int32_t e = g.in_rowptr[o]; e < g.in_rowptr[o + 1]; ++e) {
-        const int32_t x = g.in_idx[e];
+    // An input learns the child on offer.  `seen`: what its child word held a moment ago (a stale value only
+    // costs an atomic).
+    auto offer = [&](int32_t x, int32_t seen) {
         rename[x] = x;
-        if (hi < 0) continue;                               // an operator without outputs offers nothing
+        if (hi < 0) return;                                 // an operator without outputs offers nothing
         if (lo != hi) {                                     // two distinct children at once
             __hip_atomic_store(&child[x], kManyChildren, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            continue;
+            return;
         }
-        const int32_t seen = child[x];                      // a stale value only costs an atomic
-        if (seen == lo || seen == kManyChildren) continue;
+        if (seen == lo || seen == kManyChildren) return;
         const int32_t old = atomicCAS(&child[x], -1, lo);
         if (old != -1 && old != lo && old != kManyChildren)
             __hip_atomic_store(&child[x], kManyChildren, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
+    const bool look = hi >= 0 && lo == hi;                  // exactly one child on offer: the words are worth a look
+    const int32_t ib = g.in_rowptr[o], ie = g.in_rowptr[o + 1];
+    if (ie - ib <= 4) {
+        for (int32_t e = ib; e < ie; ++e) {
+            const int32_t x = g.in_idx[e];
+            offer(x, look ? child[x] : 0);
+        }
+        return;
+    }
+    // Many inputs: four at a time, their ids and then their child words fetched together (past the end the last
+    // input is read again) -- one after the other, an operator with dozens of inputs holds its wave for three
+    // dependent accesses per input.
+    for (int32_t e0 = ib; e0 < ie; e0 += 4) {
+        int32_t x[4], seen[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) x[j] = g.in_idx[min(e0 + j, ie - 1)];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) seen[j] = look ? child[x[j]] : 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (e0 + j < ie) offer(x[j], seen[j]);
     }
 }
 
