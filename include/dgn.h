@@ -275,7 +275,7 @@ int dgn_backward_prune_workspace(const dgn_graph *g, size_t *scratch_bytes);
  *   options, stats: HOST, may be NULL; stats describes the first stage (the traversal from the
  *       derivative targets), stats->reserved = passes of the forward stage.  options->recycle: the
  *       caller states that the last call that used `scratch` was a dgn_backward_prune of this graph
- *       with this tensor_mask and op_mask, and that nobody has written to the three since: the call
+ *       with this tensor_mask, op_mask and op_flag, and that nobody has written to them since: the call
  *       then zeroes only the words that call set (checked on the device, as for dgn_prune).
  *
  * Single graphs only (DGN_ERR_INVALID_ARG for a packed batch).  An id outside [0, num_tensors) is

@@ -852,9 +852,11 @@ int dgn_prune(const dgn_graph *g, int32_t num_sets, int64_t num_targets, const i
 }
 
 // Removal rule + compaction: K computed from tensor_mask_in (from_tensor_mask), or taken as it stands in op_mask.
+// flag_in (or NULL): a byte per operator, 1 exactly where op_mask is not zero (then K is read there only).
 static int keep_compact_impl(const dgn_graph *g, const uint64_t *tensor_mask_in, bool from_tensor_mask, uint64_t *op_mask,
                              uint8_t *op_flag, int32_t *kept_ops, uint64_t *kept_masks, int64_t *kept_count,
-                             int64_t *per_query_count, void *scratch, size_t scratch_bytes, dgn_stream stream)
+                             int64_t *per_query_count, void *scratch, size_t scratch_bytes, dgn_stream stream,
+                             const uint8_t *flag_in = nullptr)
 {
     if (!g) return DGN_ERR_NULL_PTR;
     if (!kept_count || !scratch) return DGN_ERR_NULL_PTR;
@@ -882,6 +884,7 @@ static int keep_compact_impl(const dgn_graph *g, const uint64_t *tensor_mask_in,
     ca.pq_part = S.pq_part;
     ca.pq_replicas = S.pq_replicas;
     ca.from_tensor_mask = from_tensor_mask;
+    ca.flag_in = from_tensor_mask ? nullptr : flag_in;
     DGN_HIP(launch_keep_compact(ca, s));
     return DGN_OK;
 }
@@ -999,10 +1002,17 @@ int dgn_backward_prune(const dgn_graph *g, int32_t num_pairs, const int32_t *obj
     // The marked masks F (the caller's tensor_mask) and the final K (its op_mask) are non-zero only inside stage
     // one's coloured set and kept list, so stage one zeroes them along with its own M and K: everything, or, when
     // the caller recycles the buffers, what the previous call's log and kept list name.
+    // Stage one keeps its flag bytes (1 for every operator of its kept list) in the caller's op_flag when that can take
+    // them, else in its scratch; the final removal rule turns them into the flags of the result, which spares the
+    // last count pass the read of all of K.
     int rc = prune_impl(g, num_pairs, num_pairs, S.tgt_rowptr, wrt, reinterpret_cast<uint64_t *>(S.B),
-                        reinterpret_cast<uint64_t *>(S.KB), nullptr, S.kept, nullptr, S.kept_count, nullptr, scratch,
+                        reinterpret_cast<uint64_t *>(S.KB), op_flag, S.kept, nullptr, S.kept_count, nullptr, scratch,
                         S.prune_bytes, &o1, stats, stream, tensor_mask, op_mask);
     if (rc != DGN_OK) return rc;
+    uint8_t *stage_flags = nullptr;
+    if (!o1.recompute_keep)
+        stage_flags = (op_flag && ((uintptr_t)op_flag & 7) == 0 && g->P % 8 == 0)
+                          ? op_flag : prune_scratch(scratch, g->P, g->T, g->G, o1.max_queue_entries).flagbuf;
 
     // stage two: forwards from every x_obj, inside the coloured set of stage one
     FillRegion clr[1] = {{S.flags, 256}};
@@ -1041,9 +1051,9 @@ int dgn_backward_prune(const dgn_graph *g, int32_t num_pairs, const int32_t *obj
 
     // Removal rule and ordered compaction on the marked set.  A marked tensor lies in stage one's coloured set,
     // so only operators of stage one's kept list can have a marked output: K is cleared and written for those.
-    DGN_HIP(launch_keep_from_list(g->v, S.kept, S.kept_count, F, reinterpret_cast<u64 *>(op_mask), grid, s));
+    DGN_HIP(launch_keep_from_list(g->v, S.kept, S.kept_count, F, reinterpret_cast<u64 *>(op_mask), stage_flags, grid, s));
     return keep_compact_impl(g, tensor_mask, false, op_mask, op_flag, kept_ops, kept_masks, kept_count, per_query_count,
-                             scratch, S.prune_bytes, stream);
+                             scratch, S.prune_bytes, stream, stage_flags);
 }
 
 int dgn_ignore_mask(const dgn_graph *g, const uint64_t *tensor_mask, const int32_t *kept_ops, const uint64_t *kept_masks,

@@ -92,9 +92,10 @@ __global__ __launch_bounds__(kFwThreads) void k_forward_within(GraphView g, cons
     if (ballot64(added) && lane == 0) *changed = 1;         // same value from every writer
 }
 
-// K[o] = OR of F over the outputs of o (removal rule of Sec. 2.1), for the operators of a kept list only
+// K[o] = OR of F over the outputs of o (removal rule of Sec. 2.1), for the operators of a kept list only; flags
+// (or NULL): a byte per operator that is 1 exactly for the operators of the list on entry, 1 where K != 0 on return
 __global__ __launch_bounds__(kFwThreads) void k_keep_from_list(GraphView g, const int32_t *kept, const int64_t *kept_count,
-                                                                const u64 *F, u64 *K)
+                                                                const u64 *F, u64 *K, uint8_t *flags)
 {
     const int64_t n = *kept_count;
     const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
@@ -103,13 +104,15 @@ __global__ __launch_bounds__(kFwThreads) void k_keep_from_list(GraphView g, cons
         u64 k = 0;
         for (int32_t e = g.out_rowptr[o]; e < g.out_rowptr[o + 1]; ++e) k |= F[g.out_idx[e]];
         K[o] = k;
+        if (flags && k == 0) flags[o] = 0;
     }
 }
 
 hipError_t launch_keep_from_list(const GraphView &g, const int32_t *kept, const int64_t *kept_count, const u64 *F, u64 *K,
-                                 int grid_blocks, hipStream_t s)
+                                 uint8_t *flags, int grid_blocks, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_keep_from_list, dim3((unsigned)grid_blocks), dim3(kFwThreads), 0, s, g, kept, kept_count, F, K);
+    hipLaunchKernelGGL(k_keep_from_list, dim3((unsigned)grid_blocks), dim3(kFwThreads), 0, s, g, kept, kept_count, F, K,
+                       flags);
     return hipGetLastError();
 }
 

@@ -294,7 +294,7 @@ hipError_t launch_target_digest(int32_t num_sets, int64_t n, const int32_t *tgt_
 hipError_t launch_backward_seed(int64_t T, int num_pairs, const int32_t *obj, const int32_t *wrt, int32_t *tgt_rowptr,
                                 const u64 *B, u64 *F, int32_t *flags, bool rowptr_only, hipStream_t s);
 hipError_t launch_keep_from_list(const GraphView &g, const int32_t *kept, const int64_t *kept_count, const u64 *F, u64 *K,
-                                 int grid_blocks, hipStream_t s);
+                                 uint8_t *flags, int grid_blocks, hipStream_t s);
 hipError_t launch_forward_within(const GraphView &g, const int32_t *kept, const int64_t *kept_count, const u64 *B, u64 *F,
                                  int32_t *changed, int grid_blocks, hipStream_t s);
 

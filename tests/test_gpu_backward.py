@@ -168,3 +168,37 @@ def test_full_size_config3_sampled_pairs(dgn, oracle):
     assert np.array_equal(out["op_mask"], K) and np.array_equal(out["op_flag"], flag)
     assert np.array_equal(out["kept_ops"], kept_ops) and np.array_equal(out["kept_masks"], kept_masks)
     assert np.array_equal(out["kept_count"], kept_count) and np.array_equal(out["per_query_count"], pq)
+
+
+@pytest.mark.parametrize("k,scale", [(1, 0.3), (3, 0.1)])
+def test_flag_array_of_the_caller_absent_or_unaligned(dgn, oracle, k, scale):
+    """The first stage keeps a byte per kept operator in the caller's op_flag when that is 8-byte aligned, else in
+    scratch memory, and the last count pass reads those bytes instead of all of K: the result must not depend on
+    where they live (config 3 at five million operators takes the flag-driven count pass)."""
+    import torch
+    g, _ = gg.config(k, scale)
+    n_pairs = 64 if k == 1 else 4                           # (the oracle searches the whole graph once per pair)
+    obj, wrt = gg.backward_pairs(g, 99 + k, n_pairs, 400 if k == 1 else 16)
+    ref = oracle.backward_prune(_adj(oracle, g), obj, wrt)
+    dg = dgn.DeviceGraph.from_coo(g)
+    buf = dgn.BackwardPruneBuffers(dg, n_pairs)
+    own = buf.op_flag
+    for how in ("aligned", "none", "unaligned", "aligned"):
+        if how == "none":
+            buf.op_flag = None
+        elif how == "unaligned":
+            store = torch.zeros(g.num_ops + 8, dtype=torch.uint8, device="cuda")
+            buf.op_flag = store[1:1 + g.num_ops]
+        else:
+            buf.op_flag = own
+        for rep in range(2):                                # the second call recycles what the first left
+            rc = buf.backward_prune(torch.from_numpy(obj).cuda(), torch.from_numpy(wrt).cuda())
+            assert rc == 0, dgn.dgn_strerror(rc)
+            torch.cuda.synchronize()
+            n = int(buf.kept_count[0].item())
+            assert np.array_equal(buf.tensor_mask.cpu().numpy().view(np.uint64), ref.tensor_mask), how
+            assert np.array_equal(buf.op_mask.cpu().numpy().view(np.uint64), ref.op_mask), how
+            assert np.array_equal(buf.kept_ops[:n].cpu().numpy(), ref.kept_ops), how
+            assert np.array_equal(buf.per_query_count.cpu().numpy(), ref.per_query_count), how
+            if buf.op_flag is not None:
+                assert np.array_equal(buf.op_flag.cpu().numpy(), ref.op_flag), how
