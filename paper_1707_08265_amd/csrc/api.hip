@@ -284,13 +284,14 @@ int finish_build(dgn_graph *h, const GraphLayout &L, const int64_t *op_off_host,
         DGN_HIP(hipMemcpyAsync(L.t_off, t_off_host, sizeof(int64_t) * (h->G + 1), hipMemcpyHostToDevice, s));
         h->v.op_off = L.op_off;
         h->v.t_off = L.t_off;
-        DGN_HIP(launch_check_graph_ranges(h->v, status, s));
     }
     // The topological precondition is checked when the caller asks for validation, and for packed
     // batches, whose per-graph sweep is only chosen when it holds.  (One random access per edge: not
-    // worth paying on every build of a big single graph, whose traversal does not depend on it.)
+    // worth paying on every build of a big single graph, whose traversal does not depend on it.)  A packed batch
+    // gets it in the walk over the edges that checks the graphs' ranges.
     const bool check_topo = (options && options->validate) || h->G >= kSweepMinGraphs;
-    if (check_topo) DGN_HIP(launch_check_topological(h->v, status, s));
+    if (h->G > 1) DGN_HIP(launch_check_graph_ranges(h->v, status, check_topo, s));
+    else if (check_topo) DGN_HIP(launch_check_topological(h->v, status, s));
     void *pin = nullptr;
     int rc = pinned_buffer(&pin);
     if (rc) return rc;

@@ -225,7 +225,7 @@ hipError_t launch_check_csr(const int32_t *rowptr, const int32_t *idx, int32_t n
                             int32_t n_vals, int32_t *error, hipStream_t s);
 hipError_t launch_expand_rows(const int32_t *rowptr, int32_t n_rows, int32_t *row_of, hipStream_t s);
 hipError_t launch_check_topological(const GraphView &g, int32_t *error, hipStream_t s);
-hipError_t launch_check_graph_ranges(const GraphView &g, int32_t *error, hipStream_t s);
+hipError_t launch_check_graph_ranges(const GraphView &g, int32_t *error, bool also_topological, hipStream_t s);
 
 // Traversal.
 hipError_t launch_build_pinfo(const GraphView &g, int4 *pinfo, int32_t *multi, hipStream_t s);

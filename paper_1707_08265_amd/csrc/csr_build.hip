@@ -243,7 +243,9 @@ __device__ __forceinline__ int find_graph(const int64_t *off, int num_graphs, in
     return lo;
 }
 
-__global__ __launch_bounds__(256) void k_check_graph_ranges(GraphView g, int32_t *error)
+// also_topological: the topological precondition is checked in the same walk (see k_check_topological), which
+// spares a packed batch a second pass over its input edges.
+__global__ __launch_bounds__(256) void k_check_graph_ranges(GraphView g, int32_t *error, bool also_topological)
 {
     // a wave walks a contiguous stretch of operators 64 at a time, so a lane's graph index only ever steps
     // forward: one binary search per lane, not one per operator
@@ -251,26 +253,37 @@ __global__ __launch_bounds__(256) void k_check_graph_ranges(GraphView g, int32_t
     const int64_t wave_id = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x >> 6);
     const int64_t per = (((int64_t)g.num_ops + waves - 1) / waves + kWave - 1) / kWave * kWave;
     const int64_t first = wave_id * per, last = min(first + per, (int64_t)g.num_ops);
-    bool bad = false;
+    bool bad = false, late = false;
     int gi = -1;
     for (int64_t o = first + lane_id(); o < last; o += kWave) {
         if (gi < 0) gi = find_graph(g.op_off, g.num_graphs, o);
         while (o >= g.op_off[gi + 1]) ++gi;                 // op_off[num_graphs] == num_ops > o: stops in range
         const int64_t lo = g.t_off[gi], hi = g.t_off[gi + 1];
-        for (int32_t e = g.in_rowptr[o]; e < g.in_rowptr[o + 1]; ++e)
-            if (g.in_idx[e] < lo || g.in_idx[e] >= hi) bad = true;
+        for (int32_t e = g.in_rowptr[o]; e < g.in_rowptr[o + 1]; ++e) {
+            const int32_t t = g.in_idx[e];
+            if (t < lo || t >= hi) bad = true;
+            if (also_topological && t >= 0 && t < g.num_tensors) {
+                const int4 pi = g.pinfo[t];
+                if (pi.x >= 0) {
+                    if (pi.x >= o) late = true;
+                } else if (pi.x == kMulti) {
+                    for (int32_t p = pi.y; p < pi.y + pi.z; ++p)
+                        if (g.prod_idx[p] >= o) late = true;
+                }
+            }
+        }
         for (int32_t e = g.out_rowptr[o]; e < g.out_rowptr[o + 1]; ++e)
             if (g.out_idx[e] < lo || g.out_idx[e] >= hi) bad = true;
     }
-    if (bad) atomicOr(error, kErrCrossGraph);
+    if (bad || late) atomicOr(error, (bad ? kErrCrossGraph : 0) | (late ? kErrTopo : 0));
 }
 
-hipError_t launch_check_graph_ranges(const GraphView &g, int32_t *error, hipStream_t s)
+hipError_t launch_check_graph_ranges(const GraphView &g, int32_t *error, bool also_topological, hipStream_t s)
 {
     if (g.num_ops == 0 || g.num_graphs <= 1) return hipSuccess;
     int64_t blocks = ((int64_t)g.num_ops + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(k_check_graph_ranges, dim3((unsigned)blocks), dim3(256), 0, s, g, error);
+    hipLaunchKernelGGL(k_check_graph_ranges, dim3((unsigned)blocks), dim3(256), 0, s, g, error, also_topological);
     return hipGetLastError();
 }
 
