@@ -58,8 +58,7 @@ enum {
     DGN_ERR_WORKSPACE_TOO_SMALL = -6, /* graph_bytes or scratch_bytes below the queried size      */
     DGN_ERR_NOT_TOPOLOGICAL = -7,     /* validation found a producer id >= its consumer id        */
     DGN_ERR_HIP = -8,                 /* a HIP call failed; see dgn_last_hip_error()              */
-    DGN_ERR_BAD_CSR = -9,             /* row pointers not monotone or not ending at nnz           */
-    DGN_ERR_INTERNAL = -10            /* a device-side wait gave up (results are not valid)       */
+    DGN_ERR_BAD_CSR = -9              /* row pointers not monotone or not ending at nnz           */
 };
 
 /* Operators as two COO edge lists, in any order (Sec. 2.2: an operator with its inputs and its

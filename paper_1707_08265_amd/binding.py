@@ -26,7 +26,6 @@ DGN_ERR_WORKSPACE_TOO_SMALL = -6
 DGN_ERR_NOT_TOPOLOGICAL = -7
 DGN_ERR_HIP = -8
 DGN_ERR_BAD_CSR = -9
-DGN_ERR_INTERNAL = -10
 
 EXPORTS = [
     "dgn_graph_build_workspace", "dgn_graph_build", "dgn_graph_from_csr_workspace", "dgn_graph_from_csr",

@@ -339,7 +339,6 @@ const char *dgn_strerror(int code)
         case DGN_ERR_NOT_TOPOLOGICAL: return "operator ids are not a topological order";
         case DGN_ERR_HIP: return "HIP runtime error";
         case DGN_ERR_BAD_CSR: return "malformed CSR row pointers";
-        case DGN_ERR_INTERNAL: return "a device-side wait gave up";
         default: return "unknown error";
     }
 }
@@ -581,8 +580,10 @@ static int prune_impl(const dgn_graph *g, int32_t num_sets, int64_t num_targets,
     const ColourLog log{recycle ? S.log.entries : nullptr, S.log.cnt, S.log.seg_cap};
     const RecycleHeader want{kRecycleMagic, g->serial, M, K, kept_ops, kept_count, flags, also_M, also_K, {0, 0, 0}};
     if (recycle) {
+        // (the flag bytes are cleared whether or not this call's count pass reads them: the header this call leaves
+        // names them, and the call that finds it zeroes them at this call's kept operators only)
         FillRegion big[6] = {{M, (size_t)g->T * 8}, {K, (size_t)g->P * 8}, {S.DB, S.db_bytes},
-                             {flags, use_flags ? flag_bytes : 0}, {also_M, (size_t)g->T * 8}, {also_K, (size_t)g->P * 8}};
+                             {flags, flag_bytes}, {also_M, (size_t)g->T * 8}, {also_K, (size_t)g->P * 8}};
         DGN_HIP(launch_clear_or_reset(big, 6, S.hdr, want, reinterpret_cast<u64 *>(S.state + 1), S.log, kept_ops, kept_count, M, K,
                                       S.DB, flags, s));
         // (the word behind the state header says which way the kernel above went: it comes back with the header)

@@ -108,8 +108,13 @@ def test_deep_chain_and_edge_cases(dgn, oracle):
     g = graph_from_ops([([i], [i + 1]) for i in range(n)], n + 1)
     obj = np.asarray([0, 1000, 5, n, 7], np.int32)
     wrt = np.asarray([n, 2000, 5, 0, 8], np.int32)
-    dg, buf, out = gpu_backward(dgn, g, obj, wrt)
+    st = dgn.dgn_stats()
+    dg, buf, out = gpu_backward(dgn, g, obj, wrt, stats=st)
     assert_same(out, oracle.backward_prune(_adj(oracle, g), obj, wrt), "chain")
+    # the forward stage repeats whole passes over stage one's kept list until one adds nothing: on a chain a pass gets
+    # as far as the waves that happen to run in list order carry it, so the count is bounded by the groups of 64
+    print(f"chain of {n}: {int(st.reserved)} forward passes", flush=True)
+    assert 1 <= st.reserved <= n // 64 + 64
     # bad ids are reported, not followed
     bad = np.asarray([0, n + 5], np.int32)
     rc = buf.backward_prune(torch.from_numpy(bad).cuda(), torch.from_numpy(np.asarray([3, 4], np.int32)).cuda())

@@ -259,6 +259,16 @@ def _full_size_check(dgn, oracle, k, sampled_graphs=None):
             assert np.array_equal(out["per_query_count"][gi * 64:(gi + 1) * 64], r1.per_query_count), gi
             a, b = out["kept_count"][1 + gi], out["kept_count"][2 + gi]
             assert np.array_equal(out["kept_ops"][a:b] - oa, r1.kept_ops), gi
+        # (4) the per-graph outputs of EVERY graph, recounted from K: kept_count[1 + g] = kept operators below graph g's
+        # first operator; per_query_count[g*64 + q] = operators of graph g with bit q of K
+        kept_below = np.concatenate(([0], np.cumsum(out["op_mask"] != 0)))[g.graph_op_offsets]
+        assert np.array_equal(out["kept_count"][1:], kept_below.astype(np.int64))
+        pq = np.zeros((g.num_graphs, 64), dtype=np.int64)
+        graph_of = np.repeat(np.arange(g.num_graphs), np.diff(g.graph_op_offsets))
+        for q in range(Q):
+            has = ((out["op_mask"] >> np.uint64(q)) & np.uint64(1)).astype(bool)
+            pq[:, q] = np.bincount(graph_of[has], minlength=g.num_graphs)
+        assert np.array_equal(out["per_query_count"].reshape(g.num_graphs, 64), pq)
 
 
 def test_full_size_config2_unrolled_rnn(dgn, oracle):
@@ -628,3 +638,59 @@ def test_edges_and_targets_that_cross_packed_graphs_are_reported(dgn):
     idx[0] = int(g.graph_tensor_offsets[3])
     rc = buf.prune(torch.from_numpy(tg.tgt_rowptr).cuda(), torch.from_numpy(idx).cuda())
     assert rc == dgn.DGN_ERR_ID_OUT_OF_RANGE
+
+
+def test_depth_stress_unrolled_rnn_with_every_recurrent_edge(dgn, oracle):
+    """The unrolled-RNN family with a recurrent edge on EVERY operator and the final loss as the only target: the
+    dependence chain runs through all time steps, so the traversal needs at least as many levels as there are
+    steps (2 000 here, 50 operators each; the workload's own recurrent probability of 0.1 dies out after a few)."""
+    steps = 2000
+    g = gg.rnn(steps, 50, gg.BASE_SEED + 2000, rec_prob=1.0, name="rnn-depth-stress")
+    tg = targets_from_sets([[g.num_tensors - 1]])
+    st = dgn.dgn_stats()
+    _, _, out = gpu_prune(dgn, g, tg, stats=st)
+    _, r = oracle_prune(oracle, g, tg)
+    assert_same(out, r, "depth stress")
+    assert st.levels >= steps
+    kept_steps = np.unique(r.kept_ops // 50)
+    assert len(kept_steps) == steps            # every time step keeps an operator
+    _, _, out = gpu_prune(dgn, g, tg, traversal=2, defer_percent=70)
+    assert_same(out, r, "depth stress, deferral on")
+
+
+def test_borrowed_csr_with_bad_row_pointers_is_reported(dgn, oracle):
+    """dgn_graph_from_csr checks the borrowed row pointers on the device before any kernel trusts them."""
+    import torch
+    g, _ = gg.config(0, 0.5)
+    adj = oracle.build_adjacency(g.num_ops, g.num_tensors, g.in_op, g.in_tensor, g.out_op, g.out_tensor)
+    c = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    good = dict(in_rowptr=adj.in_rowptr.copy(), in_idx=adj.in_idx.copy(), out_rowptr=adj.out_rowptr.copy(),
+                out_idx=adj.out_idx.copy())
+
+    def build(**changed):
+        a = dict(good, **changed)
+        desc = dgn.make_csr_desc(g.num_ops, g.num_tensors, c(a["in_rowptr"]), c(a["in_idx"]), c(a["out_rowptr"]),
+                                 c(a["out_idx"]))
+        desc._keep = a
+        rc, gb, sb = dgn.dgn_graph_from_csr_workspace(desc)
+        assert rc == 0
+        mem = torch.empty(gb, dtype=torch.uint8, device="cuda")
+        scr = torch.empty(sb, dtype=torch.uint8, device="cuda")
+        rc, h = dgn.dgn_graph_from_csr(desc, mem, gb, scr, sb)
+        if h:
+            dgn.dgn_graph_destroy(h)
+        return rc
+
+    assert build() == 0
+    rp = good["in_rowptr"].copy()
+    rp[5], rp[6] = rp[6] + 1, rp[5]                      # decreasing somewhere in the middle
+    assert build(in_rowptr=rp) == dgn.DGN_ERR_BAD_CSR
+    rp = good["out_rowptr"].copy()
+    rp[-1] -= 1                                          # does not end at nnz
+    assert build(out_rowptr=rp) == dgn.DGN_ERR_BAD_CSR
+    rp = good["out_rowptr"].copy()
+    rp[0] = 1                                            # does not start at zero
+    assert build(out_rowptr=rp) == dgn.DGN_ERR_BAD_CSR
+    ix = good["in_idx"].copy()
+    ix[3] = g.num_tensors                                # a tensor id out of range
+    assert build(in_idx=ix) == dgn.DGN_ERR_ID_OUT_OF_RANGE

@@ -86,6 +86,37 @@ def test_recycled_prunes_of_a_graph_large_enough_for_the_flag_driven_count_pass(
     torch.cuda.synchronize()
 
 
+def test_flag_bytes_in_scratch_are_cleared_even_when_the_count_pass_does_not_read_them(dgn, oracle):
+    """The keep flags live in the scratch buffer when the caller gives no flag array.  A call with the stand-alone
+    removal-rule pass does not read them, but with ``recycle`` it leaves a header that names them: the call that
+    finds the header zeroes them at the kept operators only, so everything else must have been cleared by the call
+    that wrote it.  Sequence over a scratch buffer that starts as all 0xFF: stand-alone pass, stand-alone pass +
+    recycle, recycle (the flag-driven count pass: five million operators), each against the oracle."""
+    import torch
+    g, tg = gg.config(3, 0.1)
+    assert g.num_ops >= 1 << 22
+    dg = dgn.DeviceGraph.from_coo(g)
+    buf = dgn.PruneBuffers(dg, tg.num_sets, recycle=False)
+    buf.scratch.fill_(255)
+    adj, _ = oracle_prune(oracle, g, tg)
+    draws = _draws(g, tg, 3)
+    seq = [dict(recompute_keep=1), dict(recompute_keep=1, recycle=1), dict(recycle=1)]
+    recycled = []
+    for i, (t, knobs) in enumerate(zip(draws, seq)):
+        st = dgn.dgn_stats()
+        rc = dgn.dgn_prune(dg.handle, t.num_sets, len(t.tgt_idx), torch.from_numpy(t.tgt_rowptr).cuda(),
+                           torch.from_numpy(t.tgt_idx).cuda(), buf.tensor_mask, buf.op_mask, None, buf.kept_ops,
+                           buf.kept_masks, buf.kept_count, buf.per_query_count, buf.scratch, buf.scratch_bytes,
+                           options=dgn.dgn_options(**knobs), stats=st)
+        assert rc == 0, dgn.dgn_strerror(rc)
+        out = buf.to_host()
+        ref = oracle.forward_prune(adj, t.num_sets, t.tgt_rowptr, t.tgt_idx, g.num_graphs, g.graph_op_offsets)
+        for name in ("tensor_mask", "op_mask", "kept_count", "kept_ops", "kept_masks", "per_query_count"):
+            assert np.array_equal(out[name], getattr(ref, name)), f"call {i} {knobs}: {name}"
+        recycled.append(int(st.recycled))
+    assert recycled == [0, 0, 1], recycled
+
+
 def test_recycled_prunes_of_a_small_packed_batch(dgn, oracle):
     """Eight packed graphs go through the frontier traversal (the per-graph sweep starts at 64 graphs): the log,
     the per-graph kept offsets and the per-graph set counts must all survive recycling."""
