@@ -368,6 +368,32 @@ int dgn_inplace_kept(const dgn_graph *g, const uint64_t *op_mask, uint64_t selec
                      const int64_t *kept_count, int32_t *rename, int64_t *renamed_count, void *scratch,
                      size_t scratch_bytes, int32_t *rounds_out, dgn_stream stream);
 
+/* ---- machine rates --------------------------------------------------------------------------- */
+
+/* The traversal of Algorithm 1 moves few bytes; it is made of random 8-byte reads, 64-bit atomic ORs, kernel
+ * launches (one per wide frontier level) and chains of accesses that each wait for the one before.  None of
+ * these has a published peak, so dgn_calibrate measures them on this GPU, with HIP events on `stream`:
+ * they are the ceilings the traversal's own counts (atomics per prune, levels per prune) are priced against.
+ * HOST struct. */
+typedef struct dgn_machine_rates {
+    float random_load_gps;         /* 10^9 independent 8-byte loads per second, addresses uniform over the buffer */
+    float random_atomic_gps;       /* the same with returning 64-bit atomic ORs                                   */
+    float random_store_gps;        /* the same with plain 8-byte stores                                           */
+    float dependent_load_ns;       /* one step of a chain of loads whose address needs the value loaded before   */
+    float dependent_atomic_ns;     /* the same with returning atomics                                             */
+    float same_address_atomic_ns;  /* per atomic when 8 192 waves add to ONE word (a single shared counter)      */
+    float launch_floor_us;         /* event-to-event time of one empty kernel of 2 048 workgroups                 */
+    float launch_back_to_back_us;  /* per kernel in a run of 100 such kernels                                     */
+    float copy_gbs;                /* streaming copy inside the buffer, bytes read + written, 10^9 per second     */
+    float reserved[7];
+    int64_t buffer_bytes;
+} dgn_machine_rates;
+
+/* buffer: DEVICE, 16-byte aligned, at least 1 MiB; its contents are destroyed.  Pass a buffer of the size of
+ * the mask array of the workload (8 bytes per tensor) so that the random accesses see the workload's locality.
+ * Creates and destroys two HIP events, synchronises `stream` repeatedly, takes a few milliseconds. */
+int dgn_calibrate(void *buffer, size_t bytes, dgn_machine_rates *out, dgn_stream stream);
+
 /* ---- misc ---------------------------------------------------------------------------------- */
 const char *dgn_strerror(int code);
 int dgn_version(void);

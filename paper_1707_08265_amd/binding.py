@@ -32,7 +32,7 @@ EXPORTS = [
     "dgn_graph_get_csr", "dgn_graph_get_sizes", "dgn_graph_destroy", "dgn_prune_workspace", "dgn_prune",
     "dgn_prune_words", "dgn_keep_compact", "dgn_backward_prune_workspace", "dgn_backward_prune", "dgn_inplace_workspace",
     "dgn_inplace", "dgn_inplace_kept", "dgn_ignore_mask", "dgn_per_set_lists_workspace", "dgn_per_set_lists",
-    "dgn_target_digest_workspace", "dgn_target_digest", "dgn_strerror",
+    "dgn_target_digest_workspace", "dgn_target_digest", "dgn_calibrate", "dgn_strerror",
     "dgn_version",
     "dgn_last_hip_error",
 ]
@@ -62,6 +62,17 @@ class dgn_stats(ctypes.Structure):
                 ("launches", c_int64), ("level_launches", c_int64), ("level_trace", c_void_p),
                 ("level_trace_cap", c_int64), ("reserved", c_int64), ("recycled", c_int64),
                 ("phase_ms", ctypes.c_float * 8)]
+
+class dgn_machine_rates(ctypes.Structure):
+    _fields_ = [("random_load_gps", ctypes.c_float), ("random_atomic_gps", ctypes.c_float),
+                ("random_store_gps", ctypes.c_float), ("dependent_load_ns", ctypes.c_float),
+                ("dependent_atomic_ns", ctypes.c_float), ("same_address_atomic_ns", ctypes.c_float),
+                ("launch_floor_us", ctypes.c_float), ("launch_back_to_back_us", ctypes.c_float),
+                ("copy_gbs", ctypes.c_float), ("reserved", ctypes.c_float * 7), ("buffer_bytes", c_int64)]
+
+    def as_dict(self):
+        return {n: round(float(getattr(self, n)), 3) for n, _ in self._fields_[:9]} | {"buffer_bytes": int(self.buffer_bytes)}
+
 
 PHASES = ["clear", "seed", "traverse", "count", "scan", "scatter", "total"]
 
@@ -107,6 +118,7 @@ def _load() -> ctypes.CDLL:
     lib.dgn_target_digest_workspace.argtypes = [POINTER(c_size_t)]
     lib.dgn_target_digest.argtypes = [c_void_p, c_int32, c_int64, c_void_p, c_void_p, POINTER(ctypes.c_uint64), c_void_p,
                                       c_size_t, c_void_p]
+    lib.dgn_calibrate.argtypes = [c_void_p, c_size_t, POINTER(dgn_machine_rates), c_void_p]
     lib.dgn_inplace_workspace.argtypes = [c_void_p, POINTER(c_size_t)]
     lib.dgn_inplace.argtypes = [c_void_p, c_void_p, ctypes.c_uint64, c_void_p, c_void_p, c_void_p, c_size_t,
                                 POINTER(c_int32), c_void_p]
@@ -305,6 +317,13 @@ def dgn_target_digest(handle, num_sets, num_targets, tgt_rowptr, tgt_idx, scratc
     rc = _lib.dgn_target_digest(handle, num_sets, num_targets, _dp(tgt_rowptr), _dp(tgt_idx), out, _dp(scratch),
                                 scratch_bytes, _stream(stream))
     return rc, (int(out[0]), int(out[1]))
+
+
+def dgn_calibrate(buffer, nbytes, stream=None):
+    """Returns (return code, dgn_machine_rates)."""
+    out = dgn_machine_rates()
+    rc = _lib.dgn_calibrate(_dp(buffer), nbytes, ctypes.byref(out), _stream(stream))
+    return rc, out
 
 
 def dgn_inplace_workspace(handle):

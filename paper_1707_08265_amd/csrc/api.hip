@@ -26,6 +26,10 @@ inline int hip_fail(hipError_t e)
     } while (0)
 
 constexpr int64_t kMaxCount = 2147483646;   // counts must stay below 2^31 - 1
+#ifndef DGN_LEVEL_BLOCKS_PER_CU
+#define DGN_LEVEL_BLOCKS_PER_CU 5
+#endif
+constexpr int kLevelBlocksPerCU = DGN_LEVEL_BLOCKS_PER_CU;   // workgroups of a wide level per compute unit
 constexpr int kNarrowCap = 1024;            // frontiers up to this size are walked by one workgroup (one round of its threads)
 constexpr int kWidePerGroup = 12;           // wide level launches between two single-workgroup launches
 constexpr int kWideGroupsFirst = 4;         // groups in the first batch (one state read-back per batch) ...
@@ -39,9 +43,9 @@ constexpr int kSweepMinGraphs = 64;         // packed batches with at least this
 constexpr int64_t kSweepMaxGraphOps = 1 << 18;   // ... none larger than this use the per-graph sweep
 constexpr u64 kRecycleMagic = 0x44474e5f52435943ull;   // "DGN_RCYC"
 constexpr int kSmallLevel = 16384;           // levels expanding fewer entries than this decay the threshold faster
-constexpr int kDefaultDeferPercent = 85;
+constexpr int kDefaultDeferPercent = 78;
 constexpr int kDefaultStartShift = 1;       // deferral threshold starts at P >> 1 ...
-constexpr int kDefaultFloorShift = 9;       // ... and stops (drops to 0) below P >> 9
+constexpr int kDefaultFloorShift = 10;      // ... and stops (drops to 0) below P >> 10
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -81,7 +85,8 @@ int check_sizes(int64_t P, int64_t T, int64_t Ein, int64_t Eout, int32_t G, cons
 
 struct GraphLayout {
     int32_t *in_rowptr, *in_idx, *out_rowptr, *out_idx, *prod_rowptr, *prod_idx;
-    int4 *pinfo;
+    int4 *orec;
+    int32_t *prod1;
     int64_t *op_off, *t_off;
     size_t bytes;
 };
@@ -98,7 +103,8 @@ GraphLayout graph_layout(void *mem, int64_t P, int64_t T, int64_t Ein, int64_t E
     }
     L.prod_rowptr = c.take<int32_t>(T + 1);
     L.prod_idx = c.take<int32_t>(Eout);
-    L.pinfo = c.take<int4>(T);
+    L.orec = c.take<int4>(P);
+    L.prod1 = c.take<int32_t>(T);
     if (G > 1) {
         L.op_off = c.take<int64_t>(G + 1);
         L.t_off = c.take<int64_t>(G + 1);
@@ -278,7 +284,7 @@ namespace {
 int finish_build(dgn_graph *h, const GraphLayout &L, const int64_t *op_off_host, const int64_t *t_off_host,
                  int32_t *status, const dgn_options *options, hipStream_t s, dgn_graph **out)
 {
-    DGN_HIP(launch_build_pinfo(h->v, L.pinfo, status + kStatusMulti, s));
+    DGN_HIP(launch_build_records(h->v, L.orec, L.prod1, status + kStatusMulti, s));
     if (h->G > 1) {
         DGN_HIP(hipMemcpyAsync(L.op_off, op_off_host, sizeof(int64_t) * (h->G + 1), hipMemcpyHostToDevice, s));
         DGN_HIP(hipMemcpyAsync(L.t_off, t_off_host, sizeof(int64_t) * (h->G + 1), hipMemcpyHostToDevice, s));
@@ -421,7 +427,7 @@ int dgn_graph_build(const dgn_coo_desc *d, void *graph_mem, size_t graph_bytes, 
     if (!h) return DGN_ERR_INVALID_ARG;
     h->P = P; h->T = T; h->Ein = Ein; h->Eout = Eout; h->G = d->num_graphs;
     h->v = GraphView{(int32_t)P, (int32_t)T, (int32_t)Ein, (int32_t)Eout, d->num_graphs, L.in_rowptr, L.in_idx,
-                     L.out_rowptr, L.out_idx, L.prod_rowptr, L.prod_idx, nullptr, nullptr, L.pinfo};
+                     L.out_rowptr, L.out_idx, L.prod_rowptr, L.prod_idx, nullptr, nullptr, L.orec, L.prod1};
     rc = finish_build(h, L, d->graph_op_offsets, d->graph_tensor_offsets, S.status, options, s, out);
     if (rc) delete h;
     return rc;
@@ -480,7 +486,7 @@ int dgn_graph_from_csr(const dgn_csr_desc *d, void *graph_mem, size_t graph_byte
     if (!h) return DGN_ERR_INVALID_ARG;
     h->P = P; h->T = T; h->Ein = Ein; h->Eout = Eout; h->G = d->num_graphs;
     h->v = GraphView{(int32_t)P, (int32_t)T, (int32_t)Ein, (int32_t)Eout, d->num_graphs, d->in_rowptr, d->in_idx,
-                     d->out_rowptr, d->out_idx, L.prod_rowptr, L.prod_idx, nullptr, nullptr, L.pinfo};
+                     d->out_rowptr, d->out_idx, L.prod_rowptr, L.prod_idx, nullptr, nullptr, L.orec, L.prod1};
     rc = finish_build(h, L, d->graph_op_offsets, d->graph_tensor_offsets, S.status, options, s, out);
     if (rc) delete h;
     return rc;
@@ -682,7 +688,7 @@ static int prune_impl(const dgn_graph *g, int32_t num_sets, int64_t num_targets,
     //   2. otherwise batches of wide levels with a single-workgroup launch after every few of them; the
     //      removal-rule/compaction passes are enqueued right behind the first batch and redone only if
     //      the traversal turns out unfinished.
-    int grid = g->num_cus * 8;
+    int grid = g->num_cus * kLevelBlocksPerCU;
     const int64_t max_useful = (g->T + 255) / 256;
     if (grid > max_useful) grid = (int)(max_useful > 0 ? max_useful : 1);
     const bool generic_only = options && options->traversal == 1;

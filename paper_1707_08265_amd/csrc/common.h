@@ -32,12 +32,17 @@ struct GraphView {
     const int32_t *out_rowptr, *out_idx;
     const int32_t *prod_rowptr, *prod_idx;
     const int64_t *op_off, *t_off;    // [G+1] device copies, NULL when num_graphs == 1
-    const int4 *pinfo;                // [T] producer record of every tensor: (o, eb, deg, 0), see traverse.hip
+    // What the traversal reads per operator and per pushed tensor, one access each (see traverse.hip):
+    const int4 *orec;                 // [P] operator record (first input edge, fan-in, outputs)
+    const int32_t *prod1;             // [T] the producer of a tensor, or kMulti / kNoProducer
 };
 
-// producer-record / frontier-entry tags (values of the `o` field below zero)
-constexpr int32_t kFresh = -1;        // entry not looked up yet
-constexpr int32_t kMulti = -2;        // several producers: (eb, deg) index prod_idx
+// Operator record: x = first entry of the operator's row in in_idx, y = its fan-in, and the outputs: w >= 0
+// says that the operator writes the w tensors z, z + 1, ... (consecutive ids in the order of its row, the usual
+// case for a graph whose tensors are numbered as they are created), w < 0 that its -w outputs are
+// out_idx[z], out_idx[z + 1], ...
+// prod1 values below zero:
+constexpr int32_t kMulti = -2;        // several producers: see prod_rowptr / prod_idx
 constexpr int32_t kNoProducer = -3;   // graph input
 
 // Record of one launch of the traversal: the state it started from and whether it ran a level.
@@ -180,6 +185,10 @@ __device__ __forceinline__ void store_coherent(int32_t *p, int32_t v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ void store_coherent(u64 *p, u64 v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ __forceinline__ void store_coherent(uint8_t *p, uint8_t v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -228,7 +237,8 @@ hipError_t launch_check_topological(const GraphView &g, int32_t *error, hipStrea
 hipError_t launch_check_graph_ranges(const GraphView &g, int32_t *error, bool also_topological, hipStream_t s);
 
 // Traversal.
-hipError_t launch_build_pinfo(const GraphView &g, int4 *pinfo, int32_t *multi, hipStream_t s);
+// operator records and producer words, once per graph; *multi = 1 when some tensor has several producers
+hipError_t launch_build_records(const GraphView &g, int4 *orec, int32_t *prod1, int32_t *multi, hipStream_t s);
 hipError_t launch_seed(const GraphView &g, int32_t Q, int64_t num_targets, const int32_t *tgt_rowptr,
                        const int32_t *tgt_idx, u64 *M, TravState *st, TravCounters *ctr, int32_t *q0,
                        const QueueGeom &qg, int32_t theta0, const ColourLog &log, hipStream_t s);

@@ -211,11 +211,11 @@ __global__ __launch_bounds__(256) void k_check_topological(GraphView g, int32_t 
         for (int32_t e = g.in_rowptr[o]; e < g.in_rowptr[o + 1]; ++e) {
             const int32_t t = g.in_idx[e];
             if (t < 0 || t >= g.num_tensors) continue;      // reported by the range check
-            const int4 pi = g.pinfo[t];                     // one record instead of two CSR hops
-            if (pi.x >= 0) {
-                if (pi.x >= o) bad = true;
-            } else if (pi.x == kMulti) {
-                for (int32_t p = pi.y; p < pi.y + pi.z; ++p)
+            const int32_t pr = g.prod1[t];                  // one word instead of two CSR hops
+            if (pr >= 0) {
+                if (pr >= o) bad = true;
+            } else if (pr == kMulti) {
+                for (int32_t p = g.prod_rowptr[t]; p < g.prod_rowptr[t + 1]; ++p)
                     if (g.prod_idx[p] >= o) bad = true;
             }
         }
@@ -263,11 +263,11 @@ __global__ __launch_bounds__(256) void k_check_graph_ranges(GraphView g, int32_t
             const int32_t t = g.in_idx[e];
             if (t < lo || t >= hi) bad = true;
             if (also_topological && t >= 0 && t < g.num_tensors) {
-                const int4 pi = g.pinfo[t];
-                if (pi.x >= 0) {
-                    if (pi.x >= o) late = true;
-                } else if (pi.x == kMulti) {
-                    for (int32_t p = pi.y; p < pi.y + pi.z; ++p)
+                const int32_t pr = g.prod1[t];
+                if (pr >= 0) {
+                    if (pr >= o) late = true;
+                } else if (pr == kMulti) {
+                    for (int32_t p = g.prod_rowptr[t]; p < g.prod_rowptr[t + 1]; ++p)
                         if (g.prod_idx[p] >= o) late = true;
                 }
             }

@@ -4,76 +4,87 @@
 // The DFS of Algorithm 1 computes, per target set, the set of tensors with a directed path to a
 // target.  Marking is monotone (flags are only ever set), so the marked set is the least fixed point
 // of "a marked tensor marks all of its parents" and does not depend on visiting order: here the
-// frontier is processed level by level in parallel instead of depth first.
+// work is processed level by level in parallel instead of depth first.
 //
-// Invariants maintained by every kernel in this file (u64 masks, bit q = flag of set q):
+// The unit of work is an OPERATOR whose outputs have gained bits: processing o reads M of its outputs,
+// k = OR M[out(o)], and ORs the bits K[o] did not have yet into M of every input; an input u that gains
+// bits hands its producer on as new work.  Invariants (u64 masks, bit q = flag of set q):
 //   (I1)  K[o] only receives bits that some output of o holds in M;
-//   (I2)  whenever K[o] gains bits n, the same thread ORs n into M[i] of every input i of o;
-//   (I3)  whenever M[t] gains bits, t is queued for the next level, or (queue full) an overflow
-//         flag is raised and a fix-up sweep restores the fixed point afterwards;
-//   (I4)  processing frontier entry t ORs the whole current M[t] into K of every producer of t;
-//   (I5)  instead of (I4), an entry whose single producer o is below the level's threshold may set
-//         bit o of the deferred-operator bitmap; when the threshold passes o, K[o] receives the OR
-//         of M over all outputs of o (which covers every entry deferred to o).
-// At an empty frontier with no deferred operator left: K[o] = OR M[out(o)] and
-// M[t] = S[t] | OR_{o reads t} K[o].
+//   (I2)  whenever K[o] gains bits n, the same lane ORs n into M[u] of every input u of o;
+//   (I3)  whenever M[u] gains bits (the atomic's return value says so, to exactly one lane), every producer
+//         of u is noted for a LATER step: queued for the next level, or -- when its id is below the level's
+//         threshold -- stamped in a byte map that is read when the threshold has passed it; if a queue is
+//         full an overflow flag is raised and fix-up sweeps restore the fixed point afterwards;
+//   (I4)  a noted operator is processed in a launch (or, in the single-workgroup kernel, a barrier-separated
+//         level) after the one that noted it, so it sees the bits it was noted for.
+// With no work left: K[o] = OR M[out(o)] and M[t] = S[t] | OR_{o reads t} K[o].
 //
-// Why defer: 64-bit atomics retire at roughly 25 G/s on this chip whatever their locality, so the
-// traversal is bound by the number of atomics.  Operator ids are a topological order, hence a tensor
-// whose producer id is low keeps receiving bits from higher-numbered operators for many levels;
-// expanding it once, after the geometrically decaying threshold has passed it, replaces several
-// expansions (each costing 1 + fan-in atomics) by one.  The frontier itself is not deduplicated:
-// a duplicate entry finds its bits already in K and costs one atomic.
+// K is read and written without atomics.  Several lanes may process one operator in the same launch (the queue
+// is not deduplicated) and the last store may then lack bits another lane had seen; but such bits arrived during
+// this launch, so by (I3)/(I4) the operator is processed again later, and in the last launch that processes it
+// nothing arrives any more: every lane reads the same masks and stores the same, final, value.  A bit is pushed
+// to the inputs by the first lane that stores it (it was not in the K that lane had read).  Launches in which a
+// wave expands its own pushes at once (small levels, see run_level) break (I4) and use atomic ORs on K instead.
+//
+// Why thresholds: 64-bit atomics retire at roughly 20 G/s on this chip whatever their locality, so the
+// traversal is bound by the number of atomics -- one per input edge of a processed operator.  Operator ids are a
+// topological order, hence a low-numbered producer keeps receiving bits from higher-numbered operators for many
+// levels; processing it once, after the geometrically decaying threshold has passed it, replaces several
+// expansions by one.  It is a schedule only: the fixed point is the same for any order.
 #include "common.h"
 
 namespace dgn {
 
-// Frontier queues hold tensor ids.  A queue is split into S segments with one push counter each
-// (64 bytes apart): atomics on ONE address retire at about 11 ns each on this chip, so a single
-// counter bumped by every wave of a wide level would cost more than the level's real work.
-
 // ------------------------------------------------------------------------------------------------
-// producer records, built once per graph
+// operator records and producer words, built once per graph
 // ------------------------------------------------------------------------------------------------
-// *multi is set when some tensor has more than one producer (same value from every writer).
-__global__ __launch_bounds__(256) void k_build_pinfo(GraphView g, int4 *pinfo, int32_t *multi)
+__global__ __launch_bounds__(256) void k_build_records(GraphView g, int4 *orec, int32_t *prod1, int32_t *multi)
 {
-    const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < g.num_tensors; t += gsize) {
+    const int64_t gsize = (int64_t)gridDim.x * blockDim.x, gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (int64_t t = gtid; t < g.num_tensors; t += gsize) {
         const int32_t pb = g.prod_rowptr[t], pe = g.prod_rowptr[t + 1];
-        int4 r;
-        if (pe == pb) {
-            r = make_int4(kNoProducer, 0, 0, 0);
-        } else if (pe - pb == 1) {
-            const int32_t o = g.prod_idx[pb];
-            const int32_t eb = g.in_rowptr[o];
-            r = make_int4(o, eb, g.in_rowptr[o + 1] - eb, 0);
-        } else {
-            r = make_int4(kMulti, pb, pe - pb, 0);
-            *multi = 1;
+        int32_t r = kNoProducer;
+        if (pe - pb == 1) {
+            r = g.prod_idx[pb];
+        } else if (pe - pb > 1) {
+            r = kMulti;
+            *multi = 1;                                      // (the same value from every writer)
         }
-        pinfo[t] = r;
+        prod1[t] = r;
+    }
+    for (int64_t o = gtid; o < g.num_ops; o += gsize) {
+        const int32_t ib = g.in_rowptr[o], ie = g.in_rowptr[o + 1];
+        const int32_t ob = g.out_rowptr[o], oe = g.out_rowptr[o + 1];
+        const int32_t first = oe > ob ? g.out_idx[ob] : 0;
+        bool consecutive = true;
+        for (int32_t e = ob + 1; e < oe; ++e) consecutive &= g.out_idx[e] == first + (e - ob);
+        orec[o] = consecutive ? make_int4(ib, ie - ib, first, oe - ob) : make_int4(ib, ie - ib, ob, -(oe - ob));
     }
 }
 
-hipError_t launch_build_pinfo(const GraphView &g, int4 *pinfo, int32_t *multi, hipStream_t s)
+hipError_t launch_build_records(const GraphView &g, int4 *orec, int32_t *prod1, int32_t *multi, hipStream_t s)
 {
-    if (g.num_tensors == 0) return hipSuccess;
-    int64_t blocks = ((int64_t)g.num_tensors + 255) / 256;
+    const int64_t n = g.num_tensors > g.num_ops ? g.num_tensors : g.num_ops;
+    if (n == 0) return hipSuccess;
+    int64_t blocks = (n + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(k_build_pinfo, dim3((unsigned)blocks), dim3(256), 0, s, g, pinfo, multi);
+    hipLaunchKernelGGL(k_build_records, dim3((unsigned)blocks), dim3(256), 0, s, g, orec, prod1, multi);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------------
-// segmented frontier queues
+// segmented work queues
+//
+// A queue holds operator ids.  It is split into S segments with one push counter each (64 bytes apart):
+// atomics on ONE address retire at about 11 ns each on this chip, so a single counter bumped by every
+// wave of a wide level would cost more than the level's real work.
 // ------------------------------------------------------------------------------------------------
 constexpr int kStageCap = 256;     // staged pushes per wave before a flush (a power of two: the buffer is a ring)
 constexpr int kLogStageCap = 128;  // staged log entries per wave
 
-// Per-wave staging in LDS.  Next-frontier entries sit in a ring: slots are reserved with ballot + popcount, a
+// Per-wave staging in LDS.  Queue entries sit in a ring: slots are reserved with ballot + popcount, a
 // segment counter in memory is touched once per flush instead of once per push, and a wave may take entries
-// back out of the ring to expand them itself before they ever reach memory (see run_level).  Tensors coloured
+// back out of the ring to process them itself before they ever reach memory (see run_level).  Tensors coloured
 // for the first time are noted in a second, small buffer that is written to the log when it fills up and when
 // the kernel ends.
 struct WaveStage {
@@ -103,7 +114,7 @@ __device__ __forceinline__ void flush_entries(WaveStage &ws, const Frontier &f)
         int base = 0;
         if (lane_id() == 0) {
             base = atomicAdd(f.cnt, n);
-            if (base + n > f.seg_cap) atomicOr(f.error, kErrOverflow);   // (I3): fix-up sweep will follow
+            if (base + n > f.seg_cap) atomicOr(f.error, kErrOverflow);   // (I3): fix-up sweeps will follow
         }
         base = __builtin_amdgcn_readfirstlane(base);
         for (int k = lane_id(); k < n; k += kWave) {
@@ -131,28 +142,29 @@ __device__ __forceinline__ void flush_log(WaveStage &ws, const Frontier &f)
     }
 }
 
-// `first`: this push is the one that coloured t (its mask was zero before), which happens once per tensor.
-__device__ __forceinline__ void stage_push(WaveStage &ws, bool push, bool first, int32_t t, const Frontier &f)
+// Lanes with `push` queue operator `op`; lanes with `first` note tensor `t` as coloured by this prune (its
+// mask was zero before, which the atomic tells exactly one lane).  Wave-uniform control flow.
+__device__ __forceinline__ void stage_push(WaveStage &ws, bool push, int32_t op, bool first, int32_t t, const Frontier &f)
 {
     const u64 pm = ballot64(push);
-    if (pm) {                                   // wave-uniform branch
+    if (pm) {
         const int np = __popcll(pm);
         if (ws.tail - ws.head + np > kStageCap) flush_entries(ws, f);
-        if (push) ws.buf[(ws.tail + __popcll(pm & lanemask_lt())) & (kStageCap - 1)] = t;
+        if (push) ws.buf[(ws.tail + __popcll(pm & lanemask_lt())) & (kStageCap - 1)] = op;
         ws.tail += np;
-        if (ws.lbuf) {
-            const u64 fm = ballot64(first);
-            if (fm) {
-                const int nf = __popcll(fm);
-                if (ws.lcnt + nf > kLogStageCap) flush_log(ws, f);
-                if (first) ws.lbuf[ws.lcnt + __popcll(fm & lanemask_lt())] = t;
-                ws.lcnt += nf;
-            }
+    }
+    if (ws.lbuf) {
+        const u64 fm = ballot64(first);
+        if (fm) {
+            const int nf = __popcll(fm);
+            if (ws.lcnt + nf > kLogStageCap) flush_log(ws, f);
+            if (first) ws.lbuf[ws.lcnt + __popcll(fm & lanemask_lt())] = t;
+            ws.lcnt += nf;
         }
     }
 }
 
-// Reader side: item i of a frontier whose segment counts have the prefix sums s_pref[0..S].
+// Reader side: item i of a queue whose segment counts have the prefix sums s_pref[0..S].
 __device__ __forceinline__ int32_t load_item(const int32_t *q, const QueueGeom &qg, const int *s_pref, int i)
 {
     int lo = 0, hi = kMaxSeg - 1;               // segment holding item i: last s with s_pref[s] <= i
@@ -166,7 +178,8 @@ __device__ __forceinline__ int32_t load_item(const int32_t *q, const QueueGeom &
 }
 
 // ------------------------------------------------------------------------------------------------
-// seed: main loop of Algorithm 1 ("for t in T: if not m_t: ...") -- scatter the target bits
+// seed: main loop of Algorithm 1 ("for t in T: if not m_t: ...") -- scatter the target bits; the producers of
+// the targets are the first work
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_seed(GraphView g, int32_t Q, int64_t num_targets, int64_t num_sets_total,
                                                const int32_t *tgt_rowptr, const int32_t *tgt_idx, u64 *M,
@@ -178,7 +191,7 @@ __global__ __launch_bounds__(256) void k_seed(GraphView g, int32_t Q, int64_t nu
         st->slot[1].theta = theta0;
         st->slot[1].theta_hi = g.num_ops;
     }
-    bool push = false, first = false, bad = false, cross = false;
+    bool fresh = false, first = false, bad = false, cross = false;
     int32_t t = 0;
     if (j < num_targets) {
         // set s owns entries [tgt_rowptr[s], tgt_rowptr[s+1]): largest s with tgt_rowptr[s] <= j
@@ -199,23 +212,36 @@ __global__ __launch_bounds__(256) void k_seed(GraphView g, int32_t Q, int64_t nu
                 }
                 const u64 bit = (u64)1 << (lo % Q);
                 const u64 old = atomicOr(&M[t], bit);
-                push = (old & bit) == 0;                    // a duplicate target adds nothing new
+                fresh = (old & bit) == 0;                   // a duplicate target adds nothing new
                 first = old == 0;                           // this thread coloured t
             }
         }
     }
-    // wave-aggregated slot reservation: one counter update per wave, counters spread over segments
-    const u64 pm = q0 ? ballot64(push) : 0;    // no queue in the per-graph sweep mode: the bits in M are all it needs
+    // The producers of the tensors that gained a bit are queued (all of them, whatever the threshold: there are
+    // few).  Wave-aggregated slot reservation: one counter update per wave and round, counters spread over
+    // segments.  (No queue in the per-graph sweep mode: the bits in M are all it needs.)
     bool overflow = false;
-    if (pm) {
+    if (q0) {
+        int32_t pr = kNoProducer, pb = 0, np = 0;
+        if (fresh) {
+            pr = g.prod1[t];
+            if (pr >= 0) np = 1;
+            else if (pr == kMulti) { pb = g.prod_rowptr[t]; np = g.prod_rowptr[t + 1] - pb; }
+        }
+        const int rounds = wave_max(np);
         const int seg = (int)((j >> 6) & (qg.S - 1));
-        int base = 0;
-        if (lane_id() == 0) base = atomicAdd(&ctr->cnt[2][seg].v, __popcll(pm));   // tallies "of launch -1"
-        base = __builtin_amdgcn_readfirstlane(base);
-        const int pos = base + __popcll(pm & lanemask_lt());
-        if (push) {
-            if (pos < qg.seg_cap) q0[(int64_t)seg * qg.seg_cap + pos] = t;
-            else overflow = true;
+        for (int r = 0; r < rounds; ++r) {
+            const bool push = r < np;
+            const u64 pm = ballot64(push);
+            int base = 0;
+            if (lane_id() == 0) base = atomicAdd(&ctr->cnt[2][seg].v, __popcll(pm));   // tallies "of launch -1"
+            base = __builtin_amdgcn_readfirstlane(base);
+            const int pos = base + __popcll(pm & lanemask_lt());
+            if (push) {
+                const int32_t op = pr >= 0 ? pr : g.prod_idx[pb + r];
+                if (pos < qg.seg_cap) q0[(int64_t)seg * qg.seg_cap + pos] = op;
+                else overflow = true;
+            }
         }
     }
     bool log_full = false;
@@ -247,14 +273,40 @@ hipError_t launch_seed(const GraphView &g, int32_t Q, int64_t num_targets, const
 }
 
 // ------------------------------------------------------------------------------------------------
-// frontier expansion shared by the level kernels
+// operator processing shared by the level kernels
 // ------------------------------------------------------------------------------------------------
+struct LevelCounters {   // per-lane tallies, reduced by the caller
+    int processed;
+    int max_deferred_key;
+};
 
-// Lane l holds operator-side work (eb, deg, bits): OR `bits` into M of the deg inputs starting at
-// in_idx[eb].  The edges of all 64 lanes are spread evenly over the wave (prefix sum + search), so a
-// fan-in of 64 next to fan-ins of 1 costs no idle lanes.  Wave-uniform control flow throughout.
-__device__ __forceinline__ void expand_edges(const GraphView &g, int eb, int deg, u64 bits, u64 *M, int *s_incl,
-                                             WaveStage &ws, const Frontier &f)
+struct Masks {           // what a prune writes
+    u64 *M, *K;
+    uint8_t *DB;         // a byte per operator: "has gained bits and waits for the threshold to pass it"
+    uint8_t *flags;      // a byte per operator: K != 0 (read by the count pass instead of all of K)
+};
+
+// A tensor has gained bits: note one of its producers for a later step (I3).  Returns whether to queue it.
+__device__ __forceinline__ bool note_producer(int32_t op, int32_t theta, uint8_t *DB, LevelCounters &lc)
+{
+    if (op >= theta) return true;
+    DB[op] = 1;                 // a plain byte store, no atomic: read by a later launch, when theta has passed op
+    lc.max_deferred_key = max(lc.max_deferred_key, op);
+    return false;
+}
+
+// Lane l holds (eb, deg, bits): OR `bits` into M of the deg inputs starting at in_idx[eb].  The edges of
+// all 64 lanes are spread evenly over the wave (prefix sum + search), so a fan-in of 64 next to fan-ins
+// of 1 costs no idle lanes.  A wave with more than 64 edges takes kEdgeRounds rounds of 64 at a time: their
+// targets are fetched together, then their atomics sent together, so that a wave that met an operator with many
+// inputs pays the two dependent accesses once, not once per round.  Wave-uniform control flow throughout.
+#ifndef DGN_EDGE_ROUNDS
+#define DGN_EDGE_ROUNDS 1
+#endif
+constexpr int kEdgeRounds = DGN_EDGE_ROUNDS;
+
+__device__ __forceinline__ void expand_edges(const GraphView &g, int eb, int deg, u64 bits, int32_t theta, const Masks &mk,
+                                             int *s_incl, WaveStage &ws, const Frontier &f, LevelCounters &lc)
 {
     const int lane = lane_id();
     const int incl = wave_incl_scan(deg);
@@ -263,117 +315,105 @@ __device__ __forceinline__ void expand_edges(const GraphView &g, int eb, int deg
     if (total == 0) return;
     s_incl[lane] = incl;
     __builtin_amdgcn_wave_barrier();
-    for (int e0 = 0; e0 < total; e0 += kWave) {
-        const int e = e0 + lane;
-        const bool ev = e < total;
-        int lo = 0, hi = kWave - 1;                         // first lane whose inclusive sum exceeds e
+    for (int e0 = 0; e0 < total; e0 += kWave * kEdgeRounds) {
+        int32_t u[kEdgeRounds], pr[kEdgeRounds];
+        u64 b[kEdgeRounds], old[kEdgeRounds];
+        bool ev[kEdgeRounds];
 #pragma unroll
-        for (int it = 0; it < 6; ++it) {
-            const int mid = (lo + hi) >> 1;
-            if (s_incl[mid] > e) hi = mid; else lo = mid + 1;
+        for (int r = 0; r < kEdgeRounds; ++r) {
+            const int e = e0 + r * kWave + lane;
+            ev[r] = e < total;
+            int lo = 0, hi = kWave - 1;                     // first lane whose inclusive sum exceeds e
+#pragma unroll
+            for (int it = 0; it < 6; ++it) {
+                const int mid = (lo + hi) >> 1;
+                if (s_incl[mid] > e) hi = mid; else lo = mid + 1;
+            }
+            const int owner = lo;
+            const int o_eb = __shfl(eb, owner, kWave);
+            const int o_excl = __shfl(excl, owner, kWave);
+            b[r] = shfl64(bits, owner);
+            u[r] = ev[r] ? g.in_idx[o_eb + (e - o_excl)] : 0;
         }
-        const int owner = lo;
-        const int o_eb = __shfl(eb, owner, kWave);
-        const int o_excl = __shfl(excl, owner, kWave);
-        const u64 b = shfl64(bits, owner);
-        bool push = false, first = false;
-        int32_t u = 0;
-        if (ev) {
-            u = g.in_idx[o_eb + (e - o_excl)];
-            const u64 old = atomicOr(&M[u], b);             // (I2)
-            push = (b & ~old) != 0;                         // (I3)
-            first = old == 0;
+#pragma unroll
+        for (int r = 0; r < kEdgeRounds; ++r) {
+            pr[r] = kNoProducer;
+            old[r] = ~(u64)0;
+            if (ev[r]) {
+                pr[r] = g.prod1[u[r]];                      // in flight together with the atomic
+                old[r] = atomicOr(&mk.M[u[r]], b[r]);       // (I2)
+            }
         }
-        stage_push(ws, push, first, u, f);
+#pragma unroll
+        for (int r = 0; r < kEdgeRounds; ++r) {
+            if (e0 + r * kWave >= total) break;             // wave-uniform
+            bool push = false, many = false;
+            const bool first = ev[r] && old[r] == 0;
+            if (ev[r] && (b[r] & ~old[r]) != 0) {           // (I3): u gained bits
+                if (pr[r] >= 0) push = note_producer(pr[r], theta, mk.DB, lc);
+                else many = pr[r] == kMulti;
+            }
+            stage_push(ws, push, pr[r], first, u[r], f);
+            if (ballot64(many)) {                           // tensors with several producers: one round per producer rank
+                int pb = 0, np = 0;
+                if (many) { pb = g.prod_rowptr[u[r]]; np = g.prod_rowptr[u[r] + 1] - pb; }
+                const int rounds = wave_max(np);
+                for (int k = 0; k < rounds; ++k) {
+                    int32_t op = 0;
+                    bool p2 = false;
+                    if (k < np) {
+                        op = g.prod_idx[pb + k];
+                        p2 = note_producer(op, theta, mk.DB, lc);
+                    }
+                    stage_push(ws, p2, op, false, 0, f);
+                }
+            }
+        }
     }
     __builtin_amdgcn_wave_barrier();
 }
 
-struct LevelCounters {   // per-lane tallies, reduced by the caller
-    int processed;
-    int max_deferred_key;
-};
-
-// Tensor-side step: 64 frontier tensors held one per lane (valid lanes only).
-__device__ __forceinline__ void process_entries(const GraphView &g, bool valid, int32_t t, int32_t theta, uint8_t *DB,
-                                                uint8_t *flags, u64 *M, u64 *K, int *s_incl, WaveStage &ws,
-                                                const Frontier &f, LevelCounters &lc, bool lazy_mask)
-{
-    u64 m = 0;
-    bool active = false;
-    int4 pi = make_int4(kNoProducer, 0, 0, 0);
-    if (valid) {
-        pi = g.pinfo[t];                                    // (o, eb, deg): producer record
-        // (I4): everything t holds right now.  The single-workgroup kernel, bound by latency, issues the load
-        // together with the record; a wide level, where half the entries are deferred, only for the others
-        u64 mt = 0;
-        if (!lazy_mask) mt = load_coherent(&M[t]);
-        else if (!(pi.x >= 0 && pi.x < theta)) mt = load_coherent(&M[t]);
-        if (pi.x >= 0 && pi.x < theta) {                    // (I5): wait for the threshold to pass o
-            DB[pi.x] = 1;          // a byte per operator, no atomic; read by a later launch, when theta has passed o
-            lc.max_deferred_key = max(lc.max_deferred_key, pi.x);
-        } else if (pi.x != kNoProducer) {
-            active = true;
-            m = mt;
-            lc.processed++;
-        }
-    }
-    // single-producer tensors (the common case)
-    {
-        u64 nb = 0;
-        int deg = 0;
-        if (active && pi.x >= 0) {
-            const u64 old = atomicOr(&K[pi.x], m);          // (I1)
-            nb = m & ~old;                                  // bits o did not have yet
-            if (old == 0 && m != 0) flags[pi.x] = 1;        // o is kept: a byte the count pass reads instead of K
-            if (nb) deg = pi.z;
-        }
-        expand_edges(g, pi.y, deg, nb, M, s_incl, ws, f);
-    }
-    // tensors with several producers: one pass per producer rank
-    const bool multi = active && pi.x == kMulti;
-    const int max_prod = wave_max(multi ? pi.z : 0);
-    for (int r = 0; r < max_prod; ++r) {
-        u64 nb = 0;
-        int eb = 0, deg = 0;
-        if (multi && r < pi.z) {
-            const int32_t o = g.prod_idx[pi.y + r];
-            const u64 old = atomicOr(&K[o], m);
-            nb = m & ~old;
-            if (old == 0 && m != 0) flags[o] = 1;
-            if (nb) {
-                eb = g.in_rowptr[o];
-                deg = g.in_rowptr[o + 1] - eb;
-            }
-        }
-        expand_edges(g, eb, deg, nb, M, s_incl, ws, f);
-    }
-}
-
-// Operator-side step: 64 operators held one per lane; K[o] |= OR of M over the outputs of o, new bits
-// go to the inputs.  Used for deferred operators (I5) and by the fix-up sweep.  Returns whether this
+// 64 operators held one per lane (valid lanes only): k = OR of M over the outputs of o; the bits K[o] did not
+// have go to the inputs.  atomic_k: OR into K atomically (launches that process an operator in the launch that
+// noted it, and the fix-up sweep); else K is read and written plainly (see the header).  Returns whether this
 // lane's operator gained bits.
-__device__ __forceinline__ bool process_ops(const GraphView &g, bool valid, int32_t o, uint8_t *flags, u64 *M, u64 *K,
-                                            int *s_incl, WaveStage &ws, const Frontier &f)
+__device__ __forceinline__ bool process_ops(const GraphView &g, bool valid, int32_t o, int32_t theta, bool atomic_k,
+                                            const Masks &mk, int *s_incl, WaveStage &ws, const Frontier &f,
+                                            LevelCounters &lc)
 {
-    int ob = 0, n_out = 0, ib = 0, n_in = 0;
+    int4 r = make_int4(0, 0, 0, 0);
+    u64 kold = 0, k = 0;
     if (valid) {
-        ob = g.out_rowptr[o];
-        n_out = g.out_rowptr[o + 1] - ob;
-        ib = g.in_rowptr[o];
-        n_in = g.in_rowptr[o + 1] - ib;
+        r = g.orec[o];
+        kold = load_coherent(&mk.K[o]);
+        const int n_out = r.w >= 0 ? r.w : -r.w;
+        // the masks of the first four outputs are fetched together
+        u64 m0 = 0, m1 = 0, m2 = 0, m3 = 0;
+        if (r.w >= 0) {
+            if (n_out > 0) m0 = load_coherent(&mk.M[r.z]);
+            if (n_out > 1) m1 = load_coherent(&mk.M[r.z + 1]);
+            if (n_out > 2) m2 = load_coherent(&mk.M[r.z + 2]);
+            if (n_out > 3) m3 = load_coherent(&mk.M[r.z + 3]);
+            for (int j = 4; j < n_out; ++j) k |= load_coherent(&mk.M[r.z + j]);
+        } else {
+            const int32_t t0 = n_out > 0 ? g.out_idx[r.z] : 0, t1 = n_out > 1 ? g.out_idx[r.z + 1] : 0;
+            const int32_t t2 = n_out > 2 ? g.out_idx[r.z + 2] : 0, t3 = n_out > 3 ? g.out_idx[r.z + 3] : 0;
+            if (n_out > 0) m0 = load_coherent(&mk.M[t0]);
+            if (n_out > 1) m1 = load_coherent(&mk.M[t1]);
+            if (n_out > 2) m2 = load_coherent(&mk.M[t2]);
+            if (n_out > 3) m3 = load_coherent(&mk.M[t3]);
+            for (int j = 4; j < n_out; ++j) k |= load_coherent(&mk.M[g.out_idx[r.z + j]]);
+        }
+        k |= m0 | m1 | m2 | m3;
+        lc.processed++;
     }
-    u64 k = 0;
-    const int max_out = wave_max(n_out);
-    for (int r = 0; r < max_out; ++r)
-        if (r < n_out) k |= load_coherent(&M[g.out_idx[ob + r]]);
-    u64 nb = 0;
-    if (valid && k) {
-        const u64 old = atomicOr(&K[o], k);                 // (I1)
-        nb = k & ~old;
-        if (old == 0) flags[o] = 1;
+    const u64 nb = k & ~kold;                               // bits o did not have yet
+    if (nb) {
+        if (atomic_k) atomicOr(&mk.K[o], k);                // (I1)
+        else store_coherent(&mk.K[o], kold | k);
+        if (kold == 0) mk.flags[o] = 1;                     // o is kept
     }
-    expand_edges(g, ib, nb ? n_in : 0, nb, M, s_incl, ws, f);
+    expand_edges(g, r.x, nb ? r.y : 0, nb, theta, mk, s_incl, ws, f, lc);
     return nb != 0;
 }
 
@@ -394,11 +434,11 @@ __device__ __forceinline__ int32_t next_theta(int32_t theta, const Schedule &sch
 }
 
 // ------------------------------------------------------------------------------------------------
-// wide levels: one frontier level per launch, the whole chip
+// wide levels: one level per launch, the whole chip
 //
 // No block waits for another and nobody "closes" a level.  A launch leaves behind (a) a record: the
 // state it started from, and whether it ran a level from there; (b) its tallies, spread over 64 words:
-// pushes per queue segment, expansions, largest deferred id.  Every block of the NEXT launch folds the
+// pushes per queue segment, operators processed, largest deferred id.  Every block of the NEXT launch folds the
 // two into the state it starts from -- a few dozen loads and a wave reduction, the same arithmetic in
 // every block, so all blocks agree without talking to each other.  Records alternate between two slots
 // and tallies between three buffers (written by launch e, read by e + 1, zeroed by e + 2), so nothing a
@@ -406,59 +446,89 @@ __device__ __forceinline__ int32_t next_theta(int32_t theta, const Schedule &sch
 // ------------------------------------------------------------------------------------------------
 constexpr int kLevelThreads = 256;
 constexpr int kLevelWaves = kLevelThreads / kWave;
-constexpr int kChaseBelow = 32768;                 // frontiers up to this size get a second hop in the same launch ...
+constexpr int kChaseBelow = 32768;                 // queues up to this size get a second hop in the same launch ...
 constexpr int kChaseAlwaysBelow = 8192;            // ... or, while the deferral threshold is still coming down, up to this size
 constexpr int kThinPerWave = 8;                    // ... with about this many entries dealt to a wave
-constexpr int kChunkOps = 16 * 64;                 // at most 16 deferred-bitmap words are expanded per wave step
+constexpr int kMinChunkLog = 3;                    // a wave scans between 8 ...
+constexpr int kMaxChunkLog = 12;                   // ... and 4096 marker bytes per step (64 per lane)
+constexpr int kListCap = 16 * kWave;               // marked operators listed per wave before they are processed
+#ifndef DGN_THIN_ENTRIES
+#define DGN_THIN_ENTRIES 0                         // 1: a queue that leaves waves idle is dealt thinly over all of them
+#endif
+constexpr int kThinMin = 16;
+#ifndef DGN_CHASE_HOPS
+#define DGN_CHASE_HOPS 1
+#endif
+constexpr int kChaseHops = DGN_CHASE_HOPS;         // hops a wave adds on its own in a launch with a small queue
+#ifndef DGN_CHASE_WITH_RANGE
+#define DGN_CHASE_WITH_RANGE 1                     // 1: a second hop also in launches that open a range
+#endif
 
 struct LevelShared {
     int32_t stage[kLevelWaves][kStageCap];
     int32_t lstage[kLevelWaves][kLogStageCap];
     int incl[kLevelWaves][kWave];
-    int32_t ops[kLevelWaves][kChunkOps];
+    int32_t ops[kLevelWaves][kListCap];
     int pref[kMaxSeg + 1];
-    int derived[2];         // expansions and 1 + largest deferred id of the previous launch
+    int derived[2];         // operators processed and 1 + largest deferred id of the previous launch
 };
 
 // How one level's work is dealt to `grid` blocks.
 struct LevelPlan {
-    int w_lo, w_hi;      // deferred-bitmap words of the range [theta, theta_hi) that opens at this level
-    int cw_log, chunks;  // the words are dealt to the waves in chunks of 1 << cw_log (1..16) words: small
-                         // enough that a dense range is spread over many waves, large enough that a
-                         // sparse one needs few steps per wave
-    int nb_e, nb_s;      // blocks wanted by the frontier entries / by the range chunks
-    bool split;          // entries and chunks go to different blocks when the grid has room for both, so
-                         // the two dependent-access chains of a small level overlap
-    int nwork;           // blocks that have something to do
-    int per_wave;        // 0: every wave takes 64 entries at a time.  Else (small frontier) the entries are dealt
-                         // thinly, per_wave to a wave, so that what a wave pushes fits one more step of its own:
-                         // it then expands those pushes itself, a second hop within the same launch.  (Dealing
-                         // every level thinly, to shorten the rounds of 64 edges a wave goes through, was slower:
-                         // twice the waves flushing, tallying and loading half-empty.)
+    int band_lo, band_hi;  // marker bytes of the operators [band_lo, band_hi) are read: the range [theta, theta_hi) that
+                           // opens at this level, its lower end rounded down to a whole chunk
+    int cs_log, chunks;    // the range is dealt to the waves in chunks of 1 << cs_log operators (8..4096): as small as
+                           // the number of waves allows -- a range far down the graph is dense with marked operators,
+                           // and a wave that finds 64 of them works through several hundred input edges while the
+                           // rest of the chip idles -- and large enough that a wide, sparse range needs one step per wave
+    int nb_e, nb_s;        // blocks wanted by the queue entries / by the range chunks
+    bool split;            // entries and chunks go to different blocks when the grid has room for both, so
+                           // the two dependent-access chains of a small level overlap
+    int nwork;             // blocks that have something to do
+    int per_wave;          // 0: every wave takes 64 entries at a time.  Else the entries are dealt thinly, per_wave to a wave
+    bool chase;            // (small queue, no range to scan) what a wave pushes fits one more step of its own: it then
+                           // processes those pushes itself, a second hop within the same launch
 };
 
 __device__ __forceinline__ LevelPlan plan_level(const LevelSlot &in, int n, bool ranges_left, int grid)
 {
     LevelPlan p;
-    p.w_lo = ranges_left ? in.theta >> 6 : 0;
-    p.w_hi = ranges_left ? (in.theta_hi + 63) >> 6 : 0;
-    p.cw_log = 0;
-    while (p.cw_log < 4 && ((p.w_hi - p.w_lo) >> p.cw_log) > grid * kLevelWaves) ++p.cw_log;
-    const int cw = 1 << p.cw_log;
-    p.chunks = (p.w_hi - p.w_lo + cw - 1) >> p.cw_log;
+    p.band_lo = p.band_hi = p.chunks = 0;
+    p.cs_log = kMinChunkLog;
+    const int waves = grid * kLevelWaves;
+    if (ranges_left) {
+        // waves left over by the queue entries, but at least a quarter of the grid
+        const int avail = max(waves - (n + kWave - 1) / kWave, grid);
+        const int span = in.theta_hi - in.theta;
+        while (p.cs_log < kMaxChunkLog && (span >> p.cs_log) + 1 > avail) ++p.cs_log;
+        p.band_lo = in.theta & ~((1 << p.cs_log) - 1);
+        p.band_hi = in.theta_hi;
+        p.chunks = (p.band_hi - p.band_lo + (1 << p.cs_log) - 1) >> p.cs_log;
+    }
     p.nb_e = (n + kLevelThreads - 1) / kLevelThreads;
     p.nb_s = (p.chunks + kLevelWaves - 1) / kLevelWaves;
     p.per_wave = 0;
-    // (no second hop for larger frontiers while the threshold is still coming down: it takes one step per launch,
-    // so the number of launches is set by its schedule and a second hop would only make each of them longer)
-    if (n > 0 && (n <= kChaseAlwaysBelow || (n <= kChaseBelow && in.theta <= 0)) && p.nb_s < grid) {
-        const int room = grid - p.nb_s;
+    p.chase = false;
+    // (no second hop in a launch that opens a range: what the range's operators push is most of the launch's work,
+    // and it would all be processed by the few waves that happened to scan it)
+    if (n > 0 && (p.chunks == 0 || DGN_CHASE_WITH_RANGE) && p.nb_s < grid &&
+        (n <= kChaseAlwaysBelow || (n <= kChaseBelow && in.theta <= 0))) {
         const int want = (n + kLevelWaves * kThinPerWave - 1) / (kLevelWaves * kThinPerWave);
-        const int nb = min(room, want);
+        const int nb = min(grid - p.nb_s, want);
         const int per = (n + nb * kLevelWaves - 1) / (nb * kLevelWaves);
         if (per <= 2 * kThinPerWave) {
             p.nb_e = nb;
             p.per_wave = per;
+            p.chase = true;
+        }
+    }
+    if (DGN_THIN_ENTRIES && n > 0 && !p.chase && p.nb_s < grid) {
+        const int wave_room = (grid - p.nb_s) * kLevelWaves;
+        int per = (n + wave_room - 1) / wave_room;
+        per = max(per, kThinMin);
+        if (per < kWave) {
+            p.per_wave = per;
+            p.nb_e = (n + per * kLevelWaves - 1) / (per * kLevelWaves);
         }
     }
     p.split = p.nb_e + p.nb_s <= grid;
@@ -466,18 +536,21 @@ __device__ __forceinline__ LevelPlan plan_level(const LevelSlot &in, int n, bool
     return p;
 }
 
-// The work of block `blk` (< p.nwork) in one level: its share of the frontier entries and of the
-// newly opened operator range.  Adds the block's tallies to tally_proc / tally_key.
+// bit j of the result = bit 0 of byte j of x (marker bytes are 0 or 1)
+__device__ __forceinline__ uint32_t gather4(uint32_t x) { return ((x & 0x01010101u) * 0x01020408u) >> 24; }
+
+// The work of block `blk` (< p.nwork) in one level: its share of the queue entries and of the newly opened
+// operator range.  Adds the block's tallies to `tally`.
 __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &in, int n, const LevelPlan &p, int blk,
-                                          const int32_t *qin, const QueueGeom &qg, const Frontier &f, uint8_t *DB,
-                                          uint8_t *flags, u64 *M, u64 *K, LevelShared &sh, SegCounter *tally)
+                                          const int32_t *qin, const QueueGeom &qg, const Frontier &f, const Masks &mk,
+                                          LevelShared &sh, SegCounter *tally)
 {
     const int lane = lane_id(), wave = threadIdx.x >> 6;
     const bool do_entries = !p.split || blk < p.nb_e;
     const bool do_scan = !p.split || blk >= p.nb_e;
     const int e_blocks = p.split ? p.nb_e : p.nwork, e_first = blk;
     const int s_blocks = p.split ? p.nb_s : p.nwork, s_first = p.split ? blk - p.nb_e : blk;
-    const int cw = 1 << p.cw_log;
+    const bool atomic_k = p.chase;                          // the same in every block of the launch
 
     WaveStage ws{&sh.stage[wave][0], 0, 0, f.log ? &sh.lstage[wave][0] : nullptr, 0};
     LevelCounters lc{0, -1};
@@ -485,69 +558,85 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
         if (do_entries) {
             const int i = (e_first * kLevelWaves + wave) * p.per_wave + lane;
             const bool valid = lane < p.per_wave && i < n;
-            const int32_t t = valid ? load_item(qin, qg, sh.pref, i) : 0;
-            process_entries(g, valid, t, in.theta, DB, flags, M, K, &sh.incl[wave][0], ws, f, lc, true);
+            const int32_t o = valid ? load_item(qin, qg, sh.pref, i) : 0;
+            process_ops(g, valid, o, in.theta, atomic_k, mk, &sh.incl[wave][0], ws, f, lc);
         }
     } else {
         for (int base = e_first * kLevelThreads; do_entries && base < n; base += e_blocks * kLevelThreads) {
             const int i = base + threadIdx.x;
             const bool valid = i < n;
-            const int32_t t = valid ? load_item(qin, qg, sh.pref, i) : 0;
-            process_entries(g, valid, t, in.theta, DB, flags, M, K, &sh.incl[wave][0], ws, f, lc, true);
+            const int32_t o = valid ? load_item(qin, qg, sh.pref, i) : 0;
+            process_ops(g, valid, o, in.theta, atomic_k, mk, &sh.incl[wave][0], ws, f, lc);
         }
     }
-    // expand the bitmap words of the newly opened range into dense operator lists, 64 per step
+    // the marker bytes of the newly opened range, a chunk per step: every lane fetches its 1..64 bytes at once and
+    // squeezes them into a bit mask; the marked operators are listed in LDS, sixteen bytes per lane at a time, and
+    // processed 64 per step
+    const int lw_log = max(p.cs_log - 6, 0), lw = 1 << lw_log;              // marker bytes per lane
+    const int lanes_on = 1 << min(p.cs_log, 6);
+    const int64_t limit = ((int64_t)p.band_hi + 63) & ~(int64_t)63;         // the byte map is padded to whole 64s
     for (int c = s_first * kLevelWaves + wave; do_scan && c < p.chunks; c += s_blocks * kLevelWaves) {
-        const int w0 = p.w_lo + (c << p.cw_log);
-        // lane L looks at the cw operators from op0 on (cw = 1..16 marker bytes, aligned to cw)
-        const int64_t op0 = (int64_t)w0 * 64 + (lane << p.cw_log);
-        uint32_t bits16 = 0;
-        if (op0 < (int64_t)p.w_hi * 64) {
-            const uint32_t *src = reinterpret_cast<const uint32_t *>(DB + (op0 & ~(int64_t)3));
-            if (cw >= 4) {
-                for (int k = 0; k < (cw >> 2); ++k)         // bytes are 0 or 1: gather bit 0 of each
-                    bits16 |= (((src[k] & 0x01010101u) * 0x01020408u) >> 24) << (4 * k);
+        const int64_t op0 = (int64_t)p.band_lo + ((int64_t)c << p.cs_log) + ((int64_t)lane << lw_log);
+        u64 bits = 0;
+        if (lane < lanes_on && op0 < limit) {
+            if (lw >= 16) {
+                const uint4 *src = reinterpret_cast<const uint4 *>(mk.DB + op0);
+                for (int k = 0; k < (lw >> 4); ++k) {
+                    const uint4 x = src[k];
+                    const uint32_t b16 = gather4(x.x) | (gather4(x.y) << 4) | (gather4(x.z) << 8) | (gather4(x.w) << 12);
+                    bits |= (u64)b16 << (16 * k);
+                }
+            } else if (lw >= 4) {
+                const uint32_t *src = reinterpret_cast<const uint32_t *>(mk.DB + op0);
+                for (int k = 0; k < (lw >> 2); ++k) bits |= (u64)gather4(src[k]) << (4 * k);
             } else {
-                const uint32_t x = src[0] >> ((int)(op0 & 3) * 8);
-                bits16 = (((x & 0x01010101u) * 0x01020408u) >> 24) & ((1u << cw) - 1u);
+                const uint32_t *src = reinterpret_cast<const uint32_t *>(mk.DB + (op0 & ~(int64_t)3));
+                bits = gather4(src[0] >> ((int)(op0 & 3) * 8)) & ((1u << lw) - 1u);
             }
             // keep only ids in [theta, theta_hi)
             const int64_t lo_cut = in.theta - op0, hi_cut = in.theta_hi - op0;
-            if (lo_cut > 0) bits16 &= lo_cut >= cw ? 0u : ~((1u << lo_cut) - 1u);
-            if (hi_cut < cw) bits16 &= hi_cut <= 0 ? 0u : (1u << hi_cut) - 1u;
+            if (lo_cut > 0) bits &= lo_cut >= 64 ? (u64)0 : ~(((u64)1 << lo_cut) - 1);
+            if (hi_cut < lw) bits &= hi_cut <= 0 ? (u64)0 : ((u64)1 << hi_cut) - 1;
         }
-        const int cnt = __popc(bits16);
-        const int incl = wave_incl_scan(cnt);
-        const int total = __shfl(incl, kWave - 1, kWave);
-        int pos = incl - cnt;
-        const int32_t op_base = (int32_t)op0;
-        while (bits16) {
-            const int b = __builtin_ctz(bits16);
-            bits16 &= bits16 - 1;
-            sh.ops[wave][pos++] = op_base + b;
-        }
-        __builtin_amdgcn_wave_barrier();
-        for (int i0 = 0; i0 < total; i0 += kWave) {
-            const bool valid = i0 + lane < total;
-            const int32_t o = valid ? sh.ops[wave][i0 + lane] : 0;
-            process_ops(g, valid, o, flags, M, K, &sh.incl[wave][0], ws, f);
-            if (valid) lc.processed++;
-        }
-        __builtin_amdgcn_wave_barrier();
-    }
-    // With a small frontier the level is a chain of dependent accesses plus the fixed cost of a launch: the wave
-    // then expands what it has just pushed itself, one more hop within this launch, and only what that hop pushes
-    // goes to memory (any order of expansions reaches the same fixed point; a hop done here is a launch saved
-    // wherever the levels are small).
-    if (p.per_wave > 0) {
-        int gen_end = ws.tail;                              // the entries pushed so far: this launch's second hop
-        while (gen_end - ws.head > 0) {                     // wave-uniform (a flush empties the ring: head = tail)
-            const int take = min(gen_end - ws.head, kWave);
-            const bool valid = lane < take;
-            const int32_t t = valid ? ws.buf[(ws.head + lane) & (kStageCap - 1)] : 0;
-            ws.head += take;
+        for (int part = 0; part < max(lw >> 4, 1); ++part) {
+            uint32_t bits16 = (uint32_t)(bits >> (16 * part)) & 0xffffu;
+            const int cnt = __popc(bits16);
+            const int incl = wave_incl_scan(cnt);
+            const int total = __shfl(incl, kWave - 1, kWave);
+            if (total == 0) continue;                       // wave-uniform
+            int pos = incl - cnt;
+            const int32_t op_base = (int32_t)op0 + 16 * part;
+            while (bits16) {
+                const int b = __builtin_ctz(bits16);
+                bits16 &= bits16 - 1;
+                sh.ops[wave][pos++] = op_base + b;
+            }
             __builtin_amdgcn_wave_barrier();
-            process_entries(g, valid, t, in.theta, DB, flags, M, K, &sh.incl[wave][0], ws, f, lc, true);
+            for (int i0 = 0; i0 < total; i0 += kWave) {
+                const bool valid = i0 + lane < total;
+                const int32_t o = valid ? sh.ops[wave][i0 + lane] : 0;
+                process_ops(g, valid, o, in.theta, atomic_k, mk, &sh.incl[wave][0], ws, f, lc);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+    // With a small queue the level is a chain of dependent accesses plus the fixed cost of a launch: the wave
+    // then processes what it has just pushed itself, one more hop within this launch, and only what that hop pushes
+    // goes to memory (any order reaches the same fixed point; a hop done here is a launch saved wherever the
+    // levels are small).
+    if (p.chase) {
+        for (int hop = 0; hop < kChaseHops; ++hop) {
+            int gen_end = ws.tail;                          // the entries pushed so far: the next hop of this launch
+            if (gen_end - ws.head <= 0) break;              // wave-uniform
+            while (gen_end - ws.head > 0) {                 // wave-uniform (a flush empties the ring: head = tail)
+                const int take = min(gen_end - ws.head, kWave);
+                const bool valid = lane < take;
+                const int32_t o = valid ? ws.buf[(ws.head + lane) & (kStageCap - 1)] : 0;
+                ws.head += take;
+                __builtin_amdgcn_wave_barrier();
+                process_ops(g, valid, o, in.theta, atomic_k, mk, &sh.incl[wave][0], ws, f, lc);
+                if (ws.head > gen_end) gen_end = ws.head;   // the ring was flushed under us: nothing of this hop is left
+            }
         }
     }
     flush_entries(ws, f);
@@ -563,7 +652,7 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
 
 // The state a launch starts from, derived by every block on its own from the record of the previous
 // launch and, if that launch ran a level, from its tallies.  Whole block; fills s_pref (prefix sums of
-// the frontier's segment counts).  prev = tallies buffer of the previous launch.
+// the queue's segment counts).  prev = tallies buffer of the previous launch.
 __device__ __forceinline__ LevelSlot derive_state(const TravState *st, const TravCounters *ctr, int launch_no,
                                                   const QueueGeom &qg, const Schedule &sch, int *s_pref, int *s_derived,
                                                   int *tot_proc_out)
@@ -634,7 +723,7 @@ __device__ __forceinline__ void keep_books(TravState *st, TravCounters *ctr, int
     }
 }
 
-// The frontier is handed to the next launch untouched: its segment counts move into this launch's tallies.
+// The queue is handed to the next launch untouched: its segment counts move into this launch's tallies.
 __device__ __forceinline__ void hand_on_frontier(TravCounters *ctr, int launch_no, const int *s_pref)
 {
     const int lane = lane_id();
@@ -642,10 +731,8 @@ __device__ __forceinline__ void hand_on_frontier(TravCounters *ctr, int launch_n
 }
 
 __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState *st, TravCounters *ctr, int launch_no,
-                                                          int32_t *q0, int32_t *q1, QueueGeom qg, uint8_t *DB,
-                                                          uint8_t *flags, u64 *M, u64 *K, int narrow_cap, Schedule sch,
-                                                          ColourLog log,
-                                                          int4 *trace)
+                                                          int32_t *q0, int32_t *q1, QueueGeom qg, Masks mk,
+                                                          int narrow_cap, Schedule sch, ColourLog log, int4 *trace)
 {
     __shared__ LevelShared sh;
     const int wave = threadIdx.x >> 6;
@@ -673,7 +760,7 @@ __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState 
     const Frontier f{qout + (int64_t)seg * qg.seg_cap, &ctr->cnt[mine][seg].v, qg.seg_cap, &st->error,
                      log.entries ? log.entries + (int64_t)lseg * log.seg_cap : nullptr, &log.cnt[lseg].v, log.seg_cap,
                      nullptr, 0};
-    run_level(g, in, n, p, (int)blockIdx.x, qin, qg, f, DB, flags, M, K, sh, ctr->cnt[mine]);
+    run_level(g, in, n, p, (int)blockIdx.x, qin, qg, f, mk, sh, ctr->cnt[mine]);
 }
 
 hipError_t launch_level(const GraphView &g, TravState *st, TravCounters *ctr, int launch_no, int32_t *q0, int32_t *q1,
@@ -681,23 +768,21 @@ hipError_t launch_level(const GraphView &g, TravState *st, TravCounters *ctr, in
                         const Schedule &sch, const ColourLog &log, int4 *trace, hipStream_t s)
 {
     hipLaunchKernelGGL(k_level, dim3((unsigned)grid_blocks), dim3(kLevelThreads), 0, s, g, st, ctr, launch_no, q0, q1,
-                       qg, DB, flags, M, K, narrow_cap, sch, log, trace);
+                       qg, Masks{M, K, DB, flags}, narrow_cap, sch, log, trace);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------------
-// narrow levels: one workgroup walks level after level while the frontier is small, with workgroup
+// narrow levels: one workgroup walks level after level while the queue is small, with workgroup
 // barriers instead of kernel launches (deep graphs have hundreds of small levels)
 // ------------------------------------------------------------------------------------------------
 constexpr int kNarrowThreads = 1024;
 constexpr int kNarrowWaves = kNarrowThreads / kWave;
-constexpr int kNarrowFront = 1024;      // entries of a frontier that the kernel also keeps in LDS
+constexpr int kNarrowFront = 1024;      // entries of a queue that the kernel also keeps in LDS
 
 __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravState *st, TravCounters *ctr, int launch_no,
-                                                            int32_t *q0, int32_t *q1, QueueGeom qg, uint8_t *DB,
-                                                            uint8_t *flags, u64 *M, u64 *K, int narrow_cap, Schedule sch,
-                                                            ColourLog log,
-                                                            int4 *trace)
+                                                            int32_t *q0, int32_t *q1, QueueGeom qg, Masks mk,
+                                                            int narrow_cap, Schedule sch, ColourLog log, int4 *trace)
 {
     __shared__ int32_t s_stage[kNarrowWaves][kStageCap];
     __shared__ int32_t s_lstage[kNarrowWaves][kLogStageCap];
@@ -705,7 +790,7 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
     __shared__ int s_pref[kMaxSeg + 1];
     __shared__ int s_derived[2];
     __shared__ int s_nout;
-    // The frontier a level builds is also kept here: the next level -- at most kNarrowFront entries, or this
+    // The queue a level builds is also kept here: the next level -- at most kNarrowFront entries, or this
     // kernel does not run it -- takes it from LDS and need not wait for its own queue stores to reach memory.
     __shared__ int32_t s_front[2][kNarrowFront];
 
@@ -732,14 +817,15 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
         for (int base = 0; base < n; base += kNarrowThreads) {
             const int i = base + threadIdx.x;
             const bool valid = i < n;
-            const int32_t t = !valid ? 0 : from_lds ? s_front[cur][i] : load_item(qin, qg, s_pref, i);
-            // threshold 0: a small frontier is latency bound, so nothing is gained by deferring
-            process_entries(g, valid, t, 0, DB, flags, M, K, &s_incl[wave][0], ws, f, lc, false);
+            const int32_t o = !valid ? 0 : from_lds ? s_front[cur][i] : load_item(qin, qg, s_pref, i);
+            // threshold 0: a small queue is latency bound, so nothing is gained by deferring.  What a level notes
+            // is processed by the next one, behind a barrier: plain reads and writes of K will do (see the header)
+            process_ops(g, valid, o, 0, false, mk, &s_incl[wave][0], ws, f, lc);
         }
         flush_entries(ws, f);
-        // without the copy in LDS the block's queue stores must have completed before other waves of this same
-        // block re-read them (with cache-bypassing loads); no other block reads them before the kernel ends
-        if (!use_mirror) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        // the block's stores (K, and without the copy in LDS the queue) must have completed before other waves of this
+        // same block read them; no other block reads them before the kernel ends
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __syncthreads();
         visits += (u64)n;
         if ((u64)n > maxf) maxf = (u64)n;
@@ -747,7 +833,7 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
         n = min(s_nout, qg.seg_cap);
         ++level;
         from_lds = use_mirror;
-        // the next frontier lives in segment 0 only
+        // the next queue lives in segment 0 only
         if (threadIdx.x <= kMaxSeg) s_pref[threadIdx.x] = threadIdx.x == 0 ? 0 : n;
         __syncthreads();          // everyone has read s_nout before it is reset; s_pref is in place
     }
@@ -756,7 +842,7 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
                           log.seg_cap, nullptr, 0};
         flush_log(ws, lf);
     }
-    // This launch leaves no tallies to fold: its record IS the state after it.  The frontier it ends with
+    // This launch leaves no tallies to fold: its record IS the state after it.  The queue it ends with
     // (untouched, or the one it built in segment 0) goes to the next launch through this launch's counters.
     if (threadIdx.x < kWave) {
         keep_books(st, ctr, launch_no, prev_rec, in, false, in.n <= narrow_cap && !ranges_left, tot_proc, trace);
@@ -775,16 +861,16 @@ hipError_t launch_narrow(const GraphView &g, TravState *st, TravCounters *ctr, i
                          const QueueGeom &qg, uint8_t *DB, uint8_t *flags, u64 *M, u64 *K, int narrow_cap, const Schedule &sch,
                          const ColourLog &log, int4 *trace, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_narrow, dim3(1), dim3(kNarrowThreads), 0, s, g, st, ctr, launch_no, q0, q1, qg, DB, flags, M, K,
-                       narrow_cap, sch, log, trace);
+    hipLaunchKernelGGL(k_narrow, dim3(1), dim3(kNarrowThreads), 0, s, g, st, ctr, launch_no, q0, q1, qg,
+                       Masks{M, K, DB, flags}, narrow_cap, sch, log, trace);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------------
-// fix-up sweep (only after a frontier queue overflowed): every operator re-derives K from its outputs
+// fix-up sweep (only after a queue overflowed): every operator re-derives K from its outputs
 // and pushes what is new to its inputs; repeated by the host until a sweep changes nothing
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kLevelThreads) void k_fix_sweep(GraphView g, u64 *M, u64 *K, uint8_t *flags, int32_t *changed)
+__global__ __launch_bounds__(kLevelThreads) void k_fix_sweep(GraphView g, Masks mk, int32_t *changed)
 {
     __shared__ int32_t s_stage[kLevelWaves][kStageCap];
     __shared__ int s_incl[kLevelWaves][kWave];
@@ -794,13 +880,15 @@ __global__ __launch_bounds__(kLevelThreads) void k_fix_sweep(GraphView g, u64 *M
     __syncthreads();
     WaveStage ws{&s_stage[wave][0], 0, 0, nullptr, 0};
     const Frontier f{nullptr, &s_sink, 0, &s_err, nullptr, nullptr, 0, nullptr, 0};   // capacity 0: pushes are counted and dropped
+    LevelCounters lc{0, -1};
     bool any = false;
-    // descending ids: most of a sweep then sees its consumers' results (ids are a topological order)
+    // descending ids: most of a sweep then sees its consumers' results (ids are a topological order).  Operators
+    // are processed while their consumers still push, in no order between blocks: K by atomic ORs, threshold 0.
     const int64_t tiles = ((int64_t)g.num_ops + kLevelThreads - 1) / kLevelThreads;
     for (int64_t tile = tiles - 1 - blockIdx.x; tile >= 0; tile -= gridDim.x) {
         const int64_t o = tile * kLevelThreads + threadIdx.x;
         const bool valid = o < g.num_ops;
-        any |= process_ops(g, valid, valid ? (int32_t)o : 0, flags, M, K, &s_incl[wave][0], ws, f);
+        any |= process_ops(g, valid, valid ? (int32_t)o : 0, 0, true, mk, &s_incl[wave][0], ws, f, lc);
         ws.head = ws.tail;
     }
     if (ballot64(any) != 0 && lane_id() == 0) atomicOr(changed, 1);
@@ -809,7 +897,7 @@ __global__ __launch_bounds__(kLevelThreads) void k_fix_sweep(GraphView g, u64 *M
 hipError_t launch_fix_sweep(const GraphView &g, u64 *M, u64 *K, uint8_t *flags, int32_t *changed, int grid_blocks, hipStream_t s)
 {
     if (g.num_ops == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_fix_sweep, dim3((unsigned)grid_blocks), dim3(kLevelThreads), 0, s, g, M, K, flags, changed);
+    hipLaunchKernelGGL(k_fix_sweep, dim3((unsigned)grid_blocks), dim3(kLevelThreads), 0, s, g, Masks{M, K, nullptr, flags}, changed);
     return hipGetLastError();
 }
 

@@ -669,9 +669,8 @@ def test_borrowed_csr_with_bad_row_pointers_is_reported(dgn, oracle):
 
     def build(**changed):
         a = dict(good, **changed)
-        desc = dgn.make_csr_desc(g.num_ops, g.num_tensors, c(a["in_rowptr"]), c(a["in_idx"]), c(a["out_rowptr"]),
-                                 c(a["out_idx"]))
-        desc._keep = a
+        dev = [c(a[n]) for n in ("in_rowptr", "in_idx", "out_rowptr", "out_idx")]     # alive until the build returns
+        desc = dgn.make_csr_desc(g.num_ops, g.num_tensors, *dev)
         rc, gb, sb = dgn.dgn_graph_from_csr_workspace(desc)
         assert rc == 0
         mem = torch.empty(gb, dtype=torch.uint8, device="cuda")
