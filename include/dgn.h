@@ -257,6 +257,23 @@ int dgn_keep_compact(const dgn_graph *g, const uint64_t *tensor_mask_in, uint64_
                      uint8_t *op_flag, int32_t *kept_ops, uint64_t *kept_masks, int64_t *kept_count,
                      int64_t *per_query_count, void *scratch, size_t scratch_bytes, dgn_stream stream);
 
+/* For callers that cannot allocate device memory or size a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid allocation): dgn_keep_compact with its scratch in a fixed array that is
+ * part of the library's code object instead of a caller-provided buffer.  Same arguments otherwise, same outputs,
+ * asynchronous on `stream`; the call allocates nothing, frees nothing and reads nothing back (the first call on
+ * a device looks up the array's device address, which loads the code object if nothing has yet).
+ *   Limits: num_ops <= 2^26 (DGN_ERR_TOO_LARGE beyond); the array takes about 8.4 MB of every device the
+ *   library runs kernels on, until the process ends.  dgn_keep_compact_static_limits reports both numbers
+ *   (either pointer may be NULL).
+ *   The device that `stream` belongs to must be the current device.  Every call on a device shares that
+ *   device's array: two calls that overlap on one device (different streams, or host threads) race on it
+ *   and give unspecified outputs; calls on one stream, one after the other, are fine.  The array keeps
+ *   the last call's contents; the call clears what it needs at zero itself. */
+int dgn_keep_compact_static_limits(int64_t *max_ops, size_t *static_bytes);
+int dgn_keep_compact_static(const dgn_graph *g, const uint64_t *tensor_mask_in, uint64_t *op_mask,
+                            uint8_t *op_flag, int32_t *kept_ops, uint64_t *kept_masks, int64_t *kept_count,
+                            int64_t *per_query_count, dgn_stream stream);
+
 /* ---- Backward Prune ---------------------------------------------------------------------- */
 
 /* Scratch bytes dgn_backward_prune needs for this graph. */

@@ -30,7 +30,7 @@ DGN_ERR_BAD_CSR = -9
 EXPORTS = [
     "dgn_graph_build_workspace", "dgn_graph_build", "dgn_graph_from_csr_workspace", "dgn_graph_from_csr",
     "dgn_graph_get_csr", "dgn_graph_get_sizes", "dgn_graph_destroy", "dgn_prune_workspace", "dgn_prune",
-    "dgn_prune_words", "dgn_keep_compact", "dgn_backward_prune_workspace", "dgn_backward_prune", "dgn_inplace_workspace",
+    "dgn_prune_words", "dgn_keep_compact", "dgn_keep_compact_static_limits", "dgn_keep_compact_static", "dgn_backward_prune_workspace", "dgn_backward_prune", "dgn_inplace_workspace",
     "dgn_inplace", "dgn_inplace_kept", "dgn_ignore_mask", "dgn_per_set_lists_workspace", "dgn_per_set_lists",
     "dgn_target_digest_workspace", "dgn_target_digest", "dgn_calibrate", "dgn_strerror",
     "dgn_version",
@@ -108,6 +108,8 @@ def _load() -> ctypes.CDLL:
     lib.dgn_prune_words.argtypes = [c_void_p, c_int64, c_int64] + [c_void_p] * 9 + [c_void_p, c_size_t,
                                     POINTER(dgn_options), POINTER(dgn_stats), c_void_p]
     lib.dgn_keep_compact.argtypes = [c_void_p] + [c_void_p] * 7 + [c_void_p, c_size_t, c_void_p]
+    lib.dgn_keep_compact_static.argtypes = [c_void_p] + [c_void_p] * 7 + [c_void_p]
+    lib.dgn_keep_compact_static_limits.argtypes = [POINTER(c_int64), POINTER(c_size_t)]
     lib.dgn_backward_prune_workspace.argtypes = [c_void_p, POINTER(c_size_t)]
     lib.dgn_backward_prune.argtypes = [c_void_p, c_int32] + [c_void_p] * 9 + [c_void_p, c_size_t,
                                        POINTER(dgn_options), POINTER(dgn_stats), c_void_p]
@@ -270,6 +272,19 @@ def dgn_keep_compact(handle, tensor_mask_in, op_mask, op_flag, kept_ops, kept_ma
     return _lib.dgn_keep_compact(handle, _dp(tensor_mask_in), _dp(op_mask), _dp(op_flag), _dp(kept_ops),
                                  _dp(kept_masks), _dp(kept_count), _dp(per_query_count), _dp(scratch),
                                  scratch_bytes, _stream(stream))
+
+
+def dgn_keep_compact_static_limits():
+    """Returns (return code, largest num_ops, bytes of the library's static device array)."""
+    m, b = c_int64(0), c_size_t(0)
+    rc = _lib.dgn_keep_compact_static_limits(ctypes.byref(m), ctypes.byref(b))
+    return rc, m.value, b.value
+
+
+def dgn_keep_compact_static(handle, tensor_mask_in, op_mask, op_flag, kept_ops, kept_masks, kept_count,
+                            per_query_count, stream=None) -> int:
+    return _lib.dgn_keep_compact_static(handle, _dp(tensor_mask_in), _dp(op_mask), _dp(op_flag), _dp(kept_ops),
+                                        _dp(kept_masks), _dp(kept_count), _dp(per_query_count), _stream(stream))
 
 
 def dgn_backward_prune_workspace(handle):

@@ -905,6 +905,82 @@ int dgn_keep_compact(const dgn_graph *g, const uint64_t *tensor_mask_in, uint64_
                              scratch, scratch_bytes, stream);
 }
 
+// ---- removal rule + compaction for callers that cannot allocate ---------------------------------
+// The passes' scratch (kept-operator bitmap, tile counts, replicated per-set counters) lives in an array
+// of the code object itself, one copy per device; the host works with its device address, fetched once
+// per device, never with the array's name.
+constexpr int64_t kStaticMaxOps = (int64_t)1 << 26;
+constexpr size_t kStaticBitmapBytes = (size_t)(kStaticMaxOps / 8);
+constexpr size_t kStaticCountsBytes = ((size_t)(kStaticMaxOps / kCompactTile + 1) * sizeof(int32_t) + 255) & ~(size_t)255;
+constexpr size_t kStaticPqBytes = sizeof(int64_t) * 64 * 64 * kPqStride;
+constexpr size_t kStaticScratchBytes = kStaticBitmapBytes + kStaticCountsBytes + kStaticPqBytes;
+static __device__ __align__(256) unsigned char static_scratch[kStaticScratchBytes];
+constexpr int kStaticMaxDevices = 64;
+static std::atomic<void *> g_static_scratch_ptr[kStaticMaxDevices];
+
+// Device address of the current device's copy of the array.
+static int static_scratch_address(char **out)
+{
+    int dev = -1;
+    DGN_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kStaticMaxDevices) return DGN_ERR_INVALID_ARG;
+    void *p = g_static_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        DGN_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(static_scratch)));
+        if (!p) return DGN_ERR_INVALID_ARG;
+        g_static_scratch_ptr[dev].store(p, std::memory_order_release);   // (two threads racing here fetch the same address)
+    }
+    *out = static_cast<char *>(p);
+    return DGN_OK;
+}
+
+int dgn_keep_compact_static_limits(int64_t *max_ops, size_t *static_bytes)
+{
+    if (max_ops) *max_ops = kStaticMaxOps;
+    if (static_bytes) *static_bytes = kStaticScratchBytes;
+    return DGN_OK;
+}
+
+int dgn_keep_compact_static(const dgn_graph *g, const uint64_t *tensor_mask_in, uint64_t *op_mask, uint8_t *op_flag,
+                            int32_t *kept_ops, uint64_t *kept_masks, int64_t *kept_count, int64_t *per_query_count,
+                            dgn_stream stream)
+{
+    if (!g || !kept_count) return DGN_ERR_NULL_PTR;
+    if (g->P > kStaticMaxOps) return DGN_ERR_TOO_LARGE;
+    if ((g->T > 0 && !tensor_mask_in) || (g->P > 0 && (!op_mask || !kept_ops))) return DGN_ERR_NULL_PTR;
+    if (((uintptr_t)tensor_mask_in | (uintptr_t)op_mask | (uintptr_t)kept_masks | (uintptr_t)kept_count |
+         (uintptr_t)per_query_count) & 7)
+        return DGN_ERR_INVALID_ARG;
+    char *base = nullptr;
+    const int rc = static_scratch_address(&base);
+    if (rc != DGN_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    CompactArgs ca{};
+    ca.g = g->v;
+    ca.M = reinterpret_cast<const u64 *>(tensor_mask_in);
+    ca.K = reinterpret_cast<u64 *>(op_mask);
+    ca.op_flag = op_flag;
+    ca.kept_ops = kept_ops;
+    ca.kept_masks = reinterpret_cast<u64 *>(kept_masks);
+    ca.kept_count = kept_count;
+    ca.per_query_count = per_query_count;
+    ca.opbits = reinterpret_cast<u64 *>(base);
+    ca.block_counts = reinterpret_cast<int32_t *>(base + kStaticBitmapBytes);
+    // replicated per-set counters exactly as dgn_keep_compact lays them out: only with few graphs
+    ca.pq_replicas = 1;
+    while (ca.pq_replicas * 2 * (int64_t)g->G <= 64) ca.pq_replicas *= 2;
+    const size_t pq_part_bytes = ca.pq_replicas > 1 ? sizeof(int64_t) * 64 * (size_t)g->G * ca.pq_replicas * kPqStride : 0;
+    ca.pq_part = ca.pq_replicas > 1 ? reinterpret_cast<int64_t *>(base + kStaticBitmapBytes + kStaticCountsBytes) : nullptr;
+    ca.from_tensor_mask = true;
+    // the array keeps what the last call left: the counters must start at zero (a fill kernel, not a memset,
+    // so that the call may be captured into a graph)
+    const size_t pq_bytes = per_query_count ? sizeof(int64_t) * 64 * (size_t)(g->G > 1 ? g->G : 1) : 0;
+    FillRegion pq[2] = {{per_query_count, pq_bytes}, {ca.pq_part, per_query_count ? pq_part_bytes : 0}};
+    DGN_HIP(launch_clear(pq, 2, s));
+    DGN_HIP(launch_keep_compact(ca, s));
+    return DGN_OK;
+}
+
 int dgn_prune_words(const dgn_graph *g, int64_t num_sets, int64_t num_targets, const int32_t *tgt_rowptr,
                     const int32_t *tgt_idx, uint64_t *tensor_mask, uint64_t *op_mask, uint8_t *op_flag, int32_t *kept_ops,
                     uint64_t *kept_masks, int64_t *kept_count, int64_t *per_query_count, void *scratch,
