@@ -1,9 +1,9 @@
 #!/usr/bin/env python3
 """Benchmark: 64-set batched Forward Prune on the 50M-operator power-law DAG, one MI355X.
 
-One "step" = one dgn_prune call = clear + seed + frontier traversal + removal rule + ordered
-compaction over the whole graph, with the graph's adjacency already resident in HBM.  The CSR build
-is timed separately (it is amortised over the prunes of one recorded graph).  Prints ONE JSON line.
+One "step" = one dgn_prune call = clear + seed + traversal + removal rule + ordered compaction over the
+whole graph, with the graph's adjacency already resident in HBM.  The CSR build is timed separately (it is
+amortised over the prunes of one recorded graph), for operator-major and for shuffled COO.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W]
 """
@@ -17,15 +17,15 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, vendor figure
+COUNTERS = os.path.join("profiles", "prune_config3_hbm_counters.txt")
 
 
 def measured_traffic(kernel):
     """HBM bytes per launch from the committed rocprofv3 counter summary, or None when the kernels have
     changed since the counters were taken (or the workload is not the one they were taken on)."""
     import hashlib
-    path = os.path.join(ROOT, "profiles", "prune_config3_hbm_counters.txt")
     try:
-        vals = dict(line.split(": ", 1) for line in open(path).read().splitlines()
+        vals = dict(line.split(": ", 1) for line in open(os.path.join(ROOT, COUNTERS)).read().splitlines()
                     if ": " in line and not line.startswith("#"))
         h = hashlib.sha256()
         for f in ("traverse.hip", "keep_compact.hip", "primitives.hip"):
@@ -39,6 +39,117 @@ def measured_traffic(kernel):
 
 def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def timed_build(d, torch, np, desc, graph_mem, gb, scratch, sb, keep_last=True):
+    """Median of the last two of three builds; returns (ms, handle of the last build or None)."""
+    ms, handle = [], None
+    for _ in range(3):
+        if handle:
+            d.dgn_graph_destroy(handle)
+        torch.cuda.synchronize()
+        tb = time.perf_counter()
+        rc, handle = d.dgn_graph_build(desc, graph_mem, gb, scratch, sb)
+        torch.cuda.synchronize()
+        ms.append((time.perf_counter() - tb) * 1e3)
+        assert rc == 0, d.dgn_strerror(rc)
+    if not keep_last:
+        d.dgn_graph_destroy(handle)
+        handle = None
+    return float(np.median(ms[1:])), handle
+
+
+def shuffled_build_ms(d, torch, np, gg, g, in_op, in_t, out_op, out_t, gb, sb, scratch):
+    """The same edges in a seeded random COO order (the keys of graphgen's permutation, sorted on the device: input
+    preparation, untimed): every sort of the builder runs."""
+    def perm(n, seed):
+        keys = (gg.permutation_keys(n, seed) ^ np.uint64(1 << 63)).view(np.int64)      # order-preserving uint64 -> int64
+        return torch.argsort(torch.from_numpy(keys).cuda(), stable=True)
+    pi, po = perm(g.nnz_in, 12345), perm(g.nnz_out, 12346)
+    s_in_op, s_in_t, s_out_op, s_out_t = in_op[pi], in_t[pi], out_op[po], out_t[po]
+    del pi, po
+    sdesc = d.make_coo_desc(g.num_ops, g.num_tensors, s_in_op, s_in_t, s_out_op, s_out_t, g.num_graphs,
+                            g.graph_op_offsets, g.graph_tensor_offsets)
+    smem = torch.empty(gb, dtype=torch.uint8, device=in_op.device)
+    ms, _ = timed_build(d, torch, np, sdesc, smem, gb, scratch, sb, keep_last=False)
+    return ms
+
+
+def other_config(d, torch, np, gg, orc, k, steps, warmup, with_oracle):
+    """One of the workloads the metric is not quoted on: build, K timed prunes, and the result against the oracle
+    (whole workload for configs 0-2; the packed batch through the fixed-point certificate over all of M and K plus
+    Algorithm 1 on three of its graphs)."""
+    t0 = time.time()
+    g, tg = gg.config(k, 1.0)
+    E = g.nnz_in + g.nnz_out
+    dev = torch.device("cuda:0")
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
+    in_op, in_t, out_op, out_t = up(g.in_op), up(g.in_tensor), up(g.out_op), up(g.out_tensor)
+    desc = d.make_coo_desc(g.num_ops, g.num_tensors, in_op, in_t, out_op, out_t, g.num_graphs,
+                           g.graph_op_offsets, g.graph_tensor_offsets)
+    rc, gb, sb = d.dgn_graph_build_workspace(desc)
+    assert rc == 0, d.dgn_strerror(rc)
+    graph_mem = torch.empty(gb, dtype=torch.uint8, device=dev)
+    scratch = torch.empty(sb, dtype=torch.uint8, device=dev)
+    build_ms, handle = timed_build(d, torch, np, desc, graph_mem, gb, scratch, sb)
+    del scratch, in_op, in_t, out_op, out_t
+    rc, sizes = d.dgn_graph_get_sizes(handle)
+    dg = d.DeviceGraph(handle, graph_mem, (), sizes)
+    buf = d.PruneBuffers(dg, tg.num_sets)
+    rowptr, idx = up(tg.tgt_rowptr), up(tg.tgt_idx)
+    st = d.dgn_stats()
+    for _ in range(warmup):
+        rc = buf.prune(rowptr, idx, stats=st)
+        assert rc == 0, d.dgn_strerror(rc)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(steps):
+        rc = buf.prune(rowptr, idx, stats=st)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t1) / steps * 1e3
+    assert rc == 0, d.dgn_strerror(rc)
+    out = buf.to_host()
+    res = {"workload": f"configs[{k}] {g.name}", "num_ops": g.num_ops, "num_sets": tg.num_sets, "num_graphs": g.num_graphs,
+           "ms_per_step": round(ms, 4), "gteps": round(E / (ms * 1e-3) / 1e9, 3), "build_ms": round(build_ms, 3),
+           "levels": int(st.levels), "operator_visits": int(st.tensor_visits), "launches": int(st.launches),
+           "kept_ops": int(out["kept_count"][0]), "output_buffers": "recycled" if st.recycled else "cleared in full",
+           "bit_exact_vs_oracle": None, "oracle": None}
+    del buf, dg, graph_mem
+    torch.cuda.empty_cache()
+    if with_oracle:
+        tb = time.time()
+        if g.num_graphs == 1:
+            adj = orc.build_adjacency(g.num_ops, g.num_tensors, g.in_op, g.in_tensor, g.out_op, g.out_tensor)
+            t2 = time.perf_counter()
+            ref = orc.forward_prune(adj, tg.num_sets, tg.tgt_rowptr, tg.tgt_idx, g.num_graphs, g.graph_op_offsets)
+            res["oracle"] = {"seconds": round(time.perf_counter() - t2, 3), "sample": "whole workload, one core"}
+            same = all(np.array_equal(out[n], getattr(ref, n)) for n in
+                       ("tensor_mask", "op_mask", "op_flag", "kept_ops", "kept_masks", "kept_count", "per_query_count"))
+        else:
+            adj = orc.build_adjacency(g.num_ops, g.num_tensors, g.in_op, g.in_tensor, g.out_op, g.out_tensor)
+            S = orc.seed_masks(g.num_tensors, tg.num_sets, tg.tgt_rowptr, tg.tgt_idx)
+            same = orc.certificate(adj, S, out["tensor_mask"], out["op_mask"]) == 0
+            same = same and np.array_equal(out["kept_ops"], np.nonzero(out["op_mask"])[0].astype(np.int32))
+            del adj, S
+            t2 = time.perf_counter()
+            for gi in (0, g.num_graphs // 2, g.num_graphs - 1):
+                one = gg.layered(20000, gg.BASE_SEED + 4000 + gi)
+                t1g = gg.targets_tail(one, gg.BASE_SEED + 4000 + gi, tg.num_sets, 4, 4, 0.10)
+                a1 = orc.build_adjacency(one.num_ops, one.num_tensors, one.in_op, one.in_tensor, one.out_op, one.out_tensor)
+                r1 = orc.forward_prune(a1, t1g.num_sets, t1g.tgt_rowptr, t1g.tgt_idx)
+                ta, tb_ = g.graph_tensor_offsets[gi], g.graph_tensor_offsets[gi + 1]
+                oa, ob = g.graph_op_offsets[gi], g.graph_op_offsets[gi + 1]
+                same = same and np.array_equal(out["tensor_mask"][ta:tb_], r1.tensor_mask)
+                same = same and np.array_equal(out["op_mask"][oa:ob], r1.op_mask)
+                same = same and np.array_equal(out["per_query_count"][gi * 64:(gi + 1) * 64], r1.per_query_count)
+            res["oracle"] = {"seconds": round(time.perf_counter() - t2, 3),
+                             "sample": "Algorithm 1 on 3 of the graphs, one core; all of M and K through the fixed-point certificate"}
+        res["bit_exact_vs_oracle"] = bool(same)
+        assert same, f"config {k}: GPU result differs from the oracle"
+        log(f"config {k}: oracle check {time.time() - tb:.1f}s, bit-exact: {same}")
+    log(f"config {k} ({g.name}): {ms:.3f} ms/step, {res['gteps']} GTEPS, build {build_ms:.2f} ms, levels={res['levels']} "
+        f"visits={res['operator_visits']} kept={res['kept_ops']} ({time.time() - t0:.0f}s in all)")
+    return res
 
 
 def main():
@@ -57,10 +168,11 @@ def main():
     ap.add_argument("--generic", action="store_true", help="force the one-launch-per-level traversal")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known size, to scale profiler byte counters)")
-    ap.add_argument("--shuffled-build", action="store_true",
-                    help="also time the CSR build on the same edges in shuffled COO order (every sort runs)")
+    ap.add_argument("--no-shuffled-build", action="store_true",
+                    help="skip the CSR build on the same edges in shuffled COO order (every sort runs)")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip the four workloads the metric is not quoted on")
     ap.add_argument("--prune-only", action="store_true",
-                    help="skip the separately timed in-place, read-out and backward-prune legs (for profiling runs)")
+                    help="only the timed prunes: no other legs, configs, shuffled build or machine rates (for profiling runs)")
     ap.add_argument("--no-recycle", action="store_true",
                     help="clear all of M and K in every step instead of only what the previous step set")
     ap.add_argument("--trace-levels", action="store_true", help="print the per-level trace of the last step")
@@ -97,43 +209,17 @@ def main():
     assert rc == 0, d.dgn_strerror(rc)
     graph_mem = torch.empty(gb, dtype=torch.uint8, device=dev)
     scratch = torch.empty(sb, dtype=torch.uint8, device=dev)
-    build_ms = []
-    handle = None
-    for _ in range(3):
-        if handle:
-            d.dgn_graph_destroy(handle)
-        torch.cuda.synchronize()
-        tb = time.perf_counter()
-        rc, handle = d.dgn_graph_build(desc, graph_mem, gb, scratch, sb)
-        torch.cuda.synchronize()
-        build_ms.append((time.perf_counter() - tb) * 1e3)
-        assert rc == 0, d.dgn_strerror(rc)
-    build_ms = float(np.median(build_ms[1:]))
+    build_ms, handle = timed_build(d, torch, np, desc, graph_mem, gb, scratch, sb)
     log(f"CSR build: {build_ms:.2f} ms ({E / build_ms / 1e6:.1f} GTEPS)")
     build_shuffled_ms = None
-    if args.shuffled_build:
-        gs = gg.shuffle_coo(g, 12345)
-        s_in_op, s_in_t, s_out_op, s_out_t = up(gs.in_op), up(gs.in_tensor), up(gs.out_op), up(gs.out_tensor)
-        del gs
-        sdesc = d.make_coo_desc(g.num_ops, g.num_tensors, s_in_op, s_in_t, s_out_op, s_out_t, g.num_graphs,
-                                g.graph_op_offsets, g.graph_tensor_offsets)
-        smem = torch.empty(gb, dtype=torch.uint8, device=dev)
-        times = []
-        for _ in range(3):
-            torch.cuda.synchronize()
-            tb = time.perf_counter()
-            rc, sh = d.dgn_graph_build(sdesc, smem, gb, scratch, sb)
-            torch.cuda.synchronize()
-            times.append((time.perf_counter() - tb) * 1e3)
-            assert rc == 0, d.dgn_strerror(rc)
-            d.dgn_graph_destroy(sh)
-        build_shuffled_ms = float(np.median(times[1:]))
+    if not (args.no_shuffled_build or args.prune_only):
+        build_shuffled_ms = shuffled_build_ms(d, torch, np, gg, g, in_op, in_t, out_op, out_t, gb, sb, scratch)
         log(f"CSR build, shuffled COO: {build_shuffled_ms:.2f} ms ({E / build_shuffled_ms / 1e6:.1f} GTEPS)")
-        del smem, s_in_op, s_in_t, s_out_op, s_out_t
     del scratch
     rc, sizes = d.dgn_graph_get_sizes(handle)
     dg = d.DeviceGraph(handle, graph_mem, (), sizes)
     del in_op, in_t, out_op, out_t
+    torch.cuda.empty_cache()
 
     # ---- prune --------------------------------------------------------------------------------
     buf = d.PruneBuffers(dg, tg.num_sets, recycle=not args.no_recycle)
@@ -163,6 +249,8 @@ def main():
     gteps = E / (ms_per_step * 1e-3) / 1e9
     recycled = bool(st.recycled)
     level_launches = int(st.level_launches)
+    atomics_per_step = int(st.atomic_updates)
+    levels_total, launches_total = int(st.levels), int(st.launches)
     opts.profile = 1
     phases_all = np.zeros((5, 8))
     # these extra steps also take the per-level trace (device clock at the start of every launch): the time from one
@@ -180,6 +268,7 @@ def main():
             wide = trace[:nl, 2] != -1
             dt = ((trace[1:nl, 3].astype(np.int64) - trace[:nl - 1, 3].astype(np.int64)) & 0xFFFFFFFF) / 100.0
             wide_us += dt[wide[1:] & wide[:-1]].tolist()
+    narrow_levels = int((trace[:min(int(st.levels), trace.shape[0]), 2] == -1).sum())
     if not traced:
         st.level_trace, st.level_trace_cap = None, 0
     level_us_device_clock = float(np.mean(wide_us)) if wide_us else None
@@ -209,6 +298,8 @@ def main():
         full_clear = {"ms_per_step": round(ms2, 4), "gteps": round(E / (ms2 * 1e-3) / 1e9, 2)}
         log(f"prune with a full clear per step: {ms2:.3f} ms/step, {full_clear['gteps']:.1f} GTEPS")
         del buf2
+    elif not recycled:
+        full_clear = {"ms_per_step": round(ms_per_step, 4), "gteps": round(gteps, 2)}
     # recycled buffers with target sets that change from step to step (a second draw of the same recipe, taken in
     # turns with the workload's own): no step finds anything of its own result in place, only words to zero
     other_targets = None
@@ -234,7 +325,7 @@ def main():
         rc = buf.prune(rowptr, idx, options=opts, stats=st)      # st and the buffers describe the timed workload again
         assert rc == 0
     # the same steps once more, each one timed on its own (a synchronisation after every step): median and minimum
-    per_step = copy_gbs = None
+    one_by_one = copy_gbs = rates = None
     if not args.prune_only:
         one = []
         for _ in range(max(args.steps, 20)):
@@ -244,7 +335,7 @@ def main():
             torch.cuda.synchronize()
             one.append((time.perf_counter() - t2) * 1e3)
             assert rc == 0, d.dgn_strerror(rc)
-        per_step = {"median": round(float(np.median(one)), 4), "min": round(float(np.min(one)), 4), "steps": len(one)}
+        one_by_one = {"median": round(float(np.median(one)), 4), "min": round(float(np.min(one)), 4), "steps": len(one)}
         # what a plain device-to-device copy reaches on this GPU: the practical ceiling beside the published peak
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -257,8 +348,15 @@ def main():
         torch.cuda.synchronize()
         copy_gbs = round(5 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
         del src, dst
-        log(f"steps timed one by one: median {per_step['median']:.3f} ms, min {per_step['min']:.3f} ms; "
+        log(f"steps timed one by one: median {one_by_one['median']:.3f} ms, min {one_by_one['min']:.3f} ms; "
             f"1 GiB device copy: {copy_gbs} GB/s (read + write)")
+        # the rates that bound the traversal, measured on this GPU over a buffer as large as the mask array (untimed leg)
+        cal = torch.empty(max(8 * g.num_tensors, 1 << 24), dtype=torch.uint8, device=dev)
+        rc, r = d.dgn_calibrate(cal, cal.numel())
+        assert rc == 0, d.dgn_strerror(rc)
+        rates = r.as_dict()
+        del cal
+        log("machine rates: " + ", ".join(f"{k}={v}" for k, v in rates.items()))
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -269,7 +367,7 @@ def main():
     if args.trace_levels:
         for lv in range(min(int(st.levels), trace.shape[0])):
             dt = ((int(trace[lv, 3]) - int(trace[lv - 1, 3])) & 0xFFFFFFFF) / 100.0 if lv else 0.0
-            log(f"level {lv}: frontier={trace[lv, 0]} expanded={trace[lv, 1]} theta={trace[lv, 2]} us_since_prev={dt:.1f}")
+            log(f"level {lv}: queue={trace[lv, 0]} processed={trace[lv, 1]} theta={trace[lv, 2]} us_since_prev={dt:.1f}")
     out = buf.to_host()
     P, T = g.num_ops, g.num_tensors
 
@@ -367,10 +465,10 @@ def main():
             inc_out = buf.to_host()
             same = all(np.array_equal(inc_out[k], out[k]) for k in out)
             incremental = {"ms": round(float(np.median(inc_ms[1:])), 4), "added_sets": 1,
-                           "tensor_visits": int(inc_st.tensor_visits), "levels": int(inc_st.levels),
+                           "operator_visits": int(inc_st.tensor_visits), "levels": int(inc_st.levels),
                            "equals_one_shot_result": bool(same)}
             log(f"incremental prune (set {last} added to the other {last}): {incremental['ms']:.3f} ms, "
-                f"{incremental['tensor_visits']} visits in {incremental['levels']} levels; equals the one-shot result: {same}")
+                f"{incremental['operator_visits']} visits in {incremental['levels']} levels; equals the one-shot result: {same}")
             assert same, "incremental prune differs from the one-shot prune"
 
         # ---- backward prune (Algorithm 2) on the same graph, 64 pairs, timed on its own ---------------
@@ -416,13 +514,15 @@ def main():
     E_query = int(((fan_in[out["kept_ops"][:P_k]] + n_out[out["kept_ops"][:P_k]]) * sets_of).sum())
 
     # ---- algorithmic bytes per kernel launch (int32 ids, uint64 masks) ---------------------------
-    levels = max(1, int(st.levels))
+    wide = max(1, level_launches)
+    traversal_bytes = 4 * T_c + 8 * P_k + 4 * E_k + 16 * E_k + 16 * P_k
     alg = {
         # all of M and K, or (recycled buffers) the log and the kept list read, their M, K and marker words zeroed
         # (a packed batch swept per graph stores K of every operator: only M is cleared)
-        "k_clear": (12 * T_c + 13 * P_k) if recycled else (8 * T) if int(st.levels) == 0 and g.num_graphs >= 64
+        "k_clear": (12 * T_c + 13 * P_k) if recycled else (8 * T) if levels_total == 0 and g.num_graphs >= 64
                    else (8 * T + 8 * P),
-        "k_level": (4 * T_c + 8 * P_k + 4 * E_k + 16 * E_k + 16 * P_k) / levels,
+        # the traversal's bytes per wide launch (the launches the events and the profiler time)
+        "k_level": traversal_bytes / wide,
         # stand-alone: K from M; large single graphs: keep flags (P bytes) read, K of the kept operators, bitmap
         # written; else all of K read, flags written
         "k_keep_count": (4 * P + 12 * g.nnz_out + 8 * P + P) if args.recompute_keep
@@ -431,7 +531,7 @@ def main():
     }
     dur_ms = {
         "k_clear": ph["clear"],
-        "k_level": ph["traverse"] / max(1, level_launches),
+        "k_level": ph["traverse"] / wide,
         "k_keep_count": ph["count"],
         "k_scatter": ph["scatter"],
     }
@@ -439,11 +539,15 @@ def main():
               "k_scatter": ph["scatter"]}
     dominant = max(tot_ms, key=tot_ms.get)
     achieved = alg[dominant] / (dur_ms[dominant] * 1e-3) / 1e9 if dur_ms[dominant] > 0 else 0.0
-    b_alg_total = alg["k_clear"] + alg["k_level"] * levels + alg["k_keep_count"] + alg["k_scatter"]
+    b_alg_total = alg["k_clear"] + traversal_bytes + alg["k_keep_count"] + alg["k_scatter"]
+    counters_apply = args.config == 3 and args.scale == 1.0 and not args.recompute_keep
+    traffic = measured_traffic(dominant) if counters_apply else None
     roofline = {
         "bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": measured_traffic(dominant) if (args.config == 3 and args.scale == 1.0 and not args.recompute_keep) else None,
+        "traffic": traffic,
+        "traffic_source": (COUNTERS + " (committed rocprofv3 --pmc summary, not measured in this run; null when the kernel "
+                           "sources have changed since)"),
         "launch_ms": round(dur_ms[dominant], 4), "launches_per_step": 1 if dominant != "k_level" else level_launches,
         "k_level_launch_ms_device_clock": None if level_us_device_clock is None else round(level_us_device_clock / 1e3, 4),
         "per_kernel_GBs": {k: round(alg[k] / (dur_ms[k] * 1e-3) / 1e9, 1) if dur_ms[k] > 0 else None for k in alg},
@@ -451,20 +555,40 @@ def main():
         "whole_path_frac": round(b_alg_total / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "measured_copy_GBs": copy_gbs,
         "whole_path_measured_GBs": None, "whole_path_measured_frac": None,
+        "atomics": None, "latency_floor_ms": None, "machine_rates": rates,
     }
+    # What does bound the traversal: the 64-bit atomics it issues, against the rate this GPU sustains for random
+    # atomics over an array of the masks' size; and its chain of dependent accesses -- per wide level a launch and
+    # five accesses that each need the one before (state, stamp bytes or queue entry, operator record, output
+    # masks / input ids, atomic), per level of the single-workgroup kernel three loads and an atomic -- at the
+    # unloaded latencies measured on this GPU
+    if rates is not None and ph["traverse"] > 0:
+        a_gps = atomics_per_step / (ph["traverse"] * 1e-3) / 1e9
+        roofline["atomics"] = {"per_step": atomics_per_step, "achieved_Gps": round(a_gps, 2),
+                               "ceiling_Gps": rates["random_atomic_gps"],
+                               "frac": round(a_gps / rates["random_atomic_gps"], 4) if rates["random_atomic_gps"] else None,
+                               "throughput_floor_ms": round(atomics_per_step / (rates["random_atomic_gps"] * 1e9) * 1e3, 4)
+                                                     if rates["random_atomic_gps"] else None}
+        chain_wide = rates["launch_back_to_back_us"] + (4 * rates["dependent_load_ns"] + rates["dependent_atomic_ns"]) / 1e3
+        chain_narrow = (3 * rates["dependent_load_ns"] + rates["dependent_atomic_ns"]) / 1e3
+        roofline["latency_floor_ms"] = round((level_launches * chain_wide + narrow_levels * chain_narrow) / 1e3, 4)
+        roofline["latency_floor_levels"] = {"wide_launches": level_launches, "single_workgroup_levels": narrow_levels,
+                                            "us_per_wide_level": round(chain_wide, 2),
+                                            "us_per_single_workgroup_level": round(chain_narrow, 2)}
 
     # bytes that crossed the HBM interface in one prune according to the committed counter runs (every kernel of the
     # step: the level kernel once per launch), over the step time
-    if roofline["traffic"] is not None and recycled and dominant == "k_level":
-        per_step = [measured_traffic(k) for k in ("k_clear", "k_keep_count", "k_scatter")]
-        if all(v is not None for v in per_step):
-            moved = sum(per_step) + roofline["traffic"] * level_launches
+    if traffic is not None and recycled and dominant == "k_level":
+        others = [measured_traffic(k) for k in ("k_clear", "k_keep_count", "k_scatter")]
+        if all(v is not None for v in others):
+            moved = sum(others) + traffic * level_launches
             roofline["whole_path_measured_GBs"] = round(moved / (ms_per_step * 1e-3) / 1e9, 1)
             roofline["whole_path_measured_frac"] = round(moved / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
 
     # ---- CPU baseline: the oracle as it stands, on this machine's host cores -------------------------
     cpu = None
     parity = None
+    orc = None
     if not args.no_cpu_baseline:
         import oracle as orc
         tb = time.time()
@@ -513,11 +637,27 @@ def main():
             log(f"oracle backward prune, pair {i}: {backward['cpu_oracle_ms_per_pair']:.0f} ms; GPU marks bit-exact: {same}")
             assert same, "GPU backward-prune marks differ from the oracle"
 
+    # ---- the workloads the metric is not quoted on, each built, pruned and checked on its own ------
+    others_out = None
+    if not (args.no_other_configs or args.prune_only) and args.scale == 1.0:
+        del buf, dg, graph_mem, out, extras
+        if cpu is not None:
+            del adj, ref
+        torch.cuda.empty_cache()
+        others_out = {}
+        for k in (0, 1, 2, 4):
+            if k == args.config:
+                continue
+            others_out[f"config{k}"] = other_config(d, torch, np, gg, orc, k, args.steps, args.warmup, cpu is not None)
+
     line = {
         "metric": "pruned edges/sec (GTEPS), 64-query batched prune", "value": round(gteps, 2), "unit": "GTEPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u64", "data": "synthetic",
-        "query_gteps": round(E_query / (ms_per_step * 1e-3) / 1e9, 2), "per_step_ms": per_step,
+        # the same steps with every word of M and K cleared inside each step (a stateless call)
+        "value_full_clear": None if full_clear is None else full_clear["gteps"],
+        "ms_per_step_full_clear": None if full_clear is None else full_clear["ms_per_step"],
+        "query_gteps": round(E_query / (ms_per_step * 1e-3) / 1e9, 2), "steps_timed_one_by_one_ms": one_by_one,
         "config": {"workload": f"configs[{args.config}] {g.name}" + ("" if args.scale == 1.0 else f" x{args.scale}"),
                    "num_ops": P, "num_tensors": T, "nnz_in": g.nnz_in, "nnz_out": g.nnz_out,
                    "num_sets": tg.num_sets, "num_graphs": g.num_graphs,
@@ -536,10 +676,11 @@ def main():
         "full_clear_per_step": full_clear,
         "recycled_alternating_targets": other_targets,
         "transaction_cache": transaction,
+        "other_configs": others_out,
         "build_plus_prune_gteps": round(E / ((build_ms + ms_per_step) * 1e-3) / 1e9, 2),
         "result": {"kept_ops": P_k, "coloured_tensors": T_c, "kept_in_edges": E_k, "kept_out_edges": Eo_k,
-                   "levels": int(st.levels), "tensor_visits": int(st.tensor_visits),
-                   "max_frontier": int(st.max_frontier), "launches": int(st.launches),
+                   "levels": levels_total, "operator_visits": int(st.tensor_visits), "atomic_updates": atomics_per_step,
+                   "max_queue": int(st.max_frontier), "launches": launches_total,
                    "bit_exact_vs_oracle": parity},
     }
     print(json.dumps(line), flush=True)

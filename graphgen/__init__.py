@@ -322,9 +322,14 @@ def backward_pairs(g: Graph, seed: int, num_pairs: int = 64, num_sources: int = 
 # --------------------------------------------------------------------------
 # Input transformations used by tests (no effect on the graph's meaning)
 # --------------------------------------------------------------------------
+def permutation_keys(n: int, seed: int) -> np.ndarray:
+    """The uint64 keys whose stable argsort is ``permutation(n, seed)`` (a caller with a faster sort may use them)."""
+    return rng_u64(seed, S_PERM, np.arange(n, dtype=np.int64))
+
+
 def permutation(n: int, seed: int) -> np.ndarray:
     """Seeded permutation of ``range(n)`` (argsort of counter-based keys; ties impossible in practice)."""
-    return np.argsort(rng_u64(seed, S_PERM, np.arange(n, dtype=np.int64)), kind="stable").astype(np.int64)
+    return np.argsort(permutation_keys(n, seed), kind="stable").astype(np.int64)
 
 
 def shuffle_coo(g: Graph, seed: int) -> Graph:

@@ -158,6 +158,8 @@ typedef struct dgn_stats {
     int64_t reserved;        /* dgn_backward_prune: passes of its forward stage; 0 otherwise                */
     int64_t recycled;        /* 1 when options->recycle found the previous result in place and the call
                                 zeroed only what that result had set                               */
+    int64_t atomic_updates;  /* 64-bit atomic ORs the traversal issued (one per input edge of an operator that
+                                gained bits, plus the seeds); 0 for a packed batch swept per graph      */
     float phase_ms[DGN_NUM_PHASES];   /* filled when options->profile is 1 (all) or 2 (traversal); zero otherwise */
 } dgn_stats;
 

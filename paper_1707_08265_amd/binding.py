@@ -61,7 +61,7 @@ class dgn_stats(ctypes.Structure):
     _fields_ = [("levels", c_int64), ("tensor_visits", c_int64), ("max_frontier", c_int64),
                 ("launches", c_int64), ("level_launches", c_int64), ("level_trace", c_void_p),
                 ("level_trace_cap", c_int64), ("reserved", c_int64), ("recycled", c_int64),
-                ("phase_ms", ctypes.c_float * 8)]
+                ("atomic_updates", c_int64), ("phase_ms", ctypes.c_float * 8)]
 
 class dgn_machine_rates(ctypes.Structure):
     _fields_ = [("random_load_gps", ctypes.c_float), ("random_atomic_gps", ctypes.c_float),

@@ -839,6 +839,7 @@ static int prune_impl(const dgn_graph *g, int32_t num_sets, int64_t num_targets,
         stats->max_frontier = (int64_t)hst->max_frontier;
         stats->launches = launches;
         stats->level_launches = level_launches;
+        stats->atomic_updates = (int64_t)hst->atomic_updates + num_targets;
         if (recycle) stats->recycled = *reinterpret_cast<const u64 *>(static_cast<const char *>(pin) + sizeof(TravState)) ? 1 : 0;
         if (ev) {
             for (int i = 0; i < 6; ++i) DGN_HIP(hipEventElapsedTime(&stats->phase_ms[i], ev[i], ev[i + 1]));

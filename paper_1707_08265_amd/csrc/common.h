@@ -61,7 +61,7 @@ struct LevelSlot {
     int32_t pad;
 };
 
-constexpr int kMaxRuns = 6;
+constexpr int kMaxRuns = 4;
 struct TravState {            // header of the traversal state; the host reads these 128 bytes back
     LevelSlot slot[2];
     int32_t error;             // sticky kErr* bits
@@ -73,6 +73,7 @@ struct TravState {            // header of the traversal state; the host reads t
     int32_t n_runs;            // such stretches completed so far; the first kMaxRuns lengths are kept
     int32_t wide_runs[kMaxRuns];
     int32_t pad;
+    u64 atomic_updates;        // atomic ORs on M and K issued so far (one per input edge of an operator that gained bits)
 };
 
 // Contended words live 64 bytes apart, one per queue segment / block group.
@@ -83,7 +84,8 @@ struct SegCounter {
     int32_t v;           // pushes into this segment of the frontier the launch produced (or handed on)
     int32_t proc;        // entries / operators expanded by the waves that tally here
     int32_t key1;        // 1 + largest operator id those waves deferred
-    int32_t pad[13];
+    int32_t atomics;     // atomic ORs on M and K those waves issued
+    int32_t pad[12];
 };
 // Tallies of a launch, in buffer (launch number) % 3: written by launch e, read by launch e + 1, zeroed by
 // launch e + 2 (one wave, at its start) for launch e + 3.

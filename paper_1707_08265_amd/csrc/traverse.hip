@@ -278,6 +278,7 @@ hipError_t launch_seed(const GraphView &g, int32_t Q, int64_t num_targets, const
 struct LevelCounters {   // per-lane tallies, reduced by the caller
     int processed;
     int max_deferred_key;
+    int atomics;         // atomic ORs issued (statistics only)
 };
 
 struct Masks {           // what a prune writes
@@ -342,6 +343,7 @@ __device__ __forceinline__ void expand_edges(const GraphView &g, int eb, int deg
             if (ev[r]) {
                 pr[r] = g.prod1[u[r]];                      // in flight together with the atomic
                 old[r] = atomicOr(&mk.M[u[r]], b[r]);       // (I2)
+                lc.atomics++;
             }
         }
 #pragma unroll
@@ -409,7 +411,7 @@ __device__ __forceinline__ bool process_ops(const GraphView &g, bool valid, int3
     }
     const u64 nb = k & ~kold;                               // bits o did not have yet
     if (nb) {
-        if (atomic_k) atomicOr(&mk.K[o], k);                // (I1)
+        if (atomic_k) { atomicOr(&mk.K[o], k); lc.atomics++; }   // (I1)
         else store_coherent(&mk.K[o], kold | k);
         if (kold == 0) mk.flags[o] = 1;                     // o is kept
     }
@@ -470,7 +472,7 @@ struct LevelShared {
     int incl[kLevelWaves][kWave];
     int32_t ops[kLevelWaves][kListCap];
     int pref[kMaxSeg + 1];
-    int derived[2];         // operators processed and 1 + largest deferred id of the previous launch
+    int derived[3];         // operators processed, 1 + largest deferred id and atomics of the previous launch
 };
 
 // How one level's work is dealt to `grid` blocks.
@@ -511,7 +513,7 @@ __device__ __forceinline__ LevelPlan plan_level(const LevelSlot &in, int n, bool
     p.chase = false;
     // (no second hop in a launch that opens a range: what the range's operators push is most of the launch's work,
     // and it would all be processed by the few waves that happened to scan it)
-    if (n > 0 && (p.chunks == 0 || DGN_CHASE_WITH_RANGE) && p.nb_s < grid &&
+    if (n > 0 && (p.chunks == 0 || DGN_CHASE_WITH_RANGE == 1 || (DGN_CHASE_WITH_RANGE == 2 && in.theta > 0)) && p.nb_s < grid &&
         (n <= kChaseAlwaysBelow || (n <= kChaseBelow && in.theta <= 0))) {
         const int want = (n + kLevelWaves * kThinPerWave - 1) / (kLevelWaves * kThinPerWave);
         const int nb = min(grid - p.nb_s, want);
@@ -553,7 +555,7 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
     const bool atomic_k = p.chase;                          // the same in every block of the launch
 
     WaveStage ws{&sh.stage[wave][0], 0, 0, f.log ? &sh.lstage[wave][0] : nullptr, 0};
-    LevelCounters lc{0, -1};
+    LevelCounters lc{0, -1, 0};
     if (p.per_wave > 0) {
         if (do_entries) {
             const int i = (e_first * kLevelWaves + wave) * p.per_wave + lane;
@@ -642,11 +644,12 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
     flush_entries(ws, f);
     flush_log(ws, f);
     // the wave's tallies go to one of 64 spread words each; nobody waits for them
-    const int wproc = wave_sum(lc.processed), wkey = wave_max(lc.max_deferred_key);
+    const int wproc = wave_sum(lc.processed), wkey = wave_max(lc.max_deferred_key), wat = wave_sum(lc.atomics);
     if (lane == 0) {
         const int word = (blk * kLevelWaves + wave) & (kMaxSeg - 1);
         if (wproc) atomicAdd(&tally[word].proc, wproc);
         if (wkey >= 0) atomicMax(&tally[word].key1, wkey + 1);
+        if (wat) atomicAdd(&tally[word].atomics, wat);
     }
 }
 
@@ -666,11 +669,12 @@ __device__ __forceinline__ LevelSlot derive_state(const TravState *st, const Tra
         if (lane < qg.S) c = min(tally->v, qg.seg_cap);
         const int pr = tally->proc;
         const int mk = tally->key1;
+        const int at = tally->atomics;
         const int incl = wave_incl_scan(c);
         if (lane == 0) s_pref[0] = 0;
         s_pref[lane + 1] = incl;
-        const int tot = wave_sum(pr), key1 = wave_max(mk);
-        if (lane == 0) { s_derived[0] = tot; s_derived[1] = key1; }
+        const int tot = wave_sum(pr), key1 = wave_max(mk), tat = wave_sum(at);
+        if (lane == 0) { s_derived[0] = tot; s_derived[1] = key1; s_derived[2] = tat; }
     }
     __syncthreads();
     LevelSlot s = rec;
@@ -695,19 +699,21 @@ __device__ __forceinline__ LevelSlot derive_state(const TravState *st, const Tra
 // wave clears the tallies buffer of the NEXT launch (last read by the previous one).  works: this launch
 // runs a wide level; small: the state it starts from is one the single-workgroup kernel takes (or final).
 __device__ __forceinline__ void keep_books(TravState *st, TravCounters *ctr, int launch_no, const LevelSlot &prev_rec,
-                                           const LevelSlot &now, bool works, bool small, int tot_proc, int4 *trace)
+                                           const LevelSlot &now, bool works, bool small, int tot_proc, int tot_atomics, int4 *trace)
 {
     const int lane = lane_id();
     const int nxt = (launch_no + 1) % 3;
     ctr->cnt[nxt][lane].v = 0;
     ctr->cnt[nxt][lane].proc = 0;
     ctr->cnt[nxt][lane].key1 = 0;
+    ctr->cnt[nxt][lane].atomics = 0;
     if (lane == 0) {
         LevelSlot rec = now;
         rec.worked = works ? 1 : 0;
         st->slot[launch_no & 1] = rec;
         if (prev_rec.worked) {
             st->tensor_visits += (u64)tot_proc;
+            st->atomic_updates += (u64)tot_atomics;
             if ((u64)prev_rec.n > st->max_frontier) st->max_frontier = (u64)prev_rec.n;
             if (trace && prev_rec.level < kTraceLevels)
                 trace[prev_rec.level] = make_int4(prev_rec.n, tot_proc, prev_rec.theta, (int)(uint32_t)wall_clock64());
@@ -744,7 +750,7 @@ __global__ __launch_bounds__(kLevelThreads) void k_level(GraphView g, TravState 
     // finished, or small enough for the single-workgroup kernel: nothing to do but to pass things on
     const bool works = !(n <= narrow_cap && !ranges_left);
     if (blockIdx.x == 0 && threadIdx.x < kWave) {
-        keep_books(st, ctr, launch_no, prev_rec, in, works, !works, tot_proc, trace);
+        keep_books(st, ctr, launch_no, prev_rec, in, works, !works, tot_proc, sh.derived[2], trace);
         if (!works) hand_on_frontier(ctr, launch_no, sh.pref);
     }
     if (!works) return;
@@ -788,7 +794,7 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
     __shared__ int32_t s_lstage[kNarrowWaves][kLogStageCap];
     __shared__ int s_incl[kNarrowWaves][kWave];
     __shared__ int s_pref[kMaxSeg + 1];
-    __shared__ int s_derived[2];
+    __shared__ int s_derived[3];
     __shared__ int s_nout;
     // The queue a level builds is also kept here: the next level -- at most kNarrowFront entries, or this
     // kernel does not run it -- takes it from LDS and need not wait for its own queue stores to reach memory.
@@ -804,7 +810,7 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
     const bool ranges_left = in.deferred_seen && in.theta_hi > 0;   // then the wide kernel must go on
     const int lane = lane_id(), wave = threadIdx.x >> 6;
     WaveStage ws{&s_stage[wave][0], 0, 0, log.entries ? &s_lstage[wave][0] : nullptr, 0};
-    LevelCounters lc{0, -1};
+    LevelCounters lc{0, -1, 0};
     u64 visits = 0, maxf = 0;
     while (n > 0 && n <= narrow_cap && !ranges_left) {
         if (threadIdx.x == 0) s_nout = 0;
@@ -842,10 +848,14 @@ __global__ __launch_bounds__(kNarrowThreads) void k_narrow(GraphView g, TravStat
                           log.seg_cap, nullptr, 0};
         flush_log(ws, lf);
     }
+    {
+        const int wat = wave_sum(lc.atomics);
+        if (lane == 0 && wat) atomicAdd(&st->atomic_updates, (u64)wat);
+    }
     // This launch leaves no tallies to fold: its record IS the state after it.  The queue it ends with
     // (untouched, or the one it built in segment 0) goes to the next launch through this launch's counters.
     if (threadIdx.x < kWave) {
-        keep_books(st, ctr, launch_no, prev_rec, in, false, in.n <= narrow_cap && !ranges_left, tot_proc, trace);
+        keep_books(st, ctr, launch_no, prev_rec, in, false, in.n <= narrow_cap && !ranges_left, tot_proc, s_derived[2], trace);
         hand_on_frontier(ctr, launch_no, s_pref);
         if (lane == 0) {
             LevelSlot *rec = &st->slot[launch_no & 1];
@@ -880,7 +890,7 @@ __global__ __launch_bounds__(kLevelThreads) void k_fix_sweep(GraphView g, Masks 
     __syncthreads();
     WaveStage ws{&s_stage[wave][0], 0, 0, nullptr, 0};
     const Frontier f{nullptr, &s_sink, 0, &s_err, nullptr, nullptr, 0, nullptr, 0};   // capacity 0: pushes are counted and dropped
-    LevelCounters lc{0, -1};
+    LevelCounters lc{0, -1, 0};
     bool any = false;
     // descending ids: most of a sweep then sees its consumers' results (ids are a topological order).  Operators
     // are processed while their consumers still push, in no order between blocks: K by atomic ORs, threshold 0.
