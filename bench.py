@@ -170,6 +170,7 @@ def main():
                     help="also run one plain 1 GiB device copy (known size, to scale profiler byte counters)")
     ap.add_argument("--no-shuffled-build", action="store_true",
                     help="skip the CSR build on the same edges in shuffled COO order (every sort runs)")
+    ap.add_argument("--build-only", action="store_true", help="time the two CSR builds and stop (for profiling runs)")
     ap.add_argument("--no-other-configs", action="store_true", help="skip the four workloads the metric is not quoted on")
     ap.add_argument("--prune-only", action="store_true",
                     help="only the timed prunes: no other legs, configs, shuffled build or machine rates (for profiling runs)")
@@ -212,10 +213,14 @@ def main():
     build_ms, handle = timed_build(d, torch, np, desc, graph_mem, gb, scratch, sb)
     log(f"CSR build: {build_ms:.2f} ms ({E / build_ms / 1e6:.1f} GTEPS)")
     build_shuffled_ms = None
-    if not (args.no_shuffled_build or args.prune_only):
+    if args.build_only or not (args.no_shuffled_build or args.prune_only):
         build_shuffled_ms = shuffled_build_ms(d, torch, np, gg, g, in_op, in_t, out_op, out_t, gb, sb, scratch)
         log(f"CSR build, shuffled COO: {build_shuffled_ms:.2f} ms ({E / build_shuffled_ms / 1e6:.1f} GTEPS)")
     del scratch
+    if args.build_only:
+        print(json.dumps({"build_ms": round(build_ms, 3), "build_shuffled_ms": round(build_shuffled_ms, 3),
+                          "config": {"workload": f"configs[{args.config}] {g.name}"}}), flush=True)
+        return
     rc, sizes = d.dgn_graph_get_sizes(handle)
     dg = d.DeviceGraph(handle, graph_mem, (), sizes)
     del in_op, in_t, out_op, out_t

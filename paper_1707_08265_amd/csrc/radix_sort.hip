@@ -1,21 +1,29 @@
-// Stable LSD radix sort of (int32 key, int32 value) pairs, 8 bits per pass, for the CSR builder.
+// Stable LSD radix sort of (int32 key, int32 value) pairs, 9 bits per pass, for the CSR builder.
 //
 // Per pass: (1) per-tile digit histogram, stored digit-major so that one exclusive scan over the
 // whole table yields, for every (digit, tile), the first output slot of that tile's keys with that
 // digit; (2) the scan; (3) a scatter in which every wave ranks its keys with ballot "match" masks:
 // keys of one tile are visited in their stored order, so equal keys keep their relative order.
-// Only the significant key bits are sorted (ceil(log2(rows)) of them), so 50M operators cost four
-// passes, not eight.
+// Only the significant key bits are sorted (ceil(log2(rows)) of them), so 50M operators (26 bits) or 100M
+// tensors (27 bits) cost three passes.  (Eight bits per pass and four passes: 9 % slower on that graph; a pass
+// with 512 digits costs more than one with 256, because a tile of 4 096 keys then leaves in runs of 8 keys per
+// digit instead of 16, but not a third more.)
 #include "common.h"
 
 namespace dgn {
 
-constexpr int kSortThreads = 256;
-constexpr int kSortWaves = kSortThreads / kWave;
-constexpr int kSortRounds = 16;                         // keys per lane
-constexpr int kSortTile = kSortThreads * kSortRounds;   // 4096 keys per workgroup
-constexpr int kRadixBits = 8;
+#ifndef DGN_RADIX_BITS
+#define DGN_RADIX_BITS 9
+#endif
+#ifndef DGN_SORT_ROUNDS
+#define DGN_SORT_ROUNDS 8
+#endif
+constexpr int kRadixBits = DGN_RADIX_BITS;
 constexpr int kRadix = 1 << kRadixBits;
+constexpr int kSortThreads = kRadix;                    // one thread per digit in the per-tile bookkeeping
+constexpr int kSortWaves = kSortThreads / kWave;
+constexpr int kSortRounds = DGN_SORT_ROUNDS;            // keys per lane
+constexpr int kSortTile = kSortThreads * kSortRounds;   // keys per workgroup
 
 __device__ __forceinline__ int digit_of(int32_t key, int shift) { return ((uint32_t)key >> shift) & (kRadix - 1); }
 
@@ -49,7 +57,7 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_scatter(const int32_t *ke
     for (int i = threadIdx.x; i < kSortWaves * kRadix; i += kSortThreads) (&wcount[0][0])[i] = 0;
     __syncthreads();
 
-    // wave w owns keys [base + w*1024, base + (w+1)*1024) of the tile, visited 64 at a time
+    // wave w owns kSortRounds * 64 consecutive keys of the tile, visited 64 at a time
     const int64_t tbase = (int64_t)blockIdx.x * kSortTile;
     const int64_t wbase = tbase + (int64_t)wave * (kSortRounds * kWave);
     int32_t key[kSortRounds], val[kSortRounds];
