@@ -448,7 +448,10 @@ __device__ __forceinline__ int32_t next_theta(int32_t theta, const Schedule &sch
 // ------------------------------------------------------------------------------------------------
 constexpr int kLevelThreads = 256;
 constexpr int kLevelWaves = kLevelThreads / kWave;
-constexpr int kChaseBelow = 32768;                 // queues up to this size get a second hop in the same launch ...
+#ifndef DGN_CHASE_BELOW
+#define DGN_CHASE_BELOW 32768
+#endif
+constexpr int kChaseBelow = DGN_CHASE_BELOW;       // queues up to this size get a second hop in the same launch ...
 constexpr int kChaseAlwaysBelow = 8192;            // ... or, while the deferral threshold is still coming down, up to this size
 constexpr int kThinPerWave = 8;                    // ... with about this many entries dealt to a wave
 constexpr int kMinChunkLog = 3;                    // a wave scans between 8 ...
@@ -461,7 +464,11 @@ constexpr int kThinMin = 16;
 #ifndef DGN_CHASE_HOPS
 #define DGN_CHASE_HOPS 1
 #endif
-constexpr int kChaseHops = DGN_CHASE_HOPS;         // hops a wave adds on its own in a launch with a small queue
+constexpr int kChaseHops = DGN_CHASE_HOPS;         // hops a wave adds on its own in a launch with a small queue ...
+#ifndef DGN_TAIL_HOPS
+#define DGN_TAIL_HOPS 32
+#endif
+constexpr int kTailHops = DGN_TAIL_HOPS;           // ... and once the threshold has reached zero
 #ifndef DGN_CHASE_WITH_RANGE
 #define DGN_CHASE_WITH_RANGE 1                     // 1: a second hop also in launches that open a range
 #endif
@@ -627,7 +634,8 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
     // goes to memory (any order reaches the same fixed point; a hop done here is a launch saved wherever the
     // levels are small).
     if (p.chase) {
-        for (int hop = 0; hop < kChaseHops; ++hop) {
+        const int hops = in.theta > 0 ? kChaseHops : kTailHops;
+        for (int hop = 0; hop < hops; ++hop) {
             int gen_end = ws.tail;                          // the entries pushed so far: the next hop of this launch
             if (gen_end - ws.head <= 0) break;              // wave-uniform
             while (gen_end - ws.head > 0) {                 // wave-uniform (a flush empties the ring: head = tail)
