@@ -22,24 +22,29 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRCS = [os.path.join(_HERE, f) for f in ("forward_prune.c", "backward_prune.c", "inplace.c",
                                              "postprocess.c", "transaction.c")]
 _LIB = os.path.join(_HERE, "liboracle.so")
+_LIB_SAN = os.path.join(_HERE, "liboracle_san.so")
 _lib = None
 
 
-def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (plain -O2, no threading)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(f) for f in _SRCS):
-        tmp = _LIB + f".tmp{os.getpid()}"
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fPIC", "-shared",
-                               *_SRCS, "-o", tmp])
-        os.replace(tmp, _LIB)
-    return _LIB
+def build(force: bool = False, sanitize: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, no threading).  ``sanitize``: a second library built with
+    AddressSanitizer and UndefinedBehaviorSanitizer (any finding aborts the process); a process that loads it must
+    have been started with the ASan runtime preloaded (see ``tests/test_oracle_sanitized.py``)."""
+    lib = _LIB_SAN if sanitize else _LIB
+    flags = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer"] \
+        if sanitize else ["-O2"]
+    if force or not os.path.exists(lib) or os.path.getmtime(lib) < max(os.path.getmtime(f) for f in _SRCS):
+        tmp = lib + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", *flags, "-std=c11", "-Wall", "-Wextra", "-fPIC", "-shared", *_SRCS, "-o", tmp])
+        os.replace(tmp, lib)
+    return lib
 
 
 def _load():
     global _lib
     if _lib is None:
-        build()
-        _lib = ctypes.CDLL(_LIB)
+        # ORACLE_SANITIZE=1: run on the sanitizer build (the oracle's own arithmetic is the same source)
+        _lib = ctypes.CDLL(build(sanitize=os.environ.get("ORACLE_SANITIZE") == "1"))
         _lib.orc_certificate.restype = ctypes.c_int64
         _lib.orc_child_sets.restype = ctypes.c_int64
         _lib.orc_per_set_lists.restype = ctypes.c_int64
