@@ -583,38 +583,54 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
     // processed 64 per step
     const int lw_log = max(p.cs_log - 6, 0), lw = 1 << lw_log;              // marker bytes per lane
     const int lanes_on = 1 << min(p.cs_log, 6);
+    const int parts = max(lw >> 4, 1);                                      // 16-byte pieces per lane (1..4)
     const int64_t limit = ((int64_t)p.band_hi + 63) & ~(int64_t)63;         // the byte map is padded to whole 64s
     for (int c = s_first * kLevelWaves + wave; do_scan && c < p.chunks; c += s_blocks * kLevelWaves) {
-        const int64_t op0 = (int64_t)p.band_lo + ((int64_t)c << p.cs_log) + ((int64_t)lane << lw_log);
-        u64 bits = 0;
-        if (lane < lanes_on && op0 < limit) {
-            if (lw >= 16) {
-                const uint4 *src = reinterpret_cast<const uint4 *>(mk.DB + op0);
-                for (int k = 0; k < (lw >> 4); ++k) {
-                    const uint4 x = src[k];
-                    const uint32_t b16 = gather4(x.x) | (gather4(x.y) << 4) | (gather4(x.z) << 8) | (gather4(x.w) << 12);
-                    bits |= (u64)b16 << (16 * k);
-                }
-            } else if (lw >= 4) {
+        const int64_t c_lo = (int64_t)p.band_lo + ((int64_t)c << p.cs_log);
+        // Up to 16 bytes per lane: lane l looks at the lw operators from c_lo + l * lw on.  More: the chunk is taken in
+        // pieces of 1024 operators, lane l looking at 16 of each, so that every load of the wave is one contiguous KiB.
+        const int64_t op0 = lw >= 16 ? c_lo + lane * 16 : c_lo + ((int64_t)lane << lw_log);
+        u64 bits = 0;                                       // piece p in bits [16 p, 16 p + 16)
+        if (lw >= 16) {
+            uint4 x[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                x[q] = make_uint4(0, 0, 0, 0);
+                if (q < parts && op0 + q * 1024 < limit) x[q] = *reinterpret_cast<const uint4 *>(mk.DB + op0 + q * 1024);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (q >= parts) break;
+                uint32_t b16 = gather4(x[q].x) | (gather4(x[q].y) << 4) | (gather4(x[q].z) << 8) | (gather4(x[q].w) << 12);
+                // keep only ids in [theta, theta_hi)
+                const int64_t lo_cut = in.theta - (op0 + q * 1024), hi_cut = in.theta_hi - (op0 + q * 1024);
+                if (lo_cut > 0) b16 &= lo_cut >= 16 ? 0u : ~((1u << lo_cut) - 1u);
+                if (hi_cut < 16) b16 &= hi_cut <= 0 ? 0u : (1u << hi_cut) - 1u;
+                bits |= (u64)b16 << (16 * q);
+            }
+        } else if (lane < lanes_on && op0 < limit) {
+            uint32_t b16;
+            if (lw >= 4) {
                 const uint32_t *src = reinterpret_cast<const uint32_t *>(mk.DB + op0);
-                for (int k = 0; k < (lw >> 2); ++k) bits |= (u64)gather4(src[k]) << (4 * k);
+                b16 = gather4(src[0]);
+                if (lw == 8) b16 |= gather4(src[1]) << 4;
             } else {
                 const uint32_t *src = reinterpret_cast<const uint32_t *>(mk.DB + (op0 & ~(int64_t)3));
-                bits = gather4(src[0] >> ((int)(op0 & 3) * 8)) & ((1u << lw) - 1u);
+                b16 = gather4(src[0] >> ((int)(op0 & 3) * 8)) & ((1u << lw) - 1u);
             }
-            // keep only ids in [theta, theta_hi)
             const int64_t lo_cut = in.theta - op0, hi_cut = in.theta_hi - op0;
-            if (lo_cut > 0) bits &= lo_cut >= 64 ? (u64)0 : ~(((u64)1 << lo_cut) - 1);
-            if (hi_cut < lw) bits &= hi_cut <= 0 ? (u64)0 : ((u64)1 << hi_cut) - 1;
+            if (lo_cut > 0) b16 &= lo_cut >= 16 ? 0u : ~((1u << lo_cut) - 1u);
+            if (hi_cut < lw) b16 &= hi_cut <= 0 ? 0u : (1u << hi_cut) - 1u;
+            bits = b16;
         }
-        for (int part = 0; part < max(lw >> 4, 1); ++part) {
+        for (int part = 0; part < parts; ++part) {
             uint32_t bits16 = (uint32_t)(bits >> (16 * part)) & 0xffffu;
             const int cnt = __popc(bits16);
             const int incl = wave_incl_scan(cnt);
             const int total = __shfl(incl, kWave - 1, kWave);
             if (total == 0) continue;                       // wave-uniform
             int pos = incl - cnt;
-            const int32_t op_base = (int32_t)op0 + 16 * part;
+            const int32_t op_base = (int32_t)op0 + 1024 * part;
             while (bits16) {
                 const int b = __builtin_ctz(bits16);
                 bits16 &= bits16 - 1;
