@@ -43,7 +43,7 @@ constexpr int kSweepMinGraphs = 64;         // packed batches with at least this
 constexpr int64_t kSweepMaxGraphOps = 1 << 18;   // ... none larger than this use the per-graph sweep
 constexpr u64 kRecycleMagic = 0x44474e5f52435943ull;   // "DGN_RCYC"
 constexpr int kSmallLevel = 16384;           // levels expanding fewer entries than this decay the threshold faster
-constexpr int kDefaultDeferPercent = 78;
+constexpr int kDefaultDeferPercent = 74;
 constexpr int kDefaultStartShift = 1;       // deferral threshold starts at P >> 1 ...
 constexpr int kDefaultFloorShift = 10;      // ... and stops (drops to 0) below P >> 10
 

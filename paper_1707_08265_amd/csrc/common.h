@@ -82,9 +82,9 @@ constexpr int kMaxSeg = 64;
 constexpr int kTraceLevels = 4096;
 struct SegCounter {
     int32_t v;           // pushes into this segment of the frontier the launch produced (or handed on)
-    int32_t proc;        // entries / operators expanded by the waves that tally here
-    int32_t key1;        // 1 + largest operator id those waves deferred
-    int32_t atomics;     // atomic ORs on M and K those waves issued
+    int32_t key1;        // 1 + largest operator id deferred by the workgroups that tally here
+    int32_t proc;        // entries / operators expanded by those workgroups ...
+    int32_t atomics;     // ... and the atomic ORs on M and K they issued (the two are added as one 64-bit word)
     int32_t pad[12];
 };
 // Tallies of a launch, in buffer (launch number) % 3: written by launch e, read by launch e + 1, zeroed by

@@ -448,30 +448,18 @@ __device__ __forceinline__ int32_t next_theta(int32_t theta, const Schedule &sch
 // ------------------------------------------------------------------------------------------------
 constexpr int kLevelThreads = 256;
 constexpr int kLevelWaves = kLevelThreads / kWave;
-#ifndef DGN_CHASE_BELOW
-#define DGN_CHASE_BELOW 32768
-#endif
-constexpr int kChaseBelow = DGN_CHASE_BELOW;       // queues up to this size get a second hop in the same launch ...
-constexpr int kChaseAlwaysBelow = 8192;            // ... or, while the deferral threshold is still coming down, up to this size
-constexpr int kThinPerWave = 8;                    // ... with about this many entries dealt to a wave
+constexpr int kThinPerWave = 8;                    // queue entries dealt to a wave, when the grid has the waves for it
 constexpr int kMinChunkLog = 3;                    // a wave scans between 8 ...
 constexpr int kMaxChunkLog = 12;                   // ... and 4096 marker bytes per step (64 per lane)
 constexpr int kListCap = 16 * kWave;               // marked operators listed per wave before they are processed
-#ifndef DGN_THIN_ENTRIES
-#define DGN_THIN_ENTRIES 0                         // 1: a queue that leaves waves idle is dealt thinly over all of them
-#endif
-constexpr int kThinMin = 16;
 #ifndef DGN_CHASE_HOPS
 #define DGN_CHASE_HOPS 1
 #endif
-constexpr int kChaseHops = DGN_CHASE_HOPS;         // hops a wave adds on its own in a launch with a small queue ...
+constexpr int kChaseHops = DGN_CHASE_HOPS;         // hops a wave adds on its own in a launch ...
 #ifndef DGN_TAIL_HOPS
 #define DGN_TAIL_HOPS 32
 #endif
 constexpr int kTailHops = DGN_TAIL_HOPS;           // ... and once the threshold has reached zero
-#ifndef DGN_CHASE_WITH_RANGE
-#define DGN_CHASE_WITH_RANGE 1                     // 1: a second hop also in launches that open a range
-#endif
 
 struct LevelShared {
     int32_t stage[kLevelWaves][kStageCap];
@@ -480,68 +468,73 @@ struct LevelShared {
     int32_t ops[kLevelWaves][kListCap];
     int pref[kMaxSeg + 1];
     int derived[3];         // operators processed, 1 + largest deferred id and atomics of the previous launch
+    int tally[kLevelWaves][3];
 };
 
-// How one level's work is dealt to `grid` blocks.
+// How one level's work is dealt to `grid` blocks.  Queue entries and range chunks go to different blocks, so that
+// the two dependent-access chains of a level overlap and no wave does one after the other.
 struct LevelPlan {
     int band_lo, band_hi;  // marker bytes of the operators [band_lo, band_hi) are read: the range [theta, theta_hi) that
-                           // opens at this level, its lower end rounded down to a whole chunk
-    int cs_log, chunks;    // the range is dealt to the waves in chunks of 1 << cs_log operators (8..4096): as small as
-                           // the number of waves allows -- a range far down the graph is dense with marked operators,
-                           // and a wave that finds 64 of them works through several hundred input edges while the
-                           // rest of the chip idles -- and large enough that a wide, sparse range needs one step per wave
-    int nb_e, nb_s;        // blocks wanted by the queue entries / by the range chunks
-    bool split;            // entries and chunks go to different blocks when the grid has room for both, so
-                           // the two dependent-access chains of a small level overlap
+                           // opens at this level, its lower end rounded down to a whole load
+    int cs, lw_log, chunks;// the range is dealt to the waves in chunks of cs operators (8..4096), a lane reading
+                           // 1 << lw_log marker bytes (cs <= 512: 1, 2, 4 or 8 and only cs >> lw_log lanes read; above: cs / 64):
+                           // as small as the number of waves allows -- a range far down the graph is dense with marked
+                           // operators, and a wave that finds 64 of them works through several hundred input edges while
+                           // the rest of the chip idles -- and large enough that a wide, sparse range needs one step per wave
+    int nb_e, nb_s;        // blocks that take the queue entries / the range chunks
     int nwork;             // blocks that have something to do
-    int per_wave;          // 0: every wave takes 64 entries at a time.  Else the entries are dealt thinly, per_wave to a wave
-    bool chase;            // (small queue, no range to scan) what a wave pushes fits one more step of its own: it then
-                           // processes those pushes itself, a second hop within the same launch
+    int per_wave;          // the entries are dealt thinly, per_wave (8..64) to a wave: all the waves that the range leaves
+                           // idle share them.  0: more entries than that; every wave then takes 64 at a time
+    bool chase;            // (per_wave > 0) a wave then processes what it has just pushed itself, a second hop within the
+                           // same launch
 };
 
 __device__ __forceinline__ LevelPlan plan_level(const LevelSlot &in, int n, bool ranges_left, int grid)
 {
     LevelPlan p;
     p.band_lo = p.band_hi = p.chunks = 0;
-    p.cs_log = kMinChunkLog;
+    p.cs = 1 << kMinChunkLog;
+    p.lw_log = 0;
     const int waves = grid * kLevelWaves;
-    if (ranges_left) {
-        // waves left over by the queue entries, but at least a quarter of the grid
-        const int avail = max(waves - (n + kWave - 1) / kWave, grid);
-        const int span = in.theta_hi - in.theta;
-        while (p.cs_log < kMaxChunkLog && (span >> p.cs_log) + 1 > avail) ++p.cs_log;
-        p.band_lo = in.theta & ~((1 << p.cs_log) - 1);
-        p.band_hi = in.theta_hi;
-        p.chunks = (p.band_hi - p.band_lo + (1 << p.cs_log) - 1) >> p.cs_log;
-    }
-    p.nb_e = (n + kLevelThreads - 1) / kLevelThreads;
-    p.nb_s = (p.chunks + kLevelWaves - 1) / kLevelWaves;
-    p.per_wave = 0;
-    p.chase = false;
-    // (no second hop in a launch that opens a range: what the range's operators push is most of the launch's work,
-    // and it would all be processed by the few waves that happened to scan it)
-    if (n > 0 && (p.chunks == 0 || DGN_CHASE_WITH_RANGE == 1 || (DGN_CHASE_WITH_RANGE == 2 && in.theta > 0)) && p.nb_s < grid &&
-        (n <= kChaseAlwaysBelow || (n <= kChaseBelow && in.theta <= 0))) {
-        const int want = (n + kLevelWaves * kThinPerWave - 1) / (kLevelWaves * kThinPerWave);
-        const int nb = min(grid - p.nb_s, want);
-        const int per = (n + nb * kLevelWaves - 1) / (nb * kLevelWaves);
-        if (per <= 2 * kThinPerWave) {
-            p.nb_e = nb;
-            p.per_wave = per;
-            p.chase = true;
+    // no operator above the largest id noted so far is marked
+    const int top = min(in.theta_hi, in.max_key1);
+    if (ranges_left && top > in.theta) {
+        // the waves that the queue entries leave over, but at least half of them
+        const int reserve = (n + kThinPerWave - 1) / kThinPerWave;
+        const int avail = max(waves - reserve, waves / 2);
+        const int span = top - in.theta;
+        int cs = max((span + avail) / avail, 1 << kMinChunkLog);            // > span / avail
+        if (cs <= 512) {
+            while ((kWave << p.lw_log) < cs) ++p.lw_log;
+            cs = (cs + (1 << p.lw_log) - 1) & ~((1 << p.lw_log) - 1);
+        } else {
+            int lg = 10;
+            while (lg < kMaxChunkLog && (1 << lg) < cs) ++lg;
+            cs = 1 << lg;
+            p.lw_log = lg - 6;
         }
+        p.cs = cs;
+        p.band_lo = in.theta & ~((1 << min(p.lw_log, 4)) - 1);
+        p.band_hi = top;
+        p.chunks = (p.band_hi - p.band_lo + cs - 1) / cs;
     }
-    if (DGN_THIN_ENTRIES && n > 0 && !p.chase && p.nb_s < grid) {
-        const int wave_room = (grid - p.nb_s) * kLevelWaves;
-        int per = (n + wave_room - 1) / wave_room;
-        per = max(per, kThinMin);
-        if (per < kWave) {
+    // (more chunks than waves: the waves loop.  The grid has at least two blocks: one is left for the entries)
+    p.nb_s = min((p.chunks + kLevelWaves - 1) / kLevelWaves, grid - (n > 0 ? 1 : 0));
+    const int room = (grid - p.nb_s) * kLevelWaves;                        // waves for the entries
+    p.per_wave = 0;
+    p.nb_e = 0;
+    p.chase = false;
+    if (n > 0) {
+        const int per = max((n + room - 1) / room, kThinPerWave);
+        if (per <= kWave) {
             p.per_wave = per;
             p.nb_e = (n + per * kLevelWaves - 1) / (per * kLevelWaves);
+            p.chase = true;
+        } else {
+            p.nb_e = grid - p.nb_s;
         }
     }
-    p.split = p.nb_e + p.nb_s <= grid;
-    p.nwork = p.split ? max(1, p.nb_e + p.nb_s) : grid;
+    p.nwork = max(1, p.nb_e + p.nb_s);
     return p;
 }
 
@@ -555,10 +548,10 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
                                           LevelShared &sh, SegCounter *tally)
 {
     const int lane = lane_id(), wave = threadIdx.x >> 6;
-    const bool do_entries = !p.split || blk < p.nb_e;
-    const bool do_scan = !p.split || blk >= p.nb_e;
-    const int e_blocks = p.split ? p.nb_e : p.nwork, e_first = blk;
-    const int s_blocks = p.split ? p.nb_s : p.nwork, s_first = p.split ? blk - p.nb_e : blk;
+    const bool do_entries = blk < p.nb_e;
+    const bool do_scan = !do_entries;
+    const int e_blocks = p.nb_e, e_first = blk;
+    const int s_blocks = p.nb_s, s_first = blk - p.nb_e;
     const bool atomic_k = p.chase;                          // the same in every block of the launch
 
     WaveStage ws{&sh.stage[wave][0], 0, 0, f.log ? &sh.lstage[wave][0] : nullptr, 0};
@@ -581,13 +574,13 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
     // the marker bytes of the newly opened range, a chunk per step: every lane fetches its 1..64 bytes at once and
     // squeezes them into a bit mask; the marked operators are listed in LDS, sixteen bytes per lane at a time, and
     // processed 64 per step
-    const int lw_log = max(p.cs_log - 6, 0), lw = 1 << lw_log;              // marker bytes per lane
-    const int lanes_on = 1 << min(p.cs_log, 6);
+    const int lw_log = p.lw_log, lw = 1 << lw_log;                          // marker bytes per lane
+    const int lanes_on = min(p.cs >> lw_log, kWave);
     const int parts = max(lw >> 4, 1);                                      // 16-byte pieces per lane (1..4)
     const int64_t limit = ((int64_t)p.band_hi + 63) & ~(int64_t)63;         // the byte map is padded to whole 64s
     for (int c = s_first * kLevelWaves + wave; do_scan && c < p.chunks; c += s_blocks * kLevelWaves) {
-        const int64_t c_lo = (int64_t)p.band_lo + ((int64_t)c << p.cs_log);
-        // Up to 16 bytes per lane: lane l looks at the lw operators from c_lo + l * lw on.  More: the chunk is taken in
+        const int64_t c_lo = (int64_t)p.band_lo + (int64_t)c * p.cs;
+        // Up to 8 bytes per lane: lane l looks at the lw operators from c_lo + l * lw on.  More: the chunk is taken in
         // pieces of 1024 operators, lane l looking at 16 of each, so that every load of the wave is one contiguous KiB.
         const int64_t op0 = lw >= 16 ? c_lo + lane * 16 : c_lo + ((int64_t)lane << lw_log);
         u64 bits = 0;                                       // piece p in bits [16 p, 16 p + 16)
@@ -610,13 +603,15 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
             }
         } else if (lane < lanes_on && op0 < limit) {
             uint32_t b16;
-            if (lw >= 4) {
-                const uint32_t *src = reinterpret_cast<const uint32_t *>(mk.DB + op0);
-                b16 = gather4(src[0]);
-                if (lw == 8) b16 |= gather4(src[1]) << 4;
+            if (lw == 8) {
+                const uint2 x = *reinterpret_cast<const uint2 *>(mk.DB + op0);
+                b16 = gather4(x.x) | (gather4(x.y) << 4);
+            } else if (lw == 4) {
+                b16 = gather4(*reinterpret_cast<const uint32_t *>(mk.DB + op0));
+            } else if (lw == 2) {
+                b16 = gather4(*reinterpret_cast<const uint16_t *>(mk.DB + op0));
             } else {
-                const uint32_t *src = reinterpret_cast<const uint32_t *>(mk.DB + (op0 & ~(int64_t)3));
-                b16 = gather4(src[0] >> ((int)(op0 & 3) * 8)) & ((1u << lw) - 1u);
+                b16 = mk.DB[op0] & 1u;
             }
             const int64_t lo_cut = in.theta - op0, hi_cut = in.theta_hi - op0;
             if (lo_cut > 0) b16 &= lo_cut >= 16 ? 0u : ~((1u << lo_cut) - 1u);
@@ -667,13 +662,26 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
     }
     flush_entries(ws, f);
     flush_log(ws, f);
-    // the wave's tallies go to one of 64 spread words each; nobody waits for them
+    // the block's tallies go to one of 64 spread words; nobody waits for them
     const int wproc = wave_sum(lc.processed), wkey = wave_max(lc.max_deferred_key), wat = wave_sum(lc.atomics);
     if (lane == 0) {
-        const int word = (blk * kLevelWaves + wave) & (kMaxSeg - 1);
-        if (wproc) atomicAdd(&tally[word].proc, wproc);
-        if (wkey >= 0) atomicMax(&tally[word].key1, wkey + 1);
-        if (wat) atomicAdd(&tally[word].atomics, wat);
+        sh.tally[wave][0] = wproc;
+        sh.tally[wave][1] = wkey;
+        sh.tally[wave][2] = wat;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int bproc = 0, bkey = -1, bat = 0;
+#pragma unroll
+        for (int w = 0; w < kLevelWaves; ++w) {
+            bproc += sh.tally[w][0];
+            bkey = max(bkey, sh.tally[w][1]);
+            bat += sh.tally[w][2];
+        }
+        const int word = blk & (kMaxSeg - 1);
+        if (bproc | bat)
+            atomicAdd(reinterpret_cast<unsigned long long *>(&tally[word].proc), (u64)(uint32_t)bproc | ((u64)(uint32_t)bat << 32));
+        if (bkey >= 0) atomicMax(&tally[word].key1, bkey + 1);
     }
 }
 
@@ -797,6 +805,7 @@ hipError_t launch_level(const GraphView &g, TravState *st, TravCounters *ctr, in
                         const QueueGeom &qg, uint8_t *DB, uint8_t *flags, u64 *M, u64 *K, int grid_blocks, int narrow_cap,
                         const Schedule &sch, const ColourLog &log, int4 *trace, hipStream_t s)
 {
+    if (grid_blocks < 2) grid_blocks = 2;                   // entries and range chunks go to different blocks
     hipLaunchKernelGGL(k_level, dim3((unsigned)grid_blocks), dim3(kLevelThreads), 0, s, g, st, ctr, launch_no, q0, q1,
                        qg, Masks{M, K, DB, flags}, narrow_cap, sch, log, trace);
     return hipGetLastError();
