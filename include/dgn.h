@@ -404,7 +404,8 @@ typedef struct dgn_machine_rates {
     float launch_floor_us;         /* event-to-event time of one empty kernel of 2 048 workgroups                 */
     float launch_back_to_back_us;  /* per kernel in a run of 100 such kernels                                     */
     float copy_gbs;                /* streaming copy inside the buffer, bytes read + written, 10^9 per second     */
-    float reserved[7];
+    float random_atomic_noreturn_gps;  /* random 64-bit atomic ORs whose old value is not asked for                */
+    float reserved[6];
     int64_t buffer_bytes;
 } dgn_machine_rates;
 

@@ -68,10 +68,11 @@ class dgn_machine_rates(ctypes.Structure):
                 ("random_store_gps", ctypes.c_float), ("dependent_load_ns", ctypes.c_float),
                 ("dependent_atomic_ns", ctypes.c_float), ("same_address_atomic_ns", ctypes.c_float),
                 ("launch_floor_us", ctypes.c_float), ("launch_back_to_back_us", ctypes.c_float),
-                ("copy_gbs", ctypes.c_float), ("reserved", ctypes.c_float * 7), ("buffer_bytes", c_int64)]
+                ("copy_gbs", ctypes.c_float), ("random_atomic_noreturn_gps", ctypes.c_float),
+                ("reserved", ctypes.c_float * 6), ("buffer_bytes", c_int64)]
 
     def as_dict(self):
-        return {n: round(float(getattr(self, n)), 3) for n, _ in self._fields_[:9]} | {"buffer_bytes": int(self.buffer_bytes)}
+        return {n: round(float(getattr(self, n)), 3) for n, _ in self._fields_[:10]} | {"buffer_bytes": int(self.buffer_bytes)}
 
 
 PHASES = ["clear", "seed", "traverse", "count", "scan", "scatter", "total"]
