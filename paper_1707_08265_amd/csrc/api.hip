@@ -721,17 +721,19 @@ static int prune_impl(const dgn_graph *g, int32_t num_sets, int64_t num_targets,
         done = sl.n == 0 && !(sl.deferred_seen && sl.theta_hi > 0);
         return DGN_OK;
     };
-    if (!generic_only) {
+    // A graph that needed wide levels last time starts with them at once: the wide kernel's second hop takes
+    // the first two levels in one launch, where the single-workgroup kernel would stop after the first.
+    if (!generic_only && !g->wide_hint[hk].load(std::memory_order_relaxed)) {
         rc = narrow();
         if (rc) return rc;
-        if (!g->wide_hint[hk].load(std::memory_order_relaxed)) {
-            rc = read_state();
-            if (rc) return rc;
-        }
+        rc = read_state();
+        if (rc) return rc;
     }
     auto group = [&](int levels) -> int {            // `levels` wide launches, then the single-workgroup kernel
         for (int i = 0; i < levels; ++i) {
-            DGN_HIP(launch_level(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, flags, M, K, grid, narrow_cap, sch, log, trace, s));
+            // (a traversal that starts with a wide launch: that launch takes the seeds' level however small it is)
+            const int cap = launch_no == 0 ? 0 : narrow_cap;
+            DGN_HIP(launch_level(g->v, S.state, S.ctr, launch_no, S.q0, S.q1, S.qg, S.DB, flags, M, K, grid, cap, sch, log, trace, s));
             ++launch_no; ++launches; ++level_launches;
         }
         last_was_narrow = false;
