@@ -24,7 +24,7 @@
 // this launch, so by (I3)/(I4) the operator is processed again later, and in the last launch that processes it
 // nothing arrives any more: every lane reads the same masks and stores the same, final, value.  A bit is pushed
 // to the inputs by the first lane that stores it (it was not in the K that lane had read).  Launches in which a
-// wave expands its own pushes at once (small levels, see run_level) break (I4) and use atomic ORs on K instead.
+// wave expands its own pushes at once (see run_level) break (I4) and use atomic ORs on K instead.
 //
 // Why thresholds: 64-bit atomics retire at roughly 20 G/s on this chip whatever their locality, so the
 // traversal is bound by the number of atomics -- one per input edge of a processed operator.  Operator ids are a
@@ -640,10 +640,11 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
             __builtin_amdgcn_wave_barrier();
         }
     }
-    // With a small queue the level is a chain of dependent accesses plus the fixed cost of a launch: the wave
-    // then processes what it has just pushed itself, one more hop within this launch, and only what that hop pushes
-    // goes to memory (any order reaches the same fixed point; a hop done here is a launch saved wherever the
-    // levels are small).
+    // A level is a chain of dependent accesses plus the fixed cost of a launch: the wave then processes what it has
+    // just pushed itself, one more hop within this launch, and only what that hop pushes goes to memory (any order
+    // reaches the same fixed point).  While the threshold comes down this keeps the late pushes -- producers inside
+    // ranges that are open already -- from trailing through the following levels; once it is zero a hop done here
+    // is a launch saved.
     if (p.chase) {
         const int hops = in.theta > 0 ? kChaseHops : kTailHops;
         for (int hop = 0; hop < hops; ++hop) {
