@@ -255,6 +255,7 @@ def main():
     recycled = bool(st.recycled)
     level_launches = int(st.level_launches)
     atomics_per_step = int(st.atomic_updates)
+    stats_visits = int(st.tensor_visits)
     levels_total, launches_total = int(st.levels), int(st.launches)
     opts.profile = 1
     phases_all = np.zeros((5, 8))
@@ -574,6 +575,18 @@ def main():
                                "frac": round(a_gps / rates["random_atomic_gps"], 4) if rates["random_atomic_gps"] else None,
                                "throughput_floor_ms": round(atomics_per_step / (rates["random_atomic_gps"] * 1e9) * 1e3, 4)
                                                      if rates["random_atomic_gps"] else None}
+        # Random accesses as a whole: per operator visit its record, K, the outputs' masks and the input ids (one
+        # memory sector each), per input edge the producer word beside the atomic.  A random load issued together with
+        # an atomic costs what the pair rate says on top of the atomic (about a third of a load on its own).
+        pair, ra = rates.get("random_load_and_atomic_gps"), rates["random_atomic_gps"]
+        if pair and ra and stats_visits is not None:
+            loads = 4 * stats_visits + max(atomics_per_step - stats_visits, 0)
+            per_load_ns = max(1.0 / pair - 1.0 / ra, 0.0)
+            floor_ms = (atomics_per_step / ra + loads * per_load_ns) / 1e9 * 1e3
+            roofline["random_access"] = {"atomics_per_step": atomics_per_step, "loads_per_step_model": loads,
+                                         "ns_per_atomic": round(1.0 / ra, 4), "ns_per_load_beside_an_atomic": round(per_load_ns, 4),
+                                         "floor_ms": round(floor_ms, 4),
+                                         "frac": round(floor_ms / ph["traverse"], 4)}
         chain_wide = rates["launch_back_to_back_us"] + (4 * rates["dependent_load_ns"] + rates["dependent_atomic_ns"]) / 1e3
         chain_narrow = (3 * rates["dependent_load_ns"] + rates["dependent_atomic_ns"]) / 1e3
         roofline["latency_floor_ms"] = round((level_launches * chain_wide + narrow_levels * chain_narrow) / 1e3, 4)

@@ -405,7 +405,9 @@ typedef struct dgn_machine_rates {
     float launch_back_to_back_us;  /* per kernel in a run of 100 such kernels                                     */
     float copy_gbs;                /* streaming copy inside the buffer, bytes read + written, 10^9 per second     */
     float random_atomic_noreturn_gps;  /* random 64-bit atomic ORs whose old value is not asked for                */
-    float reserved[6];
+    float random_load_and_atomic_gps;  /* pairs per second of one random load and one random atomic OR, unrelated
+                                          addresses, issued together: do the two rates share a ceiling?            */
+    float reserved[5];
     int64_t buffer_bytes;
 } dgn_machine_rates;
 

@@ -19,7 +19,7 @@ __device__ __forceinline__ u64 cal_mix(u64 z)
     return z ^ (z >> 31);
 }
 
-enum { kCalLoad = 0, kCalAtomic = 1, kCalStore = 2, kCalAtomicNoReturn = 3 };
+enum { kCalLoad = 0, kCalAtomic = 1, kCalStore = 2, kCalAtomicNoReturn = 3, kCalLoadAndAtomic = 4 };
 
 // `total` independent accesses to words drawn uniformly from A[0, nwords)
 template <int MODE>
@@ -32,6 +32,10 @@ __global__ __launch_bounds__(256) void k_cal_random(u64 *A, u64 nwords, u64 tota
         if (MODE == kCalLoad) acc += load_coherent(&A[idx]);
         else if (MODE == kCalAtomic) acc += atomicOr(&A[idx], (u64)1 << (i & 63));
         else if (MODE == kCalAtomicNoReturn) atomicOr(&A[idx], (u64)1 << (i & 63));     // result unused: no data comes back
+        else if (MODE == kCalLoadAndAtomic) {                                            // a load and an atomic, unrelated addresses
+            acc += load_coherent(&A[cal_mix(i * 11 + 5) % nwords]);
+            atomicOr(&A[idx], (u64)1 << (i & 63));
+        }
         else A[idx] = 0;
     }
     if (acc == 0x123456789abcdefull) sink[0] = acc;       // keeps the loads alive
@@ -109,6 +113,8 @@ extern "C" int dgn_calibrate(void *buffer, size_t bytes, dgn_machine_rates *out,
     out->random_store_gps = ms > 0 ? (float)(total / (ms * 1e6)) : 0.0f;
     ms = timed([&] { hipLaunchKernelGGL(k_cal_random<kCalAtomicNoReturn>, grid, block, 0, s, A, nwords, total, sink); }, 3);
     out->random_atomic_noreturn_gps = ms > 0 ? (float)(total / (ms * 1e6)) : 0.0f;
+    ms = timed([&] { hipLaunchKernelGGL(k_cal_random<kCalLoadAndAtomic>, grid, block, 0, s, A, nwords, total, sink); }, 3);
+    out->random_load_and_atomic_gps = ms > 0 ? (float)(total / (ms * 1e6)) : 0.0f;
     const int steps = 2000;
     ms = timed([&] { hipLaunchKernelGGL(k_cal_chain<kCalLoad>, dim3(1), dim3(1), 0, s, A, nwords, steps, sink); }, 2);
     const float empty1 = timed([&] { hipLaunchKernelGGL(k_cal_empty, dim3(1), dim3(64), 0, s, sink); }, 5);
