@@ -229,9 +229,10 @@ def main():
     # ---- prune --------------------------------------------------------------------------------
     buf = d.PruneBuffers(dg, tg.num_sets, recycle=not args.no_recycle)
     rowptr, idx = up(tg.tgt_rowptr), up(tg.tgt_idx)
-    # timed steps: HIP events around the traversal only (every event between two kernels idles the stream for
-    # a few microseconds); the other phases are timed in a few extra steps after the timed region
-    opts = d.dgn_options(profile=2, recompute_keep=1 if args.recompute_keep else 0,
+    # timed steps: no HIP events inside the library (every event between two kernels idles the stream for a few
+    # microseconds: two of them cost 8 us of a step).  The phases are timed in extra steps after the timed region:
+    # as many again with events around the traversal only, then five with every phase bracketed
+    opts = d.dgn_options(profile=0, recompute_keep=1 if args.recompute_keep else 0,
                          defer_percent=args.defer_percent, traversal=1 if args.generic else 0,
                          defer_start_shift=args.defer_start_shift, defer_floor_shift=args.defer_floor_shift)
     st = d.dgn_stats()
@@ -246,10 +247,14 @@ def main():
     t_start = time.perf_counter()
     for i in range(args.steps):
         rc = buf.prune(rowptr, idx, options=opts, stats=st)
-        phases[i] = list(st.phase_ms)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
     assert rc == 0, d.dgn_strerror(rc)
+    opts.profile = 2
+    for i in range(args.steps):
+        rc = buf.prune(rowptr, idx, options=opts, stats=st)
+        assert rc == 0, d.dgn_strerror(rc)
+        phases[i] = list(st.phase_ms)
     ms_per_step = elapsed / args.steps * 1e3
     gteps = E / (ms_per_step * 1e-3) / 1e9
     recycled = bool(st.recycled)
@@ -278,13 +283,13 @@ def main():
     if not traced:
         st.level_trace, st.level_trace_cap = None, 0
     level_us_device_clock = float(np.mean(wide_us)) if wide_us else None
-    opts.profile = 2
+    opts.profile = 0
     ph = dict(zip(d.PHASES, phases_all.mean(0)[:7].tolist()))
-    ph["traverse"] = float(phases.mean(0)[2])              # from the timed steps themselves
+    ph["traverse"] = float(phases.mean(0)[2])              # events around the traversal only
     log(f"prune: {ms_per_step:.3f} ms/step, {gteps:.1f} GTEPS; levels={st.levels} launches={st.launches} "
         f"visits={st.tensor_visits} max_frontier={st.max_frontier} recycled={int(recycled)}")
-    log("phase ms (HIP events; traverse: mean over the timed steps, the others: 5 extra steps with every phase "
-        "bracketed): " + ", ".join(f"{k}={v:.3f}" for k, v in ph.items()))
+    log("phase ms (HIP events, extra steps after the timed ones; traverse: events around the traversal only, the others: "
+        "5 steps with every phase bracketed): " + ", ".join(f"{k}={v:.3f}" for k, v in ph.items()))
 
     # the same steps with every word of M and K cleared each time (what a caller gets who writes to the output
     # buffers between calls, or prunes once)
