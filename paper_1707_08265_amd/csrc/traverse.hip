@@ -142,6 +142,32 @@ __device__ __forceinline__ void flush_log(WaveStage &ws, const Frontier &f)
     }
 }
 
+// Both at once, at the end of a launch: the two counter updates are in flight together, so the wave waits for one
+// trip to memory, not two.
+__device__ __forceinline__ void flush_both(WaveStage &ws, const Frontier &f)
+{
+    const int n = ws.tail - ws.head, nl = ws.lcnt;
+    if (n <= 0 && nl <= 0) return;                          // wave-uniform
+    int base = 0, lbase = 0;
+    if (lane_id() == 0) {
+        if (n > 0) base = atomicAdd(f.cnt, n);
+        if (nl > 0) lbase = atomicAdd(f.log_cnt, nl);
+        if (n > 0 && base + n > f.seg_cap) atomicOr(f.error, kErrOverflow);      // (I3): fix-up sweeps will follow
+        if (nl > 0 && lbase + nl > f.log_cap) atomicOr(f.error, kErrLogFull);
+    }
+    base = __builtin_amdgcn_readfirstlane(base);
+    lbase = __builtin_amdgcn_readfirstlane(lbase);
+    for (int k = lane_id(); k < n; k += kWave) {
+        const int32_t v = ws.buf[(ws.head + k) & (kStageCap - 1)];
+        if (base + k < f.seg_cap) store_coherent(&f.seg[base + k], v);           // read by other blocks
+        if (base + k < f.mirror_cap) f.mirror[base + k] = v;
+    }
+    for (int k = lane_id(); k < nl; k += kWave)
+        if (lbase + k < f.log_cap) f.log[lbase + k] = ws.lbuf[k];
+    ws.head = ws.tail;
+    ws.lcnt = 0;
+}
+
 // Lanes with `push` queue operator `op`; lanes with `first` note tensor `t` as coloured by this prune (its
 // mask was zero before, which the atomic tells exactly one lane).  Wave-uniform control flow.
 __device__ __forceinline__ void stage_push(WaveStage &ws, bool push, int32_t op, bool first, int32_t t, const Frontier &f)
@@ -661,8 +687,7 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
             }
         }
     }
-    flush_entries(ws, f);
-    flush_log(ws, f);
+    flush_both(ws, f);
     // the block's tallies go to one of 64 spread words; nobody waits for them
     const int wproc = wave_sum(lc.processed), wkey = wave_max(lc.max_deferred_key), wat = wave_sum(lc.atomics);
     if (lane == 0) {
