@@ -120,33 +120,60 @@ __device__ __forceinline__ int lane_id() { return (int)__lane_id(); }
 __device__ __forceinline__ u64 lanemask_lt() { return ((u64)1 << lane_id()) - 1; }
 __device__ __forceinline__ u64 ballot64(bool p) { return __ballot(p); }
 
+// Scans and reductions over the 64 lanes by data-parallel-primitive moves (shifts inside a row of 16 lanes, then a
+// broadcast of lane 15 of a row to the next row and of lane 31 to the upper half): eight cheap vector instructions
+// where a shuffle-based scan is six cross-lane permutes, each with the latency of an LDS access.
+//   kRowShr + n: lane i of a row reads lane i - n of its row (lanes without a source keep `identity`);
+//   kRowBcast15 / kRowBcast31 with row masks 0xa / 0xc: rows 1 and 3 read lane 15 of the row before, rows 2 and 3
+//   read lane 31.
+constexpr int kRowShr = 0x110, kRowBcast15 = 0x142, kRowBcast31 = 0x143;
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_move(int identity, int v)
+{
+    return __builtin_amdgcn_update_dpp(identity, v, CTRL, ROW_MASK, 0xf, false);
+}
+
 __device__ __forceinline__ int wave_incl_scan(int v)
 {
-    const int l = lane_id();
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        int t = __shfl_up(v, d, kWave);
-        if (l >= d) v += t;
-    }
+    v += dpp_move<kRowShr + 1, 0xf>(0, v);
+    v += dpp_move<kRowShr + 2, 0xf>(0, v);
+    v += dpp_move<kRowShr + 4, 0xf>(0, v);
+    v += dpp_move<kRowShr + 8, 0xf>(0, v);
+    v += dpp_move<kRowBcast15, 0xa>(0, v);
+    v += dpp_move<kRowBcast31, 0xc>(0, v);
     return v;
 }
-__device__ __forceinline__ int wave_max(int v)
+// inclusive running maximum
+__device__ __forceinline__ int wave_incl_max(int v)
 {
-#pragma unroll
-    for (int d = kWave / 2; d >= 1; d >>= 1) v = max(v, __shfl_xor(v, d, kWave));
+    constexpr int kLowest = -2147483647 - 1;
+    v = max(v, dpp_move<kRowShr + 1, 0xf>(kLowest, v));
+    v = max(v, dpp_move<kRowShr + 2, 0xf>(kLowest, v));
+    v = max(v, dpp_move<kRowShr + 4, 0xf>(kLowest, v));
+    v = max(v, dpp_move<kRowShr + 8, 0xf>(kLowest, v));
+    v = max(v, dpp_move<kRowBcast15, 0xa>(kLowest, v));
+    v = max(v, dpp_move<kRowBcast31, 0xc>(kLowest, v));
     return v;
 }
-__device__ __forceinline__ int wave_sum(int v)
+__device__ __forceinline__ int wave_incl_or(int v)
 {
-#pragma unroll
-    for (int d = kWave / 2; d >= 1; d >>= 1) v += __shfl_xor(v, d, kWave);
+    v |= dpp_move<kRowShr + 1, 0xf>(0, v);
+    v |= dpp_move<kRowShr + 2, 0xf>(0, v);
+    v |= dpp_move<kRowShr + 4, 0xf>(0, v);
+    v |= dpp_move<kRowShr + 8, 0xf>(0, v);
+    v |= dpp_move<kRowBcast15, 0xa>(0, v);
+    v |= dpp_move<kRowBcast31, 0xc>(0, v);
     return v;
 }
+// reductions: the last lane of the scan holds the result (one scalar read)
+__device__ __forceinline__ int wave_max(int v) { return __builtin_amdgcn_readlane(wave_incl_max(v), kWave - 1); }
+__device__ __forceinline__ int wave_sum(int v) { return __builtin_amdgcn_readlane(wave_incl_scan(v), kWave - 1); }
 __device__ __forceinline__ u64 wave_or(u64 v)
 {
-#pragma unroll
-    for (int d = kWave / 2; d >= 1; d >>= 1) v |= (u64)__shfl_xor((long long)v, d, kWave);
-    return v;
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane(wave_incl_or((int)(uint32_t)v), kWave - 1);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane(wave_incl_or((int)(uint32_t)(v >> 32)), kWave - 1);
+    return ((u64)hi << 32) | lo;
 }
 __device__ __forceinline__ u64 shfl64(u64 v, int src) { return (u64)__shfl((long long)v, src, kWave); }
 __device__ __forceinline__ u64 shfl_xor64(u64 v, int mask) { return (u64)__shfl_xor((long long)v, mask, kWave); }

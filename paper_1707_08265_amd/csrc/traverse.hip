@@ -338,25 +338,25 @@ __device__ __forceinline__ void expand_edges(const GraphView &g, int eb, int deg
     const int lane = lane_id();
     const int incl = wave_incl_scan(deg);
     const int excl = incl - deg;
-    const int total = __shfl(incl, kWave - 1, kWave);
+    const int total = __builtin_amdgcn_readlane(incl, kWave - 1);
     if (total == 0) return;
-    s_incl[lane] = incl;
-    __builtin_amdgcn_wave_barrier();
     for (int e0 = 0; e0 < total; e0 += kWave * kEdgeRounds) {
         int32_t u[kEdgeRounds], pr[kEdgeRounds];
         u64 b[kEdgeRounds], old[kEdgeRounds];
         bool ev[kEdgeRounds];
 #pragma unroll
         for (int r = 0; r < kEdgeRounds; ++r) {
-            const int e = e0 + r * kWave + lane;
+            const int e = e0 + r * kWave + lane, w0 = e0 + r * kWave;
             ev[r] = e < total;
-            int lo = 0, hi = kWave - 1;                     // first lane whose inclusive sum exceeds e
-#pragma unroll
-            for (int it = 0; it < 6; ++it) {
-                const int mid = (lo + hi) >> 1;
-                if (s_incl[mid] > e) hi = mid; else lo = mid + 1;
-            }
-            const int owner = lo;
+            // Whose edge is edge e?  Every lane whose edges reach into this window of 64 marks the window position
+            // where they begin (0: they began before it); the owners ascend with the position, so a running maximum
+            // over the marks gives each position its owner.
+            s_incl[lane] = 0;
+            __builtin_amdgcn_wave_barrier();
+            if (deg > 0 && incl > w0 && excl < w0 + kWave) s_incl[max(excl - w0, 0)] = lane + 1;
+            __builtin_amdgcn_wave_barrier();
+            const int owner = max(wave_incl_max(s_incl[lane]) - 1, 0);
+            __builtin_amdgcn_wave_barrier();
             const int o_eb = __shfl(eb, owner, kWave);
             const int o_excl = __shfl(excl, owner, kWave);
             b[r] = shfl64(bits, owner);
@@ -648,7 +648,7 @@ __device__ __forceinline__ void run_level(const GraphView &g, const LevelSlot &i
             uint32_t bits16 = (uint32_t)(bits >> (16 * part)) & 0xffffu;
             const int cnt = __popc(bits16);
             const int incl = wave_incl_scan(cnt);
-            const int total = __shfl(incl, kWave - 1, kWave);
+            const int total = __builtin_amdgcn_readlane(incl, kWave - 1);
             if (total == 0) continue;                       // wave-uniform
             int pos = incl - cnt;
             const int32_t op_base = (int32_t)op0 + 1024 * part;
