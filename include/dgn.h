@@ -416,6 +416,13 @@ typedef struct dgn_machine_rates {
  * Creates and destroys two HIP events, synchronises `stream` repeatedly, takes a few milliseconds. */
 int dgn_calibrate(void *buffer, size_t bytes, dgn_machine_rates *out, dgn_stream stream);
 
+/* The kernels add up and compare values across the 64 lanes of a wave with data-parallel-primitive moves (row shifts,
+ * row broadcasts) whose lane layout is a property of the GPU generation the library is built for.  This runs every such
+ * scan and reduction on 64 waves of fixed test values and compares with the same sums computed on the host.
+ * buffer: DEVICE, 16-byte aligned, at least 98 304 bytes (destroyed).  Returns the number of values that differ (0: all
+ * well) or a negative DGN_ERR_*.  Synchronises `stream`; not thread safe (static host arrays). */
+int dgn_selftest_wave_ops(void *buffer, size_t bytes, dgn_stream stream);
+
 /* ---- misc ---------------------------------------------------------------------------------- */
 const char *dgn_strerror(int code);
 int dgn_version(void);

@@ -32,7 +32,7 @@ EXPORTS = [
     "dgn_graph_get_csr", "dgn_graph_get_sizes", "dgn_graph_destroy", "dgn_prune_workspace", "dgn_prune",
     "dgn_prune_words", "dgn_keep_compact", "dgn_keep_compact_static_limits", "dgn_keep_compact_static", "dgn_backward_prune_workspace", "dgn_backward_prune", "dgn_inplace_workspace",
     "dgn_inplace", "dgn_inplace_kept", "dgn_ignore_mask", "dgn_per_set_lists_workspace", "dgn_per_set_lists",
-    "dgn_target_digest_workspace", "dgn_target_digest", "dgn_calibrate", "dgn_strerror",
+    "dgn_target_digest_workspace", "dgn_target_digest", "dgn_calibrate", "dgn_selftest_wave_ops", "dgn_strerror",
     "dgn_version",
     "dgn_last_hip_error",
 ]
@@ -122,6 +122,7 @@ def _load() -> ctypes.CDLL:
     lib.dgn_target_digest.argtypes = [c_void_p, c_int32, c_int64, c_void_p, c_void_p, POINTER(ctypes.c_uint64), c_void_p,
                                       c_size_t, c_void_p]
     lib.dgn_calibrate.argtypes = [c_void_p, c_size_t, POINTER(dgn_machine_rates), c_void_p]
+    lib.dgn_selftest_wave_ops.argtypes = [c_void_p, c_size_t, c_void_p]
     lib.dgn_inplace_workspace.argtypes = [c_void_p, POINTER(c_size_t)]
     lib.dgn_inplace.argtypes = [c_void_p, c_void_p, ctypes.c_uint64, c_void_p, c_void_p, c_void_p, c_size_t,
                                 POINTER(c_int32), c_void_p]
@@ -333,6 +334,10 @@ def dgn_target_digest(handle, num_sets, num_targets, tgt_rowptr, tgt_idx, scratc
     rc = _lib.dgn_target_digest(handle, num_sets, num_targets, _dp(tgt_rowptr), _dp(tgt_idx), out, _dp(scratch),
                                 scratch_bytes, _stream(stream))
     return rc, (int(out[0]), int(out[1]))
+
+
+def dgn_selftest_wave_ops(buffer, nbytes, stream=None) -> int:
+    return int(_lib.dgn_selftest_wave_ops(_dp(buffer), nbytes, _stream(stream)))
 
 
 def dgn_calibrate(buffer, nbytes, stream=None):

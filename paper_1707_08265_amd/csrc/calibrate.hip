@@ -73,9 +73,67 @@ __global__ __launch_bounds__(256) void k_cal_copy(const ulonglong2 *src, ulonglo
     for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gsize) dst[i] = src[i];
 }
 
+// Every wave scan and reduction of common.h on one wave's 64 values (in), side by side (out: five arrays of n)
+__global__ __launch_bounds__(256) void k_selftest_wave(const int *in, int *out, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;        // n is a multiple of the block size
+    const int v = in[i];
+    out[i] = wave_incl_scan(v);
+    out[n + i] = wave_incl_max(v);
+    out[2 * n + i] = wave_sum(v);
+    out[3 * n + i] = wave_max(v);
+    const u64 o = wave_or(((u64)(uint32_t)v << 32) | (uint32_t)(v * 0x9E3779B1u));
+    out[4 * n + i] = (int)(uint32_t)(o ^ (o >> 32));
+}
+
 }  // namespace dgn
 
 using namespace dgn;
+
+extern "C" int dgn_selftest_wave_ops(void *buffer, size_t bytes, dgn_stream stream)
+{
+    constexpr int kWaves = 64, n = kWaves * kWave;
+    if (!buffer) return DGN_ERR_NULL_PTR;
+    if (bytes < (size_t)6 * n * sizeof(int) || ((uintptr_t)buffer & 15)) return DGN_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // small sums, large values, sparse values and negative ones, a wave each in turn (a fixed linear congruential sequence)
+    static int h_in[n], h_out[5 * n];
+    uint32_t x = 12345u;
+    for (int i = 0; i < n; ++i) {
+        x = x * 1664525u + 1013904223u;
+        const int r = (int)(x >> 8), w = i / kWave;
+        h_in[i] = w % 4 == 0 ? r % 5 : w % 4 == 1 ? r % 100000 : w % 4 == 2 ? (r % 7 == 0 ? r % 64 : 0) : -(r % 1000) - 1;
+    }
+    int *d_in = static_cast<int *>(buffer), *d_out = d_in + n;
+    if (hipMemcpyAsync(d_in, h_in, sizeof(h_in), hipMemcpyHostToDevice, s) != hipSuccess) return DGN_ERR_HIP;
+    hipLaunchKernelGGL(k_selftest_wave, dim3(n / 256), dim3(256), 0, s, d_in, d_out, n);
+    if (hipGetLastError() != hipSuccess) return DGN_ERR_HIP;
+    if (hipMemcpyAsync(h_out, d_out, sizeof(h_out), hipMemcpyDeviceToHost, s) != hipSuccess) return DGN_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return DGN_ERR_HIP;
+    int bad = 0;
+    for (int w = 0; w < kWaves; ++w) {
+        int tot = 0, top = -2147483647 - 1;
+        u64 all = 0;
+        for (int l = 0; l < kWave; ++l) {
+            const int v = h_in[w * kWave + l];
+            tot += v;
+            top = top > v ? top : v;
+            all |= ((u64)(uint32_t)v << 32) | (uint32_t)(v * 0x9E3779B1u);
+        }
+        int run = 0, run_max = -2147483647 - 1;
+        for (int l = 0; l < kWave; ++l) {
+            const int i = w * kWave + l;
+            run += h_in[i];
+            run_max = run_max > h_in[i] ? run_max : h_in[i];
+            bad += h_out[i] != run;
+            bad += h_out[n + i] != run_max;
+            bad += h_out[2 * n + i] != tot;
+            bad += h_out[3 * n + i] != top;
+            bad += h_out[4 * n + i] != (int)(uint32_t)(all ^ (all >> 32));
+        }
+    }
+    return bad;
+}
 
 extern "C" int dgn_calibrate(void *buffer, size_t bytes, dgn_machine_rates *out, dgn_stream stream)
 {
