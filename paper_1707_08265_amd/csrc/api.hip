@@ -26,10 +26,7 @@ inline int hip_fail(hipError_t e)
     } while (0)
 
 constexpr int64_t kMaxCount = 2147483646;   // counts must stay below 2^31 - 1
-#ifndef DGN_LEVEL_BLOCKS_PER_CU
-#define DGN_LEVEL_BLOCKS_PER_CU 5
-#endif
-constexpr int kLevelBlocksPerCU = DGN_LEVEL_BLOCKS_PER_CU;   // workgroups of a wide level per compute unit
+constexpr int kLevelBlocksPerCU = 5;   // workgroups of a wide level per compute unit
 constexpr int kNarrowCap = 1024;            // frontiers up to this size are walked by one workgroup (one round of its threads)
 constexpr int kWidePerGroup = 12;           // wide level launches between two single-workgroup launches
 constexpr int kWideGroupsFirst = 4;         // groups in the first batch (one state read-back per batch) ...

@@ -12,17 +12,11 @@
 
 namespace dgn {
 
-#ifndef DGN_RADIX_BITS
-#define DGN_RADIX_BITS 9
-#endif
-#ifndef DGN_SORT_ROUNDS
-#define DGN_SORT_ROUNDS 8
-#endif
-constexpr int kRadixBits = DGN_RADIX_BITS;
+constexpr int kRadixBits = 9;
 constexpr int kRadix = 1 << kRadixBits;
 constexpr int kSortThreads = kRadix;                    // one thread per digit in the per-tile bookkeeping
 constexpr int kSortWaves = kSortThreads / kWave;
-constexpr int kSortRounds = DGN_SORT_ROUNDS;            // keys per lane
+constexpr int kSortRounds = 8;                          // keys per lane
 constexpr int kSortTile = kSortThreads * kSortRounds;   // keys per workgroup
 
 __device__ __forceinline__ int digit_of(int32_t key, int shift) { return ((uint32_t)key >> shift) & (kRadix - 1); }

@@ -327,10 +327,7 @@ __device__ __forceinline__ bool note_producer(int32_t op, int32_t theta, uint8_t
 // of 1 costs no idle lanes.  A wave with more than 64 edges takes kEdgeRounds rounds of 64 at a time: their
 // targets are fetched together, then their atomics sent together, so that a wave that met an operator with many
 // inputs pays the two dependent accesses once, not once per round.  Wave-uniform control flow throughout.
-#ifndef DGN_EDGE_ROUNDS
-#define DGN_EDGE_ROUNDS 1
-#endif
-constexpr int kEdgeRounds = DGN_EDGE_ROUNDS;
+constexpr int kEdgeRounds = 1;          // (two and four were measured: no gain, more registers)
 
 __device__ __forceinline__ void expand_edges(const GraphView &g, int eb, int deg, u64 bits, int32_t theta, const Masks &mk,
                                              int *s_incl, WaveStage &ws, const Frontier &f, LevelCounters &lc)
@@ -478,14 +475,8 @@ constexpr int kThinPerWave = 8;                    // queue entries dealt to a w
 constexpr int kMinChunkLog = 3;                    // a wave scans between 8 ...
 constexpr int kMaxChunkLog = 12;                   // ... and 4096 marker bytes per step (64 per lane)
 constexpr int kListCap = 16 * kWave;               // marked operators listed per wave before they are processed
-#ifndef DGN_CHASE_HOPS
-#define DGN_CHASE_HOPS 1
-#endif
-constexpr int kChaseHops = DGN_CHASE_HOPS;         // hops a wave adds on its own in a launch ...
-#ifndef DGN_TAIL_HOPS
-#define DGN_TAIL_HOPS 32
-#endif
-constexpr int kTailHops = DGN_TAIL_HOPS;           // ... and once the threshold has reached zero
+constexpr int kChaseHops = 1;                      // hops a wave adds on its own in a launch ...
+constexpr int kTailHops = 32;                      // ... and once the threshold has reached zero
 
 struct LevelShared {
     int32_t stage[kLevelWaves][kStageCap];
