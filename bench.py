@@ -28,7 +28,7 @@ def measured_traffic(kernel):
         vals = dict(line.split(": ", 1) for line in open(os.path.join(ROOT, COUNTERS)).read().splitlines()
                     if ": " in line and not line.startswith("#"))
         h = hashlib.sha256()
-        for f in ("traverse.hip", "keep_compact.hip", "primitives.hip"):
+        for f in ("traverse.hip", "keep_compact.hip", "primitives.hip", "common.h"):
             h.update(open(os.path.join(ROOT, "paper_1707_08265_amd", "csrc", f), "rb").read())
         if h.hexdigest()[:16] != vals.get("source_hash", "").strip():
             return None
