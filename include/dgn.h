@@ -407,7 +407,9 @@ typedef struct dgn_machine_rates {
     float random_atomic_noreturn_gps;  /* random 64-bit atomic ORs whose old value is not asked for                */
     float random_load_and_atomic_gps;  /* pairs per second of one random load and one random atomic OR, unrelated
                                           addresses, issued together: do the two rates share a ceiling?            */
-    float reserved[5];
+    float run_atomic_gps;              /* atomic ORs (old value not asked for) whose 64 lanes hit 64 consecutive words,
+                                          the runs at random places: what an OR on K of neighbouring operators costs */
+    float reserved[4];
     int64_t buffer_bytes;
 } dgn_machine_rates;
 

@@ -69,10 +69,11 @@ class dgn_machine_rates(ctypes.Structure):
                 ("dependent_atomic_ns", ctypes.c_float), ("same_address_atomic_ns", ctypes.c_float),
                 ("launch_floor_us", ctypes.c_float), ("launch_back_to_back_us", ctypes.c_float),
                 ("copy_gbs", ctypes.c_float), ("random_atomic_noreturn_gps", ctypes.c_float),
-                ("random_load_and_atomic_gps", ctypes.c_float), ("reserved", ctypes.c_float * 5), ("buffer_bytes", c_int64)]
+                ("random_load_and_atomic_gps", ctypes.c_float), ("run_atomic_gps", ctypes.c_float),
+                ("reserved", ctypes.c_float * 4), ("buffer_bytes", c_int64)]
 
     def as_dict(self):
-        return {n: round(float(getattr(self, n)), 3) for n, _ in self._fields_[:11]} | {"buffer_bytes": int(self.buffer_bytes)}
+        return {n: round(float(getattr(self, n)), 3) for n, _ in self._fields_[:12]} | {"buffer_bytes": int(self.buffer_bytes)}
 
 
 PHASES = ["clear", "seed", "traverse", "count", "scan", "scatter", "total"]

@@ -19,7 +19,7 @@ __device__ __forceinline__ u64 cal_mix(u64 z)
     return z ^ (z >> 31);
 }
 
-enum { kCalLoad = 0, kCalAtomic = 1, kCalStore = 2, kCalAtomicNoReturn = 3, kCalLoadAndAtomic = 4 };
+enum { kCalLoad = 0, kCalAtomic = 1, kCalStore = 2, kCalAtomicNoReturn = 3, kCalLoadAndAtomic = 4, kCalAtomicRun = 5 };
 
 // `total` independent accesses to words drawn uniformly from A[0, nwords)
 template <int MODE>
@@ -28,10 +28,12 @@ __global__ __launch_bounds__(256) void k_cal_random(u64 *A, u64 nwords, u64 tota
     const u64 gtid = (u64)blockIdx.x * blockDim.x + threadIdx.x, gsize = (u64)gridDim.x * blockDim.x;
     u64 acc = 0;
     for (u64 i = gtid; i < total; i += gsize) {
-        const u64 idx = cal_mix(i * 7 + MODE) % nwords;
+        // (kCalAtomicRun: the 64 lanes of a wave hit 64 consecutive words, the run's start is random)
+        const u64 idx = MODE == kCalAtomicRun ? ((cal_mix((i >> 6) * 7 + MODE) % (nwords >> 6)) << 6) + (i & 63) : cal_mix(i * 7 + MODE) % nwords;
         if (MODE == kCalLoad) acc += load_coherent(&A[idx]);
         else if (MODE == kCalAtomic) acc += atomicOr(&A[idx], (u64)1 << (i & 63));
         else if (MODE == kCalAtomicNoReturn) atomicOr(&A[idx], (u64)1 << (i & 63));     // result unused: no data comes back
+        else if (MODE == kCalAtomicRun) atomicOr(&A[idx], (u64)1 << (i & 63));
         else if (MODE == kCalLoadAndAtomic) {                                            // a load and an atomic, unrelated addresses
             acc += load_coherent(&A[cal_mix(i * 11 + 5) % nwords]);
             atomicOr(&A[idx], (u64)1 << (i & 63));
@@ -173,6 +175,8 @@ extern "C" int dgn_calibrate(void *buffer, size_t bytes, dgn_machine_rates *out,
     out->random_atomic_noreturn_gps = ms > 0 ? (float)(total / (ms * 1e6)) : 0.0f;
     ms = timed([&] { hipLaunchKernelGGL(k_cal_random<kCalLoadAndAtomic>, grid, block, 0, s, A, nwords, total, sink); }, 3);
     out->random_load_and_atomic_gps = ms > 0 ? (float)(total / (ms * 1e6)) : 0.0f;
+    ms = timed([&] { hipLaunchKernelGGL(k_cal_random<kCalAtomicRun>, grid, block, 0, s, A, nwords, total, sink); }, 3);
+    out->run_atomic_gps = ms > 0 ? (float)(total / (ms * 1e6)) : 0.0f;
     const int steps = 2000;
     ms = timed([&] { hipLaunchKernelGGL(k_cal_chain<kCalLoad>, dim3(1), dim3(1), 0, s, A, nwords, steps, sink); }, 2);
     const float empty1 = timed([&] { hipLaunchKernelGGL(k_cal_empty, dim3(1), dim3(64), 0, s, sink); }, 5);
