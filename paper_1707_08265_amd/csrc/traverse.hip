@@ -364,8 +364,8 @@ __device__ __forceinline__ void expand_edges(const GraphView &g, int eb, int deg
             pr[r] = kNoProducer;
             old[r] = ~(u64)0;
             if (ev[r]) {
-                pr[r] = g.prod1[u[r]];                      // in flight together with the atomic
                 old[r] = atomicOr(&mk.M[u[r]], b[r]);       // (I2)
+                pr[r] = g.prod1[u[r]];                      // in flight together with the atomic (which goes first: the earlier it lands, the fewer pushes come late)
                 lc.atomics++;
             }
         }
