@@ -1030,9 +1030,12 @@ __device__ __forceinline__ u64 readlane64(u64 v, int l)     // l wave-uniform
     return ((u64)hi << 32) | lo;
 }
 
-// position of tensor t in the table of output tensors, or -1
-__device__ __forceinline__ int find_out(const SweepShared &sh, int32_t t)
+// position of tensor t in the table of output tensors, or -1.  span > 0: the group's outputs are the `span`
+// consecutive tensors from `first` on (operators that number their outputs as they create them), and the table is
+// indexed by t - first: nothing to look up.
+__device__ __forceinline__ int find_out(const SweepShared &sh, int32_t t, int32_t first, int span)
 {
+    if (span > 0) return (uint32_t)(t - first) < (uint32_t)span ? t - first : -1;      // wave-uniform branch
     for (int slot = out_slot_of(t);; slot = (slot + 1) & (kOutSlots - 1)) {
         const int32_t key = sh.okey[slot];
         if (key == t) return slot;
@@ -1170,8 +1173,29 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64
         const int n_out = valid ? row.oe - row.ob : 0, n_in = valid ? row.ie - row.ib : 0;
         const int max_out = wave_max(n_out), max_in = wave_max(n_in);
         const int total_in = wave_sum(n_in);
-        bool tables = wave_sum(n_out) <= kOutMax && total_in <= kInMax;
-        if (tables) {                                        // the group's output tensors and who writes them
+        const int total_out = wave_sum(n_out);
+        bool tables = total_out <= kOutMax && total_in <= kInMax;
+        // Are the group's outputs one run of consecutive tensors, each written once?  (No tensor of the batch has two
+        // producers, and the smallest and the largest id are as far apart as there are outputs.)
+        int32_t first_out = 0;
+        int span = 0;
+        if (tables && !multi_producer && total_out > 0) {
+            int32_t lo_t = 0x7fffffff, hi_t = -1;
+            for (int r = 0; r < max_out; ++r) {
+                if (r < n_out) {
+                    const int32_t t = sweep_out(g, row, r);
+                    lo_t = min(lo_t, t);
+                    hi_t = max(hi_t, t);
+                }
+            }
+            const int32_t glo = -wave_max(-lo_t), ghi = wave_max(hi_t);
+            if (ghi - glo + 1 == total_out) { first_out = glo; span = total_out; }
+        }
+        if (tables && span > 0) {                            // the table is indexed by tensor: only the owners to note
+            sh.ndep[lane] = 0;
+            for (int r = 0; r < max_out; ++r)
+                if (r < n_out) sh.oowner[sweep_out(g, row, r) - first_out] = (uint8_t)lane;
+        } else if (tables) {                                 // the group's output tensors and who writes them
             for (int i = lane; i < kOutSlots; i += kWave) sh.okey[i] = -1;
             sh.ndep[lane] = 0;
             wave_lds_sync();
@@ -1210,7 +1234,7 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64
                             break;
                         }
                     }
-                    sh.oacc[find_out(sh, t)] = m;
+                    sh.oacc[find_out(sh, t, first_out, span)] = m;
                     k |= m;
                 }
             }
@@ -1218,7 +1242,7 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64
             u64 feeds = 0;
             for (int r = 0; r < max_in; ++r) {
                 if (r < n_in) {
-                    const int slot = find_out(sh, sweep_in(g, row, r));
+                    const int slot = find_out(sh, sweep_in(g, row, r), first_out, span);
                     if (slot >= 0) {
                         const int b = sh.oowner[slot];
                         if (b > lane && !((feeds >> b) & 1)) {       // first time this lane meets producer b
@@ -1262,7 +1286,7 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64
             for (int r = 0; r < max_in; ++r) {
                 if (r < n_in && k) {
                     const int32_t t = sweep_in(g, row, r);
-                    const int os = find_out(sh, t);
+                    const int os = find_out(sh, t, first_out, span);
                     if (os >= 0) {
                         atomicOr(&sh.oacc[os], k);
                     } else {
@@ -1281,7 +1305,7 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_graphs(GraphView g, u64
             for (int r = 0; r < max_out; ++r)                // the group's tensors are final
                 if (r < n_out) {
                     const int32_t t = sweep_out(g, row, r);
-                    M[t] = sh.oacc[find_out(sh, t)];
+                    M[t] = sh.oacc[find_out(sh, t, first_out, span)];
                 }
             wave_lds_sync();
         } else {
