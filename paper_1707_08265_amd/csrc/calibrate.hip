@@ -85,7 +85,10 @@ __global__ __launch_bounds__(256) void k_selftest_wave(const int *in, int *out, 
     out[2 * n + i] = wave_sum(v);
     out[3 * n + i] = wave_max(v);
     const u64 o = wave_or(((u64)(uint32_t)v << 32) | (uint32_t)(v * 0x9E3779B1u));
-    out[4 * n + i] = (int)(uint32_t)(o ^ (o >> 32));
+    // and the three-input bit operation, its middle operand the same for the whole wave as in the sort's ranking
+    const uint32_t u = (uint32_t)__builtin_amdgcn_readfirstlane(v) * 0xC2B2AE35u;
+    const uint32_t x = or_of_xor((uint32_t)v * 0x85EBCA6Bu, u, (uint32_t)v * 0x27D4EB2Fu);
+    out[4 * n + i] = (int)((uint32_t)(o ^ (o >> 32)) ^ x);
 }
 
 }  // namespace dgn
@@ -131,7 +134,9 @@ extern "C" int dgn_selftest_wave_ops(void *buffer, size_t bytes, dgn_stream stre
             bad += h_out[n + i] != run_max;
             bad += h_out[2 * n + i] != tot;
             bad += h_out[3 * n + i] != top;
-            bad += h_out[4 * n + i] != (int)(uint32_t)(all ^ (all >> 32));
+            const uint32_t v = (uint32_t)h_in[i], u = (uint32_t)h_in[w * kWave] * 0xC2B2AE35u;
+            const uint32_t x = (v * 0x85EBCA6Bu) | (u ^ (v * 0x27D4EB2Fu));
+            bad += h_out[4 * n + i] != (int)((uint32_t)(all ^ (all >> 32)) ^ x);
         }
     }
     return bad;

@@ -119,6 +119,11 @@ __device__ __forceinline__ bool same_header(const RecycleHeader &a, const Recycl
 __device__ __forceinline__ int lane_id() { return (int)__lane_id(); }
 __device__ __forceinline__ u64 lanemask_lt() { return ((u64)1 << lane_id()) - 1; }
 __device__ __forceinline__ u64 ballot64(bool p) { return __ballot(p); }
+// acc | (a ^ b) in one instruction (a three-input bit operation with the truth table 0xF0 | (0xCC ^ 0xAA))
+__device__ __forceinline__ uint32_t or_of_xor(uint32_t acc, uint32_t a, uint32_t b)
+{
+    return __builtin_amdgcn_bitop3_b32(acc, a, b, 0xF6);
+}
 
 // Scans and reductions over the 64 lanes by data-parallel-primitive moves (shifts inside a row of 16 lanes, then a
 // broadcast of lane 15 of a row to the next row and of lane 31 to the upper half): eight cheap vector instructions
