@@ -81,37 +81,59 @@ __global__ __launch_bounds__(256) void k_scan_edges(const int32_t *keys, const i
                                                      int32_t n_rows, int32_t n_vals, int32_t *idx_out, int32_t *rowptr,
                                                      int32_t *error, int32_t *unsorted, int32_t *wide_gap)
 {
-    const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
+    // a thread takes four neighbouring positions per step, in 16-byte loads and stores where the arrays are aligned
+    // for them: with a single position per thread the pass waits for memory most of its time
+    constexpr int kPer = 4;
+    const bool wide = ((reinterpret_cast<uintptr_t>(keys) | reinterpret_cast<uintptr_t>(vals) |
+                        reinterpret_cast<uintptr_t>(idx_out)) & 15) == 0;
+    const int64_t gsize = (int64_t)gridDim.x * blockDim.x * kPer;
     const int64_t steps = (nnz + 1 + gsize - 1) / gsize;                // position nnz closes the last rows
-    bool bad = false, descends = false, wide = false;
+    bool bad = false, descends = false, gap = false;
     for (int64_t st = 0; st < steps; ++st) {                            // whole waves stay in the loop
-        const int64_t e = st * gsize + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-        int lo = 0, hi = -1;
-        if (e <= nnz) {
-            const int32_t prev = e > 0 ? keys[e - 1] : -1;
-            int32_t k = n_rows;
-            if (e < nnz) {
-                k = keys[e];
-                const int32_t v = vals[e];
-                if (k < 0 || k >= n_rows || v < 0 || v >= n_vals) bad = true;
-                if (prev > k) descends = true;
-                idx_out[e] = v;
-            }
-            // rows (prev, k]; keys outside their range write nothing (the call fails anyway)
-            if (prev >= -1 && prev < n_rows && k >= 0 && k <= n_rows) {
-                lo = prev + 1;
-                hi = k;
-            }
-            // A long run of empty rows is left to a pass of its own (*wide_gap): keys in random order jump far
-            // at nearly every position, and filling those jumps here would cost more than the sort that follows.
-            if (hi - lo >= kMaxGapHere) {
-                wide = true;
-                hi = lo - 1;
+        const int64_t e0 = st * gsize + ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * kPer;
+        int32_t k[kPer + 1], v[kPer];                                   // k[j] = key before position e0 + j
+        k[0] = e0 > 0 && e0 <= nnz ? keys[e0 - 1] : -1;
+        if (wide && e0 + kPer <= nnz) {
+            const int4 kk = *reinterpret_cast<const int4 *>(keys + e0);
+            const int4 vv = *reinterpret_cast<const int4 *>(vals + e0);
+            k[1] = kk.x; k[2] = kk.y; k[3] = kk.z; k[4] = kk.w;
+            v[0] = vv.x; v[1] = vv.y; v[2] = vv.z; v[3] = vv.w;
+            *reinterpret_cast<int4 *>(idx_out + e0) = vv;
+        } else {
+#pragma unroll
+            for (int j = 0; j < kPer; ++j) {
+                const bool edge = e0 + j < nnz;
+                k[j + 1] = edge ? keys[e0 + j] : n_rows;
+                v[j] = edge ? vals[e0 + j] : 0;
+                if (edge) idx_out[e0 + j] = v[j];
             }
         }
-        write_rows(rowptr, lo, hi, (int32_t)e);
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            const int64_t e = e0 + j;
+            int lo = 0, hi = -1;
+            if (e <= nnz) {
+                const int32_t prev = k[j], cur = k[j + 1];
+                if (e < nnz) {
+                    if (cur < 0 || cur >= n_rows || v[j] < 0 || v[j] >= n_vals) bad = true;
+                    if (prev > cur) descends = true;
+                }
+                // rows (prev, cur]; keys outside their range write nothing (the call fails anyway)
+                if (prev >= -1 && prev < n_rows && cur >= 0 && cur <= n_rows) {
+                    lo = prev + 1;
+                    hi = cur;
+                }
+                // A long run of empty rows is left to a pass of its own (*wide_gap): keys in random order jump far
+                // at nearly every position, and filling those jumps here would cost more than the sort that follows.
+                if (hi - lo >= kMaxGapHere) {
+                    gap = true;
+                    hi = lo - 1;
+                }
+            }
+            write_rows(rowptr, lo, hi, (int32_t)e);
+        }
     }
-    if (ballot64(wide) != 0 && lane_id() == 0 && load_coherent(wide_gap) == 0) store_coherent(wide_gap, 1);
+    if (ballot64(gap) != 0 && lane_id() == 0 && load_coherent(wide_gap) == 0) store_coherent(wide_gap, 1);
     if (ballot64(bad) != 0 && lane_id() == 0) atomicOr(error, kErrIdRange);
     // shuffled input would have every wave report: look first, and store (same value from everyone) only if needed
     if (ballot64(descends) != 0 && lane_id() == 0 && load_coherent(unsorted) == 0) store_coherent(unsorted, 1);
@@ -121,7 +143,7 @@ hipError_t launch_scan_edges(const int32_t *keys, const int32_t *vals, int64_t n
                              int32_t *idx_out, int32_t *rowptr, int32_t *error, int32_t *unsorted, int32_t *wide_gap,
                              hipStream_t s)
 {
-    int64_t blocks = (nnz + 1 + 255) / 256;
+    int64_t blocks = (nnz + 1 + 1023) / 1024;
     if (blocks > 8192) blocks = 8192;
     hipLaunchKernelGGL(k_scan_edges, dim3((unsigned)blocks), dim3(256), 0, s, keys, vals, nnz, n_rows, n_vals, idx_out,
                        rowptr, error, unsorted, wide_gap);
@@ -132,22 +154,38 @@ hipError_t launch_scan_edges(const int32_t *keys, const int32_t *vals, int64_t n
 // Position i writes the rows (keys[i-1], keys[i]]; gaps longer than a few rows are filled by the whole wave.
 __global__ __launch_bounds__(256) void k_row_bounds(const int32_t *keys, int64_t nnz, int32_t n_rows, int32_t *rowptr)
 {
-    const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
+    // a thread takes four neighbouring positions per step (one 16-byte load when the keys are aligned for it): with a
+    // single position per thread the pass waits for memory most of its time
+    constexpr int kPer = 4;
+    const bool wide = (reinterpret_cast<uintptr_t>(keys) & 15) == 0;
+    const int64_t gsize = (int64_t)gridDim.x * blockDim.x * kPer;
     const int64_t steps = (nnz + 1 + gsize - 1) / gsize;                // position nnz closes the last rows
     for (int64_t st = 0; st < steps; ++st) {                            // whole waves stay in the loop
-        const int64_t i = st * gsize + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-        int lo = 0, hi = -1;                                            // rows lo..hi get the value i
-        if (i <= nnz) {
-            lo = i == 0 ? 0 : keys[i - 1] + 1;
-            hi = i == nnz ? n_rows : keys[i];
+        const int64_t i0 = st * gsize + ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * kPer;
+        int32_t k[kPer + 1];                                            // k[j] = key before position i0 + j
+        if (i0 <= nnz) k[0] = i0 == 0 ? -1 : keys[i0 - 1];
+        if (wide && i0 + kPer <= nnz) {
+            const int4 v = *reinterpret_cast<const int4 *>(keys + i0);
+            k[1] = v.x; k[2] = v.y; k[3] = v.z; k[4] = v.w;
+        } else {
+#pragma unroll
+            for (int j = 0; j < kPer; ++j) k[j + 1] = i0 + j < nnz ? keys[i0 + j] : n_rows;
         }
-        write_rows(rowptr, lo, hi, (int32_t)i);
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            int lo = 0, hi = -1;                                        // rows lo..hi get the value i0 + j
+            if (i0 + j <= nnz) {
+                lo = k[j] + 1;
+                hi = k[j + 1];
+            }
+            write_rows(rowptr, lo, hi, (int32_t)(i0 + j));
+        }
     }
 }
 
 hipError_t launch_row_bounds(const int32_t *keys, int64_t nnz, int32_t n_rows, int32_t *rowptr, hipStream_t s)
 {
-    int64_t blocks = (nnz + 1 + 255) / 256;
+    int64_t blocks = (nnz + 1 + 1023) / 1024;
     if (blocks > 8192) blocks = 8192;
     hipLaunchKernelGGL(k_row_bounds, dim3((unsigned)blocks), dim3(256), 0, s, keys, nnz, n_rows, rowptr);
     return hipGetLastError();
