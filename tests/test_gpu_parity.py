@@ -91,6 +91,36 @@ def test_csr_builder_parity_on_shuffled_coo(dgn, oracle, k, scale):
     assert_same(out, r, "shuffled")
 
 
+def test_sort_of_many_tiles_and_of_few_distinct_keys(dgn, oracle):
+    """The radix sort keeps its slot tables per tile, per group of 16 tiles and per chunk of groups: an edge list of
+    > 64 groups (8.4 M edges) makes a chunk hold several groups, with a ragged last chunk, group and tile.  And a
+    graph of few operators with thousands of inputs each (duplicates included) leaves most digits of a pass empty
+    and the others crowded."""
+    g, _ = gg.config(3, 0.1)                                   # 5 M operators, ~13 M input edges, ~10 M output edges
+    assert g.nnz_in > 64 * 16 * 8192 and g.nnz_out > 64 * 16 * 8192
+    gs = gg.shuffle_coo(g, 23)
+    adj = oracle.build_adjacency(gs.num_ops, gs.num_tensors, gs.in_op, gs.in_tensor, gs.out_op, gs.out_tensor)
+    dg = dgn.DeviceGraph.from_coo(gs)
+    csr = {n: v.cpu().numpy() for n, v in dg.csr().items()}
+    for name in ("in_rowptr", "in_idx", "out_rowptr", "out_idx", "prod_rowptr", "prod_idx"):
+        assert np.array_equal(csr[name], getattr(adj, name)), name
+    del dg, csr, adj
+
+    rng = np.random.default_rng(29)
+    P, T, fan = 700, 60000, 3000
+    in_op = np.repeat(np.arange(P, dtype=np.int32), fan)
+    in_tensor = rng.integers(0, T - P, size=P * fan).astype(np.int32)      # with repeats inside an operator
+    out_op = np.arange(P, dtype=np.int32)
+    out_tensor = (T - P + out_op).astype(np.int32)
+    few = gg.Graph(P, T, in_op, in_tensor, out_op, out_tensor, name="few-keys")
+    fs = gg.shuffle_coo(few, 31)
+    adj = oracle.build_adjacency(P, T, fs.in_op, fs.in_tensor, fs.out_op, fs.out_tensor)
+    dg = dgn.DeviceGraph.from_coo(fs)
+    csr = {n: v.cpu().numpy() for n, v in dg.csr().items()}
+    for name in ("in_rowptr", "in_idx", "out_rowptr", "out_idx", "prod_rowptr", "prod_idx"):
+        assert np.array_equal(csr[name], getattr(adj, name)), name
+
+
 def test_from_csr_and_keep_compact(dgn, oracle):
     import torch
     g, tg = gg.config(1, 0.3)
