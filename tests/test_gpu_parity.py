@@ -121,6 +121,41 @@ def test_sort_of_many_tiles_and_of_few_distinct_keys(dgn, oracle):
         assert np.array_equal(csr[name], getattr(adj, name)), name
 
 
+@pytest.mark.parametrize("offset", [1, 2, 3])
+def test_coo_arrays_at_unaligned_addresses(dgn, oracle, offset):
+    """The builder reads the edge lists 16 bytes at a time where their addresses allow it: arrays that start 4, 8 or
+    12 bytes past such an address, with ragged lengths, must give the same adjacency -- recorded operator by
+    operator (the one-pass path) and shuffled (the sort and the row-pointer pass)."""
+    import torch
+    rng = np.random.default_rng(40 + offset)
+    g0, _ = random_small_graph(rng, 3000 + offset, num_inputs=4)
+    for variant in ("ordered", "shuffled"):
+        g = g0 if variant == "ordered" else gg.shuffle_coo(g0, 7)
+        adj = oracle.build_adjacency(g.num_ops, g.num_tensors, g.in_op, g.in_tensor, g.out_op, g.out_tensor)
+
+        def shifted(a):
+            buf = torch.zeros(len(a) + 8, dtype=torch.int32, device="cuda")
+            view = buf[offset:offset + len(a)]
+            view.copy_(torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)))
+            assert view.data_ptr() % 16 == 4 * offset
+            return view
+
+        in_op, in_t, out_op, out_t = shifted(g.in_op), shifted(g.in_tensor), shifted(g.out_op), shifted(g.out_tensor)
+        desc = dgn.make_coo_desc(g.num_ops, g.num_tensors, in_op, in_t, out_op, out_t)
+        rc, gb, sb = dgn.dgn_graph_build_workspace(desc)
+        assert rc == 0
+        graph_mem = torch.empty(gb, dtype=torch.uint8, device="cuda")
+        scratch = torch.empty(sb, dtype=torch.uint8, device="cuda")
+        rc, h = dgn.dgn_graph_build(desc, graph_mem, gb, scratch, sb, dgn.dgn_options())
+        assert rc == 0, dgn.dgn_strerror(rc)
+        rc, sizes = dgn.dgn_graph_get_sizes(h)
+        assert rc == 0
+        dg = dgn.DeviceGraph(h, graph_mem, (), sizes)
+        csr = {n: v.cpu().numpy() for n, v in dg.csr().items()}
+        for name in ("in_rowptr", "in_idx", "out_rowptr", "out_idx", "prod_rowptr", "prod_idx"):
+            assert np.array_equal(csr[name], getattr(adj, name)), f"{variant}, offset {offset}: {name}"
+
+
 def test_from_csr_and_keep_compact(dgn, oracle):
     import torch
     g, tg = gg.config(1, 0.3)
