@@ -420,7 +420,8 @@ int dgn_calibrate(void *buffer, size_t bytes, dgn_machine_rates *out, dgn_stream
 
 /* The kernels add up and compare values across the 64 lanes of a wave with data-parallel-primitive moves (row shifts,
  * row broadcasts) whose lane layout is a property of the GPU generation the library is built for.  This runs every such
- * scan and reduction on 64 waves of fixed test values and compares with the same sums computed on the host.
+ * scan and reduction on 64 waves of fixed test values and compares with the same sums computed on the host; and the
+ * three-input bit operation of the sort's ranking (its truth table is an immediate operand) with the plain expression.
  * buffer: DEVICE, 16-byte aligned, at least 98 304 bytes (destroyed).  Returns the number of values that differ (0: all
  * well) or a negative DGN_ERR_*.  Synchronises `stream`; not thread safe (static host arrays). */
 int dgn_selftest_wave_ops(void *buffer, size_t bytes, dgn_stream stream);
