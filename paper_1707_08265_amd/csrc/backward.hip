@@ -43,6 +43,9 @@ constexpr int kFwThreads = 256;
 // is repeated until it adds nothing (operators of one group usually feed each other); *changed is set
 // when the pass added anything at all.  Values of F read here may be stale: F only grows, and the host
 // repeats the pass until one of them changes nothing.
+// A lane's operator comes as its 16-byte record (one access instead of four row pointers), which also names the
+// outputs when they are numbered consecutively: the marks of the first two outputs are then asked for together with
+// the inputs', not behind them.
 __global__ __launch_bounds__(kFwThreads) void k_forward_within(GraphView g, const int32_t *kept, const int64_t *kept_count,
                                                                 const u64 *B, u64 *F, int32_t *changed)
 {
@@ -53,15 +56,17 @@ __global__ __launch_bounds__(kFwThreads) void k_forward_within(GraphView g, cons
     bool added = false;
     for (int64_t base = wave_id * kWave; base < n; base += num_waves * kWave) {
         const bool valid = base + lane < n;
-        int ib = 0, ie = 0, ob = 0, oe = 0;
-        if (valid) {
-            const int32_t o = kept[base + lane];
-            ib = g.in_rowptr[o];
-            ie = g.in_rowptr[o + 1];
-            ob = g.out_rowptr[o];
-            oe = g.out_rowptr[o + 1];
-        }
+        int4 r = make_int4(0, 0, 0, 0);
+        if (valid) r = g.orec[kept[base + lane]];
+        const int ib = r.x, ie = r.x + r.y;
+        const int n_out = r.w >= 0 ? r.w : -r.w;
+        // the first two outputs and what of them may be marked at all (B does not change during these passes)
+        int32_t y0 = -1, y1 = -1;
+        if (n_out > 0) y0 = r.w >= 0 ? r.z : g.out_idx[r.z];
+        if (n_out > 1) y1 = r.w >= 0 ? r.z + 1 : g.out_idx[r.z + 1];
+        const u64 b0 = y0 >= 0 ? B[y0] : 0, b1 = y1 >= 0 ? B[y1] : 0;
         for (int iter = 0; iter < kWave; ++iter) {          // a chain inside the group is at most 64 long
+            const u64 fy0 = y0 >= 0 ? load_coherent(&F[y0]) : 0, fy1 = y1 >= 0 ? load_coherent(&F[y1]) : 0;
             // four inputs at a time, their ids and then their marks in flight together (past the row's end the last
             // input is read again): an operator with dozens of inputs would otherwise hold its wave for two dependent
             // accesses per input
@@ -76,8 +81,16 @@ __global__ __launch_bounds__(kFwThreads) void k_forward_within(GraphView g, cons
             }
             bool any_new = false;
             if (fin) {
-                for (int e = ob; e < oe; ++e) {
-                    const int32_t y = g.out_idx[e];
+                if ((fin & b0) & ~fy0) {
+                    atomicOr(&F[y0], fin & b0);
+                    any_new = true;
+                }
+                if ((fin & b1) & ~fy1) {
+                    atomicOr(&F[y1], fin & b1);
+                    any_new = true;
+                }
+                for (int j = 2; j < n_out; ++j) {
+                    const int32_t y = r.w >= 0 ? r.z + j : g.out_idx[r.z + j];
                     const u64 add = fin & B[y];
                     if (add & ~load_coherent(&F[y])) {
                         atomicOr(&F[y], add);
