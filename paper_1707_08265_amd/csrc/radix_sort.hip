@@ -149,11 +149,11 @@ __global__ __launch_bounds__(kRadix) void k_col_apply(int32_t *totals, int64_t g
     }
 }
 
+// (eight waves per SIMD: two workgroups of 1 024 threads per CU, which caps the kernel at 64 vector registers)
 template <bool kWriteKeys>
-__global__ __launch_bounds__(kSortThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_sort_scatter(const int32_t *keys, const int32_t *vals,
-                                                                int32_t *keys_out, int32_t *vals_out,
-                                                                int64_t n, int shift, const int32_t *table,
-                                                                const int32_t *totals, int64_t num_tiles)
+__global__ __launch_bounds__(kSortThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
+void k_sort_scatter(const int32_t *keys, const int32_t *vals, int32_t *keys_out, int32_t *vals_out, int64_t n, int shift,
+                    const int32_t *table, const int32_t *totals, int64_t num_tiles)
 {
     // Workgroups go to the chip's eight dies in turn, each with a second-level cache of its own.  Neighbouring tiles
     // write neighbouring runs of the output (a run is shorter than a cache line), so a die takes a contiguous eighth
