@@ -557,6 +557,11 @@ def main():
         "bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
         "traffic": traffic,
+        # the same kernel's measured HBM bytes per launch over its launch time: what the memory system is asked for,
+        # as opposed to the algorithmic bytes behind `achieved` (random 8-byte accesses move whole 64-byte sectors)
+        "traffic_GBs": None if not traffic or dur_ms[dominant] <= 0 else round(traffic / (dur_ms[dominant] * 1e-3) / 1e9, 1),
+        "traffic_frac": None if not traffic or dur_ms[dominant] <= 0
+                        else round(traffic / (dur_ms[dominant] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "traffic_source": (COUNTERS + " (committed rocprofv3 --pmc summary, not measured in this run; null when the kernel "
                            "sources have changed since)"),
         "launch_ms": round(dur_ms[dominant], 4), "launches_per_step": 1 if dominant != "k_level" else level_launches,
